@@ -1,0 +1,175 @@
+/*
+ * fmtc.h -- C ABI of the feature-map transform codec for AMD MI355X (gfx950).
+ *
+ * The codec is the encoder/decoder chain of "Feature Map Transform Coding for
+ * Energy-Efficient CNN Inference" (arXiv 1905.10830):
+ *
+ *   encode (section 3; section 3.1 "Implementation"): every 1x1xC block x of an
+ *   activation tensor is transformed, y = T (x - mu), with the orthonormal PCA
+ *   basis T of the channel covariance; y is quantized by a uniform scalar
+ *   quantizer with one step Delta for all coefficients; the levels are coded
+ *   with a Huffman code built from the tensor's own symbol histogram and the
+ *   bits are written to memory.
+ *   decode: variable length decoding, levels scaled back by Delta, inverse
+ *   transform x_hat = T^T y_hat + mu.  No non-linearity is applied.
+ *
+ * Conventions
+ *   - Plain C types only.  d_* pointers are DEVICE pointers owned by the caller,
+ *     h_* pointers are HOST pointers owned by the caller.  hip_stream is a
+ *     hipStream_t passed as void* (NULL = the default stream).
+ *   - Logical tensor dims are always (N, C, H, W); `layout` selects the storage:
+ *     FMTC_NHWC = [N][H][W][C] contiguous, FMTC_NCHW = [N][C][H][W] contiguous.
+ *     P = N*H*W pixels, V = P*C values.
+ *   - Symbols: level q in [-2^(b-1), 2^(b-1)-1] is stored as s = q + 2^(b-1),
+ *     one byte each, pixel major in logical (n,h,w) order, coefficient minor.
+ *   - Every call returns a status and never throws.  Argument errors are found
+ *     on the host before any launch; fmtc_last_error() gives the text for the
+ *     calling thread.  All hot-path calls are asynchronous on hip_stream and
+ *     allocate nothing: scratch comes from the caller's workspace.
+ *   - Limits: 1 <= C <= 1024, 2 <= bits <= 8, 64 <= chunk_syms <= 4096, V < 2^32.
+ *   - Two calls may overlap only if they use different workspaces and outputs.
+ *
+ * Stream container (little endian; this library's own format, the paper leaves
+ * it open):
+ *   [0,64)    header: u32 magic "FMTC", u16 version=1, u8 bits, u8 0, u32 C,
+ *             u32 px_per_chunk, u64 P, u32 n_chunks, u32 sub_syms=64, f32 Delta,
+ *             u32 subs_per_chunk, u64 payload_words, u64 payload_bits, u64 0
+ *   [64,320)  u8 code length per symbol (0 = unused symbol)
+ *   [320,..)  u32 chunk_off[n_chunks+1]  first payload word of each chunk
+ *   align 16  u16 sub_bits[n_chunks][subs_per_chunk]  code bits of each run of 64
+ *             consecutive symbols of a chunk (lets 64 lanes decode one chunk)
+ *   align 16  u32 payload[payload_words]
+ *   A chunk holds px_per_chunk = max(1, chunk_syms / C) whole pixels and starts
+ *   on a 32-bit word boundary; pad bits are 0.  Stream bit i is bit (i mod 32)
+ *   of payload word i/32.  Codes are canonical Huffman codes (symbols ordered by
+ *   (length, symbol)), written most significant code bit first.
+ */
+#ifndef FMTC_H
+#define FMTC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fmtc_status {
+    FMTC_OK = 0,
+    FMTC_EINVAL = 1,   /* bad argument (null, out of range, misaligned) */
+    FMTC_EBUFSIZE = 2, /* output or workspace capacity too small */
+    FMTC_ECORRUPT = 3, /* stream fails validation */
+    FMTC_ENOMEM = 4,   /* host or device allocation failed (basis calls only) */
+    FMTC_EHIP = 5      /* a HIP runtime call failed */
+} fmtc_status;
+
+typedef enum fmtc_layout { FMTC_NCHW = 0, FMTC_NHWC = 1 } fmtc_layout;
+
+/* Device error bits OR-ed into *d_err_flag by the decoders. */
+#define FMTC_ERR_HEADER 1u  /* header does not match the arguments or the buffer size */
+#define FMTC_ERR_TABLE 2u   /* code length table is not a complete prefix code */
+#define FMTC_ERR_OFFSETS 4u /* chunk offsets not monotone or past the payload */
+#define FMTC_ERR_CODE 8u    /* bits that match no code word, or a read past the payload */
+
+/* Basis handle: T (CxC, row k = k-th principal component), mu (C), the
+ * eigenvalues and the dynamic range A.  Owned by the library; holds small
+ * device copies of T in the operand order of the kernels. */
+typedef struct fmtc_basis fmtc_basis;
+
+/* ---- offline: the transform (section 3.1 "Linear transform", "Quantization") ----
+ * Fits the PCA basis on a calibration tensor resident on the device: channel
+ * mean and covariance (fp64 accumulation on the GPU), symmetric eigen-
+ * decomposition in fp64 on the host, rows ordered by descending eigenvalue and
+ * signed so that the largest-magnitude entry of each row is positive, T and mu
+ * rounded to fp32; A = max |y_0| over the calibration pixels (y_0: coefficient
+ * of the highest-variance component).  Synchronises the stream.  *out must be
+ * released with fmtc_basis_destroy. */
+fmtc_status fmtc_fit_basis(const float *d_x, int64_t N, int C, int H, int W, fmtc_layout layout, void *hip_stream,
+                           fmtc_basis **out);
+
+/* Builds a handle from host arrays (h_T: C*C row major, h_mu: C).  The way to
+ * reuse a stored basis, and to give two implementations the same one. */
+fmtc_status fmtc_basis_import(int C, const float *h_T, const float *h_mu, float range_A, fmtc_basis **out);
+
+/* Copies the basis to host arrays; any output pointer may be NULL.
+ * h_eigvals receives zeros for an imported basis. */
+fmtc_status fmtc_basis_export(const fmtc_basis *basis, float *h_T, float *h_mu, double *h_eigvals, float *range_A);
+
+int fmtc_basis_channels(const fmtc_basis *basis);
+void fmtc_basis_destroy(fmtc_basis *basis);
+
+/* Step of the b-bit quantizer: Delta = A / (2^(b-1) - 1) evaluated in fp64 and
+ * rounded to fp32 (1.0 if A <= 0); the range is set by the highest-variance
+ * component and shared by all coefficients (section 3.1 "Quantization"). */
+float fmtc_delta(float range_A, int bits);
+
+/* ---- sizing ---- */
+/* Upper bound of the stream size in bytes (0 on invalid arguments): an optimal
+ * prefix code never spends more than bits*V payload bits in total, plus one
+ * pad word per chunk and the side information. */
+size_t fmtc_encode_bound(int64_t P, int C, int bits, int chunk_syms);
+/* Bytes of device workspace fmtc_encode / fmtc_code_symbols need (symbols,
+ * histograms, code table, per-chunk sizes).  256-byte aligned pointer required. */
+size_t fmtc_workspace_size(int64_t P, int C, int bits, int chunk_syms);
+
+/* ---- hot path ---- */
+/* Whole encoder (section 3: transform, quantizer, VLC).  Reads d_x once, writes
+ * the container to d_stream_out (16-byte aligned, capacity cap >=
+ * fmtc_encode_bound) and, if d_out_bytes != NULL, the stream size in bytes.
+ * The Huffman table is built on the device from this tensor's histogram; the
+ * call never synchronises.  Delta = fmtc_delta(A of the basis, bits). */
+fmtc_status fmtc_encode(const fmtc_basis *basis, const float *d_x, int64_t N, int C, int H, int W,
+                        fmtc_layout layout, int bits, int chunk_syms, void *d_stream_out, size_t cap,
+                        uint64_t *d_out_bytes, void *d_workspace, size_t ws_bytes, void *hip_stream);
+
+/* Whole decoder (section 3: VLD, inverse quantizer, inverse transform).
+ * `bytes` is the readable size of d_stream_in (the exact stream size or any
+ * larger capacity); nothing beyond it is read.  d_xhat receives N*C*H*W floats
+ * in `layout`.  *d_err_flag (device u32, required) is cleared, then OR-ed with
+ * FMTC_ERR_* bits if the stream fails validation; in that case d_xhat is
+ * unspecified but no access leaves the given buffers. */
+fmtc_status fmtc_decode(const fmtc_basis *basis, const void *d_stream_in, size_t bytes, float *d_xhat, int64_t N,
+                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t *d_err_flag, void *hip_stream);
+
+/* ---- staged entry points (the same kernels, cut at the symbol boundary) ---- */
+/* Transform + quantizer + histogram only (section 3: y = T(x-mu), Q_Delta).
+ * d_syms: P*C bytes; d_hist: 256 u32 counts (may be NULL). */
+fmtc_status fmtc_quantize(const fmtc_basis *basis, const float *d_x, int64_t N, int C, int H, int W,
+                          fmtc_layout layout, int bits, uint8_t *d_syms, uint32_t *d_hist, void *d_workspace,
+                          size_t ws_bytes, void *hip_stream);
+
+/* Histogram + Huffman table + bit packing of given symbols (section 3.1
+ * "Variable length coding").  d_syms: P*C bytes, every value < 2^bits. */
+fmtc_status fmtc_code_symbols(const uint8_t *d_syms, int64_t P, int C, int bits, int chunk_syms, float delta,
+                              void *d_stream_out, size_t cap, uint64_t *d_out_bytes, void *d_workspace,
+                              size_t ws_bytes, void *hip_stream);
+
+/* Variable length decoder only: stream -> P*C symbol bytes. */
+fmtc_status fmtc_decode_symbols(const void *d_stream_in, size_t bytes, int64_t P, int C, int bits, uint8_t *d_syms,
+                                uint32_t *d_err_flag, void *hip_stream);
+
+/* Parses a 64-byte header copied to the host.  Any output may be NULL.
+ * stream_bytes is the total container size. */
+fmtc_status fmtc_stream_info(const void *h_header, size_t header_bytes, int *bits, int *C, int64_t *P,
+                             int *px_per_chunk, int64_t *n_chunks, float *delta, uint64_t *payload_bits,
+                             uint64_t *stream_bytes);
+
+/* ---- instrumentation (not part of the method) ----
+ * fmtc_profile_enable(n > 0) creates n HIP event pairs per kernel; from then on
+ * every kernel launch of the library is bracketed by events on the caller's
+ * stream, up to n launches per kernel.  fmtc_profile_enable(0) turns it off and
+ * frees the events.  fmtc_profile_read waits for the recorded launches of one
+ * kernel (index < fmtc_profile_kernels()) and returns their average and minimum
+ * duration in milliseconds.  Process-wide, not thread safe. */
+fmtc_status fmtc_profile_enable(int max_launches_per_kernel);
+int fmtc_profile_kernels(void);
+const char *fmtc_profile_name(int kernel);
+fmtc_status fmtc_profile_read(int kernel, double *avg_ms, double *min_ms, int *launches);
+
+/* Text of the last error on the calling thread ("" if none). */
+const char *fmtc_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FMTC_H */

@@ -1,0 +1,474 @@
+// Host side of libfmtc: argument checks, the basis handle, the offline fit and
+// the launch sequences of the encoder and decoder.  See include/fmtc.h.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "fmtc_internal.h"
+
+struct fmtc_basis {
+    int C = 0, Cpad = 0;
+    float range_A = 0.f;
+    std::vector<float> T, mu;
+    std::vector<double> eig;
+    float *d_fwd = nullptr, *d_inv = nullptr, *d_mu = nullptr, *d_T = nullptr;
+    int device = 0;
+};
+
+namespace {
+
+using namespace fmtc;
+
+thread_local char g_err[256] = "";
+
+fmtc_status fail(fmtc_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+fmtc_status hip_fail(hipError_t e, const char* what) {
+    return fail(FMTC_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool dims_ok(int64_t N, int C, int H, int W) {
+    if (N < 1 || C < 1 || C > 1024 || H < 1 || W < 1) return false;
+    long double v = (long double)N * C * H * W;
+    return v < 4294967296.0L;
+}
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// Operand order of the 32x32x2 fp32 matrix instruction: tile (nt, ms), lane l,
+// slot s <- M[nt*32 + l%32][ms*32 + perm(s, l/32)].
+void pack_operand(const std::vector<float>& T, int C, int Cpad, bool transpose, bool inverse_perm,
+                  std::vector<float>* out) {
+    const int nt_count = Cpad / 32;
+    out->assign((size_t)Cpad * Cpad, 0.f);
+    for (int nt = 0; nt < nt_count; nt++)
+        for (int ms = 0; ms < nt_count; ms++)
+            for (int lane = 0; lane < 64; lane++)
+                for (int s = 0; s < 16; s++) {
+                    int half = lane / 32;
+                    int row = nt * 32 + lane % 32;
+                    int col = ms * 32 + (inverse_perm ? 8 * (s / 4) + 4 * half + s % 4 : s + 16 * half);
+                    float v = 0.f;
+                    if (row < C && col < C) v = transpose ? T[(size_t)col * C + row] : T[(size_t)row * C + col];
+                    (*out)[(((size_t)nt * nt_count + ms) * 64 + lane) * 16 + s] = v;
+                }
+}
+
+fmtc_status upload_basis(fmtc_basis* b) {
+    const int C = b->C, Cpad = b->Cpad;
+    std::vector<float> fwd, inv, mu(Cpad, 0.f);
+    pack_operand(b->T, C, Cpad, false, false, &fwd);
+    pack_operand(b->T, C, Cpad, true, true, &inv);
+    for (int c = 0; c < C; c++) mu[c] = b->mu[c];
+    hipError_t e;
+    const size_t mat = sizeof(float) * (size_t)Cpad * Cpad;
+    if ((e = hipGetDevice(&b->device)) != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if ((e = hipMalloc((void**)&b->d_fwd, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    if ((e = hipMalloc((void**)&b->d_inv, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    if ((e = hipMalloc((void**)&b->d_mu, sizeof(float) * Cpad)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    if ((e = hipMemcpy(b->d_fwd, fwd.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
+    if ((e = hipMemcpy(b->d_inv, inv.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
+    if ((e = hipMemcpy(b->d_mu, mu.data(), sizeof(float) * Cpad, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
+    if ((e = hipMalloc((void**)&b->d_T, sizeof(float) * (size_t)C * C)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    if ((e = hipMemcpy(b->d_T, b->T.data(), sizeof(float) * (size_t)C * C, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
+    return FMTC_OK;
+}
+
+BasisDevice device_view(const fmtc_basis* b) {
+    BasisDevice v;
+    v.C = b->C;
+    v.Cpad = b->Cpad;
+    v.fwd = b->d_fwd;
+    v.inv = b->d_inv;
+    v.mu = b->d_mu;
+    v.T = b->d_T;
+    return v;
+}
+
+// Eigenvalues and eigenvectors of a symmetric matrix by threshold Jacobi
+// rotations on rows (the matrix and the accumulated rotations are kept so that
+// every update runs over contiguous memory).  a: n*n, overwritten; vt: n*n, row i
+// becomes the eigenvector of eigenvalue a[i][i].
+void symmetric_eigen(std::vector<double>& a, std::vector<double>& vt, int n) {
+    vt.assign((size_t)n * n, 0.0);
+    for (int i = 0; i < n; i++) vt[(size_t)i * n + i] = 1.0;
+    double total = 0.0;
+    for (double v : a) total += v * v;
+    if (total == 0.0) return;
+    for (int sweep = 0; sweep < 60; sweep++) {
+        double off = 0.0;
+        for (int p = 0; p < n; p++)
+            for (int q = p + 1; q < n; q++) off += a[(size_t)p * n + q] * a[(size_t)p * n + q];
+        if (2.0 * off <= 1e-28 * total) break;
+        for (int p = 0; p < n - 1; p++) {
+            double* ap = &a[(size_t)p * n];
+            for (int q = p + 1; q < n; q++) {
+                double* aq = &a[(size_t)q * n];
+                const double apq = ap[q];
+                if (apq == 0.0) continue;
+                const double diff = aq[q] - ap[p];
+                double t;
+                if (std::fabs(apq) < 1e-300 * std::fabs(diff)) {
+                    t = apq / diff;
+                } else {
+                    const double theta = 0.5 * diff / apq;
+                    t = 1.0 / (std::fabs(theta) + std::sqrt(theta * theta + 1.0));
+                    if (theta < 0.0) t = -t;
+                }
+                const double c = 1.0 / std::sqrt(t * t + 1.0), s = t * c;
+                const double app = ap[p], aqq = aq[q];
+                // rows p and q of A, then the two columns by symmetry
+                for (int k = 0; k < n; k++) {
+                    const double x = ap[k], y = aq[k];
+                    ap[k] = c * x - s * y;
+                    aq[k] = s * x + c * y;
+                }
+                ap[p] = app - t * apq;
+                aq[q] = aqq + t * apq;
+                ap[q] = 0.0;
+                aq[p] = 0.0;
+                for (int k = 0; k < n; k++) {
+                    if (k == p || k == q) continue;
+                    a[(size_t)k * n + p] = ap[k];
+                    a[(size_t)k * n + q] = aq[k];
+                }
+                double* vp = &vt[(size_t)p * n];
+                double* vq = &vt[(size_t)q * n];
+                for (int k = 0; k < n; k++) {
+                    const double x = vp[k], y = vq[k];
+                    vp[k] = c * x - s * y;
+                    vq[k] = s * x + c * y;
+                }
+            }
+        }
+    }
+}
+
+struct EncodePlan {
+    Geometry g;
+    Workspace ws;
+    uint64_t V;
+};
+
+fmtc_status plan_encode(int64_t P, int C, int bits, int chunk_syms, EncodePlan* pl) {
+    if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8], got %d", bits);
+    if (!make_geometry(P, C, chunk_syms, &pl->g))
+        return fail(FMTC_EINVAL, "bad geometry: P=%lld C=%d chunk_syms=%d", (long long)P, C, chunk_syms);
+    long double v = (long double)P * C;
+    if (v >= 4294967296.0L) return fail(FMTC_EINVAL, "tensor too large: V must be < 2^32");
+    pl->V = (uint64_t)P * (uint64_t)C;
+    pl->ws = make_workspace(pl->V, pl->g.n_chunks);
+    return FMTC_OK;
+}
+
+size_t bound_from(const EncodePlan& pl, int bits) {
+    return pl.g.off_payload + 4 * (size_t)((pl.V * (uint64_t)bits + 31) / 32 + pl.g.n_chunks);
+}
+
+// histogram copies and counters -> table -> run sizes -> offsets -> payload
+fmtc_status run_coder(const uint8_t* d_syms, const EncodePlan& pl, int bits, float delta, uint8_t* ws,
+                      uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s) {
+    hipError_t e;
+    uint32_t* hist_copies = reinterpret_cast<uint32_t*>(ws + pl.ws.off_hist_copies);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(ws + pl.ws.off_hist);
+    uint64_t* enc_table = reinterpret_cast<uint64_t*>(ws + pl.ws.off_enc_table);
+    uint32_t* chunk_bits = reinterpret_cast<uint32_t*>(ws + pl.ws.off_chunk_bits);
+    if ((e = launch_huffman_table(hist_copies, bits, hist, enc_table, d_stream + kHeaderBytes, s)) != hipSuccess)
+        return hip_fail(e, "huffman table kernel");
+    if ((e = launch_pack(d_syms, pl.g, bits, delta, enc_table, chunk_bits, d_stream, d_out_bytes, s)) != hipSuccess)
+        return hip_fail(e, "pack kernels");
+    return FMTC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fmtc_last_error(void) { return g_err; }
+
+float fmtc_delta(float range_A, int bits) {
+    if (!(range_A > 0.0f) || bits < 2 || bits > 8) return 1.0f;
+    return (float)((double)range_A / (double)((1 << (bits - 1)) - 1));
+}
+
+int fmtc_basis_channels(const fmtc_basis* basis) { return basis ? basis->C : 0; }
+
+void fmtc_basis_destroy(fmtc_basis* b) {
+    if (!b) return;
+    if (b->d_fwd) (void)hipFree(b->d_fwd);
+    if (b->d_inv) (void)hipFree(b->d_inv);
+    if (b->d_mu) (void)hipFree(b->d_mu);
+    if (b->d_T) (void)hipFree(b->d_T);
+    delete b;
+}
+
+fmtc_status fmtc_basis_import(int C, const float* h_T, const float* h_mu, float range_A, fmtc_basis** out) {
+    if (!out) return fail(FMTC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (C < 1 || C > 1024 || !h_T || !h_mu) return fail(FMTC_EINVAL, "bad basis arguments (C=%d)", C);
+    if (!(range_A >= 0.f)) return fail(FMTC_EINVAL, "range_A must be >= 0");
+    fmtc_basis* b = new (std::nothrow) fmtc_basis;
+    if (!b) return fail(FMTC_ENOMEM, "host allocation failed");
+    b->C = C;
+    b->Cpad = (C + 31) / 32 * 32;
+    b->range_A = range_A;
+    b->T.assign(h_T, h_T + (size_t)C * C);
+    b->mu.assign(h_mu, h_mu + C);
+    b->eig.assign(C, 0.0);
+    fmtc_status st = upload_basis(b);
+    if (st != FMTC_OK) {
+        fmtc_basis_destroy(b);
+        return st;
+    }
+    *out = b;
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_basis_export(const fmtc_basis* b, float* h_T, float* h_mu, double* h_eigvals, float* range_A) {
+    if (!b) return fail(FMTC_EINVAL, "basis is NULL");
+    if (h_T) memcpy(h_T, b->T.data(), sizeof(float) * b->T.size());
+    if (h_mu) memcpy(h_mu, b->mu.data(), sizeof(float) * b->mu.size());
+    if (h_eigvals) memcpy(h_eigvals, b->eig.data(), sizeof(double) * b->eig.size());
+    if (range_A) *range_A = b->range_A;
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_fit_basis(const float* d_x, int64_t N, int C, int H, int W, fmtc_layout layout, void* hip_stream,
+                           fmtc_basis** out) {
+    if (!out) return fail(FMTC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!d_x || !dims_ok(N, C, H, W)) return fail(FMTC_EINVAL, "bad tensor arguments");
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int64_t HW = (int64_t)H * W, P = N * HW;
+    hipError_t e;
+    double* d_stat = nullptr;  // [C] sums, [C*C] covariance sums, [1] amax
+    const size_t n_stat = (size_t)C + (size_t)C * C + 1;
+    if ((e = hipMalloc((void**)&d_stat, sizeof(double) * n_stat)) != hipSuccess)
+        return fail(FMTC_ENOMEM, "hipMalloc fit scratch: %s", hipGetErrorString(e));
+    fmtc_status st = FMTC_OK;
+    std::vector<double> stat(n_stat), vt;
+    float *d_t0 = nullptr, *d_mu = nullptr;
+    fmtc_basis* b = nullptr;
+    do {
+        if ((e = launch_clear(reinterpret_cast<uint32_t*>(d_stat), 2 * n_stat, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
+        if ((e = launch_fit_moments(d_x, N, C, HW, layout, d_stat, d_stat + C, s)) != hipSuccess) { st = hip_fail(e, "fit moments"); break; }
+        if ((e = hipMemcpyAsync(stat.data(), d_stat, sizeof(double) * n_stat, hipMemcpyDeviceToHost, s)) != hipSuccess) { st = hip_fail(e, "copy moments"); break; }
+        if ((e = hipStreamSynchronize(s)) != hipSuccess) { st = hip_fail(e, "fit sync"); break; }
+        std::vector<double> cov((size_t)C * C);
+        for (size_t i = 0; i < cov.size(); i++) cov[i] = stat[C + i] / (double)P;
+        // the two triangles are accumulated separately on the device; make the matrix exactly symmetric
+        for (int i = 0; i < C; i++)
+            for (int j = i + 1; j < C; j++) {
+                double m = 0.5 * (cov[(size_t)i * C + j] + cov[(size_t)j * C + i]);
+                cov[(size_t)i * C + j] = cov[(size_t)j * C + i] = m;
+            }
+        symmetric_eigen(cov, vt, C);
+        std::vector<int> order(C);
+        for (int i = 0; i < C; i++) order[i] = i;
+        for (int i = 1; i < C; i++) {  // stable, descending eigenvalue
+            int o = order[i], j = i - 1;
+            double ev = cov[(size_t)o * C + o];
+            while (j >= 0 && cov[(size_t)order[j] * C + order[j]] < ev) { order[j + 1] = order[j]; j--; }
+            order[j + 1] = o;
+        }
+        b = new (std::nothrow) fmtc_basis;
+        if (!b) { st = fail(FMTC_ENOMEM, "host allocation failed"); break; }
+        b->C = C;
+        b->Cpad = (C + 31) / 32 * 32;
+        b->T.resize((size_t)C * C);
+        b->mu.resize(C);
+        b->eig.resize(C);
+        for (int k = 0; k < C; k++) {
+            const double* v = &vt[(size_t)order[k] * C];
+            b->eig[k] = cov[(size_t)order[k] * C + order[k]];
+            int arg = 0;
+            for (int c = 1; c < C; c++)
+                if (std::fabs(v[c]) > std::fabs(v[arg])) arg = c;
+            const double sgn = v[arg] < 0.0 ? -1.0 : 1.0;
+            for (int c = 0; c < C; c++) b->T[(size_t)k * C + c] = (float)(sgn * v[c]);
+        }
+        for (int c = 0; c < C; c++) b->mu[c] = (float)(stat[c] / (double)P);
+        // dynamic range of the leading component with the rounded basis
+        if ((e = hipMalloc((void**)&d_t0, sizeof(float) * C)) != hipSuccess || (e = hipMalloc((void**)&d_mu, sizeof(float) * C)) != hipSuccess) { st = fail(FMTC_ENOMEM, "hipMalloc: %s", hipGetErrorString(e)); break; }
+        if ((e = hipMemcpyAsync(d_t0, b->T.data(), sizeof(float) * C, hipMemcpyHostToDevice, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
+        if ((e = hipMemcpyAsync(d_mu, b->mu.data(), sizeof(float) * C, hipMemcpyHostToDevice, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
+        double* d_amax = d_stat + (n_stat - 1);
+        if ((e = launch_clear(reinterpret_cast<uint32_t*>(d_amax), 2, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
+        if ((e = launch_fit_range(d_x, N, C, HW, layout, d_t0, d_mu, d_amax, s)) != hipSuccess) { st = hip_fail(e, "fit range"); break; }
+        double amax = 0.0;
+        if ((e = hipMemcpyAsync(&amax, d_amax, sizeof(double), hipMemcpyDeviceToHost, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
+        if ((e = hipStreamSynchronize(s)) != hipSuccess) { st = hip_fail(e, "fit sync"); break; }
+        b->range_A = (float)amax;
+        st = upload_basis(b);
+    } while (0);
+    (void)hipFree(d_stat);
+    if (d_t0) (void)hipFree(d_t0);
+    if (d_mu) (void)hipFree(d_mu);
+    if (st != FMTC_OK) {
+        fmtc_basis_destroy(b);
+        return st;
+    }
+    *out = b;
+    return FMTC_OK;
+}
+
+size_t fmtc_encode_bound(int64_t P, int C, int bits, int chunk_syms) {
+    EncodePlan pl;
+    if (plan_encode(P, C, bits, chunk_syms, &pl) != FMTC_OK) return 0;
+    return bound_from(pl, bits);
+}
+
+size_t fmtc_workspace_size(int64_t P, int C, int bits, int chunk_syms) {
+    EncodePlan pl;
+    if (plan_encode(P, C, bits, chunk_syms, &pl) != FMTC_OK) return 0;
+    return pl.ws.total;
+}
+
+fmtc_status fmtc_quantize(const fmtc_basis* basis, const float* d_x, int64_t N, int C, int H, int W,
+                          fmtc_layout layout, int bits, uint8_t* d_syms, uint32_t* d_hist, void* d_workspace,
+                          size_t ws_bytes, void* hip_stream) {
+    if (!basis || !d_x || !d_syms || !d_workspace) return fail(FMTC_EINVAL, "NULL argument");
+    if (!dims_ok(N, C, H, W) || basis->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", basis->C, C);
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
+    if (!aligned(d_x, 16) || !aligned(d_syms, 16) || !aligned(d_workspace, 256)) return fail(FMTC_EINVAL, "misaligned pointer");
+    const Workspace ws = make_workspace(0, 0);
+    if (ws_bytes < ws.off_chunk_bits) return fail(FMTC_EBUFSIZE, "workspace too small");
+    hipStream_t s = (hipStream_t)hip_stream;
+    uint8_t* w = static_cast<uint8_t*>(d_workspace);
+    uint32_t* hist_copies = reinterpret_cast<uint32_t*>(w + ws.off_hist_copies);
+    hipError_t e;
+    if ((e = launch_clear(hist_copies, (ws.off_hist - ws.off_hist_copies) / 4, s)) != hipSuccess) return hip_fail(e, "clear");
+    const float delta = fmtc_delta(basis->range_A, bits);
+    if ((e = launch_project_quantize(device_view(basis), d_x, N, (int64_t)H * W, layout, delta, bits, d_syms, hist_copies, s)) != hipSuccess)
+        return hip_fail(e, "project/quantize kernel");
+    if (d_hist) {
+        // sum of the copies: the table kernel does it; its other outputs go to the workspace
+        if ((e = launch_huffman_table(hist_copies, bits, d_hist, reinterpret_cast<uint64_t*>(w + ws.off_enc_table),
+                                      w + ws.off_hist /* length table scratch */, s)) != hipSuccess)
+            return hip_fail(e, "histogram reduction");
+    }
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_encode(const fmtc_basis* basis, const float* d_x, int64_t N, int C, int H, int W,
+                        fmtc_layout layout, int bits, int chunk_syms, void* d_stream_out, size_t cap,
+                        uint64_t* d_out_bytes, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!basis || !d_x || !d_stream_out || !d_workspace) return fail(FMTC_EINVAL, "NULL argument");
+    if (!dims_ok(N, C, H, W) || basis->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", basis->C, C);
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    if (!aligned(d_x, 16) || !aligned(d_stream_out, 16) || !aligned(d_workspace, 256) || !aligned(d_out_bytes, 8))
+        return fail(FMTC_EINVAL, "misaligned pointer");
+    EncodePlan pl;
+    const int64_t HW = (int64_t)H * W;
+    fmtc_status st = plan_encode(N * HW, C, bits, chunk_syms, &pl);
+    if (st != FMTC_OK) return st;
+    if (ws_bytes < pl.ws.total) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, pl.ws.total);
+    if (cap < bound_from(pl, bits)) return fail(FMTC_EBUFSIZE, "stream capacity too small: %zu < %zu", cap, bound_from(pl, bits));
+    hipStream_t s = (hipStream_t)hip_stream;
+    uint8_t* w = static_cast<uint8_t*>(d_workspace);
+    uint32_t* hist_copies = reinterpret_cast<uint32_t*>(w + pl.ws.off_hist_copies);
+    uint8_t* syms = w + pl.ws.off_syms;
+    hipError_t e;
+    if ((e = launch_clear(hist_copies, (pl.ws.off_hist - pl.ws.off_hist_copies) / 4, s)) != hipSuccess) return hip_fail(e, "clear");
+    const float delta = fmtc_delta(basis->range_A, bits);
+    if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, syms, hist_copies, s)) != hipSuccess)
+        return hip_fail(e, "project/quantize kernel");
+    return run_coder(syms, pl, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
+}
+
+fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits, int chunk_syms, float delta,
+                              void* d_stream_out, size_t cap, uint64_t* d_out_bytes, void* d_workspace,
+                              size_t ws_bytes, void* hip_stream) {
+    if (!d_syms || !d_stream_out || !d_workspace) return fail(FMTC_EINVAL, "NULL argument");
+    if (!(delta > 0.f)) return fail(FMTC_EINVAL, "delta must be > 0");
+    if (!aligned(d_syms, 16) || !aligned(d_stream_out, 16) || !aligned(d_workspace, 256) || !aligned(d_out_bytes, 8))
+        return fail(FMTC_EINVAL, "misaligned pointer");
+    EncodePlan pl;
+    fmtc_status st = plan_encode(P, C, bits, chunk_syms, &pl);
+    if (st != FMTC_OK) return st;
+    if (ws_bytes < pl.ws.off_syms) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, pl.ws.off_syms);
+    if (cap < bound_from(pl, bits)) return fail(FMTC_EBUFSIZE, "stream capacity too small: %zu < %zu", cap, bound_from(pl, bits));
+    hipStream_t s = (hipStream_t)hip_stream;
+    uint8_t* w = static_cast<uint8_t*>(d_workspace);
+    uint32_t* hist_copies = reinterpret_cast<uint32_t*>(w + pl.ws.off_hist_copies);
+    uint32_t* counters = reinterpret_cast<uint32_t*>(w + pl.ws.off_counters);
+    hipError_t e;
+    if ((e = launch_clear(hist_copies, (pl.ws.off_hist - pl.ws.off_hist_copies) / 4, s)) != hipSuccess) return hip_fail(e, "clear");
+    if ((e = launch_histogram(d_syms, pl.V, bits, hist_copies, counters, s)) != hipSuccess) return hip_fail(e, "histogram kernel");
+    return run_coder(d_syms, pl, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
+}
+
+static fmtc_status decode_common(const fmtc_basis* basis, const void* d_stream_in, size_t bytes, int64_t P, int C,
+                                 int64_t HW, int layout, int bits, float* d_xhat, uint8_t* d_syms,
+                                 uint32_t* d_err_flag, void* hip_stream) {
+    if (!d_stream_in || !d_err_flag) return fail(FMTC_EINVAL, "NULL argument");
+    if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
+    if (!aligned(d_stream_in, 16) || !aligned(d_err_flag, 4) || !aligned(d_xhat, 16) || !aligned(d_syms, 16))
+        return fail(FMTC_EINVAL, "misaligned pointer");
+    Geometry g;
+    if (!make_geometry(P, C, 4096, &g)) return fail(FMTC_EINVAL, "bad geometry");
+    if ((long double)P * C >= 4294967296.0L) return fail(FMTC_EINVAL, "tensor too large: V must be < 2^32");
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e;
+    if ((e = launch_clear(d_err_flag, 1, s)) != hipSuccess) return hip_fail(e, "clear");
+    BasisDevice view;
+    if (basis) view = device_view(basis);
+    if ((e = launch_decode(basis ? &view : nullptr, static_cast<const uint8_t*>(d_stream_in), bytes, g, bits, HW,
+                           layout, d_xhat, d_syms, d_err_flag, s)) != hipSuccess)
+        return hip_fail(e, "decode kernel");
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_decode(const fmtc_basis* basis, const void* d_stream_in, size_t bytes, float* d_xhat, int64_t N,
+                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t* d_err_flag, void* hip_stream) {
+    if (!basis || !d_xhat) return fail(FMTC_EINVAL, "NULL argument");
+    if (!dims_ok(N, C, H, W) || basis->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", basis->C, C);
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    const int64_t HW = (int64_t)H * W;
+    return decode_common(basis, d_stream_in, bytes, N * HW, C, HW, layout, bits, d_xhat, nullptr, d_err_flag, hip_stream);
+}
+
+fmtc_status fmtc_decode_symbols(const void* d_stream_in, size_t bytes, int64_t P, int C, int bits, uint8_t* d_syms,
+                                uint32_t* d_err_flag, void* hip_stream) {
+    if (!d_syms) return fail(FMTC_EINVAL, "NULL argument");
+    if (P < 1 || C < 1 || C > 1024) return fail(FMTC_EINVAL, "bad dims");
+    return decode_common(nullptr, d_stream_in, bytes, P, C, 1, FMTC_NHWC, bits, nullptr, d_syms, d_err_flag, hip_stream);
+}
+
+fmtc_status fmtc_stream_info(const void* h_header, size_t header_bytes, int* bits, int* C, int64_t* P,
+                             int* px_per_chunk, int64_t* n_chunks, float* delta, uint64_t* payload_bits,
+                             uint64_t* stream_bytes) {
+    if (!h_header || header_bytes < (size_t)kHeaderBytes) return fail(FMTC_EINVAL, "need the 64 header bytes");
+    Header h;
+    memcpy(&h, h_header, sizeof h);
+    if (h.magic != kMagic || h.version != 1) return fail(FMTC_ECORRUPT, "not a stream header");
+    if (h.bits < 2 || h.bits > 8 || h.C < 1 || h.C > 1024 || h.px_per_chunk < 1 || h.P < 1)
+        return fail(FMTC_ECORRUPT, "header fields out of range");
+    const uint64_t nch = (h.P + h.px_per_chunk - 1) / h.px_per_chunk;
+    const uint64_t spc = ((uint64_t)h.px_per_chunk * h.C + kSubSyms - 1) / kSubSyms;
+    if (nch != h.n_chunks || spc != h.subs_per_chunk) return fail(FMTC_ECORRUPT, "header geometry inconsistent");
+    const size_t off_sub = align_up(kHeaderBytes + kLenTableBytes + 4 * ((size_t)nch + 1), 16);
+    const size_t off_pay = align_up(off_sub + 2 * (size_t)nch * spc, 16);
+    if (bits) *bits = h.bits;
+    if (C) *C = (int)h.C;
+    if (P) *P = (int64_t)h.P;
+    if (px_per_chunk) *px_per_chunk = (int)h.px_per_chunk;
+    if (n_chunks) *n_chunks = (int64_t)nch;
+    if (delta) *delta = h.delta;
+    if (payload_bits) *payload_bits = h.payload_bits;
+    if (stream_bytes) *stream_bytes = off_pay + 4 * h.payload_words;
+    return FMTC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,343 @@
+// Variable length coder (paper section 3.1 "Variable length coding"; appendix
+// "Huffman encoder as VLC"): Huffman code lengths from the symbol histogram,
+// canonical code words, per-run bit counts, chunk offsets and the packed stream.
+// All integer work; results are unique, so they are bit-exact by construction.
+#include "fmtc_internal.h"
+
+namespace fmtc {
+
+// ---------------------------------------------------------------------------
+// Code table.  One workgroup.  Lengths follow the classic construction: leaves
+// ordered by (count, symbol), the two lightest nodes merged until one is left; a
+// leaf wins over an internal node of equal weight, internal nodes leave in the
+// order they were made.  Codes are canonical in (length, symbol) order.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_huffman_table(const uint32_t* __restrict__ hist_copies, int bits,
+                                                       uint32_t* __restrict__ hist_out,
+                                                       uint64_t* __restrict__ enc_table,
+                                                       uint8_t* __restrict__ len_table) {
+    __shared__ uint32_t h[256];
+    __shared__ uint32_t weight[512];  // leaves (sorted) then internal nodes
+    __shared__ uint16_t parent[512];
+    __shared__ uint16_t depth[512];
+    __shared__ uint16_t leaf_sym[256];
+    __shared__ uint8_t len[256];
+    __shared__ uint32_t len_count[kMaxLen + 2];
+    __shared__ uint64_t first_code[kMaxLen + 2];
+    __shared__ int n_used;
+
+    const int s = threadIdx.x;
+    const int K = 1 << bits;
+    uint32_t cnt = 0;
+    if (s < K)
+        for (int c = 0; c < kHistCopies; c++) cnt += hist_copies[c * 256 + s];
+    h[s] = cnt;
+    len[s] = 0;
+    if (s <= kMaxLen + 1) len_count[s] = 0;
+    if (s == 0) n_used = 0;
+    __syncthreads();
+    hist_out[s] = cnt;
+
+    // rank of every used symbol in (count, symbol) order
+    int rank = 0;
+    if (cnt) {
+        for (int t = 0; t < K; t++) {
+            uint32_t o = h[t];
+            rank += (o != 0 && (o < cnt || (o == cnt && t < s))) ? 1 : 0;
+        }
+        weight[rank] = cnt;
+        leaf_sym[rank] = (uint16_t)s;
+        atomicAdd(&n_used, 1);
+    }
+    __syncthreads();
+    const int n = n_used;
+
+    if (s == 0 && n >= 2) {
+        int next_leaf = 0, next_int = n, made = n;
+        for (int m = 0; m < n - 1; m++) {
+            uint32_t w = 0;
+            for (int t = 0; t < 2; t++) {
+                bool have_leaf = next_leaf < n, have_int = next_int < made;
+                int pick;
+                if (have_leaf && (!have_int || weight[next_leaf] <= weight[next_int])) pick = next_leaf++;
+                else pick = next_int++;
+                w += weight[pick];
+                parent[pick] = (uint16_t)made;
+            }
+            weight[made] = w;
+            made++;
+        }
+        int root = made - 1;
+        depth[root] = 0;
+        for (int node = root - 1; node >= 0; node--) depth[node] = depth[parent[node]] + 1;
+    }
+    __syncthreads();
+
+    if (cnt) {
+        int l = (n >= 2) ? depth[rank] : 1;
+        if (l > kMaxLen) l = kMaxLen;  // unreachable for V < 2^32 (depth d needs a total count >= Fibonacci(d+2))
+        len[s] = (uint8_t)l;
+        atomicAdd(&len_count[l], 1u);
+    }
+    __syncthreads();
+    if (s == 0) {
+        uint64_t code = 0;
+        first_code[0] = 0;
+        for (int l = 1; l <= kMaxLen; l++) {
+            code = (code + len_count[l - 1]) << 1;
+            first_code[l] = code;
+        }
+    }
+    __syncthreads();
+    const int l = len[s];
+    uint64_t entry = 0;
+    if (l) {
+        int before = 0;
+        for (int t = 0; t < s; t++) before += (len[t] == l) ? 1 : 0;
+        uint64_t code = first_code[l] + (uint64_t)before;
+        uint64_t rev = __brevll(code) >> (64 - l);  // stream order is least significant bit first
+        entry = rev | ((uint64_t)l << 56);
+    }
+    enc_table[s] = entry;
+    len_table[s] = (uint8_t)l;
+}
+
+hipError_t launch_huffman_table(const uint32_t* d_hist_copies, int bits, uint32_t* d_hist, uint64_t* d_enc_table,
+                                uint8_t* d_len_table, hipStream_t s) {
+    ProfScope prof(K_TABLE, s);
+    hipLaunchKernelGGL(k_huffman_table, dim3(1), dim3(256), 0, s, d_hist_copies, bits, d_hist, d_enc_table,
+                       d_len_table);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Pass 1 of packing: code bits of every run of 64 symbols and of every chunk.
+// One wavefront per chunk, one lane per run.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// exclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v, int lane) {
+    uint32_t incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t t = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += t;
+    }
+    return incl - v;
+}
+
+__global__ __launch_bounds__(256) void k_run_bits(const uint8_t* __restrict__ syms, uint64_t V, uint32_t n_chunks,
+                                                  uint32_t chunk_syms, uint32_t subs_per_chunk,
+                                                  const uint64_t* __restrict__ enc_table,
+                                                  uint16_t* __restrict__ sub_bits,
+                                                  uint32_t* __restrict__ chunk_bits) {
+    __shared__ uint8_t llen[256];
+    llen[threadIdx.x] = (uint8_t)(enc_table[threadIdx.x] >> 56);
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const uint32_t ch = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (ch >= n_chunks) return;
+    const uint64_t c0 = (uint64_t)ch * chunk_syms;
+    const uint64_t c1 = (c0 + chunk_syms < V) ? c0 + chunk_syms : V;
+    const uint64_t r0 = c0 + (uint64_t)lane * kSubSyms;
+    uint32_t bits = 0;
+    if (r0 < c1) {
+        const uint32_t cnt = (uint32_t)((c1 - r0 < kSubSyms) ? (c1 - r0) : kSubSyms);
+        if (cnt == kSubSyms && ((uintptr_t)(syms + r0) & 15) == 0) {
+            const uint4* p = reinterpret_cast<const uint4*>(syms + r0);
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                uint4 v = p[j];
+                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+#pragma unroll
+                    for (int b = 0; b < 4; b++) bits += llen[(w[q] >> (8 * b)) & 255];
+            }
+        } else {
+            for (uint32_t i = 0; i < cnt; i++) bits += llen[syms[r0 + i]];
+        }
+    }
+    if ((uint32_t)lane < subs_per_chunk) sub_bits[(size_t)ch * subs_per_chunk + lane] = (uint16_t)bits;
+    uint32_t total = wave_sum(bits);
+    if (lane == 0) chunk_bits[ch] = total;
+}
+
+// ---------------------------------------------------------------------------
+// Chunk offsets: exclusive scan of the chunk sizes in words, header, stream size.
+// One workgroup, sequential over tiles of 256 chunks.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_chunk_offsets(const uint32_t* __restrict__ chunk_bits, uint32_t n_chunks,
+                                                       Header hdr, size_t off_sub_bits, size_t off_payload,
+                                                       uint8_t* __restrict__ stream,
+                                                       uint64_t* __restrict__ out_bytes) {
+    uint32_t* chunk_off = reinterpret_cast<uint32_t*>(stream + kHeaderBytes + kLenTableBytes);
+    __shared__ uint32_t wsum[4];
+    __shared__ uint64_t bsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint64_t base_words = 0, total_bits = 0;
+    for (uint32_t t0 = 0; t0 < n_chunks; t0 += 256) {
+        uint32_t i = t0 + tid;
+        uint32_t b = (i < n_chunks) ? chunk_bits[i] : 0u;
+        uint32_t w = (b + 31) >> 5;
+        uint32_t ex = wave_exclusive_scan(w, lane);
+        uint32_t bs = wave_sum(b);
+        if (lane == 63) wsum[wave] = ex + w;
+        if (lane == 0) bsum[wave] = bs;
+        __syncthreads();
+        uint32_t woff = 0;
+        for (int q = 0; q < wave; q++) woff += wsum[q];
+        if (i < n_chunks) chunk_off[i] = (uint32_t)(base_words + woff + ex);
+        base_words += (uint64_t)wsum[0] + wsum[1] + wsum[2] + wsum[3];
+        total_bits += bsum[0] + bsum[1] + bsum[2] + bsum[3];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        chunk_off[n_chunks] = (uint32_t)base_words;
+        hdr.payload_words = base_words;
+        hdr.payload_bits = total_bits;
+        *reinterpret_cast<Header*>(stream) = hdr;
+        if (out_bytes) *out_bytes = (uint64_t)off_payload + 4 * base_words;
+        // alignment gaps between the sections are part of the stream: keep them zero
+        for (size_t o = kHeaderBytes + kLenTableBytes + 4 * ((size_t)n_chunks + 1); o < off_sub_bits; o++) stream[o] = 0;
+        for (size_t o = off_sub_bits + 2 * (size_t)n_chunks * hdr.subs_per_chunk; o < off_payload; o++) stream[o] = 0;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Pass 2 of packing.  One wavefront per chunk, one lane per run.  The lane's
+// bit offset inside the chunk is the prefix sum of the run sizes; codes are
+// appended least significant stream bit first into a 64-bit register and
+// leave as 32-bit words OR-ed into an LDS image of the chunk, which is then
+// copied out with full-width stores.  A chunk larger than the LDS image is
+// produced in several windows (the runs are re-read per window).
+// ---------------------------------------------------------------------------
+constexpr int kStageWords = 2048;  // per wavefront: 64 Kbit, i.e. 16 bits/symbol over a 4096-symbol chunk
+
+__global__ __launch_bounds__(256) void k_pack(const uint8_t* __restrict__ syms, uint64_t V, uint32_t n_chunks,
+                                              uint32_t chunk_syms, uint32_t subs_per_chunk,
+                                              const uint64_t* __restrict__ enc_table,
+                                              const uint16_t* __restrict__ sub_bits,
+                                              const uint32_t* __restrict__ chunk_off,
+                                              uint32_t* __restrict__ payload) {
+    __shared__ uint64_t tab[256];
+    __shared__ uint32_t stage[4][kStageWords];
+    tab[threadIdx.x] = enc_table[threadIdx.x];
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t ch = blockIdx.x * 4 + wave;
+    if (ch >= n_chunks) return;  // whole wavefront leaves; no workgroup barrier follows
+    uint32_t* img = stage[wave];
+    const uint64_t c0 = (uint64_t)ch * chunk_syms;
+    const uint64_t c1 = (c0 + chunk_syms < V) ? c0 + chunk_syms : V;
+    const uint64_t r0 = c0 + (uint64_t)lane * kSubSyms;
+    const uint32_t cnt = (r0 < c1) ? (uint32_t)((c1 - r0 < kSubSyms) ? (c1 - r0) : kSubSyms) : 0u;
+    const uint32_t my_bits = ((uint32_t)lane < subs_per_chunk) ? sub_bits[(size_t)ch * subs_per_chunk + lane] : 0u;
+    const uint32_t start = wave_exclusive_scan(my_bits, lane);
+    const uint32_t total_bits = __shfl(start + my_bits, 63, 64);
+    const uint32_t n_words = (total_bits + 31) >> 5;
+    uint32_t* out = payload + chunk_off[ch];
+
+    for (uint32_t win = 0; win < n_words; win += kStageWords) {
+        const uint32_t win_words = (n_words - win < (uint32_t)kStageWords) ? n_words - win : (uint32_t)kStageWords;
+        for (uint32_t i = lane; i < win_words; i += 64) img[i] = 0u;
+        // LDS operations of one wavefront complete in order: the zeros land before the ORs below
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t first_word = start >> 5, last_word = (start + my_bits + 31) >> 5;  // [first, last)
+        if (cnt && my_bits && first_word < win + win_words && last_word > win) {
+            uint64_t acc = 0;
+            uint32_t nb = start & 31;
+            uint32_t widx = first_word;
+            auto emit = [&](uint32_t word) {
+                uint32_t rel = widx - win;
+                if (rel < win_words) atomicOr(&img[rel], word);
+                widx++;
+            };
+            auto put = [&](uint64_t code, uint32_t len) {  // len <= 32, nb < 32
+                acc |= code << nb;
+                nb += len;
+                if (nb >= 32) {
+                    emit((uint32_t)acc);
+                    acc >>= 32;
+                    nb -= 32;
+                }
+            };
+            auto code_symbol = [&](uint32_t sym) {
+                uint64_t e = tab[sym];
+                uint32_t len = (uint32_t)(e >> 56);
+                uint64_t code = e & 0x00ffffffffffffffull;
+                if (len > 32) {
+                    put(code & 0xffffffffull, 32);
+                    put(code >> 32, len - 32);
+                } else {
+                    put(code, len);
+                }
+            };
+            if (cnt == kSubSyms && ((uintptr_t)(syms + r0) & 15) == 0) {
+                const uint4* p = reinterpret_cast<const uint4*>(syms + r0);
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    uint4 v = p[j];
+                    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int q = 0; q < 4; q++)
+#pragma unroll
+                        for (int b = 0; b < 4; b++) code_symbol((w[q] >> (8 * b)) & 255);
+                }
+            } else {
+                for (uint32_t i = 0; i < cnt; i++) code_symbol(syms[r0 + i]);
+            }
+            if (nb) emit((uint32_t)acc);
+        }
+        // the ORs of all lanes precede the reads below: one wavefront, LDS in order
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (uint32_t i = lane; i < win_words; i += 64) out[win + i] = img[i];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+hipError_t launch_pack(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const uint64_t* d_enc_table,
+                       uint32_t* d_chunk_bits, uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s) {
+    const uint64_t V = (uint64_t)g.P * (uint64_t)g.C;
+    uint16_t* sub_bits = reinterpret_cast<uint16_t*>(d_stream + g.off_sub_bits);
+    uint32_t* chunk_off = reinterpret_cast<uint32_t*>(d_stream + g.off_chunk_off);
+    uint32_t* payload = reinterpret_cast<uint32_t*>(d_stream + g.off_payload);
+    const unsigned blocks = (g.n_chunks + 3) / 4;
+    {
+        ProfScope prof(K_RUN_BITS, s);
+        hipLaunchKernelGGL(k_run_bits, dim3(blocks), dim3(256), 0, s, d_syms, V, g.n_chunks, g.chunk_syms,
+                           g.subs_per_chunk, d_enc_table, sub_bits, d_chunk_bits);
+    }
+    Header hdr = {};
+    hdr.magic = kMagic;
+    hdr.version = 1;
+    hdr.bits = (uint8_t)bits;
+    hdr.C = (uint32_t)g.C;
+    hdr.px_per_chunk = g.px_per_chunk;
+    hdr.P = (uint64_t)g.P;
+    hdr.n_chunks = g.n_chunks;
+    hdr.sub_syms = kSubSyms;
+    hdr.delta = delta;
+    hdr.subs_per_chunk = g.subs_per_chunk;
+    {
+        ProfScope prof(K_OFFSETS, s);
+        hipLaunchKernelGGL(k_chunk_offsets, dim3(1), dim3(256), 0, s, d_chunk_bits, g.n_chunks, hdr, g.off_sub_bits,
+                           g.off_payload, d_stream, d_out_bytes);
+    }
+    {
+        ProfScope prof(K_PACK, s);
+        hipLaunchKernelGGL(k_pack, dim3(blocks), dim3(256), 0, s, d_syms, V, g.n_chunks, g.chunk_syms,
+                           g.subs_per_chunk, d_enc_table, sub_bits, chunk_off, payload);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace fmtc

@@ -1,0 +1,143 @@
+// Internal declarations shared by the host API and the kernel files of libfmtc.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fmtc.h"
+
+namespace fmtc {
+
+constexpr uint32_t kMagic = 0x43544D46u;  // bytes 'F','M','T','C'
+constexpr int kHeaderBytes = 64;
+constexpr int kLenTableBytes = 256;
+constexpr int kSubSyms = 64;     // symbols per run; one lane codes one run
+constexpr int kMaxLen = 48;      // longest code length accepted
+constexpr int kHistCopies = 16;  // replicated global histograms (spreads atomics over L2 channels)
+constexpr int kLutBits = 10;     // decoder lookup table covers codes up to this length
+
+// 64-byte stream header (see fmtc.h for the field meaning).
+struct alignas(8) Header {
+    uint32_t magic;
+    uint16_t version;
+    uint8_t bits;
+    uint8_t reserved0;
+    uint32_t C;
+    uint32_t px_per_chunk;
+    uint64_t P;
+    uint32_t n_chunks;
+    uint32_t sub_syms;
+    float delta;
+    uint32_t subs_per_chunk;
+    uint64_t payload_words;
+    uint64_t payload_bits;
+    uint64_t reserved1;
+};
+static_assert(sizeof(Header) == kHeaderBytes, "header must be 64 bytes");
+
+// Where the sections of a container start, from the tensor geometry alone.
+struct Geometry {
+    int64_t P;
+    int C;
+    uint32_t px_per_chunk, n_chunks, subs_per_chunk;
+    uint32_t chunk_syms;  // px_per_chunk * C
+    size_t off_chunk_off, off_sub_bits, off_payload;
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline bool make_geometry(int64_t P, int C, int chunk_syms, Geometry* g) {
+    if (P < 1 || C < 1 || C > 1024 || chunk_syms < 64 || chunk_syms > 4096) return false;
+    int64_t ppc = chunk_syms / C;
+    if (ppc < 1) ppc = 1;
+    int64_t nch = (P + ppc - 1) / ppc;
+    if (nch > 0x7fffffff) return false;
+    g->P = P;
+    g->C = C;
+    g->px_per_chunk = (uint32_t)ppc;
+    g->n_chunks = (uint32_t)nch;
+    g->chunk_syms = (uint32_t)(ppc * C);
+    g->subs_per_chunk = (g->chunk_syms + kSubSyms - 1) / kSubSyms;
+    g->off_chunk_off = kHeaderBytes + kLenTableBytes;
+    g->off_sub_bits = align_up(g->off_chunk_off + 4 * ((size_t)nch + 1), 16);
+    g->off_payload = align_up(g->off_sub_bits + 2 * (size_t)nch * g->subs_per_chunk, 16);
+    return true;
+}
+
+// Device workspace of the encoder.
+struct Workspace {
+    size_t off_hist_copies;  // u32 [kHistCopies][256], cleared per call
+    size_t off_counters;     // u32 [16], cleared per call
+    size_t off_hist;         // u32 [256] final histogram
+    size_t off_enc_table;    // u64 [256]: bit-reversed code | length << 56
+    size_t off_chunk_bits;   // u32 [n_chunks]
+    size_t off_syms;         // u8 [V]
+    size_t total;
+};
+
+inline Workspace make_workspace(uint64_t V, uint32_t n_chunks) {
+    Workspace w;
+    size_t o = 0;
+    w.off_hist_copies = o;
+    o += sizeof(uint32_t) * kHistCopies * 256;
+    w.off_counters = o;
+    o += 64;
+    w.off_hist = o;
+    o += sizeof(uint32_t) * 256;
+    w.off_enc_table = o;
+    o += sizeof(uint64_t) * 256;
+    w.off_chunk_bits = o;
+    o = align_up(o + sizeof(uint32_t) * (size_t)n_chunks, 256);
+    w.off_syms = o;
+    o = align_up(o + (size_t)V, 256);
+    w.total = o;
+    return w;
+}
+
+// Operand packing of the basis for the MFMA kernels (32x32x2 f32 tiles):
+// tile (nt, ms), lane l, slot s holds M[nt*32 + l%32][ms*32 + perm(s, l/32)],
+// zero outside CxC.  perm for the forward operand: s + 16*half; for the
+// inverse operand: 8*(s/4) + 4*half + s%4.
+struct BasisDevice {
+    int C, Cpad;           // Cpad = C rounded up to 32
+    const float* fwd;      // M = T      (row = coefficient k, column = channel c)
+    const float* inv;      // M = T^T    (row = channel c, column = coefficient k)
+    const float* mu;       // [Cpad], zero padded
+    const float* T;        // [C][C] row major, unpacked
+};
+
+// ---- optional per-kernel timing (fmtc_profile_* in fmtc.h); no-ops unless enabled ----
+enum KernelId { K_CLEAR = 0, K_PROJECT, K_HISTOGRAM, K_TABLE, K_RUN_BITS, K_OFFSETS, K_PACK, K_DECODE, K_COUNT };
+void prof_mark(int id, bool end, hipStream_t s);
+struct ProfScope {
+    int id;
+    hipStream_t s;
+    ProfScope(int id_, hipStream_t s_) : id(id_), s(s_) { prof_mark(id, false, s); }
+    ~ProfScope() { prof_mark(id, true, s); }
+};
+
+// ---- kernel launchers (definitions in the *_kernels.hip files) ----
+hipError_t launch_clear(uint32_t* d_words, size_t n_words, hipStream_t s);
+
+hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
+                                   float delta, int bits, uint8_t* d_syms, uint32_t* d_hist_copies,
+                                   hipStream_t s);
+
+hipError_t launch_histogram(const uint8_t* d_syms, uint64_t V, int bits, uint32_t* d_hist_copies,
+                            uint32_t* d_counters, hipStream_t s);
+
+hipError_t launch_huffman_table(const uint32_t* d_hist_copies, int bits, uint32_t* d_hist, uint64_t* d_enc_table,
+                                uint8_t* d_len_table, hipStream_t s);
+
+hipError_t launch_pack(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const uint64_t* d_enc_table,
+                       uint32_t* d_chunk_bits, uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s);
+
+hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
+                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, hipStream_t s);
+
+hipError_t launch_fit_moments(const float* d_x, int64_t N, int C, int64_t HW, int layout, double* d_sum,
+                              double* d_cov, hipStream_t s);
+hipError_t launch_fit_range(const float* d_x, int64_t N, int C, int64_t HW, int layout, const float* d_t0,
+                            const float* d_mu, double* d_amax, hipStream_t s);
+
+}  // namespace fmtc

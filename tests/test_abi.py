@@ -1,0 +1,89 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared entry
+point, and its host-only helpers agree with the oracle's container geometry."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1905_10830_amd import binding as fmtc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(fmtc.LIB_PATH):
+        from paper_1905_10830_amd import build
+
+        build.build()
+    return fmtc.load_library()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "fmtc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fmtc_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert sorted(names) == sorted(fmtc.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_no_torch_types_in_the_header():
+    text = open(os.path.join(ROOT, "include", "fmtc.h")).read()
+    assert "at::" not in text and "torch" not in text.lower().replace("pytorch", "")
+    assert 'extern "C"' in text
+
+
+def test_delta_matches_oracle(lib, oracle):
+    for A in (0.0, 1.0, 3.7, 127.0, 1e-3, 55.5):
+        for bits in range(2, 9):
+            assert np.float32(fmtc.delta(A, bits)) == oracle.delta(A, bits)
+
+
+def test_sizes_match_oracle_geometry(lib, oracle):
+    for P, C, bits, cs in [(3136, 64, 8, 4096), (25088, 128, 6, 4096), (200704, 144, 5, 4096), (3136, 960, 5, 4096),
+                           (77, 3, 3, 64), (1, 1, 2, 64), (1000, 50, 4, 4096)]:
+        assert fmtc.encode_bound(P, C, bits, cs) == oracle.stream_bound(P, C, bits, cs)
+        assert fmtc.workspace_size(P, C, bits, cs) >= P * C
+    assert fmtc.encode_bound(0, 64, 4, 4096) == 0
+    assert fmtc.encode_bound(10, 2000, 4, 4096) == 0
+    assert fmtc.encode_bound(10, 64, 9, 4096) == 0
+    assert fmtc.encode_bound(1 << 40, 64, 4, 4096) == 0  # V must stay below 2^32
+
+
+def test_stream_info_parses_an_oracle_header(lib, oracle):
+    rng = np.random.default_rng(0)
+    sym = rng.integers(0, 16, (500, 24)).astype(np.uint8)
+    h = oracle.histogram(sym, 4)
+    ln = oracle.huffman_lengths(h[:16])
+    stream = oracle.pack(sym, 24, 4, 0.375, ln, oracle.canonical_codes(ln))
+    info = fmtc.stream_info(stream[:64])
+    ref = oracle.parse_header(stream)
+    assert info["bits"] == 4 and info["C"] == 24 and info["P"] == 500
+    assert info["px_per_chunk"] == ref["px_per_chunk"] and info["n_chunks"] == ref["n_chunks"]
+    assert info["delta"] == 0.375 and info["payload_bits"] == ref["payload_bits"]
+    assert info["stream_bytes"] == len(stream)
+    bad = stream[:64].copy()
+    bad[0] ^= 1
+    with pytest.raises(fmtc.FmtcError) as e:
+        fmtc.stream_info(bad)
+    assert e.value.status == fmtc.ECORRUPT
+
+
+def test_argument_errors_are_reported_on_the_host(lib):
+    """NULL / range errors come back as a status before anything is launched."""
+    out = ctypes.c_void_p()
+    st = lib.fmtc_basis_import(0, None, None, 1.0, ctypes.byref(out))
+    assert st == fmtc.EINVAL and b"basis" in lib.fmtc_last_error()
+    st = lib.fmtc_encode(None, None, 1, 64, 8, 8, fmtc.NHWC, 4, 4096, None, 0, None, None, 0, None)
+    assert st == fmtc.EINVAL
+    st = lib.fmtc_decode(None, None, 0, None, 1, 64, 8, 8, fmtc.NHWC, 4, None, None)
+    assert st == fmtc.EINVAL
+    st = lib.fmtc_decode_symbols(None, 0, 10, 64, 4, None, None, None)
+    assert st == fmtc.EINVAL
