@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the transform codec hot path on one MI355X.
+
+One step = fmtc_encode followed by fmtc_decode of one batch of synthetic
+activations (the ResNet-18 stage-2 shape: N=32, C=128, 28x28, fp32, NHWC, b=6,
+4096-symbol chunks; basis fitted offline on a separate 8-image calibration
+batch).  Inputs are resident in HBM before the timed region; the step rotates
+through enough buffer sets that the working set exceeds the 256 MB last-level
+cache.  Prints ONE JSON line (see the fields below).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--bits 6] [--workload NAME]
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3  # dense fp32 matrix rate (256 CUs x 256 flop/clk x 2.4 GHz)
+
+# HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/*pmc*.txt), keyed by (workload, bits, kernel).  None where no counter run exists.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--bits", type=int, default=6)
+    ap.add_argument("--workload", default="resnet18_stage2_c128_28")
+    ap.add_argument("--layout", default="nhwc", choices=["nhwc", "nchw"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hot", action="store_true", help="one buffer set only (cache-hot figure)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is a one-GPU codec; run it with --gpus 1 "
+                 "(no multi-GPU path exists, see DESIGN.md for how it would shard)")
+
+    import numpy as np
+    import torch
+
+    from paper_1905_10830_amd import binding as fmtc
+    from paper_1905_10830_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: needs a GPU")
+    torch.cuda.set_device(0)
+    lib = fmtc.load_library()
+
+    wl = synth.WORKLOADS[args.workload]
+    bits = args.bits
+    layout = fmtc.NHWC if args.layout == "nhwc" else fmtc.NCHW
+    calib, data = synth.workload(args.workload, seed=0)
+    xs = synth.to_layout(data, layout)
+    N, C, H, W = wl["N"], wl["C"], wl["H"], wl["W"]
+    P, V = N * H * W, N * H * W * C
+    in_bytes = 4 * V
+
+    # ---- offline: fit the basis on the calibration batch (GPU moments + host eigensolver) ----
+    basis = fmtc.fit_basis(torch.from_numpy(synth.to_layout(calib, layout)).cuda(), layout)
+
+    # ---- buffer sets ----
+    cap = fmtc.encode_bound(P, C, bits)
+    ws_bytes = fmtc.workspace_size(P, C, bits)
+    per_set = 2 * in_bytes + cap + ws_bytes
+    R = 1 if args.hot else max(2, int(np.ceil(320e6 / per_set)))
+    x0 = torch.from_numpy(xs).cuda()
+    sets = []
+    for r in range(R):
+        sets.append(dict(
+            x=x0.clone(), stream=torch.empty(cap, dtype=torch.uint8, device="cuda"),
+            nbytes=torch.zeros(1, dtype=torch.int64, device="cuda"),
+            ws=torch.empty(ws_bytes, dtype=torch.uint8, device="cuda"),
+            xhat=torch.empty_like(x0), err=torch.zeros(1, dtype=torch.int32, device="cuda")))
+    stream_h = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def enc_args(s):
+        return (basis._h, s["x"].data_ptr(), N, C, H, W, layout, bits, 4096, s["stream"].data_ptr(), cap,
+                s["nbytes"].data_ptr(), s["ws"].data_ptr(), ws_bytes, stream_h)
+
+    def dec_args(s):
+        return (basis._h, s["stream"].data_ptr(), cap, s["xhat"].data_ptr(), N, C, H, W, layout, bits,
+                s["err"].data_ptr(), stream_h)
+
+    ea = [enc_args(s) for s in sets]
+    da = [dec_args(s) for s in sets]
+
+    def step(i):
+        r = i % R
+        st = lib.fmtc_encode(*ea[r])
+        st |= lib.fmtc_decode(*da[r])
+        return st
+
+    def run(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        bad = 0
+        for i in range(n):
+            bad |= fn(i)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        if bad:
+            raise RuntimeError("a library call failed: " + lib.fmtc_last_error().decode())
+        return dt
+
+    run(step, args.warmup)
+    dt = run(step, args.steps)
+    ms_per_step = 1e3 * dt / args.steps
+    # encode and decode alone (same buffers; streams are valid from the runs above)
+    dt_enc = run(lambda i: lib.fmtc_encode(*ea[i % R]), args.steps)
+    dt_dec = run(lambda i: lib.fmtc_decode(*da[i % R]), args.steps)
+    for s in sets:
+        assert int(s["err"].item()) == 0, "decoder flagged its own stream"
+
+    # ---- rate and distortion of the coded batch ----
+    info = fmtc.stream_info(sets[0]["stream"][:64].cpu().numpy())
+    R_payload = info["payload_bits"] / V
+    R_container = 8.0 * info["stream_bytes"] / V
+    mse = float(((sets[0]["xhat"] - sets[0]["x"]) ** 2).mean().item())
+
+    # ---- per-kernel durations over one more pass of the same steps (HIP events on the launch stream) ----
+    fmtc.profile_enable(args.steps)
+    run(step, args.steps)
+    prof = fmtc.profile_read()
+    fmtc.profile_enable(0)
+
+    flops = 2.0 * C * V
+    alg = {  # algorithmic work per launch: (bound, amount, unit of the rate)
+        "k_project_quantize": ("mfma", flops, "TFLOP/s"),
+        "k_decode": ("mfma", flops, "TFLOP/s"),
+        "k_run_bits": ("hbm", V + 2.0 * V / 64, "GB/s"),
+        "k_pack": ("hbm", V + info["payload_bits"] / 8.0, "GB/s"),
+    }
+    kernels = {}
+    for name, (avg_ms, min_ms, n) in prof.items():
+        entry = {"avg_us": round(1e3 * avg_ms, 3), "min_us": round(1e3 * min_ms, 3), "launches": n}
+        if name in alg:
+            bound, amount, unit = alg[name]
+            peak = MFMA_F32_PEAK_TFLOPS if bound == "mfma" else HBM_PEAK_GBS
+            ach = amount / (avg_ms * 1e-3) / (1e12 if bound == "mfma" else 1e9)
+            entry.update(bound=bound, achieved=round(ach, 3), peak=peak, unit=unit, frac=round(ach / peak, 4))
+        kernels[name] = entry
+    dominant = max((k for k in kernels if k in alg), key=lambda k: kernels[k]["avg_us"])
+    dk = kernels[dominant]
+    roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
+                "unit": dk["unit"], "frac": dk["frac"],
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, bits, dominant)),
+                "avg_us": dk["avg_us"],
+                "hbm_bytes_algorithmic": (4 * V + V) if dominant == "k_project_quantize" else
+                                         (4 * V + info["stream_bytes"])}
+
+    # ---- the oracle on this machine's host cores, same tensors ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        T, mu, eig, A = basis.export()
+        d = oracle.delta(A, bits)
+        reps, t_cpu = 0, 0.0
+        while reps < 3 and t_cpu < 20.0:
+            t0 = time.perf_counter()
+            enc = oracle.encode(xs, T, mu, d, bits, layout)
+            oracle.decode(enc["stream"], xs.shape, T, mu, bits, layout)
+            t_cpu += time.perf_counter() - t0
+            reps += 1
+        cpu = {"value": round(in_bytes / (t_cpu / reps) / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"the full batch ({N} images), encode+decode, mean of {reps} runs, single thread"}
+
+    out = {
+        "metric": "encode+decode throughput of fp32 activations (input GB/s)",
+        "value": round(in_bytes / (ms_per_step * 1e-3) / 1e9, 3),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "shape_NCHW": [N, C, H, W], "layout": args.layout, "bits": bits,
+                   "chunk_syms": 4096, "buffer_sets": R, "cache": "hot" if args.hot else "cold (rotating > 256 MB)"},
+        "encode_GBps": round(in_bytes / (dt_enc / args.steps) / 1e9, 3),
+        "decode_GBps": round(in_bytes / (dt_dec / args.steps) / 1e9, 3),
+        "bits_per_value": round(R_payload, 4),
+        "container_bits_per_value": round(R_container, 4),
+        "mse": mse,
+        "roofline": roofline,
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
