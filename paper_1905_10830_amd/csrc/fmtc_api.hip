@@ -56,7 +56,7 @@ void pack_operand(const std::vector<float>& T, int C, int Cpad, bool transpose, 
                 for (int s = 0; s < 16; s++) {
                     int half = lane / 32;
                     int row = nt * 32 + lane % 32;
-                    int col = ms * 32 + (inverse_perm ? 8 * (s / 4) + 4 * half + s % 4 : s + 16 * half);
+                    int col = ms * 32 + (inverse_perm ? 8 * (s / 4) + 4 * half + s % 4 : 2 * s + half);
                     float v = 0.f;
                     if (row < C && col < C) v = transpose ? T[(size_t)col * C + row] : T[(size_t)row * C + col];
                     (*out)[(((size_t)nt * nt_count + ms) * 64 + lane) * 16 + s] = v;

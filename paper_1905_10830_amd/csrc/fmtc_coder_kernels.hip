@@ -12,15 +12,36 @@ namespace fmtc {
 // leaf wins over an internal node of equal weight, internal nodes leave in the
 // order they were made.  Codes are canonical in (length, symbol) order.
 // ---------------------------------------------------------------------------
+// one value of a per-lane array spread over NV registers (64 entries each); idx is wavefront-uniform
+template <int NV>
+__device__ __forceinline__ uint32_t lane_get(const uint32_t (&v)[NV], int idx) {
+    uint32_t r = (uint32_t)__builtin_amdgcn_readlane((int)v[0], idx & 63);
+#pragma unroll
+    for (int j = 1; j < NV; j++) {
+        uint32_t t = (uint32_t)__builtin_amdgcn_readlane((int)v[j], idx & 63);
+        r = ((idx >> 6) == j) ? t : r;
+    }
+    return r;
+}
+template <int NV>
+__device__ __forceinline__ void lane_set(uint32_t (&v)[NV], int lane, int idx, uint32_t val) {
+#pragma unroll
+    for (int j = 0; j < NV; j++) v[j] = (64 * j + lane == idx) ? val : v[j];
+}
+
+// The merge loop is serial by nature (n-1 steps).  It runs in one wavefront with
+// the two queues held in registers across the lanes and all control in scalar
+// registers, so a step costs a few lane reads/writes instead of LDS round trips.
+// NV * 64 >= alphabet size.
+template <int NV>
 __global__ __launch_bounds__(256) void k_huffman_table(const uint32_t* __restrict__ hist_copies, int bits,
                                                        uint32_t* __restrict__ hist_out,
                                                        uint64_t* __restrict__ enc_table,
                                                        uint8_t* __restrict__ len_table) {
     __shared__ uint32_t h[256];
-    __shared__ uint32_t weight[512];  // leaves (sorted) then internal nodes
-    __shared__ uint16_t parent[512];
-    __shared__ uint16_t depth[512];
-    __shared__ uint16_t leaf_sym[256];
+    __shared__ uint32_t weight[256];       // leaf weights in (count, symbol) order
+    __shared__ uint16_t leaf_parent[256];  // index of the internal node above each sorted leaf
+    __shared__ uint16_t int_parent[256];   // ... above each internal node (creation order)
     __shared__ uint8_t len[256];
     __shared__ uint32_t len_count[kMaxLen + 2];
     __shared__ uint64_t first_code[kMaxLen + 2];
@@ -46,47 +67,72 @@ __global__ __launch_bounds__(256) void k_huffman_table(const uint32_t* __restric
             rank += (o != 0 && (o < cnt || (o == cnt && t < s))) ? 1 : 0;
         }
         weight[rank] = cnt;
-        leaf_sym[rank] = (uint16_t)s;
         atomicAdd(&n_used, 1);
     }
     __syncthreads();
-    const int n = n_used;
+    const int n = __builtin_amdgcn_readfirstlane(n_used);
 
-    if (s == 0 && n >= 2) {
-        int next_leaf = 0, next_int = n, made = n;
+    if (s < 64 && n >= 2) {
+        const int lane = s;
+        uint32_t lw[NV], iw[NV], lpar[NV], ipar[NV];
+#pragma unroll
+        for (int j = 0; j < NV; j++) {
+            lw[j] = (64 * j + lane < n) ? weight[64 * j + lane] : 0xffffffffu;
+            iw[j] = 0xffffffffu;
+            lpar[j] = 0;
+            ipar[j] = 0;
+        }
+        // an exhausted queue shows weight 2^32-1; no node that can still be picked weighs that much (V < 2^32)
+        int nl = 0, ni = 0, made = 0;
+        uint32_t lh = lane_get<NV>(lw, 0), ih = 0xffffffffu;
         for (int m = 0; m < n - 1; m++) {
             uint32_t w = 0;
+#pragma unroll
             for (int t = 0; t < 2; t++) {
-                bool have_leaf = next_leaf < n, have_int = next_int < made;
-                int pick;
-                if (have_leaf && (!have_int || weight[next_leaf] <= weight[next_int])) pick = next_leaf++;
-                else pick = next_int++;
-                w += weight[pick];
-                parent[pick] = (uint16_t)made;
+                if (lh <= ih) {  // a leaf wins over an internal node of equal weight
+                    w += lh;
+                    lane_set<NV>(lpar, lane, nl, (uint32_t)made);
+                    nl++;
+                    lh = (nl < n) ? lane_get<NV>(lw, nl) : 0xffffffffu;
+                } else {
+                    w += ih;
+                    lane_set<NV>(ipar, lane, ni, (uint32_t)made);
+                    ni++;
+                    ih = (ni < made) ? lane_get<NV>(iw, ni) : 0xffffffffu;
+                }
             }
-            weight[made] = w;
+            lane_set<NV>(iw, lane, made, w);
+            if (ni == made) ih = w;  // the new node heads an empty internal queue
             made++;
         }
-        int root = made - 1;
-        depth[root] = 0;
-        for (int node = root - 1; node >= 0; node--) depth[node] = depth[parent[node]] + 1;
+#pragma unroll
+        for (int j = 0; j < NV; j++) {
+            leaf_parent[64 * j + lane] = (uint16_t)lpar[j];
+            int_parent[64 * j + lane] = (uint16_t)ipar[j];
+        }
     }
     __syncthreads();
 
     if (cnt) {
-        int l = (n >= 2) ? depth[rank] : 1;
+        int l = 1;
+        if (n >= 2) {
+            const int root = n - 2;
+            int cur = leaf_parent[rank];
+            while (cur != root && l <= kMaxLen) {  // depth = number of ancestors
+                cur = int_parent[cur];
+                l++;
+            }
+        }
         if (l > kMaxLen) l = kMaxLen;  // unreachable for V < 2^32 (depth d needs a total count >= Fibonacci(d+2))
         len[s] = (uint8_t)l;
         atomicAdd(&len_count[l], 1u);
     }
     __syncthreads();
-    if (s == 0) {
+    if (s >= 1 && s <= kMaxLen) {
+        // first canonical code of every length: code(l) = sum_{j<l} count(j) << (l-j)
         uint64_t code = 0;
-        first_code[0] = 0;
-        for (int l = 1; l <= kMaxLen; l++) {
-            code = (code + len_count[l - 1]) << 1;
-            first_code[l] = code;
-        }
+        for (int j = 1; j < s; j++) code += (uint64_t)len_count[j] << (s - j);
+        first_code[s] = code;
     }
     __syncthreads();
     const int l = len[s];
@@ -105,8 +151,15 @@ __global__ __launch_bounds__(256) void k_huffman_table(const uint32_t* __restric
 hipError_t launch_huffman_table(const uint32_t* d_hist_copies, int bits, uint32_t* d_hist, uint64_t* d_enc_table,
                                 uint8_t* d_len_table, hipStream_t s) {
     ProfScope prof(K_TABLE, s);
-    hipLaunchKernelGGL(k_huffman_table, dim3(1), dim3(256), 0, s, d_hist_copies, bits, d_hist, d_enc_table,
-                       d_len_table);
+    if (bits <= 6)
+        hipLaunchKernelGGL(k_huffman_table<1>, dim3(1), dim3(256), 0, s, d_hist_copies, bits, d_hist, d_enc_table,
+                           d_len_table);
+    else if (bits == 7)
+        hipLaunchKernelGGL(k_huffman_table<2>, dim3(1), dim3(256), 0, s, d_hist_copies, bits, d_hist, d_enc_table,
+                           d_len_table);
+    else
+        hipLaunchKernelGGL(k_huffman_table<4>, dim3(1), dim3(256), 0, s, d_hist_copies, bits, d_hist, d_enc_table,
+                           d_len_table);
     return hipGetLastError();
 }
 
@@ -140,7 +193,7 @@ __global__ __launch_bounds__(256) void k_run_bits(const uint8_t* __restrict__ sy
     llen[threadIdx.x] = (uint8_t)(enc_table[threadIdx.x] >> 56);
     __syncthreads();
     const int lane = threadIdx.x & 63;
-    const uint32_t ch = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const uint32_t ch = blockIdx.x * 4 + (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     if (ch >= n_chunks) return;
     const uint64_t c0 = (uint64_t)ch * chunk_syms;
     const uint64_t c1 = (c0 + chunk_syms < V) ? c0 + chunk_syms : V;
@@ -229,7 +282,8 @@ __global__ __launch_bounds__(256) void k_pack(const uint8_t* __restrict__ syms, 
     __shared__ uint32_t stage[4][kStageWords];
     tab[threadIdx.x] = enc_table[threadIdx.x];
     __syncthreads();
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));  // wavefront-uniform by construction
     const uint32_t ch = blockIdx.x * 4 + wave;
     if (ch >= n_chunks) return;  // whole wavefront leaves; no workgroup barrier follows
     uint32_t* img = stage[wave];
@@ -241,7 +295,7 @@ __global__ __launch_bounds__(256) void k_pack(const uint8_t* __restrict__ syms, 
     const uint32_t start = wave_exclusive_scan(my_bits, lane);
     const uint32_t total_bits = __shfl(start + my_bits, 63, 64);
     const uint32_t n_words = (total_bits + 31) >> 5;
-    uint32_t* out = payload + chunk_off[ch];
+    uint32_t* out = payload + (uint32_t)__builtin_amdgcn_readfirstlane((int)chunk_off[ch]);
 
     for (uint32_t win = 0; win < n_words; win += kStageWords) {
         const uint32_t win_words = (n_words - win < (uint32_t)kStageWords) ? n_words - win : (uint32_t)kStageWords;

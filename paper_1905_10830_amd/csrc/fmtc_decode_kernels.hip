@@ -30,6 +30,77 @@ __device__ __forceinline__ uint32_t dec_wave_exclusive_scan(uint32_t v, int lane
 // pad bytes so that the 64 lanes of a decoding wavefront hit different banks
 __device__ __forceinline__ uint32_t sym_addr(uint32_t n) { return n + 4u * (n >> 6); }
 
+
+// Decodes the `cnt` symbols of one run (one lane) starting at bit `start` of a chunk.
+// STAGED: the chunk's words are in LDS (`pw`, two zero words behind them); otherwise they are read from
+// global memory (`gw`), zero past the chunk's end.  Returns false if bits matched no code word.
+template <bool STAGED, bool ALIGNED4>
+__device__ __forceinline__ bool decode_run(const uint32_t* pw, const uint32_t* __restrict__ gw, uint32_t nwords,
+                                           uint32_t start, uint32_t cnt, uint32_t nbase, const uint16_t* lut,
+                                           const uint32_t* cnt_len, const uint32_t* first_rank,
+                                           const uint64_t* first_code, const uint16_t* sorted_sym,
+                                           uint8_t* symtile) {
+    auto fetch = [&](uint32_t rel) -> uint64_t {
+        if constexpr (STAGED) return (uint64_t)pw[rel < nwords + 1 ? rel : nwords + 1];
+        else return (rel < nwords) ? (uint64_t)gw[rel] : 0ull;
+    };
+    // word index can not wrap: start <= 64 runs * 65535 bits
+    uint32_t widx = start >> 5;
+    uint64_t window = fetch(widx) | (fetch(widx + 1) << 32);
+    widx += 2;
+    window >>= (start & 31);
+    uint32_t avail = 64 - (start & 31);
+    uint64_t nxt = fetch(widx);
+    bool ok = true;
+    uint32_t word = 0;
+    for (uint32_t i = 0; i < cnt; i++) {
+        // refill without a branch: more than 32 valid bits before every lookup
+        const bool need = avail <= 32;
+        window |= need ? (nxt << (avail & 63)) : 0ull;
+        avail += need ? 32u : 0u;
+        widx += need ? 1u : 0u;
+        nxt = fetch(widx);
+        uint32_t e = lut[window & ((1u << kLutBits) - 1)];
+        uint32_t len = e >> 8, sym = e & 255;
+        if (len) {
+            window >>= len;
+            avail -= len;
+        } else {
+            // code longer than the table: canonical decoding bit by bit
+            uint64_t code = 0;
+            bool found = false;
+            for (int l = 1; l <= kMaxLen; l++) {
+                if (avail <= 32) {
+                    window |= fetch(widx++) << avail;
+                    avail += 32;
+                }
+                code = (code << 1) | (window & 1);
+                window >>= 1;
+                avail--;
+                uint64_t f = first_code[l];
+                uint32_t c = cnt_len[l];
+                if (c && code >= f && code - f < c) {
+                    sym = sorted_sym[first_rank[l] + (uint32_t)(code - f)];
+                    found = true;
+                    break;
+                }
+            }
+            if (!found) { ok = false; sym = 0; }
+            nxt = fetch(widx);
+        }
+        if constexpr (ALIGNED4) {
+            word |= sym << (8 * (i & 3));
+            if ((i & 3) == 3) {
+                *reinterpret_cast<uint32_t*>(symtile + sym_addr(nbase + i - 3)) = word;
+                word = 0;
+            }
+        } else {
+            symtile[sym_addr(nbase + i)] = (uint8_t)sym;
+        }
+    }
+    return ok;
+}
+
 struct DecodeParams {
     const uint8_t* stream;
     size_t bytes;
@@ -47,6 +118,8 @@ struct DecodeParams {
     uint32_t* err;
 };
 
+constexpr int kPayWords = 1022;  // LDS copy of a chunk's payload: up to ~8 bits/symbol; larger chunks read global memory
+
 template <int MT, int LAYOUT, bool ALIGNED4>
 __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
     __shared__ uint16_t lut[1 << kLutBits];
@@ -57,9 +130,11 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
     __shared__ uint64_t first_code[kMaxLen + 2];
     __shared__ unsigned long long kraft;
     __shared__ uint32_t n_used, bad_len;
+    __shared__ uint32_t pay[4][kPayWords + 2];  // per wavefront: the chunk's payload words
     extern __shared__ __align__(16) uint8_t symtile[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
     const int half = lane >> 5, l32 = lane & 31;
     const int C = p.C;
     const int K = 1 << p.bits;
@@ -119,16 +194,17 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
             return;
         }
     }
-    if (tid == 0) {
+    if (tid >= 1 && tid <= kMaxLen) {
+        // first code and first rank of every length: code(l) = sum_{j<l} count(j) << (l-j)
         uint64_t code = 0;
         uint32_t rank = 0;
-        first_code[0] = 0; first_rank[0] = 0;
-        for (int l = 1; l <= kMaxLen; l++) {
-            code = (code + cnt_len[l - 1]) << 1;
-            rank += cnt_len[l - 1];
-            first_code[l] = code;
-            first_rank[l] = rank;
+        for (int j = 1; j < tid; j++) {
+            uint32_t c = cnt_len[j];
+            code += (uint64_t)c << (tid - j);
+            rank += c;
         }
+        first_code[tid] = code;
+        first_rank[tid] = rank;
     }
     __syncthreads();
     if (my_len) {
@@ -137,17 +213,25 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
         sorted_sym[first_rank[my_len] + before] = (uint16_t)tid;
     }
     __syncthreads();
-    for (int idx = tid; idx < (1 << kLutBits); idx += 256) {
-        uint32_t code = 0, e = 0;
+    {
+        uint32_t fc[kLutBits + 1], cn[kLutBits + 1], fr[kLutBits + 1];
+#pragma unroll
         for (int l = 1; l <= kLutBits; l++) {
-            code = (code << 1) | ((idx >> (l - 1)) & 1);
-            uint32_t c = cnt_len[l], f = (uint32_t)first_code[l];
-            if (c && code >= f && code - f < c) {
-                e = sorted_sym[first_rank[l] + code - f] | ((uint32_t)l << 8);
-                break;
-            }
+            fc[l] = (uint32_t)first_code[l];
+            cn[l] = cnt_len[l];
+            fr[l] = first_rank[l];
         }
-        lut[idx] = (uint16_t)e;
+        for (int idx = tid; idx < (1 << kLutBits); idx += 256) {
+            uint32_t code = 0, hit_len = 0, hit_rank = 0;
+#pragma unroll
+            for (int l = 1; l <= kLutBits; l++) {
+                code = (code << 1) | ((idx >> (l - 1)) & 1);
+                bool hit = hit_len == 0 && code >= fc[l] && code - fc[l] < cn[l];
+                hit_rank = hit ? fr[l] + code - fc[l] : hit_rank;
+                hit_len = hit ? (uint32_t)l : hit_len;
+            }
+            lut[idx] = hit_len ? (uint16_t)(sorted_sym[hit_rank] | (hit_len << 8)) : (uint16_t)0;
+        }
     }
     __syncthreads();
 
@@ -163,7 +247,9 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
             if (ch >= n_chunks) break;
             const uint64_t c0 = (uint64_t)ch * chunk_syms;
             const uint32_t clen = (uint32_t)((V - c0 < chunk_syms) ? (V - c0) : chunk_syms);
-            uint32_t w0 = chunk_off[ch], w1 = chunk_off[ch + 1];
+            // chunk bounds are the same for all lanes: keep them in scalar registers
+            uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)chunk_off[ch]);
+            uint32_t w1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)chunk_off[ch + 1]);
             if (w0 > w1 || w1 > payload_words) {
                 if (lane == 0) atomicOr(p.err, FMTC_ERR_OFFSETS);
                 w0 = 0; w1 = 0;
@@ -172,61 +258,27 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
             const uint32_t start = dec_wave_exclusive_scan(run_bits, lane);
             const uint32_t r0 = (uint32_t)lane * kSubSyms;
             const uint32_t cnt = (r0 < clen) ? ((clen - r0 < (uint32_t)kSubSyms) ? clen - r0 : (uint32_t)kSubSyms) : 0u;
-            if (cnt) {
-                auto fetch = [&](uint32_t widx) -> uint64_t { return (widx < w1) ? (uint64_t)payload[widx] : 0ull; };
-                // word index can not wrap: start <= 64 runs * 65535 bits
-                uint32_t widx = w0 + (start >> 5);
-                uint64_t window = fetch(widx) | (fetch(widx + 1) << 32);
-                widx += 2;
-                window >>= (start & 31);
-                uint32_t avail = 64 - (start & 31);
-                bool code_err = false;
-                const uint32_t nbase = (uint32_t)j * chunk_syms + r0;
-                uint32_t word = 0;
-                for (uint32_t i = 0; i < cnt; i++) {
-                    if (avail <= 32) {
-                        window |= fetch(widx++) << avail;
-                        avail += 32;
-                    }
-                    uint32_t e = lut[window & ((1u << kLutBits) - 1)];
-                    uint32_t len = e >> 8, sym = e & 255;
-                    if (len) {
-                        window >>= len;
-                        avail -= len;
-                    } else {
-                        // code longer than the table: canonical decoding bit by bit
-                        uint64_t code = 0;
-                        bool found = false;
-                        for (int l = 1; l <= kMaxLen; l++) {
-                            if (avail <= 32) {
-                                window |= fetch(widx++) << avail;
-                                avail += 32;
-                            }
-                            code = (code << 1) | (window & 1);
-                            window >>= 1;
-                            avail--;
-                            uint64_t f = first_code[l];
-                            uint32_t c = cnt_len[l];
-                            if (c && code >= f && code - f < c) {
-                                sym = sorted_sym[first_rank[l] + (uint32_t)(code - f)];
-                                found = true;
-                                break;
-                            }
-                        }
-                        if (!found) { code_err = true; sym = 0; }
-                    }
-                    if constexpr (ALIGNED4) {
-                        word |= sym << (8 * (i & 3));
-                        if ((i & 3) == 3) {
-                            *reinterpret_cast<uint32_t*>(symtile + sym_addr(nbase + i - 3)) = word;
-                            word = 0;
-                        }
-                    } else {
-                        symtile[sym_addr(nbase + i)] = (uint8_t)sym;
-                    }
-                }
-                if (code_err) atomicOr(p.err, FMTC_ERR_CODE);
+            const uint32_t nwords = w1 - w0;
+            const uint32_t nbase = (uint32_t)j * chunk_syms + r0;
+            uint32_t* pw = pay[wave];
+            bool ok_run = true;
+            if (nwords <= (uint32_t)kPayWords) {
+                // the chunk's payload goes to LDS with full-width loads
+                for (uint32_t i = lane; i < nwords + 2; i += 64) pw[i] = (i < nwords) ? payload[w0 + i] : 0u;
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                if (cnt)
+                    ok_run = decode_run<true, ALIGNED4>(pw, nullptr, nwords, start, cnt, nbase, lut, cnt_len,
+                                                        first_rank, first_code, sorted_sym, symtile);
+                // the next chunk of this wavefront overwrites pay[]: all lanes are done reading here
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            } else if (cnt) {
+                // a chunk too large for the LDS copy is read in place
+                ok_run = decode_run<false, ALIGNED4>(nullptr, payload + w0, nwords, start, cnt, nbase, lut, cnt_len,
+                                                     first_rank, first_code, sorted_sym, symtile);
             }
+            if (!ok_run) atomicOr(p.err, FMTC_ERR_CODE);
         }
         __syncthreads();
 
@@ -367,7 +419,7 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     const uint32_t n_tiles = (g.n_chunks + G - 1) / G;
     int groups = 1;
     if (!d_syms) {
-        groups = (int)((512 + n_tiles - 1) / n_tiles);
+        groups = (int)((256 + n_tiles - 1) / n_tiles);
         if (groups > ncs) groups = ncs;
         if (groups < 1) groups = 1;
     }

@@ -7,8 +7,10 @@
 // 4 wavefronts = WK coefficient tiles (32 each) x WP pixel groups; the basis
 // tile is read from its pre-packed operand order straight into registers, the
 // activations go through LDS (coalesced global reads, transposed so that a
-// wavefront reads 32 consecutive pixels of one channel).  The quantized tile is
-// staged in LDS and leaves as whole rows of symbols.
+// lanes of a wavefront read 32 pixels of one channel without bank conflicts).
+// Values that land too close to a rounding boundary for fp32 to decide are
+// recomputed in fp64 by the wavefront.  The quantized tile is staged in LDS and
+// leaves as whole rows of symbols.
 #include "fmtc_internal.h"
 
 namespace fmtc {
@@ -28,158 +30,129 @@ hipError_t launch_clear(uint32_t* d_words, size_t n_words, hipStream_t s) {
     return hipGetLastError();
 }
 
-// WK: wavefronts along the coefficient axis (1, 2 or 4); MT: 32-pixel tiles per
-// wavefront; LAYOUT: FMTC_NHWC / FMTC_NCHW; VEC: C % 4 == 0 (16-byte loads of
-// channels-last rows and 4-byte symbol stores are aligned).
-template <int WK, int MT, int LAYOUT, bool VEC>
+// PT: pixels per workgroup; MT: 32-pixel tiles per wavefront unit; LAYOUT: FMTC_NHWC / FMTC_NCHW;
+// VEC: C % 4 == 0 (16-byte loads of channels-last rows and 4-byte symbol stores are aligned).
+//
+// The workgroup first brings its whole pixel tile, all channels, into LDS (one round of loads in flight,
+// mean removed on the way), then its 4 wavefronts share out the work units (coefficient tile, pixel group)
+// of the workgroup's coefficient range [kt0, kt0 + ktg) without further barriers.
+template <int PT, int MT, int LAYOUT, bool VEC>
 __global__ __launch_bounds__(256) void k_project_quantize(const float* __restrict__ x,
                                                           const float* __restrict__ Apk,
                                                           const float* __restrict__ mu,
                                                           const float* __restrict__ Trow, int64_t P, int64_t HW,
-                                                          int C, int ncs, float inv_delta, float delta, float tau,
-                                                          int bits,
+                                                          int C, int ncs, int kt_per_group, float inv_delta,
+                                                          float delta, float tau, int bits,
                                                           uint8_t* __restrict__ syms,
                                                           uint32_t* __restrict__ hist_copies) {
-    constexpr int WP = 4 / WK;
-    constexpr int PT = WP * MT * 32;  // pixels per workgroup
-    constexpr int S = PT + 2;         // LDS row stride in floats: conflict-free writes (4S = 8 mod 64) and reads (16S = 32 mod 64)
-    constexpr int NLV = PT / 32;      // float4 loads per thread and channel step (channels-last, VEC)
-    constexpr int NLS = PT / 8;       // scalar loads per thread and channel step
-    constexpr int RSW = WK * 8 + 1;   // staging row stride in words
-
-    __shared__ float xs[2][32 * S];
+    extern __shared__ __align__(16) float dyn_lds[];
     __shared__ uint32_t lhist[256];
-    static_assert(sizeof(float) * 2 * 32 * S >= sizeof(uint32_t) * PT * RSW, "staging tile must fit");
+
+    const int Cpad = ncs * 32;
+    const int RS = Cpad + 2;  // pixel row stride in floats: lanes of a half-wavefront (32 pixels, one channel)
+                              // fall on the even banks, the other half (next channel) on the odd ones
+    const int kt0 = blockIdx.y * kt_per_group;
+    const int ktg = (ncs - kt0 < kt_per_group) ? ncs - kt0 : kt_per_group;
+    const int RSW = kt_per_group * 8 + 1;  // staging row stride in words
+    float* xs = dyn_lds;
+    uint32_t* st = reinterpret_cast<uint32_t*>(dyn_lds + (size_t)PT * RS);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wk = wave % WK, wp = wave / WK;
     const int half = lane >> 5, l32 = lane & 31;
     const int64_t px0 = (int64_t)blockIdx.x * PT;
-    const int kt = blockIdx.y * WK + wk;
-    const bool kt_valid = kt < ncs;
 
     lhist[tid] = 0u;
 
-    // ---- per-thread load coordinates (fixed over the channel steps) ----
-    float4 xv[VEC && LAYOUT == FMTC_NHWC ? NLV : 1];
-    float xsc[VEC && LAYOUT == FMTC_NHWC ? 1 : NLS];
-    int64_t nchw_base = 0;
-    bool nchw_ok = false;
-    if constexpr (LAYOUT == FMTC_NCHW) {
-        int64_t p = px0 + (tid % PT);
-        nchw_ok = p < P;
-        if (nchw_ok) {
-            int64_t n = p / HW, hw = p - n * HW;
-            nchw_base = n * (int64_t)C * HW + hw;
+    // ---- the pixel tile, mean removed, as xs[pixel][channel] ----
+    if constexpr (LAYOUT == FMTC_NHWC && VEC) {
+        const int n4 = PT * (C / 4);  // the tile is one contiguous run of PT*C floats
+        const float* src = x + px0 * C;
+        for (int idx = tid; idx < n4; idx += 256) {
+            int f = 4 * idx;
+            int pxl = f / C, c = f - pxl * C;
+            float4 v = (px0 + pxl < P) ? *reinterpret_cast<const float4*>(src + f) : make_float4(0, 0, 0, 0);
+            float4 m = *reinterpret_cast<const float4*>(mu + c);
+            float2* dst = reinterpret_cast<float2*>(xs + pxl * RS + c);
+            dst[0] = make_float2(v.x - m.x, v.y - m.y);
+            dst[1] = make_float2(v.z - m.z, v.w - m.w);
+        }
+    } else if constexpr (LAYOUT == FMTC_NHWC) {
+        const int n1 = PT * C;
+        const float* src = x + px0 * C;
+        for (int idx = tid; idx < n1; idx += 256) {
+            int pxl = idx / C, c = idx - pxl * C;
+            float v = (px0 + pxl < P) ? src[idx] : 0.f;
+            xs[pxl * RS + c] = v - mu[c];
+        }
+    } else {
+        const int pxl = tid % PT;
+        const int64_t p = px0 + pxl;
+        const bool ok = p < P;
+        int64_t base = 0;
+        if (ok) {
+            int64_t n = p / HW;
+            base = n * (int64_t)C * HW + (p - n * HW);
+        }
+        for (int c = tid / PT; c < C; c += 256 / PT) {
+            float v = ok ? x[base + (int64_t)c * HW] : 0.f;
+            xs[pxl * RS + c] = v - mu[c];
         }
     }
-
-    auto load_step = [&](int cs) {
-        if constexpr (LAYOUT == FMTC_NHWC && VEC) {
-#pragma unroll
-            for (int j = 0; j < NLV; j++) {
-                int pxl = (tid >> 3) + 32 * j;
-                int c = cs * 32 + 4 * (tid & 7);
-                int64_t px = px0 + pxl;
-                xv[j] = (px < P && c < C) ? *reinterpret_cast<const float4*>(x + px * C + c) : make_float4(0, 0, 0, 0);
-            }
-        } else if constexpr (LAYOUT == FMTC_NHWC) {
-#pragma unroll
-            for (int j = 0; j < NLS; j++) {
-                int pxl = (tid >> 5) + 8 * j;
-                int c = cs * 32 + (tid & 31);
-                int64_t px = px0 + pxl;
-                xsc[j] = (px < P && c < C) ? x[px * C + c] : 0.f;
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < NLS; j++) {
-                int c = cs * 32 + tid / PT + (256 / PT) * j;
-                xsc[j] = (nchw_ok && c < C) ? x[nchw_base + (int64_t)c * HW] : 0.f;
-            }
+    if (Cpad > C) {  // padding channels meet zero basis entries; they must still be finite
+        const int padw = Cpad - C;
+        for (int idx = tid; idx < PT * padw; idx += 256) {
+            int pxl = idx / padw, c = C + (idx - pxl * padw);
+            xs[pxl * RS + c] = 0.f;
         }
-    };
-    auto store_step = [&](int cs, float* dst) {
-        if constexpr (LAYOUT == FMTC_NHWC && VEC) {
-            int cl = 4 * (tid & 7);
-            float4 m = *reinterpret_cast<const float4*>(mu + cs * 32 + cl);
-#pragma unroll
-            for (int j = 0; j < NLV; j++) {
-                int pxl = (tid >> 3) + 32 * j;
-                dst[(cl + 0) * S + pxl] = xv[j].x - m.x;
-                dst[(cl + 1) * S + pxl] = xv[j].y - m.y;
-                dst[(cl + 2) * S + pxl] = xv[j].z - m.z;
-                dst[(cl + 3) * S + pxl] = xv[j].w - m.w;
-            }
-        } else if constexpr (LAYOUT == FMTC_NHWC) {
-            int cl = tid & 31;
-            float m = mu[cs * 32 + cl];
-#pragma unroll
-            for (int j = 0; j < NLS; j++) dst[cl * S + (tid >> 5) + 8 * j] = xsc[j] - m;
-        } else {
-#pragma unroll
-            for (int j = 0; j < NLS; j++) {
-                int cl = tid / PT + (256 / PT) * j;
-                dst[cl * S + (tid % PT)] = xsc[j] - mu[cs * 32 + cl];
-            }
-        }
-    };
-    auto load_a = [&](int cs, float4* a) {
-        const float4* src = reinterpret_cast<const float4*>(Apk + ((size_t)(kt * ncs + cs) * 64 + lane) * 16);
-#pragma unroll
-        for (int j = 0; j < 4; j++) a[j] = kt_valid ? src[j] : make_float4(0, 0, 0, 0);
-    };
-
-    floatx16 acc[MT];
-#pragma unroll
-    for (int m = 0; m < MT; m++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) acc[m][r] = 0.f;
-
-    float4 a_cur[4], a_nxt[4];
-    load_step(0);
-    load_a(0, a_cur);
-    store_step(0, xs[0]);
+    }
     __syncthreads();
 
-    for (int cs = 0; cs < ncs; cs++) {
-        const bool more = cs + 1 < ncs;
-        if (more) {
-            load_step(cs + 1);
-            load_a(cs + 1, a_nxt);
-        }
-        if (kt_valid) {
-            const float* src = xs[cs & 1] + (16 * half) * S + wp * MT * 32 + l32;
+    const int zero_sym = 1 << (bits - 1);
+    const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1);
+    constexpr int PG = PT / 32 / MT;  // pixel groups per workgroup
+    const int nunits = ktg * PG;
+    for (int u = wave; u < nunits; u += 4) {
+        const int ktl = u % ktg, pg = u / ktg;
+        const int kt = kt0 + ktl;
+        floatx16 acc[MT];
+#pragma unroll
+        for (int m = 0; m < MT; m++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[m][r] = 0.f;
+
+        // slot s of the packed basis tile holds channel cs*32 + 2*s + half for this lane
+        const float4* asrc = reinterpret_cast<const float4*>(Apk + ((size_t)kt * ncs * 64 + lane) * 16);
+        float4 a_cur[4], a_nxt[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) a_cur[j] = asrc[j];
+        const float* brow = xs + (pg * MT * 32 + l32) * RS + half;
+        for (int cs = 0; cs < ncs; cs++) {
+            if (cs + 1 < ncs) {
+                const float4* nsrc = asrc + (size_t)(cs + 1) * 64 * 4;
+#pragma unroll
+                for (int j = 0; j < 4; j++) a_nxt[j] = nsrc[j];
+            }
 #pragma unroll
             for (int s = 0; s < 16; s++) {
                 float a = reinterpret_cast<const float*>(a_cur)[s];
 #pragma unroll
                 for (int m = 0; m < MT; m++) {
-                    float b = src[s * S + m * 32];
+                    float b = brow[m * 32 * RS + cs * 32 + 2 * s];
                     acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[m], 0, 0, 0);
                 }
             }
-        }
-        if (more) {
-            store_step(cs + 1, xs[(cs + 1) & 1]);
 #pragma unroll
             for (int j = 0; j < 4; j++) a_cur[j] = a_nxt[j];
         }
-        __syncthreads();
-    }
 
-    // ---- quantize ----
-    // accumulator r of lane l holds coefficient kt*32 + 8*(r/4) + 4*(l/32) + r%4 of pixel l%32
-    uint32_t* st = reinterpret_cast<uint32_t*>(&xs[0][0]);
-    const int zero_sym = 1 << (bits - 1);
-    const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1);
-    uint32_t words[MT][4];
-    uint32_t near_mask = 0;  // bit m*16 + r: the fp32 value is too close to a rounding boundary to be trusted
-    if (kt_valid) {
+        // ---- quantize ----
+        // accumulator r of lane l holds coefficient kt*32 + 8*(r/4) + 4*(l/32) + r%4 of pixel l%32
+        uint32_t words[MT][4];
+        uint32_t near_mask = 0;  // bit m*16 + r: the fp32 value is too close to a rounding boundary to be trusted
 #pragma unroll
         for (int m = 0; m < MT; m++) {
-            const bool px_ok = px0 + (wp * MT + m) * 32 + l32 < P;
+            const bool px_ok = px0 + (pg * MT + m) * 32 + l32 < P;
 #pragma unroll
             for (int g = 0; g < 4; g++) {
                 const int k = kt * 32 + 8 * g + 4 * half;
@@ -205,7 +178,7 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
             const int v = __ffs((int)fm) - 1;
             const int m = v >> 4, r = v & 15;
             const int k = kt * 32 + 8 * (r >> 2) + 4 * (L >> 5) + (r & 3);
-            const int64_t px = px0 + (wp * MT + m) * 32 + (L & 31);
+            const int64_t px = px0 + (pg * MT + m) * 32 + (L & 31);
             int64_t xbase, xstride;
             if constexpr (LAYOUT == FMTC_NHWC) {
                 xbase = px * C;
@@ -238,7 +211,7 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
         uint32_t zero_count = 0;
 #pragma unroll
         for (int m = 0; m < MT; m++) {
-            const int pxl = (wp * MT + m) * 32 + l32;
+            const int pxl = (pg * MT + m) * 32 + l32;
             const bool px_ok = px0 + pxl < P;
 #pragma unroll
             for (int g = 0; g < 4; g++) {
@@ -251,17 +224,18 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
                     zero_count += (uint32_t)__popcll(__ballot(ok && sy == zero_sym));
                     if (ok && sy != zero_sym) atomicAdd(&lhist[sy], 1u);
                 }
-                st[pxl * RSW + wk * 8 + 2 * g + half] = word;
+                st[pxl * RSW + ktl * 8 + 2 * g + half] = word;
             }
         }
         if (lane == 0 && zero_count) atomicAdd(&lhist[zero_sym], zero_count);
     }
     __syncthreads();
 
-    // ---- symbols leave as rows of WK*32 bytes per pixel ----
-    const int kbase = blockIdx.y * WK * 32;
-    for (int idx = tid; idx < PT * WK * 8; idx += 256) {
-        int row = idx / (WK * 8), col = idx % (WK * 8);
+    // ---- symbols leave as rows of ktg*32 bytes per pixel ----
+    const int kbase = kt0 * 32;
+    const int row_words = ktg * 8;
+    for (int idx = tid; idx < PT * row_words; idx += 256) {
+        int row = idx / row_words, col = idx - row * row_words;
         int64_t px = px0 + row;
         int k = kbase + 4 * col;
         if (px < P && k < C) {
@@ -281,7 +255,7 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
     }
 }
 
-template <int WK, int MT>
+template <int PT, int MT>
 static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
                             int bits, uint8_t* d_syms, uint32_t* d_hist_copies, hipStream_t s) {
     const float inv_delta = (float)(1.0 / (double)delta);
@@ -289,14 +263,30 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
     // tau (a few times that) of a rounding boundary are decided in fp64 instead
     float tau = 8.f * sqrtf((float)b.Cpad) * 5.9604645e-8f * (float)(1 << (bits - 1));
     tau = fminf(fmaxf(tau, 1.f / 8192.f), 1.f / 128.f);
-    constexpr int PT = (4 / WK) * MT * 32;
     const int ncs = b.Cpad / 32;
-    dim3 grid((unsigned)((P + PT - 1) / PT), (unsigned)((ncs + WK - 1) / WK));
+    const int64_t px_tiles = (P + PT - 1) / PT;
+    // split the coefficient range over workgroup rows only when the pixel tiles alone leave the chip idle
+    int kgroups = (int)((256 + px_tiles - 1) / px_tiles);
+    if (kgroups < 1) kgroups = 1;
+    int ktg = (ncs + kgroups - 1) / kgroups;
+    if (ncs >= 4) ktg = (ktg + 3) / 4 * 4;  // whole rounds of the 4 wavefronts
+    if (ktg > 16) ktg = 16;  // bounds the staging tile so that LDS stays below 160 KB at C = 1024
+    if (ktg > ncs) ktg = ncs;
+    kgroups = (ncs + ktg - 1) / ktg;
+    dim3 grid((unsigned)px_tiles, (unsigned)kgroups);
+    const size_t lds = sizeof(float) * (size_t)PT * (b.Cpad + 2) + sizeof(uint32_t) * (size_t)PT * (ktg * 8 + 1);
     const bool vec = (b.C % 4) == 0;
     ProfScope prof(K_PROJECT, s);
-#define FMTC_PQ(LAY, VEC)                                                                                      \
-    hipLaunchKernelGGL((k_project_quantize<WK, MT, LAY, VEC>), grid, dim3(256), 0, s, d_x, b.fwd, b.mu, b.T, P, \
-                       HW, b.C, ncs, inv_delta, delta, tau, bits, d_syms, d_hist_copies)
+#define FMTC_PQ(LAY, VEC)                                                                                       \
+    do {                                                                                                        \
+        if (lds > 48 * 1024) {                                                                                  \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project_quantize<PT, MT, LAY, VEC>), \
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);         \
+            if (ea != hipSuccess) return ea;                                                                    \
+        }                                                                                                       \
+        hipLaunchKernelGGL((k_project_quantize<PT, MT, LAY, VEC>), grid, dim3(256), lds, s, d_x, b.fwd, b.mu,  \
+                           b.T, P, HW, b.C, ncs, ktg, inv_delta, delta, tau, bits, d_syms, d_hist_copies);     \
+    } while (0)
     if (layout == FMTC_NHWC) {
         if (vec) FMTC_PQ(FMTC_NHWC, true);
         else FMTC_PQ(FMTC_NHWC, false);
@@ -313,9 +303,10 @@ hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64
                                    hipStream_t s) {
     const int64_t P = N * HW;
     const int nkt = b.Cpad / 32;
-    if (nkt == 1) return launch_pq<1, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
-    if (nkt == 2) return launch_pq<2, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
-    return launch_pq<4, 2>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
+    if (nkt == 1) return launch_pq<128, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
+    if (nkt == 4) return launch_pq<64, 2>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
+    if (nkt <= 5) return launch_pq<64, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
+    return launch_pq<32, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
 }
 
 // Histogram of given symbols (staged coder entry point).  counters[0] receives

@@ -96,7 +96,7 @@ inline Workspace make_workspace(uint64_t V, uint32_t n_chunks) {
 
 // Operand packing of the basis for the MFMA kernels (32x32x2 f32 tiles):
 // tile (nt, ms), lane l, slot s holds M[nt*32 + l%32][ms*32 + perm(s, l/32)],
-// zero outside CxC.  perm for the forward operand: s + 16*half; for the
+// zero outside CxC.  perm for the forward operand: 2*s + half; for the
 // inverse operand: 8*(s/4) + 4*half + s%4.
 struct BasisDevice {
     int C, Cpad;           // Cpad = C rounded up to 32
