@@ -111,6 +111,9 @@ size_t fmtc_encode_bound(int64_t P, int C, int bits, int chunk_syms);
 /* Bytes of device workspace fmtc_encode / fmtc_code_symbols need (symbols,
  * histograms, code table, per-chunk sizes).  256-byte aligned pointer required. */
 size_t fmtc_workspace_size(int64_t P, int C, int bits, int chunk_syms);
+/* Bytes of device workspace fmtc_decode / fmtc_decode_symbols need (the decode
+ * tables of one stream; a constant of a few KB).  256-byte aligned pointer. */
+size_t fmtc_decode_workspace_size(void);
 
 /* ---- hot path ---- */
 /* Whole encoder (section 3: transform, quantizer, VLC).  Reads d_x once, writes
@@ -129,7 +132,8 @@ fmtc_status fmtc_encode(const fmtc_basis *basis, const float *d_x, int64_t N, in
  * FMTC_ERR_* bits if the stream fails validation; in that case d_xhat is
  * unspecified but no access leaves the given buffers. */
 fmtc_status fmtc_decode(const fmtc_basis *basis, const void *d_stream_in, size_t bytes, float *d_xhat, int64_t N,
-                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t *d_err_flag, void *hip_stream);
+                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t *d_err_flag, void *d_workspace,
+                        size_t ws_bytes, void *hip_stream);
 
 /* ---- staged entry points (the same kernels, cut at the symbol boundary) ---- */
 /* Transform + quantizer + histogram only (section 3: y = T(x-mu), Q_Delta).
@@ -146,7 +150,7 @@ fmtc_status fmtc_code_symbols(const uint8_t *d_syms, int64_t P, int C, int bits,
 
 /* Variable length decoder only: stream -> P*C symbol bytes. */
 fmtc_status fmtc_decode_symbols(const void *d_stream_in, size_t bytes, int64_t P, int C, int bits, uint8_t *d_syms,
-                                uint32_t *d_err_flag, void *hip_stream);
+                                uint32_t *d_err_flag, void *d_workspace, size_t ws_bytes, void *hip_stream);
 
 /* Parses a 64-byte header copied to the host.  Any output may be NULL.
  * stream_bytes is the total container size. */

@@ -14,7 +14,7 @@ struct fmtc_basis {
     float range_A = 0.f;
     std::vector<float> T, mu;
     std::vector<double> eig;
-    float *d_fwd = nullptr, *d_inv = nullptr, *d_mu = nullptr, *d_T = nullptr;
+    float *d_fwd = nullptr, *d_inv = nullptr, *d_invf = nullptr, *d_mu = nullptr, *d_T = nullptr;
     int device = 0;
 };
 
@@ -65,9 +65,10 @@ void pack_operand(const std::vector<float>& T, int C, int Cpad, bool transpose, 
 
 fmtc_status upload_basis(fmtc_basis* b) {
     const int C = b->C, Cpad = b->Cpad;
-    std::vector<float> fwd, inv, mu(Cpad, 0.f);
+    std::vector<float> fwd, inv, invf, mu(Cpad, 0.f);
     pack_operand(b->T, C, Cpad, false, false, &fwd);
     pack_operand(b->T, C, Cpad, true, true, &inv);
+    pack_operand(b->T, C, Cpad, true, false, &invf);
     for (int c = 0; c < C; c++) mu[c] = b->mu[c];
     hipError_t e;
     const size_t mat = sizeof(float) * (size_t)Cpad * Cpad;
@@ -77,6 +78,8 @@ fmtc_status upload_basis(fmtc_basis* b) {
     if ((e = hipMalloc((void**)&b->d_mu, sizeof(float) * Cpad)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
     if ((e = hipMemcpy(b->d_fwd, fwd.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     if ((e = hipMemcpy(b->d_inv, inv.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
+    if ((e = hipMalloc((void**)&b->d_invf, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    if ((e = hipMemcpy(b->d_invf, invf.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     if ((e = hipMemcpy(b->d_mu, mu.data(), sizeof(float) * Cpad, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     if ((e = hipMalloc((void**)&b->d_T, sizeof(float) * (size_t)C * C)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
     if ((e = hipMemcpy(b->d_T, b->T.data(), sizeof(float) * (size_t)C * C, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
@@ -89,6 +92,7 @@ BasisDevice device_view(const fmtc_basis* b) {
     v.Cpad = b->Cpad;
     v.fwd = b->d_fwd;
     v.inv = b->d_inv;
+    v.invf = b->d_invf;
     v.mu = b->d_mu;
     v.T = b->d_T;
     return v;
@@ -206,6 +210,7 @@ void fmtc_basis_destroy(fmtc_basis* b) {
     if (!b) return;
     if (b->d_fwd) (void)hipFree(b->d_fwd);
     if (b->d_inv) (void)hipFree(b->d_inv);
+    if (b->d_invf) (void)hipFree(b->d_invf);
     if (b->d_mu) (void)hipFree(b->d_mu);
     if (b->d_T) (void)hipFree(b->d_T);
     delete b;
@@ -411,8 +416,10 @@ fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits,
 
 static fmtc_status decode_common(const fmtc_basis* basis, const void* d_stream_in, size_t bytes, int64_t P, int C,
                                  int64_t HW, int layout, int bits, float* d_xhat, uint8_t* d_syms,
-                                 uint32_t* d_err_flag, void* hip_stream) {
-    if (!d_stream_in || !d_err_flag) return fail(FMTC_EINVAL, "NULL argument");
+                                 uint32_t* d_err_flag, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!d_stream_in || !d_err_flag || !d_workspace) return fail(FMTC_EINVAL, "NULL argument");
+    if (!aligned(d_workspace, 256)) return fail(FMTC_EINVAL, "misaligned pointer");
+    if (ws_bytes < decode_workspace_bytes()) return fail(FMTC_EBUFSIZE, "decode workspace too small: %zu < %zu", ws_bytes, decode_workspace_bytes());
     if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
     if (!aligned(d_stream_in, 16) || !aligned(d_err_flag, 4) || !aligned(d_xhat, 16) || !aligned(d_syms, 16))
         return fail(FMTC_EINVAL, "misaligned pointer");
@@ -425,25 +432,28 @@ static fmtc_status decode_common(const fmtc_basis* basis, const void* d_stream_i
     BasisDevice view;
     if (basis) view = device_view(basis);
     if ((e = launch_decode(basis ? &view : nullptr, static_cast<const uint8_t*>(d_stream_in), bytes, g, bits, HW,
-                           layout, d_xhat, d_syms, d_err_flag, s)) != hipSuccess)
+                           layout, d_xhat, d_syms, d_err_flag, static_cast<uint8_t*>(d_workspace), s)) != hipSuccess)
         return hip_fail(e, "decode kernel");
     return FMTC_OK;
 }
 
+size_t fmtc_decode_workspace_size(void) { return decode_workspace_bytes(); }
+
 fmtc_status fmtc_decode(const fmtc_basis* basis, const void* d_stream_in, size_t bytes, float* d_xhat, int64_t N,
-                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t* d_err_flag, void* hip_stream) {
+                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t* d_err_flag, void* d_workspace,
+                        size_t ws_bytes, void* hip_stream) {
     if (!basis || !d_xhat) return fail(FMTC_EINVAL, "NULL argument");
     if (!dims_ok(N, C, H, W) || basis->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", basis->C, C);
     if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
     const int64_t HW = (int64_t)H * W;
-    return decode_common(basis, d_stream_in, bytes, N * HW, C, HW, layout, bits, d_xhat, nullptr, d_err_flag, hip_stream);
+    return decode_common(basis, d_stream_in, bytes, N * HW, C, HW, layout, bits, d_xhat, nullptr, d_err_flag, d_workspace, ws_bytes, hip_stream);
 }
 
 fmtc_status fmtc_decode_symbols(const void* d_stream_in, size_t bytes, int64_t P, int C, int bits, uint8_t* d_syms,
-                                uint32_t* d_err_flag, void* hip_stream) {
+                                uint32_t* d_err_flag, void* d_workspace, size_t ws_bytes, void* hip_stream) {
     if (!d_syms) return fail(FMTC_EINVAL, "NULL argument");
     if (P < 1 || C < 1 || C > 1024) return fail(FMTC_EINVAL, "bad dims");
-    return decode_common(nullptr, d_stream_in, bytes, P, C, 1, FMTC_NHWC, bits, nullptr, d_syms, d_err_flag, hip_stream);
+    return decode_common(nullptr, d_stream_in, bytes, P, C, 1, FMTC_NHWC, bits, nullptr, d_syms, d_err_flag, d_workspace, ws_bytes, hip_stream);
 }
 
 fmtc_status fmtc_stream_info(const void* h_header, size_t header_bytes, int* bits, int* C, int64_t* P,

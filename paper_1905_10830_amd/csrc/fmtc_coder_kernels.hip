@@ -223,39 +223,51 @@ __global__ __launch_bounds__(256) void k_run_bits(const uint8_t* __restrict__ sy
 
 // ---------------------------------------------------------------------------
 // Chunk offsets: exclusive scan of the chunk sizes in words, header, stream size.
-// One workgroup, sequential over tiles of 256 chunks.
+// One workgroup of 1024 threads; every thread owns a contiguous segment of chunks
+// (sum, workgroup-wide scan of the 1024 sums, then the segment's offsets).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_chunk_offsets(const uint32_t* __restrict__ chunk_bits, uint32_t n_chunks,
-                                                       Header hdr, size_t off_sub_bits, size_t off_payload,
-                                                       uint8_t* __restrict__ stream,
-                                                       uint64_t* __restrict__ out_bytes) {
+__global__ __launch_bounds__(1024) void k_chunk_offsets(const uint32_t* __restrict__ chunk_bits, uint32_t n_chunks,
+                                                        Header hdr, size_t off_sub_bits, size_t off_payload,
+                                                        uint8_t* __restrict__ stream,
+                                                        uint64_t* __restrict__ out_bytes) {
     uint32_t* chunk_off = reinterpret_cast<uint32_t*>(stream + kHeaderBytes + kLenTableBytes);
-    __shared__ uint32_t wsum[4];
-    __shared__ uint64_t bsum[4];
+    __shared__ uint32_t wave_words[16];
+    __shared__ unsigned long long wave_bits[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint64_t base_words = 0, total_bits = 0;
-    for (uint32_t t0 = 0; t0 < n_chunks; t0 += 256) {
-        uint32_t i = t0 + tid;
-        uint32_t b = (i < n_chunks) ? chunk_bits[i] : 0u;
-        uint32_t w = (b + 31) >> 5;
-        uint32_t ex = wave_exclusive_scan(w, lane);
-        uint32_t bs = wave_sum(b);
-        if (lane == 63) wsum[wave] = ex + w;
-        if (lane == 0) bsum[wave] = bs;
-        __syncthreads();
-        uint32_t woff = 0;
-        for (int q = 0; q < wave; q++) woff += wsum[q];
-        if (i < n_chunks) chunk_off[i] = (uint32_t)(base_words + woff + ex);
-        base_words += (uint64_t)wsum[0] + wsum[1] + wsum[2] + wsum[3];
-        total_bits += bsum[0] + bsum[1] + bsum[2] + bsum[3];
-        __syncthreads();
+    const uint32_t seg = (n_chunks + 1023) / 1024;
+    const uint32_t i0 = (uint32_t)tid * seg;
+    const uint32_t i1 = (i0 + seg < n_chunks) ? i0 + seg : n_chunks;
+    uint32_t words = 0;
+    unsigned long long bits = 0;
+    for (uint32_t i = i0; i < i1; i++) {
+        uint32_t b = chunk_bits[i];
+        words += (b + 31) >> 5;
+        bits += b;
+    }
+    uint32_t ex = wave_exclusive_scan(words, lane);
+    unsigned long long bsum = bits;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) bsum += __shfl_xor(bsum, o, 64);
+    if (lane == 63) wave_words[wave] = ex + words;
+    if (lane == 0) wave_bits[wave] = bsum;
+    __syncthreads();
+    uint32_t base = ex;
+    for (int q = 0; q < wave; q++) base += wave_words[q];
+    for (uint32_t i = i0; i < i1; i++) {
+        chunk_off[i] = base;
+        base += (chunk_bits[i] + 31) >> 5;
     }
     if (tid == 0) {
-        chunk_off[n_chunks] = (uint32_t)base_words;
-        hdr.payload_words = base_words;
+        uint64_t total_words = 0, total_bits = 0;
+        for (int q = 0; q < 16; q++) {
+            total_words += wave_words[q];
+            total_bits += wave_bits[q];
+        }
+        chunk_off[n_chunks] = (uint32_t)total_words;
+        hdr.payload_words = total_words;
         hdr.payload_bits = total_bits;
         *reinterpret_cast<Header*>(stream) = hdr;
-        if (out_bytes) *out_bytes = (uint64_t)off_payload + 4 * base_words;
+        if (out_bytes) *out_bytes = (uint64_t)off_payload + 4 * total_words;
         // alignment gaps between the sections are part of the stream: keep them zero
         for (size_t o = kHeaderBytes + kLenTableBytes + 4 * ((size_t)n_chunks + 1); o < off_sub_bits; o++) stream[o] = 0;
         for (size_t o = off_sub_bits + 2 * (size_t)n_chunks * hdr.subs_per_chunk; o < off_payload; o++) stream[o] = 0;
@@ -383,7 +395,7 @@ hipError_t launch_pack(const uint8_t* d_syms, const Geometry& g, int bits, float
     hdr.subs_per_chunk = g.subs_per_chunk;
     {
         ProfScope prof(K_OFFSETS, s);
-        hipLaunchKernelGGL(k_chunk_offsets, dim3(1), dim3(256), 0, s, d_chunk_bits, g.n_chunks, hdr, g.off_sub_bits,
+        hipLaunchKernelGGL(k_chunk_offsets, dim3(1), dim3(1024), 0, s, d_chunk_bits, g.n_chunks, hdr, g.off_sub_bits,
                            g.off_payload, d_stream, d_out_bytes);
     }
     {

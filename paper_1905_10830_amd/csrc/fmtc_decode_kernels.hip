@@ -1,8 +1,9 @@
 // Decoder (paper section 3: variable length decoder, inverse quantizer, inverse
 // transform; section 3.1 "Implementation": levels scaled back to the transform
 // domain, then the inverse PCA).  One fused kernel:
-//   1. every workgroup validates the header and the code length table and builds
-//      the canonical decode tables and a 2^10-entry lookup table in LDS;
+//   1. a one-workgroup kernel validates the header and the code length table and
+//      builds the canonical decode tables and a 2^12-entry lookup table once; every
+//      workgroup of the main kernel copies them from the workspace into LDS;
 //   2. per tile of G chunks: one wavefront per chunk, one lane per run of 64
 //      symbols (bit offset = prefix sum of the stored run sizes) decodes into an
 //      LDS symbol tile;
@@ -31,72 +32,127 @@ __device__ __forceinline__ uint32_t dec_wave_exclusive_scan(uint32_t v, int lane
 __device__ __forceinline__ uint32_t sym_addr(uint32_t n) { return n + 4u * (n >> 6); }
 
 
-// Decodes the `cnt` symbols of one run (one lane) starting at bit `start` of a chunk.
+// Decode tables: built once per stream by k_decode_tables, copied to LDS by every workgroup.
+struct DecTables {
+    uint32_t cnt_len[64];     // number of codes of each length
+    uint32_t first_rank[64];  // rank (in (length, symbol) order) of the first code of each length
+    uint64_t first_code[64];  // first canonical code of each length
+    uint64_t limit[64];       // (first_code + count) << (32 - length) for length <= 32: first left-aligned 32-bit
+                              // value that is NOT a code of this length or shorter
+    uint16_t sorted_sym[256]; // symbols in (length, symbol) order
+    // next kLutBits stream bits -> up to two symbols: sym0 | sym1 << 8 | (len0 + len1) << 16 | len0 << 21 | n << 26,
+    // n = number of whole codes found in those bits (0: the first code is longer than kLutBits)
+    uint32_t lut[1 << kLutBits];
+};
+static_assert(sizeof(DecTables) % 16 == 0, "copied with 16-byte loads");
+constexpr size_t kDecWorkspaceBytes = 64 + sizeof(DecTables);  // word 0: 1 once the tables are valid
+
+// Decodes the `cnt` symbols of one run (one lane) starting at bit `start` of a chunk into the symbol tile.
 // STAGED: the chunk's words are in LDS (`pw`, two zero words behind them); otherwise they are read from
 // global memory (`gw`), zero past the chunk's end.  Returns false if bits matched no code word.
-template <bool STAGED, bool ALIGNED4>
+// State: lo/hi are payload words widx and widx+1, sh the bit offset in lo, nxt word widx+2 (read ahead),
+// so 32 valid bits are at hand for every table lookup and a step crosses at most one word boundary.
+//
+// Output of a run.  Byte tile: symbol n of the tile at sym_addr(n).  Float tile: the dequantized coefficient
+// Delta * (s - 2^(b-1)) at tile[pixel][coefficient] with a row stride of rs floats.
+struct ByteOut {
+    uint8_t* tile;
+    uint32_t a0, o, i;
+    __device__ __forceinline__ ByteOut(uint8_t* t, uint32_t nbase) : tile(t), a0(nbase + 4u * (nbase >> 6)), o(nbase & 63u), i(0) {}
+    __device__ __forceinline__ void put(uint32_t sym) {  // sym_addr(nbase + i) = a0 + i + 4 * ((o + i) >> 6)
+        tile[a0 + i + (((o + i) >> 6) << 2)] = (uint8_t)sym;
+        i++;
+    }
+};
+struct FloatOut {
+    float* tile;
+    uint32_t fa, krem, C, gap;
+    float delta, neg_off;
+    __device__ __forceinline__ FloatOut(float* t, uint32_t nbase, uint32_t C_, uint32_t rs, float d, float no)
+        : tile(t), C(C_), gap(rs - C_), delta(d), neg_off(no) {
+        const uint32_t px = nbase / C_, k = nbase - px * C_;
+        fa = px * rs + k;
+        krem = C_ - k;
+    }
+    __device__ __forceinline__ void put(uint32_t sym) {
+        tile[fa] = __builtin_fmaf((float)sym, delta, neg_off);
+        fa++;
+        if (--krem == 0) {  // next pixel row
+            fa += gap;
+            krem = C;
+        }
+    }
+};
+
+template <bool STAGED, typename Out>
 __device__ __forceinline__ bool decode_run(const uint32_t* pw, const uint32_t* __restrict__ gw, uint32_t nwords,
-                                           uint32_t start, uint32_t cnt, uint32_t nbase, const uint16_t* lut,
-                                           const uint32_t* cnt_len, const uint32_t* first_rank,
-                                           const uint64_t* first_code, const uint16_t* sorted_sym,
-                                           uint8_t* symtile) {
-    auto fetch = [&](uint32_t rel) -> uint64_t {
-        if constexpr (STAGED) return (uint64_t)pw[rel < nwords + 1 ? rel : nwords + 1];
-        else return (rel < nwords) ? (uint64_t)gw[rel] : 0ull;
+                                           uint32_t start, uint32_t cnt, const DecTables& T, Out out) {
+    auto fetch = [&](uint32_t rel) -> uint32_t {
+        if constexpr (STAGED) return pw[rel < nwords + 1 ? rel : nwords + 1];
+        else return (rel < nwords) ? gw[rel] : 0u;
     };
     // word index can not wrap: start <= 64 runs * 65535 bits
-    uint32_t widx = start >> 5;
-    uint64_t window = fetch(widx) | (fetch(widx + 1) << 32);
-    widx += 2;
-    window >>= (start & 31);
-    uint32_t avail = 64 - (start & 31);
-    uint64_t nxt = fetch(widx);
+    uint32_t widx = start >> 5, sh = start & 31;
+    uint32_t lo = fetch(widx), hi = fetch(widx + 1), nxt = fetch(widx + 2);
     bool ok = true;
-    uint32_t word = 0;
-    for (uint32_t i = 0; i < cnt; i++) {
-        // refill without a branch: more than 32 valid bits before every lookup
-        const bool need = avail <= 32;
-        window |= need ? (nxt << (avail & 63)) : 0ull;
-        avail += need ? 32u : 0u;
-        widx += need ? 1u : 0u;
-        nxt = fetch(widx);
-        uint32_t e = lut[window & ((1u << kLutBits) - 1)];
-        uint32_t len = e >> 8, sym = e & 255;
-        if (len) {
-            window >>= len;
-            avail -= len;
-        } else {
-            // code longer than the table: canonical decoding bit by bit
-            uint64_t code = 0;
-            bool found = false;
-            for (int l = 1; l <= kMaxLen; l++) {
-                if (avail <= 32) {
-                    window |= fetch(widx++) << avail;
-                    avail += 32;
+    uint32_t i = 0;
+    while (i < cnt) {
+        const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, sh);
+        uint32_t e = T.lut[w & ((1u << kLutBits) - 1)];
+        uint32_t n = e >> 26, sym0 = e & 255u, len0 = (e >> 21) & 31u;
+        if (__builtin_expect(n == 0, 0)) {
+            // A code longer than the table.  Canonical codes, left-aligned, grow with their length, so the
+            // length is kLutBits + 1 + the number of longer-length limits the next 32 bits reach.
+            const uint32_t v = __brev(w);  // first stream bit on top
+            uint32_t len = kLutBits + 1;
+#pragma unroll
+            for (int l = kLutBits + 1; l <= 32; l++) len += ((uint64_t)v >= T.limit[l]) ? 1u : 0u;
+            if (len <= 32) {
+                const uint32_t off = (v >> (32 - len)) - (uint32_t)T.first_code[len];
+                if (off >= T.cnt_len[len]) ok = false;
+                sym0 = T.sorted_sym[(T.first_rank[len] + off) & 255u];
+                len0 = len;
+                n = 1;
+            } else {
+                // longer than 32 bits (needs a histogram as skewed as the Fibonacci numbers): bit by bit
+                uint32_t bp = widx * 32 + sh;
+                uint64_t code = 0;
+                uint32_t sym = 0, l = 1;
+                bool found = false;
+                for (; l <= (uint32_t)kMaxLen; l++) {
+                    code = (code << 1) | ((fetch(bp >> 5) >> (bp & 31)) & 1u);
+                    bp++;
+                    const uint64_t f = T.first_code[l];
+                    const uint32_t c = T.cnt_len[l];
+                    if (c && code >= f && code - f < c) {
+                        sym = T.sorted_sym[T.first_rank[l] + (uint32_t)(code - f)];
+                        found = true;
+                        break;
+                    }
                 }
-                code = (code << 1) | (window & 1);
-                window >>= 1;
-                avail--;
-                uint64_t f = first_code[l];
-                uint32_t c = cnt_len[l];
-                if (c && code >= f && code - f < c) {
-                    sym = sorted_sym[first_rank[l] + (uint32_t)(code - f)];
-                    found = true;
-                    break;
-                }
+                if (!found) ok = false;
+                out.put(sym);
+                i++;
+                widx = bp >> 5;
+                sh = bp & 31;
+                lo = fetch(widx);
+                hi = fetch(widx + 1);
+                nxt = fetch(widx + 2);
+                continue;
             }
-            if (!found) { ok = false; sym = 0; }
-            nxt = fetch(widx);
         }
-        if constexpr (ALIGNED4) {
-            word |= sym << (8 * (i & 3));
-            if ((i & 3) == 3) {
-                *reinterpret_cast<uint32_t*>(symtile + sym_addr(nbase + i - 3)) = word;
-                word = 0;
-            }
-        } else {
-            symtile[sym_addr(nbase + i)] = (uint8_t)sym;
-        }
+        const bool two = n == 2 && i + 1 < cnt;
+        const uint32_t len = two ? ((e >> 16) & 31u) : len0;
+        out.put(sym0);
+        if (two) out.put((e >> 8) & 255u);
+        i += two ? 2u : 1u;
+        sh += len;  // at most 31 + 32: one word boundary at most
+        const bool cross = sh >= 32;
+        lo = cross ? hi : lo;
+        hi = cross ? nxt : hi;
+        widx += cross ? 1u : 0u;
+        sh &= 31u;
+        nxt = fetch(widx + 2);
     }
     return ok;
 }
@@ -110,89 +166,95 @@ struct DecodeParams {
     int bits;
     int G;             // chunks per tile
     int ct_per_group;  // 32-channel output tiles per workgroup row (blockIdx.y)
+    int tile_rows;     // float tile: pixel rows allocated
     int ncs;           // Cpad / 32
-    const float* Bpk;  // inverse operand, packed
+    const float* Bpk;  // inverse operand, packed (slot order of the byte tile)
+    const float* Bpf;  // inverse operand, packed (slot order of the float tile)
     const float* mu;   // [Cpad]
     float* xhat;       // NULL in symbols-only mode
     uint8_t* syms_out; // non-NULL in symbols-only mode
     uint32_t* err;
+    uint8_t* ws;       // kDecWorkspaceBytes: valid word + DecTables
 };
 
-constexpr int kPayWords = 1022;  // LDS copy of a chunk's payload: up to ~8 bits/symbol; larger chunks read global memory
+// Header checks shared by the two kernels.  Returns false unless the header matches the arguments and the
+// buffer holds every section it announces.
+struct StreamView {
+    uint32_t n_chunks, spc, chunk_syms, payload_words;
+    uint64_t ppc;
+    const uint32_t* chunk_off;
+    const uint16_t* sub_bits;
+    const uint32_t* payload;
+    float delta;
+};
+__device__ __forceinline__ bool open_stream(const DecodeParams& p, StreamView* v) {
+    if (p.bytes < (size_t)(kHeaderBytes + kLenTableBytes)) return false;
+    const Header hd = *reinterpret_cast<const Header*>(p.stream);
+    const uint64_t ppc = hd.px_per_chunk;
+    const uint64_t chunk_syms64 = ppc * (uint64_t)p.C;
+    bool ok = hd.magic == kMagic && hd.version == 1 && hd.bits == p.bits && hd.C == (uint32_t)p.C &&
+              hd.P == (uint64_t)p.P && hd.sub_syms == (uint32_t)kSubSyms && ppc >= 1 &&
+              (chunk_syms64 <= 4096 || ppc == 1) && hd.delta > 0.f;
+    if (!ok) return false;
+    const uint64_t nch = ((uint64_t)p.P + ppc - 1) / ppc;
+    const uint32_t spc = (uint32_t)((chunk_syms64 + kSubSyms - 1) / kSubSyms);
+    if (nch != hd.n_chunks || spc != hd.subs_per_chunk) return false;
+    const size_t off_co = kHeaderBytes + kLenTableBytes;
+    const size_t off_sub = (off_co + 4 * ((size_t)nch + 1) + 15) & ~(size_t)15;
+    const size_t off_pay = (off_sub + 2 * (size_t)nch * spc + 15) & ~(size_t)15;
+    if (!(p.bytes >= off_pay && (p.bytes - off_pay) / 4 >= hd.payload_words && hd.payload_words <= 0xffffffffull))
+        return false;
+    v->n_chunks = (uint32_t)nch;
+    v->spc = spc;
+    v->chunk_syms = (uint32_t)chunk_syms64;
+    v->payload_words = (uint32_t)hd.payload_words;
+    v->ppc = ppc;
+    v->chunk_off = reinterpret_cast<const uint32_t*>(p.stream + off_co);
+    v->sub_bits = reinterpret_cast<const uint16_t*>(p.stream + off_sub);
+    v->payload = reinterpret_cast<const uint32_t*>(p.stream + off_pay);
+    v->delta = hd.delta;
+    return true;
+}
 
-template <int MT, int LAYOUT, bool ALIGNED4>
-__global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
-    __shared__ uint16_t lut[1 << kLutBits];
+// One workgroup of 1024 threads: stream checks and decode tables, written to the workspace.
+__global__ __launch_bounds__(1024) void k_decode_tables(DecodeParams p) {
     __shared__ uint8_t len_s[256];
-    __shared__ uint16_t sorted_sym[256];
     __shared__ uint32_t cnt_len[kMaxLen + 2];
     __shared__ uint32_t first_rank[kMaxLen + 2];
     __shared__ uint64_t first_code[kMaxLen + 2];
+    __shared__ uint16_t sorted_sym[256];
     __shared__ unsigned long long kraft;
     __shared__ uint32_t n_used, bad_len;
-    __shared__ uint32_t pay[4][kPayWords + 2];  // per wavefront: the chunk's payload words
-    extern __shared__ __align__(16) uint8_t symtile[];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
-    const int half = lane >> 5, l32 = lane & 31;
-    const int C = p.C;
+    const int tid = threadIdx.x;
     const int K = 1 << p.bits;
-
-    // ---- header ----
-    if (p.bytes < (size_t)(kHeaderBytes + kLenTableBytes)) {
-        if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.err, FMTC_ERR_HEADER);
+    uint32_t* valid = reinterpret_cast<uint32_t*>(p.ws);
+    DecTables* out = reinterpret_cast<DecTables*>(p.ws + 64);
+    StreamView v;
+    if (!open_stream(p, &v)) {
+        if (tid == 0) { atomicOr(p.err, FMTC_ERR_HEADER); *valid = 0u; }
         return;
     }
-    const Header hd = *reinterpret_cast<const Header*>(p.stream);
-    const uint64_t ppc = hd.px_per_chunk;
-    const uint64_t chunk_syms64 = ppc * (uint64_t)C;
-    bool ok = hd.magic == kMagic && hd.version == 1 && hd.bits == p.bits && hd.C == (uint32_t)C &&
-              hd.P == (uint64_t)p.P && hd.sub_syms == (uint32_t)kSubSyms && ppc >= 1 &&
-              (chunk_syms64 <= 4096 || ppc == 1) && hd.delta > 0.f;
-    uint32_t n_chunks = 0, spc = 0;
-    size_t off_sub = 0, off_pay = 0;
-    if (ok) {
-        uint64_t nch = ((uint64_t)p.P + ppc - 1) / ppc;
-        spc = (uint32_t)((chunk_syms64 + kSubSyms - 1) / kSubSyms);
-        ok = nch == hd.n_chunks && spc == hd.subs_per_chunk;
-        n_chunks = (uint32_t)nch;
-        size_t off_co = kHeaderBytes + kLenTableBytes;
-        off_sub = (off_co + 4 * ((size_t)nch + 1) + 15) & ~(size_t)15;
-        off_pay = (off_sub + 2 * (size_t)nch * spc + 15) & ~(size_t)15;
-        ok = ok && p.bytes >= off_pay && (p.bytes - off_pay) / 4 >= hd.payload_words && hd.payload_words <= 0xffffffffull;
-    }
-    if (!ok) {
-        if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.err, FMTC_ERR_HEADER);
-        return;
-    }
-    const uint32_t chunk_syms = (uint32_t)chunk_syms64;
-    const uint32_t payload_words = (uint32_t)hd.payload_words;
-    const uint32_t* chunk_off = reinterpret_cast<const uint32_t*>(p.stream + kHeaderBytes + kLenTableBytes);
-    const uint16_t* sub_bits = reinterpret_cast<const uint16_t*>(p.stream + off_sub);
-    const uint32_t* payload = reinterpret_cast<const uint32_t*>(p.stream + off_pay);
-    const uint64_t V = (uint64_t)p.P * (uint64_t)C;
-
-    // ---- code tables ----
     if (tid <= kMaxLen + 1) cnt_len[tid] = 0;
     if (tid == 0) { kraft = 0ull; n_used = 0; bad_len = 0; }
     __syncthreads();
-    const int my_len = p.stream[kHeaderBytes + tid];
-    len_s[tid] = (uint8_t)my_len;
-    if (my_len > kMaxLen || (tid >= K && my_len != 0)) atomicAdd(&bad_len, 1u);
-    else if (my_len) {
-        atomicAdd(&cnt_len[my_len], 1u);
-        atomicAdd(&kraft, 1ull << (kMaxLen - my_len));
-        atomicAdd(&n_used, 1u);
+    int my_len = 0;
+    if (tid < 256) {
+        my_len = p.stream[kHeaderBytes + tid];
+        len_s[tid] = (uint8_t)my_len;
+        if (my_len > kMaxLen || (tid >= K && my_len != 0)) atomicAdd(&bad_len, 1u);
+        else if (my_len) {
+            atomicAdd(&cnt_len[my_len], 1u);
+            atomicAdd(&kraft, 1ull << (kMaxLen - my_len));
+            atomicAdd(&n_used, 1u);
+        }
     }
     __syncthreads();
-    {
-        bool table_ok = bad_len == 0 && n_used >= 1 &&
-                        (n_used == 1 ? cnt_len[1] == 1 : kraft == (1ull << kMaxLen));
-        if (!table_ok) {
-            if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.err, FMTC_ERR_TABLE);
-            return;
-        }
+    // a complete prefix code (Kraft sum exactly 1), or the single one-bit code of a one-symbol tensor
+    const bool table_ok = bad_len == 0 && n_used >= 1 &&
+                          (n_used == 1 ? cnt_len[1] == 1 : kraft == (1ull << kMaxLen));
+    if (!table_ok) {
+        if (tid == 0) { atomicOr(p.err, FMTC_ERR_TABLE); *valid = 0u; }
+        return;
     }
     if (tid >= 1 && tid <= kMaxLen) {
         // first code and first rank of every length: code(l) = sum_{j<l} count(j) << (l-j)
@@ -213,6 +275,14 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
         sorted_sym[first_rank[my_len] + before] = (uint16_t)tid;
     }
     __syncthreads();
+    if (tid < 64) {
+        const bool in = tid >= 1 && tid <= kMaxLen;
+        out->cnt_len[tid] = in ? cnt_len[tid] : 0u;
+        out->first_rank[tid] = in ? first_rank[tid] : 0u;
+        out->first_code[tid] = in ? first_code[tid] : 0ull;
+        out->limit[tid] = (in && tid <= 32) ? ((first_code[tid] + cnt_len[tid]) << (32 - tid)) : ~0ull;
+    }
+    if (tid < 256) out->sorted_sym[tid] = (tid < (int)n_used) ? sorted_sym[tid] : (uint16_t)0;
     {
         uint32_t fc[kLutBits + 1], cn[kLutBits + 1], fr[kLutBits + 1];
 #pragma unroll
@@ -221,24 +291,82 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
             cn[l] = cnt_len[l];
             fr[l] = first_rank[l];
         }
-        for (int idx = tid; idx < (1 << kLutBits); idx += 256) {
+        // first whole code in the low `maxbits` bits of v (stream order): its length and rank, 0 if none
+        auto first_code_in = [&](uint32_t v, int maxbits, uint32_t* rank) -> uint32_t {
             uint32_t code = 0, hit_len = 0, hit_rank = 0;
 #pragma unroll
             for (int l = 1; l <= kLutBits; l++) {
-                code = (code << 1) | ((idx >> (l - 1)) & 1);
-                bool hit = hit_len == 0 && code >= fc[l] && code - fc[l] < cn[l];
+                code = (code << 1) | ((v >> (l - 1)) & 1u);
+                bool hit = hit_len == 0 && l <= maxbits && code >= fc[l] && code - fc[l] < cn[l];
                 hit_rank = hit ? fr[l] + code - fc[l] : hit_rank;
                 hit_len = hit ? (uint32_t)l : hit_len;
             }
-            lut[idx] = hit_len ? (uint16_t)(sorted_sym[hit_rank] | (hit_len << 8)) : (uint16_t)0;
+            *rank = hit_rank;
+            return hit_len;
+        };
+        for (int idx = tid; idx < (1 << kLutBits); idx += 1024) {
+            uint32_t r0 = 0, r1 = 0, e = 0;
+            const uint32_t len0 = first_code_in((uint32_t)idx, kLutBits, &r0);
+            if (len0) {
+                const uint32_t len1 = first_code_in((uint32_t)idx >> len0, kLutBits - (int)len0, &r1);
+                const uint32_t s0 = sorted_sym[r0];
+                if (len1) e = s0 | ((uint32_t)sorted_sym[r1] << 8) | ((len0 + len1) << 16) | (len0 << 21) | (2u << 26);
+                else e = s0 | (len0 << 16) | (len0 << 21) | (1u << 26);
+            }
+            out->lut[idx] = e;
         }
     }
+    if (tid == 0) *valid = 1u;
+}
+
+
+constexpr int kPayWords = 1022;  // LDS copy of a chunk's payload: up to ~8 bits/symbol; larger chunks read global memory
+
+// FTILE: the tile holds dequantized coefficients as floats, [pixel][coefficient] with row stride Cpad + 2 (the
+// matrix operand then comes straight from LDS, as in the encoder); otherwise symbol bytes, converted on the fly.
+template <int MT, int LAYOUT, bool ALIGNED4, bool FTILE>
+__global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
+    __shared__ __align__(16) DecTables T;
+    __shared__ uint32_t pay[4][kPayWords + 2];  // per wavefront: the chunk's payload words
+    extern __shared__ __align__(16) uint8_t symtile[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
+    const int half = lane >> 5, l32 = lane & 31;
+    const int C = p.C;
+
+    // the table kernel has checked the stream; an invalid one leaves the flag word at 0
+    StreamView sv;
+    if (*reinterpret_cast<const uint32_t*>(p.ws) != 1u || !open_stream(p, &sv)) return;
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(p.ws + 64);
+        uint4* dst = reinterpret_cast<uint4*>(&T);
+        for (int i = tid; i < (int)(sizeof(DecTables) / 16); i += 256) dst[i] = src[i];
+    }
+    const uint32_t n_chunks = sv.n_chunks, spc = sv.spc, chunk_syms = sv.chunk_syms;
+    const uint32_t payload_words = sv.payload_words;
+    const uint64_t ppc = sv.ppc;
+    const uint32_t* chunk_off = sv.chunk_off;
+    const uint16_t* sub_bits = sv.sub_bits;
+    const uint32_t* payload = sv.payload;
+    const uint64_t V = (uint64_t)p.P * (uint64_t)C;
     __syncthreads();
 
-    const float delta = hd.delta;
+    const float delta = sv.delta;
     const float neg_off = -(float)(1 << (p.bits - 1)) * delta;  // exact: power of two times delta
     const int G = p.G;
     const uint32_t n_tiles = (n_chunks + G - 1) / G;
+    float* ftile = reinterpret_cast<float*>(symtile);
+    const int RS = p.ncs * 32 + 2;  // float tile: lanes of a half-wavefront (32 pixels) fall on the even banks
+    if constexpr (FTILE) {
+        // coefficients past C meet zero basis entries; they only have to be finite
+        const int padw = p.ncs * 32 - C;
+        const int rows = p.tile_rows;
+        for (int idx = tid; idx < rows * padw; idx += 256) {
+            int row = idx / padw;
+            ftile[row * RS + C + (idx - row * padw)] = 0.f;
+        }
+    }
 
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         // ---- variable length decoding into the LDS tile ----
@@ -268,15 +396,23 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 if (cnt)
-                    ok_run = decode_run<true, ALIGNED4>(pw, nullptr, nwords, start, cnt, nbase, lut, cnt_len,
-                                                        first_rank, first_code, sorted_sym, symtile);
+                {
+                    if constexpr (FTILE)
+                        ok_run = decode_run<true>(pw, nullptr, nwords, start, cnt, T,
+                                                  FloatOut(ftile, nbase, (uint32_t)C, (uint32_t)RS, delta, neg_off));
+                    else
+                        ok_run = decode_run<true>(pw, nullptr, nwords, start, cnt, T, ByteOut(symtile, nbase));
+                }
                 // the next chunk of this wavefront overwrites pay[]: all lanes are done reading here
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 __builtin_amdgcn_wave_barrier();
             } else if (cnt) {
                 // a chunk too large for the LDS copy is read in place
-                ok_run = decode_run<false, ALIGNED4>(nullptr, payload + w0, nwords, start, cnt, nbase, lut, cnt_len,
-                                                     first_rank, first_code, sorted_sym, symtile);
+                if constexpr (FTILE)
+                    ok_run = decode_run<false>(nullptr, payload + w0, nwords, start, cnt, T,
+                                               FloatOut(ftile, nbase, (uint32_t)C, (uint32_t)RS, delta, neg_off));
+                else
+                    ok_run = decode_run<false>(nullptr, payload + w0, nwords, start, cnt, T, ByteOut(symtile, nbase));
             }
             if (!ok_run) atomicOr(p.err, FMTC_ERR_CODE);
         }
@@ -308,6 +444,46 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
             for (int u = wave; u < nunits; u += 4) {
                 const int ct = ct0 + u % nct_g;
                 const int pt0 = (u / nct_g) * MT;
+                floatx16 acc[MT];
+#pragma unroll
+                for (int m = 0; m < MT; m++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) acc[m][r] = 0.f;
+                if constexpr (FTILE) {
+                    const float* arow[MT];
+#pragma unroll
+                    for (int m = 0; m < MT; m++) {
+                        int pxl = (pt0 + m) * 32 + l32;
+                        if (pxl > TP - 1) pxl = TP - 1;  // rows past the tile repeat the last pixel; never stored
+                        arow[m] = ftile + pxl * RS + half;
+                    }
+                    // slot s of the packed basis tile holds coefficient ks*32 + 2*s + half for this lane
+                    const float4* bsrc = reinterpret_cast<const float4*>(p.Bpf + ((size_t)ct * p.ncs * 64 + lane) * 16);
+                    float4 b_cur[4], b_nxt[4];
+#pragma unroll
+                    for (int q = 0; q < 4; q++) b_cur[q] = bsrc[q];
+                    for (int ks = 0; ks < p.ncs; ks++) {
+                        if (ks + 1 < p.ncs) {
+                            const float4* nsrc = bsrc + (size_t)(ks + 1) * 64 * 4;
+#pragma unroll
+                            for (int q = 0; q < 4; q++) b_nxt[q] = nsrc[q];
+                        }
+#pragma unroll
+                        for (int sl = 0; sl < 16; sl++) {
+                            const float bq = reinterpret_cast<const float*>(b_cur)[sl];
+#pragma unroll
+                            for (int m = 0; m < MT; m++) {
+                                const float a = arow[m][ks * 32 + 2 * sl];
+                                if constexpr (LAYOUT == FMTC_NHWC)
+                                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bq, acc[m], 0, 0, 0);
+                                else
+                                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq, a, acc[m], 0, 0, 0);
+                            }
+                        }
+#pragma unroll
+                        for (int q = 0; q < 4; q++) b_cur[q] = b_nxt[q];
+                    }
+                } else {
                 uint32_t rowbase[MT];
 #pragma unroll
                 for (int m = 0; m < MT; m++) {
@@ -315,12 +491,6 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
                     if (pxl > TP - 1) pxl = TP - 1;  // rows past the tile repeat the last pixel; never stored
                     rowbase[m] = (uint32_t)pxl * (uint32_t)C + 4u * half;
                 }
-                floatx16 acc[MT];
-#pragma unroll
-                for (int m = 0; m < MT; m++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) acc[m][r] = 0.f;
-
                 const float4* bsrc = reinterpret_cast<const float4*>(p.Bpk + ((size_t)ct * p.ncs * 64 + lane) * 16);
                 float4 b_cur[4], b_nxt[4];
 #pragma unroll
@@ -335,55 +505,82 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
                     for (int t = 0; t < 4; t++) {
                         const float4 bv = b_cur[t];
                         const float bs[4] = {bv.x, bv.y, bv.z, bv.w};
+                        uint32_t w[MT];
 #pragma unroll
                         for (int m = 0; m < MT; m++) {
                             const uint32_t n = rowbase[m] + (uint32_t)(ks * 32 + 8 * t);
-                            uint32_t w;
                             if constexpr (ALIGNED4) {
-                                w = *reinterpret_cast<const uint32_t*>(symtile + sym_addr(n));
+                                w[m] = *reinterpret_cast<const uint32_t*>(symtile + sym_addr(n));
                             } else {
-                                w = (uint32_t)symtile[sym_addr(n)] | ((uint32_t)symtile[sym_addr(n + 1)] << 8) |
-                                    ((uint32_t)symtile[sym_addr(n + 2)] << 16) | ((uint32_t)symtile[sym_addr(n + 3)] << 24);
+                                w[m] = (uint32_t)symtile[sym_addr(n)] | ((uint32_t)symtile[sym_addr(n + 1)] << 8) |
+                                       ((uint32_t)symtile[sym_addr(n + 2)] << 16) |
+                                       ((uint32_t)symtile[sym_addr(n + 3)] << 24);
                             }
+                        }
+                        // consecutive matrix instructions go to different accumulators
 #pragma unroll
-                            for (int i = 0; i < 4; i++) {
-                                float yq = __builtin_fmaf((float)((w >> (8 * i)) & 255u), delta, neg_off);
+                        for (int i = 0; i < 4; i++)
+#pragma unroll
+                            for (int m = 0; m < MT; m++) {
+                                float yq = __builtin_fmaf((float)((w[m] >> (8 * i)) & 255u), delta, neg_off);
                                 if constexpr (LAYOUT == FMTC_NHWC)
                                     acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(yq, bs[i], acc[m], 0, 0, 0);
                                 else
                                     acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(bs[i], yq, acc[m], 0, 0, 0);
                             }
-                        }
                     }
 #pragma unroll
                     for (int q = 0; q < 4; q++) b_cur[q] = b_nxt[q];
                 }
 
-                // accumulator r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of the 32x32 tile
+                }
+
+                // accumulator r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of the 32x32 tile.
+                // Whole 32-pixel tiles are stored without per-element predicates (one straight run of stores).
                 if constexpr (LAYOUT == FMTC_NHWC) {
                     const int c = ct * 32 + l32;
                     if (c < C) {
                         const float m_c = p.mu[c];
 #pragma unroll
-                        for (int m = 0; m < MT; m++)
+                        for (int m = 0; m < MT; m++) {
+                            const int px_first = (pt0 + m) * 32;
+                            float* dst = p.xhat + (px_tile0 + px_first + 4 * half) * C + c;
+                            if (px_first + 32 <= TP) {
 #pragma unroll
-                            for (int r = 0; r < 16; r++) {
-                                int pxl = (pt0 + m) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                                if (pxl < TP) p.xhat[(px_tile0 + pxl) * C + c] = acc[m][r] + m_c;
+                                for (int r = 0; r < 16; r++) dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = acc[m][r] + m_c;
+                            } else {
+#pragma unroll
+                                for (int r = 0; r < 16; r++) {
+                                    int pxl = px_first + 8 * (r >> 2) + 4 * half + (r & 3);
+                                    if (pxl < TP) dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = acc[m][r] + m_c;
+                                }
                             }
+                        }
                     }
                 } else {
+                    float m_r[16];
+                    const int cb = ct * 32 + 4 * half;
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        int c = cb + 8 * (r >> 2) + (r & 3);
+                        m_r[r] = p.mu[c];  // mu is padded to a multiple of 32
+                    }
 #pragma unroll
                     for (int m = 0; m < MT; m++) {
                         int pxl = (pt0 + m) * 32 + l32;
                         if (pxl < TP) {
                             int64_t px = px_tile0 + pxl;
                             int64_t n = px / p.HW, hw = px - n * p.HW;
-                            float* dst = p.xhat + n * (int64_t)C * p.HW + hw;
+                            float* dst = p.xhat + (n * (int64_t)C + cb) * p.HW + hw;
+                            if (ct * 32 + 32 <= C) {
 #pragma unroll
-                            for (int r = 0; r < 16; r++) {
-                                int c = ct * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                                if (c < C) dst[(int64_t)c * p.HW] = acc[m][r] + p.mu[c];
+                                for (int r = 0; r < 16; r++) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * p.HW] = acc[m][r] + m_r[r];
+                            } else {
+#pragma unroll
+                                for (int r = 0; r < 16; r++) {
+                                    int c = cb + 8 * (r >> 2) + (r & 3);
+                                    if (c < C) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * p.HW] = acc[m][r] + m_r[r];
+                                }
                             }
                         }
                     }
@@ -394,13 +591,23 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
     }
 }
 
+size_t decode_workspace_bytes() { return align_up(kDecWorkspaceBytes, 256); }
+
 hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
-                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, hipStream_t s) {
+                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, uint8_t* d_ws,
+                         hipStream_t s) {
     const int C = g.C;
     const int ncs = (C + 31) / 32;
-    // tile: enough chunks for at least 64 pixels at the nominal chunk size, 4..16 chunks
-    int G = (int)((64 * (int64_t)C + 4095) / 4096);
-    G = G < 4 ? 4 : (G > 16 ? 16 : (G + 3) / 4 * 4);
+    // Float tile (dequantized coefficients in LDS) for mid-size C; byte tile otherwise and for symbols-only.
+    const bool ftile = !d_syms && C >= 32 && C <= 256;
+    int G;
+    if (ftile) {
+        G = (C <= 32) ? 1 : 2;  // 128 pixels at C <= 64, about 64 up to C = 144, 32 at C = 256
+    } else {
+        // enough chunks for at least 64 pixels at the nominal chunk size, 4..16 chunks
+        G = (int)((64 * (int64_t)C + 4095) / 4096);
+        G = G < 4 ? 4 : (G > 16 ? 16 : (G + 3) / 4 * 4);
+    }
     DecodeParams p;
     p.stream = d_stream;
     p.bytes = bytes;
@@ -411,10 +618,20 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     p.G = G;
     p.ncs = ncs;
     p.Bpk = b ? b->inv : nullptr;
+    p.Bpf = b ? b->invf : nullptr;
     p.mu = b ? b->mu : nullptr;
     p.xhat = d_xhat;
     p.syms_out = d_syms;
     p.err = d_err;
+    p.ws = d_ws;
+    p.ct_per_group = 1;
+    // a chunk never holds more than 4096 / C pixels (one if C > 4096 / 2), whatever chunk size the stream was made with
+    const int max_ppc = 4096 / C > 1 ? 4096 / C : 1;
+    p.tile_rows = (G * max_ppc + 31) / 32 * 32;
+    {
+        ProfScope prof(K_DECODE_TABLES, s);
+        hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(1024), 0, s, p);
+    }
     // the grid is sized from the nominal geometry; the kernel takes the real one from the header
     const uint32_t n_tiles = (g.n_chunks + G - 1) / G;
     int groups = 1;
@@ -427,26 +644,33 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     groups = (ncs + p.ct_per_group - 1) / p.ct_per_group;
     unsigned gx = n_tiles < 2048u ? n_tiles : 2048u;
     dim3 grid(gx, (unsigned)groups);
-    const size_t lds = (size_t)G * 4096 + (size_t)G * 4096 / 16 + 128;
+    const size_t lds = ftile ? sizeof(float) * (size_t)p.tile_rows * (ncs * 32 + 2)
+                             : (size_t)G * 4096 + (size_t)G * 4096 / 16 + 128;
     const bool al = (C % 4) == 0;
     ProfScope prof(K_DECODE, s);
-    const bool wide = C > 256;  // fewer pixels per tile: 2 pixel tiles per wavefront unit instead of 4
     // more than 64 KB of dynamic LDS has to be requested per kernel (the CU has 160 KB)
-#define FMTC_DEC(MT, LAY, AL)                                                                                \
+#define FMTC_DEC(MT, LAY, AL, FT)                                                                            \
     do {                                                                                                     \
-        if (lds > 48 * 1024) {                                                                               \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MT, LAY, AL>),       \
+        if (lds > 32 * 1024) {                                                                               \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MT, LAY, AL, FT>),   \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);      \
             if (ea != hipSuccess) return ea;                                                                 \
         }                                                                                                    \
-        hipLaunchKernelGGL((k_decode<MT, LAY, AL>), grid, dim3(256), lds, s, p);                             \
+        hipLaunchKernelGGL((k_decode<MT, LAY, AL, FT>), grid, dim3(256), lds, s, p);                         \
     } while (0)
-    if (layout == FMTC_NHWC) {
-        if (al) { if (wide) FMTC_DEC(2, FMTC_NHWC, true); else FMTC_DEC(4, FMTC_NHWC, true); }
-        else    { if (wide) FMTC_DEC(2, FMTC_NHWC, false); else FMTC_DEC(4, FMTC_NHWC, false); }
+    if (ftile) {
+        const bool two = p.tile_rows >= 64;  // two 32-pixel tiles per wavefront unit
+        if (layout == FMTC_NHWC) { if (two) FMTC_DEC(2, FMTC_NHWC, true, true); else FMTC_DEC(1, FMTC_NHWC, true, true); }
+        else                     { if (two) FMTC_DEC(2, FMTC_NCHW, true, true); else FMTC_DEC(1, FMTC_NCHW, true, true); }
     } else {
-        if (al) { if (wide) FMTC_DEC(2, FMTC_NCHW, true); else FMTC_DEC(4, FMTC_NCHW, true); }
-        else    { if (wide) FMTC_DEC(2, FMTC_NCHW, false); else FMTC_DEC(4, FMTC_NCHW, false); }
+        const bool wide = C > 256;  // fewer pixels per tile: 2 pixel tiles per wavefront unit instead of 4
+        if (layout == FMTC_NHWC) {
+            if (al) { if (wide) FMTC_DEC(2, FMTC_NHWC, true, false); else FMTC_DEC(4, FMTC_NHWC, true, false); }
+            else    { if (wide) FMTC_DEC(2, FMTC_NHWC, false, false); else FMTC_DEC(4, FMTC_NHWC, false, false); }
+        } else {
+            if (al) { if (wide) FMTC_DEC(2, FMTC_NCHW, true, false); else FMTC_DEC(4, FMTC_NCHW, true, false); }
+            else    { if (wide) FMTC_DEC(2, FMTC_NCHW, false, false); else FMTC_DEC(4, FMTC_NCHW, false, false); }
+        }
     }
 #undef FMTC_DEC
     return hipGetLastError();

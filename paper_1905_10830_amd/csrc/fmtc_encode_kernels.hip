@@ -169,46 +169,67 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
                 words[m][g] = word;
             }
         }
-        // ---- exact decision for the flagged values: the whole wavefront recomputes y in fp64 ----
-        // (same arithmetic as the definition: sum of T[k][c] * (x[c] - mu[c]), divided by the step)
+        // ---- exact decision for the flagged values: fp64 recomputation, four values per round ----
+        // (same arithmetic as the definition: sum of T[k][c] * (x[c] - mu[c]), divided by the step).
+        // Each 16-lane group of the wavefront takes one flagged value, so the loads of four values overlap.
         unsigned long long pending = __ballot(near_mask != 0);
         while (pending) {
-            const int L = __ffsll((long long)pending) - 1;
-            const uint32_t fm = (uint32_t)__builtin_amdgcn_readlane((int)near_mask, L);
-            const int v = __ffs((int)fm) - 1;
-            const int m = v >> 4, r = v & 15;
-            const int k = kt * 32 + 8 * (r >> 2) + 4 * (L >> 5) + (r & 3);
-            const int64_t px = px0 + (pg * MT + m) * 32 + (L & 31);
-            int64_t xbase, xstride;
-            if constexpr (LAYOUT == FMTC_NHWC) {
-                xbase = px * C;
-                xstride = 1;
-            } else {
-                int64_t n = px / HW;
-                xbase = n * (int64_t)C * HW + (px - n * HW);
-                xstride = HW;
-            }
-            double part = 0.0;
-            for (int c = lane; c < C; c += 64)
-                part += (double)Trow[(size_t)k * C + c] * ((double)x[xbase + c * xstride] - (double)mu[c]);
+            int Ls[4];
+            unsigned long long pm = pending;
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+            for (int q = 0; q < 4; q++) {
+                Ls[q] = pm ? (__ffsll((long long)pm) - 1) : -1;
+                pm &= pm - 1;
+            }
+            const int grp = lane >> 4;
+            const int Lq = grp == 0 ? Ls[0] : (grp == 1 ? Ls[1] : (grp == 2 ? Ls[2] : Ls[3]));
+            const bool active = Lq >= 0;
+            const uint32_t fm = (uint32_t)__shfl((int)near_mask, active ? Lq : 0, 64);
+            const int v = active ? (__ffs((int)fm) - 1) : 0;
+            const int m = v >> 4, r = v & 15;
+            const int k = kt * 32 + 8 * (r >> 2) + 4 * (Lq >> 5) + (r & 3);
+            const int64_t px = px0 + (pg * MT + m) * 32 + (Lq & 31);
+            double part = 0.0;
+            if (active) {
+                int64_t xbase, xstride;
+                if constexpr (LAYOUT == FMTC_NHWC) {
+                    xbase = px * C;
+                    xstride = 1;
+                } else {
+                    int64_t n = px / HW;
+                    xbase = n * (int64_t)C * HW + (px - n * HW);
+                    xstride = HW;
+                }
+                for (int c = lane & 15; c < C; c += 16)
+                    part += (double)Trow[(size_t)k * C + c] * ((double)x[xbase + c * xstride] - (double)mu[c]);
+            }
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);  // stays inside the 16-lane group
             double qd = rint(part / (double)delta);
             qd = fmin(fmax(qd, (double)lo), (double)hi);
-            const uint32_t sfix = (uint32_t)((int)qd + zero_sym);
-            if (lane == L) {
+            const int sfix = (int)qd + zero_sym;
 #pragma unroll
-                for (int mm = 0; mm < MT; mm++)
+            for (int q = 0; q < 4; q++) {
+                const int vq = __shfl(v, 16 * q, 64);
+                const int sq = __shfl(sfix, 16 * q, 64);
+                if (lane == Ls[q]) {
+                    const int mq = vq >> 4, rq = vq & 15;
 #pragma unroll
-                    for (int g = 0; g < 4; g++)
-                        if (mm == m && g == (r >> 2))
-                            words[mm][g] = (words[mm][g] & ~(0xffu << (8 * (r & 3)))) | (sfix << (8 * (r & 3)));
-                near_mask &= ~(1u << v);
+                    for (int mm = 0; mm < MT; mm++)
+#pragma unroll
+                        for (int g = 0; g < 4; g++)
+                            if (mm == mq && g == (rq >> 2))
+                                words[mm][g] = (words[mm][g] & ~(0xffu << (8 * (rq & 3)))) |
+                                               ((uint32_t)sq << (8 * (rq & 3)));
+                    near_mask &= ~(1u << vq);
+                }
             }
             pending = __ballot(near_mask != 0);
         }
         // ---- count and stage ----
+        // zero-level symbols (the bulk) are counted with byte arithmetic, the others with LDS atomics
         uint32_t zero_count = 0;
+        const uint32_t zero4 = (uint32_t)zero_sym * 0x01010101u;
 #pragma unroll
         for (int m = 0; m < MT; m++) {
             const int pxl = (pg * MT + m) * 32 + l32;
@@ -217,16 +238,24 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
             for (int g = 0; g < 4; g++) {
                 const int k = kt * 32 + 8 * g + 4 * half;
                 const uint32_t word = words[m][g];
-#pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    int sy = (int)((word >> (8 * i)) & 255u);
-                    bool ok = px_ok && (k + i) < C;
-                    zero_count += (uint32_t)__popcll(__ballot(ok && sy == zero_sym));
-                    if (ok && sy != zero_sym) atomicAdd(&lhist[sy], 1u);
+                // 0x80 in every byte of the word that is a valid coefficient
+                const int nvalid = !px_ok ? 0 : (C - k >= 4 ? 4 : (C - k > 0 ? C - k : 0));
+                const uint32_t vmask = nvalid == 4 ? 0x80808080u : (0x80808080u >> (8 * (4 - nvalid))) * (nvalid != 0);
+                const uint32_t xz = word ^ zero4;
+                uint32_t t = (xz & 0x7f7f7f7fu) + 0x7f7f7f7fu;
+                t = ~(t | xz | 0x7f7f7f7fu);  // 0x80 where the byte equals the zero level
+                zero_count += (uint32_t)__popc(t & vmask);
+                uint32_t nz = ~t & vmask;
+                while (nz) {
+                    const int bit = __ffs((int)nz) - 1;  // 8*i + 7
+                    atomicAdd(&lhist[(word >> (bit - 7)) & 255u], 1u);
+                    nz &= nz - 1;
                 }
                 st[pxl * RSW + ktl * 8 + 2 * g + half] = word;
             }
         }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) zero_count += __shfl_xor(zero_count, o, 64);
         if (lane == 0 && zero_count) atomicAdd(&lhist[zero_sym], zero_count);
     }
     __syncthreads();

@@ -14,7 +14,7 @@ constexpr int kLenTableBytes = 256;
 constexpr int kSubSyms = 64;     // symbols per run; one lane codes one run
 constexpr int kMaxLen = 48;      // longest code length accepted
 constexpr int kHistCopies = 16;  // replicated global histograms (spreads atomics over L2 channels)
-constexpr int kLutBits = 10;     // decoder lookup table covers codes up to this length
+constexpr int kLutBits = 12;     // decoder lookup table covers codes up to this length
 
 // 64-byte stream header (see fmtc.h for the field meaning).
 struct alignas(8) Header {
@@ -101,13 +101,14 @@ inline Workspace make_workspace(uint64_t V, uint32_t n_chunks) {
 struct BasisDevice {
     int C, Cpad;           // Cpad = C rounded up to 32
     const float* fwd;      // M = T      (row = coefficient k, column = channel c)
-    const float* inv;      // M = T^T    (row = channel c, column = coefficient k)
+    const float* inv;      // M = T^T    (row = channel c, column = coefficient k), inverse slot order
+    const float* invf;     // M = T^T, forward slot order
     const float* mu;       // [Cpad], zero padded
     const float* T;        // [C][C] row major, unpacked
 };
 
 // ---- optional per-kernel timing (fmtc_profile_* in fmtc.h); no-ops unless enabled ----
-enum KernelId { K_CLEAR = 0, K_PROJECT, K_HISTOGRAM, K_TABLE, K_RUN_BITS, K_OFFSETS, K_PACK, K_DECODE, K_COUNT };
+enum KernelId { K_CLEAR = 0, K_PROJECT, K_HISTOGRAM, K_TABLE, K_RUN_BITS, K_OFFSETS, K_PACK, K_DECODE_TABLES, K_DECODE, K_COUNT };
 void prof_mark(int id, bool end, hipStream_t s);
 struct ProfScope {
     int id;
@@ -133,7 +134,9 @@ hipError_t launch_pack(const uint8_t* d_syms, const Geometry& g, int bits, float
                        uint32_t* d_chunk_bits, uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s);
 
 hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
-                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, hipStream_t s);
+                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, uint8_t* d_ws,
+                         hipStream_t s);
+size_t decode_workspace_bytes();
 
 hipError_t launch_fit_moments(const float* d_x, int64_t N, int C, int64_t HW, int layout, double* d_sum,
                               double* d_cov, hipStream_t s);

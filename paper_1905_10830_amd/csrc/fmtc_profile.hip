@@ -17,7 +17,7 @@ struct Profiler {
 };
 Profiler g_prof;
 const char* const kNames[K_COUNT] = {"k_clear",    "k_project_quantize", "k_histogram", "k_huffman_table",
-                                     "k_run_bits", "k_chunk_offsets",    "k_pack",      "k_decode"};
+                                     "k_run_bits", "k_chunk_offsets",    "k_pack",      "k_decode_tables", "k_decode"};
 
 void release() {
     for (int k = 0; k < K_COUNT; k++) {

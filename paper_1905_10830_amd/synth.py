@@ -60,6 +60,11 @@ WORKLOADS = {
     "resnet18_stage4_c512_7": dict(N=64, C=512, H=7, W=7, rank=128, act="relu", bits=(4,), calib=8),
     "mbv2_c144_56": dict(N=64, C=144, H=56, W=56, rank=18, act="relu6", bits=(5,), calib=8),
     "mbv2_c960_7": dict(N=64, C=960, H=7, W=7, rank=120, act="relu6", bits=(5,), calib=8),
+    # inference-shaped sweep: the four ResNet-18 post-block shapes at N = 256
+    "resnet18_n256_c64_56": dict(N=256, C=64, H=56, W=56, rank=16, act="relu", bits=(8, 6, 4, 3, 2), calib=8),
+    "resnet18_n256_c128_28": dict(N=256, C=128, H=28, W=28, rank=32, act="relu", bits=(8, 6, 4, 3, 2), calib=8),
+    "resnet18_n256_c256_14": dict(N=256, C=256, H=14, W=14, rank=64, act="relu", bits=(8, 6, 4, 3, 2), calib=8),
+    "resnet18_n256_c512_7": dict(N=256, C=512, H=7, W=7, rank=128, act="relu", bits=(8, 6, 4, 3, 2), calib=8),
 }
 
 
