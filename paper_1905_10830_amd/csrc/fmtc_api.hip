@@ -178,17 +178,20 @@ size_t bound_from(const EncodePlan& pl, int bits) {
     return pl.g.off_payload + 4 * (size_t)((pl.V * (uint64_t)bits + 31) / 32 + pl.g.n_chunks);
 }
 
-// histogram copies and counters -> table -> run sizes -> offsets -> payload
-fmtc_status run_coder(const uint8_t* d_syms, const EncodePlan& pl, int bits, float delta, uint8_t* ws,
+// partial histograms -> table -> run sizes and chunk offsets -> payload
+fmtc_status run_coder(const uint8_t* d_syms, const EncodePlan& pl, int n_parts, int bits, float delta, uint8_t* ws,
                       uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s) {
     hipError_t e;
-    uint32_t* hist_copies = reinterpret_cast<uint32_t*>(ws + pl.ws.off_hist_copies);
+    uint32_t* hist_parts = reinterpret_cast<uint32_t*>(ws + pl.ws.off_hist_parts);
+    uint32_t* counters = reinterpret_cast<uint32_t*>(ws + pl.ws.off_counters);
     uint32_t* hist = reinterpret_cast<uint32_t*>(ws + pl.ws.off_hist);
     uint64_t* enc_table = reinterpret_cast<uint64_t*>(ws + pl.ws.off_enc_table);
     uint32_t* chunk_bits = reinterpret_cast<uint32_t*>(ws + pl.ws.off_chunk_bits);
-    if ((e = launch_huffman_table(hist_copies, bits, hist, enc_table, d_stream + kHeaderBytes, s)) != hipSuccess)
+    if ((e = launch_huffman_table(hist_parts, n_parts, bits, hist, enc_table, d_stream + kHeaderBytes, counters,
+                                  s)) != hipSuccess)
         return hip_fail(e, "huffman table kernel");
-    if ((e = launch_pack(d_syms, pl.g, bits, delta, enc_table, chunk_bits, d_stream, d_out_bytes, s)) != hipSuccess)
+    if ((e = launch_pack(d_syms, pl.g, bits, delta, enc_table, chunk_bits, counters, d_stream, d_out_bytes, s)) !=
+        hipSuccess)
         return hip_fail(e, "pack kernels");
     return FMTC_OK;
 }
@@ -351,16 +354,17 @@ fmtc_status fmtc_quantize(const fmtc_basis* basis, const float* d_x, int64_t N, 
     if (ws_bytes < ws.off_chunk_bits) return fail(FMTC_EBUFSIZE, "workspace too small");
     hipStream_t s = (hipStream_t)hip_stream;
     uint8_t* w = static_cast<uint8_t*>(d_workspace);
-    uint32_t* hist_copies = reinterpret_cast<uint32_t*>(w + ws.off_hist_copies);
+    uint32_t* hist_parts = reinterpret_cast<uint32_t*>(w + ws.off_hist_parts);
     hipError_t e;
-    if ((e = launch_clear(hist_copies, (ws.off_hist - ws.off_hist_copies) / 4, s)) != hipSuccess) return hip_fail(e, "clear");
+    int n_parts = 0;
     const float delta = fmtc_delta(basis->range_A, bits);
-    if ((e = launch_project_quantize(device_view(basis), d_x, N, (int64_t)H * W, layout, delta, bits, d_syms, hist_copies, s)) != hipSuccess)
+    if ((e = launch_project_quantize(device_view(basis), d_x, N, (int64_t)H * W, layout, delta, bits, d_syms, hist_parts, &n_parts, s)) != hipSuccess)
         return hip_fail(e, "project/quantize kernel");
     if (d_hist) {
-        // sum of the copies: the table kernel does it; its other outputs go to the workspace
-        if ((e = launch_huffman_table(hist_copies, bits, d_hist, reinterpret_cast<uint64_t*>(w + ws.off_enc_table),
-                                      w + ws.off_hist /* length table scratch */, s)) != hipSuccess)
+        // sum of the partial histograms: the table kernel does it; its other outputs go to the workspace
+        if ((e = launch_huffman_table(hist_parts, n_parts, bits, d_hist, reinterpret_cast<uint64_t*>(w + ws.off_enc_table),
+                                      w + ws.off_hist /* length table scratch */,
+                                      reinterpret_cast<uint32_t*>(w + ws.off_counters), s)) != hipSuccess)
             return hip_fail(e, "histogram reduction");
     }
     return FMTC_OK;
@@ -382,14 +386,14 @@ fmtc_status fmtc_encode(const fmtc_basis* basis, const float* d_x, int64_t N, in
     if (cap < bound_from(pl, bits)) return fail(FMTC_EBUFSIZE, "stream capacity too small: %zu < %zu", cap, bound_from(pl, bits));
     hipStream_t s = (hipStream_t)hip_stream;
     uint8_t* w = static_cast<uint8_t*>(d_workspace);
-    uint32_t* hist_copies = reinterpret_cast<uint32_t*>(w + pl.ws.off_hist_copies);
+    uint32_t* hist_parts = reinterpret_cast<uint32_t*>(w + pl.ws.off_hist_parts);
     uint8_t* syms = w + pl.ws.off_syms;
     hipError_t e;
-    if ((e = launch_clear(hist_copies, (pl.ws.off_hist - pl.ws.off_hist_copies) / 4, s)) != hipSuccess) return hip_fail(e, "clear");
+    int n_parts = 0;
     const float delta = fmtc_delta(basis->range_A, bits);
-    if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, syms, hist_copies, s)) != hipSuccess)
+    if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, syms, hist_parts, &n_parts, s)) != hipSuccess)
         return hip_fail(e, "project/quantize kernel");
-    return run_coder(syms, pl, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
+    return run_coder(syms, pl, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
 }
 
 fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits, int chunk_syms, float delta,
@@ -406,12 +410,11 @@ fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits,
     if (cap < bound_from(pl, bits)) return fail(FMTC_EBUFSIZE, "stream capacity too small: %zu < %zu", cap, bound_from(pl, bits));
     hipStream_t s = (hipStream_t)hip_stream;
     uint8_t* w = static_cast<uint8_t*>(d_workspace);
-    uint32_t* hist_copies = reinterpret_cast<uint32_t*>(w + pl.ws.off_hist_copies);
-    uint32_t* counters = reinterpret_cast<uint32_t*>(w + pl.ws.off_counters);
+    uint32_t* hist_parts = reinterpret_cast<uint32_t*>(w + pl.ws.off_hist_parts);
     hipError_t e;
-    if ((e = launch_clear(hist_copies, (pl.ws.off_hist - pl.ws.off_hist_copies) / 4, s)) != hipSuccess) return hip_fail(e, "clear");
-    if ((e = launch_histogram(d_syms, pl.V, bits, hist_copies, counters, s)) != hipSuccess) return hip_fail(e, "histogram kernel");
-    return run_coder(d_syms, pl, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
+    int n_parts = 0;
+    if ((e = launch_histogram(d_syms, pl.V, bits, hist_parts, &n_parts, s)) != hipSuccess) return hip_fail(e, "histogram kernel");
+    return run_coder(d_syms, pl, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
 }
 
 static fmtc_status decode_common(const fmtc_basis* basis, const void* d_stream_in, size_t bytes, int64_t P, int C,

@@ -34,10 +34,11 @@ __device__ __forceinline__ void lane_set(uint32_t (&v)[NV], int lane, int idx, u
 // registers, so a step costs a few lane reads/writes instead of LDS round trips.
 // NV * 64 >= alphabet size.
 template <int NV>
-__global__ __launch_bounds__(256) void k_huffman_table(const uint32_t* __restrict__ hist_copies, int bits,
-                                                       uint32_t* __restrict__ hist_out,
-                                                       uint64_t* __restrict__ enc_table,
-                                                       uint8_t* __restrict__ len_table) {
+__global__ __launch_bounds__(1024) void k_huffman_table(const uint32_t* __restrict__ hist_parts, int n_parts,
+                                                        int bits, uint32_t* __restrict__ hist_out,
+                                                        uint64_t* __restrict__ enc_table,
+                                                        uint8_t* __restrict__ len_table,
+                                                        uint32_t* __restrict__ counters) {
     __shared__ uint32_t h[256];
     __shared__ uint32_t weight[256];       // leaf weights in (count, symbol) order
     __shared__ uint16_t leaf_parent[256];  // index of the internal node above each sorted leaf
@@ -49,15 +50,33 @@ __global__ __launch_bounds__(256) void k_huffman_table(const uint32_t* __restric
 
     const int s = threadIdx.x;
     const int K = 1 << bits;
-    uint32_t cnt = 0;
-    if (s < K)
-        for (int c = 0; c < kHistCopies; c++) cnt += hist_copies[c * 256 + s];
-    h[s] = cnt;
-    len[s] = 0;
+    if (s < 256) {
+        h[s] = 0u;
+        len[s] = 0;
+    }
     if (s <= kMaxLen + 1) len_count[s] = 0;
     if (s == 0) n_used = 0;
+    if (s < 16) counters[s] = 0u;  // tickets of the kernels that follow in this call
     __syncthreads();
-    hist_out[s] = cnt;
+    {
+        // sum of the partial histograms: 1024 / K threads share a bin
+        const int bin = s & (K - 1), first = s >> bits, step = 1024 >> bits;
+        uint32_t part = 0;
+        int q = first;
+        for (; q + 7 * step < n_parts; q += 8 * step) {  // eight independent loads in flight
+            uint32_t v[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) v[j] = hist_parts[(size_t)(q + j * step) * K + bin];
+#pragma unroll
+            for (int j = 0; j < 8; j++) part += v[j];
+        }
+        for (; q < n_parts; q += step) part += hist_parts[(size_t)q * K + bin];
+        if (part) atomicAdd(&h[bin], part);
+    }
+    __syncthreads();
+    // from here on at most one thread per symbol works; the others only keep the barriers company
+    const uint32_t cnt = s < 256 ? h[s] : 0u;
+    if (s < 256) hist_out[s] = cnt;
 
     // rank of every used symbol in (count, symbol) order
     int rank = 0;
@@ -135,31 +154,33 @@ __global__ __launch_bounds__(256) void k_huffman_table(const uint32_t* __restric
         first_code[s] = code;
     }
     __syncthreads();
-    const int l = len[s];
-    uint64_t entry = 0;
-    if (l) {
-        int before = 0;
-        for (int t = 0; t < s; t++) before += (len[t] == l) ? 1 : 0;
-        uint64_t code = first_code[l] + (uint64_t)before;
-        uint64_t rev = __brevll(code) >> (64 - l);  // stream order is least significant bit first
-        entry = rev | ((uint64_t)l << 56);
+    if (s < 256) {
+        const int l = len[s];
+        uint64_t entry = 0;
+        if (l) {
+            int before = 0;
+            for (int t = 0; t < s; t++) before += (len[t] == l) ? 1 : 0;
+            uint64_t code = first_code[l] + (uint64_t)before;
+            uint64_t rev = __brevll(code) >> (64 - l);  // stream order is least significant bit first
+            entry = rev | ((uint64_t)l << 56);
+        }
+        enc_table[s] = entry;
+        len_table[s] = (uint8_t)l;
     }
-    enc_table[s] = entry;
-    len_table[s] = (uint8_t)l;
 }
 
-hipError_t launch_huffman_table(const uint32_t* d_hist_copies, int bits, uint32_t* d_hist, uint64_t* d_enc_table,
-                                uint8_t* d_len_table, hipStream_t s) {
+hipError_t launch_huffman_table(const uint32_t* d_hist_parts, int n_parts, int bits, uint32_t* d_hist,
+                                uint64_t* d_enc_table, uint8_t* d_len_table, uint32_t* d_counters, hipStream_t s) {
     ProfScope prof(K_TABLE, s);
     if (bits <= 6)
-        hipLaunchKernelGGL(k_huffman_table<1>, dim3(1), dim3(256), 0, s, d_hist_copies, bits, d_hist, d_enc_table,
-                           d_len_table);
+        hipLaunchKernelGGL(k_huffman_table<1>, dim3(1), dim3(1024), 0, s, d_hist_parts, n_parts, bits, d_hist,
+                           d_enc_table, d_len_table, d_counters);
     else if (bits == 7)
-        hipLaunchKernelGGL(k_huffman_table<2>, dim3(1), dim3(256), 0, s, d_hist_copies, bits, d_hist, d_enc_table,
-                           d_len_table);
+        hipLaunchKernelGGL(k_huffman_table<2>, dim3(1), dim3(1024), 0, s, d_hist_parts, n_parts, bits, d_hist,
+                           d_enc_table, d_len_table, d_counters);
     else
-        hipLaunchKernelGGL(k_huffman_table<4>, dim3(1), dim3(256), 0, s, d_hist_copies, bits, d_hist, d_enc_table,
-                           d_len_table);
+        hipLaunchKernelGGL(k_huffman_table<4>, dim3(1), dim3(1024), 0, s, d_hist_parts, n_parts, bits, d_hist,
+                           d_enc_table, d_len_table, d_counters);
     return hipGetLastError();
 }
 
@@ -184,68 +205,74 @@ __device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v, int lane) {
     return incl - v;
 }
 
+// The last workgroup to finish (ticket counter, reset by the table kernel) turns the chunk sizes into
+// offsets: exclusive scan in words, header, stream size.  Every thread of it owns a contiguous segment.
 __global__ __launch_bounds__(256) void k_run_bits(const uint8_t* __restrict__ syms, uint64_t V, uint32_t n_chunks,
                                                   uint32_t chunk_syms, uint32_t subs_per_chunk,
                                                   const uint64_t* __restrict__ enc_table,
-                                                  uint16_t* __restrict__ sub_bits,
-                                                  uint32_t* __restrict__ chunk_bits) {
+                                                  uint16_t* __restrict__ sub_bits, uint32_t* chunk_bits,
+                                                  uint32_t* ticket, Header hdr, size_t off_sub_bits,
+                                                  size_t off_payload, uint8_t* __restrict__ stream,
+                                                  uint64_t* __restrict__ out_bytes) {
     __shared__ uint8_t llen[256];
+    __shared__ uint32_t wave_words[4];
+    __shared__ unsigned long long wave_bits[4];
+    __shared__ uint32_t is_last;
     llen[threadIdx.x] = (uint8_t)(enc_table[threadIdx.x] >> 56);
     __syncthreads();
-    const int lane = threadIdx.x & 63;
-    const uint32_t ch = blockIdx.x * 4 + (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    if (ch >= n_chunks) return;
-    const uint64_t c0 = (uint64_t)ch * chunk_syms;
-    const uint64_t c1 = (c0 + chunk_syms < V) ? c0 + chunk_syms : V;
-    const uint64_t r0 = c0 + (uint64_t)lane * kSubSyms;
-    uint32_t bits = 0;
-    if (r0 < c1) {
-        const uint32_t cnt = (uint32_t)((c1 - r0 < kSubSyms) ? (c1 - r0) : kSubSyms);
-        if (cnt == kSubSyms && ((uintptr_t)(syms + r0) & 15) == 0) {
-            const uint4* p = reinterpret_cast<const uint4*>(syms + r0);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t ch = blockIdx.x * 4 + (uint32_t)wave;
+    if (ch < n_chunks) {
+        const uint64_t c0 = (uint64_t)ch * chunk_syms;
+        const uint64_t c1 = (c0 + chunk_syms < V) ? c0 + chunk_syms : V;
+        const uint64_t r0 = c0 + (uint64_t)lane * kSubSyms;
+        uint32_t bits = 0;
+        if (r0 < c1) {
+            const uint32_t cnt = (uint32_t)((c1 - r0 < kSubSyms) ? (c1 - r0) : kSubSyms);
+            if (cnt == kSubSyms && ((uintptr_t)(syms + r0) & 15) == 0) {
+                const uint4* p = reinterpret_cast<const uint4*>(syms + r0);
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
-                uint4 v = p[j];
-                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                for (int j = 0; j < 4; j++) {
+                    uint4 v = p[j];
+                    uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                for (int q = 0; q < 4; q++)
+                    for (int q = 0; q < 4; q++)
 #pragma unroll
-                    for (int b = 0; b < 4; b++) bits += llen[(w[q] >> (8 * b)) & 255];
+                        for (int b = 0; b < 4; b++) bits += llen[(w[q] >> (8 * b)) & 255];
+                }
+            } else {
+                for (uint32_t i = 0; i < cnt; i++) bits += llen[syms[r0 + i]];
             }
-        } else {
-            for (uint32_t i = 0; i < cnt; i++) bits += llen[syms[r0 + i]];
         }
+        if ((uint32_t)lane < subs_per_chunk) sub_bits[(size_t)ch * subs_per_chunk + lane] = (uint16_t)bits;
+        uint32_t total = wave_sum(bits);
+        if (lane == 0) chunk_bits[ch] = total;
     }
-    if ((uint32_t)lane < subs_per_chunk) sub_bits[(size_t)ch * subs_per_chunk + lane] = (uint16_t)bits;
-    uint32_t total = wave_sum(bits);
-    if (lane == 0) chunk_bits[ch] = total;
-}
+    // ---- ticket: has every other workgroup published its chunk sizes? ----
+    // one release per workgroup (a cache write-back on this chip), not one per wavefront
+    __syncthreads();
+    if (tid == 0) {
+        __threadfence();
+        is_last = (atomicAdd(ticket, 1u) == gridDim.x - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
 
-// ---------------------------------------------------------------------------
-// Chunk offsets: exclusive scan of the chunk sizes in words, header, stream size.
-// One workgroup of 1024 threads; every thread owns a contiguous segment of chunks
-// (sum, workgroup-wide scan of the 1024 sums, then the segment's offsets).
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_chunk_offsets(const uint32_t* __restrict__ chunk_bits, uint32_t n_chunks,
-                                                        Header hdr, size_t off_sub_bits, size_t off_payload,
-                                                        uint8_t* __restrict__ stream,
-                                                        uint64_t* __restrict__ out_bytes) {
     uint32_t* chunk_off = reinterpret_cast<uint32_t*>(stream + kHeaderBytes + kLenTableBytes);
-    __shared__ uint32_t wave_words[16];
-    __shared__ unsigned long long wave_bits[16];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t seg = (n_chunks + 1023) / 1024;
+    const uint32_t seg = (n_chunks + 255) / 256;
     const uint32_t i0 = (uint32_t)tid * seg;
     const uint32_t i1 = (i0 + seg < n_chunks) ? i0 + seg : n_chunks;
     uint32_t words = 0;
-    unsigned long long bits = 0;
+    unsigned long long nbits = 0;
     for (uint32_t i = i0; i < i1; i++) {
-        uint32_t b = chunk_bits[i];
+        uint32_t b = __atomic_load_n(&chunk_bits[i], __ATOMIC_RELAXED);
         words += (b + 31) >> 5;
-        bits += b;
+        nbits += b;
     }
     uint32_t ex = wave_exclusive_scan(words, lane);
-    unsigned long long bsum = bits;
+    unsigned long long bsum = nbits;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) bsum += __shfl_xor(bsum, o, 64);
     if (lane == 63) wave_words[wave] = ex + words;
@@ -255,11 +282,11 @@ __global__ __launch_bounds__(1024) void k_chunk_offsets(const uint32_t* __restri
     for (int q = 0; q < wave; q++) base += wave_words[q];
     for (uint32_t i = i0; i < i1; i++) {
         chunk_off[i] = base;
-        base += (chunk_bits[i] + 31) >> 5;
+        base += (__atomic_load_n(&chunk_bits[i], __ATOMIC_RELAXED) + 31) >> 5;
     }
     if (tid == 0) {
         uint64_t total_words = 0, total_bits = 0;
-        for (int q = 0; q < 16; q++) {
+        for (int q = 0; q < 4; q++) {
             total_words += wave_words[q];
             total_bits += wave_bits[q];
         }
@@ -371,17 +398,13 @@ __global__ __launch_bounds__(256) void k_pack(const uint8_t* __restrict__ syms, 
 }
 
 hipError_t launch_pack(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const uint64_t* d_enc_table,
-                       uint32_t* d_chunk_bits, uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s) {
+                       uint32_t* d_chunk_bits, uint32_t* d_counters, uint8_t* d_stream, uint64_t* d_out_bytes,
+                       hipStream_t s) {
     const uint64_t V = (uint64_t)g.P * (uint64_t)g.C;
     uint16_t* sub_bits = reinterpret_cast<uint16_t*>(d_stream + g.off_sub_bits);
     uint32_t* chunk_off = reinterpret_cast<uint32_t*>(d_stream + g.off_chunk_off);
     uint32_t* payload = reinterpret_cast<uint32_t*>(d_stream + g.off_payload);
     const unsigned blocks = (g.n_chunks + 3) / 4;
-    {
-        ProfScope prof(K_RUN_BITS, s);
-        hipLaunchKernelGGL(k_run_bits, dim3(blocks), dim3(256), 0, s, d_syms, V, g.n_chunks, g.chunk_syms,
-                           g.subs_per_chunk, d_enc_table, sub_bits, d_chunk_bits);
-    }
     Header hdr = {};
     hdr.magic = kMagic;
     hdr.version = 1;
@@ -394,8 +417,9 @@ hipError_t launch_pack(const uint8_t* d_syms, const Geometry& g, int bits, float
     hdr.delta = delta;
     hdr.subs_per_chunk = g.subs_per_chunk;
     {
-        ProfScope prof(K_OFFSETS, s);
-        hipLaunchKernelGGL(k_chunk_offsets, dim3(1), dim3(1024), 0, s, d_chunk_bits, g.n_chunks, hdr, g.off_sub_bits,
+        ProfScope prof(K_RUN_BITS, s);
+        hipLaunchKernelGGL(k_run_bits, dim3(blocks), dim3(256), 0, s, d_syms, V, g.n_chunks, g.chunk_syms,
+                           g.subs_per_chunk, d_enc_table, sub_bits, d_chunk_bits, d_counters + 1, hdr, g.off_sub_bits,
                            g.off_payload, d_stream, d_out_bytes);
     }
     {

@@ -43,8 +43,8 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
                                                           const float* __restrict__ Trow, int64_t P, int64_t HW,
                                                           int C, int ncs, int kt_per_group, float inv_delta,
                                                           float delta, float tau, int bits,
-                                                          uint8_t* __restrict__ syms,
-                                                          uint32_t* __restrict__ hist_copies) {
+                                                          int64_t px_tiles, uint8_t* __restrict__ syms,
+                                                          uint32_t* __restrict__ hist_parts) {
     extern __shared__ __align__(16) float dyn_lds[];
     __shared__ uint32_t lhist[256];
 
@@ -60,9 +60,12 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int64_t px0 = (int64_t)blockIdx.x * PT;
 
     lhist[tid] = 0u;
+
+    // the workgroup walks over pixel tiles; its histogram accumulates in LDS and leaves once at the end
+    for (int64_t tile = blockIdx.x; tile < px_tiles; tile += gridDim.x) {
+    const int64_t px0 = tile * PT;
 
     // ---- the pixel tile, mean removed, as xs[pixel][channel] ----
     if constexpr (LAYOUT == FMTC_NHWC && VEC) {
@@ -277,16 +280,16 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
             }
         }
     }
-    uint32_t hcount = lhist[tid];
-    if (hcount) {
-        unsigned copy = (blockIdx.x + blockIdx.y * gridDim.x) % kHistCopies;
-        atomicAdd(&hist_copies[copy * 256 + tid], hcount);
+    __syncthreads();  // the staging tile and xs are reused by the next pixel tile
     }
+    // one row of partial counts per workgroup: nothing to clear beforehand, no global atomics
+    const int K = 1 << bits;
+    if (tid < K) hist_parts[(size_t)(blockIdx.x + blockIdx.y * gridDim.x) * K + tid] = lhist[tid];
 }
 
 template <int PT, int MT>
 static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
-                            int bits, uint8_t* d_syms, uint32_t* d_hist_copies, hipStream_t s) {
+                            int bits, uint8_t* d_syms, uint32_t* d_hist_parts, int* n_parts, hipStream_t s) {
     const float inv_delta = (float)(1.0 / (double)delta);
     // fp32 accumulation of C terms is off by about sqrt(C) * 2^-24 * |x - mu| / delta steps; values within
     // tau (a few times that) of a rounding boundary are decided in fp64 instead
@@ -302,7 +305,10 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
     if (ktg > 16) ktg = 16;  // bounds the staging tile so that LDS stays below 160 KB at C = 1024
     if (ktg > ncs) ktg = ncs;
     kgroups = (ncs + ktg - 1) / ktg;
-    dim3 grid((unsigned)px_tiles, (unsigned)kgroups);
+    int64_t gx = px_tiles;
+    if (gx * kgroups > kMaxHistParts) gx = kMaxHistParts / kgroups;
+    dim3 grid((unsigned)gx, (unsigned)kgroups);
+    *n_parts = (int)(gx * kgroups);
     const size_t lds = sizeof(float) * (size_t)PT * (b.Cpad + 2) + sizeof(uint32_t) * (size_t)PT * (ktg * 8 + 1);
     const bool vec = (b.C % 4) == 0;
     ProfScope prof(K_PROJECT, s);
@@ -314,7 +320,8 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
             if (ea != hipSuccess) return ea;                                                                    \
         }                                                                                                       \
         hipLaunchKernelGGL((k_project_quantize<PT, MT, LAY, VEC>), grid, dim3(256), lds, s, d_x, b.fwd, b.mu,  \
-                           b.T, P, HW, b.C, ncs, ktg, inv_delta, delta, tau, bits, d_syms, d_hist_copies);     \
+                           b.T, P, HW, b.C, ncs, ktg, inv_delta, delta, tau, bits, px_tiles, d_syms,      \
+                           d_hist_parts);                                                                       \
     } while (0)
     if (layout == FMTC_NHWC) {
         if (vec) FMTC_PQ(FMTC_NHWC, true);
@@ -328,43 +335,39 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
 }
 
 hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
-                                   float delta, int bits, uint8_t* d_syms, uint32_t* d_hist_copies,
+                                   float delta, int bits, uint8_t* d_syms, uint32_t* d_hist_parts, int* n_parts,
                                    hipStream_t s) {
     const int64_t P = N * HW;
     const int nkt = b.Cpad / 32;
-    if (nkt == 1) return launch_pq<128, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
-    if (nkt == 4) return launch_pq<64, 2>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
-    if (nkt <= 5) return launch_pq<64, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
-    return launch_pq<32, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_copies, s);
+    if (nkt == 1) return launch_pq<128, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_parts, n_parts, s);
+    if (nkt == 4) return launch_pq<64, 2>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_parts, n_parts, s);
+    if (nkt <= 5) return launch_pq<64, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_parts, n_parts, s);
+    return launch_pq<32, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_parts, n_parts, s);
 }
 
-// Histogram of given symbols (staged coder entry point).  counters[0] receives
-// the number of symbols outside the alphabet (must stay 0).
+// Histogram of given symbols (staged coder entry point): one row of partial counts per workgroup.
+// Values outside the alphabet are not counted.
 __global__ __launch_bounds__(256) void k_histogram(const uint8_t* __restrict__ syms, uint64_t V, int bits,
-                                                   uint32_t* __restrict__ hist_copies,
-                                                   uint32_t* __restrict__ counters) {
+                                                   uint32_t* __restrict__ hist_parts) {
     __shared__ uint32_t lhist[256];
     lhist[threadIdx.x] = 0u;
     __syncthreads();
     const unsigned K = 1u << bits;
-    uint32_t bad = 0;
     for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < V; i += (uint64_t)gridDim.x * 256) {
-        unsigned s = syms[i];
-        if (s < K) atomicAdd(&lhist[s], 1u);
-        else bad++;
+        unsigned sy = syms[i];
+        if (sy < K) atomicAdd(&lhist[sy], 1u);
     }
     __syncthreads();
-    uint32_t h = lhist[threadIdx.x];
-    if (h) atomicAdd(&hist_copies[(blockIdx.x % kHistCopies) * 256 + threadIdx.x], h);
-    if (bad) atomicAdd(&counters[0], bad);
+    if (threadIdx.x < K) hist_parts[(size_t)blockIdx.x * K + threadIdx.x] = lhist[threadIdx.x];
 }
 
-hipError_t launch_histogram(const uint8_t* d_syms, uint64_t V, int bits, uint32_t* d_hist_copies,
-                            uint32_t* d_counters, hipStream_t s) {
+hipError_t launch_histogram(const uint8_t* d_syms, uint64_t V, int bits, uint32_t* d_hist_parts, int* n_parts,
+                            hipStream_t s) {
     uint64_t want = (V + 256 * 16 - 1) / (256 * 16);
-    unsigned blocks = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+    unsigned blocks = (unsigned)(want < 1 ? 1 : (want > (uint64_t)kMaxHistParts ? (uint64_t)kMaxHistParts : want));
+    *n_parts = (int)blocks;
     ProfScope prof(K_HISTOGRAM, s);
-    hipLaunchKernelGGL(k_histogram, dim3(blocks), dim3(256), 0, s, d_syms, V, bits, d_hist_copies, d_counters);
+    hipLaunchKernelGGL(k_histogram, dim3(blocks), dim3(256), 0, s, d_syms, V, bits, d_hist_parts);
     return hipGetLastError();
 }
 

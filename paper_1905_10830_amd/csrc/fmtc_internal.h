@@ -13,7 +13,7 @@ constexpr int kHeaderBytes = 64;
 constexpr int kLenTableBytes = 256;
 constexpr int kSubSyms = 64;     // symbols per run; one lane codes one run
 constexpr int kMaxLen = 48;      // longest code length accepted
-constexpr int kHistCopies = 16;  // replicated global histograms (spreads atomics over L2 channels)
+constexpr int kMaxHistParts = 1024;  // per-workgroup partial histograms (no atomics, nothing to clear)
 constexpr int kLutBits = 12;     // decoder lookup table covers codes up to this length
 
 // 64-byte stream header (see fmtc.h for the field meaning).
@@ -66,8 +66,8 @@ inline bool make_geometry(int64_t P, int C, int chunk_syms, Geometry* g) {
 
 // Device workspace of the encoder.
 struct Workspace {
-    size_t off_hist_copies;  // u32 [kHistCopies][256], cleared per call
-    size_t off_counters;     // u32 [16], cleared per call
+    size_t off_hist_parts;   // u32 [kMaxHistParts][2^bits] partial histograms, one row per workgroup
+    size_t off_counters;     // u32 [16]; [1]: ticket of the run-size kernel (reset by the table kernel)
     size_t off_hist;         // u32 [256] final histogram
     size_t off_enc_table;    // u64 [256]: bit-reversed code | length << 56
     size_t off_chunk_bits;   // u32 [n_chunks]
@@ -78,8 +78,8 @@ struct Workspace {
 inline Workspace make_workspace(uint64_t V, uint32_t n_chunks) {
     Workspace w;
     size_t o = 0;
-    w.off_hist_copies = o;
-    o += sizeof(uint32_t) * kHistCopies * 256;
+    w.off_hist_parts = o;
+    o += sizeof(uint32_t) * kMaxHistParts * 256;
     w.off_counters = o;
     o += 64;
     w.off_hist = o;
@@ -108,7 +108,7 @@ struct BasisDevice {
 };
 
 // ---- optional per-kernel timing (fmtc_profile_* in fmtc.h); no-ops unless enabled ----
-enum KernelId { K_CLEAR = 0, K_PROJECT, K_HISTOGRAM, K_TABLE, K_RUN_BITS, K_OFFSETS, K_PACK, K_DECODE_TABLES, K_DECODE, K_COUNT };
+enum KernelId { K_CLEAR = 0, K_PROJECT, K_HISTOGRAM, K_TABLE, K_RUN_BITS, K_PACK, K_DECODE_TABLES, K_DECODE, K_COUNT };
 void prof_mark(int id, bool end, hipStream_t s);
 struct ProfScope {
     int id;
@@ -121,17 +121,18 @@ struct ProfScope {
 hipError_t launch_clear(uint32_t* d_words, size_t n_words, hipStream_t s);
 
 hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
-                                   float delta, int bits, uint8_t* d_syms, uint32_t* d_hist_copies,
+                                   float delta, int bits, uint8_t* d_syms, uint32_t* d_hist_parts, int* n_parts,
                                    hipStream_t s);
 
-hipError_t launch_histogram(const uint8_t* d_syms, uint64_t V, int bits, uint32_t* d_hist_copies,
-                            uint32_t* d_counters, hipStream_t s);
+hipError_t launch_histogram(const uint8_t* d_syms, uint64_t V, int bits, uint32_t* d_hist_parts, int* n_parts,
+                            hipStream_t s);
 
-hipError_t launch_huffman_table(const uint32_t* d_hist_copies, int bits, uint32_t* d_hist, uint64_t* d_enc_table,
-                                uint8_t* d_len_table, hipStream_t s);
+hipError_t launch_huffman_table(const uint32_t* d_hist_parts, int n_parts, int bits, uint32_t* d_hist,
+                                uint64_t* d_enc_table, uint8_t* d_len_table, uint32_t* d_counters, hipStream_t s);
 
 hipError_t launch_pack(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const uint64_t* d_enc_table,
-                       uint32_t* d_chunk_bits, uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s);
+                       uint32_t* d_chunk_bits, uint32_t* d_counters, uint8_t* d_stream, uint64_t* d_out_bytes,
+                       hipStream_t s);
 
 hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
                          int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, uint8_t* d_ws,

@@ -16,8 +16,8 @@ struct Profiler {
     int used[K_COUNT] = {0};
 };
 Profiler g_prof;
-const char* const kNames[K_COUNT] = {"k_clear",    "k_project_quantize", "k_histogram", "k_huffman_table",
-                                     "k_run_bits", "k_chunk_offsets",    "k_pack",      "k_decode_tables", "k_decode"};
+const char* const kNames[K_COUNT] = {"k_clear",    "k_project_quantize", "k_histogram",     "k_huffman_table",
+                                     "k_run_bits", "k_pack",             "k_decode_tables", "k_decode"};
 
 void release() {
     for (int k = 0; k < K_COUNT; k++) {
