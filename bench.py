@@ -70,7 +70,6 @@ def main():
     # ---- buffer sets ----
     cap = fmtc.encode_bound(P, C, bits)
     ws_bytes = fmtc.workspace_size(P, C, bits)
-    dws_bytes = fmtc.decode_workspace_size()
     per_set = 2 * in_bytes + cap + ws_bytes
     R = 1 if args.hot else max(2, int(np.ceil(320e6 / per_set)))
     x0 = torch.from_numpy(xs).cuda()
@@ -80,8 +79,7 @@ def main():
             x=x0.clone(), stream=torch.empty(cap, dtype=torch.uint8, device="cuda"),
             nbytes=torch.zeros(1, dtype=torch.int64, device="cuda"),
             ws=torch.empty(ws_bytes, dtype=torch.uint8, device="cuda"),
-            xhat=torch.empty_like(x0), err=torch.zeros(1, dtype=torch.int32, device="cuda"),
-            dws=torch.empty(dws_bytes, dtype=torch.uint8, device="cuda")))
+            xhat=torch.empty_like(x0), err=torch.zeros(1, dtype=torch.int32, device="cuda")))
     stream_h = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
     def enc_args(s):
@@ -90,7 +88,7 @@ def main():
 
     def dec_args(s):
         return (basis._h, s["stream"].data_ptr(), cap, s["xhat"].data_ptr(), N, C, H, W, layout, bits,
-                s["err"].data_ptr(), s["dws"].data_ptr(), dws_bytes, stream_h)
+                s["err"].data_ptr(), stream_h)
 
     ea = [enc_args(s) for s in sets]
     da = [dec_args(s) for s in sets]

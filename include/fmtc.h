@@ -109,12 +109,9 @@ float fmtc_delta(float range_A, int bits);
  * pad word per chunk and the side information. */
 size_t fmtc_encode_bound(int64_t P, int C, int bits, int chunk_syms);
 /* Bytes of device workspace fmtc_encode / fmtc_code_symbols need (symbols,
- * histograms, code table, per-chunk sizes).  256-byte aligned pointer required. */
+ * histograms, code table, running chunk offsets).  256-byte aligned pointer
+ * required; its contents need no initialisation and mean nothing between calls. */
 size_t fmtc_workspace_size(int64_t P, int C, int bits, int chunk_syms);
-/* Bytes of device workspace fmtc_decode / fmtc_decode_symbols need (the decode
- * tables of one stream; a constant of a few KB).  256-byte aligned pointer. */
-size_t fmtc_decode_workspace_size(void);
-
 /* ---- hot path ---- */
 /* Whole encoder (section 3: transform, quantizer, VLC).  Reads d_x once, writes
  * the container to d_stream_out (16-byte aligned, capacity cap >=
@@ -128,12 +125,13 @@ fmtc_status fmtc_encode(const fmtc_basis *basis, const float *d_x, int64_t N, in
 /* Whole decoder (section 3: VLD, inverse quantizer, inverse transform).
  * `bytes` is the readable size of d_stream_in (the exact stream size or any
  * larger capacity); nothing beyond it is read.  d_xhat receives N*C*H*W floats
- * in `layout`.  *d_err_flag (device u32, required) is cleared, then OR-ed with
- * FMTC_ERR_* bits if the stream fails validation; in that case d_xhat is
- * unspecified but no access leaves the given buffers. */
+ * in `layout`.  *d_err_flag (device u32, required; the caller sets it to 0
+ * before the call) is OR-ed with FMTC_ERR_* bits if the stream fails validation;
+ * in that case d_xhat is unspecified but no access leaves the given buffers.
+ * The decoder needs no workspace: every workgroup builds the decode tables from
+ * the stream's code length table in LDS. */
 fmtc_status fmtc_decode(const fmtc_basis *basis, const void *d_stream_in, size_t bytes, float *d_xhat, int64_t N,
-                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t *d_err_flag, void *d_workspace,
-                        size_t ws_bytes, void *hip_stream);
+                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t *d_err_flag, void *hip_stream);
 
 /* ---- staged entry points (the same kernels, cut at the symbol boundary) ---- */
 /* Transform + quantizer + histogram only (section 3: y = T(x-mu), Q_Delta).
@@ -150,7 +148,7 @@ fmtc_status fmtc_code_symbols(const uint8_t *d_syms, int64_t P, int C, int bits,
 
 /* Variable length decoder only: stream -> P*C symbol bytes. */
 fmtc_status fmtc_decode_symbols(const void *d_stream_in, size_t bytes, int64_t P, int C, int bits, uint8_t *d_syms,
-                                uint32_t *d_err_flag, void *d_workspace, size_t ws_bytes, void *hip_stream);
+                                uint32_t *d_err_flag, void *hip_stream);
 
 /* Parses a 64-byte header copied to the host.  Any output may be NULL.
  * stream_bytes is the total container size. */
@@ -160,15 +158,19 @@ fmtc_status fmtc_stream_info(const void *h_header, size_t header_bytes, int *bit
 
 /* ---- instrumentation (not part of the method) ----
  * fmtc_profile_enable(n > 0) creates n HIP event pairs per kernel; from then on
- * every kernel launch of the library is bracketed by events on the caller's
- * stream, up to n launches per kernel.  fmtc_profile_enable(0) turns it off and
- * frees the events.  fmtc_profile_read waits for the recorded launches of one
- * kernel (index < fmtc_profile_kernels()) and returns their average and minimum
- * duration in milliseconds.  Process-wide, not thread safe. */
+ * every kernel launch of the library carries a pair attached to its own
+ * dispatch (start and end of that kernel on the GPU), up to n launches per
+ * kernel.  fmtc_profile_enable(0) turns it off and frees the events.
+ * fmtc_profile_read waits for the recorded launches of one kernel (index <
+ * fmtc_profile_kernels()) and returns their average and minimum duration in
+ * milliseconds.  fmtc_profile_copy launches a plain device-to-device copy of
+ * `bytes` (a multiple of 16, 16-byte aligned pointers): the known traffic the
+ * hardware memory counters are scaled with.  Process-wide, not thread safe. */
 fmtc_status fmtc_profile_enable(int max_launches_per_kernel);
 int fmtc_profile_kernels(void);
 const char *fmtc_profile_name(int kernel);
 fmtc_status fmtc_profile_read(int kernel, double *avg_ms, double *min_ms, int *launches);
+fmtc_status fmtc_profile_copy(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
 
 /* Text of the last error on the calling thread ("" if none). */
 const char *fmtc_last_error(void);

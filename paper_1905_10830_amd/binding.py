@@ -17,9 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libfmtc.so")
 
 EXPORTS = [
     "fmtc_fit_basis", "fmtc_basis_import", "fmtc_basis_export", "fmtc_basis_channels", "fmtc_basis_destroy",
-    "fmtc_delta", "fmtc_encode_bound", "fmtc_workspace_size", "fmtc_decode_workspace_size", "fmtc_encode", "fmtc_decode", "fmtc_quantize",
+    "fmtc_delta", "fmtc_encode_bound", "fmtc_workspace_size", "fmtc_encode", "fmtc_decode", "fmtc_quantize",
     "fmtc_code_symbols", "fmtc_decode_symbols", "fmtc_stream_info", "fmtc_last_error",
-    "fmtc_profile_enable", "fmtc_profile_kernels", "fmtc_profile_name", "fmtc_profile_read",
+    "fmtc_profile_enable", "fmtc_profile_kernels", "fmtc_profile_name", "fmtc_profile_read", "fmtc_profile_copy",
 ]
 
 _lib = None
@@ -55,11 +55,10 @@ def load_library():
     lib.fmtc_workspace_size.argtypes = [i64, i32, i32, i32]
     lib.fmtc_workspace_size.restype = sz
     lib.fmtc_encode.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp, sz, vp]
-    lib.fmtc_decode_workspace_size.restype = sz
-    lib.fmtc_decode.argtypes = [vp, vp, sz, vp, i64, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+    lib.fmtc_decode.argtypes = [vp, vp, sz, vp, i64, i32, i32, i32, i32, i32, vp, vp]
     lib.fmtc_quantize.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.fmtc_code_symbols.argtypes = [vp, i64, i32, i32, i32, f32, vp, sz, vp, vp, sz, vp]
-    lib.fmtc_decode_symbols.argtypes = [vp, sz, i64, i32, i32, vp, vp, vp, sz, vp]
+    lib.fmtc_decode_symbols.argtypes = [vp, sz, i64, i32, i32, vp, vp, vp]
     lib.fmtc_stream_info.argtypes = [vp, sz, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i64),
                                      ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(f32),
                                      ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
@@ -69,6 +68,7 @@ def load_library():
     lib.fmtc_profile_name.restype = ctypes.c_char_p
     lib.fmtc_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                       ctypes.POINTER(i32)]
+    lib.fmtc_profile_copy.argtypes = [vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -169,10 +169,6 @@ def workspace_size(P, C, bits, chunk_syms=4096):
     return load_library().fmtc_workspace_size(P, C, bits, chunk_syms)
 
 
-def decode_workspace_size():
-    return load_library().fmtc_decode_workspace_size()
-
-
 def encode(basis, x, bits, layout=NHWC, chunk_syms=4096, stream_out=None, out_bytes=None, workspace=None):
     """Asynchronous.  -> (stream_out uint8 tensor of capacity encode_bound, out_bytes int64[1] device tensor)."""
     import torch
@@ -192,22 +188,20 @@ def encode(basis, x, bits, layout=NHWC, chunk_syms=4096, stream_out=None, out_by
     return stream_out, out_bytes
 
 
-def decode(basis, stream_in, shape, bits, layout=NHWC, xhat=None, err_flag=None, nbytes=None, workspace=None):
-    """Asynchronous.  -> (xhat fp32 tensor of `shape`, err_flag int32[1] device tensor)."""
+def decode(basis, stream_in, shape, bits, layout=NHWC, xhat=None, err_flag=None, nbytes=None):
+    """Asynchronous.  -> (xhat fp32 tensor of `shape`, err_flag int32[1] device tensor).
+    A caller-supplied err_flag must be zero on entry: the decoder only ORs bits into it."""
     import torch
 
     if xhat is None:
         xhat = torch.empty(shape, dtype=torch.float32, device=stream_in.device)
     if err_flag is None:
         err_flag = torch.zeros(1, dtype=torch.int32, device=stream_in.device)
-    if workspace is None:
-        workspace = torch.empty(decode_workspace_size(), dtype=torch.uint8, device=stream_in.device)
     n, c, h, w = _dims(xhat, layout)
     _check(load_library().fmtc_decode(basis._h, _dev(stream_in, torch.uint8),
                                       stream_in.numel() if nbytes is None else int(nbytes),
                                       _dev(xhat, torch.float32), n, c, h, w, layout, bits,
-                                      _dev(err_flag, torch.int32), _dev(workspace, torch.uint8), workspace.numel(),
-                                      _stream()))
+                                      _dev(err_flag, torch.int32), _stream()))
     return xhat, err_flag
 
 
@@ -247,7 +241,7 @@ def code_symbols(syms, C, bits, delta_value, chunk_syms=4096, stream_out=None, o
     return stream_out, out_bytes
 
 
-def decode_symbols(stream_in, P, C, bits, syms=None, err_flag=None, nbytes=None, workspace=None):
+def decode_symbols(stream_in, P, C, bits, syms=None, err_flag=None, nbytes=None):
     """Asynchronous.  -> (symbols uint8 [P, C], err_flag int32[1])."""
     import torch
 
@@ -255,12 +249,9 @@ def decode_symbols(stream_in, P, C, bits, syms=None, err_flag=None, nbytes=None,
         syms = torch.empty((P, C), dtype=torch.uint8, device=stream_in.device)
     if err_flag is None:
         err_flag = torch.zeros(1, dtype=torch.int32, device=stream_in.device)
-    if workspace is None:
-        workspace = torch.empty(decode_workspace_size(), dtype=torch.uint8, device=stream_in.device)
     _check(load_library().fmtc_decode_symbols(_dev(stream_in, torch.uint8),
                                               stream_in.numel() if nbytes is None else int(nbytes), P, C, bits,
-                                              _dev(syms, torch.uint8), _dev(err_flag, torch.int32),
-                                              _dev(workspace, torch.uint8), workspace.numel(), _stream()))
+                                              _dev(syms, torch.uint8), _dev(err_flag, torch.int32), _stream()))
     return syms, err_flag
 
 
@@ -280,6 +271,13 @@ def stream_info(header_bytes):
 
 def profile_enable(max_launches_per_kernel):
     _check(load_library().fmtc_profile_enable(int(max_launches_per_kernel)))
+
+
+def profile_copy(dst, src):
+    """Yardstick copy of src into dst (uint8 device tensors of equal size, a multiple of 16 bytes)."""
+    import torch
+
+    _check(load_library().fmtc_profile_copy(_dev(dst, torch.uint8), _dev(src, torch.uint8), src.numel(), _stream()))
 
 
 def profile_read():

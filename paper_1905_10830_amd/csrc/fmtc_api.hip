@@ -15,6 +15,7 @@ struct fmtc_basis {
     std::vector<float> T, mu;
     std::vector<double> eig;
     float *d_fwd = nullptr, *d_inv = nullptr, *d_invf = nullptr, *d_mu = nullptr, *d_T = nullptr;
+    float *d_inv4 = nullptr, *d_fwd4 = nullptr;
     int device = 0;
 };
 
@@ -63,12 +64,34 @@ void pack_operand(const std::vector<float>& T, int C, int Cpad, bool transpose, 
                 }
 }
 
+// Operand order of the narrow-tensor kernels: out[((tile * NJ + j) * 64 + lane) * 4 + i] =
+// M[tile*32 + row(lane%32)][8j + 4*(lane/32) + i], NJ = Cpad / 8, zero outside CxC.  With permute_rows the rows
+// of a tile are taken in the order that leaves a lane of the matrix instruction with 16 consecutive rows.
+void pack_operand4(const std::vector<float>& T, int C, int Cpad, bool transpose, bool permute_rows,
+                   std::vector<float>* out) {
+    const int nt_count = Cpad / 32, NJ = Cpad / 8;
+    out->assign((size_t)Cpad * Cpad, 0.f);
+    for (int nt = 0; nt < nt_count; nt++)
+        for (int j = 0; j < NJ; j++)
+            for (int lane = 0; lane < 64; lane++)
+                for (int i = 0; i < 4; i++) {
+                    const int r = lane % 32, half = lane / 32;
+                    const int row = nt * 32 + (permute_rows ? 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3) : r);
+                    const int col = 8 * j + 4 * half + i;
+                    float v = 0.f;
+                    if (row < C && col < C) v = transpose ? T[(size_t)col * C + row] : T[(size_t)row * C + col];
+                    (*out)[(((size_t)nt * NJ + j) * 64 + lane) * 4 + i] = v;
+                }
+}
+
 fmtc_status upload_basis(fmtc_basis* b) {
     const int C = b->C, Cpad = b->Cpad;
-    std::vector<float> fwd, inv, invf, mu(Cpad, 0.f);
+    std::vector<float> fwd, inv, invf, inv4, fwd4, mu(Cpad, 0.f);
     pack_operand(b->T, C, Cpad, false, false, &fwd);
     pack_operand(b->T, C, Cpad, true, true, &inv);
     pack_operand(b->T, C, Cpad, true, false, &invf);
+    pack_operand4(b->T, C, Cpad, true, false, &inv4);
+    pack_operand4(b->T, C, Cpad, false, true, &fwd4);
     for (int c = 0; c < C; c++) mu[c] = b->mu[c];
     hipError_t e;
     const size_t mat = sizeof(float) * (size_t)Cpad * Cpad;
@@ -81,6 +104,10 @@ fmtc_status upload_basis(fmtc_basis* b) {
     if ((e = hipMalloc((void**)&b->d_invf, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
     if ((e = hipMemcpy(b->d_invf, invf.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     if ((e = hipMemcpy(b->d_mu, mu.data(), sizeof(float) * Cpad, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
+    if ((e = hipMalloc((void**)&b->d_inv4, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    if ((e = hipMemcpy(b->d_inv4, inv4.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
+    if ((e = hipMalloc((void**)&b->d_fwd4, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    if ((e = hipMemcpy(b->d_fwd4, fwd4.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     if ((e = hipMalloc((void**)&b->d_T, sizeof(float) * (size_t)C * C)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
     if ((e = hipMemcpy(b->d_T, b->T.data(), sizeof(float) * (size_t)C * C, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     return FMTC_OK;
@@ -93,6 +120,8 @@ BasisDevice device_view(const fmtc_basis* b) {
     v.fwd = b->d_fwd;
     v.inv = b->d_inv;
     v.invf = b->d_invf;
+    v.inv4 = b->d_inv4;
+    v.fwd4 = b->d_fwd4;
     v.mu = b->d_mu;
     v.T = b->d_T;
     return v;
@@ -178,21 +207,21 @@ size_t bound_from(const EncodePlan& pl, int bits) {
     return pl.g.off_payload + 4 * (size_t)((pl.V * (uint64_t)bits + 31) / 32 + pl.g.n_chunks);
 }
 
-// partial histograms -> table -> run sizes and chunk offsets -> payload
-fmtc_status run_coder(const uint8_t* d_syms, const EncodePlan& pl, int n_parts, int bits, float delta, uint8_t* ws,
-                      uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s) {
-    hipError_t e;
-    uint32_t* hist_parts = reinterpret_cast<uint32_t*>(ws + pl.ws.off_hist_parts);
-    uint32_t* counters = reinterpret_cast<uint32_t*>(ws + pl.ws.off_counters);
-    uint32_t* hist = reinterpret_cast<uint32_t*>(ws + pl.ws.off_hist);
+CoderScratch coder_scratch(uint8_t* ws, const EncodePlan& pl) {
+    CoderScratch cs;
+    cs.hist_parts = reinterpret_cast<uint32_t*>(ws + pl.ws.off_hist_parts);
+    cs.ctrl = reinterpret_cast<CoderCtrl*>(ws + pl.ws.off_ctrl);
+    cs.lookback = reinterpret_cast<unsigned long long*>(ws + pl.ws.off_lookback);
+    cs.n_groups = pack_groups(pl.g.n_chunks);
+    return cs;
+}
+
+// partial histograms -> table -> run sizes, chunk offsets and payload
+fmtc_status run_coder(const uint8_t* d_syms, const EncodePlan& pl, const CoderScratch& cs, int n_parts, int bits,
+                      float delta, uint8_t* ws, uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s) {
     uint64_t* enc_table = reinterpret_cast<uint64_t*>(ws + pl.ws.off_enc_table);
-    uint32_t* chunk_bits = reinterpret_cast<uint32_t*>(ws + pl.ws.off_chunk_bits);
-    if ((e = launch_huffman_table(hist_parts, n_parts, bits, hist, enc_table, d_stream + kHeaderBytes, counters,
-                                  s)) != hipSuccess)
-        return hip_fail(e, "huffman table kernel");
-    if ((e = launch_pack(d_syms, pl.g, bits, delta, enc_table, chunk_bits, counters, d_stream, d_out_bytes, s)) !=
-        hipSuccess)
-        return hip_fail(e, "pack kernels");
+    hipError_t e = launch_coder(d_syms, pl.g, bits, delta, cs, n_parts, enc_table, d_stream, d_out_bytes, s);
+    if (e != hipSuccess) return hip_fail(e, "coder kernels");
     return FMTC_OK;
 }
 
@@ -214,6 +243,8 @@ void fmtc_basis_destroy(fmtc_basis* b) {
     if (b->d_fwd) (void)hipFree(b->d_fwd);
     if (b->d_inv) (void)hipFree(b->d_inv);
     if (b->d_invf) (void)hipFree(b->d_invf);
+    if (b->d_inv4) (void)hipFree(b->d_inv4);
+    if (b->d_fwd4) (void)hipFree(b->d_fwd4);
     if (b->d_mu) (void)hipFree(b->d_mu);
     if (b->d_T) (void)hipFree(b->d_T);
     delete b;
@@ -268,7 +299,7 @@ fmtc_status fmtc_fit_basis(const float* d_x, int64_t N, int C, int H, int W, fmt
     float *d_t0 = nullptr, *d_mu = nullptr;
     fmtc_basis* b = nullptr;
     do {
-        if ((e = launch_clear(reinterpret_cast<uint32_t*>(d_stat), 2 * n_stat, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
+        if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(d_stat), 2 * n_stat, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
         if ((e = launch_fit_moments(d_x, N, C, HW, layout, d_stat, d_stat + C, s)) != hipSuccess) { st = hip_fail(e, "fit moments"); break; }
         if ((e = hipMemcpyAsync(stat.data(), d_stat, sizeof(double) * n_stat, hipMemcpyDeviceToHost, s)) != hipSuccess) { st = hip_fail(e, "copy moments"); break; }
         if ((e = hipStreamSynchronize(s)) != hipSuccess) { st = hip_fail(e, "fit sync"); break; }
@@ -311,7 +342,7 @@ fmtc_status fmtc_fit_basis(const float* d_x, int64_t N, int C, int H, int W, fmt
         if ((e = hipMemcpyAsync(d_t0, b->T.data(), sizeof(float) * C, hipMemcpyHostToDevice, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
         if ((e = hipMemcpyAsync(d_mu, b->mu.data(), sizeof(float) * C, hipMemcpyHostToDevice, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
         double* d_amax = d_stat + (n_stat - 1);
-        if ((e = launch_clear(reinterpret_cast<uint32_t*>(d_amax), 2, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
+        if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(d_amax), 2, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
         if ((e = launch_fit_range(d_x, N, C, HW, layout, d_t0, d_mu, d_amax, s)) != hipSuccess) { st = hip_fail(e, "fit range"); break; }
         double amax = 0.0;
         if ((e = hipMemcpyAsync(&amax, d_amax, sizeof(double), hipMemcpyDeviceToHost, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
@@ -350,23 +381,20 @@ fmtc_status fmtc_quantize(const fmtc_basis* basis, const float* d_x, int64_t N, 
     if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
     if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
     if (!aligned(d_x, 16) || !aligned(d_syms, 16) || !aligned(d_workspace, 256)) return fail(FMTC_EINVAL, "misaligned pointer");
-    const Workspace ws = make_workspace(0, 0);
-    if (ws_bytes < ws.off_chunk_bits) return fail(FMTC_EBUFSIZE, "workspace too small");
+    EncodePlan pl;
+    fmtc_status st = plan_encode(N * (int64_t)H * W, C, bits, 4096, &pl);
+    if (st != FMTC_OK) return st;
+    if (ws_bytes < pl.ws.off_syms) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, pl.ws.off_syms);
     hipStream_t s = (hipStream_t)hip_stream;
     uint8_t* w = static_cast<uint8_t*>(d_workspace);
-    uint32_t* hist_parts = reinterpret_cast<uint32_t*>(w + ws.off_hist_parts);
+    const CoderScratch cs = coder_scratch(w, pl);
     hipError_t e;
     int n_parts = 0;
     const float delta = fmtc_delta(basis->range_A, bits);
-    if ((e = launch_project_quantize(device_view(basis), d_x, N, (int64_t)H * W, layout, delta, bits, d_syms, hist_parts, &n_parts, s)) != hipSuccess)
+    if ((e = launch_project_quantize(device_view(basis), d_x, N, (int64_t)H * W, layout, delta, bits, d_syms, cs, &n_parts, s)) != hipSuccess)
         return hip_fail(e, "project/quantize kernel");
-    if (d_hist) {
-        // sum of the partial histograms: the table kernel does it; its other outputs go to the workspace
-        if ((e = launch_huffman_table(hist_parts, n_parts, bits, d_hist, reinterpret_cast<uint64_t*>(w + ws.off_enc_table),
-                                      w + ws.off_hist /* length table scratch */,
-                                      reinterpret_cast<uint32_t*>(w + ws.off_counters), s)) != hipSuccess)
-            return hip_fail(e, "histogram reduction");
-    }
+    if (d_hist && (e = launch_histogram_sum(cs.hist_parts, n_parts, bits, d_hist, s)) != hipSuccess)
+        return hip_fail(e, "histogram reduction");
     return FMTC_OK;
 }
 
@@ -386,14 +414,14 @@ fmtc_status fmtc_encode(const fmtc_basis* basis, const float* d_x, int64_t N, in
     if (cap < bound_from(pl, bits)) return fail(FMTC_EBUFSIZE, "stream capacity too small: %zu < %zu", cap, bound_from(pl, bits));
     hipStream_t s = (hipStream_t)hip_stream;
     uint8_t* w = static_cast<uint8_t*>(d_workspace);
-    uint32_t* hist_parts = reinterpret_cast<uint32_t*>(w + pl.ws.off_hist_parts);
+    const CoderScratch cs = coder_scratch(w, pl);
     uint8_t* syms = w + pl.ws.off_syms;
     hipError_t e;
     int n_parts = 0;
     const float delta = fmtc_delta(basis->range_A, bits);
-    if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, syms, hist_parts, &n_parts, s)) != hipSuccess)
+    if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, syms, cs, &n_parts, s)) != hipSuccess)
         return hip_fail(e, "project/quantize kernel");
-    return run_coder(syms, pl, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
+    return run_coder(syms, pl, cs, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
 }
 
 fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits, int chunk_syms, float delta,
@@ -410,19 +438,17 @@ fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits,
     if (cap < bound_from(pl, bits)) return fail(FMTC_EBUFSIZE, "stream capacity too small: %zu < %zu", cap, bound_from(pl, bits));
     hipStream_t s = (hipStream_t)hip_stream;
     uint8_t* w = static_cast<uint8_t*>(d_workspace);
-    uint32_t* hist_parts = reinterpret_cast<uint32_t*>(w + pl.ws.off_hist_parts);
+    const CoderScratch cs = coder_scratch(w, pl);
     hipError_t e;
     int n_parts = 0;
-    if ((e = launch_histogram(d_syms, pl.V, bits, hist_parts, &n_parts, s)) != hipSuccess) return hip_fail(e, "histogram kernel");
-    return run_coder(d_syms, pl, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
+    if ((e = launch_histogram(d_syms, pl.V, bits, cs, &n_parts, s)) != hipSuccess) return hip_fail(e, "histogram kernel");
+    return run_coder(d_syms, pl, cs, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
 }
 
 static fmtc_status decode_common(const fmtc_basis* basis, const void* d_stream_in, size_t bytes, int64_t P, int C,
                                  int64_t HW, int layout, int bits, float* d_xhat, uint8_t* d_syms,
-                                 uint32_t* d_err_flag, void* d_workspace, size_t ws_bytes, void* hip_stream) {
-    if (!d_stream_in || !d_err_flag || !d_workspace) return fail(FMTC_EINVAL, "NULL argument");
-    if (!aligned(d_workspace, 256)) return fail(FMTC_EINVAL, "misaligned pointer");
-    if (ws_bytes < decode_workspace_bytes()) return fail(FMTC_EBUFSIZE, "decode workspace too small: %zu < %zu", ws_bytes, decode_workspace_bytes());
+                                 uint32_t* d_err_flag, void* hip_stream) {
+    if (!d_stream_in || !d_err_flag) return fail(FMTC_EINVAL, "NULL argument");
     if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
     if (!aligned(d_stream_in, 16) || !aligned(d_err_flag, 4) || !aligned(d_xhat, 16) || !aligned(d_syms, 16))
         return fail(FMTC_EINVAL, "misaligned pointer");
@@ -431,32 +457,28 @@ static fmtc_status decode_common(const fmtc_basis* basis, const void* d_stream_i
     if ((long double)P * C >= 4294967296.0L) return fail(FMTC_EINVAL, "tensor too large: V must be < 2^32");
     hipStream_t s = (hipStream_t)hip_stream;
     hipError_t e;
-    if ((e = launch_clear(d_err_flag, 1, s)) != hipSuccess) return hip_fail(e, "clear");
     BasisDevice view;
     if (basis) view = device_view(basis);
     if ((e = launch_decode(basis ? &view : nullptr, static_cast<const uint8_t*>(d_stream_in), bytes, g, bits, HW,
-                           layout, d_xhat, d_syms, d_err_flag, static_cast<uint8_t*>(d_workspace), s)) != hipSuccess)
+                           layout, d_xhat, d_syms, d_err_flag, s)) != hipSuccess)
         return hip_fail(e, "decode kernel");
     return FMTC_OK;
 }
 
-size_t fmtc_decode_workspace_size(void) { return decode_workspace_bytes(); }
-
 fmtc_status fmtc_decode(const fmtc_basis* basis, const void* d_stream_in, size_t bytes, float* d_xhat, int64_t N,
-                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t* d_err_flag, void* d_workspace,
-                        size_t ws_bytes, void* hip_stream) {
+                        int C, int H, int W, fmtc_layout layout, int bits, uint32_t* d_err_flag, void* hip_stream) {
     if (!basis || !d_xhat) return fail(FMTC_EINVAL, "NULL argument");
     if (!dims_ok(N, C, H, W) || basis->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", basis->C, C);
     if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
     const int64_t HW = (int64_t)H * W;
-    return decode_common(basis, d_stream_in, bytes, N * HW, C, HW, layout, bits, d_xhat, nullptr, d_err_flag, d_workspace, ws_bytes, hip_stream);
+    return decode_common(basis, d_stream_in, bytes, N * HW, C, HW, layout, bits, d_xhat, nullptr, d_err_flag, hip_stream);
 }
 
 fmtc_status fmtc_decode_symbols(const void* d_stream_in, size_t bytes, int64_t P, int C, int bits, uint8_t* d_syms,
-                                uint32_t* d_err_flag, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+                                uint32_t* d_err_flag, void* hip_stream) {
     if (!d_syms) return fail(FMTC_EINVAL, "NULL argument");
     if (P < 1 || C < 1 || C > 1024) return fail(FMTC_EINVAL, "bad dims");
-    return decode_common(nullptr, d_stream_in, bytes, P, C, 1, FMTC_NHWC, bits, nullptr, d_syms, d_err_flag, d_workspace, ws_bytes, hip_stream);
+    return decode_common(nullptr, d_stream_in, bytes, P, C, 1, FMTC_NHWC, bits, nullptr, d_syms, d_err_flag, hip_stream);
 }
 
 fmtc_status fmtc_stream_info(const void* h_header, size_t header_bytes, int* bits, int* C, int64_t* P,

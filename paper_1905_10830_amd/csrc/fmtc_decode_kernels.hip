@@ -1,38 +1,29 @@
 // Decoder (paper section 3: variable length decoder, inverse quantizer, inverse
 // transform; section 3.1 "Implementation": levels scaled back to the transform
-// domain, then the inverse PCA).  One fused kernel:
-//   1. a one-workgroup kernel validates the header and the code length table and
-//      builds the canonical decode tables and a 2^12-entry lookup table once; every
-//      workgroup of the main kernel copies them from the workspace into LDS;
-//   2. per tile of G chunks: one wavefront per chunk, one lane per run of 64
-//      symbols (bit offset = prefix sum of the stored run sizes) decodes into an
-//      LDS symbol tile;
+// domain, then the inverse PCA).  One kernel per call:
+//   1. every workgroup checks the header and the code length table and builds the
+//      canonical decode tables and a 2^11-entry two-symbol lookup table in LDS;
+//   2. one wavefront per chunk, one lane per run of 64 symbols (bit offset = prefix
+//      sum of the stored run sizes) decodes into an LDS symbol tile;
 //   3. x_hat = T^T (Delta q) + mu on the fp32 matrix cores
-//      (v_mfma_f32_32x32x2_f32): symbols are converted on the fly from LDS, the
-//      basis comes pre-packed in operand order from global memory (L2 resident).
+//      (v_mfma_f32_32x32x2_f32).  Narrow tensors (up to 128 channels): the wavefront
+//      that decoded a chunk also transforms it, the basis sits in LDS in operand
+//      order and no workgroup barrier is needed after the tables.  Wide tensors: a
+//      tile of several chunks per workgroup, the basis streamed from L2.
 // Nothing outside [stream, stream + bytes) is read whatever the stream holds.
+#include "fmtc_device.h"
 #include "fmtc_internal.h"
 
 namespace fmtc {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ uint32_t dec_wave_exclusive_scan(uint32_t v, int lane) {
-    uint32_t incl = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        uint32_t t = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += t;
-    }
-    return incl - v;
-}
-
 // byte address of symbol n of the tile: every run of 64 symbols is followed by 4
 // pad bytes so that the 64 lanes of a decoding wavefront hit different banks
 __device__ __forceinline__ uint32_t sym_addr(uint32_t n) { return n + 4u * (n >> 6); }
 
 
-// Decode tables: built once per stream by k_decode_tables, copied to LDS by every workgroup.
+// Decode tables, in LDS, built by every workgroup from the code length table of the stream.
 struct DecTables {
     uint32_t cnt_len[64];     // number of codes of each length
     uint32_t first_rank[64];  // rank (in (length, symbol) order) of the first code of each length
@@ -43,9 +34,108 @@ struct DecTables {
     // next kLutBits stream bits -> up to two symbols: sym0 | sym1 << 8 | (len0 + len1) << 16 | len0 << 21 | n << 26,
     // n = number of whole codes found in those bits (0: the first code is longer than kLutBits)
     uint32_t lut[1 << kLutBits];
+    // scratch of the construction
+    uint32_t wave_len_count[4][64];
+    uint32_t lut_limit[kLutBits + 1];  // limit[] in a kLutBits-bit frame
+    uint32_t n_used, bad_len, ok, max_len;
 };
-static_assert(sizeof(DecTables) % 16 == 0, "copied with 16-byte loads");
-constexpr size_t kDecWorkspaceBytes = 64 + sizeof(DecTables);  // word 0: 1 once the tables are valid
+
+// All THREADS threads of the workgroup call this (THREADS a multiple of 256).  Returns false (for every thread)
+// unless the lengths form a complete prefix code (Kraft sum exactly 1), or the single one-bit code of a
+// one-symbol tensor.
+template <int THREADS>
+__device__ __forceinline__ bool build_decode_tables(DecTables& T, const uint8_t* __restrict__ len_table, int bits) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int K = 1 << bits;
+    int my_len = 0;
+    if (tid < 256) my_len = len_table[tid];
+    if (tid < 64) T.cnt_len[tid] = 0u;
+    if (tid < 256) T.wave_len_count[tid >> 6][tid & 63] = 0u;
+    if (tid == 0) { T.n_used = 0u; T.bad_len = 0u; }
+    __syncthreads();
+    if (tid < 256) {
+        if (my_len > kMaxLen || (tid >= K && my_len != 0)) {
+            atomicAdd(&T.bad_len, 1u);
+            my_len = 0;
+        } else if (my_len) {
+            atomicAdd(&T.cnt_len[my_len], 1u);
+            atomicAdd(&T.n_used, 1u);
+        }
+    }
+    __syncthreads();
+    if (tid < 64) {
+        // running sums over the lengths: count(j) * 2^(48-j) gives the first code of each length (shifted down to
+        // its own width), the Kraft sum and the "first value that is no code of this length" limits
+        const bool in = tid >= 1 && tid <= kMaxLen;
+        const uint32_t c = in ? T.cnt_len[tid] : 0u;
+        const unsigned long long w = (unsigned long long)c << (in ? kMaxLen - tid : 0);
+        const unsigned long long incl = wave_inclusive_scan64(w, lane);
+        const uint32_t rank = wave_exclusive_scan(c, lane);
+        const unsigned long long kraft = __shfl(incl, 63, 64);
+        T.first_code[tid] = in ? ((incl - w) >> (kMaxLen - tid)) : 0ull;
+        T.first_rank[tid] = in ? rank : 0u;
+        T.limit[tid] = (in && tid <= 32) ? (incl >> (kMaxLen - 32)) : ~0ull;
+        if (tid >= 1 && tid <= kLutBits) T.lut_limit[tid] = (uint32_t)(incl >> (kMaxLen - kLutBits));
+        if (!in) T.cnt_len[tid] = 0u;
+        const unsigned long long used = __ballot(c != 0);
+        if (tid == 0) {
+            const uint32_t n = T.n_used;
+            T.max_len = used ? (uint32_t)(63 - __clzll((long long)used)) : 0u;
+            T.ok = (T.bad_len == 0 && n >= 1 && (n == 1 ? T.cnt_len[1] == 1 : kraft == (1ull << kMaxLen))) ? 1u : 0u;
+        }
+    }
+    __syncthreads();
+    if (!T.ok) return false;
+    // symbols of equal length are numbered in symbol order
+    uint32_t before = 0;
+    if (tid < 256) {
+        const uint32_t max_len = T.max_len;
+        for (uint32_t q = 1; q <= max_len; q++) {
+            const unsigned long long m = __ballot(my_len == (int)q);
+            if (my_len == (int)q) before = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            if (lane == 0 && m) T.wave_len_count[tid >> 6][q] = (uint32_t)__popcll(m);
+        }
+    }
+    __syncthreads();
+    if (tid < 256) {
+        if (my_len) {
+            for (int q = 0; q < (tid >> 6); q++) before += T.wave_len_count[q][my_len];
+            T.sorted_sym[T.first_rank[my_len] + before] = (uint16_t)tid;
+        }
+        if ((uint32_t)tid >= T.n_used) T.sorted_sym[tid] = 0;  // ranks past the last code stay harmless
+    }
+    __syncthreads();
+    {
+        uint32_t lim[kLutBits + 1];
+#pragma unroll
+        for (int l = 1; l <= kLutBits; l++) lim[l] = T.lut_limit[l];
+        // first whole code in the top bits of v (kLutBits-bit frame, first stream bit on top) that is at most
+        // maxbits long: its length (0 if none) and symbol
+        auto first_code_in = [&](uint32_t v, uint32_t maxbits, uint32_t* sym) -> uint32_t {
+            uint32_t len = 1;
+#pragma unroll
+            for (int l = 1; l < kLutBits; l++) len += (v >= lim[l]) ? 1u : 0u;
+            if (v >= lim[kLutBits] || len > maxbits) return 0u;
+            const uint32_t off = (v >> (kLutBits - len)) - (uint32_t)T.first_code[len];
+            *sym = T.sorted_sym[(T.first_rank[len] + off) & 255u];
+            return len;
+        };
+        for (int idx = tid; idx < (1 << kLutBits); idx += THREADS) {
+            const uint32_t v = __brev((uint32_t)idx) >> (32 - kLutBits);
+            uint32_t s0 = 0, s1 = 0, e = 0;
+            const uint32_t len0 = first_code_in(v, kLutBits, &s0);
+            if (len0) {
+                const uint32_t rest = (v << len0) & ((1u << kLutBits) - 1u);
+                const uint32_t len1 = (len0 < (uint32_t)kLutBits) ? first_code_in(rest, kLutBits - len0, &s1) : 0u;
+                if (len1) e = s0 | (s1 << 8) | ((len0 + len1) << 16) | (len0 << 21) | (2u << 26);
+                else e = s0 | (len0 << 16) | (len0 << 21) | (1u << 26);
+            }
+            T.lut[idx] = e;
+        }
+    }
+    __syncthreads();
+    return true;
+}
 
 // Decodes the `cnt` symbols of one run (one lane) starting at bit `start` of a chunk into the symbol tile.
 // STAGED: the chunk's words are in LDS (`pw`, two zero words behind them); otherwise they are read from
@@ -170,14 +260,14 @@ struct DecodeParams {
     int ncs;           // Cpad / 32
     const float* Bpk;  // inverse operand, packed (slot order of the byte tile)
     const float* Bpf;  // inverse operand, packed (slot order of the float tile)
+    const float* Bp4;  // inverse operand, packed for the one-wavefront-per-chunk kernel
     const float* mu;   // [Cpad]
     float* xhat;       // NULL in symbols-only mode
     uint8_t* syms_out; // non-NULL in symbols-only mode
     uint32_t* err;
-    uint8_t* ws;       // kDecWorkspaceBytes: valid word + DecTables
 };
 
-// Header checks shared by the two kernels.  Returns false unless the header matches the arguments and the
+// Header checks.  Returns false unless the header matches the arguments and the
 // buffer holds every section it announces.
 struct StreamView {
     uint32_t n_chunks, spc, chunk_syms, payload_words;
@@ -216,116 +306,12 @@ __device__ __forceinline__ bool open_stream(const DecodeParams& p, StreamView* v
     return true;
 }
 
-// One workgroup of 1024 threads: stream checks and decode tables, written to the workspace.
-__global__ __launch_bounds__(1024) void k_decode_tables(DecodeParams p) {
-    __shared__ uint8_t len_s[256];
-    __shared__ uint32_t cnt_len[kMaxLen + 2];
-    __shared__ uint32_t first_rank[kMaxLen + 2];
-    __shared__ uint64_t first_code[kMaxLen + 2];
-    __shared__ uint16_t sorted_sym[256];
-    __shared__ unsigned long long kraft;
-    __shared__ uint32_t n_used, bad_len;
-    const int tid = threadIdx.x;
-    const int K = 1 << p.bits;
-    uint32_t* valid = reinterpret_cast<uint32_t*>(p.ws);
-    DecTables* out = reinterpret_cast<DecTables*>(p.ws + 64);
-    StreamView v;
-    if (!open_stream(p, &v)) {
-        if (tid == 0) { atomicOr(p.err, FMTC_ERR_HEADER); *valid = 0u; }
-        return;
-    }
-    if (tid <= kMaxLen + 1) cnt_len[tid] = 0;
-    if (tid == 0) { kraft = 0ull; n_used = 0; bad_len = 0; }
-    __syncthreads();
-    int my_len = 0;
-    if (tid < 256) {
-        my_len = p.stream[kHeaderBytes + tid];
-        len_s[tid] = (uint8_t)my_len;
-        if (my_len > kMaxLen || (tid >= K && my_len != 0)) atomicAdd(&bad_len, 1u);
-        else if (my_len) {
-            atomicAdd(&cnt_len[my_len], 1u);
-            atomicAdd(&kraft, 1ull << (kMaxLen - my_len));
-            atomicAdd(&n_used, 1u);
-        }
-    }
-    __syncthreads();
-    // a complete prefix code (Kraft sum exactly 1), or the single one-bit code of a one-symbol tensor
-    const bool table_ok = bad_len == 0 && n_used >= 1 &&
-                          (n_used == 1 ? cnt_len[1] == 1 : kraft == (1ull << kMaxLen));
-    if (!table_ok) {
-        if (tid == 0) { atomicOr(p.err, FMTC_ERR_TABLE); *valid = 0u; }
-        return;
-    }
-    if (tid >= 1 && tid <= kMaxLen) {
-        // first code and first rank of every length: code(l) = sum_{j<l} count(j) << (l-j)
-        uint64_t code = 0;
-        uint32_t rank = 0;
-        for (int j = 1; j < tid; j++) {
-            uint32_t c = cnt_len[j];
-            code += (uint64_t)c << (tid - j);
-            rank += c;
-        }
-        first_code[tid] = code;
-        first_rank[tid] = rank;
-    }
-    __syncthreads();
-    if (my_len) {
-        int before = 0;
-        for (int t = 0; t < tid; t++) before += (len_s[t] == my_len) ? 1 : 0;
-        sorted_sym[first_rank[my_len] + before] = (uint16_t)tid;
-    }
-    __syncthreads();
-    if (tid < 64) {
-        const bool in = tid >= 1 && tid <= kMaxLen;
-        out->cnt_len[tid] = in ? cnt_len[tid] : 0u;
-        out->first_rank[tid] = in ? first_rank[tid] : 0u;
-        out->first_code[tid] = in ? first_code[tid] : 0ull;
-        out->limit[tid] = (in && tid <= 32) ? ((first_code[tid] + cnt_len[tid]) << (32 - tid)) : ~0ull;
-    }
-    if (tid < 256) out->sorted_sym[tid] = (tid < (int)n_used) ? sorted_sym[tid] : (uint16_t)0;
-    {
-        uint32_t fc[kLutBits + 1], cn[kLutBits + 1], fr[kLutBits + 1];
-#pragma unroll
-        for (int l = 1; l <= kLutBits; l++) {
-            fc[l] = (uint32_t)first_code[l];
-            cn[l] = cnt_len[l];
-            fr[l] = first_rank[l];
-        }
-        // first whole code in the low `maxbits` bits of v (stream order): its length and rank, 0 if none
-        auto first_code_in = [&](uint32_t v, int maxbits, uint32_t* rank) -> uint32_t {
-            uint32_t code = 0, hit_len = 0, hit_rank = 0;
-#pragma unroll
-            for (int l = 1; l <= kLutBits; l++) {
-                code = (code << 1) | ((v >> (l - 1)) & 1u);
-                bool hit = hit_len == 0 && l <= maxbits && code >= fc[l] && code - fc[l] < cn[l];
-                hit_rank = hit ? fr[l] + code - fc[l] : hit_rank;
-                hit_len = hit ? (uint32_t)l : hit_len;
-            }
-            *rank = hit_rank;
-            return hit_len;
-        };
-        for (int idx = tid; idx < (1 << kLutBits); idx += 1024) {
-            uint32_t r0 = 0, r1 = 0, e = 0;
-            const uint32_t len0 = first_code_in((uint32_t)idx, kLutBits, &r0);
-            if (len0) {
-                const uint32_t len1 = first_code_in((uint32_t)idx >> len0, kLutBits - (int)len0, &r1);
-                const uint32_t s0 = sorted_sym[r0];
-                if (len1) e = s0 | ((uint32_t)sorted_sym[r1] << 8) | ((len0 + len1) << 16) | (len0 << 21) | (2u << 26);
-                else e = s0 | (len0 << 16) | (len0 << 21) | (1u << 26);
-            }
-            out->lut[idx] = e;
-        }
-    }
-    if (tid == 0) *valid = 1u;
-}
-
-
 constexpr int kPayWords = 1022;  // LDS copy of a chunk's payload: up to ~8 bits/symbol; larger chunks read global memory
 
 // FTILE: the tile holds dequantized coefficients as floats, [pixel][coefficient] with row stride Cpad + 2 (the
 // matrix operand then comes straight from LDS, as in the encoder); otherwise symbol bytes, converted on the fly.
 template <int MT, int LAYOUT, bool ALIGNED4, bool FTILE>
-__global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
+__global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
     __shared__ __align__(16) DecTables T;
     __shared__ uint32_t pay[4][kPayWords + 2];  // per wavefront: the chunk's payload words
     extern __shared__ __align__(16) uint8_t symtile[];
@@ -335,13 +321,14 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
     const int half = lane >> 5, l32 = lane & 31;
     const int C = p.C;
 
-    // the table kernel has checked the stream; an invalid one leaves the flag word at 0
     StreamView sv;
-    if (*reinterpret_cast<const uint32_t*>(p.ws) != 1u || !open_stream(p, &sv)) return;
-    {
-        const uint4* src = reinterpret_cast<const uint4*>(p.ws + 64);
-        uint4* dst = reinterpret_cast<uint4*>(&T);
-        for (int i = tid; i < (int)(sizeof(DecTables) / 16); i += 256) dst[i] = src[i];
+    if (!open_stream(p, &sv)) {
+        if (tid == 0) atomicOr(p.err, FMTC_ERR_HEADER);
+        return;
+    }
+    if (!build_decode_tables<256>(T, p.stream + kHeaderBytes, p.bits)) {
+        if (tid == 0) atomicOr(p.err, FMTC_ERR_TABLE);
+        return;
     }
     const uint32_t n_chunks = sv.n_chunks, spc = sv.spc, chunk_syms = sv.chunk_syms;
     const uint32_t payload_words = sv.payload_words;
@@ -383,7 +370,7 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
                 w0 = 0; w1 = 0;
             }
             const uint32_t run_bits = ((uint32_t)lane < spc) ? sub_bits[(size_t)ch * spc + lane] : 0u;
-            const uint32_t start = dec_wave_exclusive_scan(run_bits, lane);
+            const uint32_t start = wave_exclusive_scan(run_bits, lane);
             const uint32_t r0 = (uint32_t)lane * kSubSyms;
             const uint32_t cnt = (r0 < clen) ? ((clen - r0 < (uint32_t)kSubSyms) ? clen - r0 : (uint32_t)kSubSyms) : 0u;
             const uint32_t nwords = w1 - w0;
@@ -591,13 +578,222 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams p) {
     }
 }
 
-size_t decode_workspace_bytes() { return align_up(kDecWorkspaceBytes, 256); }
+// ---------------------------------------------------------------------------
+// Narrow tensors (at most 128 channels after padding to 32): a chunk holds at least 32
+// pixels, so the wavefront that decoded it has whole matrix tiles of its own.  The basis is
+// copied once per workgroup into LDS in operand order:
+//   basis[(ct * NJ + j) * 64 + lane] = T[8j + 4*(lane/32) + i][ct*32 + lane%32], i = 0..3
+// and lane (row, half) of the other operand reads the four symbols 8j + 4*half + i of its pixel
+// in one LDS word: the contraction index may be walked in any order as long as both operands
+// agree on it.  Symbols enter the matrix cores as exact small integers (s - 2^(b-1)); the step
+// Delta multiplies the sum, and mu is added, in the epilogue.
+// ---------------------------------------------------------------------------
+constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes per run, slack for padded reads
+
+template <int NCT, int LAYOUT, bool ALIGNED4>
+__global__ __launch_bounds__(256) void k_decode_chunks(DecodeParams p) {
+    __shared__ __align__(16) DecTables T;
+    __shared__ uint32_t pay[4][kPayWords + 2];  // per wavefront: the chunk's payload words
+    __shared__ __align__(16) uint8_t symtile[4][kChunkTileBytes];
+    __shared__ float s_mu[NCT * 32];
+    extern __shared__ __align__(16) float4 basis4[];  // [NCT][NJ][64]
+    constexpr int NJ = NCT * 4;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
+    const int half = lane >> 5, l32 = lane & 31;
+    const int C = p.C;
+
+    StreamView sv;
+    if (!open_stream(p, &sv)) {
+        if (tid == 0 && blockIdx.x == 0) atomicOr(p.err, FMTC_ERR_HEADER);
+        return;
+    }
+    {
+        const float4* src = reinterpret_cast<const float4*>(p.Bp4);
+        for (int i = tid; i < NCT * NJ * 64; i += 256) basis4[i] = src[i];
+        if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
+    }
+    if (!build_decode_tables<256>(T, p.stream + kHeaderBytes, p.bits)) {
+        if (tid == 0 && blockIdx.x == 0) atomicOr(p.err, FMTC_ERR_TABLE);
+        return;
+    }
+    const uint32_t n_chunks = sv.n_chunks, spc = sv.spc, chunk_syms = sv.chunk_syms;
+    const uint32_t payload_words = sv.payload_words;
+    const uint64_t V = (uint64_t)p.P * (uint64_t)C;
+    const float delta = sv.delta;
+    const float zero = (float)(1 << (p.bits - 1));
+    uint8_t* tile = symtile[wave];
+    uint32_t* pw = pay[wave];
+
+    for (uint32_t ch = blockIdx.x * 4 + (uint32_t)wave; ch < n_chunks; ch += gridDim.x * 4) {
+        // ---- variable length decoding of the chunk into the wavefront's tile ----
+        const uint64_t c0 = (uint64_t)ch * chunk_syms;
+        const uint32_t clen = (uint32_t)((V - c0 < chunk_syms) ? (V - c0) : chunk_syms);
+        uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)sv.chunk_off[ch]);
+        uint32_t w1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)sv.chunk_off[ch + 1]);
+        if (w0 > w1 || w1 > payload_words) {
+            if (lane == 0) atomicOr(p.err, FMTC_ERR_OFFSETS);
+            w0 = 0; w1 = 0;
+        }
+        const uint32_t run_bits = ((uint32_t)lane < spc) ? sv.sub_bits[(size_t)ch * spc + lane] : 0u;
+        const uint32_t start = wave_exclusive_scan(run_bits, lane);
+        const uint32_t r0 = (uint32_t)lane * kSubSyms;
+        const uint32_t cnt = (r0 < clen) ? ((clen - r0 < (uint32_t)kSubSyms) ? clen - r0 : (uint32_t)kSubSyms) : 0u;
+        const uint32_t nwords = w1 - w0;
+        bool ok_run = true;
+        if (nwords <= (uint32_t)kPayWords) {
+            for (uint32_t i = lane; i < nwords + 2; i += 64) pw[i] = (i < nwords) ? sv.payload[w0 + i] : 0u;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (cnt) ok_run = decode_run<true>(pw, nullptr, nwords, start, cnt, T, ByteOut(tile, r0));
+        } else if (cnt) {
+            ok_run = decode_run<false>(nullptr, sv.payload + w0, nwords, start, cnt, T, ByteOut(tile, r0));
+        }
+        if (!ok_run) atomicOr(p.err, FMTC_ERR_CODE);
+        // the symbols of all lanes are in place before any lane reads them: one wavefront, LDS in order
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+
+        // ---- inverse quantizer + inverse transform of the chunk's pixels ----
+        const int TP = (int)(clen / (uint32_t)C);
+        const int64_t px_chunk0 = (int64_t)ch * (int64_t)sv.ppc;
+        for (int pt = 0; pt * 32 < TP; pt++) {
+            int pxl = pt * 32 + l32;
+            if (pxl > TP - 1) pxl = TP - 1;  // rows past the chunk repeat its last pixel; never stored
+            const uint32_t rowbase = (uint32_t)pxl * (uint32_t)C + 4u * (uint32_t)half;
+            floatx16 acc[NCT];
+#pragma unroll
+            for (int ct = 0; ct < NCT; ct++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[ct][r] = 0.f;
+#pragma unroll 4
+            for (int j = 0; j < NJ; j++) {
+                const uint32_t n = rowbase + 8u * (uint32_t)j;
+                uint32_t word;
+                if constexpr (ALIGNED4) {
+                    word = *reinterpret_cast<const uint32_t*>(tile + sym_addr(n));
+                } else {
+                    word = (uint32_t)tile[sym_addr(n)] | ((uint32_t)tile[sym_addr(n + 1)] << 8) |
+                           ((uint32_t)tile[sym_addr(n + 2)] << 16) | ((uint32_t)tile[sym_addr(n + 3)] << 24);
+                }
+                float q[4];
+#pragma unroll
+                for (int i = 0; i < 4; i++) q[i] = (float)((word >> (8 * i)) & 255u) - zero;
+#pragma unroll
+                for (int ct = 0; ct < NCT; ct++) {
+                    const float4 b4 = basis4[(ct * NJ + j) * 64 + lane];
+                    const float bs[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        if constexpr (LAYOUT == FMTC_NHWC)
+                            acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(q[i], bs[i], acc[ct], 0, 0, 0);
+                        else
+                            acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(bs[i], q[i], acc[ct], 0, 0, 0);
+                    }
+                }
+            }
+            // accumulator r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of the 32x32 tile
+            if constexpr (LAYOUT == FMTC_NHWC) {
+#pragma unroll
+                for (int ct = 0; ct < NCT; ct++) {
+                    const int c = ct * 32 + l32;
+                    if (c < C) {
+                        const float m_c = s_mu[c];
+                        float* dst = p.xhat + (px_chunk0 + pt * 32 + 4 * half) * C + c;
+                        if (pt * 32 + 32 <= TP) {
+#pragma unroll
+                            for (int r = 0; r < 16; r++)
+                                dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = __builtin_fmaf(acc[ct][r], delta, m_c);
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 16; r++)
+                                if (pt * 32 + 8 * (r >> 2) + 4 * half + (r & 3) < TP)
+                                    dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = __builtin_fmaf(acc[ct][r], delta, m_c);
+                        }
+                    }
+                }
+            } else {
+                const int my_px = pt * 32 + l32;
+                if (my_px < TP) {
+                    const int64_t px = px_chunk0 + my_px;
+                    const int64_t n = px / p.HW, hw = px - n * p.HW;
+#pragma unroll
+                    for (int ct = 0; ct < NCT; ct++) {
+                        const int cb = ct * 32 + 4 * half;
+                        float* dst = p.xhat + (n * (int64_t)C + cb) * p.HW + hw;
+#pragma unroll
+                        for (int r = 0; r < 16; r++) {
+                            const int co = 8 * (r >> 2) + (r & 3);
+                            if (cb + co < C) dst[(int64_t)co * p.HW] = __builtin_fmaf(acc[ct][r], delta, s_mu[cb + co]);
+                        }
+                    }
+                }
+            }
+        }
+        // the next chunk of this wavefront overwrites the tile and pay[]: all lanes are done reading here
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
 
 hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
-                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, uint8_t* d_ws,
-                         hipStream_t s) {
+                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, hipStream_t s) {
     const int C = g.C;
     const int ncs = (C + 31) / 32;
+    DecodeParams p;
+    p.stream = d_stream;
+    p.bytes = bytes;
+    p.P = g.P;
+    p.HW = HW;
+    p.C = C;
+    p.bits = bits;
+    p.ncs = ncs;
+    p.Bpk = b ? b->inv : nullptr;
+    p.Bpf = b ? b->invf : nullptr;
+    p.Bp4 = b ? b->inv4 : nullptr;
+    p.mu = b ? b->mu : nullptr;
+    p.xhat = d_xhat;
+    p.syms_out = d_syms;
+    p.err = d_err;
+    p.G = 1;
+    p.ct_per_group = 1;
+    p.tile_rows = 0;
+    const bool al = (C % 4) == 0;
+    hipError_t el = hipSuccess;
+
+    if (!d_syms && ncs <= 4) {
+        // ---- one wavefront per chunk ----
+        const size_t lds = sizeof(float) * (size_t)ncs * 32 * ncs * 32;
+        const size_t lds_static = sizeof(DecTables) + 4 * (kPayWords + 2) * 4 + 4 * kChunkTileBytes + 512;
+        const unsigned per_cu = (unsigned)((160 * 1024) / (lds + lds_static));
+        unsigned gx = (g.n_chunks + 3) / 4;
+        const unsigned cap = 256u * (per_cu < 1 ? 1u : per_cu);
+        if (gx > cap) gx = cap;
+#define FMTC_DECC(NCT, LAY, AL)                                                                                  \
+    do {                                                                                                         \
+        if (lds > 32 * 1024) {                                                                                   \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL>),   \
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
+            if (ea != hipSuccess) return ea;                                                                     \
+        }                                                                                                        \
+        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL>, dim3(gx), dim3(256), lds, s, p);                    \
+    } while (0)
+#define FMTC_DECC_N(LAY, AL)                                                                                     \
+    do {                                                                                                         \
+        if (ncs == 1) FMTC_DECC(1, LAY, AL);                                                                     \
+        else if (ncs == 2) FMTC_DECC(2, LAY, AL);                                                                \
+        else if (ncs == 3) FMTC_DECC(3, LAY, AL);                                                                \
+        else FMTC_DECC(4, LAY, AL);                                                                              \
+    } while (0)
+        if (layout == FMTC_NHWC) { if (al) FMTC_DECC_N(FMTC_NHWC, true); else FMTC_DECC_N(FMTC_NHWC, false); }
+        else                     { if (al) FMTC_DECC_N(FMTC_NCHW, true); else FMTC_DECC_N(FMTC_NCHW, false); }
+#undef FMTC_DECC_N
+#undef FMTC_DECC
+        return el;
+    }
+
+    // ---- tiles of several chunks per workgroup ----
     // Float tile (dequantized coefficients in LDS) for mid-size C; byte tile otherwise and for symbols-only.
     const bool ftile = !d_syms && C >= 32 && C <= 256;
     int G;
@@ -608,30 +804,10 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         G = (int)((64 * (int64_t)C + 4095) / 4096);
         G = G < 4 ? 4 : (G > 16 ? 16 : (G + 3) / 4 * 4);
     }
-    DecodeParams p;
-    p.stream = d_stream;
-    p.bytes = bytes;
-    p.P = g.P;
-    p.HW = HW;
-    p.C = C;
-    p.bits = bits;
     p.G = G;
-    p.ncs = ncs;
-    p.Bpk = b ? b->inv : nullptr;
-    p.Bpf = b ? b->invf : nullptr;
-    p.mu = b ? b->mu : nullptr;
-    p.xhat = d_xhat;
-    p.syms_out = d_syms;
-    p.err = d_err;
-    p.ws = d_ws;
-    p.ct_per_group = 1;
     // a chunk never holds more than 4096 / C pixels (one if C > 4096 / 2), whatever chunk size the stream was made with
     const int max_ppc = 4096 / C > 1 ? 4096 / C : 1;
     p.tile_rows = (G * max_ppc + 31) / 32 * 32;
-    {
-        ProfScope prof(K_DECODE_TABLES, s);
-        hipLaunchKernelGGL(k_decode_tables, dim3(1), dim3(1024), 0, s, p);
-    }
     // the grid is sized from the nominal geometry; the kernel takes the real one from the header
     const uint32_t n_tiles = (g.n_chunks + G - 1) / G;
     int groups = 1;
@@ -642,21 +818,19 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     }
     p.ct_per_group = (ncs + groups - 1) / groups;
     groups = (ncs + p.ct_per_group - 1) / p.ct_per_group;
-    unsigned gx = n_tiles < 2048u ? n_tiles : 2048u;
+    unsigned gx = n_tiles < 1024u ? n_tiles : 1024u;
     dim3 grid(gx, (unsigned)groups);
     const size_t lds = ftile ? sizeof(float) * (size_t)p.tile_rows * (ncs * 32 + 2)
                              : (size_t)G * 4096 + (size_t)G * 4096 / 16 + 128;
-    const bool al = (C % 4) == 0;
-    ProfScope prof(K_DECODE, s);
     // more than 64 KB of dynamic LDS has to be requested per kernel (the CU has 160 KB)
 #define FMTC_DEC(MT, LAY, AL, FT)                                                                            \
     do {                                                                                                     \
         if (lds > 32 * 1024) {                                                                               \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<MT, LAY, AL, FT>),   \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_tiles<MT, LAY, AL, FT>), \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);      \
             if (ea != hipSuccess) return ea;                                                                 \
         }                                                                                                    \
-        hipLaunchKernelGGL((k_decode<MT, LAY, AL, FT>), grid, dim3(256), lds, s, p);                         \
+        el = launch(K_DECODE, k_decode_tiles<MT, LAY, AL, FT>, grid, dim3(256), lds, s, p);                  \
     } while (0)
     if (ftile) {
         const bool two = p.tile_rows >= 64;  // two 32-pixel tiles per wavefront unit
@@ -673,7 +847,7 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         }
     }
 #undef FMTC_DEC
-    return hipGetLastError();
+    return el;
 }
 
 }  // namespace fmtc

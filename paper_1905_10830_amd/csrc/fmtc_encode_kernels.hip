@@ -17,17 +17,12 @@ namespace fmtc {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-__global__ void k_clear(uint32_t* __restrict__ w, size_t n) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) w[i] = 0u;
-}
-
-hipError_t launch_clear(uint32_t* d_words, size_t n_words, hipStream_t s) {
-    if (n_words == 0) return hipSuccess;
-    unsigned blocks = (unsigned)((n_words + 255) / 256);
-    ProfScope prof(K_CLEAR, s);
-    hipLaunchKernelGGL(k_clear, dim3(blocks), dim3(256), 0, s, d_words, n_words);
-    return hipGetLastError();
+// The first kernel of an encoder call clears what the coder kernels after it count in.
+__device__ __forceinline__ void zero_coder_scratch(CoderCtrl* ctrl, unsigned long long* lookback, uint32_t n_groups) {
+    const size_t nthreads = (size_t)gridDim.x * gridDim.y * blockDim.x;
+    const size_t gtid = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+    for (size_t i = gtid; i < n_groups; i += nthreads) lookback[i] = 0ull;
+    if (gtid < sizeof(CoderCtrl) / 4) reinterpret_cast<uint32_t*>(ctrl)[gtid] = 0u;
 }
 
 // PT: pixels per workgroup; MT: 32-pixel tiles per wavefront unit; LAYOUT: FMTC_NHWC / FMTC_NCHW;
@@ -44,9 +39,11 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
                                                           int C, int ncs, int kt_per_group, float inv_delta,
                                                           float delta, float tau, int bits,
                                                           int64_t px_tiles, uint8_t* __restrict__ syms,
-                                                          uint32_t* __restrict__ hist_parts) {
+                                                          uint32_t* __restrict__ hist_parts, CoderCtrl* ctrl,
+                                                          unsigned long long* lookback, uint32_t n_groups) {
     extern __shared__ __align__(16) float dyn_lds[];
     __shared__ uint32_t lhist[256];
+    zero_coder_scratch(ctrl, lookback, n_groups);
 
     const int Cpad = ncs * 32;
     const int RS = Cpad + 2;  // pixel row stride in floats: lanes of a half-wavefront (32 pixels, one channel)
@@ -289,7 +286,7 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
 
 template <int PT, int MT>
 static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
-                            int bits, uint8_t* d_syms, uint32_t* d_hist_parts, int* n_parts, hipStream_t s) {
+                            int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
     const float inv_delta = (float)(1.0 / (double)delta);
     // fp32 accumulation of C terms is off by about sqrt(C) * 2^-24 * |x - mu| / delta steps; values within
     // tau (a few times that) of a rounding boundary are decided in fp64 instead
@@ -311,7 +308,7 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
     *n_parts = (int)(gx * kgroups);
     const size_t lds = sizeof(float) * (size_t)PT * (b.Cpad + 2) + sizeof(uint32_t) * (size_t)PT * (ktg * 8 + 1);
     const bool vec = (b.C % 4) == 0;
-    ProfScope prof(K_PROJECT, s);
+    hipError_t el = hipSuccess;
 #define FMTC_PQ(LAY, VEC)                                                                                       \
     do {                                                                                                        \
         if (lds > 48 * 1024) {                                                                                  \
@@ -319,9 +316,9 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);         \
             if (ea != hipSuccess) return ea;                                                                    \
         }                                                                                                       \
-        hipLaunchKernelGGL((k_project_quantize<PT, MT, LAY, VEC>), grid, dim3(256), lds, s, d_x, b.fwd, b.mu,  \
-                           b.T, P, HW, b.C, ncs, ktg, inv_delta, delta, tau, bits, px_tiles, d_syms,      \
-                           d_hist_parts);                                                                       \
+        el = launch(K_PROJECT, k_project_quantize<PT, MT, LAY, VEC>, grid, dim3(256), lds, s, d_x, b.fwd, b.mu,  \
+                    b.T, P, HW, b.C, ncs, ktg, inv_delta, delta, tau, bits, px_tiles, d_syms, cs.hist_parts,    \
+                    cs.ctrl, cs.lookback, cs.n_groups);                                                         \
     } while (0)
     if (layout == FMTC_NHWC) {
         if (vec) FMTC_PQ(FMTC_NHWC, true);
@@ -331,25 +328,27 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
         else FMTC_PQ(FMTC_NCHW, false);
     }
 #undef FMTC_PQ
-    return hipGetLastError();
+    return el;
 }
 
 hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
-                                   float delta, int bits, uint8_t* d_syms, uint32_t* d_hist_parts, int* n_parts,
+                                   float delta, int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts,
                                    hipStream_t s) {
     const int64_t P = N * HW;
     const int nkt = b.Cpad / 32;
-    if (nkt == 1) return launch_pq<128, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_parts, n_parts, s);
-    if (nkt == 4) return launch_pq<64, 2>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_parts, n_parts, s);
-    if (nkt <= 5) return launch_pq<64, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_parts, n_parts, s);
-    return launch_pq<32, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, d_hist_parts, n_parts, s);
+    if (nkt == 1) return launch_pq<128, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
+    if (nkt == 4) return launch_pq<64, 2>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
+    if (nkt <= 5) return launch_pq<64, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
+    return launch_pq<32, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
 }
 
 // Histogram of given symbols (staged coder entry point): one row of partial counts per workgroup.
 // Values outside the alphabet are not counted.
 __global__ __launch_bounds__(256) void k_histogram(const uint8_t* __restrict__ syms, uint64_t V, int bits,
-                                                   uint32_t* __restrict__ hist_parts) {
+                                                   uint32_t* __restrict__ hist_parts, CoderCtrl* ctrl,
+                                                   unsigned long long* lookback, uint32_t n_groups) {
     __shared__ uint32_t lhist[256];
+    zero_coder_scratch(ctrl, lookback, n_groups);
     lhist[threadIdx.x] = 0u;
     __syncthreads();
     const unsigned K = 1u << bits;
@@ -361,14 +360,13 @@ __global__ __launch_bounds__(256) void k_histogram(const uint8_t* __restrict__ s
     if (threadIdx.x < K) hist_parts[(size_t)blockIdx.x * K + threadIdx.x] = lhist[threadIdx.x];
 }
 
-hipError_t launch_histogram(const uint8_t* d_syms, uint64_t V, int bits, uint32_t* d_hist_parts, int* n_parts,
+hipError_t launch_histogram(const uint8_t* d_syms, uint64_t V, int bits, const CoderScratch& cs, int* n_parts,
                             hipStream_t s) {
     uint64_t want = (V + 256 * 16 - 1) / (256 * 16);
     unsigned blocks = (unsigned)(want < 1 ? 1 : (want > (uint64_t)kMaxHistParts ? (uint64_t)kMaxHistParts : want));
     *n_parts = (int)blocks;
-    ProfScope prof(K_HISTOGRAM, s);
-    hipLaunchKernelGGL(k_histogram, dim3(blocks), dim3(256), 0, s, d_syms, V, bits, d_hist_parts);
-    return hipGetLastError();
+    return launch(K_HISTOGRAM, k_histogram, dim3(blocks), dim3(256), 0, s, d_syms, V, bits, cs.hist_parts, cs.ctrl,
+                  cs.lookback, cs.n_groups);
 }
 
 }  // namespace fmtc

@@ -14,7 +14,7 @@ constexpr int kLenTableBytes = 256;
 constexpr int kSubSyms = 64;     // symbols per run; one lane codes one run
 constexpr int kMaxLen = 48;      // longest code length accepted
 constexpr int kMaxHistParts = 1024;  // per-workgroup partial histograms (no atomics, nothing to clear)
-constexpr int kLutBits = 12;     // decoder lookup table covers codes up to this length
+constexpr int kLutBits = 11;     // decoder lookup table covers codes up to this length
 
 // 64-byte stream header (see fmtc.h for the field meaning).
 struct alignas(8) Header {
@@ -64,30 +64,44 @@ inline bool make_geometry(int64_t P, int C, int chunk_syms, Geometry* g) {
     return true;
 }
 
+// Control words of one encoder call (in the workspace).  Zeroed by the first kernel of the call.
+struct alignas(64) CoderCtrl {
+    uint32_t ticket;                  // next chunk group handed out by the pack kernel
+    uint32_t max_len;                 // longest code length (table kernel)
+    unsigned long long payload_bits;  // sum of count * length (table kernel)
+    uint32_t error;                   // set if a bounded wait of the pack kernel ran out
+    uint32_t reserved[11];
+};
+static_assert(sizeof(CoderCtrl) == 64, "control block is 64 bytes");
+
+constexpr int kPackWaves = 4;  // chunks per workgroup of the pack kernel (one wavefront each)
+
 // Device workspace of the encoder.
 struct Workspace {
     size_t off_hist_parts;   // u32 [kMaxHistParts][2^bits] partial histograms, one row per workgroup
-    size_t off_counters;     // u32 [16]; [1]: ticket of the run-size kernel (reset by the table kernel)
+    size_t off_ctrl;         // CoderCtrl
     size_t off_hist;         // u32 [256] final histogram
     size_t off_enc_table;    // u64 [256]: bit-reversed code | length << 56
-    size_t off_chunk_bits;   // u32 [n_chunks]
+    size_t off_lookback;     // u64 [n_groups]: running payload word count per chunk group (flag << 32 | words)
     size_t off_syms;         // u8 [V]
     size_t total;
 };
+
+inline uint32_t pack_groups(uint32_t n_chunks) { return (n_chunks + kPackWaves - 1) / kPackWaves; }
 
 inline Workspace make_workspace(uint64_t V, uint32_t n_chunks) {
     Workspace w;
     size_t o = 0;
     w.off_hist_parts = o;
     o += sizeof(uint32_t) * kMaxHistParts * 256;
-    w.off_counters = o;
-    o += 64;
+    w.off_ctrl = o;
+    o += sizeof(CoderCtrl);
     w.off_hist = o;
     o += sizeof(uint32_t) * 256;
     w.off_enc_table = o;
     o += sizeof(uint64_t) * 256;
-    w.off_chunk_bits = o;
-    o = align_up(o + sizeof(uint32_t) * (size_t)n_chunks, 256);
+    w.off_lookback = o;
+    o = align_up(o + sizeof(uint64_t) * (size_t)pack_groups(n_chunks), 256);
     w.off_syms = o;
     o = align_up(o + (size_t)V, 256);
     w.total = o;
@@ -103,45 +117,64 @@ struct BasisDevice {
     const float* fwd;      // M = T      (row = coefficient k, column = channel c)
     const float* inv;      // M = T^T    (row = channel c, column = coefficient k), inverse slot order
     const float* invf;     // M = T^T, forward slot order
+    const float* inv4;     // M = T^T as [row tile][j][lane][4]: lane (r, h) holds M[tile*32 + r][8j + 4h + i]
+    const float* fwd4;     // M = T in the same order, rows of a tile permuted so that a lane ends up with 16
+                           // consecutive coefficients: lane (r, h) holds M[tile*32 + 16*((r>>2)&1) + 4*(r>>3) + (r&3)][..]
     const float* mu;       // [Cpad], zero padded
     const float* T;        // [C][C] row major, unpacked
 };
 
-// ---- optional per-kernel timing (fmtc_profile_* in fmtc.h); no-ops unless enabled ----
-enum KernelId { K_CLEAR = 0, K_PROJECT, K_HISTOGRAM, K_TABLE, K_RUN_BITS, K_PACK, K_DECODE_TABLES, K_DECODE, K_COUNT };
-void prof_mark(int id, bool end, hipStream_t s);
-struct ProfScope {
-    int id;
-    hipStream_t s;
-    ProfScope(int id_, hipStream_t s_) : id(id_), s(s_) { prof_mark(id, false, s); }
-    ~ProfScope() { prof_mark(id, true, s); }
+// ---- optional per-kernel timing (fmtc_profile_* in fmtc.h) ----
+// When enabled, a launch carries a pair of events that the runtime attaches to the kernel's own dispatch, so
+// the elapsed time is the kernel's start-to-end time on the GPU (no bracket of separate marker commands).
+enum KernelId { K_PROJECT = 0, K_HISTOGRAM, K_TABLE, K_PACK, K_DECODE, K_COPY, K_COUNT };
+bool prof_next(int id, hipEvent_t* start, hipEvent_t* stop);
+
+template <class T>
+struct same_as { using type = T; };
+
+template <typename... KArgs>
+inline hipError_t launch(int id, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t s,
+                         typename same_as<KArgs>::type... args) {
+    void* ptrs[] = {(void*)&args...};
+    hipEvent_t a = nullptr, b = nullptr;
+    if (prof_next(id, &a, &b))
+        return hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds, s, a, b, 0);
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds, s);
+}
+
+// What the kernels that produce symbols hand to the coder.
+struct CoderScratch {
+    uint32_t* hist_parts;  // [n_parts][2^bits]
+    CoderCtrl* ctrl;
+    unsigned long long* lookback;
+    uint32_t n_groups;
 };
 
 // ---- kernel launchers (definitions in the *_kernels.hip files) ----
-hipError_t launch_clear(uint32_t* d_words, size_t n_words, hipStream_t s);
-
 hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
-                                   float delta, int bits, uint8_t* d_syms, uint32_t* d_hist_parts, int* n_parts,
+                                   float delta, int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts,
                                    hipStream_t s);
 
-hipError_t launch_histogram(const uint8_t* d_syms, uint64_t V, int bits, uint32_t* d_hist_parts, int* n_parts,
+hipError_t launch_histogram(const uint8_t* d_syms, uint64_t V, int bits, const CoderScratch& cs, int* n_parts,
                             hipStream_t s);
 
-hipError_t launch_huffman_table(const uint32_t* d_hist_parts, int n_parts, int bits, uint32_t* d_hist,
-                                uint64_t* d_enc_table, uint8_t* d_len_table, uint32_t* d_counters, hipStream_t s);
+// Sum of the partial histograms only (staged quantizer entry point).
+hipError_t launch_histogram_sum(const uint32_t* d_hist_parts, int n_parts, int bits, uint32_t* d_hist,
+                                hipStream_t s);
 
-hipError_t launch_pack(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const uint64_t* d_enc_table,
-                       uint32_t* d_chunk_bits, uint32_t* d_counters, uint8_t* d_stream, uint64_t* d_out_bytes,
-                       hipStream_t s);
+hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
+                        int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t* d_out_bytes,
+                        hipStream_t s);
 
 hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
-                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, uint8_t* d_ws,
-                         hipStream_t s);
-size_t decode_workspace_bytes();
+                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, hipStream_t s);
 
 hipError_t launch_fit_moments(const float* d_x, int64_t N, int C, int64_t HW, int layout, double* d_sum,
                               double* d_cov, hipStream_t s);
 hipError_t launch_fit_range(const float* d_x, int64_t N, int C, int64_t HW, int layout, const float* d_t0,
                             const float* d_mu, double* d_amax, hipStream_t s);
+hipError_t launch_fill_zero(uint32_t* d_words, size_t n_words, hipStream_t s);
+hipError_t launch_copy(void* d_dst, const void* d_src, size_t bytes, hipStream_t s);
 
 }  // namespace fmtc

@@ -1,7 +1,8 @@
-// Optional per-kernel timing with HIP events recorded on the caller's stream
-// around every kernel launch of the library.  Off by default; when off the
-// hooks cost one branch.  Used by the benchmark to hold each kernel against its
-// roofline.
+// Optional per-kernel timing: when enabled every kernel launch of the library
+// carries a pair of HIP events attached to its own dispatch, so the elapsed time
+// is the kernel's start-to-end time on the GPU.  Off by default; when off the
+// hook costs one branch.  Used by the benchmark to hold each kernel against its
+// roofline.  Also home of two utility kernels (zero fill, yardstick copy).
 #include <vector>
 
 #include "fmtc_internal.h"
@@ -16,8 +17,8 @@ struct Profiler {
     int used[K_COUNT] = {0};
 };
 Profiler g_prof;
-const char* const kNames[K_COUNT] = {"k_clear",    "k_project_quantize", "k_histogram",     "k_huffman_table",
-                                     "k_run_bits", "k_pack",             "k_decode_tables", "k_decode"};
+const char* const kNames[K_COUNT] = {"k_project_quantize", "k_histogram", "k_huffman_table",
+                                     "k_pack",             "k_decode",    "k_copy"};
 
 void release() {
     for (int k = 0; k < K_COUNT; k++) {
@@ -32,16 +33,40 @@ void release() {
 }
 }  // namespace
 
-void prof_mark(int id, bool end, hipStream_t s) {
-    if (!g_prof.on) return;
+bool prof_next(int id, hipEvent_t* start, hipEvent_t* stop) {
+    if (!g_prof.on) return false;
     int& n = g_prof.used[id];
-    if (n >= g_prof.cap) return;
-    if (!end) {
-        (void)hipEventRecord(g_prof.start[id][n], s);
-    } else {
-        (void)hipEventRecord(g_prof.stop[id][n], s);
-        n++;
-    }
+    if (n >= g_prof.cap) return false;
+    *start = g_prof.start[id][n];
+    *stop = g_prof.stop[id][n];
+    n++;
+    return true;
+}
+
+// Plain device-to-device copy of known size: the yardstick the memory counters are scaled with.
+__global__ __launch_bounds__(256) void k_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_copy(void* d_dst, const void* d_src, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    if (blocks < 1) blocks = 1;
+    return launch(K_COPY, k_copy, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<uint4*>(d_dst),
+                  static_cast<const uint4*>(d_src), n16);
+}
+
+__global__ void k_fill_zero(uint32_t* __restrict__ w, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) w[i] = 0u;
+}
+
+hipError_t launch_fill_zero(uint32_t* d_words, size_t n_words, hipStream_t s) {
+    if (n_words == 0) return hipSuccess;
+    unsigned blocks = (unsigned)((n_words + 255) / 256);
+    hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, s, d_words, n_words);
+    return hipGetLastError();
 }
 
 }  // namespace fmtc
@@ -71,6 +96,11 @@ int fmtc_profile_kernels(void) { return fmtc::K_COUNT; }
 
 const char* fmtc_profile_name(int kernel) {
     return (kernel >= 0 && kernel < fmtc::K_COUNT) ? fmtc::kNames[kernel] : "";
+}
+
+fmtc_status fmtc_profile_copy(void* d_dst, const void* d_src, size_t bytes, void* hip_stream) {
+    if (!d_dst || !d_src || bytes % 16 != 0 || ((uintptr_t)d_dst | (uintptr_t)d_src) % 16 != 0) return FMTC_EINVAL;
+    return fmtc::launch_copy(d_dst, d_src, bytes, (hipStream_t)hip_stream) == hipSuccess ? FMTC_OK : FMTC_EHIP;
 }
 
 fmtc_status fmtc_profile_read(int kernel, double* avg_ms, double* min_ms, int* launches) {

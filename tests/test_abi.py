@@ -83,8 +83,7 @@ def test_argument_errors_are_reported_on_the_host(lib):
     assert st == fmtc.EINVAL and b"basis" in lib.fmtc_last_error()
     st = lib.fmtc_encode(None, None, 1, 64, 8, 8, fmtc.NHWC, 4, 4096, None, 0, None, None, 0, None)
     assert st == fmtc.EINVAL
-    st = lib.fmtc_decode(None, None, 0, None, 1, 64, 8, 8, fmtc.NHWC, 4, None, None, 0, None)
+    st = lib.fmtc_decode(None, None, 0, None, 1, 64, 8, 8, fmtc.NHWC, 4, None, None)
     assert st == fmtc.EINVAL
-    assert 4096 <= fmtc.decode_workspace_size() <= 65536
-    st = lib.fmtc_decode_symbols(None, 0, 10, 64, 4, None, None, None, 0, None)
+    st = lib.fmtc_decode_symbols(None, 0, 10, 64, 4, None, None, None)
     assert st == fmtc.EINVAL
