@@ -30,25 +30,27 @@ struct DecTables {
     uint64_t first_code[64];  // first canonical code of each length
     uint64_t limit[64];       // (first_code + count) << (32 - length) for length <= 32: first left-aligned 32-bit
                               // value that is NOT a code of this length or shorter
+    uint32_t limit32[64];     // the same, saturated to 32 bits (exact for every length below the longest)
     uint16_t sorted_sym[256]; // symbols in (length, symbol) order
-    // next kLutBits stream bits -> up to two symbols: sym0 | sym1 << 8 | (len0 + len1) << 16 | len0 << 21 | n << 26,
-    // n = number of whole codes found in those bits (0: the first code is longer than kLutBits)
+    // next kLutBits stream bits -> up to three symbols: sym0 | sym1 << 8 | sym2 << 16 | bits << 24 | n << 29,
+    // n = number of whole codes found in those bits (0: the first code is longer than kLutBits), bits = their
+    // total length
     uint32_t lut[1 << kLutBits];
     // scratch of the construction
+    uint16_t first[1 << kLutBits];  // first code in a kLutBits-bit value (first stream bit on top): sym | len << 8
     uint32_t wave_len_count[4][64];
     uint32_t lut_limit[kLutBits + 1];  // limit[] in a kLutBits-bit frame
     uint32_t n_used, bad_len, ok, max_len;
 };
 
-// All THREADS threads of the workgroup call this (THREADS a multiple of 256).  Returns false (for every thread)
+// All THREADS threads of the workgroup call this (THREADS a multiple of 256); my_len is the code length of symbol
+// threadIdx.x from the stream (threads past 255: anything).  Returns false (for every thread)
 // unless the lengths form a complete prefix code (Kraft sum exactly 1), or the single one-bit code of a
 // one-symbol tensor.
 template <int THREADS>
-__device__ __forceinline__ bool build_decode_tables(DecTables& T, const uint8_t* __restrict__ len_table, int bits) {
+__device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, int bits) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int K = 1 << bits;
-    int my_len = 0;
-    if (tid < 256) my_len = len_table[tid];
     if (tid < 64) T.cnt_len[tid] = 0u;
     if (tid < 256) T.wave_len_count[tid >> 6][tid & 63] = 0u;
     if (tid == 0) { T.n_used = 0u; T.bad_len = 0u; }
@@ -74,7 +76,9 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, const uint8_t*
         const unsigned long long kraft = __shfl(incl, 63, 64);
         T.first_code[tid] = in ? ((incl - w) >> (kMaxLen - tid)) : 0ull;
         T.first_rank[tid] = in ? rank : 0u;
-        T.limit[tid] = (in && tid <= 32) ? (incl >> (kMaxLen - 32)) : ~0ull;
+        const unsigned long long lim32 = (in && tid <= 32) ? (incl >> (kMaxLen - 32)) : ~0ull;
+        T.limit[tid] = lim32;
+        T.limit32[tid] = lim32 > 0xffffffffull ? 0xffffffffu : (uint32_t)lim32;
         if (tid >= 1 && tid <= kLutBits) T.lut_limit[tid] = (uint32_t)(incl >> (kMaxLen - kLutBits));
         if (!in) T.cnt_len[tid] = 0u;
         const unsigned long long used = __ballot(c != 0);
@@ -106,30 +110,50 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, const uint8_t*
     }
     __syncthreads();
     {
+        // Step 1: the first code in every kLutBits-bit value.  Canonical codes, left-aligned, grow with their
+        // length, so the length is 1 + the number of per-length limits the value reaches.  Fixed trip count,
+        // unrolled: the searches of several values are independent and interleave.
         uint32_t lim[kLutBits + 1];
 #pragma unroll
         for (int l = 1; l <= kLutBits; l++) lim[l] = T.lut_limit[l];
-        // first whole code in the top bits of v (kLutBits-bit frame, first stream bit on top) that is at most
-        // maxbits long: its length (0 if none) and symbol
-        auto first_code_in = [&](uint32_t v, uint32_t maxbits, uint32_t* sym) -> uint32_t {
+#pragma unroll
+        for (int it = 0; it < (1 << kLutBits) / THREADS; it++) {
+            const uint32_t v = (uint32_t)(tid + it * THREADS);
             uint32_t len = 1;
 #pragma unroll
             for (int l = 1; l < kLutBits; l++) len += (v >= lim[l]) ? 1u : 0u;
-            if (v >= lim[kLutBits] || len > maxbits) return 0u;
-            const uint32_t off = (v >> (kLutBits - len)) - (uint32_t)T.first_code[len];
-            *sym = T.sorted_sym[(T.first_rank[len] + off) & 255u];
-            return len;
-        };
-        for (int idx = tid; idx < (1 << kLutBits); idx += THREADS) {
-            const uint32_t v = __brev((uint32_t)idx) >> (32 - kLutBits);
-            uint32_t s0 = 0, s1 = 0, e = 0;
-            const uint32_t len0 = first_code_in(v, kLutBits, &s0);
-            if (len0) {
-                const uint32_t rest = (v << len0) & ((1u << kLutBits) - 1u);
-                const uint32_t len1 = (len0 < (uint32_t)kLutBits) ? first_code_in(rest, kLutBits - len0, &s1) : 0u;
-                if (len1) e = s0 | (s1 << 8) | ((len0 + len1) << 16) | (len0 << 21) | (2u << 26);
-                else e = s0 | (len0 << 16) | (len0 << 21) | (1u << 26);
+            uint32_t entry = 0;
+            if (v < lim[kLutBits]) {
+                const uint32_t off = (v >> (kLutBits - len)) - (uint32_t)T.first_code[len];
+                entry = (uint32_t)T.sorted_sym[(T.first_rank[len] + off) & 255u] | (len << 8);
             }
+            T.first[v] = (uint16_t)entry;
+        }
+    }
+    __syncthreads();
+    {
+        // Step 2: chain up to three codes per table entry (the index of an entry is in stream order, least
+        // significant bit first).  A later code counts only if all its bits are inside the kLutBits bits.
+        constexpr uint32_t kMask = (1u << kLutBits) - 1u;
+#pragma unroll
+        for (int it = 0; it < (1 << kLutBits) / THREADS; it++) {
+            const int idx = tid + it * THREADS;
+            const uint32_t v0 = __brev((uint32_t)idx) >> (32 - kLutBits);
+            const uint32_t f0 = T.first[v0];
+            const uint32_t len0 = f0 >> 8;
+            const uint32_t v1 = (v0 << len0) & kMask;
+            const uint32_t f1 = T.first[v1];
+            const uint32_t len1 = f1 >> 8;
+            const uint32_t v2 = (v1 << len1) & kMask;
+            const uint32_t f2 = T.first[v2];
+            const uint32_t len2 = f2 >> 8;
+            const bool ok0 = len0 != 0;
+            const bool ok1 = ok0 && len1 != 0 && len0 + len1 <= (uint32_t)kLutBits;
+            const bool ok2 = ok1 && len2 != 0 && len0 + len1 + len2 <= (uint32_t)kLutBits;
+            uint32_t e = 0;
+            if (ok0) e = (f0 & 255u) | (len0 << 24) | (1u << 29);
+            if (ok1) e = (f0 & 255u) | ((f1 & 255u) << 8) | ((len0 + len1) << 24) | (2u << 29);
+            if (ok2) e = (f0 & 255u) | ((f1 & 255u) << 8) | ((f2 & 255u) << 16) | ((len0 + len1 + len2) << 24) | (3u << 29);
             T.lut[idx] = e;
         }
     }
@@ -189,7 +213,7 @@ __device__ __forceinline__ bool decode_run(const uint32_t* pw, const uint32_t* _
     while (i < cnt) {
         const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, sh);
         uint32_t e = T.lut[w & ((1u << kLutBits) - 1)];
-        uint32_t n = e >> 26, sym0 = e & 255u, len0 = (e >> 21) & 31u;
+        uint32_t n = e >> 29, sym0 = e & 255u, len0 = (e >> 24) & 31u;
         if (__builtin_expect(n == 0, 0)) {
             // A code longer than the table.  Canonical codes, left-aligned, grow with their length, so the
             // length is kLutBits + 1 + the number of longer-length limits the next 32 bits reach.
@@ -231,18 +255,99 @@ __device__ __forceinline__ bool decode_run(const uint32_t* pw, const uint32_t* _
                 continue;
             }
         }
-        const bool two = n == 2 && i + 1 < cnt;
-        const uint32_t len = two ? ((e >> 16) & 31u) : len0;
+        // all symbols of the entry are consumed; those past the end of the run (they belong to the next run,
+        // or are pad bits) are dropped, and where the cursor ends up after the run does not matter
         out.put(sym0);
-        if (two) out.put((e >> 8) & 255u);
-        i += two ? 2u : 1u;
-        sh += len;  // at most 31 + 32: one word boundary at most
+        if (n >= 2 && i + 1 < cnt) out.put((e >> 8) & 255u);
+        if (n >= 3 && i + 2 < cnt) out.put((e >> 16) & 255u);
+        i += n;
+        sh += len0;  // total length of the entry; at most 31 + 32: one word boundary at most
         const bool cross = sh >= 32;
         lo = cross ? hi : lo;
         hi = cross ? nxt : hi;
         widx += cross ? 1u : 0u;
         sh &= 31u;
         nxt = fetch(widx + 2);
+    }
+    return ok;
+}
+
+// The same for a chunk staged in LDS whose run goes to 64 consecutive bytes `out`, which up to 3 more bytes
+// may follow (pad bytes of the tile): every step stores the three symbol bytes of its table entry at the
+// current position, and the next step overwrites what was not a symbol.  One table read and a handful of
+// dependent operations per up to three symbols.  Codes longer than the table are rare: the wavefront branches
+// (as a whole) only when one of its lanes meets one.
+// `pw` holds the chunk's nwords words, two zero words, and at least kPayOverrun words of any content behind
+// them: a run of a corrupt stream may read that far (64 steps of at most 48 bits), never further.
+constexpr int kPayOverrun = 104;
+__device__ __forceinline__ bool decode_run_bytes(const uint32_t* pw, uint32_t nwords, uint32_t start, uint32_t cnt,
+                                                 const DecTables& T, uint8_t* out) {
+    const uint32_t w0 = (start >> 5) < nwords ? (start >> 5) : nwords;
+    const uint32_t* pp = pw + w0;  // word after the three at hand
+    uint32_t sh = start & 31;
+    uint32_t lo = pp[0], hi = pp[1], nxt = pp[2];
+    pp += 3;
+    bool ok = true;
+    uint32_t i = 0;
+    while (i < cnt) {
+        const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, sh);
+        uint32_t e = T.lut[w & ((1u << kLutBits) - 1)];
+        uint32_t after = *pp;  // does not wait for the entry: both reads are in flight
+        if (__builtin_expect(__any((e >> 29) == 0), 0)) {
+            if ((e >> 29) == 0) {
+                // A code longer than the table.  Canonical codes, left-aligned, grow with their length, so the
+                // length is kLutBits + 1 + the number of longer-length limits the next 32 bits reach (limits of
+                // the lengths below the longest one are below 2^32; the longest needs no test).
+                const uint32_t v = __brev(w);  // first stream bit on top
+                const uint32_t top = T.max_len < 33u ? T.max_len : 33u;
+                uint32_t len = kLutBits + 1;
+                for (uint32_t l = kLutBits + 1; l < top; l++) len += (v >= T.limit32[l]) ? 1u : 0u;
+                uint32_t sym = 0;
+                uint32_t bp = (uint32_t)(pp - 3 - pw) * 32u + sh;
+                if (len <= 32) {
+                    const uint32_t off = (v >> (32 - len)) - (uint32_t)T.first_code[len];
+                    if (off >= T.cnt_len[len]) ok = false;
+                    sym = T.sorted_sym[(T.first_rank[len] + off) & 255u];
+                    bp += len;
+                } else {
+                    // longer than 32 bits (needs a histogram as skewed as the Fibonacci numbers): bit by bit
+                    uint64_t code = 0;
+                    bool found = false;
+                    for (uint32_t l = 1; l <= (uint32_t)kMaxLen; l++) {
+                        code = (code << 1) | ((pw[bp >> 5] >> (bp & 31)) & 1u);
+                        bp++;
+                        const uint64_t f = T.first_code[l];
+                        const uint32_t c = T.cnt_len[l];
+                        if (c && code >= f && code - f < c) {
+                            sym = T.sorted_sym[T.first_rank[l] + (uint32_t)(code - f)];
+                            found = true;
+                            break;
+                        }
+                    }
+                    if (!found) ok = false;
+                }
+                // the cursor moves here; what follows sees an entry of one symbol and no bits
+                pp = pw + (bp >> 5);
+                sh = bp & 31;
+                lo = pp[0];
+                hi = pp[1];
+                nxt = pp[2];
+                after = pp[3];
+                pp += 3;
+                e = sym | (1u << 29);
+            }
+        }
+        out[i] = (uint8_t)e;
+        out[i + 1] = (uint8_t)(e >> 8);
+        out[i + 2] = (uint8_t)(e >> 16);
+        i += e >> 29;
+        sh += (e >> 24) & 31u;  // at most 31 + kLutBits: one word boundary at most
+        const bool cross = sh >= 32;
+        lo = cross ? hi : lo;
+        hi = cross ? nxt : hi;
+        nxt = cross ? after : nxt;
+        pp += cross ? 1 : 0;
+        sh &= 31u;
     }
     return ok;
 }
@@ -306,7 +411,7 @@ __device__ __forceinline__ bool open_stream(const DecodeParams& p, StreamView* v
     return true;
 }
 
-constexpr int kPayWords = 1022;  // LDS copy of a chunk's payload: up to ~8 bits/symbol; larger chunks read global memory
+constexpr int kPayWords = 918;  // LDS copy of a chunk's payload: up to ~7 bits/symbol; larger chunks read global memory
 
 // FTILE: the tile holds dequantized coefficients as floats, [pixel][coefficient] with row stride Cpad + 2 (the
 // matrix operand then comes straight from LDS, as in the encoder); otherwise symbol bytes, converted on the fly.
@@ -326,7 +431,7 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
         if (tid == 0) atomicOr(p.err, FMTC_ERR_HEADER);
         return;
     }
-    if (!build_decode_tables<256>(T, p.stream + kHeaderBytes, p.bits)) {
+    if (!build_decode_tables<256>(T, (int)p.stream[kHeaderBytes + tid], p.bits)) {
         if (tid == 0) atomicOr(p.err, FMTC_ERR_TABLE);
         return;
     }
@@ -591,9 +696,10 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
 constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes per run, slack for padded reads
 
 template <int NCT, int LAYOUT, bool ALIGNED4>
-__global__ __launch_bounds__(256) void k_decode_chunks(DecodeParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_decode_chunks(DecodeParams p) {
     __shared__ __align__(16) DecTables T;
-    __shared__ uint32_t pay[4][kPayWords + 2];  // per wavefront: the chunk's payload words
+    __shared__ uint32_t pay[4][kPayWords + 2 + kPayOverrun];  // per wavefront: the chunk's payload words, 2 zero
+                                                              // words, room for a corrupt stream's overrun
     __shared__ __align__(16) uint8_t symtile[4][kChunkTileBytes];
     __shared__ float s_mu[NCT * 32];
     extern __shared__ __align__(16) float4 basis4[];  // [NCT][NJ][64]
@@ -604,20 +710,38 @@ __global__ __launch_bounds__(256) void k_decode_chunks(DecodeParams p) {
     const int half = lane >> 5, l32 = lane & 31;
     const int C = p.C;
 
+    // loads that do not depend on the header go out first: the code length table and the basis
+    int my_len = 0;
+    if (p.bytes >= (size_t)(kHeaderBytes + kLenTableBytes)) my_len = p.stream[kHeaderBytes + tid];
+    // the basis goes from global memory straight into LDS (no registers in between), 16 bytes per lane and
+    // instruction: lane l of a wavefront lands at the wavefront's LDS base + 16 l
+    constexpr int kBasisPerThread = NCT * NJ * 64 / 256;  // 16-byte pieces of the basis per thread
+    {
+        const float4* src = reinterpret_cast<const float4*>(p.Bp4);
+#pragma unroll
+        for (int i = 0; i < kBasisPerThread; i++)
+            __builtin_amdgcn_global_load_lds(src + tid + 256 * i, &basis4[256 * i + 64 * wave], 16, 0, 0);
+    }
     StreamView sv;
     if (!open_stream(p, &sv)) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(p.err, FMTC_ERR_HEADER);
         return;
     }
-    {
-        const float4* src = reinterpret_cast<const float4*>(p.Bp4);
-        for (int i = tid; i < NCT * NJ * 64; i += 256) basis4[i] = src[i];
-        if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
+    // the first chunk's offsets and run sizes are on their way while the tables are built
+    const uint32_t ch_first = blockIdx.x * 4 + (uint32_t)wave;
+    uint32_t pre_w0 = 0, pre_w1 = 0, pre_run = 0;
+    if (ch_first < sv.n_chunks) {
+        pre_w0 = sv.chunk_off[ch_first];
+        pre_w1 = sv.chunk_off[ch_first + 1];
+        pre_run = ((uint32_t)lane < sv.spc) ? sv.sub_bits[(size_t)ch_first * sv.spc + lane] : 0u;
     }
-    if (!build_decode_tables<256>(T, p.stream + kHeaderBytes, p.bits)) {
+    if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
+    if (!build_decode_tables<256>(T, my_len, p.bits)) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(p.err, FMTC_ERR_TABLE);
         return;
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's part of the basis has landed in LDS
+    __syncthreads();
     const uint32_t n_chunks = sv.n_chunks, spc = sv.spc, chunk_syms = sv.chunk_syms;
     const uint32_t payload_words = sv.payload_words;
     const uint64_t V = (uint64_t)p.P * (uint64_t)C;
@@ -630,13 +754,14 @@ __global__ __launch_bounds__(256) void k_decode_chunks(DecodeParams p) {
         // ---- variable length decoding of the chunk into the wavefront's tile ----
         const uint64_t c0 = (uint64_t)ch * chunk_syms;
         const uint32_t clen = (uint32_t)((V - c0 < chunk_syms) ? (V - c0) : chunk_syms);
-        uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)sv.chunk_off[ch]);
-        uint32_t w1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)sv.chunk_off[ch + 1]);
+        const bool first = ch == ch_first;
+        uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(first ? pre_w0 : sv.chunk_off[ch]));
+        uint32_t w1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(first ? pre_w1 : sv.chunk_off[ch + 1]));
         if (w0 > w1 || w1 > payload_words) {
             if (lane == 0) atomicOr(p.err, FMTC_ERR_OFFSETS);
             w0 = 0; w1 = 0;
         }
-        const uint32_t run_bits = ((uint32_t)lane < spc) ? sv.sub_bits[(size_t)ch * spc + lane] : 0u;
+        const uint32_t run_bits = first ? pre_run : (((uint32_t)lane < spc) ? sv.sub_bits[(size_t)ch * spc + lane] : 0u);
         const uint32_t start = wave_exclusive_scan(run_bits, lane);
         const uint32_t r0 = (uint32_t)lane * kSubSyms;
         const uint32_t cnt = (r0 < clen) ? ((clen - r0 < (uint32_t)kSubSyms) ? clen - r0 : (uint32_t)kSubSyms) : 0u;
@@ -646,7 +771,8 @@ __global__ __launch_bounds__(256) void k_decode_chunks(DecodeParams p) {
             for (uint32_t i = lane; i < nwords + 2; i += 64) pw[i] = (i < nwords) ? sv.payload[w0 + i] : 0u;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            if (cnt) ok_run = decode_run<true>(pw, nullptr, nwords, start, cnt, T, ByteOut(tile, r0));
+            // run `lane` goes to bytes [68 * lane, 68 * lane + 64) of the tile (sym_addr), 4 pad bytes behind it
+            if (cnt) ok_run = decode_run_bytes(pw, nwords, start, cnt, T, tile + 68u * (uint32_t)lane);
         } else if (cnt) {
             ok_run = decode_run<false>(nullptr, sv.payload + w0, nwords, start, cnt, T, ByteOut(tile, r0));
         }
@@ -765,7 +891,7 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     if (!d_syms && ncs <= 4) {
         // ---- one wavefront per chunk ----
         const size_t lds = sizeof(float) * (size_t)ncs * 32 * ncs * 32;
-        const size_t lds_static = sizeof(DecTables) + 4 * (kPayWords + 2) * 4 + 4 * kChunkTileBytes + 512;
+        const size_t lds_static = sizeof(DecTables) + 4 * (kPayWords + 2 + kPayOverrun) * 4 + 4 * kChunkTileBytes + 512;
         const unsigned per_cu = (unsigned)((160 * 1024) / (lds + lds_static));
         unsigned gx = (g.n_chunks + 3) / 4;
         const unsigned cap = 256u * (per_cu < 1 ? 1u : per_cu);

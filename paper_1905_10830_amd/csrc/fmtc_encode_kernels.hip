@@ -11,6 +11,9 @@
 // Values that land too close to a rounding boundary for fp32 to decide are
 // recomputed in fp64 by the wavefront.  The quantized tile is staged in LDS and
 // leaves as whole rows of symbols.
+#include <type_traits>
+
+#include "fmtc_device.h"
 #include "fmtc_internal.h"
 
 namespace fmtc {
@@ -331,11 +334,404 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
     return el;
 }
 
+// ---------------------------------------------------------------------------
+// Narrow tensors (at most 128 channels after padding to 32).  One wavefront owns 32 pixels
+// for all coefficients: lane (pixel r, half h) loads its pixel's channels 8j + 4h .. 8j + 4h + 3,
+// j = 0 .. Cpad/8 - 1, straight from global memory into the registers that feed the matrix
+// instruction (the contraction index may be walked in any order as long as both operands agree,
+// so no transpose through LDS is needed), removes the mean, and runs the coefficient tiles one
+// after the other against the basis, which sits in LDS in operand order
+//   basis4[(kt * NJ + j) * 64 + lane] = T[kt*32 + rho(lane%32)][8j + 4*(lane/32) + i], i = 0..3
+// with the rows of a tile permuted (rho) so that a lane ends up with 16 consecutive coefficients
+// of its pixel: one 16-byte store of symbols per tile.  The quantizer of tile kt is scheduled
+// between the matrix instructions of tile kt+1.  Histogram: one LDS histogram per wavefront.
+// ---------------------------------------------------------------------------
+constexpr int kHistLanes = 16;  // histogram copies per wavefront in the narrow-tensor kernel
+constexpr int kFixList = 64;    // values per wavefront waiting for their exact decision
+
+// LDS traffic of one wavefront completes in order; this keeps the compiler from moving it across the point
+__device__ __forceinline__ void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+struct RowParams {
+    const float* x;
+    const float* basis4;  // fwd4 packing
+    const float* mu;      // [Cpad]
+    const float* Trow;    // [C][C] row major, for the exact decisions
+    int64_t P, HW;
+    int C, bits;
+    float inv_delta, delta, tau;
+    int64_t n_tiles;      // 32-pixel tiles
+    uint8_t* syms;
+    uint32_t* hist_parts;
+    CoderCtrl* ctrl;
+    unsigned long long* lookback;
+    uint32_t n_groups;
+};
+
+template <int NCT, int LAYOUT, bool VEC>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_project_quantize_rows(RowParams p) {
+    constexpr int NJ = NCT * 4;
+    extern __shared__ __align__(16) float4 basis4[];  // [NCT][NJ][64], then the histograms
+    __shared__ __align__(16) float s_mu[NCT * 32];
+    __shared__ uint32_t s_fix_list[4][kFixList];
+    __shared__ uint32_t s_fix_count[4];
+    // Histogram: kHistLanes interleaved copies per wavefront (bin s of copy q at word s * kHistLanes + q), lane l
+    // counts in copy l % kHistLanes.  Most symbols of a tile are the same few values: with one copy the LDS
+    // would serialise up to 64 additions to one word per instruction, and the reads of the basis queue up
+    // behind them.
+    const int K = 1 << p.bits;
+    uint32_t* whist = reinterpret_cast<uint32_t*>(basis4 + NCT * NJ * 64);  // [4][K * kHistLanes]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
+    const int half = lane >> 5, l32 = lane & 31;
+    const int C = p.C;
+    // this lane's half of its pixel: xr[4j + i] = x[px][8j + 4h + i]
+    float xr[NJ * 4];
+    auto load_pixels = [&](int64_t tile) {
+        const int64_t px = tile * 32 + l32;
+        const bool px_ok = px < p.P;
+        if constexpr (LAYOUT == FMTC_NHWC && VEC) {
+            const float4* row = reinterpret_cast<const float4*>(p.x + (px_ok ? px : 0) * C) + half;
+#pragma unroll
+            for (int j = 0; j < NJ; j++) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (px_ok && 8 * j + 4 * half < C) v = row[2 * j];
+                xr[4 * j] = v.x; xr[4 * j + 1] = v.y; xr[4 * j + 2] = v.z; xr[4 * j + 3] = v.w;
+            }
+        } else {
+            int64_t base = 0, stride = 1;
+            if constexpr (LAYOUT == FMTC_NHWC) {
+                base = (px_ok ? px : 0) * C;
+            } else {
+                const int64_t pp = px_ok ? px : 0;
+                const int64_t n = pp / p.HW;
+                base = n * (int64_t)C * p.HW + (pp - n * p.HW);
+                stride = p.HW;
+            }
+#pragma unroll
+            for (int j = 0; j < NJ; j++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const int c = 8 * j + 4 * half + i;
+                    xr[4 * j + i] = (px_ok && c < C) ? p.x[base + (int64_t)c * stride] : 0.f;
+                }
+        }
+    };
+    // the first tile's pixels come from HBM: their loads go out before anything else
+    int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+    if (tile < p.n_tiles) load_pixels(tile);
+    zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
+
+    // the basis goes from global memory straight into LDS, 16 bytes per lane and instruction
+    {
+        const float4* src = reinterpret_cast<const float4*>(p.basis4);
+#pragma unroll
+        for (int i = 0; i < NCT * NCT; i++)
+            __builtin_amdgcn_global_load_lds(src + tid + 256 * i, &basis4[256 * i + 64 * wave], 16, 0, 0);
+    }
+    if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
+    for (int i = tid; i < 4 * K * kHistLanes; i += 256) whist[i] = 0u;
+
+    const int zero_sym = 1 << (p.bits - 1);
+    const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1), zero_f = (float)zero_sym;
+    const float inv_delta = p.inv_delta;
+    const float near_limit = 0.5f - p.tau;
+    uint32_t* wh0 = whist + wave * K * kHistLanes;          // this wavefront's histogram, copy 0
+    uint32_t* wh = wh0 + (lane & (kHistLanes - 1));         // bin s of this lane's copy: wh[s * kHistLanes]
+    uint32_t* fix_list = s_fix_list[wave];
+    uint32_t* fix_count = &s_fix_count[wave];
+    if (lane == 0) *fix_count = 0u;
+
+    // the first tile's pixels are on their way while the basis lands; every wavefront of the workgroup takes
+    // part in the barrier, with or without a tile
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's part of the basis has landed in LDS
+    __syncthreads();
+
+    for (; tile < p.n_tiles; tile += (int64_t)gridDim.x * 4) {
+        const int64_t px = tile * 32 + l32;
+        const bool px_ok = px < p.P;
+        // mean removed (padding channels hold 0 - 0)
+#pragma unroll
+        for (int j = 0; j < NJ; j++) {
+            const float4 m = *reinterpret_cast<const float4*>(&s_mu[8 * j + 4 * half]);
+            xr[4 * j] -= m.x; xr[4 * j + 1] -= m.y; xr[4 * j + 2] -= m.z; xr[4 * j + 3] -= m.w;
+        }
+
+        auto project_tile = [&](int kt) -> floatx16 {
+            floatx16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[r] = 0.f;
+            float4 a_cur = basis4[(kt * NJ) * 64 + lane];
+#pragma unroll
+            for (int j = 0; j < NJ; j++) {
+                float4 a_nxt = a_cur;  // the next step's operand is read while this step's instructions run
+                if (j + 1 < NJ) a_nxt = basis4[(kt * NJ + j + 1) * 64 + lane];
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.x, xr[4 * j], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.y, xr[4 * j + 1], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.z, xr[4 * j + 2], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.w, xr[4 * j + 3], acc, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                a_cur = a_nxt;
+            }
+            return acc;
+        };
+        // accumulator r = 4g + i of lane (pixel, h) is coefficient kt*32 + 16h + 4g + i of the pixel.
+        // Quantizer, histogram and store of one tile with ragged edges (pixels past P, coefficients past C).
+        auto quantize_tile = [&](const floatx16& acc, int kt, uint32_t (&word)[4]) -> float {
+            const int k0 = kt * 32 + 16 * half;
+            float maxd = 0.f;
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                word[g] = 0u;
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const float t = acc[4 * g + i] * inv_delta;
+                    const float q = __builtin_rintf(t);  // round half to even
+                    maxd = fmaxf(maxd, fabsf(t - q));
+                    const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
+                    word[g] = __builtin_amdgcn_cvt_pk_u8_f32(qc, i, word[g]);
+                }
+            }
+            if (px_ok) {
+#pragma unroll
+                for (int r = 0; r < 16; r++)
+                    if (k0 + r < C) {
+                        const uint32_t sy = (word[r >> 2] >> (8 * (r & 3))) & 255u;
+                        atomicAdd(&wh[sy * kHistLanes], 1u);
+                        p.syms[px * C + k0 + r] = (uint8_t)sy;
+                    }
+            }
+            return maxd;
+        };
+        // ---- exact decision where fp32 can not be trusted (rare) ----
+        // A tile notes the values that lie too close to a rounding boundary in the wavefront's list: pixel lane,
+        // coefficient and the symbol already stored and counted.  When the list is full, and after the last
+        // tile of the pixels, the listed values are recomputed in fp64 (same arithmetic as the definition: sum of
+        // T[k][c] * (x[c] - mu[c]), divided by the step), four per round, all loads of a round in flight
+        // together, and the stored symbol and the histogram are patched where the decision differs.
+        auto resolve_list = [&]() {
+            // the symbols that get patched were stored by other lanes of this wavefront: those stores are
+            // acknowledged before the patches go out
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            const uint32_t n = (uint32_t)__builtin_amdgcn_readfirstlane((int)*fix_count);
+            for (uint32_t base = 0; base < n; base += 4) {
+                const uint32_t idx = base + (uint32_t)(lane >> 4);
+                const bool active = idx < n;
+                const uint32_t e = active ? fix_list[idx] : 0u;
+                const int k = (int)(e & 127u), pl = (int)((e >> 7) & 31u);
+                const uint32_t old = e >> 12;
+                const int64_t qpx = tile * 32 + pl;
+                int64_t xbase, xstride;
+                if constexpr (LAYOUT == FMTC_NHWC) {
+                    xbase = qpx * C;
+                    xstride = 1;
+                } else {
+                    const int64_t n_img = qpx / p.HW;
+                    xbase = n_img * (int64_t)C * p.HW + (qpx - n_img * p.HW);
+                    xstride = p.HW;
+                }
+                float tv[2 * NCT], xv[2 * NCT], mv[2 * NCT];
+#pragma unroll
+                for (int it = 0; it < 2 * NCT; it++) {
+                    const int c = (lane & 15) + 16 * it;
+                    const bool in = active && c < C;
+                    tv[it] = in ? p.Trow[(size_t)k * C + c] : 0.f;
+                    xv[it] = in ? p.x[xbase + c * xstride] : 0.f;
+                    mv[it] = in ? s_mu[c] : 0.f;
+                }
+                double part = 0.0;
+#pragma unroll
+                for (int it = 0; it < 2 * NCT; it++) part += (double)tv[it] * ((double)xv[it] - (double)mv[it]);
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);  // stays inside the 16-lane group
+                double qd = rint(part / (double)p.delta);
+                qd = fmin(fmax(qd, (double)lo), (double)hi);
+                const uint32_t sfix = (uint32_t)((int)qd + zero_sym);
+                if (active && (lane & 15) == 0 && sfix != old) {
+                    atomicSub(&wh0[old * kHistLanes], 1u);
+                    atomicAdd(&wh0[sfix * kHistLanes], 1u);
+                    p.syms[qpx * C + k] = (uint8_t)sfix;
+                }
+            }
+            wave_sync_lds();
+            if (lane == 0) *fix_count = 0u;
+            wave_sync_lds();
+        };
+        auto note_tile = [&](const floatx16& acc, int kt, const uint32_t (&word)[4]) {
+            const int k0 = kt * 32 + 16 * half;
+            uint32_t near_mask = 0;
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const float t = acc[r] * inv_delta;
+                if (fabsf(t - __builtin_rintf(t)) > near_limit && px_ok && k0 + r < C) near_mask |= 1u << r;
+            }
+            // at most 64 * 16 new entries would not fit: resolve what is there first if this tile could overflow
+            const uint32_t incoming = wave_sum((uint32_t)__popc(near_mask));
+            if (*fix_count + incoming > (uint32_t)kFixList) resolve_list();
+            if (incoming > (uint32_t)kFixList) {
+                // more flagged values than the list holds (a step so fine that fp32 decides almost nothing):
+                // 16 passes, one accumulator each, at most 64 entries per pass
+#pragma unroll 1
+                for (int r = 0; r < 16; r++) {
+                    if ((near_mask >> r) & 1u) {
+                        const uint32_t slot = atomicAdd(fix_count, 1u);
+                        fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 7) |
+                                         (((word[r >> 2] >> (8 * (r & 3))) & 255u) << 12);
+                    }
+                    wave_sync_lds();
+                    resolve_list();
+                }
+            } else {
+                while (near_mask) {
+                    const int r = __ffs((int)near_mask) - 1;
+                    near_mask &= near_mask - 1;
+                    uint32_t sy = 0;
+#pragma unroll
+                    for (int g = 0; g < 4; g++)
+                        if (g == (r >> 2)) sy = (word[g] >> (8 * (r & 3))) & 255u;
+                    const uint32_t slot = atomicAdd(fix_count, 1u);
+                    fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 7) | (sy << 12);
+                }
+                wave_sync_lds();
+            }
+        };
+
+        const bool full = (tile * 32 + 32 <= p.P) && (C == NCT * 32);  // wavefront-uniform
+        if (full) {
+            // One wavefront per SIMD: nothing else fills the shadow of the matrix pipe, so the quantizer of tile
+            // kt is issued by hand between the matrix instructions of tile kt + 1 -- after each group of four
+            // (one step of the contraction) the share of the previous tile's 16 values that keeps both in step.
+            floatx16 acc = project_tile(0);
+#pragma unroll
+            for (int kt = 0; kt < NCT; kt++) {
+                floatx16 nxt;
+#pragma unroll
+                for (int r = 0; r < 16; r++) nxt[r] = 0.f;
+                uint32_t word[4] = {0u, 0u, 0u, 0u};
+                float maxd = 0.f;
+                auto quantize_value = [&](int r) {
+                    const float t = acc[r] * inv_delta;
+                    const float q = __builtin_rintf(t);  // round half to even
+                    maxd = fmaxf(maxd, fabsf(t - q));
+                    const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
+                    word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
+                    atomicAdd(&wh[(uint32_t)qc * kHistLanes], 1u);
+                };
+                if (kt + 1 < NCT) {
+                    float4 a_cur = basis4[((kt + 1) * NJ) * 64 + lane];
+#pragma unroll
+                    for (int j = 0; j < NJ; j++) {
+                        float4 a_nxt = a_cur;
+                        if (j + 1 < NJ) a_nxt = basis4[((kt + 1) * NJ + j + 1) * 64 + lane];
+                        nxt = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.x, xr[4 * j], nxt, 0, 0, 0);
+                        nxt = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.y, xr[4 * j + 1], nxt, 0, 0, 0);
+                        nxt = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.z, xr[4 * j + 2], nxt, 0, 0, 0);
+                        nxt = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.w, xr[4 * j + 3], nxt, 0, 0, 0);
+#pragma unroll
+                        for (int r = 16 * j / NJ; r < 16 * (j + 1) / NJ; r++) quantize_value(r);
+                        __builtin_amdgcn_sched_barrier(0);
+                        a_cur = a_nxt;
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) quantize_value(r);
+                }
+                // FULL implies C = 32 * NCT: every lane's 16 symbols are a 16-byte aligned piece of its pixel's row
+                *reinterpret_cast<uint4*>(p.syms + px * C + kt * 32 + 16 * half) =
+                    make_uint4(word[0], word[1], word[2], word[3]);
+                if (__builtin_expect(__any(maxd > near_limit), 0)) note_tile(acc, kt, word);
+                acc = nxt;
+            }
+        } else {
+            floatx16 acc = project_tile(0);
+#pragma unroll
+            for (int kt = 0; kt < NCT; kt++) {
+                floatx16 nxt;
+                uint32_t word[4];
+                if (kt + 1 < NCT) nxt = project_tile(kt + 1);
+                const float maxd = quantize_tile(acc, kt, word);
+                if (__builtin_expect(__any(maxd > near_limit && px_ok), 0)) note_tile(acc, kt, word);
+                if (kt + 1 < NCT) acc = nxt;
+            }
+        }
+        if (*fix_count) resolve_list();
+        if (tile + (int64_t)gridDim.x * 4 < p.n_tiles) load_pixels(tile + (int64_t)gridDim.x * 4);
+    }
+    __syncthreads();
+    // one row of partial counts per workgroup: nothing to clear beforehand, no global atomics
+    if (tid < K) {
+        uint32_t total = 0;
+        for (int w = 0; w < 4; w++)
+#pragma unroll
+            for (int q = 0; q < kHistLanes; q++) total += whist[(w * K + tid) * kHistLanes + q];
+        p.hist_parts[(size_t)blockIdx.x * K + tid] = total;
+    }
+}
+
+static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
+                              int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
+    RowParams p;
+    p.x = d_x;
+    p.basis4 = b.fwd4;
+    p.mu = b.mu;
+    p.Trow = b.T;
+    p.P = P;
+    p.HW = HW;
+    p.C = b.C;
+    p.bits = bits;
+    p.inv_delta = (float)(1.0 / (double)delta);
+    p.delta = delta;
+    // fp32 accumulation of C terms is off by about sqrt(C) * 2^-24 * |x - mu| / delta steps; values within
+    // tau (a few times that) of a rounding boundary are decided in fp64 instead
+    float tau = 8.f * sqrtf((float)b.Cpad) * 5.9604645e-8f * (float)(1 << (bits - 1));
+    p.tau = fminf(fmaxf(tau, 1.f / 8192.f), 1.f / 128.f);
+    p.n_tiles = (P + 31) / 32;
+    p.syms = d_syms;
+    p.hist_parts = cs.hist_parts;
+    p.ctrl = cs.ctrl;
+    p.lookback = cs.lookback;
+    p.n_groups = cs.n_groups;
+    const int nct = b.Cpad / 32;
+    const size_t lds = sizeof(float) * (size_t)b.Cpad * b.Cpad + sizeof(uint32_t) * 4 * kHistLanes * ((size_t)1 << bits);
+    int64_t gx = (p.n_tiles + 3) / 4;
+    const int64_t cap = (lds + 2 * 1024 <= 80 * 1024) ? 512 : 256;  // one or two workgroups per compute unit
+    if (gx > cap) gx = cap;
+    *n_parts = (int)gx;
+    const bool vec = (b.C % 4) == 0;
+    hipError_t el = hipSuccess;
+#define FMTC_ROWS(NCT, LAY, VEC)                                                                                 \
+    do {                                                                                                         \
+        if (lds > 32 * 1024) {                                                                                   \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project_quantize_rows<NCT, LAY, VEC>), \
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
+            if (ea != hipSuccess) return ea;                                                                     \
+        }                                                                                                        \
+        el = launch(K_PROJECT, k_project_quantize_rows<NCT, LAY, VEC>, dim3((unsigned)gx), dim3(256), lds, s, p); \
+    } while (0)
+#define FMTC_ROWS_N(LAY, VEC)                                                                                    \
+    do {                                                                                                         \
+        if (nct == 1) FMTC_ROWS(1, LAY, VEC);                                                                    \
+        else if (nct == 2) FMTC_ROWS(2, LAY, VEC);                                                               \
+        else if (nct == 3) FMTC_ROWS(3, LAY, VEC);                                                               \
+        else FMTC_ROWS(4, LAY, VEC);                                                                             \
+    } while (0)
+    if (layout == FMTC_NHWC) { if (vec) FMTC_ROWS_N(FMTC_NHWC, true); else FMTC_ROWS_N(FMTC_NHWC, false); }
+    else                     { if (vec) FMTC_ROWS_N(FMTC_NCHW, true); else FMTC_ROWS_N(FMTC_NCHW, false); }
+#undef FMTC_ROWS_N
+#undef FMTC_ROWS
+    return el;
+}
+
 hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
                                    float delta, int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts,
                                    hipStream_t s) {
     const int64_t P = N * HW;
     const int nkt = b.Cpad / 32;
+    if (nkt <= 4) return launch_rows(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
     if (nkt == 1) return launch_pq<128, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
     if (nkt == 4) return launch_pq<64, 2>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
     if (nkt <= 5) return launch_pq<64, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
