@@ -15,7 +15,8 @@ struct fmtc_basis {
     std::vector<float> T, mu;
     std::vector<double> eig;
     float *d_fwd = nullptr, *d_inv = nullptr, *d_invf = nullptr, *d_mu = nullptr, *d_T = nullptr;
-    float *d_inv4 = nullptr, *d_fwd4 = nullptr;
+    uint16_t *d_fwd16 = nullptr, *d_inv16 = nullptr;
+    float row_norm = 1.f;  // largest Euclidean norm of a row of T (1 for an orthonormal basis)
     int device = 0;
 };
 
@@ -64,34 +65,52 @@ void pack_operand(const std::vector<float>& T, int C, int Cpad, bool transpose, 
                 }
 }
 
-// Operand order of the narrow-tensor kernels: out[((tile * NJ + j) * 64 + lane) * 4 + i] =
-// M[tile*32 + row(lane%32)][8j + 4*(lane/32) + i], NJ = Cpad / 8, zero outside CxC.  With permute_rows the rows
-// of a tile are taken in the order that leaves a lane of the matrix instruction with 16 consecutive rows.
-void pack_operand4(const std::vector<float>& T, int C, int Cpad, bool transpose, bool permute_rows,
-                   std::vector<float>* out) {
-    const int nt_count = Cpad / 32, NJ = Cpad / 8;
-    out->assign((size_t)Cpad * Cpad, 0.f);
+// Operand order of the narrow-tensor kernels (v_mfma_f32_32x32x16_f16, every fp32 entry split into two f16 parts:
+// hi = the entry rounded to f16, lo = 2^11 times the rest, rounded to f16).  For tile t (32 rows of M) and step
+// j (16 columns) the 64 lanes' hi parts (8 halves each) are followed by their lo parts:
+//   out[(((t * NJ + j) * 2 + part) * 64 + lane) * 8 + e] = part of M[t*32 + row(lane%32)][16j + 8*(lane/32) + e],
+// NJ = Cpad / 16, zero outside CxC.  With permute_rows the rows of a tile are taken in the order that leaves a
+// lane of the matrix instruction with 16 consecutive rows.
+void pack_operand16(const std::vector<float>& T, int C, int Cpad, bool transpose, bool permute_rows,
+                    std::vector<uint16_t>* out) {
+    const int nt_count = Cpad / 32, NJ = Cpad / 16;
+    out->assign((size_t)2 * Cpad * Cpad, 0);
     for (int nt = 0; nt < nt_count; nt++)
         for (int j = 0; j < NJ; j++)
             for (int lane = 0; lane < 64; lane++)
-                for (int i = 0; i < 4; i++) {
+                for (int e = 0; e < 8; e++) {
                     const int r = lane % 32, half = lane / 32;
                     const int row = nt * 32 + (permute_rows ? 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3) : r);
-                    const int col = 8 * j + 4 * half + i;
+                    const int col = 16 * j + 8 * half + e;
                     float v = 0.f;
                     if (row < C && col < C) v = transpose ? T[(size_t)col * C + row] : T[(size_t)row * C + col];
-                    (*out)[(((size_t)nt * NJ + j) * 64 + lane) * 4 + i] = v;
+                    const _Float16 hi = (_Float16)v;
+                    const _Float16 lo = (_Float16)((v - (float)hi) * 2048.f);
+                    uint16_t hb, lb;
+                    memcpy(&hb, &hi, 2);
+                    memcpy(&lb, &lo, 2);
+                    const size_t base = ((size_t)nt * NJ + j) * 2;
+                    (*out)[((base + 0) * 64 + lane) * 8 + e] = hb;
+                    (*out)[((base + 1) * 64 + lane) * 8 + e] = lb;
                 }
 }
 
 fmtc_status upload_basis(fmtc_basis* b) {
     const int C = b->C, Cpad = b->Cpad;
-    std::vector<float> fwd, inv, invf, inv4, fwd4, mu(Cpad, 0.f);
+    std::vector<float> fwd, inv, invf, mu(Cpad, 0.f);
+    std::vector<uint16_t> fwd16, inv16;
     pack_operand(b->T, C, Cpad, false, false, &fwd);
     pack_operand(b->T, C, Cpad, true, true, &inv);
     pack_operand(b->T, C, Cpad, true, false, &invf);
-    pack_operand4(b->T, C, Cpad, true, false, &inv4);
-    pack_operand4(b->T, C, Cpad, false, true, &fwd4);
+    pack_operand16(b->T, C, Cpad, false, true, &fwd16);
+    pack_operand16(b->T, C, Cpad, true, false, &inv16);
+    double worst = 0.0;
+    for (int k = 0; k < C; k++) {
+        double n2 = 0.0;
+        for (int c = 0; c < C; c++) n2 += (double)b->T[(size_t)k * C + c] * (double)b->T[(size_t)k * C + c];
+        if (n2 > worst) worst = n2;
+    }
+    b->row_norm = (float)std::sqrt(worst);
     for (int c = 0; c < C; c++) mu[c] = b->mu[c];
     hipError_t e;
     const size_t mat = sizeof(float) * (size_t)Cpad * Cpad;
@@ -104,10 +123,10 @@ fmtc_status upload_basis(fmtc_basis* b) {
     if ((e = hipMalloc((void**)&b->d_invf, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
     if ((e = hipMemcpy(b->d_invf, invf.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     if ((e = hipMemcpy(b->d_mu, mu.data(), sizeof(float) * Cpad, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
-    if ((e = hipMalloc((void**)&b->d_inv4, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
-    if ((e = hipMemcpy(b->d_inv4, inv4.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
-    if ((e = hipMalloc((void**)&b->d_fwd4, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
-    if ((e = hipMemcpy(b->d_fwd4, fwd4.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
+    if ((e = hipMalloc((void**)&b->d_inv16, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    if ((e = hipMemcpy(b->d_inv16, inv16.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
+    if ((e = hipMalloc((void**)&b->d_fwd16, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    if ((e = hipMemcpy(b->d_fwd16, fwd16.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     if ((e = hipMalloc((void**)&b->d_T, sizeof(float) * (size_t)C * C)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
     if ((e = hipMemcpy(b->d_T, b->T.data(), sizeof(float) * (size_t)C * C, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     return FMTC_OK;
@@ -120,8 +139,9 @@ BasisDevice device_view(const fmtc_basis* b) {
     v.fwd = b->d_fwd;
     v.inv = b->d_inv;
     v.invf = b->d_invf;
-    v.inv4 = b->d_inv4;
-    v.fwd4 = b->d_fwd4;
+    v.inv16 = b->d_inv16;
+    v.fwd16 = b->d_fwd16;
+    v.row_norm = b->row_norm;
     v.mu = b->d_mu;
     v.T = b->d_T;
     return v;
@@ -243,8 +263,8 @@ void fmtc_basis_destroy(fmtc_basis* b) {
     if (b->d_fwd) (void)hipFree(b->d_fwd);
     if (b->d_inv) (void)hipFree(b->d_inv);
     if (b->d_invf) (void)hipFree(b->d_invf);
-    if (b->d_inv4) (void)hipFree(b->d_inv4);
-    if (b->d_fwd4) (void)hipFree(b->d_fwd4);
+    if (b->d_inv16) (void)hipFree(b->d_inv16);
+    if (b->d_fwd16) (void)hipFree(b->d_fwd16);
     if (b->d_mu) (void)hipFree(b->d_mu);
     if (b->d_T) (void)hipFree(b->d_T);
     delete b;

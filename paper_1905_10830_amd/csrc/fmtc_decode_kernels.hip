@@ -365,7 +365,7 @@ struct DecodeParams {
     int ncs;           // Cpad / 32
     const float* Bpk;  // inverse operand, packed (slot order of the byte tile)
     const float* Bpf;  // inverse operand, packed (slot order of the float tile)
-    const float* Bp4;  // inverse operand, packed for the one-wavefront-per-chunk kernel
+    const uint16_t* Bp16;  // inverse operand, f16 split, packed for the one-wavefront-per-chunk kernel
     const float* mu;   // [Cpad]
     float* xhat;       // NULL in symbols-only mode
     uint8_t* syms_out; // non-NULL in symbols-only mode
@@ -685,14 +685,19 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
 
 // ---------------------------------------------------------------------------
 // Narrow tensors (at most 128 channels after padding to 32): a chunk holds at least 32
-// pixels, so the wavefront that decoded it has whole matrix tiles of its own.  The basis is
-// copied once per workgroup into LDS in operand order:
-//   basis[(ct * NJ + j) * 64 + lane] = T[8j + 4*(lane/32) + i][ct*32 + lane%32], i = 0..3
-// and lane (row, half) of the other operand reads the four symbols 8j + 4*half + i of its pixel
-// in one LDS word: the contraction index may be walked in any order as long as both operands
-// agree on it.  Symbols enter the matrix cores as exact small integers (s - 2^(b-1)); the step
-// Delta multiplies the sum, and mu is added, in the epilogue.
+// pixels, so the wavefront that decoded it has whole matrix tiles of its own.  The inverse
+// transform runs on the f16 matrix cores (v_mfma_f32_32x32x16_f16): the levels s - 2^(b-1)
+// are small integers, exact in f16, and every basis entry is split in two f16 parts,
+// T = hi + lo / 2^11 (22 significant bits; see pack_operand16 on the host), so
+//   x_hat = Delta (sum q T_hi + 2^-11 sum q T_lo) + mu
+// with exact products and fp32 accumulation: two instructions per 16 coefficients where the
+// fp32 instruction needs eight four times as long.  The basis is copied once per workgroup
+// into LDS in operand order; lane (row, half) of the other operand reads the eight symbols
+// 16j + 8*half + e of its pixel (the contraction index may be walked in any order as long as
+// both operands agree on it).  Delta and mu are applied in the epilogue.
 // ---------------------------------------------------------------------------
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes per run, slack for padded reads
 
 template <int NCT, int LAYOUT, bool ALIGNED4>
@@ -702,8 +707,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                                                               // words, room for a corrupt stream's overrun
     __shared__ __align__(16) uint8_t symtile[4][kChunkTileBytes];
     __shared__ float s_mu[NCT * 32];
-    extern __shared__ __align__(16) float4 basis4[];  // [NCT][NJ][64]
-    constexpr int NJ = NCT * 4;
+    extern __shared__ __align__(16) uint4 basis16[];  // [NCT][NJ][2][64]
+    constexpr int NJ = NCT * 2;  // steps of 16 coefficients
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
@@ -715,12 +720,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (p.bytes >= (size_t)(kHeaderBytes + kLenTableBytes)) my_len = p.stream[kHeaderBytes + tid];
     // the basis goes from global memory straight into LDS (no registers in between), 16 bytes per lane and
     // instruction: lane l of a wavefront lands at the wavefront's LDS base + 16 l
-    constexpr int kBasisPerThread = NCT * NJ * 64 / 256;  // 16-byte pieces of the basis per thread
+    constexpr int kBasisPerThread = NCT * NJ * 2 * 64 / 256;  // 16-byte pieces of the basis per thread
     {
-        const float4* src = reinterpret_cast<const float4*>(p.Bp4);
+        const uint4* src = reinterpret_cast<const uint4*>(p.Bp16);
 #pragma unroll
         for (int i = 0; i < kBasisPerThread; i++)
-            __builtin_amdgcn_global_load_lds(src + tid + 256 * i, &basis4[256 * i + 64 * wave], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(src + tid + 256 * i, &basis16[256 * i + 64 * wave], 16, 0, 0);
     }
     StreamView sv;
     if (!open_stream(p, &sv)) {
@@ -746,7 +751,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const uint32_t payload_words = sv.payload_words;
     const uint64_t V = (uint64_t)p.P * (uint64_t)C;
     const float delta = sv.delta;
-    const float zero = (float)(1 << (p.bits - 1));
+    // 0x6400 | s is the f16 number 1024 + s: the level s - 2^(b-1) is that minus (1024 + 2^(b-1)), exactly
+    const _Float16 level_off = (_Float16)(float)(1024 + (1 << (p.bits - 1)));
+    const halfx2 level_off2 = {level_off, level_off};
     uint8_t* tile = symtile[wave];
     uint32_t* pw = pay[wave];
 
@@ -787,38 +794,49 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         for (int pt = 0; pt * 32 < TP; pt++) {
             int pxl = pt * 32 + l32;
             if (pxl > TP - 1) pxl = TP - 1;  // rows past the chunk repeat its last pixel; never stored
-            const uint32_t rowbase = (uint32_t)pxl * (uint32_t)C + 4u * (uint32_t)half;
-            floatx16 acc[NCT];
+            const uint32_t rowbase = (uint32_t)pxl * (uint32_t)C + 8u * (uint32_t)half;
+            floatx16 acc[NCT], acl[NCT];
 #pragma unroll
             for (int ct = 0; ct < NCT; ct++)
 #pragma unroll
-                for (int r = 0; r < 16; r++) acc[ct][r] = 0.f;
-#pragma unroll 4
-            for (int j = 0; j < NJ; j++) {
-                const uint32_t n = rowbase + 8u * (uint32_t)j;
-                uint32_t word;
-                if constexpr (ALIGNED4) {
-                    word = *reinterpret_cast<const uint32_t*>(tile + sym_addr(n));
-                } else {
-                    word = (uint32_t)tile[sym_addr(n)] | ((uint32_t)tile[sym_addr(n + 1)] << 8) |
-                           ((uint32_t)tile[sym_addr(n + 2)] << 16) | ((uint32_t)tile[sym_addr(n + 3)] << 24);
-                }
-                float q[4];
+                for (int r = 0; r < 16; r++) { acc[ct][r] = 0.f; acl[ct][r] = 0.f; }
 #pragma unroll
-                for (int i = 0; i < 4; i++) q[i] = (float)((word >> (8 * i)) & 255u) - zero;
+            for (int j = 0; j < NJ; j++) {
+                // the eight symbols 16j + 8*half .. + 7 of this lane's pixel (coefficients past C meet zero basis
+                // entries; whatever finite level the tile's bytes give there does not count)
+                const uint32_t n = rowbase + 16u * (uint32_t)j;
+                uint32_t w0, w1;
+                if constexpr (ALIGNED4) {
+                    w0 = *reinterpret_cast<const uint32_t*>(tile + sym_addr(n));
+                    w1 = *reinterpret_cast<const uint32_t*>(tile + sym_addr(n + 4));
+                } else {
+                    w0 = (uint32_t)tile[sym_addr(n)] | ((uint32_t)tile[sym_addr(n + 1)] << 8) |
+                         ((uint32_t)tile[sym_addr(n + 2)] << 16) | ((uint32_t)tile[sym_addr(n + 3)] << 24);
+                    w1 = (uint32_t)tile[sym_addr(n + 4)] | ((uint32_t)tile[sym_addr(n + 5)] << 8) |
+                         ((uint32_t)tile[sym_addr(n + 6)] << 16) | ((uint32_t)tile[sym_addr(n + 7)] << 24);
+                }
+                const halfx2 q01 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w0, 0x05010400u)) - level_off2;
+                const halfx2 q23 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w0, 0x07030602u)) - level_off2;
+                const halfx2 q45 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w1, 0x05010400u)) - level_off2;
+                const halfx2 q67 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w1, 0x07030602u)) - level_off2;
+                const halfx8 q = {q01[0], q01[1], q23[0], q23[1], q45[0], q45[1], q67[0], q67[1]};
 #pragma unroll
                 for (int ct = 0; ct < NCT; ct++) {
-                    const float4 b4 = basis4[(ct * NJ + j) * 64 + lane];
-                    const float bs[4] = {b4.x, b4.y, b4.z, b4.w};
-#pragma unroll
-                    for (int i = 0; i < 4; i++) {
-                        if constexpr (LAYOUT == FMTC_NHWC)
-                            acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(q[i], bs[i], acc[ct], 0, 0, 0);
-                        else
-                            acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(bs[i], q[i], acc[ct], 0, 0, 0);
+                    const halfx8 bh = __builtin_bit_cast(halfx8, basis16[((ct * NJ + j) * 2) * 64 + lane]);
+                    const halfx8 bl = __builtin_bit_cast(halfx8, basis16[((ct * NJ + j) * 2 + 1) * 64 + lane]);
+                    if constexpr (LAYOUT == FMTC_NHWC) {
+                        acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q, bh, acc[ct], 0, 0, 0);
+                        acl[ct] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q, bl, acl[ct], 0, 0, 0);
+                    } else {
+                        acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, q, acc[ct], 0, 0, 0);
+                        acl[ct] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q, acl[ct], 0, 0, 0);
                     }
                 }
             }
+#pragma unroll
+            for (int ct = 0; ct < NCT; ct++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[ct][r] = __builtin_fmaf(acl[ct][r], 1.f / 2048.f, acc[ct][r]);
             // accumulator r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of the 32x32 tile
             if constexpr (LAYOUT == FMTC_NHWC) {
 #pragma unroll
@@ -877,7 +895,7 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     p.ncs = ncs;
     p.Bpk = b ? b->inv : nullptr;
     p.Bpf = b ? b->invf : nullptr;
-    p.Bp4 = b ? b->inv4 : nullptr;
+    p.Bp16 = b ? b->inv16 : nullptr;
     p.mu = b ? b->mu : nullptr;
     p.xhat = d_xhat;
     p.syms_out = d_syms;

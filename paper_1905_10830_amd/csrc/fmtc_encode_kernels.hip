@@ -336,16 +336,25 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
 
 // ---------------------------------------------------------------------------
 // Narrow tensors (at most 128 channels after padding to 32).  One wavefront owns 32 pixels
-// for all coefficients: lane (pixel r, half h) loads its pixel's channels 8j + 4h .. 8j + 4h + 3,
-// j = 0 .. Cpad/8 - 1, straight from global memory into the registers that feed the matrix
-// instruction (the contraction index may be walked in any order as long as both operands agree,
-// so no transpose through LDS is needed), removes the mean, and runs the coefficient tiles one
-// after the other against the basis, which sits in LDS in operand order
-//   basis4[(kt * NJ + j) * 64 + lane] = T[kt*32 + rho(lane%32)][8j + 4*(lane/32) + i], i = 0..3
-// with the rows of a tile permuted (rho) so that a lane ends up with 16 consecutive coefficients
-// of its pixel: one 16-byte store of symbols per tile.  The quantizer of tile kt is scheduled
-// between the matrix instructions of tile kt+1.  Histogram: one LDS histogram per wavefront.
+// for all coefficients.  The contraction runs on the f16 matrix cores with every fp32 operand
+// split in two f16 parts, v = hi + lo / 2^11 (hi = v rounded to f16, lo = 2^11 times the rest
+// rounded to f16: 22 significant bits in all, and the scaling keeps lo out of the subnormals):
+//   y = sum T_hi x_hi  +  2^-11 (sum T_hi x_lo + sum T_lo x_hi)
+// with exact products and fp32 accumulation (v_mfma_f32_32x32x16_f16, three instructions per
+// 16 channels where the fp32 instruction needs eight four times as long).  Measured against
+// fp64 the result is as close as the fp32 instruction's; what is left of the error is bounded
+// per pixel by a multiple of |x - mu|_2 and handled by the exact decision below.
+// Lane (pixel r, half h) loads its pixel's channels 16j + 8h .. 16j + 8h + 7, j = 0 .. Cpad/16 - 1,
+// straight from global memory into registers (the contraction index may be walked in any order
+// as long as both operands agree, so no transpose through LDS is needed); the next tile's loads
+// are issued as soon as this tile's values are converted.  The basis sits in LDS in operand
+// order (see pack_operand16 on the host), rows of a tile permuted so that a lane ends up with
+// 16 consecutive coefficients of its pixel: one 16-byte store of symbols per tile.  The
+// quantizer of tile kt is scheduled between the matrix instructions of tile kt+1.
+// Histogram: interleaved LDS copies per wavefront.
 // ---------------------------------------------------------------------------
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+
 constexpr int kHistLanes = 16;  // histogram copies per wavefront in the narrow-tensor kernel
 constexpr int kFixList = 64;    // values per wavefront waiting for their exact decision
 
@@ -357,13 +366,16 @@ __device__ __forceinline__ void wave_sync_lds() {
 
 struct RowParams {
     const float* x;
-    const float* basis4;  // fwd4 packing
-    const float* mu;      // [Cpad]
-    const float* Trow;    // [C][C] row major, for the exact decisions
+    const uint16_t* basis16;  // fwd16 packing
+    const float* mu;          // [Cpad]
+    const float* Trow;        // [C][C] row major, for the exact decisions
     int64_t P, HW;
     int C, bits;
-    float inv_delta, delta, tau;
-    int64_t n_tiles;      // 32-pixel tiles
+    float inv_delta, delta;
+    float kappa;              // distance to a rounding boundary (in steps) below which a value of a pixel with
+                              // |x - mu|_2 = 1 is decided exactly
+    float tau_min;            // floor of that distance
+    int64_t n_tiles;          // 32-pixel tiles
     uint8_t* syms;
     uint32_t* hist_parts;
     CoderCtrl* ctrl;
@@ -373,8 +385,8 @@ struct RowParams {
 
 template <int NCT, int LAYOUT, bool VEC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_project_quantize_rows(RowParams p) {
-    constexpr int NJ = NCT * 4;
-    extern __shared__ __align__(16) float4 basis4[];  // [NCT][NJ][64], then the histograms
+    constexpr int NJ = NCT * 2;  // steps of 16 channels
+    extern __shared__ __align__(16) uint4 basis16[];  // [NCT][NJ][2][64], then the histograms
     __shared__ __align__(16) float s_mu[NCT * 32];
     __shared__ uint32_t s_fix_list[4][kFixList];
     __shared__ uint32_t s_fix_count[4];
@@ -383,25 +395,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // would serialise up to 64 additions to one word per instruction, and the reads of the basis queue up
     // behind them.
     const int K = 1 << p.bits;
-    uint32_t* whist = reinterpret_cast<uint32_t*>(basis4 + NCT * NJ * 64);  // [4][K * kHistLanes]
+    uint32_t* whist = reinterpret_cast<uint32_t*>(basis16 + NCT * NJ * 2 * 64);  // [4][K * kHistLanes]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
     const int half = lane >> 5, l32 = lane & 31;
     const int C = p.C;
-    // this lane's half of its pixel: xr[4j + i] = x[px][8j + 4h + i]
-    float xr[NJ * 4];
+    // this lane's half of its pixel as loaded: xr[8j + e] = x[px][16j + 8h + e]
+    float xr[NJ * 8];
     auto load_pixels = [&](int64_t tile) {
         const int64_t px = tile * 32 + l32;
         const bool px_ok = px < p.P;
         if constexpr (LAYOUT == FMTC_NHWC && VEC) {
-            const float4* row = reinterpret_cast<const float4*>(p.x + (px_ok ? px : 0) * C) + half;
+            const float4* row = reinterpret_cast<const float4*>(p.x + (px_ok ? px : 0) * C) + 2 * half;
 #pragma unroll
-            for (int j = 0; j < NJ; j++) {
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (px_ok && 8 * j + 4 * half < C) v = row[2 * j];
-                xr[4 * j] = v.x; xr[4 * j + 1] = v.y; xr[4 * j + 2] = v.z; xr[4 * j + 3] = v.w;
-            }
+            for (int j = 0; j < NJ; j++)
+#pragma unroll
+                for (int q = 0; q < 2; q++) {
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (px_ok && 16 * j + 8 * half + 4 * q < C) v = row[4 * j + q];
+                    xr[8 * j + 4 * q] = v.x; xr[8 * j + 4 * q + 1] = v.y;
+                    xr[8 * j + 4 * q + 2] = v.z; xr[8 * j + 4 * q + 3] = v.w;
+                }
         } else {
             int64_t base = 0, stride = 1;
             if constexpr (LAYOUT == FMTC_NHWC) {
@@ -415,9 +430,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
             for (int j = 0; j < NJ; j++)
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    const int c = 8 * j + 4 * half + i;
-                    xr[4 * j + i] = (px_ok && c < C) ? p.x[base + (int64_t)c * stride] : 0.f;
+                for (int e = 0; e < 8; e++) {
+                    const int c = 16 * j + 8 * half + e;
+                    xr[8 * j + e] = (px_ok && c < C) ? p.x[base + (int64_t)c * stride] : 0.f;
                 }
         }
     };
@@ -428,10 +443,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
     // the basis goes from global memory straight into LDS, 16 bytes per lane and instruction
     {
-        const float4* src = reinterpret_cast<const float4*>(p.basis4);
+        const uint4* src = reinterpret_cast<const uint4*>(p.basis16);
 #pragma unroll
         for (int i = 0; i < NCT * NCT; i++)
-            __builtin_amdgcn_global_load_lds(src + tid + 256 * i, &basis4[256 * i + 64 * wave], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(src + tid + 256 * i, &basis16[256 * i + 64 * wave], 16, 0, 0);
     }
     if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
     for (int i = tid; i < 4 * K * kHistLanes; i += 256) whist[i] = 0u;
@@ -439,7 +454,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int zero_sym = 1 << (p.bits - 1);
     const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1), zero_f = (float)zero_sym;
     const float inv_delta = p.inv_delta;
-    const float near_limit = 0.5f - p.tau;
+    const float inv_delta_lo = p.inv_delta * (1.f / 2048.f);
     uint32_t* wh0 = whist + wave * K * kHistLanes;          // this wavefront's histogram, copy 0
     uint32_t* wh = wh0 + (lane & (kHistLanes - 1));         // bin s of this lane's copy: wh[s * kHistLanes]
     uint32_t* fix_list = s_fix_list[wave];
@@ -454,34 +469,56 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (; tile < p.n_tiles; tile += (int64_t)gridDim.x * 4) {
         const int64_t px = tile * 32 + l32;
         const bool px_ok = px < p.P;
-        // mean removed (padding channels hold 0 - 0)
+        // ---- mean removed, split into the two f16 parts (padding channels hold 0 - 0) ----
+        halfx8 xh[NJ], xl[NJ];
+        float n2 = 0.f;
+        auto split = [&](bool clamp) {
+            n2 = 0.f;
 #pragma unroll
-        for (int j = 0; j < NJ; j++) {
-            const float4 m = *reinterpret_cast<const float4*>(&s_mu[8 * j + 4 * half]);
-            xr[4 * j] -= m.x; xr[4 * j + 1] -= m.y; xr[4 * j + 2] -= m.z; xr[4 * j + 3] -= m.w;
-        }
+            for (int j = 0; j < NJ; j++)
+#pragma unroll
+                for (int q = 0; q < 2; q++) {
+                    const float4 m = *reinterpret_cast<const float4*>(&s_mu[16 * j + 8 * half + 4 * q]);
+                    const float mv[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        float v = xr[8 * j + 4 * q + i] - mv[i];
+                        n2 = __builtin_fmaf(v, v, n2);
+                        if (clamp) v = __builtin_amdgcn_fmed3f(v, -60000.f, 60000.f);
+                        const _Float16 vh = (_Float16)v;
+                        xh[j][4 * q + i] = vh;
+                        xl[j][4 * q + i] = (_Float16)((v - (float)vh) * 2048.f);
+                    }
+                }
+        };
+        split(false);
+        n2 += __shfl_xor(n2, 32, 64);  // the other half of the pixel
+        // a pixel too large for f16 (or not finite) is decided exactly, every coefficient of it; its values are
+        // clamped on the way into the matrix cores so that what comes out stays finite
+        const bool force = !(n2 < 1.0e9f);
+        if (__builtin_expect(__any(force), 0)) split(true);
+        const float tau = fminf(fmaxf(p.kappa * __builtin_sqrtf(n2), p.tau_min), 0.125f);
+        const float near_limit = force ? -1.f : 0.5f - tau;
+        // the raw registers are free: the next tile's loads are in flight during this tile's arithmetic
+        const int64_t next_tile = tile + (int64_t)gridDim.x * 4;
+        if (next_tile < p.n_tiles) load_pixels(next_tile);
 
-        auto project_tile = [&](int kt) -> floatx16 {
-            floatx16 acc;
+        auto project_tile = [&](int kt, floatx16& am, floatx16& ac) {
 #pragma unroll
-            for (int r = 0; r < 16; r++) acc[r] = 0.f;
-            float4 a_cur = basis4[(kt * NJ) * 64 + lane];
+            for (int r = 0; r < 16; r++) { am[r] = 0.f; ac[r] = 0.f; }
 #pragma unroll
             for (int j = 0; j < NJ; j++) {
-                float4 a_nxt = a_cur;  // the next step's operand is read while this step's instructions run
-                if (j + 1 < NJ) a_nxt = basis4[(kt * NJ + j + 1) * 64 + lane];
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.x, xr[4 * j], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.y, xr[4 * j + 1], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.z, xr[4 * j + 2], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.w, xr[4 * j + 3], acc, 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                a_cur = a_nxt;
+                const uint4 th4 = basis16[((kt * NJ + j) * 2) * 64 + lane];
+                const uint4 tl4 = basis16[((kt * NJ + j) * 2 + 1) * 64 + lane];
+                const halfx8 th = __builtin_bit_cast(halfx8, th4), tl = __builtin_bit_cast(halfx8, tl4);
+                am = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xh[j], am, 0, 0, 0);
+                ac = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xl[j], ac, 0, 0, 0);
+                ac = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, xh[j], ac, 0, 0, 0);
             }
-            return acc;
         };
         // accumulator r = 4g + i of lane (pixel, h) is coefficient kt*32 + 16h + 4g + i of the pixel.
         // Quantizer, histogram and store of one tile with ragged edges (pixels past P, coefficients past C).
-        auto quantize_tile = [&](const floatx16& acc, int kt, uint32_t (&word)[4]) -> float {
+        auto quantize_tile = [&](const floatx16& am, const floatx16& ac, int kt, uint32_t (&word)[4]) -> float {
             const int k0 = kt * 32 + 16 * half;
             float maxd = 0.f;
 #pragma unroll
@@ -489,7 +526,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 word[g] = 0u;
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
-                    const float t = acc[4 * g + i] * inv_delta;
+                    const float t = __builtin_fmaf(ac[4 * g + i], inv_delta_lo, am[4 * g + i] * inv_delta);
                     const float q = __builtin_rintf(t);  // round half to even
                     maxd = fmaxf(maxd, fabsf(t - q));
                     const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
@@ -507,7 +544,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             }
             return maxd;
         };
-        // ---- exact decision where fp32 can not be trusted (rare) ----
+        // ---- exact decision where the fast pass can not be trusted (rare) ----
         // A tile notes the values that lie too close to a rounding boundary in the wavefront's list: pixel lane,
         // coefficient and the symbol already stored and counted.  When the list is full, and after the last
         // tile of the pixels, the listed values are recomputed in fp64 (same arithmetic as the definition: sum of
@@ -515,7 +552,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         // together, and the stored symbol and the histogram are patched where the decision differs.
         auto resolve_list = [&]() {
             // the symbols that get patched were stored by other lanes of this wavefront: those stores are
-            // acknowledged before the patches go out
+            // acknowledged before the patches go out (this also waits for the next tile's loads; rare)
             __builtin_amdgcn_s_waitcnt(0x0F70);
             const uint32_t n = (uint32_t)__builtin_amdgcn_readfirstlane((int)*fix_count);
             for (uint32_t base = 0; base < n; base += 4) {
@@ -561,20 +598,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             if (lane == 0) *fix_count = 0u;
             wave_sync_lds();
         };
-        auto note_tile = [&](const floatx16& acc, int kt, const uint32_t (&word)[4]) {
+        auto note_tile = [&](const floatx16& am, const floatx16& ac, int kt, const uint32_t (&word)[4]) {
             const int k0 = kt * 32 + 16 * half;
             uint32_t near_mask = 0;
 #pragma unroll
             for (int r = 0; r < 16; r++) {
-                const float t = acc[r] * inv_delta;
-                if (fabsf(t - __builtin_rintf(t)) > near_limit && px_ok && k0 + r < C) near_mask |= 1u << r;
+                const float t = __builtin_fmaf(ac[r], inv_delta_lo, am[r] * inv_delta);
+                if (!(fabsf(t - __builtin_rintf(t)) <= near_limit) && px_ok && k0 + r < C) near_mask |= 1u << r;
             }
             // at most 64 * 16 new entries would not fit: resolve what is there first if this tile could overflow
             const uint32_t incoming = wave_sum((uint32_t)__popc(near_mask));
             if (*fix_count + incoming > (uint32_t)kFixList) resolve_list();
             if (incoming > (uint32_t)kFixList) {
-                // more flagged values than the list holds (a step so fine that fp32 decides almost nothing):
-                // 16 passes, one accumulator each, at most 64 entries per pass
+                // more flagged values than the list holds (a step so fine that the fast pass decides almost
+                // nothing, or pixels out of its range): 16 passes, one accumulator each, at most 64 entries per pass
 #pragma unroll 1
                 for (int r = 0; r < 16; r++) {
                     if ((near_mask >> r) & 1u) {
@@ -601,20 +638,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         };
 
         const bool full = (tile * 32 + 32 <= p.P) && (C == NCT * 32);  // wavefront-uniform
+        floatx16 am, ac;
+        project_tile(0, am, ac);
         if (full) {
             // One wavefront per SIMD: nothing else fills the shadow of the matrix pipe, so the quantizer of tile
-            // kt is issued by hand between the matrix instructions of tile kt + 1 -- after each group of four
-            // (one step of the contraction) the share of the previous tile's 16 values that keeps both in step.
-            floatx16 acc = project_tile(0);
+            // kt is issued between the matrix instructions of tile kt + 1 -- after each step of the contraction
+            // the share of the previous tile's 16 values that keeps both in step.
 #pragma unroll
             for (int kt = 0; kt < NCT; kt++) {
-                floatx16 nxt;
+                floatx16 nm, nc;
 #pragma unroll
-                for (int r = 0; r < 16; r++) nxt[r] = 0.f;
+                for (int r = 0; r < 16; r++) { nm[r] = 0.f; nc[r] = 0.f; }
                 uint32_t word[4] = {0u, 0u, 0u, 0u};
                 float maxd = 0.f;
                 auto quantize_value = [&](int r) {
-                    const float t = acc[r] * inv_delta;
+                    const float t = __builtin_fmaf(ac[r], inv_delta_lo, am[r] * inv_delta);
                     const float q = __builtin_rintf(t);  // round half to even
                     maxd = fmaxf(maxd, fabsf(t - q));
                     const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
@@ -622,19 +660,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                     atomicAdd(&wh[(uint32_t)qc * kHistLanes], 1u);
                 };
                 if (kt + 1 < NCT) {
-                    float4 a_cur = basis4[((kt + 1) * NJ) * 64 + lane];
 #pragma unroll
                     for (int j = 0; j < NJ; j++) {
-                        float4 a_nxt = a_cur;
-                        if (j + 1 < NJ) a_nxt = basis4[((kt + 1) * NJ + j + 1) * 64 + lane];
-                        nxt = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.x, xr[4 * j], nxt, 0, 0, 0);
-                        nxt = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.y, xr[4 * j + 1], nxt, 0, 0, 0);
-                        nxt = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.z, xr[4 * j + 2], nxt, 0, 0, 0);
-                        nxt = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur.w, xr[4 * j + 3], nxt, 0, 0, 0);
+                        const uint4 th4 = basis16[(((kt + 1) * NJ + j) * 2) * 64 + lane];
+                        const uint4 tl4 = basis16[(((kt + 1) * NJ + j) * 2 + 1) * 64 + lane];
+                        const halfx8 th = __builtin_bit_cast(halfx8, th4), tl = __builtin_bit_cast(halfx8, tl4);
+                        nm = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xh[j], nm, 0, 0, 0);
+                        nc = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xl[j], nc, 0, 0, 0);
+                        nc = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, xh[j], nc, 0, 0, 0);
 #pragma unroll
                         for (int r = 16 * j / NJ; r < 16 * (j + 1) / NJ; r++) quantize_value(r);
-                        __builtin_amdgcn_sched_barrier(0);
-                        a_cur = a_nxt;
                     }
                 } else {
 #pragma unroll
@@ -643,23 +678,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 // FULL implies C = 32 * NCT: every lane's 16 symbols are a 16-byte aligned piece of its pixel's row
                 *reinterpret_cast<uint4*>(p.syms + px * C + kt * 32 + 16 * half) =
                     make_uint4(word[0], word[1], word[2], word[3]);
-                if (__builtin_expect(__any(maxd > near_limit), 0)) note_tile(acc, kt, word);
-                acc = nxt;
+                if (__builtin_expect(__any(!(maxd <= near_limit)), 0)) note_tile(am, ac, kt, word);
+                am = nm;
+                ac = nc;
             }
         } else {
-            floatx16 acc = project_tile(0);
 #pragma unroll
             for (int kt = 0; kt < NCT; kt++) {
-                floatx16 nxt;
+                floatx16 nm, nc;
                 uint32_t word[4];
-                if (kt + 1 < NCT) nxt = project_tile(kt + 1);
-                const float maxd = quantize_tile(acc, kt, word);
-                if (__builtin_expect(__any(maxd > near_limit && px_ok), 0)) note_tile(acc, kt, word);
-                if (kt + 1 < NCT) acc = nxt;
+                if (kt + 1 < NCT) project_tile(kt + 1, nm, nc);
+                const float maxd = quantize_tile(am, ac, kt, word);
+                if (__builtin_expect(__any(!(maxd <= near_limit) && px_ok), 0)) note_tile(am, ac, kt, word);
+                if (kt + 1 < NCT) { am = nm; ac = nc; }
             }
         }
         if (*fix_count) resolve_list();
-        if (tile + (int64_t)gridDim.x * 4 < p.n_tiles) load_pixels(tile + (int64_t)gridDim.x * 4);
     }
     __syncthreads();
     // one row of partial counts per workgroup: nothing to clear beforehand, no global atomics
@@ -676,7 +710,7 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
                               int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
     RowParams p;
     p.x = d_x;
-    p.basis4 = b.fwd4;
+    p.basis16 = b.fwd16;
     p.mu = b.mu;
     p.Trow = b.T;
     p.P = P;
@@ -685,10 +719,12 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     p.bits = bits;
     p.inv_delta = (float)(1.0 / (double)delta);
     p.delta = delta;
-    // fp32 accumulation of C terms is off by about sqrt(C) * 2^-24 * |x - mu| / delta steps; values within
-    // tau (a few times that) of a rounding boundary are decided in fp64 instead
-    float tau = 8.f * sqrtf((float)b.Cpad) * 5.9604645e-8f * (float)(1 << (bits - 1));
-    p.tau = fminf(fmaxf(tau, 1.f / 8192.f), 1.f / 128.f);
+    // The fast pass is off by at most about 2^-22 sum |T[k][c]| |x[c] - mu[c]| (three representation errors of
+    // 2^-22 each and the fp32 accumulation) <= |T[k]|_2 |x - mu|_2 times that; values closer than 8 times this
+    // (in steps) to a rounding boundary are decided in fp64 instead.  The floor covers the rounding of the
+    // scaled value itself (magnitude up to 2^(b-1)).
+    p.kappa = 1.9073486e-6f /* 2^-19 */ * b.row_norm * p.inv_delta;
+    p.tau_min = 4.7683716e-7f /* 2^-21 */ * (float)(1 << (bits - 1));
     p.n_tiles = (P + 31) / 32;
     p.syms = d_syms;
     p.hist_parts = cs.hist_parts;

@@ -117,9 +117,11 @@ struct BasisDevice {
     const float* fwd;      // M = T      (row = coefficient k, column = channel c)
     const float* inv;      // M = T^T    (row = channel c, column = coefficient k), inverse slot order
     const float* invf;     // M = T^T, forward slot order
-    const float* inv4;     // M = T^T as [row tile][j][lane][4]: lane (r, h) holds M[tile*32 + r][8j + 4h + i]
-    const float* fwd4;     // M = T in the same order, rows of a tile permuted so that a lane ends up with 16
-                           // consecutive coefficients: lane (r, h) holds M[tile*32 + 16*((r>>2)&1) + 4*(r>>3) + (r&3)][..]
+    // M = T and M = T^T for the narrow-tensor kernels: f16 hi/lo split in the operand order of the 32x32x16
+    // matrix instruction, [row tile][step j][part][lane][8] (see pack_operand16); fwd16 with permuted rows
+    const uint16_t* fwd16;
+    const uint16_t* inv16;
+    float row_norm;        // largest Euclidean norm of a row of T
     const float* mu;       // [Cpad], zero padded
     const float* T;        // [C][C] row major, unpacked
 };
