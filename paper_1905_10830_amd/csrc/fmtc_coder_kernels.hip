@@ -164,19 +164,30 @@ __device__ __forceinline__ void sum_partials(TableLds& L, const uint32_t* __rest
     const int K = 1 << bits;
     if (tid < 256) L.h[tid] = 0u;
     __syncthreads();
-    // a thread owns four neighbouring bins of every rstep-th row; eight independent 16-byte loads in flight
+    // a thread owns four neighbouring bins of every rstep-th row; sixteen independent 16-byte loads in flight
     const int tpr = K / 4, col = tid % tpr, row0 = tid / tpr, rstep = THREADS / tpr;
     const uint4* rows = reinterpret_cast<const uint4*>(hist_parts);
     uint4 acc = make_uint4(0, 0, 0, 0);
     int q = row0;
-    for (; q + 7 * rstep < n_parts; q += 8 * rstep) {
-        uint4 v[8];
+    for (; q + 15 * rstep < n_parts; q += 16 * rstep) {
+        uint4 v[16];
 #pragma unroll
-        for (int j = 0; j < 8; j++) v[j] = rows[(size_t)(q + j * rstep) * tpr + col];
+        for (int j = 0; j < 16; j++) v[j] = rows[(size_t)(q + j * rstep) * tpr + col];
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
+        for (int j = 0; j < 16; j++) {
             acc.x += v[j].x; acc.y += v[j].y; acc.z += v[j].z; acc.w += v[j].w;
         }
+    }
+    if (q < n_parts) {  // the rest, still all in flight together
+        uint4 v[15];
+#pragma unroll
+        for (int j = 0; j < 15; j++)
+            v[j] = (q + j * rstep < n_parts) ? rows[(size_t)(q + j * rstep) * tpr + col] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 15; j++) {
+            acc.x += v[j].x; acc.y += v[j].y; acc.z += v[j].z; acc.w += v[j].w;
+        }
+        q = n_parts;
     }
     for (; q < n_parts; q += rstep) {
         const uint4 v = rows[(size_t)q * tpr + col];
@@ -207,15 +218,18 @@ __device__ __forceinline__ void table_from_hist(TableLds& L, int lane, int K, Ta
         cnt[j] = (64 * j + lane < K) ? L.h[64 * j + lane] : 0u;
         rank[j] = 0;
     }
-    // position of every used symbol in (count, symbol) order (K is a multiple of 4: four counts per LDS read)
-    for (int t = 0; t < K; t += 4) {
-        const uint4 o4 = *reinterpret_cast<const uint4*>(&L.h[t]);
-        const uint32_t o[4] = {o4.x, o4.y, o4.z, o4.w};
+    // position of every used symbol in (count, symbol) order: every count is broadcast from its register in turn
+    // and compared by all lanes
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+    for (int jo = 0; jo < NVS; jo++) {
+        const int tmax = (K - 64 * jo < 64) ? K - 64 * jo : 64;
+        for (int t = 0; t < tmax; t++) {
+            const uint32_t o = (uint32_t)__builtin_amdgcn_readlane((int)cnt[jo], t);
+            const int so = 64 * jo + t;
 #pragma unroll
             for (int j = 0; j < NVS; j++)
-                rank[j] += (o[i] != 0 && (o[i] < cnt[j] || (o[i] == cnt[j] && t + i < 64 * j + lane))) ? 1u : 0u;
+                rank[j] += (o != 0 && (o < cnt[j] || (o == cnt[j] && so < 64 * j + lane))) ? 1u : 0u;
+        }
     }
     int n = 0;
 #pragma unroll
@@ -374,16 +388,22 @@ hipError_t launch_histogram_sum(const uint32_t* d_hist_parts, int n_parts, int b
 }
 
 // ---------------------------------------------------------------------------
-// Packing.  One wavefront per chunk, one lane per run of 64 symbols, the run in
-// registers.  Pass 1 sums the code lengths of the run; the prefix sum over the
-// lanes gives each run's bit offset in the chunk.  The chunk's first payload
-// word is the number of words of all chunks before it: workgroups take their
-// chunk group from a ticket counter (so a group's predecessors are always
-// running already), publish the group's word count, and read back over their
-// predecessors' published counts until they meet one that is already a running
-// total.  Pass 2 appends the codes, least significant stream bit first, into an
-// LDS image of the chunk that leaves with full-width stores.  A chunk larger
-// than the image is produced in several windows.
+// Packing.  One wavefront per chunk, in ONE pass over the symbols: the wavefront walks the
+// chunk in steps of 256 consecutive symbols (lane l holds symbols 4l .. 4l+3 of the step, one
+// 4-byte load), looks the codes up, joins the codes of a lane into one value of at most 64
+// bits, and a prefix sum over the lanes (row shifts and row broadcasts, no LDS) gives every
+// lane its bit position; the value is ORed into an LDS image of the chunk.  The prefix sum
+// also yields the bit count of every run of 64 symbols, which the container stores so that 64
+// lanes can decode a chunk.  (A table with codes longer than 32 bits takes one symbol per lane
+// and step instead.)
+// Workgroups are persistent: the grid never exceeds what the device holds at once and
+// workgroup w takes the chunk groups w, w + grid, ... in turn, so every predecessor of a group
+// is either finished or being worked on by a resident workgroup.  The chunk's first payload
+// word is the number of words of all chunks before it: a workgroup publishes its group's word
+// count and reads back over its predecessors' published counts until it meets one that is
+// already a running total.  The image of the first window is built before that position is
+// known and leaves with full-width stores.  A chunk larger than the image is produced in
+// several windows.
 // ---------------------------------------------------------------------------
 constexpr int kStageWords = 2048;  // per wavefront: 64 Kbit, i.e. 16 bits/symbol over a 4096-symbol chunk
 constexpr unsigned long long kFlagAggregate = 1ull << 32, kFlagInclusive = 2ull << 32;
@@ -406,126 +426,189 @@ struct PackParams {
     uint64_t* out_bytes;
 };
 
-// Appends the codes of one run (`cnt` symbols, 64 at most, four per register of w) to the image, starting at
-// bit `start` of the chunk.  FULL: cnt == 64.  LONG: codes may exceed 32 bits.
-template <bool FULL, bool LONG>
-__device__ __forceinline__ void pack_run(const uint32_t (&w)[16], uint32_t cnt, uint32_t start,
-                                         const unsigned long long* tab, uint32_t* img, uint32_t win,
-                                         uint32_t win_words) {
-    uint32_t nb = start & 31, widx = start >> 5;
-    auto emit = [&](uint32_t word) {
-        const uint32_t rel = widx - win;
-        if (rel < win_words) atomicOr(&img[rel], word);
-        widx++;
-    };
-    if constexpr (!LONG) {
-        uint32_t lo = 0;
-#pragma unroll
-        for (int q = 0; q < 16; q++) {
-            // the four table reads do not depend on the bit position: they are in flight together
-            unsigned long long e[4];
-#pragma unroll
-            for (int b = 0; b < 4; b++) e[b] = tab[(w[q] >> (8 * b)) & 255u];
-#pragma unroll
-            for (int b = 0; b < 4; b++) {
-                if (FULL || (uint32_t)(4 * q + b) < cnt) {
-                    const uint32_t code = (uint32_t)e[b], len = (uint32_t)(e[b] >> 56);
-                    lo |= code << nb;
-                    const uint32_t hi = (code >> 1) >> (31 - nb);  // bits of the code that do not fit the word
-                    nb += len;
-                    if (nb >= 32) {
-                        emit(lo);
-                        lo = hi;
-                        nb -= 32;
-                    }
-                }
-            }
-        }
-        if (nb) emit(lo);
+// x + (x of the lane the control word names), 0 where that lane does not exist or the row is masked out
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_add(uint32_t x) {
+    return x + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xf, false);
+}
+// Inclusive prefix sum over the 64 lanes.  row: the sum within the lane's row of 16 lanes (lane 15 of a row
+// holds the row total); half: the sum within the lane's half of the wavefront (lanes 31 and 63 hold the totals).
+__device__ __forceinline__ uint32_t wave_inclusive_scan_rows(uint32_t v, uint32_t& row, uint32_t& half) {
+    v = dpp_add<0x111, 0xf>(v);  // row_shr:1
+    v = dpp_add<0x112, 0xf>(v);  // row_shr:2
+    v = dpp_add<0x114, 0xf>(v);  // row_shr:4
+    v = dpp_add<0x118, 0xf>(v);  // row_shr:8
+    row = v;
+    v = dpp_add<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+    half = v;
+    v = dpp_add<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// ORs the bits of `c` (zero above its length) into the image at bit `pos` of the chunk.  The image is followed
+// by spare words: ORing zeros does no harm, so nothing here branches per lane.
+//   FIRST window: positions are cut off at the end of the image, what lies beyond lands in the spare words;
+//   later windows (rare): every word is checked against the window.
+// third: some lane's bits reach into a third word (wavefront-uniform).
+template <bool FIRST>
+__device__ __forceinline__ void place_bits(unsigned long long c, uint32_t pos, uint32_t* img, uint32_t win,
+                                           uint32_t win_words, bool third) {
+    const unsigned long long t0 = (unsigned long long)(uint32_t)c << (pos & 31u);
+    const unsigned long long t1 = ((unsigned long long)(uint32_t)(c >> 32) << (pos & 31u)) | (t0 >> 32);
+    if constexpr (FIRST) {
+        const uint32_t widx = (pos < (uint32_t)kStageWords * 32u ? pos : (uint32_t)kStageWords * 32u) >> 5;
+        atomicOr(&img[widx], (uint32_t)t0);
+        atomicOr(&img[widx + 1u], (uint32_t)t1);
+        if (third) atomicOr(&img[widx + 2u], (uint32_t)(t1 >> 32));
     } else {
-        unsigned long long acc = 0;
-        auto put = [&](unsigned long long code, uint32_t len) {  // len <= 32, nb < 32
-            acc |= code << nb;
-            nb += len;
-            if (nb >= 32) {
-                emit((uint32_t)acc);
-                acc >>= 32;
-                nb -= 32;
-            }
-        };
-#pragma unroll 1
-        for (uint32_t i = 0; i < cnt; i++) {
-            uint32_t word = 0;
-#pragma unroll
-            for (int q = 0; q < 16; q++) word = ((i >> 2) == (uint32_t)q) ? w[q] : word;
-            const unsigned long long e = tab[(word >> (8 * (i & 3))) & 255u];
-            const uint32_t len = (uint32_t)(e >> 56);
-            const unsigned long long code = e & 0x00ffffffffffffffull;
-            if (len > 32) {
-                put(code & 0xffffffffull, 32);
-                put(code >> 32, len - 32);
-            } else {
-                put(code, len);
-            }
-        }
-        if (nb) emit((uint32_t)acc);
+        const uint32_t rel = (pos >> 5) - win;
+        const uint32_t i0 = rel < win_words ? rel : (uint32_t)kStageWords;
+        const uint32_t i1 = rel + 1u < win_words ? rel + 1u : (uint32_t)kStageWords;
+        const uint32_t i2 = rel + 2u < win_words ? rel + 2u : (uint32_t)kStageWords;
+        atomicOr(&img[i0], (uint32_t)t0);
+        atomicOr(&img[i1], (uint32_t)t1);
+        atomicOr(&img[i2], (uint32_t)(t1 >> 32));
     }
 }
 
-// kPackWaves chunks per workgroup: one wavefront per chunk, one lane per run of 64 symbols.
+// One chunk (`clen` symbols, in w: register q of lane l holds symbols 256q + 4l .. + 3) into the window
+// [win, win + win_words) of its image.  Returns the chunk's code bits; with run_bits != NULL also stores the bit
+// count of each of the n_runs runs of 64 symbols there.
+//   LONG = false (codes of at most 32 bits): a lane joins its four symbols of a step; in the rare step where
+//   some lane's four codes exceed 64 bits the wavefront places them as two halves.
+//   LONG = true: one symbol per lane and step.
+// The loop over the registers is a real loop (the register file has no indexed access: the working copy is
+// rotated by four registers per turn instead).
+template <bool LONG, bool FIRST>
+__device__ __forceinline__ uint32_t pack_chunk(const uint32_t (&w)[16], uint32_t clen,
+                                               const unsigned long long* tab, uint32_t* img, uint32_t win,
+                                               uint32_t win_words, int lane, uint16_t* run_bits, uint32_t n_runs) {
+    uint32_t r[16];
+#pragma unroll
+    for (int q = 0; q < 16; q++) r[q] = w[q];
+    uint32_t base = 0;  // code bits of the symbols before this step
+    const uint32_t n_regs = (clen + 255u) >> 8;
+#pragma unroll 1
+    for (uint32_t q4 = 0; q4 < n_regs; q4 += 4) {
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const uint32_t q = q4 + k;
+            if (q >= n_regs) break;  // wavefront-uniform
+            if constexpr (!LONG) {
+                const uint32_t first = 256u * q + 4u * (uint32_t)lane;  // this lane's first symbol
+                unsigned long long e[4];
+                if (256u * (q + 1) <= clen) {
+#pragma unroll
+                    for (int i = 0; i < 4; i++) e[i] = tab[(r[k] >> (8 * i)) & 255u];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; i++) e[i] = (first + i < clen) ? tab[(r[k] >> (8 * i)) & 255u] : 0ull;
+                }
+                const uint32_t l0 = (uint32_t)(e[0] >> 56), l1 = (uint32_t)(e[1] >> 56);
+                const uint32_t l2 = (uint32_t)(e[2] >> 56), l3 = (uint32_t)(e[3] >> 56);
+                const unsigned long long lo = (unsigned long long)(uint32_t)e[0] | ((unsigned long long)(uint32_t)e[1] << l0);
+                const unsigned long long hi = (unsigned long long)(uint32_t)e[2] | ((unsigned long long)(uint32_t)e[3] << l2);
+                const uint32_t l01 = l0 + l1, len = l01 + l2 + l3;
+                uint32_t row, half;
+                const uint32_t incl = wave_inclusive_scan_rows(len, row, half);
+                const uint32_t pos = base + incl - len;
+                if (__builtin_expect(__any(len > 64u), 0)) {
+                    place_bits<FIRST>(lo, pos, img, win, win_words, true);
+                    place_bits<FIRST>(hi, pos + l01, img, win, win_words, true);
+                } else {
+                    // l01 = 64 leaves no bits in hi
+                    const unsigned long long c = lo | (hi << (l01 & 63u));
+                    place_bits<FIRST>(c, pos, img, win, win_words, __any(len + (pos & 31u) > 64u) != 0);
+                }
+                if (run_bits) {  // a run of 64 symbols is a row of 16 lanes
+                    const uint32_t run = 4u * q + (uint32_t)(lane >> 4);
+                    if ((lane & 15) == 15 && run < n_runs) run_bits[run] = (uint16_t)row;
+                }
+                base += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    // symbol 64u + l of the step sits in lane 16u + l/4, byte l%4
+                    const uint32_t first = 256u * q + 64u * u + (uint32_t)lane;
+                    const uint32_t v = (uint32_t)__shfl((int)r[k], 16 * u + (lane >> 2), 64) >> (8 * (lane & 3));
+                    const unsigned long long e0 = (first < clen) ? tab[v & 255u] : 0ull;
+                    const uint32_t len = (uint32_t)(e0 >> 56);
+                    uint32_t row, half;
+                    const uint32_t incl = wave_inclusive_scan_rows(len, row, half);
+                    place_bits<FIRST>(e0 & 0x00ffffffffffffffull, base + incl - len, img, win, win_words, true);
+                    const uint32_t run = 4u * q + (uint32_t)u;
+                    if (run_bits && lane == 63 && run < n_runs) run_bits[run] = (uint16_t)incl;
+                    base += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 12; k++) r[k] = r[k + 4];
+    }
+    // runs of a short chunk that hold no symbol (the steps above stop at the chunk's end)
+    if (run_bits)
+        for (uint32_t run = 4u * n_regs + (uint32_t)lane; run < n_runs; run += 64) run_bits[run] = 0;
+    return base;
+}
+
+// kPackWaves chunks per group: one wavefront per chunk.
 template <bool BUILD>
-__global__ __launch_bounds__(256) void k_pack(PackParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_pack(PackParams p) {
     static_assert(kPackWaves == 4, "one chunk per wavefront of the 256-thread workgroup");
     __shared__ unsigned long long tab[256];
-    __shared__ __align__(16) uint32_t stage[kPackWaves][kStageWords];
+    __shared__ __align__(16) uint32_t stage[kPackWaves][kStageWords + 4];  // image + the spare word
     __shared__ uint32_t wave_words[kPackWaves];
-    __shared__ uint32_t s_group, s_excl, s_max_len;
+    __shared__ uint32_t s_excl, s_max_len;
     __shared__ unsigned long long s_payload_bits;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
-    if (tid == 0) s_group = __hip_atomic_fetch_add(&p.ctrl->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool aligned4 = (p.chunk_syms & 3u) == 0;  // every chunk starts on a 4-byte boundary of the symbols
+
+    // the symbols of a chunk: register q of lane l holds symbols 256q + 4l .. + 3 (zero past the chunk's end)
+    auto chunk_len = [&](uint32_t ch) -> uint32_t {
+        if (ch >= p.n_chunks) return 0u;
+        const uint64_t c0 = (uint64_t)ch * p.chunk_syms;
+        return (uint32_t)((p.V - c0 < p.chunk_syms) ? (p.V - c0) : p.chunk_syms);
+    };
+    auto load_chunk = [&](uint32_t ch, uint32_t (&w)[16]) {
+        const uint32_t clen = chunk_len(ch);
+        const uint8_t* src = p.syms + (uint64_t)ch * p.chunk_syms;
+        if (aligned4) {
+#pragma unroll
+            for (int q = 0; q < 16; q++) {
+                const uint32_t o = 256u * q + 4u * (uint32_t)lane;
+                w[q] = (o + 4u <= clen) ? *reinterpret_cast<const uint32_t*>(src + o) : 0u;
+            }
+            if (clen & 3u) {  // the last, partial word of the tensor
+                const uint32_t t = clen & ~3u;
+                uint32_t v = 0;
+                if ((uint32_t)lane == ((t >> 2) & 63u))
+                    for (uint32_t i = 0; i < (clen & 3u); i++) v |= (uint32_t)src[t + i] << (8 * i);
+#pragma unroll
+                for (int q = 0; q < 16; q++)
+                    if ((uint32_t)q == (t >> 8)) w[q] |= v;
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 16; q++) {
+                const uint32_t o = 256u * q + 4u * (uint32_t)lane;
+                w[q] = 0u;
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    if (o + i < clen) w[q] |= (uint32_t)src[o + i] << (8 * i);
+                __builtin_amdgcn_sched_barrier(0);  // one register's loads at a time: this path is rare
+            }
+        }
+    };
+    uint32_t w[16];
+    uint32_t group = blockIdx.x;  // the grid never has more workgroups than groups
+    load_chunk(group * kPackWaves + (uint32_t)wave, w);  // in flight while the table is made
+
     TableLds& L = *reinterpret_cast<TableLds*>(&stage[0][0]);  // shares LDS with the chunk images, not in use yet
     static_assert(sizeof(TableLds) <= sizeof(stage), "table scratch must fit the chunk images");
     if constexpr (BUILD) {
         sum_partials<256>(L, p.hist_parts, p.n_parts, p.bits);
-    } else {
-        tab[tid] = p.enc_table[tid];
-        if (tid == 0) {
-            s_max_len = p.ctrl->max_len;
-            s_payload_bits = p.ctrl->payload_bits;
-        }
-        __syncthreads();
-    }
-    const uint32_t group = s_group;
-    if (group >= p.n_groups) return;  // not reachable: the grid has n_groups workgroups
-    const uint32_t ch = group * kPackWaves + (uint32_t)wave;
-    const bool have = ch < p.n_chunks;
-
-    // ---- the run: 64 symbols in 16 registers (the loads are in flight while wavefront 0 builds the table) ----
-    uint32_t w[16];
-#pragma unroll
-    for (int q = 0; q < 16; q++) w[q] = 0;
-    uint32_t cnt = 0;
-    if (have) {
-        const uint64_t c0 = (uint64_t)ch * p.chunk_syms;
-        const uint64_t c1 = (c0 + p.chunk_syms < p.V) ? c0 + p.chunk_syms : p.V;
-        const uint64_t r0 = c0 + (uint64_t)lane * kSubSyms;
-        cnt = (r0 < c1) ? (uint32_t)((c1 - r0 < kSubSyms) ? (c1 - r0) : kSubSyms) : 0u;
-        if (cnt == kSubSyms && ((uintptr_t)(p.syms + r0) & 15) == 0) {
-            const uint4* src = reinterpret_cast<const uint4*>(p.syms + r0);
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                const uint4 v = src[j];
-                w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < kSubSyms; i++)
-                if ((uint32_t)i < cnt) w[i >> 2] |= (uint32_t)p.syms[r0 + i] << (8 * (i & 3));
-        }
-    }
-    if constexpr (BUILD) {
         if (wave == 0) {
             TableOut out;
             out.entry = tab;
@@ -536,150 +619,173 @@ __global__ __launch_bounds__(256) void k_pack(PackParams p) {
             }
         }
         __syncthreads();
-        if (group == 0) p.stream[kHeaderBytes + tid] = (uint8_t)(tab[tid] >> 56);  // the container's length table
-    }
-    const bool long_codes = s_max_len > 32;
-    const bool all_full = __all(cnt == (uint32_t)kSubSyms || cnt == 0u) != 0;
-
-    // ---- pass 1: code bits of the run ----
-    uint32_t bits = 0;
-    if (all_full) {
-        if (cnt) {
-            uint32_t part[4] = {0u, 0u, 0u, 0u};  // four independent sums
-#pragma unroll
-            for (int q = 0; q < 16; q++)
-#pragma unroll
-                for (int b = 0; b < 4; b++) part[b] += (uint32_t)(tab[(w[q] >> (8 * b)) & 255u] >> 56);
-            bits = (part[0] + part[1]) + (part[2] + part[3]);
-        }
+        if (blockIdx.x == 0) p.stream[kHeaderBytes + tid] = (uint8_t)(tab[tid] >> 56);  // the container's length table
     } else {
-#pragma unroll
-        for (int q = 0; q < 16; q++)
-#pragma unroll
-            for (int b = 0; b < 4; b++)
-                if ((uint32_t)(4 * q + b) < cnt) bits += (uint32_t)(tab[(w[q] >> (8 * b)) & 255u] >> 56);
-    }
-    if (have) {
-        uint16_t* sub_bits = reinterpret_cast<uint16_t*>(p.stream + p.off_sub_bits);
-        if ((uint32_t)lane < p.subs_per_chunk) sub_bits[(size_t)ch * p.subs_per_chunk + lane] = (uint16_t)bits;
-    }
-    const uint32_t start = wave_exclusive_scan(bits, lane);
-    const uint32_t total_bits = __shfl(start + bits, 63, 64);
-    const uint32_t n_words = (total_bits + 31) >> 5;
-    if (lane == 0) wave_words[wave] = n_words;
-    __syncthreads();  // also: nobody reads the table scratch any more, the images may be written
-    uint32_t agg = 0;
-#pragma unroll
-    for (int q = 0; q < kPackWaves; q++) agg += wave_words[q];
-    if (tid == 0) publish64(&p.lookback[group], (group == 0 ? kFlagInclusive : kFlagAggregate) | agg);
-
-    // ---- pass 2 for the first window: needs no global position, so it runs while the predecessors publish ----
-    uint32_t* img = stage[wave];
-    const uint32_t first_word = start >> 5, last_word = (start + bits + 31) >> 5;  // [first, last)
-    auto build_window = [&](uint32_t win, uint32_t win_words) {
-        for (uint32_t i = lane; i < win_words; i += 64) img[i] = 0u;
-        wave_sync();  // the zeros land before the ORs below: one wavefront, LDS in order
-        if (cnt && bits && first_word < win + win_words && last_word > win) {
-            if (long_codes) pack_run<false, true>(w, cnt, start, tab, img, win, win_words);
-            else if (all_full) pack_run<true, false>(w, cnt, start, tab, img, win, win_words);
-            else pack_run<false, false>(w, cnt, start, tab, img, win, win_words);
+        tab[tid] = p.enc_table[tid];
+        if (tid == 0) {
+            s_max_len = p.ctrl->max_len;
+            s_payload_bits = p.ctrl->payload_bits;
         }
-        wave_sync();  // the ORs of all lanes precede the reads that follow
-    };
-    const uint32_t win0_words = n_words < (uint32_t)kStageWords ? n_words : (uint32_t)kStageWords;
-    if (have && n_words) build_window(0, win0_words);
+        __syncthreads();
+    }
+    const uint32_t max_len = s_max_len;
+    uint32_t* img = stage[wave];
+    // nobody reads the table scratch any more: the images start out clear
+    for (int i = lane; i < kStageWords; i += 64) img[i] = 0u;
+    wave_sync();
+    uint16_t* sub_bits = reinterpret_cast<uint16_t*>(p.stream + p.off_sub_bits);
+    uint32_t* chunk_off = reinterpret_cast<uint32_t*>(p.stream + kHeaderBytes + kLenTableBytes);
 
-    // ---- the group's first payload word: the words of all groups before it ----
-    if (wave == 0 && group != 0) {
-        // windows of 256 predecessors, nearest first; lane l reads four of them
-        uint32_t excl = 0;
-        uint32_t top = group;  // predecessors [0, top) are still to be accounted for
-        bool failed = false;
-        while (top > 0) {
-            uint32_t sum = 0;
-            bool found = false;  // met a running total: everything before it is included
-            bool ready = false;
-            for (uint32_t tries = 0; tries < kSpinLimit; tries++) {
-                unsigned long long e[4];
+    for (; group < p.n_groups; group += gridDim.x) {
+        const uint32_t ch = group * kPackWaves + (uint32_t)wave;
+        const bool have = ch < p.n_chunks;
+        const uint32_t clen = chunk_len(ch);
+
+        // ---- the first window of the chunk's image: needs no global position ----
+        // (the image is all zero here: cleared once at the start and again by whoever reads a word out)
+        auto build_window = [&](uint32_t win, uint32_t win_words, uint16_t* run_bits) -> uint32_t {
+            uint32_t total;
+            const uint32_t n_runs = p.subs_per_chunk;
+            if (win == 0) {
+                if (max_len <= 32) total = pack_chunk<false, true>(w, clen, tab, img, win, win_words, lane, run_bits, n_runs);
+                else total = pack_chunk<true, true>(w, clen, tab, img, win, win_words, lane, run_bits, n_runs);
+            } else {
+                if (max_len <= 32) total = pack_chunk<false, false>(w, clen, tab, img, win, win_words, lane, run_bits, n_runs);
+                else total = pack_chunk<true, false>(w, clen, tab, img, win, win_words, lane, run_bits, n_runs);
+            }
+            wave_sync();  // the ORs of all lanes precede the reads that follow
+            return total;
+        };
+        uint32_t n_words = 0;
+        if (have) {
+            const uint32_t total_bits = build_window(0, kStageWords, sub_bits + (size_t)ch * p.subs_per_chunk);
+            n_words = (total_bits + 31) >> 5;
+        }
+        if (lane == 0) wave_words[wave] = n_words;
+        __syncthreads();
+        uint32_t agg = 0;
 #pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    const uint32_t back = 4u * (uint32_t)lane + (uint32_t)j + 1u;  // distance to the predecessor
-                    e[j] = (back <= top) ? peek64(&p.lookback[top - back]) : kFlagAggregate;
-                }
-                sum = 0;
-                found = false;
-                bool ok = true;
+        for (int q = 0; q < kPackWaves; q++) agg += wave_words[q];
+        if (tid == 0) publish64(&p.lookback[group], (group == 0 ? kFlagInclusive : kFlagAggregate) | agg);
+
+        // the next group's symbols are on their way during the wait for the position and the stores
+        uint32_t wn[16];
+        const uint32_t next_group = group + gridDim.x;
+        if (next_group < p.n_groups) load_chunk(next_group * kPackWaves + (uint32_t)wave, wn);
+
+        // ---- the group's first payload word: the words of all groups before it ----
+        if (wave == 0 && group != 0) {
+            // windows of 256 predecessors, nearest first; lane l reads four of them
+            uint32_t excl = 0;
+            uint32_t top = group;  // predecessors [0, top) are still to be accounted for
+            bool failed = false;
+            while (top > 0) {
+                uint32_t sum = 0;
+                bool found = false;  // met a running total: everything before it is included
+                bool ready = false;
+                for (uint32_t tries = 0; tries < kSpinLimit; tries++) {
+                    unsigned long long e[4];
 #pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    if (!found) {
-                        if (e[j] == 0) ok = false;
-                        sum += (uint32_t)e[j];
-                        found = (e[j] & kFlagInclusive) != 0;
+                    for (int j = 0; j < 4; j++) {
+                        const uint32_t back = 4u * (uint32_t)lane + (uint32_t)j + 1u;  // distance to the predecessor
+                        e[j] = (back <= top) ? peek64(&p.lookback[top - back]) : kFlagAggregate;
                     }
+                    sum = 0;
+                    found = false;
+                    bool ok = true;
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        if (!found) {
+                            if (e[j] == 0) ok = false;
+                            sum += (uint32_t)e[j];
+                            found = (e[j] & kFlagInclusive) != 0;
+                        }
+                    }
+                    // entries behind a running total need not be there yet
+                    const unsigned long long fm = __ballot(found);
+                    const unsigned long long need = fm ? ((2ull << (__ffsll((long long)fm) - 1)) - 1ull) : ~0ull;
+                    if ((__ballot(!ok) & need) == 0) {
+                        ready = true;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
                 }
-                // entries behind a running total need not be there yet
-                const unsigned long long fm = __ballot(found);
-                const unsigned long long need = fm ? ((2ull << (__ffsll((long long)fm) - 1)) - 1ull) : ~0ull;
-                if ((__ballot(!ok) & need) == 0) {
-                    ready = true;
+                if (!ready) {
+                    failed = true;
                     break;
                 }
-                __builtin_amdgcn_s_sleep(2);
+                const unsigned long long fmask = __ballot(found);
+                const int first = fmask ? (__ffsll((long long)fmask) - 1) : 64;  // lanes beyond it are not needed
+                const uint32_t part = (lane <= first) ? sum : 0u;
+                excl += wave_sum(part);
+                if (fmask) break;
+                top = (top > 256u) ? top - 256u : 0u;
             }
-            if (!ready) {
-                failed = true;
-                break;
+            if (failed) {
+                if (lane == 0) p.ctrl->error = 1u;
+                excl = 0;
             }
-            const unsigned long long fmask = __ballot(found);
-            const int first = fmask ? (__ffsll((long long)fmask) - 1) : 64;  // lanes beyond it are not needed
-            const uint32_t part = (lane <= first) ? sum : 0u;
-            excl += wave_sum(part);
-            if (fmask) break;
-            top = (top > 256u) ? top - 256u : 0u;
+            if (lane == 0) {
+                publish64(&p.lookback[group], kFlagInclusive | (unsigned long long)(excl + agg));
+                s_excl = excl;
+            }
+        } else if (tid == 0) {
+            s_excl = 0;
         }
-        if (failed) {
-            if (lane == 0) p.ctrl->error = 1u;
-            excl = 0;
+        __syncthreads();
+        if (have) {
+            uint32_t word0 = s_excl;
+            for (int q = 0; q < wave; q++) word0 += wave_words[q];
+            if (lane == 0) {
+                chunk_off[ch] = word0;
+                if (ch == p.n_chunks - 1) {
+                    const uint64_t total_words = (uint64_t)word0 + n_words;
+                    chunk_off[p.n_chunks] = (uint32_t)total_words;
+                    Header hdr = p.hdr;
+                    hdr.payload_words = total_words;
+                    hdr.payload_bits = s_payload_bits;
+                    if (p.ctrl->error) hdr.magic = 0u;  // a wait gave up: the stream is not valid
+                    *reinterpret_cast<Header*>(p.stream) = hdr;
+                    if (p.out_bytes) *p.out_bytes = (uint64_t)p.off_payload + 4 * total_words;
+                    // alignment gaps between the sections are part of the stream: keep them zero
+                    for (size_t o = kHeaderBytes + kLenTableBytes + 4 * ((size_t)p.n_chunks + 1); o < p.off_sub_bits; o++)
+                        p.stream[o] = 0;
+                    for (size_t o = p.off_sub_bits + 2 * (size_t)p.n_chunks * p.subs_per_chunk; o < p.off_payload; o++)
+                        p.stream[o] = 0;
+                }
+            }
+            // ---- the image leaves with full-width stores; further windows (rare) are built and stored in turn ----
+            uint32_t* out = reinterpret_cast<uint32_t*>(p.stream + p.off_payload) + word0;
+            for (uint32_t win = 0; win < n_words; win += kStageWords) {
+                const uint32_t win_words = (n_words - win < (uint32_t)kStageWords) ? n_words - win : (uint32_t)kStageWords;
+                if (win) build_window(win, win_words, nullptr);
+                for (uint32_t i = lane; i < win_words; i += 64) {
+                    out[win + i] = img[i];
+                    img[i] = 0u;
+                }
+                wave_sync();  // the image is read and clear before the next window or chunk writes it
+            }
         }
-        if (lane == 0) {
-            publish64(&p.lookback[group], kFlagInclusive | (unsigned long long)(excl + agg));
-            s_excl = excl;
-        }
-    } else if (tid == 0) {
-        s_excl = 0;
+        __syncthreads();  // wave_words and s_excl are rewritten by the next group
+#pragma unroll
+        for (int q = 0; q < 16; q++) w[q] = wn[q];
     }
-    __syncthreads();
-    if (!have) return;  // whole wavefront leaves; no workgroup barrier follows
-    uint32_t word0 = s_excl;
-    for (int q = 0; q < wave; q++) word0 += wave_words[q];
-    uint32_t* chunk_off = reinterpret_cast<uint32_t*>(p.stream + kHeaderBytes + kLenTableBytes);
-    if (lane == 0) {
-        chunk_off[ch] = word0;
-        if (ch == p.n_chunks - 1) {
-            const uint64_t total_words = (uint64_t)word0 + n_words;
-            chunk_off[p.n_chunks] = (uint32_t)total_words;
-            Header hdr = p.hdr;
-            hdr.payload_words = total_words;
-            hdr.payload_bits = s_payload_bits;
-            if (p.ctrl->error) hdr.magic = 0u;  // a wait gave up: the stream is not valid
-            *reinterpret_cast<Header*>(p.stream) = hdr;
-            if (p.out_bytes) *p.out_bytes = (uint64_t)p.off_payload + 4 * total_words;
-            // alignment gaps between the sections are part of the stream: keep them zero
-            for (size_t o = kHeaderBytes + kLenTableBytes + 4 * ((size_t)p.n_chunks + 1); o < p.off_sub_bits; o++)
-                p.stream[o] = 0;
-            for (size_t o = p.off_sub_bits + 2 * (size_t)p.n_chunks * p.subs_per_chunk; o < p.off_payload; o++)
-                p.stream[o] = 0;
-        }
-    }
+}
 
-    // ---- the image leaves with full-width stores; further windows (rare) are built and stored in turn ----
-    uint32_t* out = reinterpret_cast<uint32_t*>(p.stream + p.off_payload) + word0;
-    for (uint32_t win = 0; win < n_words; win += kStageWords) {
-        const uint32_t win_words = (n_words - win < (uint32_t)kStageWords) ? n_words - win : (uint32_t)kStageWords;
-        if (win) build_window(win, win_words);
-        for (uint32_t i = lane; i < win_words; i += 64) out[win + i] = img[i];
-        wave_sync();  // all lanes have read the image before the next window clears it
-    }
+// Number of workgroups of the pack kernel the device holds at once (queried once per kernel variant).
+template <bool BUILD>
+static int pack_resident_groups() {
+    static int cached = 0;
+    if (cached) return cached;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_pack<BUILD>, 256, 0) != hipSuccess || cus < 1 ||
+        per_cu < 1)
+        return 64;  // conservative: any device this library runs on holds 64 workgroups
+    if (per_cu > 4) per_cu = 4;
+    cached = cus * per_cu;
+    return cached;
 }
 
 // Table (a kernel of its own only where every pack workgroup building it would cost more than the launch)
@@ -716,14 +822,17 @@ hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, floa
     p.stream = d_stream;
     p.out_bytes = d_out_bytes;
     static const char* knob = getenv("FMTC_TABLE_IN_PACK");
-    const bool build_in_pack = knob ? (knob[0] == '1') : cs.n_groups <= 512;
+    // every pack workgroup sums the partial histograms itself while that is at most 64 KB to read
+    const bool build_in_pack = knob ? (knob[0] == '1') : ((size_t)n_parts << bits) * 4 <= 64 * 1024;
     if (!build_in_pack) {
         hipError_t e = launch(K_TABLE, k_huffman_table, dim3(1), dim3(1024), 0, s, (const uint32_t*)cs.hist_parts,
                               n_parts, bits, (uint32_t*)nullptr, d_enc_table, d_stream + kHeaderBytes, cs.ctrl);
         if (e != hipSuccess) return e;
-        return launch(K_PACK, k_pack<false>, dim3(cs.n_groups), dim3(256), 0, s, p);
+        const uint32_t cap = (uint32_t)pack_resident_groups<false>();
+        return launch(K_PACK, k_pack<false>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
     }
-    return launch(K_PACK, k_pack<true>, dim3(cs.n_groups), dim3(256), 0, s, p);
+    const uint32_t cap = (uint32_t)pack_resident_groups<true>();
+    return launch(K_PACK, k_pack<true>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
 }
 
 }  // namespace fmtc
