@@ -33,6 +33,7 @@ struct TableLds {
     uint16_t int_parent[256];   // ... each internal node (numbered in creation order); then its 2^r-th ancestor
     uint16_t depth[256];        // of the internal nodes
     uint8_t len_sorted[256];    // code length of the sorted leaves
+    uint32_t rank[256];         // position of every used symbol in (count, symbol) order
 };
 
 // one value of a per-lane array spread over NV registers (64 entries each); idx is wavefront-uniform
@@ -162,7 +163,10 @@ __device__ __forceinline__ void sum_partials(TableLds& L, const uint32_t* __rest
                                              int bits) {
     const int tid = threadIdx.x;
     const int K = 1 << bits;
-    if (tid < 256) L.h[tid] = 0u;
+    if (tid < 256) {
+        L.h[tid] = 0u;
+        L.rank[tid] = 0u;
+    }
     __syncthreads();
     // a thread owns four neighbouring bins of every rstep-th row; sixteen independent 16-byte loads in flight
     const int tpr = K / 4, col = tid % tpr, row0 = tid / tpr, rstep = THREADS / tpr;
@@ -200,6 +204,28 @@ __device__ __forceinline__ void sum_partials(TableLds& L, const uint32_t* __rest
     __syncthreads();
 }
 
+// Position of every used symbol in (count, symbol) order, into L.rank (zero on entry): the comparisons are shared
+// out over all wavefronts of the workgroup, wavefront w taking the w-th slice of the symbols to compare against.
+// All THREADS threads call it, after sum_partials; ends with a barrier.
+template <int THREADS>
+__device__ __forceinline__ void rank_symbols(TableLds& L, int bits) {
+    constexpr int NW = THREADS / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int K = 1 << bits;
+    const int per = (K + NW - 1) / NW;
+    const int t0 = wave * per, t1 = (t0 + per < K) ? t0 + per : K;
+    for (int s = lane; s < K; s += 64) {
+        const uint32_t cnt = L.h[s];
+        uint32_t r = 0;
+        for (int t = t0; t < t1; t++) {
+            const uint32_t o = L.h[t];  // same address in all lanes: a broadcast
+            r += (o != 0 && (o < cnt || (o == cnt && t < s))) ? 1u : 0u;
+        }
+        if (r && cnt) atomicAdd(&L.rank[s], r);
+    }
+    __syncthreads();
+}
+
 // What the table build leaves for its caller.
 struct TableOut {
     unsigned long long* entry;  // [256] (LDS): bit-reversed code | length << 56
@@ -216,20 +242,7 @@ __device__ __forceinline__ void table_from_hist(TableLds& L, int lane, int K, Ta
 #pragma unroll
     for (int j = 0; j < NVS; j++) {
         cnt[j] = (64 * j + lane < K) ? L.h[64 * j + lane] : 0u;
-        rank[j] = 0;
-    }
-    // position of every used symbol in (count, symbol) order: every count is broadcast from its register in turn
-    // and compared by all lanes
-#pragma unroll
-    for (int jo = 0; jo < NVS; jo++) {
-        const int tmax = (K - 64 * jo < 64) ? K - 64 * jo : 64;
-        for (int t = 0; t < tmax; t++) {
-            const uint32_t o = (uint32_t)__builtin_amdgcn_readlane((int)cnt[jo], t);
-            const int so = 64 * jo + t;
-#pragma unroll
-            for (int j = 0; j < NVS; j++)
-                rank[j] += (o != 0 && (o < cnt[j] || (o == cnt[j] && so < 64 * j + lane))) ? 1u : 0u;
-        }
+        rank[j] = (64 * j + lane < K) ? L.rank[64 * j + lane] : 0u;  // made by rank_symbols
     }
     int n = 0;
 #pragma unroll
@@ -354,6 +367,7 @@ __global__ __launch_bounds__(1024) void k_huffman_table(const uint32_t* __restri
     __shared__ TableLds L;
     __shared__ unsigned long long entry[256];
     sum_partials<1024>(L, hist_parts, n_parts, bits);
+    rank_symbols<1024>(L, bits);
     const int tid = threadIdx.x;
     if (tid < 64) {
         TableOut out;
@@ -609,6 +623,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     static_assert(sizeof(TableLds) <= sizeof(stage), "table scratch must fit the chunk images");
     if constexpr (BUILD) {
         sum_partials<256>(L, p.hist_parts, p.n_parts, p.bits);
+        rank_symbols<256>(L, p.bits);
         if (wave == 0) {
             TableOut out;
             out.entry = tab;
@@ -631,7 +646,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     const uint32_t max_len = s_max_len;
     uint32_t* img = stage[wave];
     // nobody reads the table scratch any more: the images start out clear
-    for (int i = lane; i < kStageWords; i += 64) img[i] = 0u;
+    for (int i = lane; i < kStageWords / 4; i += 64) reinterpret_cast<uint4*>(img)[i] = make_uint4(0u, 0u, 0u, 0u);
     wave_sync();
     uint16_t* sub_bits = reinterpret_cast<uint16_t*>(p.stream + p.off_sub_bits);
     uint32_t* chunk_off = reinterpret_cast<uint32_t*>(p.stream + kHeaderBytes + kLenTableBytes);

@@ -700,12 +700,15 @@ typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes per run, slack for padded reads
 
-template <int NCT, int LAYOUT, bool ALIGNED4>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_decode_chunks(DecodeParams p) {
+// WAVES wavefronts per workgroup (4 or 8): one per SIMD where the chunks do not outnumber the SIMDs, two where
+// they do (the second hides the latencies of the first; the workgroup still holds one copy of the basis).
+template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k_decode_chunks(DecodeParams p) {
+    constexpr int THREADS = WAVES * 64;
     __shared__ __align__(16) DecTables T;
-    __shared__ uint32_t pay[4][kPayWords + 2 + kPayOverrun];  // per wavefront: the chunk's payload words, 2 zero
-                                                              // words, room for a corrupt stream's overrun
-    __shared__ __align__(16) uint8_t symtile[4][kChunkTileBytes];
+    __shared__ uint32_t pay[WAVES][kPayWords + 2 + kPayOverrun];  // per wavefront: the chunk's payload words, 2 zero
+                                                                  // words, room for a corrupt stream's overrun
+    __shared__ __align__(16) uint8_t symtile[WAVES][kChunkTileBytes];
     __shared__ float s_mu[NCT * 32];
     extern __shared__ __align__(16) uint4 basis16[];  // [NCT][NJ][2][64]
     constexpr int NJ = NCT * 2;  // steps of 16 coefficients
@@ -717,15 +720,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
     // loads that do not depend on the header go out first: the code length table and the basis
     int my_len = 0;
-    if (p.bytes >= (size_t)(kHeaderBytes + kLenTableBytes)) my_len = p.stream[kHeaderBytes + tid];
+    if (tid < 256 && p.bytes >= (size_t)(kHeaderBytes + kLenTableBytes)) my_len = p.stream[kHeaderBytes + tid];
     // the basis goes from global memory straight into LDS (no registers in between), 16 bytes per lane and
     // instruction: lane l of a wavefront lands at the wavefront's LDS base + 16 l
-    constexpr int kBasisPerThread = NCT * NJ * 2 * 64 / 256;  // 16-byte pieces of the basis per thread
+    constexpr int kBasisPieces = NCT * NJ * 2 * 64;  // 16-byte pieces of the basis, a multiple of 64
     {
         const uint4* src = reinterpret_cast<const uint4*>(p.Bp16);
 #pragma unroll
-        for (int i = 0; i < kBasisPerThread; i++)
-            __builtin_amdgcn_global_load_lds(src + tid + 256 * i, &basis16[256 * i + 64 * wave], 16, 0, 0);
+        for (int i = 0; i < (kBasisPieces + THREADS - 1) / THREADS; i++)
+            if (THREADS * i + 64 * wave < kBasisPieces)  // whole wavefronts
+                __builtin_amdgcn_global_load_lds(src + tid + THREADS * i, &basis16[THREADS * i + 64 * wave], 16, 0, 0);
     }
     StreamView sv;
     if (!open_stream(p, &sv)) {
@@ -733,7 +737,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         return;
     }
     // the first chunk's offsets and run sizes are on their way while the tables are built
-    const uint32_t ch_first = blockIdx.x * 4 + (uint32_t)wave;
+    const uint32_t ch_first = blockIdx.x * WAVES + (uint32_t)wave;
     uint32_t pre_w0 = 0, pre_w1 = 0, pre_run = 0;
     if (ch_first < sv.n_chunks) {
         pre_w0 = sv.chunk_off[ch_first];
@@ -741,7 +745,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         pre_run = ((uint32_t)lane < sv.spc) ? sv.sub_bits[(size_t)ch_first * sv.spc + lane] : 0u;
     }
     if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
-    if (!build_decode_tables<256>(T, my_len, p.bits)) {
+    if (!build_decode_tables<THREADS>(T, my_len, p.bits)) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(p.err, FMTC_ERR_TABLE);
         return;
     }
@@ -757,7 +761,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     uint8_t* tile = symtile[wave];
     uint32_t* pw = pay[wave];
 
-    for (uint32_t ch = blockIdx.x * 4 + (uint32_t)wave; ch < n_chunks; ch += gridDim.x * 4) {
+    for (uint32_t ch = ch_first; ch < n_chunks; ch += gridDim.x * WAVES) {
         // ---- variable length decoding of the chunk into the wavefront's tile ----
         const uint64_t c0 = (uint64_t)ch * chunk_syms;
         const uint32_t clen = (uint32_t)((V - c0 < chunk_syms) ? (V - c0) : chunk_syms);
@@ -909,26 +913,29 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     if (!d_syms && ncs <= 4) {
         // ---- one wavefront per chunk ----
         const size_t lds = sizeof(float) * (size_t)ncs * 32 * ncs * 32;
-        const size_t lds_static = sizeof(DecTables) + 4 * (kPayWords + 2 + kPayOverrun) * 4 + 4 * kChunkTileBytes + 512;
+        // two wavefronts per SIMD once the chunks outnumber the SIMDs of the device
+        const bool eight = g.n_chunks > 1024 && ncs != 3;  // (three channel tiles need more registers than two wavefronts per SIMD leave)
+        const int waves = eight ? 8 : 4;
+        const size_t lds_static = sizeof(DecTables) + (size_t)waves * ((kPayWords + 2 + kPayOverrun) * 4 + kChunkTileBytes) + 1024;
         const unsigned per_cu = (unsigned)((160 * 1024) / (lds + lds_static));
-        unsigned gx = (g.n_chunks + 3) / 4;
-        const unsigned cap = 256u * (per_cu < 1 ? 1u : per_cu);
+        unsigned gx = (g.n_chunks + waves - 1) / waves;
+        const unsigned cap = 256u * (per_cu < 1 ? 1u : (per_cu > (unsigned)(8 / waves) ? (unsigned)(8 / waves) : per_cu));
         if (gx > cap) gx = cap;
-#define FMTC_DECC(NCT, LAY, AL)                                                                                  \
+#define FMTC_DECC(NCT, LAY, AL, WV)                                                                              \
     do {                                                                                                         \
-        if (lds > 32 * 1024) {                                                                                   \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL>),   \
+        if (lds > 16 * 1024) {                                                                                   \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV>), \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
             if (ea != hipSuccess) return ea;                                                                     \
         }                                                                                                        \
-        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL>, dim3(gx), dim3(256), lds, s, p);                    \
+        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV>, dim3(gx), dim3(WV * 64), lds, s, p);            \
     } while (0)
 #define FMTC_DECC_N(LAY, AL)                                                                                     \
     do {                                                                                                         \
-        if (ncs == 1) FMTC_DECC(1, LAY, AL);                                                                     \
-        else if (ncs == 2) FMTC_DECC(2, LAY, AL);                                                                \
-        else if (ncs == 3) FMTC_DECC(3, LAY, AL);                                                                \
-        else FMTC_DECC(4, LAY, AL);                                                                              \
+        if (ncs == 1) { if (eight) FMTC_DECC(1, LAY, AL, 8); else FMTC_DECC(1, LAY, AL, 4); }                    \
+        else if (ncs == 2) { if (eight) FMTC_DECC(2, LAY, AL, 8); else FMTC_DECC(2, LAY, AL, 4); }               \
+        else if (ncs == 3) FMTC_DECC(3, LAY, AL, 4);                                                             \
+        else { if (eight) FMTC_DECC(4, LAY, AL, 8); else FMTC_DECC(4, LAY, AL, 4); }                             \
     } while (0)
         if (layout == FMTC_NHWC) { if (al) FMTC_DECC_N(FMTC_NHWC, true); else FMTC_DECC_N(FMTC_NHWC, false); }
         else                     { if (al) FMTC_DECC_N(FMTC_NCHW, true); else FMTC_DECC_N(FMTC_NCHW, false); }
