@@ -14,7 +14,7 @@ struct fmtc_basis {
     float range_A = 0.f;
     std::vector<float> T, mu;
     std::vector<double> eig;
-    float *d_fwd = nullptr, *d_inv = nullptr, *d_invf = nullptr, *d_mu = nullptr, *d_T = nullptr;
+    float *d_mu = nullptr, *d_T = nullptr;
     uint16_t *d_fwd16 = nullptr, *d_inv16 = nullptr;
     float row_norm = 1.f;  // largest Euclidean norm of a row of T (1 for an orthonormal basis)
     int device = 0;
@@ -46,26 +46,7 @@ bool dims_ok(int64_t N, int C, int H, int W) {
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
-// Operand order of the 32x32x2 fp32 matrix instruction: tile (nt, ms), lane l,
-// slot s <- M[nt*32 + l%32][ms*32 + perm(s, l/32)].
-void pack_operand(const std::vector<float>& T, int C, int Cpad, bool transpose, bool inverse_perm,
-                  std::vector<float>* out) {
-    const int nt_count = Cpad / 32;
-    out->assign((size_t)Cpad * Cpad, 0.f);
-    for (int nt = 0; nt < nt_count; nt++)
-        for (int ms = 0; ms < nt_count; ms++)
-            for (int lane = 0; lane < 64; lane++)
-                for (int s = 0; s < 16; s++) {
-                    int half = lane / 32;
-                    int row = nt * 32 + lane % 32;
-                    int col = ms * 32 + (inverse_perm ? 8 * (s / 4) + 4 * half + s % 4 : 2 * s + half);
-                    float v = 0.f;
-                    if (row < C && col < C) v = transpose ? T[(size_t)col * C + row] : T[(size_t)row * C + col];
-                    (*out)[(((size_t)nt * nt_count + ms) * 64 + lane) * 16 + s] = v;
-                }
-}
-
-// Operand order of the narrow-tensor kernels (v_mfma_f32_32x32x16_f16, every fp32 entry split into two f16 parts:
+// Operand order of the kernels (v_mfma_f32_32x32x16_f16, every fp32 entry split into two f16 parts:
 // hi = the entry rounded to f16, lo = 2^11 times the rest, rounded to f16).  For tile t (32 rows of M) and step
 // j (16 columns) the 64 lanes' hi parts (8 halves each) are followed by their lo parts:
 //   out[(((t * NJ + j) * 2 + part) * 64 + lane) * 8 + e] = part of M[t*32 + row(lane%32)][16j + 8*(lane/32) + e],
@@ -97,11 +78,8 @@ void pack_operand16(const std::vector<float>& T, int C, int Cpad, bool transpose
 
 fmtc_status upload_basis(fmtc_basis* b) {
     const int C = b->C, Cpad = b->Cpad;
-    std::vector<float> fwd, inv, invf, mu(Cpad, 0.f);
+    std::vector<float> mu(Cpad, 0.f);
     std::vector<uint16_t> fwd16, inv16;
-    pack_operand(b->T, C, Cpad, false, false, &fwd);
-    pack_operand(b->T, C, Cpad, true, true, &inv);
-    pack_operand(b->T, C, Cpad, true, false, &invf);
     pack_operand16(b->T, C, Cpad, false, true, &fwd16);
     pack_operand16(b->T, C, Cpad, true, false, &inv16);
     double worst = 0.0;
@@ -115,13 +93,7 @@ fmtc_status upload_basis(fmtc_basis* b) {
     hipError_t e;
     const size_t mat = sizeof(float) * (size_t)Cpad * Cpad;
     if ((e = hipGetDevice(&b->device)) != hipSuccess) return hip_fail(e, "hipGetDevice");
-    if ((e = hipMalloc((void**)&b->d_fwd, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
-    if ((e = hipMalloc((void**)&b->d_inv, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
     if ((e = hipMalloc((void**)&b->d_mu, sizeof(float) * Cpad)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
-    if ((e = hipMemcpy(b->d_fwd, fwd.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
-    if ((e = hipMemcpy(b->d_inv, inv.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
-    if ((e = hipMalloc((void**)&b->d_invf, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
-    if ((e = hipMemcpy(b->d_invf, invf.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     if ((e = hipMemcpy(b->d_mu, mu.data(), sizeof(float) * Cpad, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
     if ((e = hipMalloc((void**)&b->d_inv16, mat)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
     if ((e = hipMemcpy(b->d_inv16, inv16.data(), mat, hipMemcpyHostToDevice)) != hipSuccess) return hip_fail(e, "hipMemcpy basis");
@@ -136,9 +108,6 @@ BasisDevice device_view(const fmtc_basis* b) {
     BasisDevice v;
     v.C = b->C;
     v.Cpad = b->Cpad;
-    v.fwd = b->d_fwd;
-    v.inv = b->d_inv;
-    v.invf = b->d_invf;
     v.inv16 = b->d_inv16;
     v.fwd16 = b->d_fwd16;
     v.row_norm = b->row_norm;
@@ -260,9 +229,6 @@ int fmtc_basis_channels(const fmtc_basis* basis) { return basis ? basis->C : 0; 
 
 void fmtc_basis_destroy(fmtc_basis* b) {
     if (!b) return;
-    if (b->d_fwd) (void)hipFree(b->d_fwd);
-    if (b->d_inv) (void)hipFree(b->d_inv);
-    if (b->d_invf) (void)hipFree(b->d_invf);
     if (b->d_inv16) (void)hipFree(b->d_inv16);
     if (b->d_fwd16) (void)hipFree(b->d_fwd16);
     if (b->d_mu) (void)hipFree(b->d_mu);

@@ -2,11 +2,12 @@
 // transform; section 3.1 "Implementation": levels scaled back to the transform
 // domain, then the inverse PCA).  One kernel per call:
 //   1. every workgroup checks the header and the code length table and builds the
-//      canonical decode tables and a 2^11-entry two-symbol lookup table in LDS;
+//      canonical decode tables and a 2^11-entry three-symbol lookup table in LDS;
 //   2. one wavefront per chunk, one lane per run of 64 symbols (bit offset = prefix
 //      sum of the stored run sizes) decodes into an LDS symbol tile;
-//   3. x_hat = T^T (Delta q) + mu on the fp32 matrix cores
-//      (v_mfma_f32_32x32x2_f32).  Narrow tensors (up to 128 channels): the wavefront
+//   3. x_hat = T^T (Delta q) + mu on the f16 matrix cores
+//      (v_mfma_f32_32x32x16_f16; the levels are exact in f16, the basis entries are
+//      split in two f16 parts).  Narrow tensors (up to 128 channels): the wavefront
 //      that decoded a chunk also transforms it, the basis sits in LDS in operand
 //      order and no workgroup barrier is needed after the tables.  Wide tensors: a
 //      tile of several chunks per workgroup, the basis streamed from L2.
@@ -17,6 +18,8 @@
 namespace fmtc {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 
 // byte address of symbol n of the tile: every run of 64 symbols is followed by 4
 // pad bytes so that the 64 lanes of a decoding wavefront hit different banks
@@ -167,8 +170,7 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
 // State: lo/hi are payload words widx and widx+1, sh the bit offset in lo, nxt word widx+2 (read ahead),
 // so 32 valid bits are at hand for every table lookup and a step crosses at most one word boundary.
 //
-// Output of a run.  Byte tile: symbol n of the tile at sym_addr(n).  Float tile: the dequantized coefficient
-// Delta * (s - 2^(b-1)) at tile[pixel][coefficient] with a row stride of rs floats.
+// Output of a run: symbol n of the tile at sym_addr(n).
 struct ByteOut {
     uint8_t* tile;
     uint32_t a0, o, i;
@@ -178,26 +180,6 @@ struct ByteOut {
         i++;
     }
 };
-struct FloatOut {
-    float* tile;
-    uint32_t fa, krem, C, gap;
-    float delta, neg_off;
-    __device__ __forceinline__ FloatOut(float* t, uint32_t nbase, uint32_t C_, uint32_t rs, float d, float no)
-        : tile(t), C(C_), gap(rs - C_), delta(d), neg_off(no) {
-        const uint32_t px = nbase / C_, k = nbase - px * C_;
-        fa = px * rs + k;
-        krem = C_ - k;
-    }
-    __device__ __forceinline__ void put(uint32_t sym) {
-        tile[fa] = __builtin_fmaf((float)sym, delta, neg_off);
-        fa++;
-        if (--krem == 0) {  // next pixel row
-            fa += gap;
-            krem = C;
-        }
-    }
-};
-
 template <bool STAGED, typename Out>
 __device__ __forceinline__ bool decode_run(const uint32_t* pw, const uint32_t* __restrict__ gw, uint32_t nwords,
                                            uint32_t start, uint32_t cnt, const DecTables& T, Out out) {
@@ -361,11 +343,8 @@ struct DecodeParams {
     int bits;
     int G;             // chunks per tile
     int ct_per_group;  // 32-channel output tiles per workgroup row (blockIdx.y)
-    int tile_rows;     // float tile: pixel rows allocated
     int ncs;           // Cpad / 32
-    const float* Bpk;  // inverse operand, packed (slot order of the byte tile)
-    const float* Bpf;  // inverse operand, packed (slot order of the float tile)
-    const uint16_t* Bp16;  // inverse operand, f16 split, packed for the one-wavefront-per-chunk kernel
+    const uint16_t* Bp16;  // inverse operand (T^T), f16 split, in operand order
     const float* mu;   // [Cpad]
     float* xhat;       // NULL in symbols-only mode
     uint8_t* syms_out; // non-NULL in symbols-only mode
@@ -413,9 +392,11 @@ __device__ __forceinline__ bool open_stream(const DecodeParams& p, StreamView* v
 
 constexpr int kPayWords = 918;  // LDS copy of a chunk's payload: up to ~7 bits/symbol; larger chunks read global memory
 
-// FTILE: the tile holds dequantized coefficients as floats, [pixel][coefficient] with row stride Cpad + 2 (the
-// matrix operand then comes straight from LDS, as in the encoder); otherwise symbol bytes, converted on the fly.
-template <int MT, int LAYOUT, bool ALIGNED4, bool FTILE>
+// Wide tensors and the symbols-only mode: a tile of G chunks per workgroup is decoded into an LDS tile of symbol
+// bytes; the inverse transform of the tile's pixels then runs on the f16 matrix cores as in the narrow-tensor
+// kernel below (levels exact in f16, basis entries split in two f16 parts, two matrix instructions per 16
+// coefficients), the basis streaming from L2 in operand order one step ahead of its use.
+template <int MT, int LAYOUT, bool ALIGNED4>
 __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
     __shared__ __align__(16) DecTables T;
     __shared__ uint32_t pay[4][kPayWords + 2];  // per wavefront: the chunk's payload words
@@ -445,20 +426,12 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
     __syncthreads();
 
     const float delta = sv.delta;
-    const float neg_off = -(float)(1 << (p.bits - 1)) * delta;  // exact: power of two times delta
     const int G = p.G;
     const uint32_t n_tiles = (n_chunks + G - 1) / G;
-    float* ftile = reinterpret_cast<float*>(symtile);
-    const int RS = p.ncs * 32 + 2;  // float tile: lanes of a half-wavefront (32 pixels) fall on the even banks
-    if constexpr (FTILE) {
-        // coefficients past C meet zero basis entries; they only have to be finite
-        const int padw = p.ncs * 32 - C;
-        const int rows = p.tile_rows;
-        for (int idx = tid; idx < rows * padw; idx += 256) {
-            int row = idx / padw;
-            ftile[row * RS + C + (idx - row * padw)] = 0.f;
-        }
-    }
+    // 0x6400 | s is the f16 number 1024 + s: the level s - 2^(b-1) is that minus (1024 + 2^(b-1)), exactly
+    const _Float16 level_off = (_Float16)(float)(1024 + (1 << (p.bits - 1)));
+    const halfx2 level_off2 = {level_off, level_off};
+    const int NJ = p.ncs * 2;  // steps of 16 coefficients
 
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         // ---- variable length decoding into the LDS tile ----
@@ -487,24 +460,13 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
                 for (uint32_t i = lane; i < nwords + 2; i += 64) pw[i] = (i < nwords) ? payload[w0 + i] : 0u;
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 __builtin_amdgcn_wave_barrier();
-                if (cnt)
-                {
-                    if constexpr (FTILE)
-                        ok_run = decode_run<true>(pw, nullptr, nwords, start, cnt, T,
-                                                  FloatOut(ftile, nbase, (uint32_t)C, (uint32_t)RS, delta, neg_off));
-                    else
-                        ok_run = decode_run<true>(pw, nullptr, nwords, start, cnt, T, ByteOut(symtile, nbase));
-                }
+                if (cnt) ok_run = decode_run<true>(pw, nullptr, nwords, start, cnt, T, ByteOut(symtile, nbase));
                 // the next chunk of this wavefront overwrites pay[]: all lanes are done reading here
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 __builtin_amdgcn_wave_barrier();
             } else if (cnt) {
                 // a chunk too large for the LDS copy is read in place
-                if constexpr (FTILE)
-                    ok_run = decode_run<false>(nullptr, payload + w0, nwords, start, cnt, T,
-                                               FloatOut(ftile, nbase, (uint32_t)C, (uint32_t)RS, delta, neg_off));
-                else
-                    ok_run = decode_run<false>(nullptr, payload + w0, nwords, start, cnt, T, ByteOut(symtile, nbase));
+                ok_run = decode_run<false>(nullptr, payload + w0, nwords, start, cnt, T, ByteOut(symtile, nbase));
             }
             if (!ok_run) atomicOr(p.err, FMTC_ERR_CODE);
         }
@@ -536,96 +498,65 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
             for (int u = wave; u < nunits; u += 4) {
                 const int ct = ct0 + u % nct_g;
                 const int pt0 = (u / nct_g) * MT;
-                floatx16 acc[MT];
+                floatx16 acc[MT], acl[MT];
 #pragma unroll
                 for (int m = 0; m < MT; m++)
 #pragma unroll
-                    for (int r = 0; r < 16; r++) acc[m][r] = 0.f;
-                if constexpr (FTILE) {
-                    const float* arow[MT];
-#pragma unroll
-                    for (int m = 0; m < MT; m++) {
-                        int pxl = (pt0 + m) * 32 + l32;
-                        if (pxl > TP - 1) pxl = TP - 1;  // rows past the tile repeat the last pixel; never stored
-                        arow[m] = ftile + pxl * RS + half;
-                    }
-                    // slot s of the packed basis tile holds coefficient ks*32 + 2*s + half for this lane
-                    const float4* bsrc = reinterpret_cast<const float4*>(p.Bpf + ((size_t)ct * p.ncs * 64 + lane) * 16);
-                    float4 b_cur[4], b_nxt[4];
-#pragma unroll
-                    for (int q = 0; q < 4; q++) b_cur[q] = bsrc[q];
-                    for (int ks = 0; ks < p.ncs; ks++) {
-                        if (ks + 1 < p.ncs) {
-                            const float4* nsrc = bsrc + (size_t)(ks + 1) * 64 * 4;
-#pragma unroll
-                            for (int q = 0; q < 4; q++) b_nxt[q] = nsrc[q];
-                        }
-#pragma unroll
-                        for (int sl = 0; sl < 16; sl++) {
-                            const float bq = reinterpret_cast<const float*>(b_cur)[sl];
-#pragma unroll
-                            for (int m = 0; m < MT; m++) {
-                                const float a = arow[m][ks * 32 + 2 * sl];
-                                if constexpr (LAYOUT == FMTC_NHWC)
-                                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bq, acc[m], 0, 0, 0);
-                                else
-                                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq, a, acc[m], 0, 0, 0);
-                            }
-                        }
-#pragma unroll
-                        for (int q = 0; q < 4; q++) b_cur[q] = b_nxt[q];
-                    }
-                } else {
+                    for (int r = 0; r < 16; r++) { acc[m][r] = 0.f; acl[m][r] = 0.f; }
                 uint32_t rowbase[MT];
 #pragma unroll
                 for (int m = 0; m < MT; m++) {
                     int pxl = (pt0 + m) * 32 + l32;
                     if (pxl > TP - 1) pxl = TP - 1;  // rows past the tile repeat the last pixel; never stored
-                    rowbase[m] = (uint32_t)pxl * (uint32_t)C + 4u * half;
+                    rowbase[m] = (uint32_t)pxl * (uint32_t)C + 8u * half;
                 }
-                const float4* bsrc = reinterpret_cast<const float4*>(p.Bpk + ((size_t)ct * p.ncs * 64 + lane) * 16);
-                float4 b_cur[4], b_nxt[4];
-#pragma unroll
-                for (int q = 0; q < 4; q++) b_cur[q] = bsrc[q];
-                for (int ks = 0; ks < p.ncs; ks++) {
-                    if (ks + 1 < p.ncs) {
-                        const float4* nsrc = bsrc + (size_t)(ks + 1) * 64 * 4;
-#pragma unroll
-                        for (int q = 0; q < 4; q++) b_nxt[q] = nsrc[q];
+                // (ct, ks): the 64 lanes' hi parts, then their lo parts, 16 bytes per lane each; the basis comes from
+                // L2, one step ahead of its use
+                const uint4* bsrc = reinterpret_cast<const uint4*>(p.Bp16) + (size_t)ct * NJ * 2 * 64 + lane;
+                uint4 bh4 = bsrc[0], bl4 = bsrc[64];
+                for (int ks = 0; ks < NJ; ks++) {
+                    uint4 nh4 = bh4, nl4 = bl4;
+                    if (ks + 1 < NJ) {
+                        nh4 = bsrc[(size_t)(2 * ks + 2) * 64];
+                        nl4 = bsrc[(size_t)(2 * ks + 3) * 64];
                     }
+                    const halfx8 bh = __builtin_bit_cast(halfx8, bh4), bl = __builtin_bit_cast(halfx8, bl4);
 #pragma unroll
-                    for (int t = 0; t < 4; t++) {
-                        const float4 bv = b_cur[t];
-                        const float bs[4] = {bv.x, bv.y, bv.z, bv.w};
-                        uint32_t w[MT];
-#pragma unroll
-                        for (int m = 0; m < MT; m++) {
-                            const uint32_t n = rowbase[m] + (uint32_t)(ks * 32 + 8 * t);
-                            if constexpr (ALIGNED4) {
-                                w[m] = *reinterpret_cast<const uint32_t*>(symtile + sym_addr(n));
-                            } else {
-                                w[m] = (uint32_t)symtile[sym_addr(n)] | ((uint32_t)symtile[sym_addr(n + 1)] << 8) |
-                                       ((uint32_t)symtile[sym_addr(n + 2)] << 16) |
-                                       ((uint32_t)symtile[sym_addr(n + 3)] << 24);
-                            }
+                    for (int m = 0; m < MT; m++) {
+                        // the eight symbols 16 ks + 8*half .. + 7 of this lane's pixel (coefficients past C meet zero
+                        // basis entries; whatever level the tile's bytes give there does not count)
+                        const uint32_t n = rowbase[m] + 16u * (uint32_t)ks;
+                        uint32_t w0, w1;
+                        if constexpr (ALIGNED4) {
+                            w0 = *reinterpret_cast<const uint32_t*>(symtile + sym_addr(n));
+                            w1 = *reinterpret_cast<const uint32_t*>(symtile + sym_addr(n + 4));
+                        } else {
+                            w0 = (uint32_t)symtile[sym_addr(n)] | ((uint32_t)symtile[sym_addr(n + 1)] << 8) |
+                                 ((uint32_t)symtile[sym_addr(n + 2)] << 16) | ((uint32_t)symtile[sym_addr(n + 3)] << 24);
+                            w1 = (uint32_t)symtile[sym_addr(n + 4)] | ((uint32_t)symtile[sym_addr(n + 5)] << 8) |
+                                 ((uint32_t)symtile[sym_addr(n + 6)] << 16) | ((uint32_t)symtile[sym_addr(n + 7)] << 24);
                         }
-                        // consecutive matrix instructions go to different accumulators
-#pragma unroll
-                        for (int i = 0; i < 4; i++)
-#pragma unroll
-                            for (int m = 0; m < MT; m++) {
-                                float yq = __builtin_fmaf((float)((w[m] >> (8 * i)) & 255u), delta, neg_off);
-                                if constexpr (LAYOUT == FMTC_NHWC)
-                                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(yq, bs[i], acc[m], 0, 0, 0);
-                                else
-                                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(bs[i], yq, acc[m], 0, 0, 0);
-                            }
+                        const halfx2 q01 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w0, 0x05010400u)) - level_off2;
+                        const halfx2 q23 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w0, 0x07030602u)) - level_off2;
+                        const halfx2 q45 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w1, 0x05010400u)) - level_off2;
+                        const halfx2 q67 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w1, 0x07030602u)) - level_off2;
+                        const halfx8 q = {q01[0], q01[1], q23[0], q23[1], q45[0], q45[1], q67[0], q67[1]};
+                        if constexpr (LAYOUT == FMTC_NHWC) {
+                            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q, bh, acc[m], 0, 0, 0);
+                            acl[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q, bl, acl[m], 0, 0, 0);
+                        } else {
+                            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, q, acc[m], 0, 0, 0);
+                            acl[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q, acl[m], 0, 0, 0);
+                        }
                     }
+                    bh4 = nh4;
+                    bl4 = nl4;
+                }
+                // x_hat = Delta (sum q T_hi + 2^-11 sum q T_lo) + mu
 #pragma unroll
-                    for (int q = 0; q < 4; q++) b_cur[q] = b_nxt[q];
-                }
-
-                }
+                for (int m = 0; m < MT; m++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) acc[m][r] = __builtin_fmaf(acl[m][r], 1.f / 2048.f, acc[m][r]) * delta;
 
                 // accumulator r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of the 32x32 tile.
                 // Whole 32-pixel tiles are stored without per-element predicates (one straight run of stores).
@@ -696,8 +627,6 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
 // 16j + 8*half + e of its pixel (the contraction index may be walked in any order as long as
 // both operands agree on it).  Delta and mu are applied in the epilogue.
 // ---------------------------------------------------------------------------
-typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
-typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes per run, slack for padded reads
 
 // WAVES wavefronts per workgroup (4 or 8): one per SIMD where the chunks do not outnumber the SIMDs, two where
@@ -897,8 +826,6 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     p.C = C;
     p.bits = bits;
     p.ncs = ncs;
-    p.Bpk = b ? b->inv : nullptr;
-    p.Bpf = b ? b->invf : nullptr;
     p.Bp16 = b ? b->inv16 : nullptr;
     p.mu = b ? b->mu : nullptr;
     p.xhat = d_xhat;
@@ -906,7 +833,6 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     p.err = d_err;
     p.G = 1;
     p.ct_per_group = 1;
-    p.tile_rows = 0;
     const bool al = (C % 4) == 0;
     hipError_t el = hipSuccess;
 
@@ -945,20 +871,10 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     }
 
     // ---- tiles of several chunks per workgroup ----
-    // Float tile (dequantized coefficients in LDS) for mid-size C; byte tile otherwise and for symbols-only.
-    const bool ftile = !d_syms && C >= 32 && C <= 256;
-    int G;
-    if (ftile) {
-        G = (C <= 32) ? 1 : 2;  // 128 pixels at C <= 64, about 64 up to C = 144, 32 at C = 256
-    } else {
-        // enough chunks for at least 64 pixels at the nominal chunk size, 4..16 chunks
-        G = (int)((64 * (int64_t)C + 4095) / 4096);
-        G = G < 4 ? 4 : (G > 16 ? 16 : (G + 3) / 4 * 4);
-    }
+    // enough chunks for at least 64 pixels at the nominal chunk size, 4..16 chunks
+    int G = (int)((64 * (int64_t)C + 4095) / 4096);
+    G = G < 4 ? 4 : (G > 16 ? 16 : (G + 3) / 4 * 4);
     p.G = G;
-    // a chunk never holds more than 4096 / C pixels (one if C > 4096 / 2), whatever chunk size the stream was made with
-    const int max_ppc = 4096 / C > 1 ? 4096 / C : 1;
-    p.tile_rows = (G * max_ppc + 31) / 32 * 32;
     // the grid is sized from the nominal geometry; the kernel takes the real one from the header
     const uint32_t n_tiles = (g.n_chunks + G - 1) / G;
     int groups = 1;
@@ -971,31 +887,24 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     groups = (ncs + p.ct_per_group - 1) / p.ct_per_group;
     unsigned gx = n_tiles < 1024u ? n_tiles : 1024u;
     dim3 grid(gx, (unsigned)groups);
-    const size_t lds = ftile ? sizeof(float) * (size_t)p.tile_rows * (ncs * 32 + 2)
-                             : (size_t)G * 4096 + (size_t)G * 4096 / 16 + 128;
+    const size_t lds = (size_t)G * 4096 + (size_t)G * 4096 / 16 + 128;
     // more than 64 KB of dynamic LDS has to be requested per kernel (the CU has 160 KB)
-#define FMTC_DEC(MT, LAY, AL, FT)                                                                            \
+#define FMTC_DEC(MT, LAY, AL)                                                                                \
     do {                                                                                                     \
         if (lds > 32 * 1024) {                                                                               \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_tiles<MT, LAY, AL, FT>), \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_tiles<MT, LAY, AL>), \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);      \
             if (ea != hipSuccess) return ea;                                                                 \
         }                                                                                                    \
-        el = launch(K_DECODE, k_decode_tiles<MT, LAY, AL, FT>, grid, dim3(256), lds, s, p);                  \
+        el = launch(K_DECODE, k_decode_tiles<MT, LAY, AL>, grid, dim3(256), lds, s, p);                      \
     } while (0)
-    if (ftile) {
-        const bool two = p.tile_rows >= 64;  // two 32-pixel tiles per wavefront unit
-        if (layout == FMTC_NHWC) { if (two) FMTC_DEC(2, FMTC_NHWC, true, true); else FMTC_DEC(1, FMTC_NHWC, true, true); }
-        else                     { if (two) FMTC_DEC(2, FMTC_NCHW, true, true); else FMTC_DEC(1, FMTC_NCHW, true, true); }
+    const bool wide = C > 256;  // fewer pixels per tile: 2 pixel tiles per wavefront unit instead of 4
+    if (layout == FMTC_NHWC) {
+        if (al) { if (wide) FMTC_DEC(2, FMTC_NHWC, true); else FMTC_DEC(4, FMTC_NHWC, true); }
+        else    { if (wide) FMTC_DEC(2, FMTC_NHWC, false); else FMTC_DEC(4, FMTC_NHWC, false); }
     } else {
-        const bool wide = C > 256;  // fewer pixels per tile: 2 pixel tiles per wavefront unit instead of 4
-        if (layout == FMTC_NHWC) {
-            if (al) { if (wide) FMTC_DEC(2, FMTC_NHWC, true, false); else FMTC_DEC(4, FMTC_NHWC, true, false); }
-            else    { if (wide) FMTC_DEC(2, FMTC_NHWC, false, false); else FMTC_DEC(4, FMTC_NHWC, false, false); }
-        } else {
-            if (al) { if (wide) FMTC_DEC(2, FMTC_NCHW, true, false); else FMTC_DEC(4, FMTC_NCHW, true, false); }
-            else    { if (wide) FMTC_DEC(2, FMTC_NCHW, false, false); else FMTC_DEC(4, FMTC_NCHW, false, false); }
-        }
+        if (al) { if (wide) FMTC_DEC(2, FMTC_NCHW, true); else FMTC_DEC(4, FMTC_NCHW, true); }
+        else    { if (wide) FMTC_DEC(2, FMTC_NCHW, false); else FMTC_DEC(4, FMTC_NCHW, false); }
     }
 #undef FMTC_DEC
     return el;

@@ -2,15 +2,13 @@
 // (paper section 3; section 3.1 "Linear transform", "Quantization",
 // "Variable length coding" for the statistics).
 //
-// The projection of all pixels is one dense contraction [C x C] . [C x P]; it
-// runs on the fp32 matrix cores (v_mfma_f32_32x32x2_f32).  Per workgroup:
-// 4 wavefronts = WK coefficient tiles (32 each) x WP pixel groups; the basis
-// tile is read from its pre-packed operand order straight into registers, the
-// activations go through LDS (coalesced global reads, transposed so that a
-// lanes of a wavefront read 32 pixels of one channel without bank conflicts).
-// Values that land too close to a rounding boundary for fp32 to decide are
-// recomputed in fp64 by the wavefront.  The quantized tile is staged in LDS and
-// leaves as whole rows of symbols.
+// The projection of all pixels is one dense contraction [C x C] . [C x P].  It
+// runs on the f16 matrix cores (v_mfma_f32_32x32x16_f16) with every fp32 operand
+// split into two f16 parts, which is as accurate as the fp32 matrix instruction
+// and several times as fast; values that land too close to a rounding boundary
+// for the fast pass to decide are recomputed in fp64 by the wavefront.  Two
+// kernels: one wavefront per 32 pixels with the basis in LDS (up to 128
+// channels), and a workgroup tile in LDS with the basis streamed from L2 (wider).
 #include <type_traits>
 
 #include "fmtc_device.h"
@@ -28,219 +26,279 @@ __device__ __forceinline__ void zero_coder_scratch(CoderCtrl* ctrl, unsigned lon
     if (gtid < sizeof(CoderCtrl) / 4) reinterpret_cast<uint32_t*>(ctrl)[gtid] = 0u;
 }
 
-// PT: pixels per workgroup; MT: 32-pixel tiles per wavefront unit; LAYOUT: FMTC_NHWC / FMTC_NCHW;
-// VEC: C % 4 == 0 (16-byte loads of channels-last rows and 4-byte symbol stores are aligned).
-//
-// The workgroup first brings its whole pixel tile, all channels, into LDS (one round of loads in flight,
-// mean removed on the way), then its 4 wavefronts share out the work units (coefficient tile, pixel group)
-// of the workgroup's coefficient range [kt0, kt0 + ktg) without further barriers.
-template <int PT, int MT, int LAYOUT, bool VEC>
-__global__ __launch_bounds__(256) void k_project_quantize(const float* __restrict__ x,
-                                                          const float* __restrict__ Apk,
-                                                          const float* __restrict__ mu,
-                                                          const float* __restrict__ Trow, int64_t P, int64_t HW,
-                                                          int C, int ncs, int kt_per_group, float inv_delta,
-                                                          float delta, float tau, int bits,
-                                                          int64_t px_tiles, uint8_t* __restrict__ syms,
-                                                          uint32_t* __restrict__ hist_parts, CoderCtrl* ctrl,
-                                                          unsigned long long* lookback, uint32_t n_groups) {
-    extern __shared__ __align__(16) float dyn_lds[];
-    __shared__ uint32_t lhist[256];
-    zero_coder_scratch(ctrl, lookback, n_groups);
+// ---------------------------------------------------------------------------
+// Wide tensors (more than 128 channels after padding to 32).  The contraction is the same f16
+// split as in the narrow-tensor kernel below (three v_mfma_f32_32x32x16_f16 per 16 channels,
+// see there), but a pixel's channels no longer fit a wavefront's registers: the workgroup
+// (8 wavefronts) first brings a tile of PT pixels, all channels, into LDS -- coalesced global
+// reads, mean removed and split into the two f16 parts on the way, rows padded by 16 bytes so
+// that the 16-byte operand reads of 8 neighbouring pixels cover all banks -- then its
+// wavefronts share out the work units (coefficient tile, 32-pixel group) of the workgroup's
+// coefficient range [kt0, kt0 + ktg) without further barriers, the four wavefronts of a round
+// taking the pixel groups of one coefficient tile so that they read the same part of the
+// basis, which streams from L2 in operand order one step ahead of its use.  Values too close
+// to a rounding boundary are recomputed in fp64; the quantized tile is staged in LDS and
+// leaves as whole rows of symbols.
+// PT: pixels per workgroup; LAYOUT: FMTC_NHWC / FMTC_NCHW; VEC: C % 4 == 0 (16-byte loads of
+// channels-last rows and 4-byte symbol stores are aligned).
+// ---------------------------------------------------------------------------
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
 
-    const int Cpad = ncs * 32;
-    const int RS = Cpad + 2;  // pixel row stride in floats: lanes of a half-wavefront (32 pixels, one channel)
-                              // fall on the even banks, the other half (next channel) on the odd ones
-    const int kt0 = blockIdx.y * kt_per_group;
-    const int ktg = (ncs - kt0 < kt_per_group) ? ncs - kt0 : kt_per_group;
-    const int RSW = kt_per_group * 8 + 1;  // staging row stride in words
-    float* xs = dyn_lds;
-    uint32_t* st = reinterpret_cast<uint32_t*>(dyn_lds + (size_t)PT * RS);
+struct WideParams {
+    const float* x;
+    const uint16_t* basis16;  // fwd16 packing
+    const float* mu;          // [Cpad]
+    const float* Trow;        // [C][C] row major, for the exact decisions
+    int64_t P, HW;
+    int C, ncs, kt_per_group, bits;
+    float inv_delta, delta, kappa, tau_min;
+    int64_t px_tiles;
+    uint8_t* syms;
+    uint32_t* hist_parts;
+    CoderCtrl* ctrl;
+    unsigned long long* lookback;
+    uint32_t n_groups;
+};
+
+constexpr int kWideThreads = 512;
+
+template <int PT, int LAYOUT, bool VEC>
+__global__ __launch_bounds__(kWideThreads) void k_project_quantize_wide(WideParams p) {
+    extern __shared__ __align__(16) uint8_t dyn_lds[];
+    __shared__ uint32_t lhist[256];
+    __shared__ float s_n2[PT];  // |x - mu|^2 of every pixel of the tile
+    zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
+
+    const int C = p.C, ncs = p.ncs;
+    const int Cpad = ncs * 32, NJ = ncs * 2;
+    const int RSH = Cpad + 8;  // pixel row stride in halves
+    const int kt0 = blockIdx.y * p.kt_per_group;
+    const int ktg = (ncs - kt0 < p.kt_per_group) ? ncs - kt0 : p.kt_per_group;
+    const int RSW = p.kt_per_group * 8 + 1;  // staging row stride in words
+    _Float16* xh = reinterpret_cast<_Float16*>(dyn_lds);
+    _Float16* xl = xh + (size_t)PT * RSH;
+    uint32_t* st = reinterpret_cast<uint32_t*>(xl + (size_t)PT * RSH);
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
 
-    lhist[tid] = 0u;
+    if (tid < 256) lhist[tid] = 0u;
+    const int zero_sym = 1 << (p.bits - 1);
+    const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1);
+    const float inv_delta = p.inv_delta, inv_delta_lo = p.inv_delta * (1.f / 2048.f);
+
+    // the two f16 parts of one value (clamped to what f16 holds: a pixel with such a value is decided exactly)
+    auto split = [](float v, _Float16& vh, _Float16& vl) {
+        v = __builtin_amdgcn_fmed3f(v, -60000.f, 60000.f);
+        vh = (_Float16)v;
+        vl = (_Float16)((v - (float)vh) * 2048.f);
+    };
 
     // the workgroup walks over pixel tiles; its histogram accumulates in LDS and leaves once at the end
-    for (int64_t tile = blockIdx.x; tile < px_tiles; tile += gridDim.x) {
-    const int64_t px0 = tile * PT;
+    for (int64_t tile = blockIdx.x; tile < p.px_tiles; tile += gridDim.x) {
+        const int64_t px0 = tile * PT;
+        if (tid < PT) s_n2[tid] = 0.f;
+        __syncthreads();  // also: the previous tile's staging rows have left
 
-    // ---- the pixel tile, mean removed, as xs[pixel][channel] ----
-    if constexpr (LAYOUT == FMTC_NHWC && VEC) {
-        const int n4 = PT * (C / 4);  // the tile is one contiguous run of PT*C floats
-        const float* src = x + px0 * C;
-        for (int idx = tid; idx < n4; idx += 256) {
-            int f = 4 * idx;
-            int pxl = f / C, c = f - pxl * C;
-            float4 v = (px0 + pxl < P) ? *reinterpret_cast<const float4*>(src + f) : make_float4(0, 0, 0, 0);
-            float4 m = *reinterpret_cast<const float4*>(mu + c);
-            float2* dst = reinterpret_cast<float2*>(xs + pxl * RS + c);
-            dst[0] = make_float2(v.x - m.x, v.y - m.y);
-            dst[1] = make_float2(v.z - m.z, v.w - m.w);
-        }
-    } else if constexpr (LAYOUT == FMTC_NHWC) {
-        const int n1 = PT * C;
-        const float* src = x + px0 * C;
-        for (int idx = tid; idx < n1; idx += 256) {
-            int pxl = idx / C, c = idx - pxl * C;
-            float v = (px0 + pxl < P) ? src[idx] : 0.f;
-            xs[pxl * RS + c] = v - mu[c];
-        }
-    } else {
-        const int pxl = tid % PT;
-        const int64_t p = px0 + pxl;
-        const bool ok = p < P;
-        int64_t base = 0;
-        if (ok) {
-            int64_t n = p / HW;
-            base = n * (int64_t)C * HW + (p - n * HW);
-        }
-        for (int c = tid / PT; c < C; c += 256 / PT) {
-            float v = ok ? x[base + (int64_t)c * HW] : 0.f;
-            xs[pxl * RS + c] = v - mu[c];
-        }
-    }
-    if (Cpad > C) {  // padding channels meet zero basis entries; they must still be finite
-        const int padw = Cpad - C;
-        for (int idx = tid; idx < PT * padw; idx += 256) {
-            int pxl = idx / padw, c = C + (idx - pxl * padw);
-            xs[pxl * RS + c] = 0.f;
-        }
-    }
-    __syncthreads();
-
-    const int zero_sym = 1 << (bits - 1);
-    const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1);
-    constexpr int PG = PT / 32 / MT;  // pixel groups per workgroup
-    const int nunits = ktg * PG;
-    for (int u = wave; u < nunits; u += 4) {
-        const int ktl = u % ktg, pg = u / ktg;
-        const int kt = kt0 + ktl;
-        floatx16 acc[MT];
+        // ---- the pixel tile, mean removed, split, as xh / xl [pixel][channel] ----
+        if constexpr (LAYOUT == FMTC_NHWC && VEC) {
+            const int n4 = PT * (C / 4);  // the tile is one contiguous run of PT*C floats
+            const float* src = p.x + px0 * C;
+            const int64_t lim = (p.P - px0) * C;  // floats of the tile that exist
+            constexpr int B = 8;  // loads in flight per thread
+            for (int idx0 = tid; idx0 < n4; idx0 += B * kWideThreads) {
+                float4 v[B];
 #pragma unroll
-        for (int m = 0; m < MT; m++)
+                for (int b = 0; b < B; b++) {
+                    const int f = 4 * (idx0 + b * kWideThreads);
+                    v[b] = (idx0 + b * kWideThreads < n4 && f < lim) ? *reinterpret_cast<const float4*>(src + f)
+                                                                     : make_float4(0, 0, 0, 0);
+                }
 #pragma unroll
-            for (int r = 0; r < 16; r++) acc[m][r] = 0.f;
-
-        // slot s of the packed basis tile holds channel cs*32 + 2*s + half for this lane
-        const float4* asrc = reinterpret_cast<const float4*>(Apk + ((size_t)kt * ncs * 64 + lane) * 16);
-        float4 a_cur[4], a_nxt[4];
+                for (int b = 0; b < B; b++) {
+                    const int idx = idx0 + b * kWideThreads;
+                    if (idx < n4) {
+                        const int f = 4 * idx;
+                        const int pxl = f / C, c = f - pxl * C;
+                        const float4 m = *reinterpret_cast<const float4*>(p.mu + c);
+                        const float d[4] = {v[b].x - m.x, v[b].y - m.y, v[b].z - m.z, v[b].w - m.w};
+                        halfx4 vh, vl;
+                        float n2 = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; j++) a_cur[j] = asrc[j];
-        const float* brow = xs + (pg * MT * 32 + l32) * RS + half;
-        for (int cs = 0; cs < ncs; cs++) {
-            if (cs + 1 < ncs) {
-                const float4* nsrc = asrc + (size_t)(cs + 1) * 64 * 4;
-#pragma unroll
-                for (int j = 0; j < 4; j++) a_nxt[j] = nsrc[j];
-            }
-#pragma unroll
-            for (int s = 0; s < 16; s++) {
-                float a = reinterpret_cast<const float*>(a_cur)[s];
-#pragma unroll
-                for (int m = 0; m < MT; m++) {
-                    float b = brow[m * 32 * RS + cs * 32 + 2 * s];
-                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[m], 0, 0, 0);
+                        for (int i = 0; i < 4; i++) {
+                            _Float16 a, bb;
+                            split(d[i], a, bb);
+                            vh[i] = a;
+                            vl[i] = bb;
+                            n2 = __builtin_fmaf(d[i], d[i], n2);
+                        }
+                        *reinterpret_cast<halfx4*>(xh + pxl * RSH + c) = vh;
+                        *reinterpret_cast<halfx4*>(xl + pxl * RSH + c) = vl;
+                        atomicAdd(&s_n2[pxl], n2);
+                    }
                 }
             }
-#pragma unroll
-            for (int j = 0; j < 4; j++) a_cur[j] = a_nxt[j];
+        } else if constexpr (LAYOUT == FMTC_NHWC) {
+            const int n1 = PT * C;
+            const float* src = p.x + px0 * C;
+            for (int idx = tid; idx < n1; idx += kWideThreads) {
+                const int pxl = idx / C, c = idx - pxl * C;
+                const float d = ((px0 + pxl < p.P) ? src[idx] : 0.f) - p.mu[c];
+                _Float16 a, b;
+                split(d, a, b);
+                xh[pxl * RSH + c] = a;
+                xl[pxl * RSH + c] = b;
+                atomicAdd(&s_n2[pxl], d * d);
+            }
+        } else {
+            const int pxl = tid % PT;
+            const int64_t px = px0 + pxl;
+            const bool ok = px < p.P;
+            int64_t base = 0;
+            if (ok) {
+                const int64_t n = px / p.HW;
+                base = n * (int64_t)C * p.HW + (px - n * p.HW);
+            }
+            float n2 = 0.f;
+            for (int c = tid / PT; c < C; c += kWideThreads / PT) {
+                const float d = (ok ? p.x[base + (int64_t)c * p.HW] : 0.f) - p.mu[c];
+                _Float16 a, b;
+                split(d, a, b);
+                xh[pxl * RSH + c] = a;
+                xl[pxl * RSH + c] = b;
+                n2 = __builtin_fmaf(d, d, n2);
+            }
+            atomicAdd(&s_n2[pxl], n2);
         }
+        if (Cpad > C) {  // padding channels meet zero basis entries; they must still be finite
+            const int padw = Cpad - C;
+            for (int idx = tid; idx < PT * padw; idx += kWideThreads) {
+                const int pxl = idx / padw, c = C + (idx - pxl * padw);
+                xh[pxl * RSH + c] = (_Float16)0.f;
+                xl[pxl * RSH + c] = (_Float16)0.f;
+            }
+        }
+        __syncthreads();
 
-        // ---- quantize ----
-        // accumulator r of lane l holds coefficient kt*32 + 8*(r/4) + 4*(l/32) + r%4 of pixel l%32
-        uint32_t words[MT][4];
-        uint32_t near_mask = 0;  // bit m*16 + r: the fp32 value is too close to a rounding boundary to be trusted
+        constexpr int PG = PT / 32;  // pixel groups per workgroup
+        const int nunits = ktg * PG;
+        for (int u = wave; u < nunits; u += kWideThreads / 64) {
+            const int pg = u % PG, ktl = u / PG;
+            const int kt = kt0 + ktl;
+            const int pxl = pg * 32 + l32;
+            const bool px_ok = px0 + pxl < p.P;
+            floatx16 am, ac;
 #pragma unroll
-        for (int m = 0; m < MT; m++) {
-            const bool px_ok = px0 + (pg * MT + m) * 32 + l32 < P;
+            for (int r = 0; r < 16; r++) { am[r] = 0.f; ac[r] = 0.f; }
+
+            // (kt, j): the 64 lanes' hi parts, then their lo parts, 16 bytes per lane each; the basis comes from L2
+            // (the wavefronts of a round read the same part of it), one step ahead of its use
+            const uint4* asrc = reinterpret_cast<const uint4*>(p.basis16) + (size_t)kt * NJ * 2 * 64 + lane;
+            uint4 th4 = asrc[0], tl4 = asrc[64];
+            const _Float16* bh = xh + pxl * RSH + 8 * half;
+            const _Float16* bl = xl + pxl * RSH + 8 * half;
+            for (int jj = 0; jj < NJ; jj++) {
+                uint4 nh4 = th4, nl4 = tl4;
+                if (jj + 1 < NJ) {
+                    nh4 = asrc[(size_t)(2 * jj + 2) * 64];
+                    nl4 = asrc[(size_t)(2 * jj + 3) * 64];
+                }
+                const halfx8 th = __builtin_bit_cast(halfx8, th4), tl = __builtin_bit_cast(halfx8, tl4);
+                const halfx8 xh8 = *reinterpret_cast<const halfx8*>(bh + 16 * jj);
+                const halfx8 xl8 = *reinterpret_cast<const halfx8*>(bl + 16 * jj);
+                am = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xh8, am, 0, 0, 0);
+                ac = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xl8, ac, 0, 0, 0);
+                ac = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, xh8, ac, 0, 0, 0);
+                th4 = nh4;
+                tl4 = nl4;
+            }
+
+            // ---- quantize ----
+            // accumulator r = 4g + i of lane (pixel, h) is coefficient kt*32 + 16h + 4g + i of the pixel
+            const float n2 = s_n2[pxl];
+            const bool force = !(n2 < 1.0e9f);  // too large for f16, or not finite: every coefficient decided exactly
+            const float tau = fminf(fmaxf(p.kappa * __builtin_sqrtf(n2), p.tau_min), 0.125f);
+            const float near_limit = force ? -1.f : 0.5f - tau;
+            const int k0 = kt * 32 + 16 * half;
+            uint32_t words[4];
+            uint32_t near_mask = 0;  // bit r: the fast value is too close to a rounding boundary to be trusted
 #pragma unroll
             for (int g = 0; g < 4; g++) {
-                const int k = kt * 32 + 8 * g + 4 * half;
                 uint32_t word = 0;
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
-                    float t = acc[m][4 * g + i] * inv_delta;
+                    const float t = __builtin_fmaf(ac[4 * g + i], inv_delta_lo, am[4 * g + i] * inv_delta);
                     float q = __builtin_rintf(t);  // round half to even
-                    bool near = fabsf(t - q) > 0.5f - tau;
-                    q = fminf(fmaxf(q, lo), hi);
+                    const bool near = !(fabsf(t - q) <= near_limit);
+                    q = __builtin_amdgcn_fmed3f(q, lo, hi);
                     word |= (uint32_t)((int)q + zero_sym) << (8 * i);
-                    if (near && px_ok && (k + i) < C) near_mask |= 1u << (m * 16 + 4 * g + i);
+                    if (near && px_ok && (k0 + 4 * g + i) < C) near_mask |= 1u << (4 * g + i);
                 }
-                words[m][g] = word;
+                words[g] = word;
             }
-        }
-        // ---- exact decision for the flagged values: fp64 recomputation, four values per round ----
-        // (same arithmetic as the definition: sum of T[k][c] * (x[c] - mu[c]), divided by the step).
-        // Each 16-lane group of the wavefront takes one flagged value, so the loads of four values overlap.
-        unsigned long long pending = __ballot(near_mask != 0);
-        while (pending) {
-            int Ls[4];
-            unsigned long long pm = pending;
+            // ---- exact decision for the flagged values: fp64 recomputation, four values per round ----
+            // (same arithmetic as the definition: sum of T[k][c] * (x[c] - mu[c]), divided by the step).
+            // Each 16-lane group of the wavefront takes one flagged value, so the loads of four values overlap.
+            unsigned long long pending = __ballot(near_mask != 0);
+            while (pending) {
+                int Ls[4];
+                unsigned long long pm = pending;
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
-                Ls[q] = pm ? (__ffsll((long long)pm) - 1) : -1;
-                pm &= pm - 1;
-            }
-            const int grp = lane >> 4;
-            const int Lq = grp == 0 ? Ls[0] : (grp == 1 ? Ls[1] : (grp == 2 ? Ls[2] : Ls[3]));
-            const bool active = Lq >= 0;
-            const uint32_t fm = (uint32_t)__shfl((int)near_mask, active ? Lq : 0, 64);
-            const int v = active ? (__ffs((int)fm) - 1) : 0;
-            const int m = v >> 4, r = v & 15;
-            const int k = kt * 32 + 8 * (r >> 2) + 4 * (Lq >> 5) + (r & 3);
-            const int64_t px = px0 + (pg * MT + m) * 32 + (Lq & 31);
-            double part = 0.0;
-            if (active) {
-                int64_t xbase, xstride;
-                if constexpr (LAYOUT == FMTC_NHWC) {
-                    xbase = px * C;
-                    xstride = 1;
-                } else {
-                    int64_t n = px / HW;
-                    xbase = n * (int64_t)C * HW + (px - n * HW);
-                    xstride = HW;
+                for (int q = 0; q < 4; q++) {
+                    Ls[q] = pm ? (__ffsll((long long)pm) - 1) : -1;
+                    pm &= pm - 1;
                 }
-                for (int c = lane & 15; c < C; c += 16)
-                    part += (double)Trow[(size_t)k * C + c] * ((double)x[xbase + c * xstride] - (double)mu[c]);
-            }
+                const int grp = lane >> 4;
+                const int Lq = grp == 0 ? Ls[0] : (grp == 1 ? Ls[1] : (grp == 2 ? Ls[2] : Ls[3]));
+                const bool active = Lq >= 0;
+                const uint32_t fm = (uint32_t)__shfl((int)near_mask, active ? Lq : 0, 64);
+                const int r = active ? (__ffs((int)fm) - 1) : 0;
+                const int k = kt * 32 + 16 * (Lq >> 5) + r;
+                const int64_t px = px0 + pg * 32 + (Lq & 31);
+                double part = 0.0;
+                if (active) {
+                    int64_t xbase, xstride;
+                    if constexpr (LAYOUT == FMTC_NHWC) {
+                        xbase = px * C;
+                        xstride = 1;
+                    } else {
+                        const int64_t n = px / p.HW;
+                        xbase = n * (int64_t)C * p.HW + (px - n * p.HW);
+                        xstride = p.HW;
+                    }
+                    for (int c = lane & 15; c < C; c += 16)
+                        part += (double)p.Trow[(size_t)k * C + c] * ((double)p.x[xbase + c * xstride] - (double)p.mu[c]);
+                }
 #pragma unroll
-            for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);  // stays inside the 16-lane group
-            double qd = rint(part / (double)delta);
-            qd = fmin(fmax(qd, (double)lo), (double)hi);
-            const int sfix = (int)qd + zero_sym;
+                for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);  // stays inside the 16-lane group
+                double qd = rint(part / (double)p.delta);
+                qd = fmin(fmax(qd, (double)lo), (double)hi);
+                const int sfix = (int)qd + zero_sym;
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
-                const int vq = __shfl(v, 16 * q, 64);
-                const int sq = __shfl(sfix, 16 * q, 64);
-                if (lane == Ls[q]) {
-                    const int mq = vq >> 4, rq = vq & 15;
-#pragma unroll
-                    for (int mm = 0; mm < MT; mm++)
+                for (int q = 0; q < 4; q++) {
+                    const int rq = __shfl(r, 16 * q, 64);
+                    const int sq = __shfl(sfix, 16 * q, 64);
+                    if (lane == Ls[q]) {
 #pragma unroll
                         for (int g = 0; g < 4; g++)
-                            if (mm == mq && g == (rq >> 2))
-                                words[mm][g] = (words[mm][g] & ~(0xffu << (8 * (rq & 3)))) |
-                                               ((uint32_t)sq << (8 * (rq & 3)));
-                    near_mask &= ~(1u << vq);
+                            if (g == (rq >> 2))
+                                words[g] = (words[g] & ~(0xffu << (8 * (rq & 3)))) | ((uint32_t)sq << (8 * (rq & 3)));
+                        near_mask &= ~(1u << rq);
+                    }
                 }
+                pending = __ballot(near_mask != 0);
             }
-            pending = __ballot(near_mask != 0);
-        }
-        // ---- count and stage ----
-        // zero-level symbols (the bulk) are counted with byte arithmetic, the others with LDS atomics
-        uint32_t zero_count = 0;
-        const uint32_t zero4 = (uint32_t)zero_sym * 0x01010101u;
-#pragma unroll
-        for (int m = 0; m < MT; m++) {
-            const int pxl = (pg * MT + m) * 32 + l32;
-            const bool px_ok = px0 + pxl < P;
+            // ---- count and stage ----
+            // zero-level symbols (the bulk) are counted with byte arithmetic, the others with LDS atomics
+            uint32_t zero_count = 0;
+            const uint32_t zero4 = (uint32_t)zero_sym * 0x01010101u;
 #pragma unroll
             for (int g = 0; g < 4; g++) {
-                const int k = kt * 32 + 8 * g + 4 * half;
-                const uint32_t word = words[m][g];
+                const int k = k0 + 4 * g;
+                const uint32_t word = words[g];
                 // 0x80 in every byte of the word that is a valid coefficient
                 const int nvalid = !px_ok ? 0 : (C - k >= 4 ? 4 : (C - k > 0 ? C - k : 0));
                 const uint32_t vmask = nvalid == 4 ? 0x80808080u : (0x80808080u >> (8 * (4 - nvalid))) * (nvalid != 0);
@@ -254,83 +312,106 @@ __global__ __launch_bounds__(256) void k_project_quantize(const float* __restric
                     atomicAdd(&lhist[(word >> (bit - 7)) & 255u], 1u);
                     nz &= nz - 1;
                 }
-                st[pxl * RSW + ktl * 8 + 2 * g + half] = word;
+                st[pxl * RSW + ktl * 8 + 4 * half + g] = word;
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) zero_count += __shfl_xor(zero_count, o, 64);
+            if (lane == 0 && zero_count) atomicAdd(&lhist[zero_sym], zero_count);
+        }
+        __syncthreads();
+
+        // ---- symbols leave as rows of ktg*32 bytes per pixel ----
+        const int kbase = kt0 * 32;
+        const int row_words = ktg * 8;
+        for (int idx = tid; idx < PT * row_words; idx += kWideThreads) {
+            const int row = idx / row_words, col = idx - row * row_words;
+            const int64_t px = px0 + row;
+            const int k = kbase + 4 * col;
+            if (px < p.P && k < C) {
+                const uint32_t word = st[row * RSW + col];
+                uint8_t* dst = p.syms + px * C + k;
+                if constexpr (VEC) {
+                    *reinterpret_cast<uint32_t*>(dst) = word;
+                } else {
+                    for (int i = 0; i < 4 && k + i < C; i++) dst[i] = (uint8_t)(word >> (8 * i));
+                }
             }
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) zero_count += __shfl_xor(zero_count, o, 64);
-        if (lane == 0 && zero_count) atomicAdd(&lhist[zero_sym], zero_count);
     }
     __syncthreads();
-
-    // ---- symbols leave as rows of ktg*32 bytes per pixel ----
-    const int kbase = kt0 * 32;
-    const int row_words = ktg * 8;
-    for (int idx = tid; idx < PT * row_words; idx += 256) {
-        int row = idx / row_words, col = idx - row * row_words;
-        int64_t px = px0 + row;
-        int k = kbase + 4 * col;
-        if (px < P && k < C) {
-            uint32_t word = st[row * RSW + col];
-            uint8_t* dst = syms + px * C + k;
-            if constexpr (VEC) {
-                *reinterpret_cast<uint32_t*>(dst) = word;
-            } else {
-                for (int i = 0; i < 4 && k + i < C; i++) dst[i] = (uint8_t)(word >> (8 * i));
-            }
-        }
-    }
-    __syncthreads();  // the staging tile and xs are reused by the next pixel tile
-    }
     // one row of partial counts per workgroup: nothing to clear beforehand, no global atomics
-    const int K = 1 << bits;
-    if (tid < K) hist_parts[(size_t)(blockIdx.x + blockIdx.y * gridDim.x) * K + tid] = lhist[tid];
+    const int K = 1 << p.bits;
+    if (tid < K) p.hist_parts[(size_t)(blockIdx.x + blockIdx.y * gridDim.x) * K + tid] = lhist[tid];
 }
 
-template <int PT, int MT>
-static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
-                            int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
-    const float inv_delta = (float)(1.0 / (double)delta);
-    // fp32 accumulation of C terms is off by about sqrt(C) * 2^-24 * |x - mu| / delta steps; values within
-    // tau (a few times that) of a rounding boundary are decided in fp64 instead
-    float tau = 8.f * sqrtf((float)b.Cpad) * 5.9604645e-8f * (float)(1 << (bits - 1));
-    tau = fminf(fmaxf(tau, 1.f / 8192.f), 1.f / 128.f);
-    const int ncs = b.Cpad / 32;
-    const int64_t px_tiles = (P + PT - 1) / PT;
-    // split the coefficient range over workgroup rows only when the pixel tiles alone leave the chip idle
-    int kgroups = (int)((256 + px_tiles - 1) / px_tiles);
-    if (kgroups < 1) kgroups = 1;
-    int ktg = (ncs + kgroups - 1) / kgroups;
-    if (ncs >= 4) ktg = (ktg + 3) / 4 * 4;  // whole rounds of the 4 wavefronts
-    if (ktg > 16) ktg = 16;  // bounds the staging tile so that LDS stays below 160 KB at C = 1024
-    if (ktg > ncs) ktg = ncs;
-    kgroups = (ncs + ktg - 1) / ktg;
+static hipError_t launch_wide(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
+                              int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
+    WideParams p;
+    p.x = d_x;
+    p.basis16 = b.fwd16;
+    p.mu = b.mu;
+    p.Trow = b.T;
+    p.P = P;
+    p.HW = HW;
+    p.C = b.C;
+    p.ncs = b.Cpad / 32;
+    p.bits = bits;
+    p.inv_delta = (float)(1.0 / (double)delta);
+    p.delta = delta;
+    // see launch_rows for the bound behind these two
+    p.kappa = 1.9073486e-6f /* 2^-19 */ * b.row_norm * p.inv_delta;
+    p.tau_min = 4.7683716e-7f /* 2^-21 */ * (float)(1 << (bits - 1));
+    p.syms = d_syms;
+    p.hist_parts = cs.hist_parts;
+    p.ctrl = cs.ctrl;
+    p.lookback = cs.lookback;
+    p.n_groups = cs.n_groups;
+    const int ncs = p.ncs;
+    // Pixel tile: the larger it is the fewer times the basis streams through; the tile (both f16 parts) and the
+    // staging rows have to fit LDS, and a small tensor is better off with more, smaller workgroups.
+    const size_t lds_cap = 150 * 1024;
+    int PT = 0, ktg = 0, kgroups = 1;
+    int64_t px_tiles = 0;
+    size_t lds = 0;
+    for (int cand = 128; cand >= 32; cand /= 2) {
+        px_tiles = (P + cand - 1) / cand;
+        // split the coefficient range over workgroup rows only when the pixel tiles alone leave the chip idle
+        kgroups = (int)((256 + px_tiles - 1) / px_tiles);
+        if (kgroups < 1) kgroups = 1;
+        ktg = (ncs + kgroups - 1) / kgroups;
+        if (ktg > 16) ktg = 16;  // bounds the staging rows
+        if (ktg > ncs) ktg = ncs;
+        kgroups = (ncs + ktg - 1) / ktg;
+        lds = (size_t)cand * (b.Cpad + 8) * 4 + sizeof(uint32_t) * (size_t)cand * (ktg * 8 + 1);
+        PT = cand;
+        if (lds <= lds_cap && (px_tiles >= 256 || cand == 32)) break;
+    }
+    if (lds > 158 * 1024) return hipErrorInvalidValue;  // not reachable for C <= 1024
+    p.kt_per_group = ktg;
+    p.px_tiles = px_tiles;
     int64_t gx = px_tiles;
     if (gx * kgroups > kMaxHistParts) gx = kMaxHistParts / kgroups;
     dim3 grid((unsigned)gx, (unsigned)kgroups);
     *n_parts = (int)(gx * kgroups);
-    const size_t lds = sizeof(float) * (size_t)PT * (b.Cpad + 2) + sizeof(uint32_t) * (size_t)PT * (ktg * 8 + 1);
     const bool vec = (b.C % 4) == 0;
     hipError_t el = hipSuccess;
-#define FMTC_PQ(LAY, VEC)                                                                                       \
-    do {                                                                                                        \
-        if (lds > 48 * 1024) {                                                                                  \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project_quantize<PT, MT, LAY, VEC>), \
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);         \
-            if (ea != hipSuccess) return ea;                                                                    \
-        }                                                                                                       \
-        el = launch(K_PROJECT, k_project_quantize<PT, MT, LAY, VEC>, grid, dim3(256), lds, s, d_x, b.fwd, b.mu,  \
-                    b.T, P, HW, b.C, ncs, ktg, inv_delta, delta, tau, bits, px_tiles, d_syms, cs.hist_parts,    \
-                    cs.ctrl, cs.lookback, cs.n_groups);                                                         \
+#define FMTC_WIDE(PTV, LAY, VEC)                                                                                 \
+    do {                                                                                                         \
+        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project_quantize_wide<PTV, LAY, VEC>), \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);              \
+        if (ea != hipSuccess) return ea;                                                                         \
+        el = launch(K_PROJECT, k_project_quantize_wide<PTV, LAY, VEC>, grid, dim3(kWideThreads), lds, s, p);     \
     } while (0)
-    if (layout == FMTC_NHWC) {
-        if (vec) FMTC_PQ(FMTC_NHWC, true);
-        else FMTC_PQ(FMTC_NHWC, false);
-    } else {
-        if (vec) FMTC_PQ(FMTC_NCHW, true);
-        else FMTC_PQ(FMTC_NCHW, false);
-    }
-#undef FMTC_PQ
+#define FMTC_WIDE_PT(LAY, VEC)                                                                                   \
+    do {                                                                                                         \
+        if (PT == 128) FMTC_WIDE(128, LAY, VEC);                                                                 \
+        else if (PT == 64) FMTC_WIDE(64, LAY, VEC);                                                              \
+        else FMTC_WIDE(32, LAY, VEC);                                                                            \
+    } while (0)
+    if (layout == FMTC_NHWC) { if (vec) FMTC_WIDE_PT(FMTC_NHWC, true); else FMTC_WIDE_PT(FMTC_NHWC, false); }
+    else                     { if (vec) FMTC_WIDE_PT(FMTC_NCHW, true); else FMTC_WIDE_PT(FMTC_NCHW, false); }
+#undef FMTC_WIDE_PT
+#undef FMTC_WIDE
     return el;
 }
 
@@ -353,8 +434,6 @@ static hipError_t launch_pq(const BasisDevice& b, const float* d_x, int64_t P, i
 // quantizer of tile kt is scheduled between the matrix instructions of tile kt+1.
 // Histogram: interleaved LDS copies per wavefront.
 // ---------------------------------------------------------------------------
-typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
-
 constexpr int kHistLanes = 16;  // histogram copies per wavefront in the narrow-tensor kernel
 constexpr int kFixList = 64;    // values per wavefront waiting for their exact decision
 
@@ -766,12 +845,8 @@ hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64
                                    float delta, int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts,
                                    hipStream_t s) {
     const int64_t P = N * HW;
-    const int nkt = b.Cpad / 32;
-    if (nkt <= 4) return launch_rows(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
-    if (nkt == 1) return launch_pq<128, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
-    if (nkt == 4) return launch_pq<64, 2>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
-    if (nkt <= 5) return launch_pq<64, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
-    return launch_pq<32, 1>(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
+    if (b.Cpad <= 128) return launch_rows(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
+    return launch_wide(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
 }
 
 // Histogram of given symbols (staged coder entry point): one row of partial counts per workgroup.

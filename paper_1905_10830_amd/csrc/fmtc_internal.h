@@ -108,17 +108,11 @@ inline Workspace make_workspace(uint64_t V, uint32_t n_chunks) {
     return w;
 }
 
-// Operand packing of the basis for the MFMA kernels (32x32x2 f32 tiles):
-// tile (nt, ms), lane l, slot s holds M[nt*32 + l%32][ms*32 + perm(s, l/32)],
-// zero outside CxC.  perm for the forward operand: 2*s + half; for the
-// inverse operand: 8*(s/4) + 4*half + s%4.
+// Device copies of the basis a handle holds.
 struct BasisDevice {
     int C, Cpad;           // Cpad = C rounded up to 32
-    const float* fwd;      // M = T      (row = coefficient k, column = channel c)
-    const float* inv;      // M = T^T    (row = channel c, column = coefficient k), inverse slot order
-    const float* invf;     // M = T^T, forward slot order
-    // M = T and M = T^T for the narrow-tensor kernels: f16 hi/lo split in the operand order of the 32x32x16
-    // matrix instruction, [row tile][step j][part][lane][8] (see pack_operand16); fwd16 with permuted rows
+    // M = T and M = T^T as f16 hi/lo pairs in the operand order of the 32x32x16 matrix instruction,
+    // [row tile][step j][part][lane][8] (see pack_operand16); fwd16 with permuted rows
     const uint16_t* fwd16;
     const uint16_t* inv16;
     float row_norm;        // largest Euclidean norm of a row of T
