@@ -7,7 +7,7 @@
 //      sum of the stored run sizes) decodes into an LDS symbol tile;
 //   3. x_hat = T^T (Delta q) + mu on the f16 matrix cores
 //      (v_mfma_f32_32x32x16_f16; the levels are exact in f16, the basis entries are
-//      split in two f16 parts).  Narrow tensors (up to 128 channels): the wavefront
+//      split in two f16 parts).  Narrow tensors (up to 160 channels): the wavefront
 //      that decoded a chunk also transforms it, the basis sits in LDS in operand
 //      order and no workgroup barrier is needed after the tables.  Wide tensors: a
 //      tile of several chunks per workgroup, the basis streamed from L2.
@@ -615,7 +615,7 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
 }
 
 // ---------------------------------------------------------------------------
-// Narrow tensors (at most 128 channels after padding to 32): a chunk holds at least 32
+// Narrow tensors (at most 160 channels after padding to 32): a chunk holds at least 25
 // pixels, so the wavefront that decoded it has whole matrix tiles of its own.  The inverse
 // transform runs on the f16 matrix cores (v_mfma_f32_32x32x16_f16): the levels s - 2^(b-1)
 // are small integers, exact in f16, and every basis entry is split in two f16 parts,
@@ -836,11 +836,13 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     const bool al = (C % 4) == 0;
     hipError_t el = hipSuccess;
 
-    if (!d_syms && ncs <= 4) {
+    // (five channel tiles: channels-last only, the planar stores take more registers than are left)
+    if (!d_syms && (ncs <= 4 || (ncs == 5 && layout == FMTC_NHWC))) {
         // ---- one wavefront per chunk ----
         const size_t lds = sizeof(float) * (size_t)ncs * 32 * ncs * 32;
         // two wavefronts per SIMD once the chunks outnumber the SIMDs of the device
-        const bool eight = g.n_chunks > 1024 && ncs != 3;  // (three channel tiles need more registers than two wavefronts per SIMD leave)
+        // (three channel tiles need more registers, five more LDS, than two wavefronts per SIMD leave)
+        const bool eight = g.n_chunks > 1024 && ncs != 3 && ncs != 5;
         const int waves = eight ? 8 : 4;
         const size_t lds_static = sizeof(DecTables) + (size_t)waves * ((kPayWords + 2 + kPayOverrun) * 4 + kChunkTileBytes) + 1024;
         const unsigned per_cu = (unsigned)((160 * 1024) / (lds + lds_static));
@@ -863,8 +865,9 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         else if (ncs == 3) FMTC_DECC(3, LAY, AL, 4);                                                             \
         else { if (eight) FMTC_DECC(4, LAY, AL, 8); else FMTC_DECC(4, LAY, AL, 4); }                             \
     } while (0)
-        if (layout == FMTC_NHWC) { if (al) FMTC_DECC_N(FMTC_NHWC, true); else FMTC_DECC_N(FMTC_NHWC, false); }
-        else                     { if (al) FMTC_DECC_N(FMTC_NCHW, true); else FMTC_DECC_N(FMTC_NCHW, false); }
+        if (ncs == 5) { if (al) FMTC_DECC(5, FMTC_NHWC, true, 4); else FMTC_DECC(5, FMTC_NHWC, false, 4); }
+        else if (layout == FMTC_NHWC) { if (al) FMTC_DECC_N(FMTC_NHWC, true); else FMTC_DECC_N(FMTC_NHWC, false); }
+        else                          { if (al) FMTC_DECC_N(FMTC_NCHW, true); else FMTC_DECC_N(FMTC_NCHW, false); }
 #undef FMTC_DECC_N
 #undef FMTC_DECC
         return el;

@@ -7,7 +7,7 @@
 // split into two f16 parts, which is as accurate as the fp32 matrix instruction
 // and several times as fast; values that land too close to a rounding boundary
 // for the fast pass to decide are recomputed in fp64 by the wavefront.  Two
-// kernels: one wavefront per 32 pixels with the basis in LDS (up to 128
+// kernels: one wavefront per 32 pixels with the basis in LDS (up to 160
 // channels), and a workgroup tile in LDS with the basis streamed from L2 (wider).
 #include <type_traits>
 
@@ -27,7 +27,7 @@ __device__ __forceinline__ void zero_coder_scratch(CoderCtrl* ctrl, unsigned lon
 }
 
 // ---------------------------------------------------------------------------
-// Wide tensors (more than 128 channels after padding to 32).  The contraction is the same f16
+// Wide tensors (more than 160 channels after padding to 32).  The contraction is the same f16
 // split as in the narrow-tensor kernel below (three v_mfma_f32_32x32x16_f16 per 16 channels,
 // see there), but a pixel's channels no longer fit a wavefront's registers: the workgroup
 // (8 wavefronts) first brings a tile of PT pixels, all channels, into LDS -- coalesced global
@@ -416,7 +416,7 @@ static hipError_t launch_wide(const BasisDevice& b, const float* d_x, int64_t P,
 }
 
 // ---------------------------------------------------------------------------
-// Narrow tensors (at most 128 channels after padding to 32).  One wavefront owns 32 pixels
+// Narrow tensors (at most 160 channels after padding to 32).  One wavefront owns 32 pixels
 // for all coefficients.  The contraction runs on the f16 matrix cores with every fp32 operand
 // split in two f16 parts, v = hi + lo / 2^11 (hi = v rounded to f16, lo = 2^11 times the rest
 // rounded to f16: 22 significant bits in all, and the scaling keeps lo out of the subnormals):
@@ -638,8 +638,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 const uint32_t idx = base + (uint32_t)(lane >> 4);
                 const bool active = idx < n;
                 const uint32_t e = active ? fix_list[idx] : 0u;
-                const int k = (int)(e & 127u), pl = (int)((e >> 7) & 31u);
-                const uint32_t old = e >> 12;
+                const int k = (int)(e & 255u), pl = (int)((e >> 8) & 31u);
+                const uint32_t old = e >> 13;
                 const int64_t qpx = tile * 32 + pl;
                 int64_t xbase, xstride;
                 if constexpr (LAYOUT == FMTC_NHWC) {
@@ -695,8 +695,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 for (int r = 0; r < 16; r++) {
                     if ((near_mask >> r) & 1u) {
                         const uint32_t slot = atomicAdd(fix_count, 1u);
-                        fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 7) |
-                                         (((word[r >> 2] >> (8 * (r & 3))) & 255u) << 12);
+                        fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 8) |
+                                         (((word[r >> 2] >> (8 * (r & 3))) & 255u) << 13);
                     }
                     wave_sync_lds();
                     resolve_list();
@@ -710,13 +710,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                     for (int g = 0; g < 4; g++)
                         if (g == (r >> 2)) sy = (word[g] >> (8 * (r & 3))) & 255u;
                     const uint32_t slot = atomicAdd(fix_count, 1u);
-                    fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 7) | (sy << 12);
+                    fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 8) | (sy << 13);
                 }
                 wave_sync_lds();
             }
         };
 
-        const bool full = (tile * 32 + 32 <= p.P) && (C == NCT * 32);  // wavefront-uniform
+        // whole pixel tile, and every lane's 16 coefficients of a tile all inside C or all outside (wavefront-uniform)
+        const bool full = (tile * 32 + 32 <= p.P) && (C % 16 == 0);
         floatx16 am, ac;
         project_tile(0, am, ac);
         if (full) {
@@ -730,13 +731,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 for (int r = 0; r < 16; r++) { nm[r] = 0.f; nc[r] = 0.f; }
                 uint32_t word[4] = {0u, 0u, 0u, 0u};
                 float maxd = 0.f;
+                const bool k_ok = kt * 32 + 16 * half < C;  // false only in the upper half of a padded last tile
                 auto quantize_value = [&](int r) {
                     const float t = __builtin_fmaf(ac[r], inv_delta_lo, am[r] * inv_delta);
                     const float q = __builtin_rintf(t);  // round half to even
                     maxd = fmaxf(maxd, fabsf(t - q));
                     const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
                     word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
-                    atomicAdd(&wh[(uint32_t)qc * kHistLanes], 1u);
+                    if (k_ok) atomicAdd(&wh[(uint32_t)qc * kHistLanes], 1u);
                 };
                 if (kt + 1 < NCT) {
 #pragma unroll
@@ -754,10 +756,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
                     for (int r = 0; r < 16; r++) quantize_value(r);
                 }
-                // FULL implies C = 32 * NCT: every lane's 16 symbols are a 16-byte aligned piece of its pixel's row
-                *reinterpret_cast<uint4*>(p.syms + px * C + kt * 32 + 16 * half) =
-                    make_uint4(word[0], word[1], word[2], word[3]);
-                if (__builtin_expect(__any(!(maxd <= near_limit)), 0)) note_tile(am, ac, kt, word);
+                // C is a multiple of 16: every lane's 16 symbols are a 16-byte aligned piece of its pixel's row
+                if (k_ok)
+                    *reinterpret_cast<uint4*>(p.syms + px * C + kt * 32 + 16 * half) =
+                        make_uint4(word[0], word[1], word[2], word[3]);
+                if (__builtin_expect(__any(!(maxd <= near_limit) && k_ok), 0)) note_tile(am, ac, kt, word);
                 am = nm;
                 ac = nc;
             }
@@ -834,8 +837,10 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
         else if (nct == 3) FMTC_ROWS(3, LAY, VEC);                                                               \
         else FMTC_ROWS(4, LAY, VEC);                                                                             \
     } while (0)
-    if (layout == FMTC_NHWC) { if (vec) FMTC_ROWS_N(FMTC_NHWC, true); else FMTC_ROWS_N(FMTC_NHWC, false); }
-    else                     { if (vec) FMTC_ROWS_N(FMTC_NCHW, true); else FMTC_ROWS_N(FMTC_NCHW, false); }
+    if (nct == 5) {  // channels-last only (see launch_project_quantize)
+        if (vec) FMTC_ROWS(5, FMTC_NHWC, true); else FMTC_ROWS(5, FMTC_NHWC, false);
+    } else if (layout == FMTC_NHWC) { if (vec) FMTC_ROWS_N(FMTC_NHWC, true); else FMTC_ROWS_N(FMTC_NHWC, false); }
+    else                            { if (vec) FMTC_ROWS_N(FMTC_NCHW, true); else FMTC_ROWS_N(FMTC_NCHW, false); }
 #undef FMTC_ROWS_N
 #undef FMTC_ROWS
     return el;
@@ -845,7 +850,10 @@ hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64
                                    float delta, int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts,
                                    hipStream_t s) {
     const int64_t P = N * HW;
-    if (b.Cpad <= 128) return launch_rows(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
+    // 160 padded channels still fit the one-wavefront-per-32-pixels kernel for channels-last tensors (planar
+    // loads take more registers than it has left)
+    if (b.Cpad <= 128 || (b.Cpad == 160 && layout == FMTC_NHWC))
+        return launch_rows(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
     return launch_wide(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
 }
 
