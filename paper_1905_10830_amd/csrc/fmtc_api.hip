@@ -207,9 +207,10 @@ CoderScratch coder_scratch(uint8_t* ws, const EncodePlan& pl) {
 
 // partial histograms -> table -> run sizes, chunk offsets and payload
 fmtc_status run_coder(const uint8_t* d_syms, const EncodePlan& pl, const CoderScratch& cs, int n_parts, int bits,
-                      float delta, uint8_t* ws, uint8_t* d_stream, uint64_t* d_out_bytes, hipStream_t s) {
+                      float delta, uint8_t* ws, uint8_t* d_stream, size_t cap, uint64_t* d_out_bytes, hipStream_t s) {
     uint64_t* enc_table = reinterpret_cast<uint64_t*>(ws + pl.ws.off_enc_table);
-    hipError_t e = launch_coder(d_syms, pl.g, bits, delta, cs, n_parts, enc_table, d_stream, d_out_bytes, s);
+    const uint64_t cap_words = cap > pl.g.off_payload ? (cap - pl.g.off_payload) / 4 : 0;
+    hipError_t e = launch_coder(d_syms, pl.g, bits, delta, cs, n_parts, enc_table, d_stream, cap_words, d_out_bytes, s);
     if (e != hipSuccess) return hip_fail(e, "coder kernels");
     return FMTC_OK;
 }
@@ -407,7 +408,7 @@ fmtc_status fmtc_encode(const fmtc_basis* basis, const float* d_x, int64_t N, in
     const float delta = fmtc_delta(basis->range_A, bits);
     if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, syms, cs, &n_parts, s)) != hipSuccess)
         return hip_fail(e, "project/quantize kernel");
-    return run_coder(syms, pl, cs, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
+    return run_coder(syms, pl, cs, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), cap, d_out_bytes, s);
 }
 
 fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits, int chunk_syms, float delta,
@@ -428,7 +429,7 @@ fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits,
     hipError_t e;
     int n_parts = 0;
     if ((e = launch_histogram(d_syms, pl.V, bits, cs, &n_parts, s)) != hipSuccess) return hip_fail(e, "histogram kernel");
-    return run_coder(d_syms, pl, cs, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), d_out_bytes, s);
+    return run_coder(d_syms, pl, cs, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), cap, d_out_bytes, s);
 }
 
 static fmtc_status decode_common(const fmtc_basis* basis, const void* d_stream_in, size_t bytes, int64_t P, int C,

@@ -436,6 +436,7 @@ struct PackParams {
     unsigned long long* lookback;
     Header hdr;
     size_t off_sub_bits, off_payload;
+    uint64_t cap_words;          // payload words the output buffer has room for
     uint8_t* stream;
     uint64_t* out_bytes;
 };
@@ -759,7 +760,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                     Header hdr = p.hdr;
                     hdr.payload_words = total_words;
                     hdr.payload_bits = s_payload_bits;
-                    if (p.ctrl->error) hdr.magic = 0u;  // a wait gave up: the stream is not valid
+                    // a wait gave up, or the payload outgrew the buffer (then some chunk was not written): not valid
+                    if (p.ctrl->error || total_words > p.cap_words) hdr.magic = 0u;
                     *reinterpret_cast<Header*>(p.stream) = hdr;
                     if (p.out_bytes) *p.out_bytes = (uint64_t)p.off_payload + 4 * total_words;
                     // alignment gaps between the sections are part of the stream: keep them zero
@@ -770,12 +772,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 }
             }
             // ---- the image leaves with full-width stores; further windows (rare) are built and stored in turn ----
+            // (An optimal code of the tensor's own histogram always fits the capacity the host checked.  Should the
+            // histogram and the symbols ever disagree, nothing is written past the buffer: the stream is marked
+            // invalid instead.)
+            const bool fits = (uint64_t)word0 + n_words <= p.cap_words;
+            if (!fits && lane == 0) p.ctrl->error = 1u;
             uint32_t* out = reinterpret_cast<uint32_t*>(p.stream + p.off_payload) + word0;
             for (uint32_t win = 0; win < n_words; win += kStageWords) {
                 const uint32_t win_words = (n_words - win < (uint32_t)kStageWords) ? n_words - win : (uint32_t)kStageWords;
                 if (win) build_window(win, win_words, nullptr);
                 for (uint32_t i = lane; i < win_words; i += 64) {
-                    out[win + i] = img[i];
+                    if (fits) out[win + i] = img[i];
                     img[i] = 0u;
                 }
                 wave_sync();  // the image is read and clear before the next window or chunk writes it
@@ -806,9 +813,10 @@ static int pack_resident_groups() {
 // Table (a kernel of its own only where every pack workgroup building it would cost more than the launch)
 // and packing.
 hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
-                        int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t* d_out_bytes,
-                        hipStream_t s) {
+                        int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
+                        uint64_t* d_out_bytes, hipStream_t s) {
     PackParams p;
+    p.cap_words = cap_words;
     p.syms = d_syms;
     p.V = (uint64_t)g.P * (uint64_t)g.C;
     p.n_chunks = g.n_chunks;

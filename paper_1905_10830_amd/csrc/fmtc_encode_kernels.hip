@@ -468,6 +468,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     extern __shared__ __align__(16) uint4 basis16[];  // [NCT][NJ][2][64], then the histograms
     __shared__ __align__(16) float s_mu[NCT * 32];
     __shared__ uint32_t s_fix_list[4][kFixList];
+    __shared__ uint32_t s_fix_tile[4][kFixList];
     __shared__ uint32_t s_fix_count[4];
     // Histogram: kHistLanes interleaved copies per wavefront (bin s of copy q at word s * kHistLanes + q), lane l
     // counts in copy l % kHistLanes.  Most symbols of a tile are the same few values: with one copy the LDS
@@ -537,6 +538,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     uint32_t* wh0 = whist + wave * K * kHistLanes;          // this wavefront's histogram, copy 0
     uint32_t* wh = wh0 + (lane & (kHistLanes - 1));         // bin s of this lane's copy: wh[s * kHistLanes]
     uint32_t* fix_list = s_fix_list[wave];
+    uint32_t* fix_tile = s_fix_tile[wave];
     uint32_t* fix_count = &s_fix_count[wave];
     if (lane == 0) *fix_count = 0u;
 
@@ -545,6 +547,60 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's part of the basis has landed in LDS
     __syncthreads();
 
+    // ---- exact decision where the fast pass can not be trusted (rare) ----
+    // A tile notes the values that lie too close to a rounding boundary in the wavefront's list: tile, pixel
+    // lane, coefficient and the symbol already stored and counted.  When the list is full, and after the
+    // wavefront's last tile, the listed values are recomputed in fp64 (same arithmetic as the definition: sum of
+    // T[k][c] * (x[c] - mu[c]), divided by the step), four per round, all loads of a round in flight
+    // together, and the stored symbol and the histogram are patched where the decision differs.
+    auto resolve_list = [&]() {
+        // the symbols that get patched were stored by other lanes of this wavefront: those stores are
+        // acknowledged before the patches go out (this also waits for the next tile's loads; rare)
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        const uint32_t n = (uint32_t)__builtin_amdgcn_readfirstlane((int)*fix_count);
+        for (uint32_t base = 0; base < n; base += 4) {
+            const uint32_t idx = base + (uint32_t)(lane >> 4);
+            const bool active = idx < n;
+            const uint32_t e = active ? fix_list[idx] : 0u;
+            const int k = (int)(e & 255u), pl = (int)((e >> 8) & 31u);
+            const uint32_t old = e >> 13;
+            const int64_t qpx = (int64_t)fix_tile[idx < (uint32_t)kFixList ? idx : 0] * 32 + pl;
+            int64_t xbase, xstride;
+            if constexpr (LAYOUT == FMTC_NHWC) {
+                xbase = qpx * C;
+                xstride = 1;
+            } else {
+                const int64_t n_img = qpx / p.HW;
+                xbase = n_img * (int64_t)C * p.HW + (qpx - n_img * p.HW);
+                xstride = p.HW;
+            }
+            float tv[2 * NCT], xv[2 * NCT], mv[2 * NCT];
+#pragma unroll
+            for (int it = 0; it < 2 * NCT; it++) {
+                const int c = (lane & 15) + 16 * it;
+                const bool in = active && c < C;
+                tv[it] = in ? p.Trow[(size_t)k * C + c] : 0.f;
+                xv[it] = in ? p.x[xbase + c * xstride] : 0.f;
+                mv[it] = in ? s_mu[c] : 0.f;
+            }
+            double part = 0.0;
+#pragma unroll
+            for (int it = 0; it < 2 * NCT; it++) part += (double)tv[it] * ((double)xv[it] - (double)mv[it]);
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);  // stays inside the 16-lane group
+            double qd = rint(part / (double)p.delta);
+            qd = fmin(fmax(qd, (double)lo), (double)hi);
+            const uint32_t sfix = (uint32_t)((int)qd + zero_sym);
+            if (active && (lane & 15) == 0 && sfix != old) {
+                atomicSub(&wh0[old * kHistLanes], 1u);
+                atomicAdd(&wh0[sfix * kHistLanes], 1u);
+                p.syms[qpx * C + k] = (uint8_t)sfix;
+            }
+        }
+        wave_sync_lds();
+        if (lane == 0) *fix_count = 0u;
+        wave_sync_lds();
+    };
     for (; tile < p.n_tiles; tile += (int64_t)gridDim.x * 4) {
         const int64_t px = tile * 32 + l32;
         const bool px_ok = px < p.P;
@@ -623,60 +679,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             }
             return maxd;
         };
-        // ---- exact decision where the fast pass can not be trusted (rare) ----
-        // A tile notes the values that lie too close to a rounding boundary in the wavefront's list: pixel lane,
-        // coefficient and the symbol already stored and counted.  When the list is full, and after the last
-        // tile of the pixels, the listed values are recomputed in fp64 (same arithmetic as the definition: sum of
-        // T[k][c] * (x[c] - mu[c]), divided by the step), four per round, all loads of a round in flight
-        // together, and the stored symbol and the histogram are patched where the decision differs.
-        auto resolve_list = [&]() {
-            // the symbols that get patched were stored by other lanes of this wavefront: those stores are
-            // acknowledged before the patches go out (this also waits for the next tile's loads; rare)
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            const uint32_t n = (uint32_t)__builtin_amdgcn_readfirstlane((int)*fix_count);
-            for (uint32_t base = 0; base < n; base += 4) {
-                const uint32_t idx = base + (uint32_t)(lane >> 4);
-                const bool active = idx < n;
-                const uint32_t e = active ? fix_list[idx] : 0u;
-                const int k = (int)(e & 255u), pl = (int)((e >> 8) & 31u);
-                const uint32_t old = e >> 13;
-                const int64_t qpx = tile * 32 + pl;
-                int64_t xbase, xstride;
-                if constexpr (LAYOUT == FMTC_NHWC) {
-                    xbase = qpx * C;
-                    xstride = 1;
-                } else {
-                    const int64_t n_img = qpx / p.HW;
-                    xbase = n_img * (int64_t)C * p.HW + (qpx - n_img * p.HW);
-                    xstride = p.HW;
-                }
-                float tv[2 * NCT], xv[2 * NCT], mv[2 * NCT];
-#pragma unroll
-                for (int it = 0; it < 2 * NCT; it++) {
-                    const int c = (lane & 15) + 16 * it;
-                    const bool in = active && c < C;
-                    tv[it] = in ? p.Trow[(size_t)k * C + c] : 0.f;
-                    xv[it] = in ? p.x[xbase + c * xstride] : 0.f;
-                    mv[it] = in ? s_mu[c] : 0.f;
-                }
-                double part = 0.0;
-#pragma unroll
-                for (int it = 0; it < 2 * NCT; it++) part += (double)tv[it] * ((double)xv[it] - (double)mv[it]);
-#pragma unroll
-                for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);  // stays inside the 16-lane group
-                double qd = rint(part / (double)p.delta);
-                qd = fmin(fmax(qd, (double)lo), (double)hi);
-                const uint32_t sfix = (uint32_t)((int)qd + zero_sym);
-                if (active && (lane & 15) == 0 && sfix != old) {
-                    atomicSub(&wh0[old * kHistLanes], 1u);
-                    atomicAdd(&wh0[sfix * kHistLanes], 1u);
-                    p.syms[qpx * C + k] = (uint8_t)sfix;
-                }
-            }
-            wave_sync_lds();
-            if (lane == 0) *fix_count = 0u;
-            wave_sync_lds();
-        };
         auto note_tile = [&](const floatx16& am, const floatx16& ac, int kt, const uint32_t (&word)[4]) {
             const int k0 = kt * 32 + 16 * half;
             uint32_t near_mask = 0;
@@ -697,6 +699,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                         const uint32_t slot = atomicAdd(fix_count, 1u);
                         fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 8) |
                                          (((word[r >> 2] >> (8 * (r & 3))) & 255u) << 13);
+                        fix_tile[slot] = (uint32_t)tile;
                     }
                     wave_sync_lds();
                     resolve_list();
@@ -711,6 +714,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                         if (g == (r >> 2)) sy = (word[g] >> (8 * (r & 3))) & 255u;
                     const uint32_t slot = atomicAdd(fix_count, 1u);
                     fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 8) | (sy << 13);
+                    fix_tile[slot] = (uint32_t)tile;
                 }
                 wave_sync_lds();
             }
@@ -775,8 +779,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 if (kt + 1 < NCT) { am = nm; ac = nc; }
             }
         }
-        if (*fix_count) resolve_list();
     }
+    if (*fix_count) resolve_list();
     __syncthreads();
     // one row of partial counts per workgroup: nothing to clear beforehand, no global atomics
     if (tid < K) {

@@ -160,8 +160,8 @@ hipError_t launch_histogram_sum(const uint32_t* d_hist_parts, int n_parts, int b
                                 hipStream_t s);
 
 hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
-                        int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t* d_out_bytes,
-                        hipStream_t s);
+                        int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
+                        uint64_t* d_out_bytes, hipStream_t s);
 
 hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
                          int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, hipStream_t s);
