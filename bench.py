@@ -27,7 +27,11 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense f16 matrix rate (the projections run as s
 # HBM traffic per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by what the
 # same counters read for the 64 MiB yardstick copy (profiles/*_pmc.txt has the numbers and the commands), keyed
 # by (workload, bits, kernel).  None where no counter run exists.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    ("resnet18_stage2_c128_28", 6, "k_project_quantize"): 17393575,
+    ("resnet18_stage2_c128_28", 6, "k_pack"): 7305728,
+    ("resnet18_stage2_c128_28", 6, "k_decode"): 15293732,
+}
 
 
 def main():
