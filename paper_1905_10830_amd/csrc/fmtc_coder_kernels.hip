@@ -421,6 +421,7 @@ hipError_t launch_histogram_sum(const uint32_t* d_hist_parts, int n_parts, int b
 // ---------------------------------------------------------------------------
 constexpr int kStageWords = 2048;  // per wavefront: 64 Kbit, i.e. 16 bits/symbol over a 4096-symbol chunk
 constexpr unsigned long long kFlagAggregate = 1ull << 32, kFlagInclusive = 2ull << 32;
+constexpr int kLook = 4;  // look-back entries a lane reads per poll (each is an uncached device-scope load: wider windows cost more than the extra round trips they save)
 constexpr uint32_t kSpinLimit = 1u << 22;  // polls before a wait gives up (seconds; never reached unless the
                                            // workspace is overwritten while the kernel runs)
 
@@ -691,7 +692,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 
         // ---- the group's first payload word: the words of all groups before it ----
         if (wave == 0 && group != 0) {
-            // windows of 256 predecessors, nearest first; lane l reads four of them
+            // windows of 64 * kLook predecessors, nearest first; lane l reads kLook of them, all loads in flight
+            // together
             uint32_t excl = 0;
             uint32_t top = group;  // predecessors [0, top) are still to be accounted for
             bool failed = false;
@@ -700,17 +702,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 bool found = false;  // met a running total: everything before it is included
                 bool ready = false;
                 for (uint32_t tries = 0; tries < kSpinLimit; tries++) {
-                    unsigned long long e[4];
+                    unsigned long long e[kLook];
 #pragma unroll
-                    for (int j = 0; j < 4; j++) {
-                        const uint32_t back = 4u * (uint32_t)lane + (uint32_t)j + 1u;  // distance to the predecessor
+                    for (int j = 0; j < kLook; j++) {
+                        const uint32_t back = (uint32_t)kLook * (uint32_t)lane + (uint32_t)j + 1u;  // distance to the predecessor
                         e[j] = (back <= top) ? peek64(&p.lookback[top - back]) : kFlagAggregate;
                     }
                     sum = 0;
                     found = false;
                     bool ok = true;
 #pragma unroll
-                    for (int j = 0; j < 4; j++) {
+                    for (int j = 0; j < kLook; j++) {
                         if (!found) {
                             if (e[j] == 0) ok = false;
                             sum += (uint32_t)e[j];
@@ -735,7 +737,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 const uint32_t part = (lane <= first) ? sum : 0u;
                 excl += wave_sum(part);
                 if (fmask) break;
-                top = (top > 256u) ? top - 256u : 0u;
+                top = (top > 64u * kLook) ? top - 64u * kLook : 0u;
             }
             if (failed) {
                 if (lane == 0) p.ctrl->error = 1u;

@@ -349,6 +349,9 @@ struct DecodeParams {
     float* xhat;       // NULL in symbols-only mode
     uint8_t* syms_out; // non-NULL in symbols-only mode
     uint32_t* err;
+    // where the side information and the payload start if the stream was made with the nominal chunk size
+    size_t g_off_chunk_off, g_off_sub_bits, g_off_payload;
+    uint32_t g_n_chunks, g_spc;
 };
 
 // Header checks.  Returns false unless the header matches the arguments and the
@@ -660,18 +663,49 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             if (THREADS * i + 64 * wave < kBasisPieces)  // whole wavefronts
                 __builtin_amdgcn_global_load_lds(src + tid + THREADS * i, &basis16[THREADS * i + 64 * wave], 16, 0, 0);
     }
+    // The first chunk's offsets, run sizes and payload are requested before the header has arrived, at the places
+    // the nominal chunk size puts them: three dependent memory round trips (header, offsets, payload) become
+    // two that overlap with the table build.  The guess is checked against the header below; a stream made with
+    // another chunk size loads them again.  Nothing outside [stream, stream + bytes) is touched either way.
+    const uint32_t ch_first = blockIdx.x * WAVES + (uint32_t)wave;
+    constexpr int kPrePay = (kPayWords + 2 + 63) / 64;
+    const bool guess = p.g_off_payload <= p.bytes && ch_first < p.g_n_chunks;
+    uint32_t pre_w0 = 0, pre_w1 = 0, pre_run = 0;
+    uint32_t pre_pay[kPrePay];
+    bool pay_pre = false;
+    if (guess) {
+        const uint32_t* co = reinterpret_cast<const uint32_t*>(p.stream + p.g_off_chunk_off);
+        const uint16_t* sb = reinterpret_cast<const uint16_t*>(p.stream + p.g_off_sub_bits);
+        pre_w0 = co[ch_first];
+        pre_w1 = co[ch_first + 1];
+        pre_run = ((uint32_t)lane < p.g_spc) ? sb[(size_t)ch_first * p.g_spc + lane] : 0u;
+        const size_t cap_words = (p.bytes - p.g_off_payload) / 4;
+        const uint32_t gw0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)pre_w0);
+        const uint32_t gw1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)pre_w1);
+        pay_pre = gw0 <= gw1 && (size_t)gw1 <= cap_words && gw1 - gw0 <= (uint32_t)kPayWords;
+        if (pay_pre) {
+            const uint32_t* pay_src = reinterpret_cast<const uint32_t*>(p.stream + p.g_off_payload) + gw0;
+#pragma unroll
+            for (int k = 0; k < kPrePay; k++) {
+                const uint32_t i = (uint32_t)lane + 64u * k;
+                pre_pay[k] = (i < gw1 - gw0) ? pay_src[i] : 0u;
+            }
+        }
+    }
     StreamView sv;
     if (!open_stream(p, &sv)) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(p.err, FMTC_ERR_HEADER);
         return;
     }
-    // the first chunk's offsets and run sizes are on their way while the tables are built
-    const uint32_t ch_first = blockIdx.x * WAVES + (uint32_t)wave;
-    uint32_t pre_w0 = 0, pre_w1 = 0, pre_run = 0;
-    if (ch_first < sv.n_chunks) {
-        pre_w0 = sv.chunk_off[ch_first];
-        pre_w1 = sv.chunk_off[ch_first + 1];
-        pre_run = ((uint32_t)lane < sv.spc) ? sv.sub_bits[(size_t)ch_first * sv.spc + lane] : 0u;
+    const bool guess_valid = guess && sv.n_chunks == p.g_n_chunks && sv.spc == p.g_spc;  // same section offsets
+    const uint32_t guess_w0 = pre_w0, guess_w1 = pre_w1;
+    if (!guess_valid) {
+        pre_w0 = 0; pre_w1 = 0; pre_run = 0;
+        if (ch_first < sv.n_chunks) {
+            pre_w0 = sv.chunk_off[ch_first];
+            pre_w1 = sv.chunk_off[ch_first + 1];
+            pre_run = ((uint32_t)lane < sv.spc) ? sv.sub_bits[(size_t)ch_first * sv.spc + lane] : 0u;
+        }
     }
     if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
     if (!build_decode_tables<THREADS>(T, my_len, p.bits)) {
@@ -708,7 +742,14 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         const uint32_t nwords = w1 - w0;
         bool ok_run = true;
         if (nwords <= (uint32_t)kPayWords) {
-            for (uint32_t i = lane; i < nwords + 2; i += 64) pw[i] = (i < nwords) ? sv.payload[w0 + i] : 0u;
+            if (first && guess_valid && pay_pre && w0 == guess_w0 && w1 == guess_w1) {
+                // the words requested at the start of the kernel (zero past the chunk's end)
+#pragma unroll
+                for (int k = 0; k < kPrePay; k++)
+                    if ((uint32_t)lane + 64u * k < nwords + 2) pw[lane + 64 * k] = pre_pay[k];
+            } else {
+                for (uint32_t i = lane; i < nwords + 2; i += 64) pw[i] = (i < nwords) ? sv.payload[w0 + i] : 0u;
+            }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             // run `lane` goes to bytes [68 * lane, 68 * lane + 64) of the tile (sym_addr), 4 pad bytes behind it
@@ -833,6 +874,11 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     p.err = d_err;
     p.G = 1;
     p.ct_per_group = 1;
+    p.g_off_chunk_off = g.off_chunk_off;
+    p.g_off_sub_bits = g.off_sub_bits;
+    p.g_off_payload = g.off_payload;
+    p.g_n_chunks = g.n_chunks;
+    p.g_spc = g.subs_per_chunk;
     const bool al = (C % 4) == 0;
     hipError_t el = hipSuccess;
 
