@@ -470,6 +470,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __shared__ uint32_t s_fix_list[4][kFixList];
     __shared__ uint32_t s_fix_tile[4][kFixList];
     __shared__ uint32_t s_fix_count[4];
+    __shared__ uint32_t s_red[4 * 256];  // per (wavefront, bin) sums of the histogram copies
     // Histogram: kHistLanes interleaved copies per wavefront (bin s of copy q at word s * kHistLanes + q), lane l
     // counts in copy l % kHistLanes.  Most symbols of a tile are the same few values: with one copy the LDS
     // would serialise up to 64 additions to one word per instruction, and the reads of the basis queue up
@@ -782,14 +783,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
     if (*fix_count) resolve_list();
     __syncthreads();
-    // one row of partial counts per workgroup: nothing to clear beforehand, no global atomics
-    if (tid < K) {
+    // One row of partial counts per workgroup: nothing to clear beforehand, no global atomics.  Every thread sums
+    // the 16 copies of some (wavefront, bin) rows with 16-byte reads (a row is contiguous; reading one copy of
+    // many bins instead would put all lanes on two banks), then the first K threads add the four wavefronts.
+    for (int row = tid; row < 4 * K; row += 256) {
+        const uint4* r4 = reinterpret_cast<const uint4*>(whist + (size_t)row * kHistLanes);
         uint32_t total = 0;
-        for (int w = 0; w < 4; w++)
 #pragma unroll
-            for (int q = 0; q < kHistLanes; q++) total += whist[(w * K + tid) * kHistLanes + q];
-        p.hist_parts[(size_t)blockIdx.x * K + tid] = total;
+        for (int q = 0; q < kHistLanes / 4; q++) {
+            const uint4 v = r4[q];
+            total += (v.x + v.y) + (v.z + v.w);
+        }
+        s_red[row] = total;
     }
+    __syncthreads();
+    if (tid < K)
+        p.hist_parts[(size_t)blockIdx.x * K + tid] = (s_red[tid] + s_red[K + tid]) + (s_red[2 * K + tid] + s_red[3 * K + tid]);
 }
 
 static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
