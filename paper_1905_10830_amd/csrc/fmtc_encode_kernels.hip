@@ -269,6 +269,7 @@ __global__ __launch_bounds__(kWideThreads) void k_project_quantize_wide(WidePara
                         xbase = n * (int64_t)C * p.HW + (px - n * p.HW);
                         xstride = p.HW;
                     }
+#pragma unroll 8  // independent loads of eight terms in flight together: the loop is all latency
                     for (int c = lane & 15; c < C; c += 16)
                         part += (double)p.Trow[(size_t)k * C + c] * ((double)p.x[xbase + c * xstride] - (double)p.mu[c]);
                 }
@@ -859,6 +860,368 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     return el;
 }
 
+// ---------------------------------------------------------------------------
+// Wide tensors whose channel count is a multiple of 16: the projection as a tiled matrix product.
+// A pixel's channels fit neither a wavefront's registers nor (for more than a few pixels) LDS, so
+// the contraction index is cut instead.  A workgroup owns a tile of 128 coefficients x 128 pixels
+// (each of its 4 wavefronts 64 x 64: 2 x 2 matrix tiles with two accumulators each) and walks the
+// channels 16 at a time.  What a step needs goes from L2 / HBM straight into a ring of three LDS
+// slots, two steps ahead of its use and with no registers in between:
+//   basis   8 KB in operand order (wavefront w: both f16 parts of coefficient tile w);
+//   pixels  8 KB of fp32 as they lie in the tensor: thread (pixel, h) of wavefront w its channels
+//           [16 s + 8 h, + 8) of pixel 32 w + pixel -- exactly the operand entry of its lane.
+// One step ahead of the matrix instructions every thread reads its own eight values back,
+// removes the mean, cuts them in their two f16 parts and writes them as pixel operands into one
+// of two LDS buffers; one barrier per step hands a slot and a buffer over.
+// Every operand byte read from LDS feeds two matrix tiles, every basis byte from L2 four pixel
+// tiles -- what the kernel that holds whole pixels in LDS lacks.  The waits count loads in flight
+// (they complete in order), so every wavefront issues the same loads in the same order whatever
+// part of its tile lies outside the tensor: addresses are clamped, values zeroed.  Quantizer,
+// histogram, stores and exact decisions as in the narrow-tensor kernel: a lane ends up with 16
+// consecutive coefficients of its pixel.
+// ---------------------------------------------------------------------------
+struct GemmParams {
+    const float* x;
+    const uint4* basis16;  // fwd16 packing: [ncs][NJ][2][64]
+    const float* mu;       // [Cpad]
+    const float* Trow;
+    int64_t P, HW;
+    int C, ncs, NJ, bits;
+    int64_t n_pt, n_ptg;   // 32-pixel tiles, groups of four of them
+    float inv_delta, delta, kappa, tau_min;
+    int hist_shift;
+    uint8_t* syms;
+    uint32_t* hist_parts;
+    CoderCtrl* ctrl;
+    unsigned long long* lookback;
+    uint32_t n_groups;
+};
+
+constexpr int kGemmFix = 64;  // values per wavefront waiting for their exact decision
+
+// One wavefront's 64 x 16 (or 64 x 4) bytes from global memory straight into LDS, lane l to lds_base + 16 l
+// (4 l).  Written as assembly because the compiler, which cannot tell the LDS stages apart, would hold every
+// later LDS read until all transfers it knows of have landed -- the full latency, in every step; the kernel
+// counts its loads in flight itself (s_waitcnt vmcnt, then a barrier) before it reads a stage.
+typedef __attribute__((address_space(3))) void lds_void_t;
+template <int BYTES>
+__device__ __forceinline__ void load_to_lds(const void* src, void* lds_base) {
+    const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(lds_void_t*)lds_base);
+    uint32_t keep;
+    if constexpr (BYTES == 16)
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep) : "v"(src), "s"(base) : "memory");
+    else
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %1, off\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep) : "v"(src), "s"(base) : "memory");
+}
+
+// Wait until at most N of this wavefront's loads are in flight (they complete in order); no memory access
+// moves across it.
+template <int N>
+__device__ __forceinline__ void wait_loads() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+template <int LAYOUT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_project_quantize_gemm(GemmParams p) {
+    __shared__ __align__(16) uint4 stageA[3][8][64];     // per 16-channel step: (coefficient tile, part), operand order
+    __shared__ __align__(16) uint4 stageX[3][4][2][64];  // per step: fp32 pixels as loaded, [wavefront][instruction][lane]
+    __shared__ __align__(16) uint4 stageB[2][4][2][64];  // per step: (pixel tile, part), operand order
+    __shared__ float s_n2[4][32];
+    __shared__ uint32_t s_fix_a[4][kGemmFix], s_fix_px[4][kGemmFix], s_fix_count[4];
+    extern __shared__ __align__(16) uint8_t dyn_lds[];    // mean [Cpad], then histogram copies [4][K << HS]
+    constexpr int XL = LAYOUT == FMTC_NHWC ? 2 : 8;       // transfers of one step's pixels per wavefront
+    constexpr int LD = 2 + XL;                            // ... of one step in all (basis: 2)
+
+    zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    const int C = p.C, NJ = p.NJ, K = 1 << p.bits, HS = p.hist_shift, HC = 1 << HS;
+    const int ktp = wave & 1, ptp = wave >> 1;  // this wavefront's pair of coefficient tiles / pixel tiles
+    const int kt0 = blockIdx.y * 4;
+    float* s_mu = reinterpret_cast<float*>(dyn_lds);
+    uint32_t* whist = reinterpret_cast<uint32_t*>(dyn_lds) + 16 * NJ;
+    for (int i = tid; i < 4 * K * HC; i += 256) whist[i] = 0u;
+    for (int i = tid; i < 16 * NJ; i += 256) s_mu[i] = p.mu[i];
+    uint32_t* wh0 = whist + wave * K * HC;
+    uint32_t* wh = wh0 + (lane & (HC - 1));
+    uint32_t* fix_a = s_fix_a[wave];
+    uint32_t* fix_px = s_fix_px[wave];
+    uint32_t* fix_count = &s_fix_count[wave];
+    if (lane == 0) *fix_count = 0u;
+    __syncthreads();
+
+    const int zero_sym = 1 << (p.bits - 1);
+    const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1), zero_f = (float)zero_sym;
+    const float inv_delta = p.inv_delta, inv_delta_lo = p.inv_delta * (1.f / 2048.f);
+
+    // exact fp64 decision of the listed values, four per round (one per 16-lane group)
+    auto resolve_list = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // the symbols that get patched have been stored
+        const uint32_t n = (uint32_t)__builtin_amdgcn_readfirstlane((int)*fix_count);
+        for (uint32_t base = 0; base < n; base += 4) {
+            const uint32_t idx = base + (uint32_t)(lane >> 4);
+            const bool active = idx < n;
+            const uint32_t e = active ? fix_a[idx] : 0u;
+            const int k = (int)(e & 0xffffu);
+            const uint32_t old = e >> 16;
+            const int64_t qpx = active ? (int64_t)fix_px[idx] : 0;
+            int64_t xbase, xstride;
+            if constexpr (LAYOUT == FMTC_NHWC) {
+                xbase = qpx * C;
+                xstride = 1;
+            } else {
+                const int64_t n_img = qpx / p.HW;
+                xbase = n_img * (int64_t)C * p.HW + (qpx - n_img * p.HW);
+                xstride = p.HW;
+            }
+            double part = 0.0;
+            if (active)
+#pragma unroll 8  // independent loads of eight terms in flight together: the loop is all latency
+                for (int c = lane & 15; c < C; c += 16)
+                    part += (double)p.Trow[(size_t)k * C + c] * ((double)p.x[xbase + c * xstride] - (double)p.mu[c]);
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);  // stays inside the 16-lane group
+            double qd = rint(part / (double)p.delta);
+            qd = fmin(fmax(qd, (double)lo), (double)hi);
+            const uint32_t sfix = (uint32_t)((int)qd + zero_sym);
+            if (active && (lane & 15) == 0 && sfix != old) {
+                atomicSub(&wh0[old << HS], 1u);
+                atomicAdd(&wh0[sfix << HS], 1u);
+                p.syms[qpx * C + k] = (uint8_t)sfix;
+            }
+        }
+        wave_sync_lds();
+        if (lane == 0) *fix_count = 0u;
+        wave_sync_lds();
+    };
+
+    for (int64_t ptg = blockIdx.x; ptg < p.n_ptg; ptg += gridDim.x) {
+        const int64_t pt0 = ptg * 4;
+        floatx16 am[2][2], ac[2][2];
+#pragma unroll
+        for (int a = 0; a < 2; a++)
+#pragma unroll
+            for (int b = 0; b < 2; b++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) { am[a][b][r] = 0.f; ac[a][b][r] = 0.f; }
+
+        // this thread's pixel (of pixel tile pt0 + wave); past the end of the tensor the last pixel is loaded
+        // in its place and zeroed on conversion
+        const int64_t px_raw = (pt0 + wave) * 32 + l32;
+        const bool px_ok = px_raw < p.P;
+        const int64_t px_ld = px_ok ? px_raw : p.P - 1;
+        int64_t xbase, xstride;
+        if constexpr (LAYOUT == FMTC_NHWC) {
+            xbase = px_ld * C;
+            xstride = 1;
+        } else {
+            const int64_t n_img = px_ld / p.HW;
+            xbase = n_img * (int64_t)C * p.HW + (px_ld - n_img * p.HW);
+            xstride = p.HW;
+        }
+        int kt_ld = kt0 + wave;
+        kt_ld = kt_ld < p.ncs ? kt_ld : p.ncs - 1;  // a tile past the end repeats the last one; its results are dropped
+        const uint4* a_src = p.basis16 + (size_t)kt_ld * NJ * 128 + lane;
+        // Everything step s needs, on its way into ring slot s % 3: both parts of basis tile kt0 + wave, and
+        // channels [16 s + 8 h, + 8) of this thread's pixel -- the operand entry of lane (pixel, h).  Steps past the
+        // end repeat the last one, so that every wavefront always has the same number of loads in flight.
+        auto issue = [&](int s) {
+            const int slot = s % 3;
+            s = s < NJ ? s : NJ - 1;
+            load_to_lds<16>(a_src + (size_t)s * 128, &stageA[slot][2 * wave][0]);
+            load_to_lds<16>(a_src + (size_t)s * 128 + 64, &stageA[slot][2 * wave + 1][0]);
+            int c0 = 16 * s + 8 * half;
+            c0 = c0 < C ? c0 : 0;  // C is a multiple of 16: all eight channels or none (then zeroed on conversion)
+            if constexpr (LAYOUT == FMTC_NHWC) {
+                const float* src = p.x + xbase + c0;
+                load_to_lds<16>(src, &stageX[slot][wave][0][0]);
+                load_to_lds<16>(src + 4, &stageX[slot][wave][1][0]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    load_to_lds<4>(p.x + xbase + (int64_t)(c0 + e) * xstride,
+                                   reinterpret_cast<uint32_t*>(&stageX[slot][wave][0][0]) + 64 * e);
+            }
+        };
+        float n2 = 0.f;
+        // this thread's eight channels of step s: mean removed, cut in two f16 parts, written as pixel operands
+        auto convert = [&](int s) {
+            const int c0 = 16 * s + 8 * half;
+            const bool ok = px_ok && c0 < C;
+            float v[8];
+            if constexpr (LAYOUT == FMTC_NHWC) {
+                const float4 a = *reinterpret_cast<const float4*>(&stageX[s % 3][wave][0][lane]);
+                const float4 b = *reinterpret_cast<const float4*>(&stageX[s % 3][wave][1][lane]);
+                v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+            } else {
+                const float* raw = reinterpret_cast<const float*>(&stageX[s % 3][wave][0][0]) + lane;
+#pragma unroll
+                for (int e = 0; e < 8; e++) v[e] = raw[64 * e];
+            }
+            const float4 m0 = *reinterpret_cast<const float4*>(&s_mu[c0]);
+            const float4 m1 = *reinterpret_cast<const float4*>(&s_mu[c0 + 4]);
+            const float m[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+            halfx8 vh, vl;
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                float d = ok ? v[e] - m[e] : 0.f;
+                n2 = __builtin_fmaf(d, d, n2);
+                d = __builtin_amdgcn_fmed3f(d, -60000.f, 60000.f);  // such a pixel is decided exactly (see n2)
+                const _Float16 h = (_Float16)d;
+                vh[e] = h;
+                vl[e] = (_Float16)((d - (float)h) * 2048.f);
+            }
+            stageB[s & 1][wave][0][lane] = __builtin_bit_cast(uint4, vh);
+            stageB[s & 1][wave][1][lane] = __builtin_bit_cast(uint4, vl);
+        };
+
+        issue(0);
+        issue(1);
+        wait_loads<LD>();  // step 0 has landed (this wavefront's part)
+        convert(0);
+        for (int s = 0; s < NJ; s++) {
+            // in flight: step s (unless s = 0) and step s + 1
+            wait_loads<LD>();  // step s has landed
+            __syncthreads();  // everybody's part of it, and everybody's pixel operands of step s; slot of step s - 1 is free
+            issue(s + 2);
+            const uint4(*sa)[64] = stageA[s % 3];
+            halfx8 th[2], tl[2], xh[2], xl[2];
+#pragma unroll
+            for (int a = 0; a < 2; a++) {
+                th[a] = __builtin_bit_cast(halfx8, sa[(2 * ktp + a) * 2][lane]);
+                tl[a] = __builtin_bit_cast(halfx8, sa[(2 * ktp + a) * 2 + 1][lane]);
+                xh[a] = __builtin_bit_cast(halfx8, stageB[s & 1][2 * ptp + a][0][lane]);
+                xl[a] = __builtin_bit_cast(halfx8, stageB[s & 1][2 * ptp + a][1][lane]);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; a++)
+#pragma unroll
+                for (int b = 0; b < 2; b++) {
+                    am[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(th[a], xh[b], am[a][b], 0, 0, 0);
+                    ac[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(th[a], xl[b], ac[a][b], 0, 0, 0);
+                }
+#pragma unroll
+            for (int a = 0; a < 2; a++)
+#pragma unroll
+                for (int b = 0; b < 2; b++)
+                    ac[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl[a], xh[b], ac[a][b], 0, 0, 0);
+            wait_loads<LD>();  // step s + 1 has landed
+            if (s + 1 < NJ) convert(s + 1);  // into the operand buffer step s - 1 read, free since the barrier above
+        }
+        wait_loads<0>();  // the repeated loads of the last steps too
+        n2 += __shfl_xor(n2, 32, 64);
+        if (half == 0) s_n2[wave][l32] = n2;
+        __syncthreads();  // all wavefronts are done with the stages: the next group's first loads may overwrite them
+
+        // ---- quantizer, histogram, stores: accumulator r of lane (pixel, h) is coefficient kt*32 + 16h + r ----
+#pragma unroll
+        for (int b = 0; b < 2; b++) {
+            const int64_t pt = pt0 + 2 * ptp + b;
+            if (pt >= p.n_pt) continue;  // wavefront-uniform
+            const int64_t px = pt * 32 + l32;
+            const bool out_ok = px < p.P;
+            const float pn2 = s_n2[2 * ptp + b][l32];
+            const bool force = !(pn2 < 1.0e9f);  // too large for f16, or not finite: every coefficient decided exactly
+            const float tau = fminf(fmaxf(p.kappa * __builtin_sqrtf(pn2), p.tau_min), 0.125f);
+            const float near_limit = force ? -1.f : 0.5f - tau;
+#pragma unroll
+            for (int a = 0; a < 2; a++) {
+                const int kt = kt0 + 2 * ktp + a;
+                if (kt >= p.ncs) continue;  // wavefront-uniform
+                const int k0 = kt * 32 + 16 * half;
+                const bool ok = out_ok && k0 < C;  // C is a multiple of 16: all sixteen coefficients or none
+                uint32_t word[4] = {0u, 0u, 0u, 0u};
+                uint32_t near_mask = 0;
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const float t = __builtin_fmaf(ac[a][b][r], inv_delta_lo, am[a][b][r] * inv_delta);
+                    const float q = __builtin_rintf(t);  // round half to even
+                    if (!(fabsf(t - q) <= near_limit)) near_mask |= 1u << r;
+                    const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
+                    word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
+                    if (ok) atomicAdd(&wh[(uint32_t)qc << HS], 1u);
+                }
+                if (ok)
+                    *reinterpret_cast<uint4*>(p.syms + px * C + k0) = make_uint4(word[0], word[1], word[2], word[3]);
+                if (!ok) near_mask = 0;
+                if (__builtin_expect(__any(near_mask != 0), 0)) {
+                    // note the flagged values; the list is resolved when it could overflow and at the end
+#pragma unroll 1
+                    for (int r = 0; r < 16; r++) {
+                        const bool f = (near_mask >> r) & 1u;
+                        const uint32_t incoming = (uint32_t)__popcll(__ballot(f));
+                        if (incoming == 0) continue;
+                        if (*fix_count + incoming > (uint32_t)kGemmFix) resolve_list();
+                        if (f) {
+                            const uint32_t slot = atomicAdd(fix_count, 1u);
+                            fix_a[slot] = (uint32_t)(k0 + r) | (((word[r >> 2] >> (8 * (r & 3))) & 255u) << 16);
+                            fix_px[slot] = (uint32_t)px;
+                        }
+                        wave_sync_lds();
+                    }
+                }
+            }
+        }
+        if (*fix_count) resolve_list();  // before the next group's loads: the waits there count loads in flight
+    }
+    __syncthreads();
+    // one row of partial counts per workgroup (see the narrow-tensor kernel); the operand buffers are free now
+    uint32_t* s_red = reinterpret_cast<uint32_t*>(&stageA[0][0][0]);
+    for (int row = tid; row < 4 * K; row += 256) {
+        uint32_t total = 0;
+        for (int q = 0; q < HC; q++) total += whist[((size_t)row << HS) + q];
+        s_red[row] = total;
+    }
+    __syncthreads();
+    if (tid < K)
+        p.hist_parts[(size_t)(blockIdx.y * gridDim.x + blockIdx.x) * K + tid] =
+            (s_red[tid] + s_red[K + tid]) + (s_red[2 * K + tid] + s_red[3 * K + tid]);
+}
+
+static hipError_t launch_gemm(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
+                              int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
+    const int ncs = b.Cpad / 32, NJ = b.Cpad / 16;
+    const int64_t n_pt = (P + 31) / 32;
+    GemmParams p;
+    p.x = d_x;
+    p.basis16 = reinterpret_cast<const uint4*>(b.fwd16);
+    p.mu = b.mu;
+    p.Trow = b.T;
+    p.P = P;
+    p.HW = HW;
+    p.C = b.C;
+    p.ncs = ncs;
+    p.NJ = NJ;
+    p.bits = bits;
+    p.n_pt = n_pt;
+    p.n_ptg = (n_pt + 3) / 4;
+    p.inv_delta = (float)(1.0 / (double)delta);
+    p.delta = delta;
+    p.kappa = 1.9073486e-6f /* 2^-19 */ * b.row_norm * p.inv_delta;  // see launch_rows
+    p.tau_min = 4.7683716e-7f /* 2^-21 */ * (float)(1 << (bits - 1));
+    // histogram copies per wavefront: as many as 8 KB of LDS hold, 16 at most, 2 at least
+    int copies = 512 >> bits;
+    copies = copies >= 16 ? 16 : (copies >= 8 ? 8 : (copies >= 4 ? 4 : 2));
+    p.hist_shift = copies == 16 ? 4 : (copies == 8 ? 3 : (copies == 4 ? 2 : 1));
+    p.syms = d_syms;
+    p.hist_parts = cs.hist_parts;
+    p.ctrl = cs.ctrl;
+    p.lookback = cs.lookback;
+    p.n_groups = cs.n_groups;
+    const int gy = (ncs + 3) / 4;
+    int64_t gx = p.n_ptg;
+    if (gx * gy > kMaxHistParts) gx = kMaxHistParts / gy;
+    *n_parts = (int)(gx * gy);
+    const size_t lds = sizeof(float) * b.Cpad + sizeof(uint32_t) * 4 * copies * ((size_t)1 << bits);
+    dim3 grid((unsigned)gx, (unsigned)gy);
+    return layout == FMTC_NHWC
+               ? launch(K_PROJECT, k_project_quantize_gemm<FMTC_NHWC>, grid, dim3(256), lds, s, p)
+               : launch(K_PROJECT, k_project_quantize_gemm<FMTC_NCHW>, grid, dim3(256), lds, s, p);
+}
+
 hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
                                    float delta, int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts,
                                    hipStream_t s) {
@@ -867,6 +1230,8 @@ hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64
     // loads take more registers than it has left)
     if (b.Cpad <= 128 || (b.Cpad == 160 && layout == FMTC_NHWC))
         return launch_rows(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
+    // wide: the tiled matrix product needs whole groups of 16 channels; other channel counts keep the pixel-tile kernel
+    if (b.C % 16 == 0) return launch_gemm(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
     return launch_wide(b, d_x, P, HW, layout, delta, bits, d_syms, cs, n_parts, s);
 }
 

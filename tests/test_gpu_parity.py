@@ -79,6 +79,9 @@ CASES = [
     (512, 7, 7, 2, 9, 128, "relu", 4),
     (144, 13, 11, 2, 3, 18, "relu6", 5),   # C not a multiple of 32, chunk of 28 pixels
     (960, 7, 7, 1, 2, 120, "relu6", 5),
+    (192, 5, 9, 1, 4, 24, "relu", 4),      # wide, 6 coefficient tiles: the second group of four is half empty
+    (208, 6, 7, 1, 3, 26, "relu", 5),      # wide, C % 32 == 16: the last 16-channel step is padding
+    (200, 6, 7, 1, 3, 25, "relu", 5),      # wide, C % 16 != 0
     (32, 9, 7, 0, 2, 8, "relu", 3),
     (50, 10, 10, 0, 2, 10, "relu", 5),     # C % 4 != 0: scalar paths
     (3, 17, 5, 0, 1, 2, "none", 2),
@@ -176,6 +179,31 @@ def test_encode_decode_end_to_end(fmtc, oracle, case, layout):
     assert int(err.item()) == 0
     ref_xhat = oracle.reconstruct(sym_gpu, xs.shape, T, mu, d, bits, layout)
     assert np.abs(xhat.cpu().numpy().astype(np.float64) - ref_xhat).max() <= RECON_TOL
+
+
+@pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("C", [64, 144, 200, 256])
+def test_outlier_pixels_are_decided_exactly(fmtc, oracle, C, layout):
+    """Values far beyond the range of the reduced-precision operands (and one beyond fp32's square range): the
+    pixels that hold them take the exact path, every other pixel is unaffected."""
+    xs, T, mu, A = make_case(oracle, C, 9, 7, 1, 3, max(4, C // 8), "relu", 900 + C, synth.NHWC)
+    xs = xs.copy()
+    flat = xs.reshape(-1, C)
+    flat[5, 3] = 3.0e5
+    flat[40, C - 1] = -7.0e6
+    flat[41, :] *= 1.0e4
+    flat[100, 0] = 1.0e25
+    xs = synth.to_layout(xs, layout)
+    bits = 5
+    d = oracle.delta(A, bits)
+    y = oracle.project(xs, T, mu, layout)
+    ref_sym, margin = oracle.quantize(y, d, bits, want_margin=True)
+    basis = fmtc.basis_import(T, mu, A)
+    sym, hist = fmtc.quantize(basis, dev(xs), bits, layout)
+    torch.cuda.synchronize()
+    sym, hist = sym.cpu().numpy(), hist.cpu().numpy()
+    check_symbols(sym, ref_sym, margin)
+    assert hist.tolist() == np.bincount(sym.reshape(-1), minlength=256).tolist()
 
 
 def test_long_codes_and_odd_geometry(fmtc, oracle):
