@@ -133,6 +133,42 @@ fmtc_status fmtc_encode(const fmtc_basis *basis, const float *d_x, int64_t N, in
 fmtc_status fmtc_decode(const fmtc_basis *basis, const void *d_stream_in, size_t bytes, float *d_xhat, int64_t N,
                         int C, int H, int W, fmtc_layout layout, int bits, uint32_t *d_err_flag, void *hip_stream);
 
+/* ---- encoder with a code table fixed at calibration time ----
+ * Section 3.1 ("Variable length coding") codes the quantizer output with a
+ * Huffman code and says nothing on when its table is made.  fmtc_encode makes
+ * it from the tensor being coded; a streaming datapath that codes values as
+ * they are produced has to know the table beforehand.  fmtc_fit_table makes it
+ * once from calibration data: the histogram of the calibration tensor's
+ * symbols (same basis, same bit depth) with one count added to every one of
+ * the 2^bits symbols, so that every symbol a later tensor can contain has a
+ * code; Huffman lengths of those counts, canonical codes as in fmtc_encode.
+ * The container written by fmtc_encode_static has the same format (it carries
+ * the table), so fmtc_decode reads it unchanged.  Where the tensor's shape
+ * allows (32, 64 or 128 channels, 4096-symbol chunks) projection, quantizer
+ * and bit packing run as ONE kernel and the symbols never reach memory.
+ *
+ * fmtc_fit_table synchronises the stream and allocates/frees device memory
+ * (calibration time, not the hot path).  fmtc_table_import takes the lengths
+ * of a complete prefix code over the 2^bits symbols (h_lengths: 2^bits bytes
+ * on the host, each 1..48, Kraft sum exactly 1; FMTC_EINVAL otherwise).
+ * fmtc_table_export writes 256 bytes (zero beyond 2^bits).
+ * fmtc_encode_static_bound: capacity that can not be exceeded whatever the
+ * tensor holds (longest code for every symbol).  A smaller capacity is
+ * accepted as long as it covers the side information; if the payload outgrows
+ * it nothing is written past the buffer and the header is left invalid
+ * (fmtc_decode then reports FMTC_ERR_HEADER). */
+typedef struct fmtc_table fmtc_table;
+fmtc_status fmtc_fit_table(const fmtc_basis *basis, const float *d_x, int64_t N, int C, int H, int W,
+                           fmtc_layout layout, int bits, void *hip_stream, fmtc_table **out);
+fmtc_status fmtc_table_import(const uint8_t *h_lengths, int bits, fmtc_table **out);
+fmtc_status fmtc_table_export(const fmtc_table *table, uint8_t *h_lengths, int *bits);
+void fmtc_table_destroy(fmtc_table *table);
+size_t fmtc_encode_static_bound(const fmtc_table *table, int64_t P, int C, int chunk_syms);
+/* Workspace: fmtc_workspace_size(P, C, bits of the table, chunk_syms). */
+fmtc_status fmtc_encode_static(const fmtc_basis *basis, const fmtc_table *table, const float *d_x, int64_t N, int C,
+                               int H, int W, fmtc_layout layout, int chunk_syms, void *d_stream_out, size_t cap,
+                               uint64_t *d_out_bytes, void *d_workspace, size_t ws_bytes, void *hip_stream);
+
 /* ---- staged entry points (the same kernels, cut at the symbol boundary) ---- */
 /* Transform + quantizer + histogram only (section 3: y = T(x-mu), Q_Delta).
  * d_syms: P*C bytes; d_hist: 256 u32 counts (may be NULL). */

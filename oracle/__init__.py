@@ -147,6 +147,14 @@ def huffman_lengths(hist):
     return length
 
 
+def static_lengths(calib_hist):
+    """Lengths of a code table fixed at calibration time, from the calibration symbols' counts [2^bits]."""
+    hist = np.ascontiguousarray(calib_hist, dtype=np.uint64)
+    length = np.empty(hist.size, np.uint8)
+    _chk(lib().fmtc_oracle_static_lengths(_p(hist), int(hist.size), _p(length)), "static_lengths")
+    return length
+
+
 def canonical_codes(length):
     length = np.ascontiguousarray(length, dtype=np.uint8)
     code = np.empty(length.size, np.uint64)
@@ -221,6 +229,16 @@ def encode(x, T, mu, dlt, bits, layout=NHWC, chunk_syms=4096, want_margin=False)
     if want_margin:
         res["margin"] = margin
     return res
+
+
+def encode_static(x, T, mu, dlt, bits, length, layout=NHWC, chunk_syms=4096):
+    """Encoder with a given code table (lengths of all 2^bits symbols).  -> dict(stream, sym [P,C])."""
+    y = project(x, T, mu, layout)
+    sym = quantize(y, dlt, bits)
+    length = np.ascontiguousarray(length, dtype=np.uint8)
+    cap = stream_bound(sym.shape[0], sym.shape[1], bits, chunk_syms) + sym.size * int(length.max()) // 8
+    return {"stream": pack(sym, sym.shape[1], bits, dlt, length, canonical_codes(length), chunk_syms, cap=cap),
+            "sym": sym}
 
 
 def decode(stream, shape, T, mu, bits, layout=NHWC):

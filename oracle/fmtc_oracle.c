@@ -318,6 +318,20 @@ int fmtc_oracle_huffman_lengths(const uint64_t *hist, int K, uint8_t *len)
     return ORC_OK;
 }
 
+/* Code lengths of a table made before the tensors it will code are known
+ * (section 3.1 names a Huffman code and leaves open when its table is made; a
+ * coder that emits bits as the values arrive cannot take it from the tensor
+ * itself).  Reading: the counts are those of a calibration tensor's symbols,
+ * and one is added to every symbol of the alphabet, so that any symbol a
+ * later tensor holds has a code.  Huffman lengths of those counts. */
+int fmtc_oracle_static_lengths(const uint64_t *calib_hist, int K, uint8_t *len)
+{
+    if (!calib_hist || !len || K < 2 || K > MAX_SYMS) return ORC_EINVAL;
+    uint64_t smoothed[MAX_SYMS];
+    for (int s = 0; s < K; s++) smoothed[s] = calib_hist[s] + 1;
+    return fmtc_oracle_huffman_lengths(smoothed, K, len);
+}
+
 /* Canonical code words for given lengths: used symbols ordered by (length,
  * symbol); the first gets code 0, each next one (previous + 1) shifted left by
  * the growth in length. */

@@ -19,6 +19,8 @@ EXPORTS = [
     "fmtc_fit_basis", "fmtc_basis_import", "fmtc_basis_export", "fmtc_basis_channels", "fmtc_basis_destroy",
     "fmtc_delta", "fmtc_encode_bound", "fmtc_workspace_size", "fmtc_encode", "fmtc_decode", "fmtc_quantize",
     "fmtc_code_symbols", "fmtc_decode_symbols", "fmtc_stream_info", "fmtc_last_error",
+    "fmtc_fit_table", "fmtc_table_import", "fmtc_table_export", "fmtc_table_destroy", "fmtc_encode_static_bound",
+    "fmtc_encode_static",
     "fmtc_profile_enable", "fmtc_profile_kernels", "fmtc_profile_name", "fmtc_profile_read", "fmtc_profile_copy",
 ]
 
@@ -56,6 +58,14 @@ def load_library():
     lib.fmtc_workspace_size.restype = sz
     lib.fmtc_encode.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp, sz, vp]
     lib.fmtc_decode.argtypes = [vp, vp, sz, vp, i64, i32, i32, i32, i32, i32, vp, vp]
+    lib.fmtc_fit_table.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, ctypes.POINTER(vp)]
+    lib.fmtc_table_import.argtypes = [vp, i32, ctypes.POINTER(vp)]
+    lib.fmtc_table_export.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    lib.fmtc_table_destroy.argtypes = [vp]
+    lib.fmtc_table_destroy.restype = None
+    lib.fmtc_encode_static_bound.argtypes = [vp, i64, i32, i32]
+    lib.fmtc_encode_static_bound.restype = sz
+    lib.fmtc_encode_static.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp, vp, sz, vp]
     lib.fmtc_quantize.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.fmtc_code_symbols.argtypes = [vp, i64, i32, i32, i32, f32, vp, sz, vp, vp, sz, vp]
     lib.fmtc_decode_symbols.argtypes = [vp, sz, i64, i32, i32, vp, vp, vp]
@@ -185,6 +195,82 @@ def encode(basis, x, bits, layout=NHWC, chunk_syms=4096, stream_out=None, out_by
                                       _dev(stream_out, torch.uint8), stream_out.numel(),
                                       _dev(out_bytes, torch.int64), _dev(workspace, torch.uint8),
                                       workspace.numel(), _stream()))
+    return stream_out, out_bytes
+
+
+class Table:
+    """Owns an fmtc_table handle (a code table fixed at calibration time)."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    def export(self):
+        """-> (code lengths uint8[2^bits] numpy, bits)."""
+        import numpy as np
+
+        ln = np.zeros(256, np.uint8)
+        bits = ctypes.c_int32(0)
+        _check(load_library().fmtc_table_export(self._h, ln.ctypes.data, ctypes.byref(bits)))
+        return ln[: 1 << bits.value].copy(), bits.value
+
+    @property
+    def bits(self):
+        return self.export()[1]
+
+    def close(self):
+        if self._h:
+            load_library().fmtc_table_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def fit_table(basis, x, bits, layout=NHWC):
+    import torch
+
+    n, c, h, w = _dims(x, layout)
+    out = ctypes.c_void_p()
+    _check(load_library().fmtc_fit_table(basis._h, _dev(x, torch.float32), n, c, h, w, layout, bits, _stream(),
+                                         ctypes.byref(out)))
+    return Table(out)
+
+
+def table_import(lengths, bits):
+    import numpy as np
+
+    ln = np.ascontiguousarray(lengths, dtype=np.uint8)
+    if ln.size != 1 << bits:
+        raise ValueError("one length per symbol of the alphabet")
+    out = ctypes.c_void_p()
+    _check(load_library().fmtc_table_import(ln.ctypes.data, bits, ctypes.byref(out)))
+    return Table(out)
+
+
+def encode_static_bound(table, P, C, chunk_syms=4096):
+    return load_library().fmtc_encode_static_bound(table._h, P, C, chunk_syms)
+
+
+def encode_static(basis, table, x, layout=NHWC, chunk_syms=4096, stream_out=None, out_bytes=None, workspace=None):
+    """Asynchronous.  -> (stream_out uint8 tensor, out_bytes int64[1] device tensor)."""
+    import torch
+
+    n, c, h, w = _dims(x, layout)
+    P = n * h * w
+    bits = table.bits
+    if stream_out is None:
+        stream_out = torch.empty(encode_static_bound(table, P, c, chunk_syms), dtype=torch.uint8, device=x.device)
+    if out_bytes is None:
+        out_bytes = torch.zeros(1, dtype=torch.int64, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(workspace_size(P, c, bits, chunk_syms), dtype=torch.uint8, device=x.device)
+    _check(load_library().fmtc_encode_static(basis._h, table._h, _dev(x, torch.float32), n, c, h, w, layout,
+                                             chunk_syms, _dev(stream_out, torch.uint8), stream_out.numel(),
+                                             _dev(out_bytes, torch.int64), _dev(workspace, torch.uint8),
+                                             workspace.numel(), _stream()))
     return stream_out, out_bytes
 
 

@@ -20,6 +20,14 @@ struct fmtc_basis {
     int device = 0;
 };
 
+struct fmtc_table {
+    int bits = 0;
+    uint32_t max_len = 0;
+    uint8_t lengths[256] = {0};
+    uint64_t* d_enc_table = nullptr;  // [256]: bit-reversed code | length << 56
+    int device = 0;
+};
+
 namespace {
 
 using namespace fmtc;
@@ -409,6 +417,148 @@ fmtc_status fmtc_encode(const fmtc_basis* basis, const float* d_x, int64_t N, in
     if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, syms, cs, &n_parts, s)) != hipSuccess)
         return hip_fail(e, "project/quantize kernel");
     return run_coder(syms, pl, cs, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), cap, d_out_bytes, s);
+}
+
+// ---- code table fixed at calibration time ----
+static bool lengths_complete(const uint8_t* len, int bits, uint32_t* max_len) {
+    // Kraft sum of a complete prefix code: sum 2^-len == 1, in units of 2^-48
+    unsigned long long sum = 0;
+    uint32_t mx = 0;
+    for (int s = 0; s < (1 << bits); s++) {
+        if (len[s] < 1 || len[s] > kMaxLen) return false;
+        sum += 1ull << (kMaxLen - len[s]);
+        if (len[s] > mx) mx = len[s];
+    }
+    *max_len = mx;
+    return sum == (1ull << kMaxLen);
+}
+
+void fmtc_table_destroy(fmtc_table* t) {
+    if (!t) return;
+    if (t->d_enc_table) (void)hipFree(t->d_enc_table);
+    delete t;
+}
+
+fmtc_status fmtc_table_import(const uint8_t* h_lengths, int bits, fmtc_table** out) {
+    if (!h_lengths || !out) return fail(FMTC_EINVAL, "NULL argument");
+    if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
+    uint32_t max_len = 0;
+    if (!lengths_complete(h_lengths, bits, &max_len))
+        return fail(FMTC_EINVAL, "lengths are not those of a complete prefix code over %d symbols", 1 << bits);
+    fmtc_table* t = new fmtc_table;
+    t->bits = bits;
+    t->max_len = max_len;
+    memcpy(t->lengths, h_lengths, (size_t)1 << bits);
+    hipError_t e;
+    uint8_t* d_len = nullptr;
+    if ((e = hipGetDevice(&t->device)) != hipSuccess || (e = hipMalloc((void**)&t->d_enc_table, 256 * sizeof(uint64_t))) != hipSuccess ||
+        (e = hipMalloc((void**)&d_len, 256)) != hipSuccess) {
+        fmtc_table_destroy(t);
+        return fail(FMTC_ENOMEM, "hipMalloc table: %s", hipGetErrorString(e));
+    }
+    if ((e = hipMemcpy(d_len, t->lengths, 256, hipMemcpyHostToDevice)) == hipSuccess &&
+        (e = launch_table_from_lengths(d_len, bits, t->d_enc_table, nullptr)) == hipSuccess)
+        e = hipStreamSynchronize(nullptr);
+    (void)hipFree(d_len);
+    if (e != hipSuccess) {
+        fmtc_table_destroy(t);
+        return hip_fail(e, "table upload");
+    }
+    *out = t;
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_table_export(const fmtc_table* t, uint8_t* h_lengths, int* bits) {
+    if (!t) return fail(FMTC_EINVAL, "NULL argument");
+    if (h_lengths) memcpy(h_lengths, t->lengths, 256);
+    if (bits) *bits = t->bits;
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_fit_table(const fmtc_basis* basis, const float* d_x, int64_t N, int C, int H, int W,
+                           fmtc_layout layout, int bits, void* hip_stream, fmtc_table** out) {
+    if (!basis || !d_x || !out) return fail(FMTC_EINVAL, "NULL argument");
+    if (!dims_ok(N, C, H, W) || basis->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", basis->C, C);
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
+    if (!aligned(d_x, 16)) return fail(FMTC_EINVAL, "misaligned pointer");
+    EncodePlan pl;
+    const int64_t HW = (int64_t)H * W;
+    fmtc_status st = plan_encode(N * HW, C, bits, 4096, &pl);
+    if (st != FMTC_OK) return st;
+    hipStream_t s = (hipStream_t)hip_stream;
+    fmtc_table* t = new fmtc_table;
+    t->bits = bits;
+    uint8_t *ws = nullptr, *d_len = nullptr;
+    hipError_t e;
+    if ((e = hipGetDevice(&t->device)) != hipSuccess || (e = hipMalloc((void**)&t->d_enc_table, 256 * sizeof(uint64_t))) != hipSuccess ||
+        (e = hipMalloc((void**)&ws, pl.ws.total)) != hipSuccess || (e = hipMalloc((void**)&d_len, 256)) != hipSuccess) {
+        if (ws) (void)hipFree(ws);
+        fmtc_table_destroy(t);
+        return fail(FMTC_ENOMEM, "hipMalloc table fit: %s", hipGetErrorString(e));
+    }
+    const CoderScratch cs = coder_scratch(ws, pl);
+    int n_parts = 0;
+    const float delta = fmtc_delta(basis->range_A, bits);
+    if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, ws + pl.ws.off_syms, cs, &n_parts, s)) == hipSuccess &&
+        (e = launch_table_from_hist(cs.hist_parts, n_parts, bits, 1u, t->d_enc_table, d_len, s)) == hipSuccess &&
+        (e = hipMemcpyAsync(t->lengths, d_len, 256, hipMemcpyDeviceToHost, s)) == hipSuccess)
+        e = hipStreamSynchronize(s);
+    (void)hipFree(ws);
+    (void)hipFree(d_len);
+    if (e != hipSuccess) {
+        fmtc_table_destroy(t);
+        return hip_fail(e, "table fit");
+    }
+    if (!lengths_complete(t->lengths, bits, &t->max_len)) {
+        fmtc_table_destroy(t);
+        return fail(FMTC_EHIP, "table fit produced an incomplete code");
+    }
+    *out = t;
+    return FMTC_OK;
+}
+
+static size_t static_bound_from(const EncodePlan& pl, uint32_t max_len) {
+    // every chunk: its symbols at the longest code, rounded up to whole words
+    const uint64_t full = (uint64_t)pl.g.chunk_syms * max_len;
+    return pl.g.off_payload + 4 * (size_t)(((full + 31) / 32) * pl.g.n_chunks);
+}
+
+size_t fmtc_encode_static_bound(const fmtc_table* t, int64_t P, int C, int chunk_syms) {
+    EncodePlan pl;
+    if (!t || plan_encode(P, C, t->bits, chunk_syms, &pl) != FMTC_OK) return 0;
+    return static_bound_from(pl, t->max_len);
+}
+
+fmtc_status fmtc_encode_static(const fmtc_basis* basis, const fmtc_table* t, const float* d_x, int64_t N, int C, int H,
+                               int W, fmtc_layout layout, int chunk_syms, void* d_stream_out, size_t cap,
+                               uint64_t* d_out_bytes, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!basis || !t || !d_x || !d_stream_out || !d_workspace) return fail(FMTC_EINVAL, "NULL argument");
+    if (!dims_ok(N, C, H, W) || basis->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", basis->C, C);
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    if (!aligned(d_x, 16) || !aligned(d_stream_out, 16) || !aligned(d_workspace, 256) || !aligned(d_out_bytes, 8))
+        return fail(FMTC_EINVAL, "misaligned pointer");
+    const int bits = t->bits;
+    EncodePlan pl;
+    const int64_t HW = (int64_t)H * W;
+    fmtc_status st = plan_encode(N * HW, C, bits, chunk_syms, &pl);
+    if (st != FMTC_OK) return st;
+    if (ws_bytes < pl.ws.total) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, pl.ws.total);
+    if (cap < pl.g.off_payload) return fail(FMTC_EBUFSIZE, "stream capacity too small: %zu < %zu", cap, (size_t)pl.g.off_payload);
+    hipStream_t s = (hipStream_t)hip_stream;
+    uint8_t* w = static_cast<uint8_t*>(d_workspace);
+    const CoderScratch cs = coder_scratch(w, pl);
+    uint8_t* syms = w + pl.ws.off_syms;
+    const float delta = fmtc_delta(basis->range_A, bits);
+    const uint64_t cap_words = (cap - pl.g.off_payload) / 4;
+    hipError_t e;
+    int n_parts = 0;
+    if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, syms, cs, &n_parts, s)) != hipSuccess)
+        return hip_fail(e, "project/quantize kernel");
+    if ((e = launch_coder_static(syms, pl.g, bits, delta, cs, t->d_enc_table, t->max_len, static_cast<uint8_t*>(d_stream_out),
+                                 cap_words, d_out_bytes, s)) != hipSuccess)
+        return hip_fail(e, "coder kernel");
+    return FMTC_OK;
 }
 
 fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits, int chunk_syms, float delta,

@@ -233,6 +233,48 @@ struct TableOut {
     unsigned long long payload_bits;
 };
 
+// Canonical codes from code lengths (len[j] of symbol 64 j + lane, 0 = unused; max_len the longest, the same in
+// every lane): codes of one length are numbered in symbol order, shorter codes first.  One wavefront; entry[] (256
+// words, LDS or global) is written whole.
+template <int NVS>
+__device__ __forceinline__ void canonical_entries(const uint32_t (&len)[NVS], int lane, uint32_t max_len,
+                                                  unsigned long long* entry_out) {
+    uint32_t before[NVS];
+#pragma unroll
+    for (int j = 0; j < NVS; j++) before[j] = 0;
+    // lane q ends up with the number of codes of length q
+    uint32_t my_count = 0;
+    for (uint32_t q = 1; q <= max_len; q++) {
+        uint32_t total = 0;
+#pragma unroll
+        for (int j = 0; j < NVS; j++) {
+            const unsigned long long m = __ballot(len[j] == q);
+            if (len[j] == q) before[j] = total + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+            total += (uint32_t)__popcll(m);
+        }
+        if ((uint32_t)lane == q) my_count = total;
+    }
+    // first canonical code of every length: code(l) = sum_{j<l} count(j) << (l-j), i.e. the running sum of
+    // count(j) * 2^(48-j) shifted down to l bits
+    const bool in = lane >= 1 && lane <= kMaxLen;
+    const unsigned long long w = (unsigned long long)my_count << (in ? kMaxLen - lane : 0);
+    const unsigned long long incl = wave_inclusive_scan64(w, lane);
+    const unsigned long long first_code = in ? ((incl - w) >> (kMaxLen - lane)) : 0ull;
+#pragma unroll
+    for (int j = 0; j < NVS; j++) {
+        const unsigned long long fc = __shfl(first_code, (int)len[j], 64);
+        unsigned long long entry = 0;
+        if (len[j]) {
+            const unsigned long long code = fc + (unsigned long long)before[j];
+            const unsigned long long rev = __brevll(code) >> (64 - len[j]);  // stream order: least significant bit first
+            entry = rev | ((unsigned long long)len[j] << 56);
+        }
+        entry_out[64 * j + lane] = entry;
+    }
+    if (NVS < 4)
+        for (int s = 64 * NVS + lane; s < 256; s += 64) entry_out[s] = 0ull;
+}
+
 // Code table from the histogram L.h.  Runs in ONE wavefront (64 lanes, `lane`), no workgroup barrier inside;
 // lane l owns symbols l, l + 64, ... (NVS = alphabet size / 64, at least 1).  Every lane returns the same
 // max_len and payload_bits; entry[] is complete when the function returns (for this wavefront).
@@ -300,13 +342,12 @@ __device__ __forceinline__ void table_from_hist(TableLds& L, int lane, int K, Ta
         L.len_sorted[0] = 1;  // a single used symbol gets the one-bit code 0
     }
     wave_sync();
-    uint32_t len[NVS], before[NVS];
+    uint32_t len[NVS];
     uint32_t max_len = 0;
     unsigned long long pbits = 0;
 #pragma unroll
     for (int j = 0; j < NVS; j++) {
         len[j] = cnt[j] ? (uint32_t)L.len_sorted[rank[j]] : 0u;
-        before[j] = 0;
         max_len = len[j] > max_len ? len[j] : max_len;
         pbits += (unsigned long long)cnt[j] * len[j];
     }
@@ -317,37 +358,7 @@ __device__ __forceinline__ void table_from_hist(TableLds& L, int lane, int K, Ta
         pbits += __shfl_xor(pbits, o, 64);
     }
     max_len = (uint32_t)__builtin_amdgcn_readfirstlane((int)max_len);
-    // codes of one length are numbered in symbol order; lane q ends up with the number of codes of length q
-    uint32_t my_count = 0;
-    for (uint32_t q = 1; q <= max_len; q++) {
-        uint32_t total = 0;
-#pragma unroll
-        for (int j = 0; j < NVS; j++) {
-            const unsigned long long m = __ballot(len[j] == q);
-            if (len[j] == q) before[j] = total + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-            total += (uint32_t)__popcll(m);
-        }
-        if ((uint32_t)lane == q) my_count = total;
-    }
-    // first canonical code of every length: code(l) = sum_{j<l} count(j) << (l-j), i.e. the running sum of
-    // count(j) * 2^(48-j) shifted down to l bits
-    const bool in = lane >= 1 && lane <= kMaxLen;
-    const unsigned long long w = (unsigned long long)my_count << (in ? kMaxLen - lane : 0);
-    const unsigned long long incl = wave_inclusive_scan64(w, lane);
-    const unsigned long long first_code = in ? ((incl - w) >> (kMaxLen - lane)) : 0ull;
-#pragma unroll
-    for (int j = 0; j < NVS; j++) {
-        const unsigned long long fc = __shfl(first_code, (int)len[j], 64);
-        unsigned long long entry = 0;
-        if (len[j]) {
-            const unsigned long long code = fc + (unsigned long long)before[j];
-            const unsigned long long rev = __brevll(code) >> (64 - len[j]);  // stream order: least significant bit first
-            entry = rev | ((unsigned long long)len[j] << 56);
-        }
-        out.entry[64 * j + lane] = entry;
-    }
-    if (NVS < 4)
-        for (int s = 64 * NVS + lane; s < 256; s += 64) out.entry[s] = 0ull;
+    canonical_entries<NVS>(len, lane, max_len, out.entry);
     out.max_len = max_len;
     out.payload_bits = pbits;
     wave_sync();
@@ -363,10 +374,14 @@ __global__ __launch_bounds__(1024) void k_huffman_table(const uint32_t* __restri
                                                         int bits, uint32_t* __restrict__ hist_out,
                                                         uint64_t* __restrict__ enc_table,
                                                         uint8_t* __restrict__ len_table,
-                                                        CoderCtrl* __restrict__ ctrl) {
+                                                        CoderCtrl* __restrict__ ctrl, uint32_t add_each) {
     __shared__ TableLds L;
     __shared__ unsigned long long entry[256];
     sum_partials<1024>(L, hist_parts, n_parts, bits);
+    if (add_each) {  // a table for tensors to come: every symbol of the alphabet gets a code
+        if ((int)threadIdx.x < (1 << bits)) L.h[threadIdx.x] += add_each;
+        __syncthreads();
+    }
     rank_symbols<1024>(L, bits);
     const int tid = threadIdx.x;
     if (tid < 64) {
@@ -384,6 +399,36 @@ __global__ __launch_bounds__(1024) void k_huffman_table(const uint32_t* __restri
         if (enc_table) enc_table[tid] = entry[tid];
         if (len_table) len_table[tid] = (uint8_t)(entry[tid] >> 56);
     }
+}
+
+// Code table of given lengths (a complete prefix code over the 2^bits symbols; the host has checked that).
+__global__ __launch_bounds__(64) void k_table_from_lengths(const uint8_t* __restrict__ len_table, int bits,
+                                                           uint64_t* __restrict__ enc_table) {
+    const int lane = threadIdx.x, K = 1 << bits;
+    uint32_t len[4], max_len = 0;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        len[j] = (64 * j + lane < K) ? (uint32_t)len_table[64 * j + lane] : 0u;
+        max_len = len[j] > max_len ? len[j] : max_len;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t t = __shfl_xor(max_len, o, 64);
+        max_len = t > max_len ? t : max_len;
+    }
+    max_len = (uint32_t)__builtin_amdgcn_readfirstlane((int)max_len);
+    canonical_entries<4>(len, lane, max_len, reinterpret_cast<unsigned long long*>(enc_table));
+}
+
+hipError_t launch_table_from_lengths(const uint8_t* d_len_table, int bits, uint64_t* d_enc_table, hipStream_t s) {
+    return launch(K_TABLE, k_table_from_lengths, dim3(1), dim3(64), 0, s, d_len_table, bits, d_enc_table);
+}
+
+// Table of the summed partial histograms with `add_each` added to every symbol's count.
+hipError_t launch_table_from_hist(const uint32_t* d_hist_parts, int n_parts, int bits, uint32_t add_each,
+                                  uint64_t* d_enc_table, uint8_t* d_len_table, hipStream_t s) {
+    return launch(K_TABLE, k_huffman_table, dim3(1), dim3(1024), 0, s, d_hist_parts, n_parts, bits,
+                  (uint32_t*)nullptr, d_enc_table, d_len_table, (CoderCtrl*)nullptr, add_each);
 }
 
 // Sum of the partial histograms only.
@@ -420,7 +465,12 @@ hipError_t launch_histogram_sum(const uint32_t* d_hist_parts, int n_parts, int b
 // several windows.
 // ---------------------------------------------------------------------------
 constexpr int kStageWords = 2048;  // per wavefront: 64 Kbit, i.e. 16 bits/symbol over a 4096-symbol chunk
-constexpr unsigned long long kFlagAggregate = 1ull << 32, kFlagInclusive = 2ull << 32;
+// A look-back entry: payload words in bits 0..31, bits left unused in the last words of the chunks ("slack",
+// below 32 per chunk) in bits 32..61, and in bits 62..63 whether it covers one group or everything up to it.
+constexpr unsigned long long kFlagAggregate = 1ull << 62, kFlagInclusive = 2ull << 62;
+constexpr uint32_t kSlackMask = 0x3fffffffu;
+enum PackMode { kPackBuild = 0, kPackTable = 1, kPackStatic = 2 };  // who made the table: this kernel from the
+                                                                     // histogram, k_huffman_table, or the caller
 constexpr int kLook = 4;  // look-back entries a lane reads per poll (each is an uncached device-scope load: wider windows cost more than the extra round trips they save)
 constexpr uint32_t kSpinLimit = 1u << 22;  // polls before a wait gives up (seconds; never reached unless the
                                            // workspace is overwritten while the kernel runs)
@@ -430,9 +480,10 @@ struct PackParams {
     uint64_t V;
     uint32_t n_chunks, chunk_syms, subs_per_chunk, n_groups;
     int bits;
-    const uint32_t* hist_parts;  // BUILD: partial histograms to build the table from
+    const uint32_t* hist_parts;  // kPackBuild: partial histograms to build the table from
     int n_parts;
-    const uint64_t* enc_table;   // !BUILD: table made by k_huffman_table
+    const uint64_t* enc_table;   // otherwise: the table (k_huffman_table's, or a static one)
+    uint32_t static_max_len;     // kPackStatic: longest code of the table
     CoderCtrl* ctrl;
     unsigned long long* lookback;
     Header hdr;
@@ -568,13 +619,13 @@ __device__ __forceinline__ uint32_t pack_chunk(const uint32_t (&w)[16], uint32_t
 }
 
 // kPackWaves chunks per group: one wavefront per chunk.
-template <bool BUILD>
+template <int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_pack(PackParams p) {
     static_assert(kPackWaves == 4, "one chunk per wavefront of the 256-thread workgroup");
     __shared__ unsigned long long tab[256];
     __shared__ __align__(16) uint32_t stage[kPackWaves][kStageWords + 4];  // image + the spare word
-    __shared__ uint32_t wave_words[kPackWaves];
-    __shared__ uint32_t s_excl, s_max_len;
+    __shared__ uint32_t wave_words[kPackWaves], wave_slack[kPackWaves];
+    __shared__ uint32_t s_excl, s_excl_slack, s_max_len;
     __shared__ unsigned long long s_payload_bits;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -623,7 +674,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 
     TableLds& L = *reinterpret_cast<TableLds*>(&stage[0][0]);  // shares LDS with the chunk images, not in use yet
     static_assert(sizeof(TableLds) <= sizeof(stage), "table scratch must fit the chunk images");
-    if constexpr (BUILD) {
+    if constexpr (MODE == kPackBuild) {
         sum_partials<256>(L, p.hist_parts, p.n_parts, p.bits);
         rank_symbols<256>(L, p.bits);
         if (wave == 0) {
@@ -640,10 +691,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     } else {
         tab[tid] = p.enc_table[tid];
         if (tid == 0) {
-            s_max_len = p.ctrl->max_len;
-            s_payload_bits = p.ctrl->payload_bits;
+            // a static table does not know this tensor's bit count: it comes out of the look-back (see below)
+            s_max_len = MODE == kPackStatic ? p.static_max_len : p.ctrl->max_len;
+            s_payload_bits = MODE == kPackStatic ? 0ull : p.ctrl->payload_bits;
         }
         __syncthreads();
+        if (MODE == kPackStatic && blockIdx.x == 0) p.stream[kHeaderBytes + tid] = (uint8_t)(tab[tid] >> 56);
     }
     const uint32_t max_len = s_max_len;
     uint32_t* img = stage[wave];
@@ -673,17 +726,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             wave_sync();  // the ORs of all lanes precede the reads that follow
             return total;
         };
-        uint32_t n_words = 0;
+        uint32_t n_words = 0, slack = 0;
         if (have) {
             const uint32_t total_bits = build_window(0, kStageWords, sub_bits + (size_t)ch * p.subs_per_chunk);
             n_words = (total_bits + 31) >> 5;
+            slack = 32u * n_words - total_bits;
         }
-        if (lane == 0) wave_words[wave] = n_words;
+        if (lane == 0) {
+            wave_words[wave] = n_words;
+            wave_slack[wave] = slack;
+        }
         __syncthreads();
-        uint32_t agg = 0;
+        uint32_t agg = 0, agg_slack = 0;
 #pragma unroll
-        for (int q = 0; q < kPackWaves; q++) agg += wave_words[q];
-        if (tid == 0) publish64(&p.lookback[group], (group == 0 ? kFlagInclusive : kFlagAggregate) | agg);
+        for (int q = 0; q < kPackWaves; q++) {
+            agg += wave_words[q];
+            agg_slack += wave_slack[q];
+        }
+        if (tid == 0)
+            publish64(&p.lookback[group], (group == 0 ? kFlagInclusive : kFlagAggregate) |
+                                              ((unsigned long long)agg_slack << 32) | agg);
 
         // the next group's symbols are on their way during the wait for the position and the stores
         uint32_t wn[16];
@@ -694,11 +756,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         if (wave == 0 && group != 0) {
             // windows of 64 * kLook predecessors, nearest first; lane l reads kLook of them, all loads in flight
             // together
-            uint32_t excl = 0;
+            uint32_t excl = 0, excl_slack = 0;
             uint32_t top = group;  // predecessors [0, top) are still to be accounted for
             bool failed = false;
             while (top > 0) {
-                uint32_t sum = 0;
+                uint32_t sum = 0, ssum = 0;
                 bool found = false;  // met a running total: everything before it is included
                 bool ready = false;
                 for (uint32_t tries = 0; tries < kSpinLimit; tries++) {
@@ -709,6 +771,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                         e[j] = (back <= top) ? peek64(&p.lookback[top - back]) : kFlagAggregate;
                     }
                     sum = 0;
+                    ssum = 0;
                     found = false;
                     bool ok = true;
 #pragma unroll
@@ -716,6 +779,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                         if (!found) {
                             if (e[j] == 0) ok = false;
                             sum += (uint32_t)e[j];
+                            ssum += (uint32_t)(e[j] >> 32) & kSlackMask;
                             found = (e[j] & kFlagInclusive) != 0;
                         }
                     }
@@ -734,21 +798,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 }
                 const unsigned long long fmask = __ballot(found);
                 const int first = fmask ? (__ffsll((long long)fmask) - 1) : 64;  // lanes beyond it are not needed
-                const uint32_t part = (lane <= first) ? sum : 0u;
-                excl += wave_sum(part);
+                excl += wave_sum((lane <= first) ? sum : 0u);
+                excl_slack += wave_sum((lane <= first) ? ssum : 0u);
                 if (fmask) break;
                 top = (top > 64u * kLook) ? top - 64u * kLook : 0u;
             }
             if (failed) {
                 if (lane == 0) p.ctrl->error = 1u;
                 excl = 0;
+                excl_slack = 0;
             }
             if (lane == 0) {
-                publish64(&p.lookback[group], kFlagInclusive | (unsigned long long)(excl + agg));
+                publish64(&p.lookback[group], kFlagInclusive | ((unsigned long long)(excl_slack + agg_slack) << 32) |
+                                                  (unsigned long long)(excl + agg));
                 s_excl = excl;
+                s_excl_slack = excl_slack;
             }
         } else if (tid == 0) {
             s_excl = 0;
+            s_excl_slack = 0;
         }
         __syncthreads();
         if (have) {
@@ -762,6 +830,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                     Header hdr = p.hdr;
                     hdr.payload_words = total_words;
                     hdr.payload_bits = s_payload_bits;
+                    if constexpr (MODE == kPackStatic) {
+                        // every code bit of the tensor: the words of all chunks less what their last words leave unused
+                        uint32_t total_slack = s_excl_slack + slack;
+                        for (int q = 0; q < wave; q++) total_slack += wave_slack[q];
+                        hdr.payload_bits = 32ull * total_words - total_slack;
+                    }
                     // a wait gave up, or the payload outgrew the buffer (then some chunk was not written): not valid
                     if (p.ctrl->error || total_words > p.cap_words) hdr.magic = 0u;
                     *reinterpret_cast<Header*>(p.stream) = hdr;
@@ -790,21 +864,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 wave_sync();  // the image is read and clear before the next window or chunk writes it
             }
         }
-        __syncthreads();  // wave_words and s_excl are rewritten by the next group
+        __syncthreads();  // wave_words, wave_slack and s_excl* are rewritten by the next group
 #pragma unroll
         for (int q = 0; q < 16; q++) w[q] = wn[q];
     }
 }
 
 // Number of workgroups of the pack kernel the device holds at once (queried once per kernel variant).
-template <bool BUILD>
+template <int MODE>
 static int pack_resident_groups() {
     static int cached = 0;
     if (cached) return cached;
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_pack<BUILD>, 256, 0) != hipSuccess || cus < 1 ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_pack<MODE>, 256, 0) != hipSuccess || cus < 1 ||
         per_cu < 1)
         return 64;  // conservative: any device this library runs on holds 64 workgroups
     if (per_cu > 4) per_cu = 4;
@@ -814,9 +888,9 @@ static int pack_resident_groups() {
 
 // Table (a kernel of its own only where every pack workgroup building it would cost more than the launch)
 // and packing.
-hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
-                        int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
-                        uint64_t* d_out_bytes, hipStream_t s) {
+static PackParams pack_params(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
+                              int n_parts, const uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
+                              uint64_t* d_out_bytes) {
     PackParams p;
     p.cap_words = cap_words;
     p.syms = d_syms;
@@ -846,18 +920,37 @@ hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, floa
     p.off_payload = g.off_payload;
     p.stream = d_stream;
     p.out_bytes = d_out_bytes;
+    p.static_max_len = 0;
+    return p;
+}
+
+hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
+                        int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
+                        uint64_t* d_out_bytes, hipStream_t s) {
+    PackParams p = pack_params(d_syms, g, bits, delta, cs, n_parts, d_enc_table, d_stream, cap_words, d_out_bytes);
     static const char* knob = getenv("FMTC_TABLE_IN_PACK");
     // every pack workgroup sums the partial histograms itself while that is at most 64 KB to read
     const bool build_in_pack = knob ? (knob[0] == '1') : ((size_t)n_parts << bits) * 4 <= 64 * 1024;
     if (!build_in_pack) {
         hipError_t e = launch(K_TABLE, k_huffman_table, dim3(1), dim3(1024), 0, s, (const uint32_t*)cs.hist_parts,
-                              n_parts, bits, (uint32_t*)nullptr, d_enc_table, d_stream + kHeaderBytes, cs.ctrl);
+                              n_parts, bits, (uint32_t*)nullptr, d_enc_table, d_stream + kHeaderBytes, cs.ctrl, 0u);
         if (e != hipSuccess) return e;
-        const uint32_t cap = (uint32_t)pack_resident_groups<false>();
-        return launch(K_PACK, k_pack<false>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
+        const uint32_t cap = (uint32_t)pack_resident_groups<kPackTable>();
+        return launch(K_PACK, k_pack<kPackTable>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
     }
-    const uint32_t cap = (uint32_t)pack_resident_groups<true>();
-    return launch(K_PACK, k_pack<true>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
+    const uint32_t cap = (uint32_t)pack_resident_groups<kPackBuild>();
+    return launch(K_PACK, k_pack<kPackBuild>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
+}
+
+// Packing with a table fixed beforehand (one code for every symbol of the alphabet): no histogram, no table build.
+// The coder's counters must be clear (the kernel that made the symbols clears them).
+hipError_t launch_coder_static(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
+                               const uint64_t* d_enc_table, uint32_t max_len, uint8_t* d_stream, uint64_t cap_words,
+                               uint64_t* d_out_bytes, hipStream_t s) {
+    PackParams p = pack_params(d_syms, g, bits, delta, cs, 0, d_enc_table, d_stream, cap_words, d_out_bytes);
+    p.static_max_len = max_len;
+    const uint32_t cap = (uint32_t)pack_resident_groups<kPackStatic>();
+    return launch(K_PACK, k_pack<kPackStatic>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
 }
 
 }  // namespace fmtc

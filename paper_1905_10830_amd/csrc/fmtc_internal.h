@@ -163,6 +163,14 @@ hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, floa
                         int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
                         uint64_t* d_out_bytes, hipStream_t s);
 
+// Packing with a table fixed beforehand (every symbol of the alphabet has a code).
+hipError_t launch_coder_static(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
+                               const uint64_t* d_enc_table, uint32_t max_len, uint8_t* d_stream, uint64_t cap_words,
+                               uint64_t* d_out_bytes, hipStream_t s);
+hipError_t launch_table_from_lengths(const uint8_t* d_len_table, int bits, uint64_t* d_enc_table, hipStream_t s);
+hipError_t launch_table_from_hist(const uint32_t* d_hist_parts, int n_parts, int bits, uint32_t add_each,
+                                  uint64_t* d_enc_table, uint8_t* d_len_table, hipStream_t s);
+
 hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
                          int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, hipStream_t s);
 

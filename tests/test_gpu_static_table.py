@@ -1,0 +1,165 @@
+"""GPU parity of the encoder with a code table fixed at calibration time: the table the library fits against the
+oracle's (same counts), the stream against the oracle's packing of the same symbols with the same table, bit for
+bit, and the unchanged decoder on those streams."""
+import numpy as np
+import pytest
+
+from paper_1905_10830_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from test_gpu_parity import RECON_TOL, check_symbols, dev, make_case  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def fmtc():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1905_10830_amd import binding
+
+    binding.load_library()
+    return binding
+
+
+# (C, H, W, calib images, data images, rank, act, bits, chunk_syms)
+CASES = [
+    (128, 28, 28, 2, 3, 32, "relu", 6, 4096),   # stage-2 shape: one chunk per 32-pixel tile
+    (128, 28, 28, 2, 2, 32, "relu", 4, 4096),
+    (64, 56, 56, 1, 1, 16, "relu", 8, 4096),    # two tiles per chunk
+    (32, 9, 7, 1, 5, 8, "relu", 3, 4096),       # four tiles per chunk, ragged end
+    (128, 5, 5, 1, 3, 32, "relu", 5, 4096),     # 75 pixels: last chunk and last tile partial
+    (64, 28, 28, 1, 2, 16, "relu", 6, 1000),    # chunk size that is no multiple of a pixel
+    (144, 13, 11, 2, 3, 18, "relu6", 5, 4096),
+    (256, 14, 14, 2, 3, 64, "relu", 4, 4096),   # wide
+    (50, 10, 10, 1, 2, 10, "relu", 5, 4096),
+    (3, 17, 5, 1, 1, 2, "none", 2, 64),
+]
+IDS = [f"C{c[0]}_{c[1]}x{c[2]}_n{c[4]}_b{c[7]}_cs{c[8]}" for c in CASES]
+
+
+def split_case(oracle, case, seed, layout):
+    """Calibration tensor and a different data tensor of the same stream, basis fitted on the calibration part."""
+    C, H, W, ncal, ndat, rank, act, bits, cs = case
+    s = synth.FeatureMapStream(C, H, W, rank, act, seed)
+    cal = synth.to_layout(s.images(ncal), layout)
+    dat = synth.to_layout(s.images(ndat), layout)
+    if C <= 160:
+        T, mu, eig, A = oracle.fit(cal, layout)
+    else:
+        mean, cov = oracle.covariance(cal, layout)
+        w, v = np.linalg.eigh(cov)
+        T = np.ascontiguousarray(v[:, ::-1].T).astype(np.float32)
+        mu = mean.astype(np.float32)
+        A = np.float32(np.abs(oracle.project(cal, T, mu, layout)[:, 0]).max())
+    return cal, dat, T, mu, A
+
+
+@pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+def test_static_table_encode_matches_oracle(fmtc, oracle, case, layout):
+    C, H, W, ncal, ndat, rank, act, bits, cs = case
+    cal, dat, T, mu, A = split_case(oracle, case, 700 + C, layout)
+    d = oracle.delta(A, bits)
+    K = 1 << bits
+    basis = fmtc.basis_import(T, mu, A)
+
+    # ---- the table: Huffman lengths of the calibration symbols' counts plus one ----
+    table = fmtc.fit_table(basis, dev(cal), bits, layout)
+    ln, tb = table.export()
+    assert tb == bits and ln.size == K
+    cal_sym, cal_hist = fmtc.quantize(basis, dev(cal), bits, layout)  # the symbols the fit counted
+    torch.cuda.synchronize()
+    cal_hist = cal_hist.cpu().numpy()[:K].astype(np.uint64)
+    ref_sym, margin = oracle.quantize(oracle.project(cal, T, mu, layout), d, bits, want_margin=True)
+    check_symbols(cal_sym.cpu().numpy(), ref_sym, margin)
+    assert ln.tolist() == oracle.static_lengths(cal_hist).tolist()
+
+    # ---- the stream of a tensor the table has not seen ----
+    P = dat.size // C
+    stream, nbytes = fmtc.encode_static(basis, table, dev(dat), layout, chunk_syms=cs)
+    torch.cuda.synchronize()
+    n = int(nbytes.item())
+    got = stream[:n].cpu().numpy()
+    sym_gpu, d2, pbits = oracle.unpack(got, P, C, bits)
+    assert d2 == d
+    ref = oracle.encode_static(dat, T, mu, d, bits, ln, layout, chunk_syms=cs)
+    ref_margin = oracle.quantize(oracle.project(dat, T, mu, layout), d, bits, want_margin=True)[1]
+    n_bad = check_symbols(sym_gpu, ref["sym"], ref_margin)
+    again = ref["stream"] if n_bad == 0 else oracle.pack(sym_gpu, C, bits, d, ln, oracle.canonical_codes(ln),
+                                                         chunk_syms=cs, cap=n + 4096)
+    assert len(again) == n and (got == again).all(), "stream differs from the oracle's packing of the same symbols"
+    assert got[64:64 + K].tolist() == ln.tolist() and not got[64 + K:320].any()
+    assert pbits == int(ln[sym_gpu].astype(np.uint64).sum())
+    info = fmtc.stream_info(got[:64])
+    assert info["payload_bits"] == pbits and info["stream_bytes"] == n
+
+    # ---- the decoder needs no change: the container carries the table ----
+    xhat, err = fmtc.decode(basis, stream, dat.shape, bits, layout)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    ref_xhat = oracle.reconstruct(sym_gpu, dat.shape, T, mu, d, bits, layout)
+    assert np.abs(xhat.cpu().numpy().astype(np.float64) - ref_xhat).max() <= RECON_TOL
+    # deterministic
+    stream2, nbytes2 = fmtc.encode_static(basis, table, dev(dat), layout, chunk_syms=cs)
+    torch.cuda.synchronize()
+    assert int(nbytes2.item()) == n and (stream2[:n].cpu().numpy() == got).all()
+
+
+def test_table_import_export_and_bad_tables(fmtc, oracle):
+    case = CASES[1]
+    C, H, W, ncal, ndat, rank, act, bits, cs = case
+    cal, dat, T, mu, A = split_case(oracle, case, 811, synth.NHWC)
+    basis = fmtc.basis_import(T, mu, A)
+    fitted = fmtc.fit_table(basis, dev(cal), bits)
+    ln, _ = fitted.export()
+    imported = fmtc.table_import(ln, bits)
+    assert imported.export()[0].tolist() == ln.tolist()
+    a, na = fmtc.encode_static(basis, fitted, dev(dat))
+    b, nb = fmtc.encode_static(basis, imported, dev(dat))
+    torch.cuda.synchronize()
+    n = int(na.item())
+    assert int(nb.item()) == n and (a[:n] == b[:n]).all()
+    # a long-code table (lengths 1, 2, ..., 15, 15) through the same path
+    skew = np.array(list(range(1, 16)) + [15], np.uint8)
+    long_table = fmtc.table_import(skew, 4)
+    stream, nbytes = fmtc.encode_static(basis, long_table, dev(dat))
+    torch.cuda.synchronize()
+    n = int(nbytes.item())
+    got = stream[:n].cpu().numpy()
+    sym_gpu, d2, pbits = oracle.unpack(got, dat.size // C, C, bits)
+    d = oracle.delta(A, bits)
+    again = oracle.pack(sym_gpu, C, bits, d, skew, oracle.canonical_codes(skew), cap=n + 4096)
+    assert len(again) == n and (got == again).all()
+    # not a complete prefix code: rejected on the host
+    for bad in (np.full(16, 3, np.uint8), np.array([1] + [0] * 15, np.uint8), np.full(16, 5, np.uint8)):
+        with pytest.raises(fmtc.FmtcError) as e:
+            fmtc.table_import(bad, 4)
+        assert e.value.status == fmtc.EINVAL
+    # a table of another bit depth than the basis' step is fine (the step follows the table's bits), but the channel
+    # count must match the basis
+    with pytest.raises(fmtc.FmtcError) as e:
+        fmtc.encode_static(basis, fitted, torch.zeros((1, 4, 4, 16), device="cuda"))
+    assert e.value.status == fmtc.EINVAL
+
+
+def test_static_stream_that_outgrows_its_buffer_is_marked_invalid(fmtc, oracle):
+    case = CASES[1]
+    C, H, W, ncal, ndat, rank, act, bits, cs = case
+    cal, dat, T, mu, A = split_case(oracle, case, 812, synth.NHWC)
+    basis = fmtc.basis_import(T, mu, A)
+    table = fmtc.fit_table(basis, dev(cal), bits)
+    P = dat.size // C
+    full = fmtc.encode_static_bound(table, P, C)
+    good, ngood = fmtc.encode_static(basis, table, dev(dat))
+    torch.cuda.synchronize()
+    need = int(ngood.item())
+    small = need - 4096  # room for the side information and most, not all, of the payload
+    assert small < need <= full
+    guard = torch.full((small + 4096,), 0xAB, dtype=torch.uint8, device="cuda")
+    fmtc.encode_static(basis, table, dev(dat), stream_out=guard[:small])
+    torch.cuda.synchronize()
+    assert (guard[small:] == 0xAB).all(), "wrote past the capacity it was given"
+    xhat, err = fmtc.decode(basis, guard[:small], dat.shape, bits)
+    torch.cuda.synchronize()
+    assert int(err.item()) & fmtc.ERR_HEADER

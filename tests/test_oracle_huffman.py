@@ -124,3 +124,61 @@ def test_canonical_codes_are_prefix_free_and_ordered(oracle):
 def test_invalid_inputs(oracle):
     with pytest.raises(oracle.OracleError):
         oracle.huffman_lengths(np.zeros(16, np.uint64))  # nothing to code
+
+
+# ---- code table fixed at calibration time (section 3.1 leaves open when the Huffman table is made) ----
+def test_static_table_hand_worked(oracle):
+    # counts 7,1,0,0 -> smoothed 8,2,1,1: merge 1+1, then 2+2, then 4+8 -> depths 1,2,3,3
+    assert oracle.static_lengths(np.array([7, 1, 0, 0], np.uint64)).tolist() == [1, 2, 3, 3]
+    # all counts equal (here: no calibration data at all): a fixed-length code
+    assert oracle.static_lengths(np.zeros(16, np.uint64)).tolist() == [4] * 16
+    # smoothing changes nothing where one more count per symbol cannot reorder the merges
+    assert oracle.static_lengths(np.array([80, 40, 20, 10], np.uint64)).tolist() == \
+        oracle.huffman_lengths(np.array([80, 40, 20, 10], np.uint64)).tolist() == [1, 2, 3, 3]
+
+
+def test_static_table_is_complete_and_ordered(oracle):
+    rng = np.random.default_rng(31)
+    for bits in (2, 4, 6, 8):
+        K = 1 << bits
+        h = np.zeros(K, np.uint64)
+        used = rng.choice(K, size=max(2, K // 3), replace=False)
+        h[used] = rng.geometric(0.002, used.size)
+        ln = oracle.static_lengths(h)
+        assert ln.min() >= 1                                          # every symbol of the alphabet has a code
+        assert sum(2.0 ** -int(l) for l in ln) == 1.0                 # Kraft equality: a complete prefix code
+        order = np.argsort(h, kind="stable")
+        assert all(ln[order[i]] >= ln[order[i + 1]] for i in range(K - 1))  # rarer symbols never get shorter codes
+        # the symbols calibration never saw share the longest lengths
+        assert ln[h == 0].min() >= ln[h > 0].max()
+
+
+def test_static_table_rate_bounds(oracle):
+    """Coding a tensor with a table made from another sample of the same source costs at least the tensor's own
+    Huffman code (optimality) and at most cross-entropy + 1 bit per symbol (Kraft: len <= -log2 q + 1 fails for
+    Huffman in general, but the average obeys sum p len < H(p, q) + 1 only for Shannon lengths; so the pin is
+    against the table's own source: its average length on the calibration distribution is below H + 1)."""
+    rng = np.random.default_rng(32)
+    bits = 6
+    p = rng.dirichlet(np.full(64, 0.3))
+    cal = np.bincount(rng.choice(64, 200000, p=p), minlength=64).astype(np.uint64)
+    dat = np.bincount(rng.choice(64, 50000, p=p), minlength=64).astype(np.uint64)
+    ls = oracle.static_lengths(cal)
+    la = oracle.huffman_lengths(dat)
+    assert int((dat * ls).sum()) >= int((dat * la).sum())
+    q = (cal + 1) / float((cal + 1).sum())
+    assert float((q * ls).sum()) < float(-(q * np.log2(q)).sum()) + 1.0
+    # and the penalty on fresh data from the same source is small (a fraction of a bit per symbol)
+    assert (int((dat * ls).sum()) - int((dat * la).sum())) / dat.sum() < 0.05
+
+
+def test_static_table_stream_round_trip(oracle):
+    rng = np.random.default_rng(33)
+    bits, C, P = 4, 24, 500
+    cal = np.bincount(rng.choice(16, 5000, p=rng.dirichlet(np.full(16, 0.4))), minlength=16).astype(np.uint64)
+    ln = oracle.static_lengths(cal)
+    sym = rng.integers(0, 16, (P, C)).astype(np.uint8)  # uniform: includes symbols calibration hardly saw
+    stream = oracle.pack(sym, C, bits, 0.25, ln, oracle.canonical_codes(ln), cap=1 << 20)
+    back, d, pbits = oracle.unpack(stream, P, C, bits)
+    assert (back == sym).all() and d == np.float32(0.25)
+    assert pbits == int(ln[sym].astype(np.uint64).sum())
