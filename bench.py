@@ -174,6 +174,28 @@ def main():
                 "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, bits, dominant)),
                 "avg_us": dk["avg_us"], "hbm_bytes_algorithmic": dk["hbm_bytes_algorithmic"]}
 
+    # ---- the encoder with a code table fixed at calibration time (reported beside `value`, not part of it) ----
+    table = fmtc.fit_table(basis, torch.from_numpy(synth.to_layout(calib, layout)).cuda(), bits, layout)
+    scap = fmtc.encode_static_bound(table, P, C)
+    sstreams = [torch.empty(scap, dtype=torch.uint8, device="cuda") for _ in sets]
+    sa = [(basis._h, table._h, s["x"].data_ptr(), N, C, H, W, layout, 4096, st.data_ptr(), scap,
+           s["nbytes"].data_ptr(), s["ws"].data_ptr(), ws_bytes, stream_h) for s, st in zip(sets, sstreams)]
+    run(lambda i: lib.fmtc_encode_static(*sa[i % R]), args.warmup)
+    dt_static = run(lambda i: lib.fmtc_encode_static(*sa[i % R]), args.steps)
+    fmtc.profile_enable(args.steps)
+    run(lambda i: lib.fmtc_encode_static(*sa[i % R]), args.steps)
+    sprof = fmtc.profile_read()
+    fmtc.profile_enable(0)
+    sinfo = fmtc.stream_info(sstreams[0][:64].cpu().numpy())
+    static = {"encode_GBps": round(in_bytes / (dt_static / args.steps) / 1e9, 3),
+              "us_per_encode": round(1e6 * dt_static / args.steps, 2),
+              "bits_per_value": round(sinfo["payload_bits"] / V, 4),
+              "container_bits_per_value": round(8.0 * sinfo["stream_bytes"] / V, 4),
+              "kernels": {k: round(1e3 * v[0], 3) for k, v in sprof.items()},
+              "note": "projection, quantizer and packing in one kernel where the shape allows (32/64/128 channels)"}
+    xh2, err2 = fmtc.decode(basis, sstreams[0], xs.shape, bits, layout)
+    assert int(err2.item()) == 0 and torch.equal(xh2, sets[0]["xhat"]), "the two encoders disagree on the symbols"
+
     # ---- yardstick for the memory counters: one plain copy of known size (not timed) ----
     ysrc = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     ydst = torch.empty_like(ysrc)
@@ -223,6 +245,7 @@ def main():
         "mse": mse,
         "roofline": roofline,
         "kernels": kernels,
+        "static_table_encoder": static,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "fmtc_internal.h"
+#include "fmtc_pack_device.h"
 
 struct fmtc_basis {
     int C = 0, Cpad = 0;
@@ -553,6 +554,23 @@ fmtc_status fmtc_encode_static(const fmtc_basis* basis, const fmtc_table* t, con
     const uint64_t cap_words = (cap - pl.g.off_payload) / 4;
     hipError_t e;
     int n_parts = 0;
+    // one kernel where the shape allows it: the coder's counters are cleared first, since the kernel that counts
+    // in them is also the one that would clear them
+    {
+        PackParams pk = pack_params(nullptr, pl.g, bits, delta, cs, 0, t->d_enc_table, static_cast<uint8_t*>(d_stream_out),
+                                    cap_words, d_out_bytes);
+        pk.static_max_len = t->max_len;
+        const char* knob = getenv("FMTC_STATIC_FUSED");  // "0": always the two kernels (read at every call)
+        if (!(knob && knob[0] == '0') && (C == 32 || C == 64 || C == 128) && chunk_syms == 4096) {
+            static_assert(sizeof(CoderCtrl) % 4 == 0, "control block is cleared as words");
+            const size_t clear_bytes = pl.ws.off_lookback + sizeof(uint64_t) * (size_t)cs.n_groups - pl.ws.off_ctrl;
+            if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(w + pl.ws.off_ctrl), clear_bytes / 4, s)) != hipSuccess)
+                return hip_fail(e, "clear kernel");
+            e = launch_encode_static_fused(device_view(basis), d_x, N, HW, layout, delta, bits, cs, pk, s);
+            if (e == hipSuccess) return FMTC_OK;
+            if (e != hipErrorNotSupported) return hip_fail(e, "fused encode kernel");
+        }
+    }
     if ((e = launch_project_quantize(device_view(basis), d_x, N, HW, layout, delta, bits, syms, cs, &n_parts, s)) != hipSuccess)
         return hip_fail(e, "project/quantize kernel");
     if ((e = launch_coder_static(syms, pl.g, bits, delta, cs, t->d_enc_table, t->max_len, static_cast<uint8_t*>(d_stream_out),

@@ -13,6 +13,7 @@
 
 #include "fmtc_device.h"
 #include "fmtc_internal.h"
+#include "fmtc_pack_device.h"
 
 namespace fmtc {
 
@@ -461,9 +462,15 @@ struct RowParams {
     CoderCtrl* ctrl;
     unsigned long long* lookback;
     uint32_t n_groups;
+    PackParams pk;            // FUSED only: where the container goes
 };
 
-template <int NCT, int LAYOUT, bool VEC>
+// FUSED: the same projection and quantizer, but the symbols of a chunk stay in LDS and the wavefront packs them
+// with a code table fixed beforehand (no histogram, nothing but the container leaves the kernel).  Needs
+// C = 32 NCT in {32, 64, 128} and chunks of 4096 symbols, i.e. 4 / NCT whole pixel tiles; the grid must not exceed
+// what the device holds at once (a chunk's position in the payload comes from the workgroups before it), and the
+// look-back words and the control block must be clear when the kernel starts.
+template <int NCT, int LAYOUT, bool VEC, bool FUSED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_project_quantize_rows(RowParams p) {
     constexpr int NJ = NCT * 2;  // steps of 16 channels
     extern __shared__ __align__(16) uint4 basis16[];  // [NCT][NJ][2][64], then the histograms
@@ -478,6 +485,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // behind them.
     const int K = 1 << p.bits;
     uint32_t* whist = reinterpret_cast<uint32_t*>(basis16 + NCT * NJ * 2 * 64);  // [4][K * kHistLanes]
+    // FUSED: in place of the histograms, the four wavefronts' chunks of symbols (4096 bytes each, stream order)
+    // and the packer's tables and images
+    constexpr int TPC = FUSED ? 4 / NCT : 1;  // pixel tiles per chunk
+    uint8_t* sym_tiles = reinterpret_cast<uint8_t*>(whist);
+    PackShared& S = *reinterpret_cast<PackShared*>(sym_tiles + 4 * 4096);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
@@ -519,9 +531,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     };
     // the first tile's pixels come from HBM: their loads go out before anything else
-    int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+    int64_t tile = ((int64_t)blockIdx.x * 4 + wave) * TPC;
     if (tile < p.n_tiles) load_pixels(tile);
-    zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
+    if constexpr (!FUSED) zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
 
     // the basis goes from global memory straight into LDS, 16 bytes per lane and instruction
     {
@@ -531,7 +543,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             __builtin_amdgcn_global_load_lds(src + tid + 256 * i, &basis16[256 * i + 64 * wave], 16, 0, 0);
     }
     if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
-    for (int i = tid; i < 4 * K * kHistLanes; i += 256) whist[i] = 0u;
+    if constexpr (!FUSED) {
+        for (int i = tid; i < 4 * K * kHistLanes; i += 256) whist[i] = 0u;
+    } else {
+        S.tab[tid] = p.pk.enc_table[tid];
+        if (tid == 0) {
+            S.max_len = p.pk.static_max_len;
+            S.payload_bits = 0ull;
+        }
+        if (blockIdx.x == 0) p.pk.stream[kHeaderBytes + tid] = (uint8_t)(p.pk.enc_table[tid] >> 56);  // the container's length table
+        pack_clear_image(S, wave, lane);
+    }
 
     const int zero_sym = 1 << (p.bits - 1);
     const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1), zero_f = (float)zero_sym;
@@ -549,6 +571,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's part of the basis has landed in LDS
     __syncthreads();
 
+    int64_t chunk_px0 = 0;  // FUSED: first pixel of the chunk this wavefront is working on
     // ---- exact decision where the fast pass can not be trusted (rare) ----
     // A tile notes the values that lie too close to a rounding boundary in the wavefront's list: tile, pixel
     // lane, coefficient and the symbol already stored and counted.  When the list is full, and after the
@@ -594,16 +617,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             qd = fmin(fmax(qd, (double)lo), (double)hi);
             const uint32_t sfix = (uint32_t)((int)qd + zero_sym);
             if (active && (lane & 15) == 0 && sfix != old) {
-                atomicSub(&wh0[old * kHistLanes], 1u);
-                atomicAdd(&wh0[sfix * kHistLanes], 1u);
-                p.syms[qpx * C + k] = (uint8_t)sfix;
+                if constexpr (FUSED) {
+                    // the listed tiles are those of the chunk in this wavefront's LDS tile
+                    sym_tiles[wave * 4096 + ((qpx - chunk_px0) * C + k)] = (uint8_t)sfix;
+                } else {
+                    atomicSub(&wh0[old * kHistLanes], 1u);
+                    atomicAdd(&wh0[sfix * kHistLanes], 1u);
+                    p.syms[qpx * C + k] = (uint8_t)sfix;
+                }
             }
         }
         wave_sync_lds();
         if (lane == 0) *fix_count = 0u;
         wave_sync_lds();
     };
-    for (; tile < p.n_tiles; tile += (int64_t)gridDim.x * 4) {
+    auto process_tile = [&](const int64_t tile, const int64_t next_tile) {
         const int64_t px = tile * 32 + l32;
         const bool px_ok = px < p.P;
         // ---- mean removed, split into the two f16 parts (padding channels hold 0 - 0) ----
@@ -637,7 +665,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         const float tau = fminf(fmaxf(p.kappa * __builtin_sqrtf(n2), p.tau_min), 0.125f);
         const float near_limit = force ? -1.f : 0.5f - tau;
         // the raw registers are free: the next tile's loads are in flight during this tile's arithmetic
-        const int64_t next_tile = tile + (int64_t)gridDim.x * 4;
         if (next_tile < p.n_tiles) load_pixels(next_tile);
 
         auto project_tile = [&](int kt, floatx16& am, floatx16& ac) {
@@ -675,8 +702,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 for (int r = 0; r < 16; r++)
                     if (k0 + r < C) {
                         const uint32_t sy = (word[r >> 2] >> (8 * (r & 3))) & 255u;
-                        atomicAdd(&wh[sy * kHistLanes], 1u);
-                        p.syms[px * C + k0 + r] = (uint8_t)sy;
+                        if constexpr (FUSED) {
+                            sym_tiles[wave * 4096 + ((px - chunk_px0) * C + k0 + r)] = (uint8_t)sy;
+                        } else {
+                            atomicAdd(&wh[sy * kHistLanes], 1u);
+                            p.syms[px * C + k0 + r] = (uint8_t)sy;
+                        }
                     }
             }
             return maxd;
@@ -744,7 +775,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                     maxd = fmaxf(maxd, fabsf(t - q));
                     const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
                     word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
-                    if (k_ok) atomicAdd(&wh[(uint32_t)qc * kHistLanes], 1u);
+                    if constexpr (!FUSED)
+                        if (k_ok) atomicAdd(&wh[(uint32_t)qc * kHistLanes], 1u);
                 };
                 if (kt + 1 < NCT) {
 #pragma unroll
@@ -763,9 +795,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                     for (int r = 0; r < 16; r++) quantize_value(r);
                 }
                 // C is a multiple of 16: every lane's 16 symbols are a 16-byte aligned piece of its pixel's row
-                if (k_ok)
+                if constexpr (FUSED) {
+                    *reinterpret_cast<uint4*>(sym_tiles + wave * 4096 + ((px - chunk_px0) * C + kt * 32 + 16 * half)) =
+                        make_uint4(word[0], word[1], word[2], word[3]);
+                } else if (k_ok) {
                     *reinterpret_cast<uint4*>(p.syms + px * C + kt * 32 + 16 * half) =
                         make_uint4(word[0], word[1], word[2], word[3]);
+                }
                 if (__builtin_expect(__any(!(maxd <= near_limit) && k_ok), 0)) note_tile(am, ac, kt, word);
                 am = nm;
                 ac = nc;
@@ -781,6 +817,41 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 if (kt + 1 < NCT) { am = nm; ac = nc; }
             }
         }
+    };
+    if constexpr (FUSED) {
+        // Chunk group g = the chunks 4g .. 4g + 3, one per wavefront; the workgroup takes groups blockIdx.x,
+        // blockIdx.x + gridDim.x, ... in turn, so every group before one in progress is finished or in progress too.
+        for (uint32_t group = blockIdx.x; group < p.pk.n_groups; group += gridDim.x) {
+            const uint32_t ch = group * 4 + (uint32_t)wave;
+            const int64_t tile0 = (int64_t)ch * TPC;
+            const int64_t next_chunk_tile = ((int64_t)(group + gridDim.x) * 4 + wave) * TPC;  // past the end: no loads
+            chunk_px0 = tile0 * 32;
+            uint32_t clen = 0;
+            if (ch < p.pk.n_chunks) {
+                const uint64_t c0 = (uint64_t)ch * 4096u;
+                clen = (uint32_t)((p.pk.V - c0 < 4096u) ? (p.pk.V - c0) : 4096u);
+#pragma unroll
+                for (int t = 0; t < TPC; t++) {
+                    const int64_t tl = tile0 + t;
+                    if (tl < p.n_tiles)  // wavefront-uniform
+                        process_tile(tl, (t + 1 < TPC && tl + 1 < p.n_tiles) ? tl + 1
+                                         : (group + gridDim.x < p.pk.n_groups ? next_chunk_tile : p.n_tiles));
+                }
+                if (*fix_count) resolve_list();
+            }
+            wave_sync_lds();  // the symbols other lanes wrote precede the reads below
+            // register q of lane l: symbols 256q + 4l .. + 3 of the chunk (C is a multiple of 32: clen one of 4)
+            uint32_t w[16];
+#pragma unroll
+            for (int q = 0; q < 16; q++) {
+                const uint32_t o = 256u * q + 4u * (uint32_t)lane;
+                w[q] = (o + 4u <= clen) ? *reinterpret_cast<const uint32_t*>(sym_tiles + wave * 4096 + o) : 0u;
+            }
+            pack_group<kPackStatic>(S, p.pk, group, w, clen, []() {});
+        }
+        return;
+    } else {
+        for (; tile < p.n_tiles; tile += (int64_t)gridDim.x * 4) process_tile(tile, tile + (int64_t)gridDim.x * 4);
     }
     if (*fix_count) resolve_list();
     __syncthreads();
@@ -827,6 +898,7 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     p.ctrl = cs.ctrl;
     p.lookback = cs.lookback;
     p.n_groups = cs.n_groups;
+    p.pk = PackParams{};
     const int nct = b.Cpad / 32;
     const size_t lds = sizeof(float) * (size_t)b.Cpad * b.Cpad + sizeof(uint32_t) * 4 * kHistLanes * ((size_t)1 << bits);
     int64_t gx = (p.n_tiles + 3) / 4;
@@ -858,6 +930,64 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
 #undef FMTC_ROWS_N
 #undef FMTC_ROWS
     return el;
+}
+
+// Projection, quantizer and packing with a table fixed beforehand as one kernel.  Returns hipErrorNotSupported
+// where the shape does not allow it (the caller then runs the two kernels one after the other).
+hipError_t launch_encode_static_fused(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
+                                      float delta, int bits, const CoderScratch& cs, const PackParams& pk,
+                                      hipStream_t s) {
+    const int64_t P = N * HW;
+    if (!(b.C == 32 || b.C == 64 || b.C == 128) || pk.chunk_syms != 4096u) return hipErrorNotSupported;
+    RowParams p;
+    p.x = d_x;
+    p.basis16 = b.fwd16;
+    p.mu = b.mu;
+    p.Trow = b.T;
+    p.P = P;
+    p.HW = HW;
+    p.C = b.C;
+    p.bits = bits;
+    p.inv_delta = (float)(1.0 / (double)delta);
+    p.delta = delta;
+    p.kappa = 1.9073486e-6f /* 2^-19 */ * b.row_norm * p.inv_delta;  // see launch_rows
+    p.tau_min = 4.7683716e-7f /* 2^-21 */ * (float)(1 << (bits - 1));
+    p.n_tiles = (P + 31) / 32;
+    p.syms = nullptr;
+    p.hist_parts = nullptr;
+    p.ctrl = cs.ctrl;
+    p.lookback = cs.lookback;
+    p.n_groups = cs.n_groups;
+    p.pk = pk;
+    const int nct = b.C / 32;
+    const size_t lds = sizeof(float) * (size_t)b.C * b.C + 4 * 4096 + sizeof(PackShared);
+    const void* fn = nullptr;
+#define FMTC_FUSED(NCT, LAY) fn = reinterpret_cast<const void*>(&k_project_quantize_rows<NCT, LAY, true, true>)
+    if (layout == FMTC_NHWC) {
+        if (nct == 1) FMTC_FUSED(1, FMTC_NHWC); else if (nct == 2) FMTC_FUSED(2, FMTC_NHWC); else FMTC_FUSED(4, FMTC_NHWC);
+    } else {
+        if (nct == 1) FMTC_FUSED(1, FMTC_NCHW); else if (nct == 2) FMTC_FUSED(2, FMTC_NCHW); else FMTC_FUSED(4, FMTC_NCHW);
+    }
+#undef FMTC_FUSED
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    // every workgroup of the grid must be on the device at once
+    static int resident[2][3] = {{0, 0, 0}, {0, 0, 0}};
+    int& cap = resident[layout == FMTC_NHWC][nct == 4 ? 2 : nct - 1];
+    if (!cap) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, lds) != hipSuccess || cus < 1 || per_cu < 1)
+            return hipErrorNotSupported;
+        cap = cus;  // one workgroup per compute unit, whatever more would fit
+    }
+    const uint32_t grid = pk.n_groups < (uint32_t)cap ? pk.n_groups : (uint32_t)cap;
+    void* args[] = {(void*)&p};
+    hipEvent_t ev_a = nullptr, ev_b = nullptr;
+    if (prof_next(K_PROJECT, &ev_a, &ev_b))
+        return hipExtLaunchKernel(fn, dim3(grid), dim3(256), args, lds, s, ev_a, ev_b, 0);
+    return hipLaunchKernel(fn, dim3(grid), dim3(256), args, lds, s);
 }
 
 // ---------------------------------------------------------------------------

@@ -368,4 +368,12 @@ __device__ __forceinline__ void pack_group(PackShared& S, const PackParams& p, u
     __syncthreads();  // wave_words, wave_slack and excl* are rewritten by the next group
 }
 
+// Host side (fmtc_coder_kernels.hip): the packer's arguments for a tensor geometry.
+PackParams pack_params(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
+                       int n_parts, const uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
+                       uint64_t* d_out_bytes);
+hipError_t launch_encode_static_fused(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
+                                      float delta, int bits, const CoderScratch& cs, const PackParams& pk,
+                                      hipStream_t s);
+
 }  // namespace fmtc

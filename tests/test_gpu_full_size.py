@@ -110,3 +110,50 @@ def test_full_size_encode_decode(fmtc, oracle, name, bits):
         ref = oracle.reconstruct(sym_gpu[n0 * hw:n1 * hw], x[n0:n1].shape, T, mu, d, bits)
         worst = max(worst, float(np.abs(xhat[n0:n1].astype(np.float64) - ref).max()))
     assert worst <= RECON_TOL, f"reconstruction off by {worst:.3e}"
+
+
+# the shapes the one-kernel encoder with a fixed table takes, at full size: one chunk group per workgroup
+# (stage 2), and many more groups than the device holds workgroups (N = 256)
+STATIC = [
+    ("resnet18_stage2_c128_28", 6),
+    ("cfg0_c64_56", 8),
+    ("resnet18_n256_c128_28", 4),
+    ("resnet18_n256_c64_56", 6),
+]
+
+
+@pytest.mark.parametrize("name,bits", STATIC, ids=[f"{n}_b{b}" for n, b in STATIC])
+def test_full_size_static_table_encode(fmtc, oracle, name, bits):
+    wl = synth.WORKLOADS[name]
+    C = wl["C"]
+    calib, x = synth.workload(name, seed=0)
+    T, mu, A = fit_on_host(oracle, calib, C)
+    d = oracle.delta(A, bits)
+    P = x.size // C
+    print(f"{name} b={bits}: V={x.size}", flush=True)
+    basis = fmtc.basis_import(T, mu, A)
+    table = fmtc.fit_table(basis, torch.from_numpy(calib).cuda(), bits, synth.NHWC)
+    ln, _ = table.export()
+    x_d = torch.from_numpy(x).cuda()
+    stream, nbytes = fmtc.encode_static(basis, table, x_d, synth.NHWC)
+    xhat, err = fmtc.decode(basis, stream, x.shape, bits, synth.NHWC)
+    torch.cuda.synchronize()
+    n = int(nbytes.item())
+    got = stream[:n].cpu().numpy()
+    assert int(err.item()) == 0
+    sym_gpu, d2, pbits = oracle.unpack(got, P, C, bits)
+    assert d2 == d
+    ref_sym, margin = oracle.quantize(oracle.project(x, T, mu), d, bits, want_margin=True)
+    diff = sym_gpu != ref_sym
+    n_bad = int(diff.sum())
+    if n_bad:
+        assert margin[diff].max() <= SYM_MARGIN and n_bad / ref_sym.size <= SYM_RATE
+    del margin, diff, ref_sym
+    again = oracle.pack(sym_gpu, C, bits, d, ln, oracle.canonical_codes(ln), cap=n + 4096)
+    assert len(again) == n and (got == again).all()
+    assert pbits == int(ln[sym_gpu].astype(np.uint64).sum())
+    # same symbols as the encoder that builds its own table -> the same reconstruction, bit for bit
+    stream_a, _ = fmtc.encode(basis, x_d, bits, synth.NHWC)
+    xhat_a, err_a = fmtc.decode(basis, stream_a, x.shape, bits, synth.NHWC)
+    torch.cuda.synchronize()
+    assert int(err_a.item()) == 0 and torch.equal(xhat, xhat_a)

@@ -106,6 +106,22 @@ def test_static_table_encode_matches_oracle(fmtc, oracle, case, layout):
     assert int(nbytes2.item()) == n and (stream2[:n].cpu().numpy() == got).all()
 
 
+@pytest.mark.parametrize("case", [CASES[0], CASES[2], CASES[3], CASES[4]], ids=[IDS[0], IDS[2], IDS[3], IDS[4]])
+def test_single_kernel_and_two_kernel_paths_agree(fmtc, oracle, case, monkeypatch):
+    """Shapes the one-kernel encoder takes: the same call with that kernel switched off gives the same bytes."""
+    C, H, W, ncal, ndat, rank, act, bits, cs = case
+    cal, dat, T, mu, A = split_case(oracle, case, 750 + C, synth.NHWC)
+    basis = fmtc.basis_import(T, mu, A)
+    table = fmtc.fit_table(basis, dev(cal), bits)
+    a, na = fmtc.encode_static(basis, table, dev(dat))
+    torch.cuda.synchronize()
+    monkeypatch.setenv("FMTC_STATIC_FUSED", "0")
+    b, nb = fmtc.encode_static(basis, table, dev(dat))
+    torch.cuda.synchronize()
+    n = int(na.item())
+    assert int(nb.item()) == n and (a[:n] == b[:n]).all()
+
+
 def test_table_import_export_and_bad_tables(fmtc, oracle):
     case = CASES[1]
     C, H, W, ncal, ndat, rank, act, bits, cs = case
