@@ -182,6 +182,7 @@ __device__ __forceinline__ uint32_t pack_chunk(const uint32_t (&w)[16], uint32_t
 struct PackShared {
     unsigned long long tab[256];                                  // bit-reversed code | length << 56
     __align__(16) uint32_t stage[kPackWaves][kStageWords + 4];    // per wavefront: chunk image + the spare words
+    uint16_t runs[kPackWaves][64];                                // bit counts of a chunk's runs on their way out
     uint32_t wave_words[kPackWaves], wave_slack[kPackWaves];
     uint32_t excl, excl_slack, max_len;
     unsigned long long payload_bits;
@@ -232,7 +233,12 @@ __device__ __forceinline__ void pack_group(PackShared& S, const PackParams& p, u
     };
     uint32_t n_words = 0, slack = 0;
     if (have) {
-        const uint32_t total_bits = build_window(0, kStageWords, sub_bits + (size_t)ch * p.subs_per_chunk);
+        // the run sizes are produced four at a time: up to 64 of them are collected in LDS and leave as one
+        // contiguous store (scattered two-byte stores cost a partial memory write each)
+        uint16_t* runs_out = sub_bits + (size_t)ch * p.subs_per_chunk;
+        const bool staged = p.subs_per_chunk <= 64u;
+        const uint32_t total_bits = build_window(0, kStageWords, staged ? S.runs[wave] : runs_out);
+        if (staged && (uint32_t)lane < p.subs_per_chunk) runs_out[lane] = S.runs[wave][lane];
         n_words = (total_bits + 31) >> 5;
         slack = 32u * n_words - total_bits;
     }
