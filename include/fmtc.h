@@ -143,9 +143,11 @@ fmtc_status fmtc_decode(const fmtc_basis *basis, const void *d_stream_in, size_t
  * the 2^bits symbols, so that every symbol a later tensor can contain has a
  * code; Huffman lengths of those counts, canonical codes as in fmtc_encode.
  * The container written by fmtc_encode_static has the same format (it carries
- * the table), so fmtc_decode reads it unchanged.  Where the tensor's shape
- * allows (32, 64 or 128 channels, 4096-symbol chunks) projection, quantizer
- * and bit packing run as ONE kernel and the symbols never reach memory.
+ * the table), so fmtc_decode reads it unchanged.  For 32, 64 or 128 channels
+ * with 4096-symbol chunks, and a tensor of at most four chunks per compute
+ * unit of the device, projection, quantizer and bit packing run as ONE kernel
+ * and the symbols never reach memory; otherwise the projection kernel is
+ * followed by the packing kernel, which then skips histogram and table.
  *
  * fmtc_fit_table synchronises the stream and allocates/frees device memory
  * (calibration time, not the hot path).  fmtc_table_import takes the lengths

@@ -561,7 +561,7 @@ fmtc_status fmtc_encode_static(const fmtc_basis* basis, const fmtc_table* t, con
                                     cap_words, d_out_bytes);
         pk.static_max_len = t->max_len;
         const char* knob = getenv("FMTC_STATIC_FUSED");  // "0": always the two kernels (read at every call)
-        if (!(knob && knob[0] == '0') && (C == 32 || C == 64 || C == 128) && chunk_syms == 4096) {
+        if (!(knob && knob[0] == '0') && encode_static_fused_applies(C, layout, (uint32_t)chunk_syms, cs.n_groups)) {
             static_assert(sizeof(CoderCtrl) % 4 == 0, "control block is cleared as words");
             const size_t clear_bytes = pl.ws.off_lookback + sizeof(uint64_t) * (size_t)cs.n_groups - pl.ws.off_ctrl;
             if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(w + pl.ws.off_ctrl), clear_bytes / 4, s)) != hipSuccess)

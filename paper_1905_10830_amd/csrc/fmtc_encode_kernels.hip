@@ -932,13 +932,58 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     return el;
 }
 
+// The fused kernel for a channel count and layout, its LDS size, and how many of its workgroups the device
+// holds at once (0: shape not supported or the query failed).
+static int fused_kernel_for(int C, int layout, const void** fn_out, size_t* lds_out) {
+    if (!(C == 32 || C == 64 || C == 128)) return 0;
+    const int nct = C / 32;
+    const size_t lds = sizeof(float) * (size_t)C * C + 4 * 4096 + sizeof(PackShared);
+    const void* fn = nullptr;
+#define FMTC_FUSED(NCT, LAY) fn = reinterpret_cast<const void*>(&k_project_quantize_rows<NCT, LAY, true, true>)
+    if (layout == FMTC_NHWC) {
+        if (nct == 1) FMTC_FUSED(1, FMTC_NHWC); else if (nct == 2) FMTC_FUSED(2, FMTC_NHWC); else FMTC_FUSED(4, FMTC_NHWC);
+    } else {
+        if (nct == 1) FMTC_FUSED(1, FMTC_NCHW); else if (nct == 2) FMTC_FUSED(2, FMTC_NCHW); else FMTC_FUSED(4, FMTC_NCHW);
+    }
+#undef FMTC_FUSED
+    *fn_out = fn;
+    *lds_out = lds;
+    static int resident[2][3] = {{0, 0, 0}, {0, 0, 0}};
+    int& cap = resident[layout == FMTC_NHWC][nct == 4 ? 2 : nct - 1];
+    if (!cap) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, lds) != hipSuccess || cus < 1 || per_cu < 1)
+            return 0;
+        cap = cus;  // one workgroup per compute unit, whatever more would fit
+    }
+    return cap;
+}
+
+// The one-kernel encoder is used where every chunk group gets a workgroup of its own: its workgroups work through
+// their groups in lock step (project, pack, wait for the position, store), which is the shortest path for a
+// tensor the device holds at once and loses to two specialised kernels beyond that (measured: 25 us against
+// 17 + 10 us at 196 groups, 135 us against 60 + 40 us at 1568).
+bool encode_static_fused_applies(int C, int layout, uint32_t chunk_syms, uint32_t n_groups) {
+    const void* fn;
+    size_t lds;
+    if (chunk_syms != 4096u) return false;
+    const int cap = fused_kernel_for(C, layout, &fn, &lds);
+    return cap > 0 && n_groups <= (uint32_t)cap;
+}
+
 // Projection, quantizer and packing with a table fixed beforehand as one kernel.  Returns hipErrorNotSupported
-// where the shape does not allow it (the caller then runs the two kernels one after the other).
+// where encode_static_fused_applies() says no.
 hipError_t launch_encode_static_fused(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
                                       float delta, int bits, const CoderScratch& cs, const PackParams& pk,
                                       hipStream_t s) {
     const int64_t P = N * HW;
-    if (!(b.C == 32 || b.C == 64 || b.C == 128) || pk.chunk_syms != 4096u) return hipErrorNotSupported;
+    const void* fn = nullptr;
+    size_t lds = 0;
+    const int cap = fused_kernel_for(b.C, layout, &fn, &lds);
+    if (cap <= 0 || pk.chunk_syms != 4096u || pk.n_groups > (uint32_t)cap) return hipErrorNotSupported;
     RowParams p;
     p.x = d_x;
     p.basis16 = b.fwd16;
@@ -959,29 +1004,6 @@ hipError_t launch_encode_static_fused(const BasisDevice& b, const float* d_x, in
     p.lookback = cs.lookback;
     p.n_groups = cs.n_groups;
     p.pk = pk;
-    const int nct = b.C / 32;
-    const size_t lds = sizeof(float) * (size_t)b.C * b.C + 4 * 4096 + sizeof(PackShared);
-    const void* fn = nullptr;
-#define FMTC_FUSED(NCT, LAY) fn = reinterpret_cast<const void*>(&k_project_quantize_rows<NCT, LAY, true, true>)
-    if (layout == FMTC_NHWC) {
-        if (nct == 1) FMTC_FUSED(1, FMTC_NHWC); else if (nct == 2) FMTC_FUSED(2, FMTC_NHWC); else FMTC_FUSED(4, FMTC_NHWC);
-    } else {
-        if (nct == 1) FMTC_FUSED(1, FMTC_NCHW); else if (nct == 2) FMTC_FUSED(2, FMTC_NCHW); else FMTC_FUSED(4, FMTC_NCHW);
-    }
-#undef FMTC_FUSED
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    // every workgroup of the grid must be on the device at once
-    static int resident[2][3] = {{0, 0, 0}, {0, 0, 0}};
-    int& cap = resident[layout == FMTC_NHWC][nct == 4 ? 2 : nct - 1];
-    if (!cap) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, lds) != hipSuccess || cus < 1 || per_cu < 1)
-            return hipErrorNotSupported;
-        cap = cus;  // one workgroup per compute unit, whatever more would fit
-    }
     const uint32_t grid = pk.n_groups < (uint32_t)cap ? pk.n_groups : (uint32_t)cap;
     void* args[] = {(void*)&p};
     hipEvent_t ev_a = nullptr, ev_b = nullptr;

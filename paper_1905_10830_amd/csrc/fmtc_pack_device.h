@@ -378,6 +378,7 @@ __device__ __forceinline__ void pack_group(PackShared& S, const PackParams& p, u
 PackParams pack_params(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
                        int n_parts, const uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
                        uint64_t* d_out_bytes);
+bool encode_static_fused_applies(int C, int layout, uint32_t chunk_syms, uint32_t n_groups);
 hipError_t launch_encode_static_fused(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
                                       float delta, int bits, const CoderScratch& cs, const PackParams& pk,
                                       hipStream_t s);
