@@ -400,9 +400,17 @@ constexpr int kPayWords = 918;  // LDS copy of a chunk's payload: up to ~7 bits/
 // kernel below (levels exact in f16, basis entries split in two f16 parts, two matrix instructions per 16
 // coefficients), the basis streaming from L2 in operand order one step ahead of its use.
 template <int MT, int LAYOUT, bool ALIGNED4>
-__global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
+__global__ __launch_bounds__(512) void k_decode_tiles(DecodeParams p) {
     __shared__ __align__(16) DecTables T;
-    __shared__ uint32_t pay[4][kPayWords + 2];  // per wavefront: the chunk's payload words
+    // 8 wavefronts.  Workgroup tile in units of 32: 4 pixel tiles x 8 channel tiles (128 pixels x 256 channels, a
+    // wavefront 2 x 2 of them), or 2 x 8 (64 pixels, a wavefront 1 x 2) where 128 pixels of symbols do not fit LDS.
+    constexpr int PTW = MT, CTW = 8, PPW = MT / 2;  // PPW: pixel tiles per wavefront
+    // the chunks' payload words (one buffer per wavefront) while decoding, the basis blocks of three contraction
+    // steps afterwards: the two uses are a workgroup barrier apart
+    constexpr size_t kPayBytes = sizeof(uint32_t) * 8 * (kPayWords + 2), kRingBytes = sizeof(uint4) * 3 * CTW * 2 * 64;
+    __shared__ __align__(16) uint8_t s_shared[kPayBytes > kRingBytes ? kPayBytes : kRingBytes];
+    uint32_t(*pay)[kPayWords + 2] = reinterpret_cast<uint32_t(*)[kPayWords + 2]>(s_shared);
+    uint4(*s_ring)[CTW * 2][64] = reinterpret_cast<uint4(*)[CTW * 2][64]>(s_shared);
     extern __shared__ __align__(16) uint8_t symtile[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -415,7 +423,7 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
         if (tid == 0) atomicOr(p.err, FMTC_ERR_HEADER);
         return;
     }
-    if (!build_decode_tables<256>(T, (int)p.stream[kHeaderBytes + tid], p.bits)) {
+    if (!build_decode_tables<512>(T, tid < 256 ? (int)p.stream[kHeaderBytes + tid] : 0, p.bits)) {
         if (tid == 0) atomicOr(p.err, FMTC_ERR_TABLE);
         return;
     }
@@ -436,9 +444,57 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
     const halfx2 level_off2 = {level_off, level_off};
     const int NJ = p.ncs * 2;  // steps of 16 coefficients
 
+    // x_hat = Delta (sum q T_hi + 2^-11 sum q T_lo) + mu for one 32 x 32 tile (channel tile ct, pixel tile pt of a
+    // workgroup tile of TP pixels starting at pixel px_tile0).  Accumulator r of lane l is element
+    // (8*(r/4) + 4*(l/32) + r%4, l%32) of the tile: rows = pixels for NHWC, channels for NCHW.  Whole tiles are
+    // stored without per-element predicates (one straight run of stores).
+    auto store_tile = [&](int ct, int pt, int TP, int64_t px_tile0, floatx16& acc, const floatx16& acl) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[r] = __builtin_fmaf(acl[r], 1.f / 2048.f, acc[r]) * delta;
+        if constexpr (LAYOUT == FMTC_NHWC) {
+            const int c = ct * 32 + l32;
+            if (c < C) {
+                const float m_c = p.mu[c];
+                const int px_first = pt * 32;
+                float* dst = p.xhat + (px_tile0 + px_first + 4 * half) * C + c;
+                if (px_first + 32 <= TP) {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = acc[r] + m_c;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        int pxl = px_first + 8 * (r >> 2) + 4 * half + (r & 3);
+                        if (pxl < TP) dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = acc[r] + m_c;
+                    }
+                }
+            }
+        } else {
+            float m_r[16];
+            const int cb = ct * 32 + 4 * half;
+#pragma unroll
+            for (int r = 0; r < 16; r++) m_r[r] = p.mu[cb + 8 * (r >> 2) + (r & 3)];  // mu is padded to a multiple of 32
+            const int pxl = pt * 32 + l32;
+            if (pxl < TP) {
+                const int64_t px = px_tile0 + pxl;
+                const int64_t n = px / p.HW, hw = px - n * p.HW;
+                float* dst = p.xhat + (n * (int64_t)C + cb) * p.HW + hw;
+                if (ct * 32 + 32 <= C) {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * p.HW] = acc[r] + m_r[r];
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        int c = cb + 8 * (r >> 2) + (r & 3);
+                        if (c < C) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * p.HW] = acc[r] + m_r[r];
+                    }
+                }
+            }
+        }
+    };
+
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         // ---- variable length decoding into the LDS tile ----
-        for (int j = wave; j < G; j += 4) {
+        for (int j = wave; j < G; j += 8) {
             const uint32_t ch = tile * G + j;
             if (ch >= n_chunks) break;
             const uint64_t c0 = (uint64_t)ch * chunk_syms;
@@ -483,52 +539,74 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
 
         if (p.syms_out) {
             if constexpr (ALIGNED4) {
-                for (uint32_t n = 4 * tid; n < tile_syms; n += 1024)
+                for (uint32_t n = 4 * tid; n < tile_syms; n += 2048)
                     *reinterpret_cast<uint32_t*>(p.syms_out + tile_s0 + n) =
                         *reinterpret_cast<const uint32_t*>(symtile + sym_addr(n));
             } else {
-                for (uint32_t n = tid; n < tile_syms; n += 256) p.syms_out[tile_s0 + n] = symtile[sym_addr(n)];
+                for (uint32_t n = tid; n < tile_syms; n += 512) p.syms_out[tile_s0 + n] = symtile[sym_addr(n)];
             }
         } else {
-            // ---- inverse quantizer + inverse transform ----
+            // ---- inverse quantizer + inverse transform: a tiled matrix product over the workgroup's pixels ----
+            // The tile of PTW x 32 pixels times CTW x 32 output channels is shared out 2 x 2 per wavefront; the
+            // contraction runs over the coefficients 16 at a time.  The basis (both f16 parts of CTW tiles, 16 bytes
+            // per lane and block, operand order) goes from L2 straight into a ring of three LDS slots two steps
+            // ahead -- once per workgroup and step, for all its pixels; the loads are counted by hand (see
+            // load_to_lds).  The other operand is read from the symbol tile: lane (pixel, h) takes the eight symbols
+            // 16 ks + 8 h .. + 7 of its pixel and turns them into f16 levels with two byte permutes each.
             const int64_t px_tile0 = (int64_t)first_ch * (int64_t)ppc;
-            const int TP = (int)(tile_syms / (uint32_t)C);  // pixels in this tile
-            const int npt = (TP + 31) / 32;
-            const int nptg = (npt + MT - 1) / MT;
-            const int ct0 = blockIdx.y * p.ct_per_group;
-            const int nct_g = (p.ncs - ct0 < p.ct_per_group) ? p.ncs - ct0 : p.ct_per_group;
-            const int nunits = nct_g * nptg;
-            for (int u = wave; u < nunits; u += 4) {
-                const int ct = ct0 + u % nct_g;
-                const int pt0 = (u / nct_g) * MT;
-                floatx16 acc[MT], acl[MT];
+            int TP = (int)(tile_syms / (uint32_t)C);  // pixels in this tile
+            if (TP > PTW * 32) TP = PTW * 32;         // (a stream with other chunk geometry than the grid assumed)
+            const int n_cg = (p.ncs + CTW - 1) / CTW;
+            const int ctp = wave & 3;   // this wavefront's pair of channel tiles ...
+            const int ptp = wave >> 2;  // ... and its PPW pixel tiles
+            constexpr int BPW = CTW * 2 / 8;  // basis blocks a wavefront brings per step
+            for (int cg = blockIdx.y; cg < n_cg; cg += gridDim.y) {
+                const int ct_base = cg * CTW;
+                floatx16 acc[2][PPW], acl[2][PPW];
 #pragma unroll
-                for (int m = 0; m < MT; m++)
+                for (int a = 0; a < 2; a++)
 #pragma unroll
-                    for (int r = 0; r < 16; r++) { acc[m][r] = 0.f; acl[m][r] = 0.f; }
-                uint32_t rowbase[MT];
+                    for (int b = 0; b < PPW; b++)
 #pragma unroll
-                for (int m = 0; m < MT; m++) {
-                    int pxl = (pt0 + m) * 32 + l32;
+                        for (int r = 0; r < 16; r++) { acc[a][b][r] = 0.f; acl[a][b][r] = 0.f; }
+                uint32_t rowbase[PPW];
+#pragma unroll
+                for (int b = 0; b < PPW; b++) {
+                    int pxl = (PPW * ptp + b) * 32 + l32;
                     if (pxl > TP - 1) pxl = TP - 1;  // rows past the tile repeat the last pixel; never stored
-                    rowbase[m] = (uint32_t)pxl * (uint32_t)C + 8u * half;
+                    if (pxl < 0) pxl = 0;
+                    rowbase[b] = (uint32_t)pxl * (uint32_t)C + 8u * half;
                 }
-                // (ct, ks): the 64 lanes' hi parts, then their lo parts, 16 bytes per lane each; the basis comes from
-                // L2, one step ahead of its use
-                const uint4* bsrc = reinterpret_cast<const uint4*>(p.Bp16) + (size_t)ct * NJ * 2 * 64 + lane;
-                uint4 bh4 = bsrc[0], bl4 = bsrc[64];
-                for (int ks = 0; ks < NJ; ks++) {
-                    uint4 nh4 = bh4, nl4 = bl4;
-                    if (ks + 1 < NJ) {
-                        nh4 = bsrc[(size_t)(2 * ks + 2) * 64];
-                        nl4 = bsrc[(size_t)(2 * ks + 3) * 64];
-                    }
-                    const halfx8 bh = __builtin_bit_cast(halfx8, bh4), bl = __builtin_bit_cast(halfx8, bl4);
+                // steps past the end repeat the last one: the number of loads in flight is the same in every step
+                auto issue = [&](int ks) {
+                    const int slot = ks % 3;
+                    ks = ks < NJ ? ks : NJ - 1;
 #pragma unroll
-                    for (int m = 0; m < MT; m++) {
-                        // the eight symbols 16 ks + 8*half .. + 7 of this lane's pixel (coefficients past C meet zero
-                        // basis entries; whatever level the tile's bytes give there does not count)
-                        const uint32_t n = rowbase[m] + 16u * (uint32_t)ks;
+                    for (int q = 0; q < BPW; q++) {
+                        const int blk = wave * BPW + q;  // (channel tile blk / 2, part blk % 2)
+                        int ct = ct_base + (blk >> 1);
+                        ct = ct < p.ncs ? ct : p.ncs - 1;  // tiles past the end repeat the last; never stored
+                        load_to_lds<16>(reinterpret_cast<const uint4*>(p.Bp16) + (((size_t)ct * NJ + ks) * 2 + (blk & 1)) * 64 + lane,
+                                        &s_ring[slot][blk][0]);
+                    }
+                };
+                issue(0);
+                issue(1);
+                for (int ks = 0; ks < NJ; ks++) {
+                    wait_loads<BPW>();  // this wavefront's blocks of step ks have landed
+                    __syncthreads();    // everybody's have, and everybody is done with the slot of step ks - 1
+                    issue(ks + 2);
+                    halfx8 bh[2], bl[2], q[PPW];
+#pragma unroll
+                    for (int a = 0; a < 2; a++) {
+                        bh[a] = __builtin_bit_cast(halfx8, s_ring[ks % 3][(2 * ctp + a) * 2][lane]);
+                        bl[a] = __builtin_bit_cast(halfx8, s_ring[ks % 3][(2 * ctp + a) * 2 + 1][lane]);
+                    }
+#pragma unroll
+                    for (int b = 0; b < PPW; b++) {
+                        // (coefficients past C meet zero basis entries; whatever level the tile's bytes give there
+                        // does not count)
+                        const uint32_t n = rowbase[b] + 16u * (uint32_t)ks;
                         uint32_t w0, w1;
                         if constexpr (ALIGNED4) {
                             w0 = *reinterpret_cast<const uint32_t*>(symtile + sym_addr(n));
@@ -543,72 +621,33 @@ __global__ __launch_bounds__(256) void k_decode_tiles(DecodeParams p) {
                         const halfx2 q23 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w0, 0x07030602u)) - level_off2;
                         const halfx2 q45 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w1, 0x05010400u)) - level_off2;
                         const halfx2 q67 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w1, 0x07030602u)) - level_off2;
-                        const halfx8 q = {q01[0], q01[1], q23[0], q23[1], q45[0], q45[1], q67[0], q67[1]};
-                        if constexpr (LAYOUT == FMTC_NHWC) {
-                            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q, bh, acc[m], 0, 0, 0);
-                            acl[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q, bl, acl[m], 0, 0, 0);
-                        } else {
-                            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, q, acc[m], 0, 0, 0);
-                            acl[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q, acl[m], 0, 0, 0);
-                        }
+                        q[b] = halfx8{q01[0], q01[1], q23[0], q23[1], q45[0], q45[1], q67[0], q67[1]};
                     }
-                    bh4 = nh4;
-                    bl4 = nl4;
+#pragma unroll
+                    for (int a = 0; a < 2; a++)
+#pragma unroll
+                        for (int b = 0; b < PPW; b++) {
+                            if constexpr (LAYOUT == FMTC_NHWC) {
+                                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[b], bh[a], acc[a][b], 0, 0, 0);
+                                acl[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[b], bl[a], acl[a][b], 0, 0, 0);
+                            } else {
+                                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh[a], q[b], acc[a][b], 0, 0, 0);
+                                acl[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl[a], q[b], acl[a][b], 0, 0, 0);
+                            }
+                        }
                 }
-                // x_hat = Delta (sum q T_hi + 2^-11 sum q T_lo) + mu
-#pragma unroll
-                for (int m = 0; m < MT; m++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) acc[m][r] = __builtin_fmaf(acl[m][r], 1.f / 2048.f, acc[m][r]) * delta;
+                wait_loads<0>();  // the repeated loads of the last steps
+                __syncthreads();  // nobody reads the ring any more: the next channel group may refill it
 
-                // accumulator r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of the 32x32 tile.
-                // Whole 32-pixel tiles are stored without per-element predicates (one straight run of stores).
-                if constexpr (LAYOUT == FMTC_NHWC) {
-                    const int c = ct * 32 + l32;
-                    if (c < C) {
-                        const float m_c = p.mu[c];
 #pragma unroll
-                        for (int m = 0; m < MT; m++) {
-                            const int px_first = (pt0 + m) * 32;
-                            float* dst = p.xhat + (px_tile0 + px_first + 4 * half) * C + c;
-                            if (px_first + 32 <= TP) {
+                for (int a = 0; a < 2; a++) {
+                    const int ct = ct_base + 2 * ctp + a;
+                    if (ct >= p.ncs) continue;  // wavefront-uniform
 #pragma unroll
-                                for (int r = 0; r < 16; r++) dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = acc[m][r] + m_c;
-                            } else {
-#pragma unroll
-                                for (int r = 0; r < 16; r++) {
-                                    int pxl = px_first + 8 * (r >> 2) + 4 * half + (r & 3);
-                                    if (pxl < TP) dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = acc[m][r] + m_c;
-                                }
-                            }
-                        }
-                    }
-                } else {
-                    float m_r[16];
-                    const int cb = ct * 32 + 4 * half;
-#pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        int c = cb + 8 * (r >> 2) + (r & 3);
-                        m_r[r] = p.mu[c];  // mu is padded to a multiple of 32
-                    }
-#pragma unroll
-                    for (int m = 0; m < MT; m++) {
-                        int pxl = (pt0 + m) * 32 + l32;
-                        if (pxl < TP) {
-                            int64_t px = px_tile0 + pxl;
-                            int64_t n = px / p.HW, hw = px - n * p.HW;
-                            float* dst = p.xhat + (n * (int64_t)C + cb) * p.HW + hw;
-                            if (ct * 32 + 32 <= C) {
-#pragma unroll
-                                for (int r = 0; r < 16; r++) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * p.HW] = acc[m][r] + m_r[r];
-                            } else {
-#pragma unroll
-                                for (int r = 0; r < 16; r++) {
-                                    int c = cb + 8 * (r >> 2) + (r & 3);
-                                    if (c < C) dst[(int64_t)(8 * (r >> 2) + (r & 3)) * p.HW] = acc[m][r] + m_r[r];
-                                }
-                            }
-                        }
+                    for (int b = 0; b < PPW; b++) {
+                        const int pt = PPW * ptp + b;
+                        if (pt * 32 >= TP) continue;  // wavefront-uniform
+                        store_tile(ct, pt, TP, px_tile0, acc[a][b], acl[a][b]);
                     }
                 }
             }
@@ -920,20 +959,30 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     }
 
     // ---- tiles of several chunks per workgroup ----
-    // enough chunks for at least 64 pixels at the nominal chunk size, 4..16 chunks
-    int G = (int)((64 * (int64_t)C + 4095) / 4096);
-    G = G < 4 ? 4 : (G > 16 ? 16 : (G + 3) / 4 * 4);
+    // A workgroup tile is 128 pixels x 256 output channels (4 x 8 matrix tiles), or 64 x 256 for more than 512
+    // channels (the symbols of 128 such pixels would not fit LDS): as many chunks as give that many pixels at the
+    // nominal chunk size, 16 at most.
+    const int n_cg = (ncs + 7) / 8;
+    auto chunks_for = [&](int px) {
+        int n = (int)(px / (int64_t)g.px_per_chunk);
+        return n < 1 ? 1 : (n > 16 ? 16 : n);
+    };
+    // ... and 64 pixels also where 128 would leave most of the device without a workgroup
+    const bool wide = C > 512 || (uint64_t)((g.n_chunks + chunks_for(128) - 1) / chunks_for(128)) * n_cg < 128;
+    int G = chunks_for(wide ? 64 : 128);
+    if (d_syms) G = 8;  // symbols only: no projection to feed, one chunk per wavefront and as many workgroups as that gives
     p.G = G;
     // the grid is sized from the nominal geometry; the kernel takes the real one from the header
     const uint32_t n_tiles = (g.n_chunks + G - 1) / G;
+    // the channel groups (256 channels) of a tile go to workgroups of their own (each decodes the tile's
+    // symbols again) while that still fills the device; otherwise a workgroup walks them in turn
     int groups = 1;
     if (!d_syms) {
-        groups = (int)((256 + n_tiles - 1) / n_tiles);
-        if (groups > ncs) groups = ncs;
+        groups = (int)(1024 / (n_tiles < 1024u ? n_tiles : 1024u));
+        if (groups > n_cg) groups = n_cg;
         if (groups < 1) groups = 1;
     }
-    p.ct_per_group = (ncs + groups - 1) / groups;
-    groups = (ncs + p.ct_per_group - 1) / p.ct_per_group;
+    p.ct_per_group = 0;  // (unused by the tiled kernel)
     unsigned gx = n_tiles < 1024u ? n_tiles : 1024u;
     dim3 grid(gx, (unsigned)groups);
     const size_t lds = (size_t)G * 4096 + (size_t)G * 4096 / 16 + 128;
@@ -945,9 +994,8 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);      \
             if (ea != hipSuccess) return ea;                                                                 \
         }                                                                                                    \
-        el = launch(K_DECODE, k_decode_tiles<MT, LAY, AL>, grid, dim3(256), lds, s, p);                      \
+        el = launch(K_DECODE, k_decode_tiles<MT, LAY, AL>, grid, dim3(512), lds, s, p);                      \
     } while (0)
-    const bool wide = C > 256;  // fewer pixels per tile: 2 pixel tiles per wavefront unit instead of 4
     if (layout == FMTC_NHWC) {
         if (al) { if (wide) FMTC_DEC(2, FMTC_NHWC, true); else FMTC_DEC(4, FMTC_NHWC, true); }
         else    { if (wide) FMTC_DEC(2, FMTC_NHWC, false); else FMTC_DEC(4, FMTC_NHWC, false); }

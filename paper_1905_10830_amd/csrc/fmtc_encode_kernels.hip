@@ -1051,30 +1051,6 @@ struct GemmParams {
 
 constexpr int kGemmFix = 64;  // values per wavefront waiting for their exact decision
 
-// One wavefront's 64 x 16 (or 64 x 4) bytes from global memory straight into LDS, lane l to lds_base + 16 l
-// (4 l).  Written as assembly because the compiler, which cannot tell the LDS stages apart, would hold every
-// later LDS read until all transfers it knows of have landed -- the full latency, in every step; the kernel
-// counts its loads in flight itself (s_waitcnt vmcnt, then a barrier) before it reads a stage.
-typedef __attribute__((address_space(3))) void lds_void_t;
-template <int BYTES>
-__device__ __forceinline__ void load_to_lds(const void* src, void* lds_base) {
-    const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(lds_void_t*)lds_base);
-    uint32_t keep;
-    if constexpr (BYTES == 16)
-        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
-                     : "=&s"(keep) : "v"(src), "s"(base) : "memory");
-    else
-        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %1, off\n\ts_mov_b32 m0, %0"
-                     : "=&s"(keep) : "v"(src), "s"(base) : "memory");
-}
-
-// Wait until at most N of this wavefront's loads are in flight (they complete in order); no memory access
-// moves across it.
-template <int N>
-__device__ __forceinline__ void wait_loads() {
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
 template <int LAYOUT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_project_quantize_gemm(GemmParams p) {
     __shared__ __align__(16) uint4 stageA[3][8][64];     // per 16-channel step: (coefficient tile, part), operand order
