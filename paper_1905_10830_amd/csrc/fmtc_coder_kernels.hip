@@ -601,9 +601,8 @@ hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, floa
                         int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
                         uint64_t* d_out_bytes, hipStream_t s) {
     PackParams p = pack_params(d_syms, g, bits, delta, cs, n_parts, d_enc_table, d_stream, cap_words, d_out_bytes);
-    static const char* knob = getenv("FMTC_TABLE_IN_PACK");
     // every pack workgroup sums the partial histograms itself while that is at most 64 KB to read
-    const bool build_in_pack = knob ? (knob[0] == '1') : ((size_t)n_parts << bits) * 4 <= 64 * 1024;
+    const bool build_in_pack = ((size_t)n_parts << bits) * 4 <= 64 * 1024;
     if (!build_in_pack) {
         hipError_t e = launch(K_TABLE, k_huffman_table, dim3(1), dim3(1024), 0, s, (const uint32_t*)cs.hist_parts,
                               n_parts, bits, (uint32_t*)nullptr, d_enc_table, d_stream + kHeaderBytes, cs.ctrl, 0u);

@@ -118,3 +118,30 @@ def test_damaged_streams_through_the_fused_decoder(fmtc, oracle):
         idx = rng.integers(max(pay0, 320), len(good), size=16)
         bad[idx] = rng.integers(0, 256, size=16, dtype=np.uint8)
         flag(bad)
+
+
+@pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("C", [320, 960])
+def test_wide_decoder_walking_its_channel_groups(fmtc, oracle, C, layout, monkeypatch):
+    """More than 256 channels: a tile's channel groups normally go to workgroups of their own; with more tiles than
+    the device holds at once one workgroup walks them in turn.  That second way is forced here on a small tensor
+    and must give the same tensor, to the bit, as the first."""
+    s = synth.FeatureMapStream(C, 9, 11, max(8, C // 8), "relu", 1200 + C)
+    x = synth.to_layout(s.images(3), layout)
+    mean, cov = oracle.covariance(x, layout)
+    w, v = np.linalg.eigh(cov)
+    T = np.ascontiguousarray(v[:, ::-1].T).astype(np.float32)
+    mu = mean.astype(np.float32)
+    A = np.float32(np.abs(oracle.project(x, T, mu, layout)[:, 0]).max())
+    basis = fmtc.basis_import(T, mu, A)
+    x_d = torch.from_numpy(x).cuda()
+    stream, nbytes = fmtc.encode(basis, x_d, 5, layout)
+    a, ea = fmtc.decode(basis, stream, x.shape, 5, layout)
+    torch.cuda.synchronize()
+    monkeypatch.setenv("FMTC_DECODE_ONE_ROW", "1")
+    b, eb = fmtc.decode(basis, stream, x.shape, 5, layout)
+    torch.cuda.synchronize()
+    assert int(ea.item()) == 0 and int(eb.item()) == 0 and torch.equal(a, b)
+    sym, d, _ = oracle.unpack(stream[: int(nbytes.item())].cpu().numpy(), x.size // C, C, 5)
+    ref = oracle.reconstruct(sym, x.shape, T, mu, d, 5, layout)
+    assert np.abs(b.cpu().numpy().astype(np.float64) - ref).max() <= 1e-4
