@@ -28,31 +28,14 @@ constexpr uint32_t kInf = 0xffffffffu;
 // ---------------------------------------------------------------------------
 struct TableLds {
     __attribute__((aligned(16))) uint32_t h[256];
-    uint32_t weight[256];       // leaf weights in (count, symbol) order
+    uint32_t weight[260];       // leaf weights in (count, symbol) order (4 spare entries: reads just past the end)
     uint32_t children[256];     // per merge: node ids of the two children (leaf i: i, internal j: 256 + j)
     uint16_t leaf_parent[256];  // merge that consumed each sorted leaf
     uint16_t int_parent[256];   // ... each internal node (numbered in creation order); then its 2^r-th ancestor
     uint16_t depth[256];        // of the internal nodes
     uint8_t len_sorted[256];    // code length of the sorted leaves
-    uint32_t rank[256];         // position of every used symbol in (count, symbol) order
+    uint32_t rank[260];         // position of every used symbol in (count, symbol) order; reused by the serial merge
 };
-
-// one value of a per-lane array spread over NV registers (64 entries each); idx is wavefront-uniform
-template <int NV>
-__device__ __forceinline__ uint32_t lane_get(const uint32_t (&v)[NV], int idx) {
-    uint32_t r = (uint32_t)__builtin_amdgcn_readlane((int)v[0], idx & 63);
-#pragma unroll
-    for (int j = 1; j < NV; j++) {
-        uint32_t t = (uint32_t)__builtin_amdgcn_readlane((int)v[j], idx & 63);
-        r = ((idx >> 6) == j) ? t : r;
-    }
-    return r;
-}
-template <int NV>
-__device__ __forceinline__ void lane_put(uint32_t (&v)[NV], int lane, int idx, uint32_t val) {
-#pragma unroll
-    for (int j = 0; j < NV; j++) v[j] = (64 * j + lane == idx) ? val : v[j];
-}
 
 // LDS traffic of one wavefront completes in order; this keeps the compiler from moving it across the point
 __device__ __forceinline__ void wave_sync() {
@@ -60,40 +43,39 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
-// The merge loop is serial by nature (n-1 steps).  It runs in one wavefront with the two queues held in
-// registers across the lanes and all control in scalar registers, without branches: queue slots that hold
-// nothing (leaves past n, nodes not made yet) weigh "infinity", which no node that can still be picked does
-// (V < 2^32), and 64 * NV >= n + 2 keeps every index read inside the registers.
-template <int NV>
-__device__ __forceinline__ void huffman_merge(TableLds& L, int lane, int n) {
-    uint32_t lw[NV], iw[NV], ch[NV];
-#pragma unroll
-    for (int j = 0; j < NV; j++) {
-        lw[j] = (64 * j + lane < n) ? L.weight[64 * j + lane] : kInf;
-        iw[j] = kInf;
-        ch[j] = 0;
+// The merge loop is serial by nature (n - 1 steps).
+// More than 64 used symbols: the queues in LDS and the whole loop in ONE lane.  A step is four LDS reads in flight
+// together, a dozen dependent operations and two LDS writes; spreading the queues over the lanes' registers
+// instead costs four cross-lane reads per queue entry and, measured, several times as long per step.
+// Internal node weights go where the ranks were (the caller holds those in registers by now).
+__device__ __forceinline__ void huffman_merge_serial(TableLds& L, int lane, int n) {
+    uint32_t* iw = L.rank;
+    for (int i = lane; i < 260; i += 64) {
+        iw[i] = kInf;
+        if (i >= n) L.weight[i] = kInf;
     }
-    int nl = 0, ni = 0;
-    for (int made = 0; made < n - 1; made++) {
-        const uint32_t l0 = lane_get<NV>(lw, nl), l1 = lane_get<NV>(lw, nl + 1);
-        const uint32_t i0 = lane_get<NV>(iw, ni), i1 = lane_get<NV>(iw, ni + 1);
-        // first pick: a leaf wins over an internal node of equal weight
-        const bool a_leaf = l0 <= i0;
-        const uint32_t wa = a_leaf ? l0 : i0;
-        const uint32_t ida = a_leaf ? (uint32_t)nl : 256u + (uint32_t)ni;
-        const uint32_t ln = a_leaf ? l1 : l0, in = a_leaf ? i0 : i1;
-        const int nl1 = nl + (a_leaf ? 1 : 0), ni1 = ni + (a_leaf ? 0 : 1);
-        const bool b_leaf = ln <= in;
-        const uint32_t wb = b_leaf ? ln : in;
-        const uint32_t idb = b_leaf ? (uint32_t)nl1 : 256u + (uint32_t)ni1;
-        nl = nl1 + (b_leaf ? 1 : 0);
-        ni = ni1 + (b_leaf ? 0 : 1);
-        lane_put<NV>(iw, lane, made, wa + wb);
-        lane_put<NV>(ch, lane, made, ida | (idb << 16));
+    wave_sync();
+    if (lane == 0) {
+        int nl = 0, ni = 0;
+        for (int made = 0; made < n - 1; made++) {
+            // a queue that has run out shows "infinity" (the arrays have spare entries behind index 255)
+            const uint32_t l0 = L.weight[nl], l1 = L.weight[nl + 1];
+            const uint32_t i0 = iw[ni], i1 = iw[ni + 1];
+            const bool a_leaf = l0 <= i0;  // first pick: a leaf wins over an internal node of equal weight
+            const uint32_t wa = a_leaf ? l0 : i0;
+            const uint32_t ida = a_leaf ? (uint32_t)nl : 256u + (uint32_t)ni;
+            const uint32_t ln = a_leaf ? l1 : l0, in = a_leaf ? i0 : i1;
+            const int nl1 = nl + (a_leaf ? 1 : 0), ni1 = ni + (a_leaf ? 0 : 1);
+            const bool b_leaf = ln <= in;
+            const uint32_t wb = b_leaf ? ln : in;
+            const uint32_t idb = b_leaf ? (uint32_t)nl1 : 256u + (uint32_t)ni1;
+            nl = nl1 + (b_leaf ? 1 : 0);
+            ni = ni1 + (b_leaf ? 0 : 1);
+            iw[made] = wa + wb;
+            L.children[made] = ida | (idb << 16);
+        }
     }
-#pragma unroll
-    for (int j = 0; j < NV; j++)
-        if (64 * j + lane < 256) L.children[64 * j + lane] = ch[j];
+    wave_sync();
 }
 
 // The same loop for at most 64 used symbols (one register per queue), written out by hand: the compiler's
@@ -218,6 +200,7 @@ __device__ __forceinline__ void rank_symbols(TableLds& L, int bits) {
     for (int s = lane; s < K; s += 64) {
         const uint32_t cnt = L.h[s];
         uint32_t r = 0;
+#pragma unroll 16  // the reads of many steps in flight together: a step is one LDS round trip otherwise
         for (int t = t0; t < t1; t++) {
             const uint32_t o = L.h[t];  // same address in all lanes: a broadcast
             r += (o != 0 && (o < cnt || (o == cnt && t < s))) ? 1u : 0u;
@@ -297,9 +280,7 @@ __device__ __forceinline__ void table_from_hist(TableLds& L, int lane, int K, Ta
     wave_sync();
     if (n >= 2) {
         if (n <= 64) huffman_merge_small(L, lane, n);
-        else if (n <= 126) huffman_merge<2>(L, lane, n);
-        else if (n <= 254) huffman_merge<4>(L, lane, n);
-        else huffman_merge<5>(L, lane, n);
+        else huffman_merge_serial(L, lane, n);
         wave_sync();
         const int root = n - 2;
         for (int m = lane; m < n - 1; m += 64) {
