@@ -195,6 +195,24 @@ def main():
               "note": "projection, quantizer and packing as one kernel for 32/64/128 channels and at most 4 chunks per compute unit, else two kernels without histogram and table"}
     xh2, err2 = fmtc.decode(basis, sstreams[0], xs.shape, bits, layout)
     assert int(err2.item()) == 0 and torch.equal(xh2, sets[0]["xhat"]), "the two encoders disagree on the symbols"
+    # ... and the decoder with ready-made tables, and the two together as a step
+    sda = [(basis._h, table._h, st.data_ptr(), scap, s["xhat"].data_ptr(), N, C, H, W, layout, s["err"].data_ptr(),
+            stream_h) for s, st in zip(sets, sstreams)]
+    run(lambda i: lib.fmtc_encode_static(*sa[i % R]) | lib.fmtc_decode_static(*sda[i % R]), args.warmup)
+    dt_sstep = run(lambda i: lib.fmtc_encode_static(*sa[i % R]) | lib.fmtc_decode_static(*sda[i % R]), args.steps)
+    dt_sdec = run(lambda i: lib.fmtc_decode_static(*sda[i % R]), args.steps)
+    fmtc.profile_enable(args.steps)
+    run(lambda i: lib.fmtc_decode_static(*sda[i % R]), args.steps)
+    sdprof = fmtc.profile_read()
+    fmtc.profile_enable(0)
+    for s in sets:
+        assert int(s["err"].item()) == 0, "decoder flagged its own stream"
+    assert torch.equal(sets[0]["xhat"], xh2), "the decoder with ready-made tables differs"
+    static["decode_GBps"] = round(in_bytes / (dt_sdec / args.steps) / 1e9, 3)
+    static["us_per_decode"] = round(1e6 * dt_sdec / args.steps, 2)
+    static["decode_kernel_us"] = round(1e3 * sdprof["k_decode"][0], 3)
+    static["encode_decode_GBps"] = round(in_bytes / (dt_sstep / args.steps) / 1e9, 3)
+    static["us_per_step"] = round(1e6 * dt_sstep / args.steps, 2)
 
     # ---- yardstick for the memory counters: one plain copy of known size (not timed) ----
     ysrc = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
@@ -245,7 +263,7 @@ def main():
         "mse": mse,
         "roofline": roofline,
         "kernels": kernels,
-        "static_table_encoder": static,
+        "static_table_codec": static,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -171,6 +171,15 @@ fmtc_status fmtc_encode_static(const fmtc_basis *basis, const fmtc_table *table,
                                int H, int W, fmtc_layout layout, int chunk_syms, void *d_stream_out, size_t cap,
                                uint64_t *d_out_bytes, void *d_workspace, size_t ws_bytes, void *hip_stream);
 
+/* Decoder for streams written with `table` (fmtc_encode_static, or any stream
+ * that carries exactly its code lengths): as fmtc_decode, but the decode
+ * tables come ready-made from the handle instead of being built by every
+ * workgroup from the stream.  A stream with other code lengths sets
+ * FMTC_ERR_TABLE; every other check of fmtc_decode still applies. */
+fmtc_status fmtc_decode_static(const fmtc_basis *basis, const fmtc_table *table, const void *d_stream_in, size_t bytes,
+                               float *d_xhat, int64_t N, int C, int H, int W, fmtc_layout layout,
+                               uint32_t *d_err_flag, void *hip_stream);
+
 /* ---- staged entry points (the same kernels, cut at the symbol boundary) ---- */
 /* Transform + quantizer + histogram only (section 3: y = T(x-mu), Q_Delta).
  * d_syms: P*C bytes; d_hist: 256 u32 counts (may be NULL). */

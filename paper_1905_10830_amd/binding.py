@@ -20,7 +20,7 @@ EXPORTS = [
     "fmtc_delta", "fmtc_encode_bound", "fmtc_workspace_size", "fmtc_encode", "fmtc_decode", "fmtc_quantize",
     "fmtc_code_symbols", "fmtc_decode_symbols", "fmtc_stream_info", "fmtc_last_error",
     "fmtc_fit_table", "fmtc_table_import", "fmtc_table_export", "fmtc_table_destroy", "fmtc_encode_static_bound",
-    "fmtc_encode_static",
+    "fmtc_encode_static", "fmtc_decode_static",
     "fmtc_profile_enable", "fmtc_profile_kernels", "fmtc_profile_name", "fmtc_profile_read", "fmtc_profile_copy",
 ]
 
@@ -66,6 +66,7 @@ def load_library():
     lib.fmtc_encode_static_bound.argtypes = [vp, i64, i32, i32]
     lib.fmtc_encode_static_bound.restype = sz
     lib.fmtc_encode_static.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp, vp, sz, vp]
+    lib.fmtc_decode_static.argtypes = [vp, vp, vp, sz, vp, i64, i32, i32, i32, i32, vp, vp]
     lib.fmtc_quantize.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.fmtc_code_symbols.argtypes = [vp, i64, i32, i32, i32, f32, vp, sz, vp, vp, sz, vp]
     lib.fmtc_decode_symbols.argtypes = [vp, sz, i64, i32, i32, vp, vp, vp]
@@ -272,6 +273,22 @@ def encode_static(basis, table, x, layout=NHWC, chunk_syms=4096, stream_out=None
                                              _dev(out_bytes, torch.int64), _dev(workspace, torch.uint8),
                                              workspace.numel(), _stream()))
     return stream_out, out_bytes
+
+
+def decode_static(basis, table, stream_in, shape, layout=NHWC, xhat=None, err_flag=None, nbytes=None):
+    """Asynchronous.  -> (xhat fp32 tensor of `shape`, err_flag int32[1] device tensor)."""
+    import torch
+
+    if xhat is None:
+        xhat = torch.empty(shape, dtype=torch.float32, device=stream_in.device)
+    if err_flag is None:
+        err_flag = torch.zeros(1, dtype=torch.int32, device=stream_in.device)
+    n, c, h, w = _dims(xhat, layout)
+    _check(load_library().fmtc_decode_static(basis._h, table._h, _dev(stream_in, torch.uint8),
+                                             stream_in.numel() if nbytes is None else nbytes,
+                                             _dev(xhat, torch.float32), n, c, h, w, layout,
+                                             _dev(err_flag, torch.int32), _stream()))
+    return xhat, err_flag
 
 
 def decode(basis, stream_in, shape, bits, layout=NHWC, xhat=None, err_flag=None, nbytes=None):

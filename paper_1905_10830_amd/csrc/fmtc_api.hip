@@ -26,6 +26,7 @@ struct fmtc_table {
     uint32_t max_len = 0;
     uint8_t lengths[256] = {0};
     uint64_t* d_enc_table = nullptr;  // [256]: bit-reversed code | length << 56
+    void* d_dec_tables = nullptr;     // the decoder's tables for this code, made once
     int device = 0;
 };
 
@@ -434,9 +435,32 @@ static bool lengths_complete(const uint8_t* len, int bits, uint32_t* max_len) {
     return sum == (1ull << kMaxLen);
 }
 
+// The decoder's tables for the handle's code lengths (t->lengths), on the given stream; synchronises it.
+static fmtc_status make_decode_tables(fmtc_table* t, hipStream_t s) {
+    uint8_t* d_len = nullptr;
+    uint32_t* d_ok = nullptr;
+    uint32_t ok = 0;
+    hipError_t e;
+    if ((e = hipMalloc(&t->d_dec_tables, prebuilt_decode_tables_bytes())) != hipSuccess ||
+        (e = hipMalloc((void**)&d_len, 256)) != hipSuccess || (e = hipMalloc((void**)&d_ok, 4)) != hipSuccess) {
+        if (d_len) (void)hipFree(d_len);
+        return fail(FMTC_ENOMEM, "hipMalloc decode tables: %s", hipGetErrorString(e));
+    }
+    if ((e = hipMemcpyAsync(d_len, t->lengths, 256, hipMemcpyHostToDevice, s)) == hipSuccess &&
+        (e = launch_build_decode_tables(d_len, t->bits, t->d_dec_tables, d_ok, s)) == hipSuccess &&
+        (e = hipMemcpyAsync(&ok, d_ok, 4, hipMemcpyDeviceToHost, s)) == hipSuccess)
+        e = hipStreamSynchronize(s);
+    (void)hipFree(d_len);
+    (void)hipFree(d_ok);
+    if (e != hipSuccess) return hip_fail(e, "decode table build");
+    if (!ok) return fail(FMTC_EHIP, "decode tables rejected the code lengths");
+    return FMTC_OK;
+}
+
 void fmtc_table_destroy(fmtc_table* t) {
     if (!t) return;
     if (t->d_enc_table) (void)hipFree(t->d_enc_table);
+    if (t->d_dec_tables) (void)hipFree(t->d_dec_tables);
     delete t;
 }
 
@@ -464,6 +488,11 @@ fmtc_status fmtc_table_import(const uint8_t* h_lengths, int bits, fmtc_table** o
     if (e != hipSuccess) {
         fmtc_table_destroy(t);
         return hip_fail(e, "table upload");
+    }
+    const fmtc_status st = make_decode_tables(t, nullptr);
+    if (st != FMTC_OK) {
+        fmtc_table_destroy(t);
+        return st;
     }
     *out = t;
     return FMTC_OK;
@@ -514,6 +543,11 @@ fmtc_status fmtc_fit_table(const fmtc_basis* basis, const float* d_x, int64_t N,
     if (!lengths_complete(t->lengths, bits, &t->max_len)) {
         fmtc_table_destroy(t);
         return fail(FMTC_EHIP, "table fit produced an incomplete code");
+    }
+    st = make_decode_tables(t, s);
+    if (st != FMTC_OK) {
+        fmtc_table_destroy(t);
+        return st;
     }
     *out = t;
     return FMTC_OK;
@@ -602,7 +636,7 @@ fmtc_status fmtc_code_symbols(const uint8_t* d_syms, int64_t P, int C, int bits,
 
 static fmtc_status decode_common(const fmtc_basis* basis, const void* d_stream_in, size_t bytes, int64_t P, int C,
                                  int64_t HW, int layout, int bits, float* d_xhat, uint8_t* d_syms,
-                                 uint32_t* d_err_flag, void* hip_stream) {
+                                 uint32_t* d_err_flag, void* hip_stream, const void* d_prebuilt = nullptr) {
     if (!d_stream_in || !d_err_flag) return fail(FMTC_EINVAL, "NULL argument");
     if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
     if (!aligned(d_stream_in, 16) || !aligned(d_err_flag, 4) || !aligned(d_xhat, 16) || !aligned(d_syms, 16))
@@ -615,7 +649,7 @@ static fmtc_status decode_common(const fmtc_basis* basis, const void* d_stream_i
     BasisDevice view;
     if (basis) view = device_view(basis);
     if ((e = launch_decode(basis ? &view : nullptr, static_cast<const uint8_t*>(d_stream_in), bytes, g, bits, HW,
-                           layout, d_xhat, d_syms, d_err_flag, s)) != hipSuccess)
+                           layout, d_xhat, d_syms, d_err_flag, d_prebuilt, s)) != hipSuccess)
         return hip_fail(e, "decode kernel");
     return FMTC_OK;
 }
@@ -627,6 +661,17 @@ fmtc_status fmtc_decode(const fmtc_basis* basis, const void* d_stream_in, size_t
     if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
     const int64_t HW = (int64_t)H * W;
     return decode_common(basis, d_stream_in, bytes, N * HW, C, HW, layout, bits, d_xhat, nullptr, d_err_flag, hip_stream);
+}
+
+fmtc_status fmtc_decode_static(const fmtc_basis* basis, const fmtc_table* table, const void* d_stream_in, size_t bytes,
+                               float* d_xhat, int64_t N, int C, int H, int W, fmtc_layout layout,
+                               uint32_t* d_err_flag, void* hip_stream) {
+    if (!basis || !table || !d_xhat) return fail(FMTC_EINVAL, "NULL argument");
+    if (!dims_ok(N, C, H, W) || basis->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", basis->C, C);
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    const int64_t HW = (int64_t)H * W;
+    return decode_common(basis, d_stream_in, bytes, N * HW, C, HW, layout, table->bits, d_xhat, nullptr, d_err_flag,
+                         hip_stream, table->d_dec_tables);
 }
 
 fmtc_status fmtc_decode_symbols(const void* d_stream_in, size_t bytes, int64_t P, int C, int bits, uint8_t* d_syms,

@@ -166,6 +166,46 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
     return true;
 }
 
+// Decode tables made once for a code table that is fixed beforehand, in global memory: what build_decode_tables
+// leaves in LDS, and the code lengths they were made from.
+struct PrebuiltTables {
+    DecTables T;
+    uint8_t len[256];
+};
+static_assert(sizeof(DecTables) % 16 == 0, "copied 16 bytes at a time");
+
+// The prebuilt tables into LDS in place of building them -- after checking that the stream carries the very
+// lengths they were made from (my_len: the stream's length of symbol threadIdx.x, threads past 255: anything).
+// All THREADS threads call it; returns false for every thread on a mismatch.
+template <int THREADS>
+__device__ __forceinline__ bool load_decode_tables(DecTables& T, int my_len, const PrebuiltTables* pre) {
+    const int tid = threadIdx.x;
+    const uint4* src = reinterpret_cast<const uint4*>(&pre->T);
+    uint4* dst = reinterpret_cast<uint4*>(&T);
+    for (int i = tid; i < (int)(sizeof(DecTables) / 16); i += THREADS) dst[i] = src[i];
+    const int mismatch = (tid < 256 && my_len != (int)pre->len[tid]) ? 1 : 0;
+    return __syncthreads_or(mismatch) == 0;  // (also the barrier behind the copy)
+}
+
+__global__ __launch_bounds__(256) void k_build_decode_tables(const uint8_t* __restrict__ len_table, int bits,
+                                                             PrebuiltTables* __restrict__ out, uint32_t* __restrict__ ok) {
+    __shared__ __align__(16) DecTables T;
+    const int tid = threadIdx.x;
+    const bool good = build_decode_tables<256>(T, (int)len_table[tid], bits);
+    if (tid == 0) *ok = good ? 1u : 0u;
+    if (!good) return;
+    const uint4* src = reinterpret_cast<const uint4*>(&T);
+    uint4* dst = reinterpret_cast<uint4*>(&out->T);
+    for (int i = tid; i < (int)(sizeof(DecTables) / 16); i += 256) dst[i] = src[i];
+    out->len[tid] = len_table[tid];
+}
+
+hipError_t launch_build_decode_tables(const uint8_t* d_len_table, int bits, void* d_prebuilt, uint32_t* d_ok, hipStream_t s) {
+    return launch(K_TABLE, k_build_decode_tables, dim3(1), dim3(256), 0, s, d_len_table, bits,
+                  static_cast<PrebuiltTables*>(d_prebuilt), d_ok);
+}
+size_t prebuilt_decode_tables_bytes() { return sizeof(PrebuiltTables); }
+
 // Decodes the `cnt` symbols of one run (one lane) starting at bit `start` of a chunk into the symbol tile.
 // STAGED: the chunk's words are in LDS (`pw`, two zero words behind them); otherwise they are read from
 // global memory (`gw`), zero past the chunk's end.  Returns false if bits matched no code word.
@@ -354,6 +394,7 @@ struct DecodeParams {
     // where the side information and the payload start if the stream was made with the nominal chunk size
     size_t g_off_chunk_off, g_off_sub_bits, g_off_payload;
     uint32_t g_n_chunks, g_spc;
+    const void* prebuilt;  // PrebuiltTables of a code table fixed beforehand, or NULL: build them from the stream
 };
 
 // Header checks.  Returns false unless the header matches the arguments and the
@@ -425,7 +466,9 @@ __global__ __launch_bounds__(512) void k_decode_tiles(DecodeParams p) {
         if (tid == 0) atomicOr(p.err, FMTC_ERR_HEADER);
         return;
     }
-    if (!build_decode_tables<512>(T, tid < 256 ? (int)p.stream[kHeaderBytes + tid] : 0, p.bits)) {
+    const int my_len = tid < 256 ? (int)p.stream[kHeaderBytes + tid] : 0;
+    if (!(p.prebuilt ? load_decode_tables<512>(T, my_len, static_cast<const PrebuiltTables*>(p.prebuilt))
+                     : build_decode_tables<512>(T, my_len, p.bits))) {
         if (tid == 0) atomicOr(p.err, FMTC_ERR_TABLE);
         return;
     }
@@ -749,7 +792,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         }
     }
     if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
-    if (!build_decode_tables<THREADS>(T, my_len, p.bits)) {
+    if (!(p.prebuilt ? load_decode_tables<THREADS>(T, my_len, static_cast<const PrebuiltTables*>(p.prebuilt))
+                     : build_decode_tables<THREADS>(T, my_len, p.bits))) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(p.err, FMTC_ERR_TABLE);
         return;
     }
@@ -897,7 +941,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 }
 
 hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
-                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, hipStream_t s) {
+                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, const void* d_prebuilt,
+                         hipStream_t s) {
     const int C = g.C;
     const int ncs = (C + 31) / 32;
     DecodeParams p;
@@ -913,6 +958,7 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     p.xhat = d_xhat;
     p.syms_out = d_syms;
     p.err = d_err;
+    p.prebuilt = d_prebuilt;
     p.G = 1;
     p.ct_per_group = 1;
     p.g_off_chunk_off = g.off_chunk_off;

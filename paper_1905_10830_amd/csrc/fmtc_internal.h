@@ -171,8 +171,13 @@ hipError_t launch_table_from_lengths(const uint8_t* d_len_table, int bits, uint6
 hipError_t launch_table_from_hist(const uint32_t* d_hist_parts, int n_parts, int bits, uint32_t add_each,
                                   uint64_t* d_enc_table, uint8_t* d_len_table, hipStream_t s);
 
+// d_prebuilt: decode tables made beforehand by launch_build_decode_tables (the stream must carry the same code
+// lengths), or NULL: every workgroup builds them from the stream
 hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
-                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, hipStream_t s);
+                         int64_t HW, int layout, float* d_xhat, uint8_t* d_syms, uint32_t* d_err, const void* d_prebuilt,
+                         hipStream_t s);
+hipError_t launch_build_decode_tables(const uint8_t* d_len_table, int bits, void* d_prebuilt, uint32_t* d_ok, hipStream_t s);
+size_t prebuilt_decode_tables_bytes();
 
 hipError_t launch_fit_moments(const float* d_x, int64_t N, int C, int64_t HW, int layout, double* d_sum,
                               double* d_cov, hipStream_t s);

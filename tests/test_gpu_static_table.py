@@ -100,6 +100,10 @@ def test_static_table_encode_matches_oracle(fmtc, oracle, case, layout):
     assert int(err.item()) == 0
     ref_xhat = oracle.reconstruct(sym_gpu, dat.shape, T, mu, d, bits, layout)
     assert np.abs(xhat.cpu().numpy().astype(np.float64) - ref_xhat).max() <= RECON_TOL
+    # ... and the decoder that takes its tables ready-made from the handle gives the same tensor, bit for bit
+    xhat_s, err_s = fmtc.decode_static(basis, table, stream, dat.shape, layout)
+    torch.cuda.synchronize()
+    assert int(err_s.item()) == 0 and torch.equal(xhat_s, xhat)
     # deterministic
     stream2, nbytes2 = fmtc.encode_static(basis, table, dev(dat), layout, chunk_syms=cs)
     torch.cuda.synchronize()
@@ -157,6 +161,34 @@ def test_table_import_export_and_bad_tables(fmtc, oracle):
     with pytest.raises(fmtc.FmtcError) as e:
         fmtc.encode_static(basis, fitted, torch.zeros((1, 4, 4, 16), device="cuda"))
     assert e.value.status == fmtc.EINVAL
+
+
+@pytest.mark.parametrize("case", [CASES[1], CASES[7]], ids=[IDS[1], IDS[7]])
+def test_static_decoder_refuses_a_stream_of_another_table(fmtc, oracle, case):
+    C, H, W, ncal, ndat, rank, act, bits, cs = case
+    cal, dat, T, mu, A = split_case(oracle, case, 813, synth.NHWC)
+    basis = fmtc.basis_import(T, mu, A)
+    table = fmtc.fit_table(basis, dev(cal), bits)
+    ln, _ = table.export()
+    # the tensor's own table differs from the calibration table (at least one length)
+    own, nown = fmtc.encode(basis, dev(dat), bits)
+    torch.cuda.synchronize()
+    own_len = own[64:64 + (1 << bits)].cpu().numpy()
+    assert own_len.tolist() != ln.tolist()
+    xhat, err = fmtc.decode_static(basis, table, own, dat.shape)
+    torch.cuda.synchronize()
+    assert int(err.item()) & fmtc.ERR_TABLE
+    # the general decoder reads it, and a damaged stream of the right table still raises its flag
+    xhat, err = fmtc.decode(basis, own, dat.shape, bits)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    good, ngood = fmtc.encode_static(basis, table, dev(dat))
+    torch.cuda.synchronize()
+    bad = good.clone()
+    bad[320 + 7] = 0xFF  # a chunk offset far past the payload
+    xhat, err = fmtc.decode_static(basis, table, bad, dat.shape)
+    torch.cuda.synchronize()
+    assert int(err.item()) & fmtc.ERR_OFFSETS
 
 
 def test_static_stream_that_outgrows_its_buffer_is_marked_invalid(fmtc, oracle):
