@@ -384,7 +384,6 @@ struct DecodeParams {
     int C;
     int bits;
     int G;             // chunks per tile
-    int ct_per_group;  // 32-channel output tiles per workgroup row (blockIdx.y)
     int ncs;           // Cpad / 32
     const uint16_t* Bp16;  // inverse operand (T^T), f16 split, in operand order
     const float* mu;   // [Cpad]
@@ -439,9 +438,10 @@ __device__ __forceinline__ bool open_stream(const DecodeParams& p, StreamView* v
 constexpr int kPayWords = 918;  // LDS copy of a chunk's payload: up to ~7 bits/symbol; larger chunks read global memory
 
 // Wide tensors and the symbols-only mode: a tile of G chunks per workgroup is decoded into an LDS tile of symbol
-// bytes; the inverse transform of the tile's pixels then runs on the f16 matrix cores as in the narrow-tensor
-// kernel below (levels exact in f16, basis entries split in two f16 parts, two matrix instructions per 16
-// coefficients), the basis streaming from L2 in operand order one step ahead of its use.
+// bytes, one chunk per wavefront and round; the inverse transform of the tile's pixels then runs on the f16 matrix
+// cores with the arithmetic of the narrow-tensor kernel below (levels exact in f16, basis entries split in two f16
+// parts, two matrix instructions per 16 coefficients), as a matrix product tiled over the workgroup: the basis
+// blocks of a contraction step are brought into LDS once for all the tile's pixels (see the loop).
 template <int MT, int LAYOUT, bool ALIGNED4>
 __global__ __launch_bounds__(512) void k_decode_tiles(DecodeParams p) {
     __shared__ __align__(16) DecTables T;
@@ -960,7 +960,6 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     p.err = d_err;
     p.prebuilt = d_prebuilt;
     p.G = 1;
-    p.ct_per_group = 1;
     p.g_off_chunk_off = g.off_chunk_off;
     p.g_off_sub_bits = g.off_sub_bits;
     p.g_off_payload = g.off_payload;
@@ -1034,7 +1033,6 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         const char* knob = getenv("FMTC_DECODE_ONE_ROW");
         if (knob && knob[0] == '1') groups = 1;
     }
-    p.ct_per_group = 0;  // (unused by the tiled kernel)
     unsigned gx = n_tiles < 1024u ? n_tiles : 1024u;
     dim3 grid(gx, (unsigned)groups);
     const size_t lds = (size_t)G * 4096 + (size_t)G * 4096 / 16 + 128;
