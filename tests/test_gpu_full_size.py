@@ -157,3 +157,7 @@ def test_full_size_static_table_encode(fmtc, oracle, name, bits):
     xhat_a, err_a = fmtc.decode(basis, stream_a, x.shape, bits, synth.NHWC)
     torch.cuda.synchronize()
     assert int(err_a.item()) == 0 and torch.equal(xhat, xhat_a)
+    # and so does the decoder that takes its tables from the handle
+    xhat_s, err_s = fmtc.decode_static(basis, table, stream, x.shape, synth.NHWC)
+    torch.cuda.synchronize()
+    assert int(err_s.item()) == 0 and torch.equal(xhat_s, xhat)
