@@ -545,7 +545,7 @@ static int pack_resident_groups() {
 PackParams pack_params(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
                        int n_parts, const uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
                        uint64_t* d_out_bytes) {
-    PackParams p;
+    PackParams p{};
     p.cap_words = cap_words;
     p.syms = d_syms;
     p.V = (uint64_t)g.P * (uint64_t)g.C;

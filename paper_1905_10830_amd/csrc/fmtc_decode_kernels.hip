@@ -945,7 +945,7 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
                          hipStream_t s) {
     const int C = g.C;
     const int ncs = (C + 31) / 32;
-    DecodeParams p;
+    DecodeParams p{};
     p.stream = d_stream;
     p.bytes = bytes;
     p.P = g.P;

@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kWideThreads) void k_project_quantize_wide(WidePara
 
 static hipError_t launch_wide(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
                               int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
-    WideParams p;
+    WideParams p{};
     p.x = d_x;
     p.basis16 = b.fwd16;
     p.mu = b.mu;
@@ -368,6 +368,8 @@ static hipError_t launch_wide(const BasisDevice& b, const float* d_x, int64_t P,
     p.ctrl = cs.ctrl;
     p.lookback = cs.lookback;
     p.n_groups = cs.n_groups;
+    if (!p.x || !p.basis16 || !p.mu || !p.Trow || !p.syms || !p.hist_parts || !p.ctrl || !p.lookback)
+        return hipErrorInvalidValue;  // (a field left out would be a wild pointer on the device)
     const int ncs = p.ncs;
     // Pixel tile: the larger it is the fewer times the basis streams through; the tile (both f16 parts) and the
     // staging rows have to fit LDS, and a small tensor is better off with more, smaller workgroups.
@@ -875,7 +877,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
 static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
                               int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
-    RowParams p;
+    RowParams p{};
     p.x = d_x;
     p.basis16 = b.fwd16;
     p.mu = b.mu;
@@ -899,6 +901,8 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     p.lookback = cs.lookback;
     p.n_groups = cs.n_groups;
     p.pk = PackParams{};
+    if (!p.x || !p.basis16 || !p.mu || !p.Trow || !p.syms || !p.hist_parts || !p.ctrl || !p.lookback)
+        return hipErrorInvalidValue;  // (a field left out would be a wild pointer on the device)
     const int nct = b.Cpad / 32;
     const size_t lds = sizeof(float) * (size_t)b.Cpad * b.Cpad + sizeof(uint32_t) * 4 * kHistLanes * ((size_t)1 << bits);
     int64_t gx = (p.n_tiles + 3) / 4;
@@ -984,7 +988,7 @@ hipError_t launch_encode_static_fused(const BasisDevice& b, const float* d_x, in
     size_t lds = 0;
     const int cap = fused_kernel_for(b.C, layout, &fn, &lds);
     if (cap <= 0 || pk.chunk_syms != 4096u || pk.n_groups > (uint32_t)cap) return hipErrorNotSupported;
-    RowParams p;
+    RowParams p{};
     p.x = d_x;
     p.basis16 = b.fwd16;
     p.mu = b.mu;
@@ -1004,6 +1008,9 @@ hipError_t launch_encode_static_fused(const BasisDevice& b, const float* d_x, in
     p.lookback = cs.lookback;
     p.n_groups = cs.n_groups;
     p.pk = pk;
+    if (!p.x || !p.basis16 || !p.mu || !p.Trow || !p.ctrl || !p.lookback || !pk.enc_table || !pk.stream || !pk.lookback ||
+        !pk.ctrl)
+        return hipErrorInvalidValue;  // (a field left out would be a wild pointer on the device)
     const uint32_t grid = pk.n_groups < (uint32_t)cap ? pk.n_groups : (uint32_t)cap;
     void* args[] = {(void*)&p};
     hipEvent_t ev_a = nullptr, ev_b = nullptr;
@@ -1052,7 +1059,7 @@ struct GemmParams {
 constexpr int kGemmFix = 64;  // values per wavefront waiting for their exact decision
 
 template <int LAYOUT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_project_quantize_gemm(GemmParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_project_quantize_gemm4(GemmParams p) {
     __shared__ __align__(16) uint4 stageA[3][8][64];     // per 16-channel step: (coefficient tile, part), operand order
     __shared__ __align__(16) uint4 stageX[3][4][2][64];  // per step: fp32 pixels as loaded, [wavefront][instruction][lane]
     __shared__ __align__(16) uint4 stageB[2][4][2][64];  // per step: (pixel tile, part), operand order
@@ -1309,11 +1316,270 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             (s_red[tid] + s_red[K + tid]) + (s_red[2 * K + tid] + s_red[3 * K + tid]);
 }
 
+// The same product with 8 wavefronts per 128 x 128 tile, two per SIMD, each 2 coefficient tiles x 1 pixel tile and a
+// quarter of the conversion work: while one wavefront of a SIMD converts, the other's matrix instructions run.  More
+// LDS operand reads per matrix instruction and one workgroup per compute unit: the faster form for tensors whose
+// tiles all fit the device at once (measured C = 960: 57 -> 47 us, C = 512 at N = 64: 33 -> 26 us), the slower one
+// beyond (N = 256, C = 256: 49 -> 61 us).
+template <int LAYOUT>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_project_quantize_gemm8(GemmParams p) {
+    __shared__ __align__(16) uint4 stageA[3][8][64];     // per 16-channel step: (coefficient tile, part), operand order
+    __shared__ __align__(16) uint4 stageX[3][8][64];     // per step: fp32 pixels as loaded, [wavefront][lane] (16 bytes each)
+    __shared__ __align__(16) uint4 stageB[2][4][2][64];  // per step: (pixel tile, part), operand order
+    __shared__ float s_n2[4][32];
+    __shared__ uint32_t s_fix_a[8][kGemmFix], s_fix_px[8][kGemmFix], s_fix_count[8];
+    extern __shared__ __align__(16) uint8_t dyn_lds[];    // mean [Cpad], then histogram copies [8][K << HS]
+    constexpr int XL = LAYOUT == FMTC_NHWC ? 1 : 4;       // transfers of one step's pixels per wavefront
+    constexpr int LD = 1 + XL;                            // ... of one step in all (basis: 1)
+
+    zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    const int C = p.C, NJ = p.NJ, K = 1 << p.bits, HS = p.hist_shift, HC = 1 << HS;
+    // 8 wavefronts, two per SIMD (one converts while the other's matrix instructions run): wavefront w owns the
+    // pair ktp of coefficient tiles and pixel tile xpt, and brings quarter xq of the 16 channels of xpt's pixels
+    const int ktp = wave & 1, xpt = wave >> 1, xq = 2 * (wave & 1) + half;
+    const int kt0 = blockIdx.y * 4;
+    float* s_mu = reinterpret_cast<float*>(dyn_lds);
+    uint32_t* whist = reinterpret_cast<uint32_t*>(dyn_lds) + 16 * NJ;
+    for (int i = tid; i < 8 * K * HC; i += 512) whist[i] = 0u;
+    for (int i = tid; i < 16 * NJ; i += 512) s_mu[i] = p.mu[i];
+    uint32_t* wh0 = whist + wave * K * HC;
+    uint32_t* wh = wh0 + (lane & (HC - 1));
+    uint32_t* fix_a = s_fix_a[wave];
+    uint32_t* fix_px = s_fix_px[wave];
+    uint32_t* fix_count = &s_fix_count[wave];
+    if (lane == 0) *fix_count = 0u;
+    __syncthreads();
+
+    const int zero_sym = 1 << (p.bits - 1);
+    const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1), zero_f = (float)zero_sym;
+    const float inv_delta = p.inv_delta, inv_delta_lo = p.inv_delta * (1.f / 2048.f);
+
+    // exact fp64 decision of the listed values, four per round (one per 16-lane group)
+    auto resolve_list = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // the symbols that get patched have been stored
+        const uint32_t n = (uint32_t)__builtin_amdgcn_readfirstlane((int)*fix_count);
+        for (uint32_t base = 0; base < n; base += 4) {
+            const uint32_t idx = base + (uint32_t)(lane >> 4);
+            const bool active = idx < n;
+            const uint32_t e = active ? fix_a[idx] : 0u;
+            const int k = (int)(e & 0xffffu);
+            const uint32_t old = e >> 16;
+            const int64_t qpx = active ? (int64_t)fix_px[idx] : 0;
+            int64_t xbase, xstride;
+            if constexpr (LAYOUT == FMTC_NHWC) {
+                xbase = qpx * C;
+                xstride = 1;
+            } else {
+                const int64_t n_img = qpx / p.HW;
+                xbase = n_img * (int64_t)C * p.HW + (qpx - n_img * p.HW);
+                xstride = p.HW;
+            }
+            double part = 0.0;
+            if (active)
+#pragma unroll 8  // independent loads of eight terms in flight together: the loop is all latency
+                for (int c = lane & 15; c < C; c += 16)
+                    part += (double)p.Trow[(size_t)k * C + c] * ((double)p.x[xbase + c * xstride] - (double)p.mu[c]);
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);  // stays inside the 16-lane group
+            double qd = rint(part / (double)p.delta);
+            qd = fmin(fmax(qd, (double)lo), (double)hi);
+            const uint32_t sfix = (uint32_t)((int)qd + zero_sym);
+            if (active && (lane & 15) == 0 && sfix != old) {
+                atomicSub(&wh0[old << HS], 1u);
+                atomicAdd(&wh0[sfix << HS], 1u);
+                p.syms[qpx * C + k] = (uint8_t)sfix;
+            }
+        }
+        wave_sync_lds();
+        if (lane == 0) *fix_count = 0u;
+        wave_sync_lds();
+    };
+
+    for (int64_t ptg = blockIdx.x; ptg < p.n_ptg; ptg += gridDim.x) {
+        const int64_t pt0 = ptg * 4;
+        floatx16 am[2], ac[2];
+#pragma unroll
+        for (int a = 0; a < 2; a++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) { am[a][r] = 0.f; ac[a][r] = 0.f; }
+
+        // this thread's pixel (of pixel tile pt0 + xpt); past the end of the tensor the last pixel is loaded
+        // in its place and zeroed on conversion
+        const int64_t px_raw = (pt0 + xpt) * 32 + l32;
+        const bool px_ok = px_raw < p.P;
+        const int64_t px_ld = px_ok ? px_raw : p.P - 1;
+        int64_t xbase, xstride;
+        if constexpr (LAYOUT == FMTC_NHWC) {
+            xbase = px_ld * C;
+            xstride = 1;
+        } else {
+            const int64_t n_img = px_ld / p.HW;
+            xbase = n_img * (int64_t)C * p.HW + (px_ld - n_img * p.HW);
+            xstride = p.HW;
+        }
+        int kt_ld = kt0 + (wave >> 1);
+        kt_ld = kt_ld < p.ncs ? kt_ld : p.ncs - 1;  // a tile past the end repeats the last one; its results are dropped
+        const uint4* a_src = p.basis16 + ((size_t)kt_ld * NJ * 2 + (wave & 1)) * 64 + lane;
+        // Everything step s needs, on its way into ring slot s % 3: part wave % 2 of basis tile kt0 + wave / 2, and
+        // channels [16 s + 4 xq, + 4) of this thread's pixel -- half of an operand entry.  Steps past the end
+        // repeat the last one, so that every wavefront always has the same number of loads in flight.
+        auto issue = [&](int s) {
+            const int slot = s % 3;
+            s = s < NJ ? s : NJ - 1;
+            load_to_lds<16>(a_src + (size_t)s * 128, &stageA[slot][wave][0]);
+            int c0 = 16 * s + 4 * xq;
+            c0 = c0 < C ? c0 : 0;  // C is a multiple of 16: all four channels or none (then zeroed on conversion)
+            if constexpr (LAYOUT == FMTC_NHWC) {
+                load_to_lds<16>(p.x + xbase + c0, &stageX[slot][wave][0]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; e++)
+                    load_to_lds<4>(p.x + xbase + (int64_t)(c0 + e) * xstride,
+                                   reinterpret_cast<uint32_t*>(&stageX[slot][wave][0]) + 64 * e);
+            }
+        };
+        float n2 = 0.f;
+        // this thread's four channels of step s: mean removed, cut in two f16 parts, written into the pixel
+        // operands (entry of lane (pixel, xq / 2), elements 4 (xq % 2) .. + 3)
+        typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+        auto convert = [&](int s) {
+            const int c0 = 16 * s + 4 * xq;
+            const bool ok = px_ok && c0 < C;
+            float v[4];
+            if constexpr (LAYOUT == FMTC_NHWC) {
+                const float4 a = *reinterpret_cast<const float4*>(&stageX[s % 3][wave][lane]);
+                v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+            } else {
+                const float* raw = reinterpret_cast<const float*>(&stageX[s % 3][wave][0]) + lane;
+#pragma unroll
+                for (int e = 0; e < 4; e++) v[e] = raw[64 * e];
+            }
+            const float4 m0 = *reinterpret_cast<const float4*>(&s_mu[c0]);
+            const float m[4] = {m0.x, m0.y, m0.z, m0.w};
+            halfx4 vh, vl;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                float d = ok ? v[e] - m[e] : 0.f;
+                n2 = __builtin_fmaf(d, d, n2);
+                d = __builtin_amdgcn_fmed3f(d, -60000.f, 60000.f);  // such a pixel is decided exactly (see n2)
+                const _Float16 h = (_Float16)d;
+                vh[e] = h;
+                vl[e] = (_Float16)((d - (float)h) * 2048.f);
+            }
+            uint2* dst = reinterpret_cast<uint2*>(&stageB[s & 1][xpt][0][l32 + 32 * (xq >> 1)]) + (xq & 1);
+            dst[0] = __builtin_bit_cast(uint2, vh);
+            dst[128] = __builtin_bit_cast(uint2, vl);  // part 1: 64 entries of 16 bytes further on
+        };
+
+        issue(0);
+        issue(1);
+        wait_loads<LD>();  // step 0 has landed (this wavefront's part)
+        convert(0);
+        for (int s = 0; s < NJ; s++) {
+            // in flight: step s (unless s = 0) and step s + 1
+            wait_loads<LD>();  // step s has landed
+            __syncthreads();  // everybody's part of it, and everybody's pixel operands of step s; slot of step s - 1 is free
+            if (s == 0 && tid < 128) s_n2[tid >> 5][tid & 31] = 0.f;  // everybody has left the previous group's epilogue
+            issue(s + 2);
+            const uint4(*sa)[64] = stageA[s % 3];
+            halfx8 th[2], tl[2];
+#pragma unroll
+            for (int a = 0; a < 2; a++) {
+                th[a] = __builtin_bit_cast(halfx8, sa[(2 * ktp + a) * 2][lane]);
+                tl[a] = __builtin_bit_cast(halfx8, sa[(2 * ktp + a) * 2 + 1][lane]);
+            }
+            const halfx8 xh = __builtin_bit_cast(halfx8, stageB[s & 1][xpt][0][lane]);
+            const halfx8 xl = __builtin_bit_cast(halfx8, stageB[s & 1][xpt][1][lane]);
+#pragma unroll
+            for (int a = 0; a < 2; a++) {
+                am[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(th[a], xh, am[a], 0, 0, 0);
+                ac[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(th[a], xl, ac[a], 0, 0, 0);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; a++) ac[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl[a], xh, ac[a], 0, 0, 0);
+            wait_loads<LD>();  // step s + 1 has landed
+            if (s + 1 < NJ) convert(s + 1);  // into the operand buffer step s - 1 read, free since the barrier above
+        }
+        wait_loads<0>();  // the repeated loads of the last steps too
+        // a pixel's sum of squares: its four quarters sit in two lanes of each of two wavefronts
+        n2 += __shfl_xor(n2, 32, 64);
+        if (half == 0) atomicAdd(&s_n2[xpt][l32], n2);
+        __syncthreads();  // all wavefronts are done with the stages: the next group's first loads may overwrite them
+
+        // ---- quantizer, histogram, stores: accumulator r of lane (pixel, h) is coefficient kt*32 + 16h + r ----
+        {
+            const int64_t pt = pt0 + xpt;
+            if (pt < p.n_pt) {  // wavefront-uniform
+            const int64_t px = pt * 32 + l32;
+            const bool out_ok = px < p.P;
+            const float pn2 = s_n2[xpt][l32];
+            const bool force = !(pn2 < 1.0e9f);  // too large for f16, or not finite: every coefficient decided exactly
+            const float tau = fminf(fmaxf(p.kappa * __builtin_sqrtf(pn2), p.tau_min), 0.125f);
+            const float near_limit = force ? -1.f : 0.5f - tau;
+#pragma unroll
+            for (int a = 0; a < 2; a++) {
+                const int kt = kt0 + 2 * ktp + a;
+                if (kt >= p.ncs) continue;  // wavefront-uniform
+                const int k0 = kt * 32 + 16 * half;
+                const bool ok = out_ok && k0 < C;  // C is a multiple of 16: all sixteen coefficients or none
+                uint32_t word[4] = {0u, 0u, 0u, 0u};
+                uint32_t near_mask = 0;
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const float t = __builtin_fmaf(ac[a][r], inv_delta_lo, am[a][r] * inv_delta);
+                    const float q = __builtin_rintf(t);  // round half to even
+                    if (!(fabsf(t - q) <= near_limit)) near_mask |= 1u << r;
+                    const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
+                    word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
+                    if (ok) atomicAdd(&wh[(uint32_t)qc << HS], 1u);
+                }
+                if (ok)
+                    *reinterpret_cast<uint4*>(p.syms + px * C + k0) = make_uint4(word[0], word[1], word[2], word[3]);
+                if (!ok) near_mask = 0;
+                if (__builtin_expect(__any(near_mask != 0), 0)) {
+                    // note the flagged values; the list is resolved when it could overflow and at the end
+#pragma unroll 1
+                    for (int r = 0; r < 16; r++) {
+                        const bool f = (near_mask >> r) & 1u;
+                        const uint32_t incoming = (uint32_t)__popcll(__ballot(f));
+                        if (incoming == 0) continue;
+                        if (*fix_count + incoming > (uint32_t)kGemmFix) resolve_list();
+                        if (f) {
+                            const uint32_t slot = atomicAdd(fix_count, 1u);
+                            fix_a[slot] = (uint32_t)(k0 + r) | (((word[r >> 2] >> (8 * (r & 3))) & 255u) << 16);
+                            fix_px[slot] = (uint32_t)px;
+                        }
+                        wave_sync_lds();
+                    }
+                }
+            }
+        }
+        }
+        if (*fix_count) resolve_list();  // before the next group's loads: the waits there count loads in flight
+    }
+    __syncthreads();
+    // one row of partial counts per workgroup (see the narrow-tensor kernel); the operand buffers are free now
+    uint32_t* s_red = reinterpret_cast<uint32_t*>(&stageA[0][0][0]);
+    for (int row = tid; row < 8 * K; row += 512) {
+        uint32_t total = 0;
+        for (int q = 0; q < HC; q++) total += whist[((size_t)row << HS) + q];
+        s_red[row] = total;
+    }
+    __syncthreads();
+    if (tid < K)
+        p.hist_parts[(size_t)(blockIdx.y * gridDim.x + blockIdx.x) * K + tid] =
+            ((s_red[tid] + s_red[K + tid]) + (s_red[2 * K + tid] + s_red[3 * K + tid])) +
+            ((s_red[4 * K + tid] + s_red[5 * K + tid]) + (s_red[6 * K + tid] + s_red[7 * K + tid]));
+}
+
 static hipError_t launch_gemm(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
                               int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
     const int ncs = b.Cpad / 32, NJ = b.Cpad / 16;
     const int64_t n_pt = (P + 31) / 32;
-    GemmParams p;
+    GemmParams p{};
     p.x = d_x;
     p.basis16 = reinterpret_cast<const uint4*>(b.fwd16);
     p.mu = b.mu;
@@ -1330,24 +1596,34 @@ static hipError_t launch_gemm(const BasisDevice& b, const float* d_x, int64_t P,
     p.delta = delta;
     p.kappa = 1.9073486e-6f /* 2^-19 */ * b.row_norm * p.inv_delta;  // see launch_rows
     p.tau_min = 4.7683716e-7f /* 2^-21 */ * (float)(1 << (bits - 1));
-    // histogram copies per wavefront: as many as 8 KB of LDS hold, 16 at most, 2 at least
-    int copies = 512 >> bits;
-    copies = copies >= 16 ? 16 : (copies >= 8 ? 8 : (copies >= 4 ? 4 : 2));
-    p.hist_shift = copies == 16 ? 4 : (copies == 8 ? 3 : (copies == 4 ? 2 : 1));
     p.syms = d_syms;
     p.hist_parts = cs.hist_parts;
     p.ctrl = cs.ctrl;
     p.lookback = cs.lookback;
     p.n_groups = cs.n_groups;
+    // every pointer the kernel follows is set (a field left out here would be a wild pointer on the device)
+    if (!p.x || !p.basis16 || !p.mu || !p.Trow || !p.syms || !p.hist_parts || !p.ctrl || !p.lookback)
+        return hipErrorInvalidValue;
     const int gy = (ncs + 3) / 4;
     int64_t gx = p.n_ptg;
     if (gx * gy > kMaxHistParts) gx = kMaxHistParts / gy;
     *n_parts = (int)(gx * gy);
-    const size_t lds = sizeof(float) * b.Cpad + sizeof(uint32_t) * 4 * copies * ((size_t)1 << bits);
+    // 8 wavefronts per tile while every tile has a compute unit of its own, 4 (two workgroups per compute unit) beyond
+    const bool eight = p.n_ptg * gy <= 256;
+    const int waves = eight ? 8 : 4;
+    // histogram copies per wavefront: as many as 2 KB of LDS hold, 16 at most, 2 at least
+    int copies = 512 >> bits;
+    copies = copies >= 16 ? 16 : (copies >= 8 ? 8 : (copies >= 4 ? 4 : 2));
+    p.hist_shift = copies == 16 ? 4 : (copies == 8 ? 3 : (copies == 4 ? 2 : 1));
+    const size_t lds = sizeof(float) * b.Cpad + sizeof(uint32_t) * waves * copies * ((size_t)1 << bits);
     dim3 grid((unsigned)gx, (unsigned)gy);
+    if (eight)
+        return layout == FMTC_NHWC
+                   ? launch(K_PROJECT, k_project_quantize_gemm8<FMTC_NHWC>, grid, dim3(512), lds, s, p)
+                   : launch(K_PROJECT, k_project_quantize_gemm8<FMTC_NCHW>, grid, dim3(512), lds, s, p);
     return layout == FMTC_NHWC
-               ? launch(K_PROJECT, k_project_quantize_gemm<FMTC_NHWC>, grid, dim3(256), lds, s, p)
-               : launch(K_PROJECT, k_project_quantize_gemm<FMTC_NCHW>, grid, dim3(256), lds, s, p);
+               ? launch(K_PROJECT, k_project_quantize_gemm4<FMTC_NHWC>, grid, dim3(256), lds, s, p)
+               : launch(K_PROJECT, k_project_quantize_gemm4<FMTC_NCHW>, grid, dim3(256), lds, s, p);
 }
 
 hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,

@@ -145,3 +145,29 @@ def test_wide_decoder_walking_its_channel_groups(fmtc, oracle, C, layout, monkey
     sym, d, _ = oracle.unpack(stream[: int(nbytes.item())].cpu().numpy(), x.size // C, C, 5)
     ref = oracle.reconstruct(sym, x.shape, T, mu, d, 5, layout)
     assert np.abs(b.cpu().numpy().astype(np.float64) - ref).max() <= 1e-4
+
+
+@pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
+def test_wide_projection_with_more_tiles_than_compute_units(fmtc, oracle, layout):
+    """256 channels, 18000 pixels: 141 x 2 workgroup tiles, which takes the 4-wavefront form of the tiled
+    projection (small tensors take the 8-wavefront form), including a ragged last pixel tile."""
+    C, bits = 256, 4
+    s = synth.FeatureMapStream(C, 30, 30, 64, "relu", 1400)
+    calib, data = s.images(2), s.images(20)
+    x = synth.to_layout(data, layout)
+    mean, cov = oracle.covariance(synth.to_layout(calib, layout), layout)
+    w, v = np.linalg.eigh(cov)
+    T = np.ascontiguousarray(v[:, ::-1].T).astype(np.float32)
+    mu = mean.astype(np.float32)
+    A = np.float32(np.abs(oracle.project(synth.to_layout(calib, layout), T, mu, layout)[:, 0]).max())
+    d = oracle.delta(A, bits)
+    ref_sym, margin = oracle.quantize(oracle.project(x, T, mu, layout), d, bits, want_margin=True)
+    basis = fmtc.basis_import(T, mu, A)
+    sym, hist = fmtc.quantize(basis, torch.from_numpy(x).cuda(), bits, layout)
+    torch.cuda.synchronize()
+    sym, hist = sym.cpu().numpy().reshape(ref_sym.shape), hist.cpu().numpy()
+    diff = sym != ref_sym
+    n_bad = int(diff.sum())
+    if n_bad:
+        assert margin[diff].max() <= 1e-4 and n_bad / ref_sym.size <= 1e-6
+    assert hist.tolist() == np.bincount(sym.reshape(-1), minlength=256).tolist()
