@@ -1,0 +1,71 @@
+"""Rate-distortion sweep of the codec on the GPU (section 3: rate = average code bits per value, distortion =
+mean squared error of the reconstruction; the paper's rate-distortion figures sweep the quantizer step).
+
+Utilities around the library's entry points, nothing more: for every bit depth the tensor is encoded and decoded
+by the HIP kernels; the entropy of the symbols (the bound section 3.1 compares the Huffman code with,
+H <= R < H + 1) is computed on the host from the GPU's histogram.
+"""
+import math
+
+from . import binding as fmtc
+
+
+def entropy_bits(hist):
+    """-sum p log2 p of a histogram (any iterable of counts)."""
+    total = float(sum(int(h) for h in hist))
+    if total <= 0:
+        return 0.0
+    return -sum((int(h) / total) * math.log2(int(h) / total) for h in hist if int(h) > 0)
+
+
+def sweep(basis, x, bits_list=(8, 7, 6, 5, 4, 3, 2), layout=fmtc.NHWC):
+    """x: device fp32 tensor.  -> list of dicts, one per bit depth:
+    bits, delta, entropy (bits/value), rate (Huffman payload bits/value), container (all stream bits/value),
+    mse, psnr (dB against the tensor's peak magnitude)."""
+    import torch
+
+    T, mu, eig, A = basis.export()
+    V = x.numel()
+    peak = float(x.abs().max().item())
+    out = []
+    for bits in bits_list:
+        sym, hist = fmtc.quantize(basis, x, bits, layout)
+        stream, nbytes = fmtc.encode(basis, x, bits, layout)
+        xhat, err = fmtc.decode(basis, stream, tuple(x.shape), bits, layout)
+        torch.cuda.synchronize()
+        if int(err.item()):
+            raise RuntimeError("decoder flagged its own stream")
+        info = fmtc.stream_info(stream[:64].cpu().numpy())
+        mse = float(((xhat - x) ** 2).mean().item())
+        out.append({
+            "bits": bits,
+            "delta": fmtc.delta(A, bits),
+            "entropy": entropy_bits(hist.cpu().tolist()),
+            "rate": info["payload_bits"] / V,
+            "container": 8.0 * info["stream_bytes"] / V,
+            "mse": mse,
+            "psnr": (10.0 * math.log10(peak * peak / mse)) if mse > 0 and peak > 0 else float("inf"),
+        })
+    return out
+
+
+def main():
+    import argparse
+
+    import torch
+
+    from . import synth
+
+    ap = argparse.ArgumentParser(description="rate-distortion table of a synthetic workload")
+    ap.add_argument("--workload", default="resnet18_stage2_c128_28", choices=sorted(synth.WORKLOADS))
+    args = ap.parse_args()
+    calib, data = synth.workload(args.workload, seed=0)
+    basis = fmtc.fit_basis(torch.from_numpy(calib).cuda())
+    print(f"{args.workload}: bits  delta      H       R   container   mse        psnr")
+    for r in sweep(basis, torch.from_numpy(data).cuda()):
+        print(f"  {r['bits']:4d}  {r['delta']:.5f}  {r['entropy']:.4f}  {r['rate']:.4f}  {r['container']:.4f}  "
+              f"{r['mse']:.4e}  {r['psnr']:.2f}")
+
+
+if __name__ == "__main__":
+    main()

@@ -171,3 +171,34 @@ def test_wide_projection_with_more_tiles_than_compute_units(fmtc, oracle, layout
     if n_bad:
         assert margin[diff].max() <= 1e-4 and n_bad / ref_sym.size <= 1e-6
     assert hist.tolist() == np.bincount(sym.reshape(-1), minlength=256).tolist()
+
+
+def test_rate_distortion_sweep_against_the_oracle(fmtc, oracle):
+    """The sweep utility's numbers are the oracle's: entropy and rate from identical histograms, distortion from
+    the fp64 reconstruction of the same symbols; and they behave as section 3.1 says (H <= R < H + 1), with the
+    distortion near Delta^2 / 12 per coefficient while the quantizer does not clamp."""
+    from paper_1905_10830_amd import rd
+
+    s = synth.FeatureMapStream(64, 12, 12, 16, "relu", 1500)
+    calib, x = s.images(2), s.images(3)
+    T, mu, eig, A = oracle.fit(calib)
+    basis = fmtc.basis_import(T, mu, A)
+    rows = rd.sweep(basis, torch.from_numpy(x).cuda(), bits_list=(8, 6, 4, 2))
+    prev_rate, prev_mse = None, None
+    for r in rows:
+        bits = r["bits"]
+        d = oracle.delta(A, bits)
+        assert r["delta"] == float(d)
+        enc = oracle.encode(x, T, mu, d, bits, want_margin=True)
+        h = enc["hist"][: 1 << bits]
+        ln = oracle.huffman_lengths(h)
+        # a symbol or two may sit on a rounding boundary: allow the histogram to move by that much
+        assert abs(r["entropy"] - oracle.entropy(h)) < 1e-3
+        assert abs(r["rate"] - float((h * ln.astype(np.uint64)).sum()) / x.size) < 1e-3
+        assert r["entropy"] <= r["rate"] + 1e-9 < r["entropy"] + 1.0
+        ref_hat, _ = oracle.decode(enc["stream"], x.shape, T, mu, bits)
+        assert abs(r["mse"] - oracle.mse(x, ref_hat)) <= 1e-3 * oracle.mse(x, ref_hat) + 1e-9
+        if prev_rate is not None:
+            assert r["rate"] < prev_rate and r["mse"] > prev_mse  # fewer bits: lower rate, higher distortion
+        prev_rate, prev_mse = r["rate"], r["mse"]
+    assert rows[0]["mse"] < 1.3 * rows[0]["delta"] ** 2 / 12
