@@ -87,3 +87,26 @@ def test_argument_errors_are_reported_on_the_host(lib):
     assert st == fmtc.EINVAL
     st = lib.fmtc_decode_symbols(None, 0, 10, 64, 4, None, None, None)
     assert st == fmtc.EINVAL
+
+
+def test_fixed_table_argument_errors_are_reported_on_the_host(lib):
+    """The lengths of an imported table are checked before any device memory is touched."""
+    out = ctypes.c_void_p()
+    flat = (ctypes.c_uint8 * 16)(*([3] * 16))                    # Kraft sum 2: not a prefix code
+    assert lib.fmtc_table_import(flat, 4, ctypes.byref(out)) == fmtc.EINVAL
+    assert b"prefix code" in lib.fmtc_last_error()
+    short = (ctypes.c_uint8 * 16)(*([5] * 16))                   # Kraft sum 1/2: not complete
+    assert lib.fmtc_table_import(short, 4, ctypes.byref(out)) == fmtc.EINVAL
+    missing = (ctypes.c_uint8 * 16)(*([1] + [0] * 15))           # a symbol without a code
+    assert lib.fmtc_table_import(missing, 4, ctypes.byref(out)) == fmtc.EINVAL
+    good = (ctypes.c_uint8 * 16)(*([4] * 16))
+    assert lib.fmtc_table_import(good, 9, ctypes.byref(out)) == fmtc.EINVAL   # bit depth out of range
+    assert lib.fmtc_table_import(None, 4, ctypes.byref(out)) == fmtc.EINVAL
+    assert lib.fmtc_encode_static_bound(None, 100, 64, 4096) == 0
+    st = lib.fmtc_encode_static(None, None, None, 1, 64, 8, 8, fmtc.NHWC, 4096, None, 0, None, None, 0, None)
+    assert st == fmtc.EINVAL
+    st = lib.fmtc_decode_static(None, None, None, 0, None, 1, 64, 8, 8, fmtc.NHWC, None, None)
+    assert st == fmtc.EINVAL
+    st = lib.fmtc_fit_table(None, None, 1, 64, 8, 8, fmtc.NHWC, 4, None, ctypes.byref(out))
+    assert st == fmtc.EINVAL
+    lib.fmtc_table_destroy(None)  # a no-op
