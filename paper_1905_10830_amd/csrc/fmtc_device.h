@@ -59,7 +59,8 @@ __device__ __forceinline__ void load_to_lds(const void* src, void* lds_base) {
 }
 
 // Wait until at most N of this wavefront's loads are in flight (they complete in order); no memory access
-// moves across it.
+// moves across it.  A memory operation the caller's count does not know of (the compiler may add some) can only
+// make the wait stricter: issued after the awaited load, it takes one of the N places.
 template <int N>
 __device__ __forceinline__ void wait_loads() {
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
