@@ -87,6 +87,38 @@ typedef struct fmtc_basis fmtc_basis;
 fmtc_status fmtc_fit_basis(const float *d_x, int64_t N, int C, int H, int W, fmtc_layout layout, void *hip_stream,
                            fmtc_basis **out);
 
+/* Calibration over several tensors (section 3.1 "Linear transform": the
+ * covariance comes from a small batch and may be updated online).  A fit state
+ * holds, on the host in fp64, the pixel count, the channel mean and the centred
+ * second moments of everything it has seen.  fmtc_fit_state_update adds one
+ * device tensor (moments accumulated on the GPU as in fmtc_fit_basis, merged by
+ * the exact rule for the union of two sample sets; synchronises the stream).
+ * fmtc_fit_state_basis makes a basis exactly as fmtc_fit_basis would from the
+ * concatenation of all tensors seen (up to rounding order), except that the
+ * dynamic range A is measured over the pixels of the tensor passed here
+ * (d_x, typically the latest batch): a maximum under a basis that changes with
+ * every update cannot be carried along.  The state is not consumed; more updates
+ * and further bases may follow.  Errors: FMTC_EINVAL for NULL or mismatching
+ * arguments and for a state that has seen nothing. */
+typedef struct fmtc_fit_state fmtc_fit_state;
+fmtc_status fmtc_fit_state_create(int C, fmtc_fit_state **out);
+fmtc_status fmtc_fit_state_update(fmtc_fit_state *state, const float *d_x, int64_t N, int C, int H, int W,
+                                  fmtc_layout layout, void *hip_stream);
+fmtc_status fmtc_fit_state_basis(const fmtc_fit_state *state, const float *d_x, int64_t N, int C, int H, int W,
+                                 fmtc_layout layout, void *hip_stream, fmtc_basis **out);
+int64_t fmtc_fit_state_count(const fmtc_fit_state *state);
+void fmtc_fit_state_destroy(fmtc_fit_state *state);
+
+/* Truncated basis (section 4 "Ablation study": the least significant
+ * principal components are dropped).  *out is a new handle whose rows keep..C-1
+ * of T are zero, everything else (mean, A, eigenvalues) as in `basis`; 1 <= keep
+ * <= C.  With it every entry point works unchanged: a dropped coefficient is 0,
+ * its symbol the zero level 2^(bits-1), and the reconstruction is the sum over
+ * the kept components plus the mean.  The container keeps C symbols per pixel,
+ * so a dropped coefficient still costs its (short) code word; the kernels do not
+ * skip the zero rows.  `basis` stays valid; release both. */
+fmtc_status fmtc_basis_truncate(const fmtc_basis *basis, int keep, fmtc_basis **out);
+
 /* Builds a handle from host arrays (h_T: C*C row major, h_mu: C).  The way to
  * reuse a stored basis, and to give two implementations the same one. */
 fmtc_status fmtc_basis_import(int C, const float *h_T, const float *h_mu, float range_A, fmtc_basis **out);

@@ -105,6 +105,70 @@ def fit(x, layout=NHWC):
     return T, mu, eig, np.float32(A.value)
 
 
+def dynamic_range(x, t0, mu, layout=NHWC):
+    """A = max |t0 . (x - mu)| over the pixels of x (fp32 row and mean)."""
+    x, t0, mu = _f32(x), _f32(t0), _f32(mu)
+    n, c, hw = _dims(x, layout)
+    A = ctypes.c_float(0)
+    _chk(lib().fmtc_oracle_range(_p(x), ctypes.c_int64(n), c, ctypes.c_int64(hw), layout, _p(t0), _p(mu),
+                                 ctypes.byref(A)), "range")
+    return np.float32(A.value)
+
+
+def _pixel_major(x, layout):
+    """The tensor's values as [P, C] in logical (n, h, w) pixel order: a copy, no arithmetic."""
+    x = _f32(x)
+    if layout == NCHW:
+        x = np.transpose(x, (0, 2, 3, 1))
+    return np.ascontiguousarray(x).reshape(-1, x.shape[-1])
+
+
+def fit_online(batches, range_x, layout=NHWC):
+    """Calibration over several tensors: the fit of their concatenation (mean, covariance, PCA, fp32
+    rounding), with the dynamic range measured on range_x.  -> T, mu, eigenvalues, A."""
+    allpx = np.concatenate([_pixel_major(b, layout) for b in batches], axis=0)
+    mean, cov = covariance(allpx.reshape(1, allpx.shape[0], 1, allpx.shape[1]), NHWC)
+    Td, eig = pca(cov)
+    T, mu = Td.astype(np.float32), mean.astype(np.float32)
+    return T, mu, eig, dynamic_range(range_x, T[0], mu, layout)
+
+
+def project_keep(x, T, mu, keep, layout=NHWC):
+    """Projection onto the `keep` leading components; dropped coefficients are 0.  -> y fp64 [P, C]."""
+    x, T, mu = _f32(x), _f32(T), _f32(mu)
+    n, c, hw = _dims(x, layout)
+    y = np.empty((n * hw, c), np.float64)
+    _chk(lib().fmtc_oracle_project_keep(_p(x), ctypes.c_int64(n), c, ctypes.c_int64(hw), layout, _p(T), _p(mu),
+                                        int(keep), _p(y)), "project_keep")
+    return y
+
+
+def reconstruct_keep(sym, shape, T, mu, dlt, bits, keep, layout=NHWC):
+    """symbols [P, C] -> x_hat fp64 from the `keep` leading components only."""
+    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    T, mu = _f32(T), _f32(mu)
+    xhat = np.empty(shape, np.float64)
+    n, c, hw = _dims(xhat, layout)
+    _chk(lib().fmtc_oracle_reconstruct_keep(_p(sym), ctypes.c_int64(n), c, ctypes.c_int64(hw), layout, int(bits),
+                                            ctypes.c_float(float(dlt)), _p(T), _p(mu), int(keep), _p(xhat)),
+         "reconstruct_keep")
+    return xhat
+
+
+def encode_keep(x, T, mu, dlt, bits, keep, layout=NHWC, chunk_syms=4096, want_margin=False):
+    """Encoder with truncation: project_keep, quantizer, this tensor's Huffman table, container."""
+    y = project_keep(x, T, mu, keep, layout)
+    q = quantize(y, dlt, bits, want_margin)
+    sym, margin = q if want_margin else (q, None)
+    hist = histogram(sym, bits)
+    length = huffman_lengths(hist[: 1 << bits])
+    res = {"stream": pack(sym, sym.shape[1], bits, dlt, length, canonical_codes(length), chunk_syms),
+           "sym": sym, "hist": hist}
+    if want_margin:
+        res["margin"] = margin
+    return res
+
+
 def delta(range_A, bits):
     return np.float32(lib().fmtc_oracle_delta(ctypes.c_float(float(range_A)), int(bits)))
 

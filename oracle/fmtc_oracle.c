@@ -212,6 +212,50 @@ int fmtc_oracle_fit(const float *x, int64_t N, int C, int64_t HW, int layout,
     return rc;
 }
 
+/* Dynamic range of the leading component over the pixels of a given tensor:
+ * A = max |t0 . (x - mu)| with the fp32 row t0 and mean (section 3.1
+ * "Quantization").  Serves a calibration whose statistics come from several
+ * tensors while the range is measured on one of them. */
+int fmtc_oracle_range(const float *x, int64_t N, int C, int64_t HW, int layout, const float *t0, const float *mu,
+                      float *range_A)
+{
+    if (!x || !t0 || !mu || !range_A || N < 1 || C < 1 || HW < 1) return ORC_EINVAL;
+    double amax = 0.0;
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t hw = 0; hw < HW; hw++) {
+            double acc = 0.0;
+            for (int c = 0; c < C; c++)
+                acc += (double)t0[c] * ((double)x[x_index(layout, n, c, hw, C, HW)] - (double)mu[c]);
+            if (fabs(acc) > amax) amax = fabs(acc);
+        }
+    *range_A = (float)amax;
+    return ORC_OK;
+}
+
+/* Projection with the least significant components dropped (section 4
+ * "Ablation study"): only the `keep` leading coefficients are computed; a
+ * dropped coefficient is 0 (its symbol is then the zero level).  y is [P][C]. */
+int fmtc_oracle_project_keep(const float *x, int64_t N, int C, int64_t HW, int layout,
+                             const float *T, const float *mu, int keep, double *y)
+{
+    if (!x || !T || !mu || !y || N < 1 || C < 1 || HW < 1 || keep < 1 || keep > C) return ORC_EINVAL;
+    double *d = (double *)malloc(sizeof(double) * (size_t)C);
+    if (!d) return ORC_ENOMEM;
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t hw = 0; hw < HW; hw++) {
+            size_t p = (size_t)n * (size_t)HW + (size_t)hw;
+            for (int c = 0; c < C; c++) d[c] = (double)x[x_index(layout, n, c, hw, C, HW)] - (double)mu[c];
+            for (int k = 0; k < keep; k++) {
+                double acc = 0.0;
+                for (int c = 0; c < C; c++) acc += (double)T[(size_t)k * C + c] * d[c];
+                y[p * (size_t)C + k] = acc;
+            }
+            for (int k = keep; k < C; k++) y[p * (size_t)C + k] = 0.0;
+        }
+    free(d);
+    return ORC_OK;
+}
+
 /* ------------------------------------------------------------ quantizer */
 
 /* Step of the b-bit mid-tread quantizer whose positive range 2^(b-1)-1 levels
@@ -586,6 +630,28 @@ int fmtc_oracle_reconstruct(const uint8_t *sym, int64_t N, int C, int64_t HW, in
             }
         }
     free(yh);
+    return ORC_OK;
+}
+
+/* Reconstruction from the `keep` leading components only (section 4 "Ablation
+ * study"): x_hat = sum_{k < keep} T[k] y_hat[k] + mu; the symbols of the dropped
+ * coefficients are not looked at. */
+int fmtc_oracle_reconstruct_keep(const uint8_t *sym, int64_t N, int C, int64_t HW, int layout, int bits, float delta,
+                                 const float *T, const float *mu, int keep, double *xhat)
+{
+    if (!sym || !T || !mu || !xhat || N < 1 || C < 1 || HW < 1 || bits < 2 || bits > 8 || keep < 1 || keep > C)
+        return ORC_EINVAL;
+    double half = (double)(1 << (bits - 1));
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t hw = 0; hw < HW; hw++) {
+            size_t p = (size_t)n * (size_t)HW + (size_t)hw;
+            for (int c = 0; c < C; c++) {
+                double acc = 0.0;
+                for (int k = 0; k < keep; k++)
+                    acc += (double)T[(size_t)k * C + c] * ((double)delta * ((double)sym[p * (size_t)C + k] - half));
+                xhat[x_index(layout, n, c, hw, C, HW)] = acc + (double)mu[c];
+            }
+        }
     return ORC_OK;
 }
 

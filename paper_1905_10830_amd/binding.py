@@ -21,6 +21,8 @@ EXPORTS = [
     "fmtc_code_symbols", "fmtc_decode_symbols", "fmtc_stream_info", "fmtc_last_error",
     "fmtc_fit_table", "fmtc_table_import", "fmtc_table_export", "fmtc_table_destroy", "fmtc_encode_static_bound",
     "fmtc_encode_static", "fmtc_decode_static",
+    "fmtc_fit_state_create", "fmtc_fit_state_update", "fmtc_fit_state_basis", "fmtc_fit_state_count",
+    "fmtc_fit_state_destroy", "fmtc_basis_truncate",
     "fmtc_profile_enable", "fmtc_profile_kernels", "fmtc_profile_name", "fmtc_profile_read", "fmtc_profile_copy",
 ]
 
@@ -50,6 +52,14 @@ def load_library():
     lib.fmtc_basis_channels.argtypes = [vp]
     lib.fmtc_basis_destroy.argtypes = [vp]
     lib.fmtc_basis_destroy.restype = None
+    lib.fmtc_fit_state_create.argtypes = [i32, ctypes.POINTER(vp)]
+    lib.fmtc_fit_state_update.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp]
+    lib.fmtc_fit_state_basis.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, ctypes.POINTER(vp)]
+    lib.fmtc_fit_state_count.argtypes = [vp]
+    lib.fmtc_fit_state_count.restype = i64
+    lib.fmtc_fit_state_destroy.argtypes = [vp]
+    lib.fmtc_fit_state_destroy.restype = None
+    lib.fmtc_basis_truncate.argtypes = [vp, i32, ctypes.POINTER(vp)]
     lib.fmtc_delta.argtypes = [f32, i32]
     lib.fmtc_delta.restype = f32
     lib.fmtc_encode_bound.argtypes = [i64, i32, i32, i32]
@@ -136,6 +146,12 @@ class Basis:
                                                 ctypes.byref(A)))
         return T, mu, eig, np.float32(A.value)
 
+    def truncate(self, keep):
+        """-> a new Basis that keeps the `keep` leading components (the other rows of T are zero)."""
+        out = ctypes.c_void_p()
+        _check(load_library().fmtc_basis_truncate(self._h, int(keep), ctypes.byref(out)))
+        return Basis(out)
+
     def close(self):
         if self._h:
             load_library().fmtc_basis_destroy(self._h)
@@ -155,6 +171,45 @@ def fit_basis(x, layout=NHWC):
     out = ctypes.c_void_p()
     _check(load_library().fmtc_fit_basis(_dev(x, torch.float32), n, c, h, w, layout, _stream(), ctypes.byref(out)))
     return Basis(out)
+
+
+class FitState:
+    """Owns an fmtc_fit_state handle: calibration statistics accumulated over several tensors."""
+
+    def __init__(self, C):
+        self._h = ctypes.c_void_p()
+        _check(load_library().fmtc_fit_state_create(int(C), ctypes.byref(self._h)))
+
+    @property
+    def count(self):
+        return load_library().fmtc_fit_state_count(self._h)
+
+    def update(self, x, layout=NHWC):
+        import torch
+
+        n, c, h, w = _dims(x, layout)
+        _check(load_library().fmtc_fit_state_update(self._h, _dev(x, torch.float32), n, c, h, w, layout, _stream()))
+
+    def basis(self, x, layout=NHWC):
+        """Basis of everything seen so far; the dynamic range is measured on x."""
+        import torch
+
+        n, c, h, w = _dims(x, layout)
+        out = ctypes.c_void_p()
+        _check(load_library().fmtc_fit_state_basis(self._h, _dev(x, torch.float32), n, c, h, w, layout, _stream(),
+                                                   ctypes.byref(out)))
+        return Basis(out)
+
+    def close(self):
+        if self._h:
+            load_library().fmtc_fit_state_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def basis_import(T, mu, range_A):

@@ -225,6 +225,94 @@ fmtc_status run_coder(const uint8_t* d_syms, const EncodePlan& pl, const CoderSc
     return FMTC_OK;
 }
 
+
+// Sums [C] and cross-product sums about this tensor's own mean [C*C] (both triangles accumulated separately on the
+// device, made exactly symmetric here), in fp64.  Synchronises the stream.
+fmtc_status device_moments(const float* d_x, int64_t N, int C, int64_t HW, int layout, hipStream_t s,
+                           std::vector<double>* sum, std::vector<double>* m2) {
+    hipError_t e;
+    double* d_stat = nullptr;
+    const size_t n_stat = (size_t)C + (size_t)C * C;
+    if ((e = hipMalloc((void**)&d_stat, sizeof(double) * n_stat)) != hipSuccess)
+        return fail(FMTC_ENOMEM, "hipMalloc fit scratch: %s", hipGetErrorString(e));
+    std::vector<double> stat(n_stat);
+    fmtc_status st = FMTC_OK;
+    do {
+        if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(d_stat), 2 * n_stat, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
+        if ((e = launch_fit_moments(d_x, N, C, HW, layout, d_stat, d_stat + C, s)) != hipSuccess) { st = hip_fail(e, "fit moments"); break; }
+        if ((e = hipMemcpyAsync(stat.data(), d_stat, sizeof(double) * n_stat, hipMemcpyDeviceToHost, s)) != hipSuccess) { st = hip_fail(e, "copy moments"); break; }
+        if ((e = hipStreamSynchronize(s)) != hipSuccess) { st = hip_fail(e, "fit sync"); break; }
+    } while (0);
+    (void)hipFree(d_stat);
+    if (st != FMTC_OK) return st;
+    sum->assign(stat.begin(), stat.begin() + C);
+    m2->assign(stat.begin() + C, stat.end());
+    for (int i = 0; i < C; i++)
+        for (int j = i + 1; j < C; j++) {
+            double m = 0.5 * ((*m2)[(size_t)i * C + j] + (*m2)[(size_t)j * C + i]);
+            (*m2)[(size_t)i * C + j] = (*m2)[(size_t)j * C + i] = m;
+        }
+    return FMTC_OK;
+}
+
+// Basis of a mean and a (symmetric) covariance: eigenvectors by descending eigenvalue, each signed so that its
+// largest-magnitude entry is positive, rounded to fp32; then A = max |y_0| over the pixels of d_x with the rounded
+// leading row and mean, and the upload.  Synchronises the stream.
+fmtc_status finish_fit(int C, const std::vector<double>& mean, std::vector<double> cov, const float* d_x, int64_t N,
+                       int64_t HW, int layout, hipStream_t s, fmtc_basis** out) {
+    std::vector<double> vt;
+    symmetric_eigen(cov, vt, C);
+    std::vector<int> order(C);
+    for (int i = 0; i < C; i++) order[i] = i;
+    for (int i = 1; i < C; i++) {  // stable, descending eigenvalue
+        int o = order[i], j = i - 1;
+        double ev = cov[(size_t)o * C + o];
+        while (j >= 0 && cov[(size_t)order[j] * C + order[j]] < ev) { order[j + 1] = order[j]; j--; }
+        order[j + 1] = o;
+    }
+    fmtc_basis* b = new (std::nothrow) fmtc_basis;
+    if (!b) return fail(FMTC_ENOMEM, "host allocation failed");
+    b->C = C;
+    b->Cpad = (C + 31) / 32 * 32;
+    b->T.resize((size_t)C * C);
+    b->mu.resize(C);
+    b->eig.resize(C);
+    for (int k = 0; k < C; k++) {
+        const double* v = &vt[(size_t)order[k] * C];
+        b->eig[k] = cov[(size_t)order[k] * C + order[k]];
+        int arg = 0;
+        for (int c = 1; c < C; c++)
+            if (std::fabs(v[c]) > std::fabs(v[arg])) arg = c;
+        const double sgn = v[arg] < 0.0 ? -1.0 : 1.0;
+        for (int c = 0; c < C; c++) b->T[(size_t)k * C + c] = (float)(sgn * v[c]);
+    }
+    for (int c = 0; c < C; c++) b->mu[c] = (float)mean[c];
+    hipError_t e;
+    fmtc_status st = FMTC_OK;
+    float* d_row = nullptr;  // [C] leading row, [C] mean, then the fp64 maximum
+    do {
+        if ((e = hipMalloc((void**)&d_row, sizeof(float) * 2 * C + 16)) != hipSuccess) { st = fail(FMTC_ENOMEM, "hipMalloc: %s", hipGetErrorString(e)); break; }
+        float* d_mu = d_row + C;
+        double* d_amax = reinterpret_cast<double*>(reinterpret_cast<uint8_t*>(d_row) + (sizeof(float) * 2 * C + 7) / 8 * 8);
+        if ((e = hipMemcpyAsync(d_row, b->T.data(), sizeof(float) * C, hipMemcpyHostToDevice, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
+        if ((e = hipMemcpyAsync(d_mu, b->mu.data(), sizeof(float) * C, hipMemcpyHostToDevice, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
+        if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(d_amax), 2, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
+        if ((e = launch_fit_range(d_x, N, C, HW, layout, d_row, d_mu, d_amax, s)) != hipSuccess) { st = hip_fail(e, "fit range"); break; }
+        double amax = 0.0;
+        if ((e = hipMemcpyAsync(&amax, d_amax, sizeof(double), hipMemcpyDeviceToHost, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
+        if ((e = hipStreamSynchronize(s)) != hipSuccess) { st = hip_fail(e, "fit sync"); break; }
+        b->range_A = (float)amax;
+        st = upload_basis(b);
+    } while (0);
+    if (d_row) (void)hipFree(d_row);
+    if (st != FMTC_OK) {
+        fmtc_basis_destroy(b);
+        return st;
+    }
+    *out = b;
+    return FMTC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -286,70 +374,89 @@ fmtc_status fmtc_fit_basis(const float* d_x, int64_t N, int C, int H, int W, fmt
     if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
     hipStream_t s = (hipStream_t)hip_stream;
     const int64_t HW = (int64_t)H * W, P = N * HW;
-    hipError_t e;
-    double* d_stat = nullptr;  // [C] sums, [C*C] covariance sums, [1] amax
-    const size_t n_stat = (size_t)C + (size_t)C * C + 1;
-    if ((e = hipMalloc((void**)&d_stat, sizeof(double) * n_stat)) != hipSuccess)
-        return fail(FMTC_ENOMEM, "hipMalloc fit scratch: %s", hipGetErrorString(e));
-    fmtc_status st = FMTC_OK;
-    std::vector<double> stat(n_stat), vt;
-    float *d_t0 = nullptr, *d_mu = nullptr;
-    fmtc_basis* b = nullptr;
-    do {
-        if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(d_stat), 2 * n_stat, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
-        if ((e = launch_fit_moments(d_x, N, C, HW, layout, d_stat, d_stat + C, s)) != hipSuccess) { st = hip_fail(e, "fit moments"); break; }
-        if ((e = hipMemcpyAsync(stat.data(), d_stat, sizeof(double) * n_stat, hipMemcpyDeviceToHost, s)) != hipSuccess) { st = hip_fail(e, "copy moments"); break; }
-        if ((e = hipStreamSynchronize(s)) != hipSuccess) { st = hip_fail(e, "fit sync"); break; }
-        std::vector<double> cov((size_t)C * C);
-        for (size_t i = 0; i < cov.size(); i++) cov[i] = stat[C + i] / (double)P;
-        // the two triangles are accumulated separately on the device; make the matrix exactly symmetric
-        for (int i = 0; i < C; i++)
-            for (int j = i + 1; j < C; j++) {
-                double m = 0.5 * (cov[(size_t)i * C + j] + cov[(size_t)j * C + i]);
-                cov[(size_t)i * C + j] = cov[(size_t)j * C + i] = m;
-            }
-        symmetric_eigen(cov, vt, C);
-        std::vector<int> order(C);
-        for (int i = 0; i < C; i++) order[i] = i;
-        for (int i = 1; i < C; i++) {  // stable, descending eigenvalue
-            int o = order[i], j = i - 1;
-            double ev = cov[(size_t)o * C + o];
-            while (j >= 0 && cov[(size_t)order[j] * C + order[j]] < ev) { order[j + 1] = order[j]; j--; }
-            order[j + 1] = o;
-        }
-        b = new (std::nothrow) fmtc_basis;
-        if (!b) { st = fail(FMTC_ENOMEM, "host allocation failed"); break; }
-        b->C = C;
-        b->Cpad = (C + 31) / 32 * 32;
-        b->T.resize((size_t)C * C);
-        b->mu.resize(C);
-        b->eig.resize(C);
-        for (int k = 0; k < C; k++) {
-            const double* v = &vt[(size_t)order[k] * C];
-            b->eig[k] = cov[(size_t)order[k] * C + order[k]];
-            int arg = 0;
-            for (int c = 1; c < C; c++)
-                if (std::fabs(v[c]) > std::fabs(v[arg])) arg = c;
-            const double sgn = v[arg] < 0.0 ? -1.0 : 1.0;
-            for (int c = 0; c < C; c++) b->T[(size_t)k * C + c] = (float)(sgn * v[c]);
-        }
-        for (int c = 0; c < C; c++) b->mu[c] = (float)(stat[c] / (double)P);
-        // dynamic range of the leading component with the rounded basis
-        if ((e = hipMalloc((void**)&d_t0, sizeof(float) * C)) != hipSuccess || (e = hipMalloc((void**)&d_mu, sizeof(float) * C)) != hipSuccess) { st = fail(FMTC_ENOMEM, "hipMalloc: %s", hipGetErrorString(e)); break; }
-        if ((e = hipMemcpyAsync(d_t0, b->T.data(), sizeof(float) * C, hipMemcpyHostToDevice, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
-        if ((e = hipMemcpyAsync(d_mu, b->mu.data(), sizeof(float) * C, hipMemcpyHostToDevice, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
-        double* d_amax = d_stat + (n_stat - 1);
-        if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(d_amax), 2, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
-        if ((e = launch_fit_range(d_x, N, C, HW, layout, d_t0, d_mu, d_amax, s)) != hipSuccess) { st = hip_fail(e, "fit range"); break; }
-        double amax = 0.0;
-        if ((e = hipMemcpyAsync(&amax, d_amax, sizeof(double), hipMemcpyDeviceToHost, s)) != hipSuccess) { st = hip_fail(e, "copy"); break; }
-        if ((e = hipStreamSynchronize(s)) != hipSuccess) { st = hip_fail(e, "fit sync"); break; }
-        b->range_A = (float)amax;
-        st = upload_basis(b);
-    } while (0);
-    (void)hipFree(d_stat);
-    if (d_t0) (void)hipFree(d_t0);
-    if (d_mu) (void)hipFree(d_mu);
+    std::vector<double> sum, m2;
+    fmtc_status st = device_moments(d_x, N, C, HW, layout, s, &sum, &m2);
+    if (st != FMTC_OK) return st;
+    std::vector<double> mean(C);
+    for (int c = 0; c < C; c++) mean[c] = sum[c] / (double)P;
+    for (size_t i = 0; i < m2.size(); i++) m2[i] /= (double)P;
+    return finish_fit(C, mean, m2, d_x, N, HW, layout, s, out);
+}
+
+struct fmtc_fit_state {
+    int C = 0;
+    int64_t count = 0;            // pixels seen so far
+    std::vector<double> mean, m2;  // channel mean; sum of (x - mean)(x - mean)^T over those pixels
+};
+
+fmtc_status fmtc_fit_state_create(int C, fmtc_fit_state** out) {
+    if (!out) return fail(FMTC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (C < 1 || C > 1024) return fail(FMTC_EINVAL, "bad channel count %d", C);
+    fmtc_fit_state* f = new (std::nothrow) fmtc_fit_state;
+    if (!f) return fail(FMTC_ENOMEM, "host allocation failed");
+    f->C = C;
+    f->mean.assign(C, 0.0);
+    f->m2.assign((size_t)C * C, 0.0);
+    *out = f;
+    return FMTC_OK;
+}
+
+void fmtc_fit_state_destroy(fmtc_fit_state* state) { delete state; }
+
+int64_t fmtc_fit_state_count(const fmtc_fit_state* state) { return state ? state->count : 0; }
+
+fmtc_status fmtc_fit_state_update(fmtc_fit_state* state, const float* d_x, int64_t N, int C, int H, int W,
+                                  fmtc_layout layout, void* hip_stream) {
+    if (!state || !d_x) return fail(FMTC_EINVAL, "NULL argument");
+    if (!dims_ok(N, C, H, W) || state->C != C) return fail(FMTC_EINVAL, "bad dims or state has %d channels, tensor %d", state->C, C);
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    const int64_t HW = (int64_t)H * W, nb = N * HW;
+    std::vector<double> sum, m2b;
+    fmtc_status st = device_moments(d_x, N, C, HW, layout, (hipStream_t)hip_stream, &sum, &m2b);
+    if (st != FMTC_OK) return st;
+    // union of two pixel sets from their counts, means and centred second moments:
+    // M2 = M2_a + M2_b + (n_a n_b / n) d d^T, mean = mean_a + (n_b / n) d, d = mean_b - mean_a
+    const double na = (double)state->count, n = na + (double)nb;
+    std::vector<double> d(C);
+    for (int c = 0; c < C; c++) d[c] = sum[c] / (double)nb - state->mean[c];
+    const double w = na * (double)nb / n;
+    for (int i = 0; i < C; i++)
+        for (int j = 0; j < C; j++) state->m2[(size_t)i * C + j] += m2b[(size_t)i * C + j] + w * d[i] * d[j];
+    for (int c = 0; c < C; c++) state->mean[c] += d[c] * ((double)nb / n);
+    state->count += nb;
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_fit_state_basis(const fmtc_fit_state* state, const float* d_x, int64_t N, int C, int H, int W,
+                                 fmtc_layout layout, void* hip_stream, fmtc_basis** out) {
+    if (!out) return fail(FMTC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!state || !d_x) return fail(FMTC_EINVAL, "NULL argument");
+    if (!dims_ok(N, C, H, W) || state->C != C) return fail(FMTC_EINVAL, "bad dims or state has %d channels, tensor %d", state->C, C);
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    if (state->count < 1) return fail(FMTC_EINVAL, "the state has seen no pixels");
+    std::vector<double> cov(state->m2);
+    for (size_t i = 0; i < cov.size(); i++) cov[i] /= (double)state->count;
+    return finish_fit(C, state->mean, cov, d_x, N, (int64_t)H * W, layout, (hipStream_t)hip_stream, out);
+}
+
+fmtc_status fmtc_basis_truncate(const fmtc_basis* basis, int keep, fmtc_basis** out) {
+    if (!out) return fail(FMTC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!basis) return fail(FMTC_EINVAL, "basis is NULL");
+    if (keep < 1 || keep > basis->C) return fail(FMTC_EINVAL, "keep must be in [1,%d], got %d", basis->C, keep);
+    fmtc_basis* b = new (std::nothrow) fmtc_basis;
+    if (!b) return fail(FMTC_ENOMEM, "host allocation failed");
+    const int C = basis->C;
+    b->C = C;
+    b->Cpad = basis->Cpad;
+    b->range_A = basis->range_A;
+    b->T = basis->T;
+    b->mu = basis->mu;
+    b->eig = basis->eig;
+    for (size_t i = (size_t)keep * C; i < (size_t)C * C; i++) b->T[i] = 0.f;
+    fmtc_status st = upload_basis(b);
     if (st != FMTC_OK) {
         fmtc_basis_destroy(b);
         return st;

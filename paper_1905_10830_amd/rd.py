@@ -49,6 +49,22 @@ def sweep(basis, x, bits_list=(8, 7, 6, 5, 4, 3, 2), layout=fmtc.NHWC):
     return out
 
 
+def truncation_sweep(basis, x, bits, keeps, layout=fmtc.NHWC):
+    """Rate and distortion against the number of principal components kept (section 4 "Ablation study": dropping
+    the least significant components trades projection work against rate and error).  -> list of dicts with keep,
+    work (share of the projection's multiply-adds that the kept rows need) and the fields of sweep()."""
+    out = []
+    C = basis.C
+    for keep in keeps:
+        t = basis.truncate(keep)
+        row = sweep(t, x, (bits,), layout)[0]
+        t.close()
+        row["keep"] = keep
+        row["work"] = keep / C
+        out.append(row)
+    return out
+
+
 def main():
     import argparse
 
@@ -58,6 +74,8 @@ def main():
 
     ap = argparse.ArgumentParser(description="rate-distortion table of a synthetic workload")
     ap.add_argument("--workload", default="resnet18_stage2_c128_28", choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--truncate-at", type=int, default=0, metavar="BITS",
+                    help="also print the table over the number of components kept, at this bit depth")
     args = ap.parse_args()
     calib, data = synth.workload(args.workload, seed=0)
     basis = fmtc.fit_basis(torch.from_numpy(calib).cuda())
@@ -65,6 +83,13 @@ def main():
     for r in sweep(basis, torch.from_numpy(data).cuda()):
         print(f"  {r['bits']:4d}  {r['delta']:.5f}  {r['entropy']:.4f}  {r['rate']:.4f}  {r['container']:.4f}  "
               f"{r['mse']:.4e}  {r['psnr']:.2f}")
+    if args.truncate_at:
+        C = basis.C
+        keeps = sorted({max(1, C * k // 8) for k in range(1, 9)})
+        print(f"{args.workload}, {args.truncate_at} bits: keep  work    H       R   container   mse        psnr")
+        for r in truncation_sweep(basis, torch.from_numpy(data).cuda(), args.truncate_at, keeps):
+            print(f"  {r['keep']:4d}  {r['work']:.3f}  {r['entropy']:.4f}  {r['rate']:.4f}  {r['container']:.4f}  "
+                  f"{r['mse']:.4e}  {r['psnr']:.2f}")
 
 
 if __name__ == "__main__":

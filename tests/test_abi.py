@@ -110,3 +110,23 @@ def test_fixed_table_argument_errors_are_reported_on_the_host(lib):
     st = lib.fmtc_fit_table(None, None, 1, 64, 8, 8, fmtc.NHWC, 4, None, ctypes.byref(out))
     assert st == fmtc.EINVAL
     lib.fmtc_table_destroy(None)  # a no-op
+
+
+def test_fit_state_and_truncation_argument_errors_are_reported_on_the_host(lib):
+    """A fit state lives on the host; its argument checks and those of the truncation need no GPU."""
+    st = ctypes.c_void_p()
+    assert lib.fmtc_fit_state_create(0, ctypes.byref(st)) == fmtc.EINVAL
+    assert lib.fmtc_fit_state_create(2000, ctypes.byref(st)) == fmtc.EINVAL
+    assert lib.fmtc_fit_state_create(16, None) == fmtc.EINVAL
+    assert lib.fmtc_fit_state_create(16, ctypes.byref(st)) == fmtc.OK and st.value
+    assert lib.fmtc_fit_state_count(st) == 0
+    assert lib.fmtc_fit_state_count(None) == 0
+    assert lib.fmtc_fit_state_update(st, None, 1, 16, 4, 4, fmtc.NHWC, None) == fmtc.EINVAL
+    assert lib.fmtc_fit_state_update(None, None, 1, 16, 4, 4, fmtc.NHWC, None) == fmtc.EINVAL
+    out = ctypes.c_void_p()
+    assert lib.fmtc_fit_state_basis(st, None, 1, 16, 4, 4, fmtc.NHWC, None, ctypes.byref(out)) == fmtc.EINVAL
+    assert lib.fmtc_fit_state_basis(st, None, 1, 16, 4, 4, fmtc.NHWC, None, None) == fmtc.EINVAL
+    lib.fmtc_fit_state_destroy(st)
+    lib.fmtc_fit_state_destroy(None)  # a no-op
+    assert lib.fmtc_basis_truncate(None, 4, ctypes.byref(out)) == fmtc.EINVAL
+    assert lib.fmtc_basis_truncate(None, 4, None) == fmtc.EINVAL

@@ -1,0 +1,219 @@
+"""GPU parity of the truncated basis (section 4 'Ablation study': least significant principal components
+dropped) and of the calibration over several tensors (section 3.1 'Linear transform'), through the C ABI,
+against the CPU oracle.  Same bars as the other parity tests."""
+import numpy as np
+import pytest
+
+from paper_1905_10830_amd import synth
+from test_gpu_parity import RECON_TOL, check_symbols, dev, make_case
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fmtc():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1905_10830_amd import binding
+
+    binding.load_library()
+    return binding
+
+
+# (C, H, W, data images, rank, act, bits, keep): every projection / decoder kernel family, keep on and off tile edges
+CASES = [
+    (64, 20, 20, 2, 16, "relu", 6, 9),
+    (128, 28, 28, 2, 32, "relu", 6, 32),
+    (128, 14, 14, 3, 32, "relu", 4, 127),
+    (256, 14, 14, 5, 64, "relu", 4, 40),     # tiled matrix-product kernels, three coefficient tiles of zeros
+    (512, 7, 7, 9, 128, "relu", 5, 130),
+    (200, 6, 7, 3, 25, "relu", 5, 17),       # channel count that is no multiple of 16
+    (50, 10, 10, 2, 10, "relu", 5, 1),
+    (3, 17, 5, 1, 2, "none", 2, 2),
+]
+IDS = [f"C{c[0]}_keep{c[7]}_b{c[6]}" for c in CASES]
+
+
+@pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+def test_truncated_encode_matches_oracle(fmtc, oracle, case, layout):
+    C, H, W, ndat, rank, act, bits, keep = case
+    xs, T, mu, A = make_case(oracle, C, H, W, 0, ndat, rank, act, 500 + C, layout)
+    d = oracle.delta(A, bits)
+    enc = oracle.encode_keep(xs, T, mu, d, bits, keep, layout, want_margin=True)
+    full = fmtc.basis_import(T, mu, A)
+    basis = full.truncate(keep)
+    sym, hist = fmtc.quantize(basis, dev(xs), bits, layout)
+    stream, nbytes = fmtc.encode(basis, dev(xs), bits, layout)
+    torch.cuda.synchronize()
+    sym = sym.cpu().numpy().reshape(-1, C)
+    assert (sym[:, keep:] == 1 << (bits - 1)).all(), "a dropped coefficient must be the zero level"
+    n_bad = check_symbols(sym, enc["sym"], enc["margin"])
+    n = int(nbytes.item())
+    got = stream[:n].cpu().numpy()
+    sym_gpu, d2, pbits = oracle.unpack(got, xs.size // C, C, bits)
+    assert np.array_equal(sym_gpu.reshape(-1, C), sym)
+    if n_bad == 0:
+        assert np.array_equal(got, enc["stream"])
+    else:
+        h = oracle.histogram(sym_gpu, bits)
+        ln = oracle.huffman_lengths(h[: 1 << bits])
+        assert np.array_equal(got, oracle.pack(sym_gpu, C, bits, d, ln, oracle.canonical_codes(ln)))
+
+
+@pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+def test_truncated_decode_matches_oracle(fmtc, oracle, case, layout):
+    C, H, W, ndat, rank, act, bits, keep = case
+    xs, T, mu, A = make_case(oracle, C, H, W, 0, ndat, rank, act, 600 + C, layout)
+    d = oracle.delta(A, bits)
+    enc = oracle.encode_keep(xs, T, mu, d, bits, keep, layout)
+    want = oracle.reconstruct_keep(enc["sym"], xs.shape, T, mu, d, bits, keep, layout)
+    basis = fmtc.basis_import(T, mu, A).truncate(keep)
+    xhat, err = fmtc.decode(basis, dev(enc["stream"]), xs.shape, bits, layout)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    assert np.abs(xhat.cpu().numpy().astype(np.float64) - want).max() <= RECON_TOL
+    # whatever a stream holds in the dropped positions does not reach the output
+    junk = enc["sym"].copy()
+    junk[:, keep:] = np.random.default_rng(C).integers(0, 1 << bits, size=junk[:, keep:].shape)
+    h = oracle.histogram(junk, bits)
+    ln = oracle.huffman_lengths(h[: 1 << bits])
+    s2 = oracle.pack(junk, C, bits, d, ln, oracle.canonical_codes(ln))
+    xhat2, err2 = fmtc.decode(basis, dev(s2), xs.shape, bits, layout)
+    torch.cuda.synchronize()
+    assert int(err2.item()) == 0
+    assert np.abs(xhat2.cpu().numpy().astype(np.float64) - want).max() <= RECON_TOL
+
+
+def test_truncated_handle(fmtc, oracle):
+    s = synth.FeatureMapStream(C=24, H=8, W=8, rank=6, act="relu", seed=12)
+    x = s.images(2)
+    T, mu, eig, A = oracle.fit(x)
+    full = fmtc.basis_import(T, mu, A)
+    t = full.truncate(7)
+    T2, mu2, eig2, A2 = t.export()
+    assert np.array_equal(T2[:7], T[:7]) and (T2[7:] == 0).all()
+    assert np.array_equal(mu2, mu) and A2 == A and t.C == 24
+    same = full.truncate(24)
+    assert np.array_equal(same.export()[0], T)
+    for bad in (0, -3, 25):
+        with pytest.raises(fmtc.FmtcError) as e:
+            full.truncate(bad)
+        assert e.value.status == fmtc.EINVAL
+    # the two handles are independent
+    t.close()
+    same.close()
+    ref_sym, margin = oracle.quantize(oracle.project(x, T, mu), oracle.delta(A, 6), 6, want_margin=True)
+    sym, _ = fmtc.quantize(full, dev(x), 6)
+    torch.cuda.synchronize()
+    check_symbols(sym.cpu().numpy(), ref_sym, margin)
+    # a fitted basis keeps its eigenvalues through truncation
+    fitted = fmtc.fit_basis(dev(x))
+    assert np.array_equal(fitted.truncate(3).export()[2], fitted.export()[2])
+
+
+def test_truncated_static_table_round_trip(fmtc, oracle):
+    """The fixed-table entry points take a truncated basis like any other."""
+    s = synth.FeatureMapStream(C=128, H=14, W=14, rank=32, act="relu", seed=21)
+    cal, x = s.images(2), s.images(4)
+    T, mu, eig, A = oracle.fit(cal)
+    bits, keep = 6, 20
+    d = oracle.delta(A, bits)
+    basis = fmtc.basis_import(T, mu, A).truncate(keep)
+    table = fmtc.fit_table(basis, dev(cal), bits)
+    cal_sym = oracle.quantize(oracle.project_keep(cal, T, mu, keep), d, bits)
+    sym, _ = fmtc.quantize(basis, dev(cal), bits)
+    torch.cuda.synchronize()
+    if np.array_equal(sym.cpu().numpy().reshape(cal_sym.shape), cal_sym):
+        ln = oracle.static_lengths(oracle.histogram(cal_sym, bits)[: 1 << bits])
+        assert np.array_equal(table.export()[0][: 1 << bits], ln)
+    stream, nbytes = fmtc.encode_static(basis, table, dev(x))
+    xhat, err = fmtc.decode_static(basis, table, stream, x.shape)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    sym_gpu, d2, pbits = oracle.unpack(stream[: int(nbytes.item())].cpu().numpy(), x.size // 128, 128, bits)
+    assert (sym_gpu.reshape(-1, 128)[:, keep:] == 32).all()
+    want = oracle.reconstruct_keep(sym_gpu.reshape(-1, 128), x.shape, T, mu, d, bits, keep)
+    assert np.abs(xhat.cpu().numpy().astype(np.float64) - want).max() <= RECON_TOL
+
+
+@pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
+def test_fit_over_several_tensors_matches_oracle(fmtc, oracle, layout):
+    s = synth.FeatureMapStream(C=48, H=12, W=12, rank=12, act="relu", seed=78)
+    parts = [synth.to_layout(s.images(n), layout) for n in (1, 3, 2)]
+    T, mu, eig, A = oracle.fit_online(parts, parts[-1], layout)
+    st = fmtc.FitState(48)
+    assert st.count == 0
+    with pytest.raises(fmtc.FmtcError) as e:
+        st.basis(dev(parts[0]), layout)
+    assert e.value.status == fmtc.EINVAL
+    seen = 0
+    for p in parts:
+        st.update(dev(p), layout)
+        seen += p.size // 48
+        assert st.count == seen
+    basis = st.basis(dev(parts[-1]), layout)
+    Tg, mug, eigg, Ag = basis.export()
+    assert np.abs(mug - mu).max() <= 1e-7
+    assert np.allclose(eigg, eig, rtol=1e-9, atol=1e-12)
+    assert np.abs(Tg.astype(np.float64) @ Tg.T.astype(np.float64) - np.eye(48)).max() < 1e-6
+    gaps = np.minimum(np.abs(np.diff(eig, prepend=np.inf)), np.abs(np.diff(eig, append=-np.inf)))
+    sep = gaps > 1e-6 * eig[0]
+    assert sep.sum() >= 12
+    assert np.abs(Tg[sep] - T[sep]).max() < 1e-5
+    assert Ag == pytest.approx(float(A), rel=1e-6)
+    # the state is not consumed: one more tensor, and the basis is that of all four
+    more = synth.to_layout(s.images(2), layout)
+    st.update(dev(more), layout)
+    T4, mu4, eig4, A4 = oracle.fit_online(parts + [more], more, layout)
+    b4 = st.basis(dev(more), layout)
+    assert np.allclose(b4.export()[2], eig4, rtol=1e-9, atol=1e-12)
+    assert b4.export()[3] == pytest.approx(float(A4), rel=1e-6)
+    # tensors of another shape with the same channel count are fine; another channel count is refused
+    other = synth.to_layout(synth.FeatureMapStream(C=48, H=5, W=7, rank=12, act="relu", seed=79).images(1), layout)
+    st.update(dev(other), layout)
+    with pytest.raises(fmtc.FmtcError) as e:
+        st.update(dev(np.zeros((1, 4, 4, 32), np.float32)), synth.NHWC)
+    assert e.value.status == fmtc.EINVAL
+
+
+def test_one_update_is_the_plain_fit(fmtc, oracle):
+    s = synth.FeatureMapStream(C=40, H=9, W=9, rank=10, act="relu", seed=80)
+    x = s.images(3)
+    st = fmtc.FitState(40)
+    st.update(dev(x))
+    a, b = st.basis(dev(x)).export(), fmtc.fit_basis(dev(x)).export()
+    assert np.allclose(a[2], b[2], rtol=1e-12) and np.abs(a[1] - b[1]).max() <= 1e-7
+    assert a[3] == pytest.approx(float(b[3]), rel=1e-6)
+
+
+def test_truncation_sweep_against_the_oracle(fmtc, oracle):
+    """Rate and error over the number of components kept: the utility's numbers are the oracle's, and on the
+    calibration data the added error is the dropped eigenvalues' sum spread over the channels."""
+    from paper_1905_10830_amd import rd
+
+    s = synth.FeatureMapStream(64, 12, 12, 16, "relu", 1600)
+    x = s.images(4)
+    T, mu, eig, A = oracle.fit(x)
+    basis = fmtc.basis_import(T, mu, A)
+    bits = 6
+    d = oracle.delta(A, bits)
+    rows = rd.truncation_sweep(basis, torch.from_numpy(x).cuda(), bits, (64, 32, 12, 4))
+    prev = None
+    for r in rows:
+        keep = r["keep"]
+        assert r["work"] == keep / 64
+        enc = oracle.encode_keep(x, T, mu, d, bits, keep)
+        h = enc["hist"][: 1 << bits]
+        ln = oracle.huffman_lengths(h)
+        assert abs(r["entropy"] - oracle.entropy(h)) < 1e-3
+        assert abs(r["rate"] - float((h * ln.astype(np.uint64)).sum()) / x.size) < 1e-3
+        ref = oracle.mse(x, oracle.reconstruct_keep(enc["sym"], x.shape, T, mu, d, bits, keep))
+        assert abs(r["mse"] - ref) <= 1e-3 * ref + 1e-9
+        if prev is not None:
+            assert r["rate"] <= prev["rate"] and r["mse"] >= prev["mse"]
+            # quantization error of the kept coefficients shrinks with their number, truncation adds eig/C
+            assert r["mse"] == pytest.approx(eig[keep:].sum() / 64 + rows[0]["mse"] * keep / 64, rel=0.02)
+        prev = r
