@@ -169,6 +169,45 @@ def encode_keep(x, T, mu, dlt, bits, keep, layout=NHWC, chunk_syms=4096, want_ma
     return res
 
 
+def basis8(T, mu, act_scale):
+    """8-bit basis for 8-bit activations.  -> Tq int8 [C, C], s_T fp32, mean_fix int32 [C]."""
+    T, mu = _f32(T), _f32(mu)
+    c = T.shape[0]
+    Tq = np.empty((c, c), np.int8)
+    mf = np.empty(c, np.int32)
+    sT = ctypes.c_float(0)
+    _chk(lib().fmtc_oracle_basis8(_p(T), _p(mu), c, ctypes.c_float(float(act_scale)), _p(Tq), ctypes.byref(sT),
+                                  _p(mf)), "basis8")
+    return Tq, np.float32(sT.value), mf
+
+
+def quantize_u8(xq, Tq, scale_T, mean_fix, act_scale, dlt, bits, layout=NHWC):
+    """uint8 activations (4-d, given layout) -> symbols [P, C] under the 8-bit basis."""
+    xq = np.ascontiguousarray(xq, dtype=np.uint8)
+    Tq = np.ascontiguousarray(Tq, dtype=np.int8)
+    mf = np.ascontiguousarray(mean_fix, dtype=np.int32)
+    n, c, hw = _dims(xq, layout)
+    sym = np.empty((n * hw, c), np.uint8)
+    _chk(lib().fmtc_oracle_quantize_u8(_p(xq), ctypes.c_int64(n), c, ctypes.c_int64(hw), layout, _p(Tq),
+                                       ctypes.c_float(float(scale_T)), _p(mf), ctypes.c_float(float(act_scale)),
+                                       ctypes.c_float(float(dlt)), int(bits), _p(sym)), "quantize_u8")
+    return sym
+
+
+def reconstruct_u8(sym, shape, Tq, scale_T, mean_fix, act_scale, dlt, bits, layout=NHWC):
+    """symbols [P, C] -> uint8 activations of the given 4-d storage shape."""
+    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    Tq = np.ascontiguousarray(Tq, dtype=np.int8)
+    mf = np.ascontiguousarray(mean_fix, dtype=np.int32)
+    out = np.empty(shape, np.uint8)
+    n, c, hw = _dims(out, layout)
+    _chk(lib().fmtc_oracle_reconstruct_u8(_p(sym), ctypes.c_int64(n), c, ctypes.c_int64(hw), layout, _p(Tq),
+                                          ctypes.c_float(float(scale_T)), _p(mf),
+                                          ctypes.c_float(float(act_scale)), ctypes.c_float(float(dlt)), int(bits),
+                                          _p(out)), "reconstruct_u8")
+    return out
+
+
 def delta(range_A, bits):
     return np.float32(lib().fmtc_oracle_delta(ctypes.c_float(float(range_A)), int(bits)))
 

@@ -655,6 +655,97 @@ int fmtc_oracle_reconstruct_keep(const uint8_t *sym, int64_t N, int C, int64_t H
     return ORC_OK;
 }
 
+/* ------------------------------------------- 8-bit basis and 8-bit activations */
+
+/* Section 3.1 "Linear transform" stores the PCA matrix at 8 bits, and the
+ * hardware of section 5 moves 8-bit activations.  The arithmetic below is the
+ * integer reading of y = T (x - mu), Q, Q^-1 and x_hat = T^T y_hat + mu for
+ *   x   = s_x * xq,        xq unsigned 8-bit (post-activation maps),
+ *   T   = s_T * Tq,        Tq = clamp(rne(T / s_T), -127, 127), s_T = (float)(max|T| / 127),
+ *   mu  = s_x * mf / 256,  mf = rne(256 mu / s_x)   (the mean with 8 fraction bits on the activations' grid).
+ * Sums are exact integers; every rounding decision is one correctly rounded
+ * fp64 operation on exact operands, so an implementation either reproduces
+ * these results bit for bit or is wrong. */
+
+/* Tq (C*C, row major), s_T and mf (C) from the fp32 basis, mean and activation scale. */
+int fmtc_oracle_basis8(const float *T, const float *mu, int C, float act_scale, int8_t *Tq, float *scale_T,
+                       int32_t *mean_fix)
+{
+    if (!T || !mu || !Tq || !scale_T || !mean_fix || C < 1 || !(act_scale > 0.0f)) return ORC_EINVAL;
+    double amax = 0.0;
+    for (size_t i = 0; i < (size_t)C * C; i++)
+        if (fabs((double)T[i]) > amax) amax = fabs((double)T[i]);
+    float sT = (float)(amax / 127.0);
+    if (!(sT > 0.0f)) sT = 1.0f;
+    for (size_t i = 0; i < (size_t)C * C; i++) {
+        double r = nearbyint((double)T[i] / (double)sT);
+        if (r > 127.0) r = 127.0;
+        if (r < -127.0) r = -127.0;
+        Tq[i] = (int8_t)(int)r;
+    }
+    for (int c = 0; c < C; c++) mean_fix[c] = (int32_t)nearbyint((double)mu[c] / (double)act_scale * 256.0);
+    *scale_T = sT;
+    return ORC_OK;
+}
+
+/* Symbols of 8-bit activations under the 8-bit basis: for every pixel and
+ * coefficient k, n = 256 sum_c Tq[k][c] xq[c] - sum_c Tq[k][c] mf[c] (an exact
+ * integer, = 256 y / (s_T s_x)), level = rne(n * g) with the single fp64 factor
+ * g = (s_T s_x) / (256 Delta), clamped; symbol = level + 2^(b-1).  [P][C]. */
+int fmtc_oracle_quantize_u8(const uint8_t *xq, int64_t N, int C, int64_t HW, int layout, const int8_t *Tq,
+                            float scale_T, const int32_t *mean_fix, float act_scale, float delta, int bits,
+                            uint8_t *sym)
+{
+    if (!xq || !Tq || !mean_fix || !sym || N < 1 || C < 1 || HW < 1 || bits < 2 || bits > 8) return ORC_EINVAL;
+    if (!(scale_T > 0.0f) || !(act_scale > 0.0f) || !(delta > 0.0f)) return ORC_EINVAL;
+    const double g = ((double)scale_T * (double)act_scale) / (256.0 * (double)delta);
+    const double half = (double)(1 << (bits - 1));
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t hw = 0; hw < HW; hw++) {
+            size_t p = (size_t)n * (size_t)HW + (size_t)hw;
+            for (int k = 0; k < C; k++) {
+                int64_t dot = 0, off = 0;
+                for (int c = 0; c < C; c++) {
+                    dot += (int64_t)Tq[(size_t)k * C + c] * (int64_t)xq[x_index(layout, n, c, hw, C, HW)];
+                    off += (int64_t)Tq[(size_t)k * C + c] * (int64_t)mean_fix[c];
+                }
+                double r = nearbyint((double)(256 * dot - off) * g);
+                if (r < -half) r = -half;
+                if (r > half - 1.0) r = half - 1.0;
+                sym[p * (size_t)C + k] = (uint8_t)(int)(r + half);
+            }
+        }
+    return ORC_OK;
+}
+
+/* 8-bit activations back from symbols: with levels q = s - 2^(b-1) and the exact
+ * integer m = sum_k Tq[k][c] q[k], the value on the activations' grid with 8
+ * fraction bits is v = fma(m, h, mf[c]), h = (s_T Delta 256) / s_x (one fused
+ * fp64 operation), and xq_hat = clamp(rne(v / 256), 0, 255). */
+int fmtc_oracle_reconstruct_u8(const uint8_t *sym, int64_t N, int C, int64_t HW, int layout, const int8_t *Tq,
+                               float scale_T, const int32_t *mean_fix, float act_scale, float delta, int bits,
+                               uint8_t *xq_hat)
+{
+    if (!sym || !Tq || !mean_fix || !xq_hat || N < 1 || C < 1 || HW < 1 || bits < 2 || bits > 8) return ORC_EINVAL;
+    if (!(scale_T > 0.0f) || !(act_scale > 0.0f) || !(delta > 0.0f)) return ORC_EINVAL;
+    const double h = ((double)scale_T * (double)delta * 256.0) / (double)act_scale;
+    const int halfk = 1 << (bits - 1);
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t hw = 0; hw < HW; hw++) {
+            size_t p = (size_t)n * (size_t)HW + (size_t)hw;
+            for (int c = 0; c < C; c++) {
+                int64_t m = 0;
+                for (int k = 0; k < C; k++)
+                    m += (int64_t)Tq[(size_t)k * C + c] * (int64_t)((int)sym[p * (size_t)C + k] - halfk);
+                double r = nearbyint(fma((double)m, h, (double)mean_fix[c]) / 256.0);
+                if (r < 0.0) r = 0.0;
+                if (r > 255.0) r = 255.0;
+                xq_hat[x_index(layout, n, c, hw, C, HW)] = (uint8_t)(int)r;
+            }
+        }
+    return ORC_OK;
+}
+
 /* D = (1/n) ||x - x_hat||^2 (section 3). */
 double fmtc_oracle_mse(const float *x, const double *xhat, int64_t count)
 {
