@@ -235,6 +235,46 @@ fmtc_status fmtc_stream_info(const void *h_header, size_t header_bytes, int *bit
                              int *px_per_chunk, int64_t *n_chunks, float *delta, uint64_t *payload_bits,
                              uint64_t *stream_bytes);
 
+/* ---- 8-bit basis, 8-bit activations ----
+ * Section 3.1 "Linear transform" stores the PCA matrix at 8 bits; the hardware
+ * of section 5 moves 8-bit activations.  Reading taken here, for unsigned
+ * 8-bit activations xq with x = act_scale * xq (post-activation maps):
+ *   Tq = clamp(rne(T / s_T), -127, 127), s_T = (float)(max|T| / 127);
+ *   mf[c] = rne(256 mu[c] / act_scale)   (the mean with 8 fraction bits);
+ *   forward: n = 256 sum_c Tq[k][c] xq[c] - sum_c Tq[k][c] mf[c] (exact),
+ *            level = clamp(rne(n * g)), g = (s_T act_scale) / (256 Delta) in fp64,
+ *            symbol = level + 2^(bits-1);  Delta = fmtc_delta(A of the basis, bits);
+ *   inverse: m = sum_k Tq[k][c] (s[k] - 2^(bits-1)) (exact), v = fma(m, h, mf[c]),
+ *            h = (s_T Delta 256) / act_scale in fp64, xq^ = clamp(rne(v / 256), 0, 255).
+ * Both contractions run on the integer matrix cores and every rounding is one
+ * fp64 operation on exact operands: the results are defined bit for bit.
+ * The symbols feed the same coder and container as the fp32 path.
+ * fmtc_basis8_create derives the 8-bit basis from an fp32 one (host work plus
+ * a device upload; `basis` stays valid and independent).  Export pointers may
+ * be NULL (h_Tq: C*C row major, h_mean_fix: C). */
+typedef struct fmtc_basis8 fmtc_basis8;
+fmtc_status fmtc_basis8_create(const fmtc_basis *basis, float act_scale, fmtc_basis8 **out);
+fmtc_status fmtc_basis8_export(const fmtc_basis8 *basis, int8_t *h_Tq, float *scale_T, int32_t *h_mean_fix,
+                               float *act_scale, float *range_A);
+void fmtc_basis8_destroy(fmtc_basis8 *basis);
+/* Staged: activations (uint8, N*C*H*W in `layout`, 16-byte aligned) -> symbols
+ * [P][C] (16-byte aligned), and symbols -> activations.  Asynchronous. */
+fmtc_status fmtc_quantize_u8(const fmtc_basis8 *basis, const uint8_t *d_xq, int64_t N, int C, int H, int W,
+                             fmtc_layout layout, int bits, uint8_t *d_syms, void *hip_stream);
+fmtc_status fmtc_reconstruct_u8(const fmtc_basis8 *basis, const uint8_t *d_syms, int64_t N, int C, int H, int W,
+                                fmtc_layout layout, int bits, uint8_t *d_xq_hat, void *hip_stream);
+/* Whole encoder / decoder on 8-bit activations: fmtc_quantize_u8 followed by
+ * the coder of fmtc_code_symbols (same stream, bound and workspace size as
+ * fmtc_encode), and fmtc_decode_symbols followed by fmtc_reconstruct_u8 (the
+ * decoder's workspace holds the symbols: at least P*C bytes, 16-byte aligned).
+ * Errors and *d_err_flag as for fmtc_encode / fmtc_decode. */
+fmtc_status fmtc_encode_u8(const fmtc_basis8 *basis, const uint8_t *d_xq, int64_t N, int C, int H, int W,
+                           fmtc_layout layout, int bits, int chunk_syms, void *d_stream_out, size_t cap,
+                           uint64_t *d_out_bytes, void *d_workspace, size_t ws_bytes, void *hip_stream);
+fmtc_status fmtc_decode_u8(const fmtc_basis8 *basis, const void *d_stream_in, size_t bytes, uint8_t *d_xq_hat,
+                           int64_t N, int C, int H, int W, fmtc_layout layout, int bits, uint32_t *d_err_flag,
+                           void *d_workspace, size_t ws_bytes, void *hip_stream);
+
 /* ---- instrumentation (not part of the method) ----
  * fmtc_profile_enable(n > 0) creates n HIP event pairs per kernel; from then on
  * every kernel launch of the library carries a pair attached to its own

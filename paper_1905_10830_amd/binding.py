@@ -23,6 +23,8 @@ EXPORTS = [
     "fmtc_encode_static", "fmtc_decode_static",
     "fmtc_fit_state_create", "fmtc_fit_state_update", "fmtc_fit_state_basis", "fmtc_fit_state_count",
     "fmtc_fit_state_destroy", "fmtc_basis_truncate",
+    "fmtc_basis8_create", "fmtc_basis8_export", "fmtc_basis8_destroy", "fmtc_quantize_u8", "fmtc_reconstruct_u8",
+    "fmtc_encode_u8", "fmtc_decode_u8",
     "fmtc_profile_enable", "fmtc_profile_kernels", "fmtc_profile_name", "fmtc_profile_read", "fmtc_profile_copy",
 ]
 
@@ -60,6 +62,14 @@ def load_library():
     lib.fmtc_fit_state_destroy.argtypes = [vp]
     lib.fmtc_fit_state_destroy.restype = None
     lib.fmtc_basis_truncate.argtypes = [vp, i32, ctypes.POINTER(vp)]
+    lib.fmtc_basis8_create.argtypes = [vp, f32, ctypes.POINTER(vp)]
+    lib.fmtc_basis8_export.argtypes = [vp, vp, ctypes.POINTER(f32), vp, ctypes.POINTER(f32), ctypes.POINTER(f32)]
+    lib.fmtc_basis8_destroy.argtypes = [vp]
+    lib.fmtc_basis8_destroy.restype = None
+    lib.fmtc_quantize_u8.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp]
+    lib.fmtc_reconstruct_u8.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp]
+    lib.fmtc_encode_u8.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp, sz, vp]
+    lib.fmtc_decode_u8.argtypes = [vp, vp, sz, vp, i64, i32, i32, i32, i32, i32, vp, vp, sz, vp]
     lib.fmtc_delta.argtypes = [f32, i32]
     lib.fmtc_delta.restype = f32
     lib.fmtc_encode_bound.argtypes = [i64, i32, i32, i32]
@@ -171,6 +181,99 @@ def fit_basis(x, layout=NHWC):
     out = ctypes.c_void_p()
     _check(load_library().fmtc_fit_basis(_dev(x, torch.float32), n, c, h, w, layout, _stream(), ctypes.byref(out)))
     return Basis(out)
+
+
+class Basis8:
+    """Owns an fmtc_basis8 handle: the 8-bit basis for unsigned 8-bit activations x = act_scale * xq."""
+
+    def __init__(self, basis, act_scale):
+        self._h = ctypes.c_void_p()
+        _check(load_library().fmtc_basis8_create(basis._h, float(act_scale), ctypes.byref(self._h)))
+        self.C = basis.C
+
+    def export(self):
+        """-> Tq int8 (C,C), s_T, mean_fix int32 (C), act_scale, range A."""
+        import numpy as np
+
+        Tq = np.empty((self.C, self.C), np.int8)
+        mf = np.empty(self.C, np.int32)
+        sT, sx, A = ctypes.c_float(0), ctypes.c_float(0), ctypes.c_float(0)
+        _check(load_library().fmtc_basis8_export(self._h, Tq.ctypes.data, ctypes.byref(sT), mf.ctypes.data,
+                                                 ctypes.byref(sx), ctypes.byref(A)))
+        return Tq, np.float32(sT.value), mf, np.float32(sx.value), np.float32(A.value)
+
+    def close(self):
+        if self._h:
+            load_library().fmtc_basis8_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def quantize_u8(basis8, xq, bits, layout=NHWC, syms=None):
+    """Asynchronous.  xq: uint8 device tensor (4-d).  -> symbols uint8 [P, C]."""
+    import torch
+
+    n, c, h, w = _dims(xq, layout)
+    if syms is None:
+        syms = torch.empty((n * h * w, c), dtype=torch.uint8, device=xq.device)
+    _check(load_library().fmtc_quantize_u8(basis8._h, _dev(xq, torch.uint8), n, c, h, w, layout, bits,
+                                           _dev(syms, torch.uint8), _stream()))
+    return syms
+
+
+def reconstruct_u8(basis8, syms, shape, bits, layout=NHWC, out=None):
+    """Asynchronous.  symbols [P, C] -> uint8 activations of the 4-d `shape`."""
+    import torch
+
+    if out is None:
+        out = torch.empty(tuple(shape), dtype=torch.uint8, device=syms.device)
+    n, c, h, w = _dims(out, layout)
+    _check(load_library().fmtc_reconstruct_u8(basis8._h, _dev(syms, torch.uint8), n, c, h, w, layout, bits,
+                                              _dev(out, torch.uint8), _stream()))
+    return out
+
+
+def encode_u8(basis8, xq, bits, layout=NHWC, chunk_syms=4096, stream_out=None, out_bytes=None, workspace=None):
+    """Asynchronous.  -> (stream_out uint8 tensor of capacity encode_bound, out_bytes int64[1] device tensor)."""
+    import torch
+
+    n, c, h, w = _dims(xq, layout)
+    P = n * h * w
+    if stream_out is None:
+        stream_out = torch.empty(encode_bound(P, c, bits, chunk_syms), dtype=torch.uint8, device=xq.device)
+    if out_bytes is None:
+        out_bytes = torch.zeros(1, dtype=torch.int64, device=xq.device)
+    if workspace is None:
+        workspace = torch.empty(workspace_size(P, c, bits, chunk_syms), dtype=torch.uint8, device=xq.device)
+    _check(load_library().fmtc_encode_u8(basis8._h, _dev(xq, torch.uint8), n, c, h, w, layout, bits, chunk_syms,
+                                         _dev(stream_out, torch.uint8), stream_out.numel(),
+                                         ctypes.c_void_p(out_bytes.data_ptr()), _dev(workspace, torch.uint8),
+                                         workspace.numel(), _stream()))
+    return stream_out, out_bytes
+
+
+def decode_u8(basis8, stream_in, shape, bits, layout=NHWC, out=None, err_flag=None, nbytes=None, workspace=None):
+    """Asynchronous.  -> (uint8 activations of `shape`, err_flag int32[1] device tensor)."""
+    import torch
+
+    if out is None:
+        out = torch.empty(tuple(shape), dtype=torch.uint8, device=stream_in.device)
+    if err_flag is None:
+        err_flag = torch.zeros(1, dtype=torch.int32, device=stream_in.device)
+    n, c, h, w = _dims(out, layout)
+    if workspace is None:
+        workspace = torch.empty(n * h * w * c, dtype=torch.uint8, device=stream_in.device)
+    _check(load_library().fmtc_decode_u8(basis8._h, _dev(stream_in, torch.uint8),
+                                         stream_in.numel() if nbytes is None else int(nbytes),
+                                         _dev(out, torch.uint8), n, c, h, w, layout, bits,
+                                         ctypes.c_void_p(err_flag.data_ptr()), _dev(workspace, torch.uint8),
+                                         workspace.numel(), _stream()))
+    return out, err_flag
 
 
 class FitState:

@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfmtc.so")
 SOURCES = ["fmtc_api.hip", "fmtc_encode_kernels.hip", "fmtc_coder_kernels.hip", "fmtc_decode_kernels.hip",
-           "fmtc_fit_kernels.hip", "fmtc_profile.hip"]
+           "fmtc_fit_kernels.hip", "fmtc_int8_kernels.hip", "fmtc_profile.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall",
          # packed fp32 VALU forms are kept off on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -30,6 +30,16 @@ struct fmtc_table {
     int device = 0;
 };
 
+struct fmtc_basis8 {
+    int C = 0;
+    float scale_T = 1.f, act_scale = 1.f, range_A = 0.f;
+    std::vector<int8_t> Tq;         // [C][C]
+    std::vector<int32_t> mean_fix;  // [C]
+    void* d_block = nullptr;        // one allocation: fwd8, inv8, row_off, col_sum, mean_fix
+    fmtc::Basis8Device view{};
+    int device = 0;
+};
+
 namespace {
 
 using namespace fmtc;
@@ -310,6 +320,64 @@ fmtc_status finish_fit(int C, const std::vector<double>& mean, std::vector<doubl
         return st;
     }
     *out = b;
+    return FMTC_OK;
+}
+
+
+// Tq or its transpose in the operand order of the integer matrix instruction: for tile t (32 rows), step j (16
+// columns) lane l holds the 8 bytes M[32 t + perm(l % 32)][16 j + 8 (l / 32) + e], perm as in pack_operand16.
+void pack_operand8(const std::vector<int8_t>& Tq, int C, bool transpose, std::vector<unsigned long long>* out) {
+    const int nct = (C + 31) / 32, NS = (C + 15) / 16;
+    out->assign((size_t)nct * NS * 64, 0ull);
+    for (int t = 0; t < nct; t++)
+        for (int j = 0; j < NS; j++)
+            for (int lane = 0; lane < 64; lane++) {
+                const int r = lane % 32, half = lane / 32;
+                const int row = t * 32 + 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);
+                unsigned long long v = 0ull;
+                for (int e = 0; e < 8; e++) {
+                    const int col = 16 * j + 8 * half + e;
+                    int8_t b = 0;
+                    if (row < C && col < C) b = transpose ? Tq[(size_t)col * C + row] : Tq[(size_t)row * C + col];
+                    v |= (unsigned long long)(uint8_t)b << (8 * e);
+                }
+                (*out)[((size_t)t * NS + j) * 64 + lane] = v;
+            }
+}
+
+fmtc_status upload_basis8(fmtc_basis8* b) {
+    const int C = b->C, nct = (C + 31) / 32, NS = (C + 15) / 16, rows = nct * 32;
+    std::vector<unsigned long long> fwd, inv;
+    pack_operand8(b->Tq, C, false, &fwd);
+    pack_operand8(b->Tq, C, true, &inv);
+    std::vector<long long> row_off(rows, 0);
+    std::vector<int> col_sum(rows, 0), mean_fix(rows, 0);
+    for (int k = 0; k < C; k++)
+        for (int c = 0; c < C; c++) {
+            const long long t = b->Tq[(size_t)k * C + c];
+            row_off[k] += t * ((long long)b->mean_fix[c] - 256ll * 128ll);
+            col_sum[c] += (int)t;
+        }
+    for (int c = 0; c < C; c++) mean_fix[c] = b->mean_fix[c];
+    const size_t n_op = (size_t)nct * NS * 64 * sizeof(unsigned long long);
+    const size_t o_inv = n_op, o_off = 2 * n_op, o_col = o_off + sizeof(long long) * rows,
+                 o_mean = o_col + sizeof(int) * rows, total = o_mean + sizeof(int) * rows;
+    hipError_t e;
+    if ((e = hipGetDevice(&b->device)) != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if ((e = hipMalloc(&b->d_block, total)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
+    uint8_t* d = static_cast<uint8_t*>(b->d_block);
+    if ((e = hipMemcpy(d, fwd.data(), n_op, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(d + o_inv, inv.data(), n_op, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(d + o_off, row_off.data(), sizeof(long long) * rows, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(d + o_col, col_sum.data(), sizeof(int) * rows, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(d + o_mean, mean_fix.data(), sizeof(int) * rows, hipMemcpyHostToDevice)) != hipSuccess)
+        return hip_fail(e, "hipMemcpy basis");
+    b->view.C = C;
+    b->view.fwd8 = reinterpret_cast<const unsigned long long*>(d);
+    b->view.inv8 = reinterpret_cast<const unsigned long long*>(d + o_inv);
+    b->view.row_off = reinterpret_cast<const long long*>(d + o_off);
+    b->view.col_sum = reinterpret_cast<const int*>(d + o_col);
+    b->view.mean_fix = reinterpret_cast<const int*>(d + o_mean);
     return FMTC_OK;
 }
 
@@ -811,6 +879,131 @@ fmtc_status fmtc_stream_info(const void* h_header, size_t header_bytes, int* bit
     if (payload_bits) *payload_bits = h.payload_bits;
     if (stream_bytes) *stream_bytes = off_pay + 4 * h.payload_words;
     return FMTC_OK;
+}
+
+
+fmtc_status fmtc_basis8_create(const fmtc_basis* basis, float act_scale, fmtc_basis8** out) {
+    if (!out) return fail(FMTC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!basis) return fail(FMTC_EINVAL, "basis is NULL");
+    if (!(act_scale > 0.f) || !std::isfinite(act_scale)) return fail(FMTC_EINVAL, "act_scale must be a positive number");
+    fmtc_basis8* b = new (std::nothrow) fmtc_basis8;
+    if (!b) return fail(FMTC_ENOMEM, "host allocation failed");
+    const int C = basis->C;
+    b->C = C;
+    b->act_scale = act_scale;
+    b->range_A = basis->range_A;
+    double amax = 0.0;
+    for (float v : basis->T) amax = std::fabs((double)v) > amax ? std::fabs((double)v) : amax;
+    b->scale_T = (float)(amax / 127.0);
+    if (!(b->scale_T > 0.f)) b->scale_T = 1.f;
+    b->Tq.resize((size_t)C * C);
+    for (size_t i = 0; i < b->Tq.size(); i++) {
+        double r = std::nearbyint((double)basis->T[i] / (double)b->scale_T);
+        r = r > 127.0 ? 127.0 : (r < -127.0 ? -127.0 : r);
+        b->Tq[i] = (int8_t)(int)r;
+    }
+    b->mean_fix.resize(C);
+    for (int c = 0; c < C; c++) {
+        const double m = std::nearbyint((double)basis->mu[c] / (double)act_scale * 256.0);
+        if (!(std::fabs(m) < 1073741824.0)) {
+            delete b;
+            return fail(FMTC_EINVAL, "mean of channel %d is out of range for this activation scale", c);
+        }
+        b->mean_fix[c] = (int32_t)m;
+    }
+    fmtc_status st = upload_basis8(b);
+    if (st != FMTC_OK) {
+        fmtc_basis8_destroy(b);
+        return st;
+    }
+    *out = b;
+    return FMTC_OK;
+}
+
+void fmtc_basis8_destroy(fmtc_basis8* b) {
+    if (!b) return;
+    if (b->d_block) (void)hipFree(b->d_block);
+    delete b;
+}
+
+fmtc_status fmtc_basis8_export(const fmtc_basis8* b, int8_t* h_Tq, float* scale_T, int32_t* h_mean_fix,
+                               float* act_scale, float* range_A) {
+    if (!b) return fail(FMTC_EINVAL, "basis is NULL");
+    if (h_Tq) memcpy(h_Tq, b->Tq.data(), b->Tq.size());
+    if (scale_T) *scale_T = b->scale_T;
+    if (h_mean_fix) memcpy(h_mean_fix, b->mean_fix.data(), sizeof(int32_t) * b->mean_fix.size());
+    if (act_scale) *act_scale = b->act_scale;
+    if (range_A) *range_A = b->range_A;
+    return FMTC_OK;
+}
+
+static fmtc_status check_u8_call(const fmtc_basis8* b, const void* a, const void* c, int64_t N, int C, int H, int W,
+                                 fmtc_layout layout, int bits) {
+    if (!b || !a || !c) return fail(FMTC_EINVAL, "NULL argument");
+    if (!dims_ok(N, C, H, W) || b->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", b->C, C);
+    if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
+    if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
+    if (!aligned(a, 16) || !aligned(c, 16)) return fail(FMTC_EINVAL, "misaligned pointer");
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_quantize_u8(const fmtc_basis8* basis, const uint8_t* d_xq, int64_t N, int C, int H, int W,
+                             fmtc_layout layout, int bits, uint8_t* d_syms, void* hip_stream) {
+    fmtc_status st = check_u8_call(basis, d_xq, d_syms, N, C, H, W, layout, bits);
+    if (st != FMTC_OK) return st;
+    const int64_t HW = (int64_t)H * W;
+    const double delta = (double)fmtc_delta(basis->range_A, bits);
+    const double g = ((double)basis->scale_T * (double)basis->act_scale) / (256.0 * delta);
+    hipError_t e = launch_quantize_u8(basis->view, d_xq, N * HW, HW, layout, bits, g, d_syms, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "8-bit projection kernel");
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_reconstruct_u8(const fmtc_basis8* basis, const uint8_t* d_syms, int64_t N, int C, int H, int W,
+                                fmtc_layout layout, int bits, uint8_t* d_xq_hat, void* hip_stream) {
+    fmtc_status st = check_u8_call(basis, d_syms, d_xq_hat, N, C, H, W, layout, bits);
+    if (st != FMTC_OK) return st;
+    const int64_t HW = (int64_t)H * W;
+    const double delta = (double)fmtc_delta(basis->range_A, bits);
+    const double h = ((double)basis->scale_T * delta * 256.0) / (double)basis->act_scale;
+    hipError_t e = launch_reconstruct_u8(basis->view, d_syms, N * HW, HW, layout, bits, h, d_xq_hat, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail(e, "8-bit reconstruction kernel");
+    return FMTC_OK;
+}
+
+fmtc_status fmtc_encode_u8(const fmtc_basis8* basis, const uint8_t* d_xq, int64_t N, int C, int H, int W,
+                           fmtc_layout layout, int bits, int chunk_syms, void* d_stream_out, size_t cap,
+                           uint64_t* d_out_bytes, void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!d_stream_out || !d_workspace) return fail(FMTC_EINVAL, "NULL argument");
+    fmtc_status st = check_u8_call(basis, d_xq, d_stream_out, N, C, H, W, layout, bits);
+    if (st != FMTC_OK) return st;
+    if (!aligned(d_workspace, 256) || !aligned(d_out_bytes, 8)) return fail(FMTC_EINVAL, "misaligned pointer");
+    EncodePlan pl;
+    const int64_t P = N * (int64_t)H * W;
+    st = plan_encode(P, C, bits, chunk_syms, &pl);
+    if (st != FMTC_OK) return st;
+    if (ws_bytes < pl.ws.total) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, pl.ws.total);
+    if (cap < bound_from(pl, bits)) return fail(FMTC_EBUFSIZE, "stream capacity too small: %zu < %zu", cap, bound_from(pl, bits));
+    uint8_t* syms = static_cast<uint8_t*>(d_workspace) + pl.ws.off_syms;
+    st = fmtc_quantize_u8(basis, d_xq, N, C, H, W, layout, bits, syms, hip_stream);
+    if (st != FMTC_OK) return st;
+    return fmtc_code_symbols(syms, P, C, bits, chunk_syms, fmtc_delta(basis->range_A, bits), d_stream_out, cap,
+                             d_out_bytes, d_workspace, ws_bytes, hip_stream);
+}
+
+fmtc_status fmtc_decode_u8(const fmtc_basis8* basis, const void* d_stream_in, size_t bytes, uint8_t* d_xq_hat,
+                           int64_t N, int C, int H, int W, fmtc_layout layout, int bits, uint32_t* d_err_flag,
+                           void* d_workspace, size_t ws_bytes, void* hip_stream) {
+    if (!d_workspace || !d_stream_in || !d_err_flag) return fail(FMTC_EINVAL, "NULL argument");
+    fmtc_status st = check_u8_call(basis, d_workspace, d_xq_hat, N, C, H, W, layout, bits);
+    if (st != FMTC_OK) return st;
+    const int64_t P = N * (int64_t)H * W;
+    if (ws_bytes < (size_t)P * (size_t)C) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, (size_t)P * (size_t)C);
+    uint8_t* syms = static_cast<uint8_t*>(d_workspace);
+    st = fmtc_decode_symbols(d_stream_in, bytes, P, C, bits, syms, d_err_flag, hip_stream);
+    if (st != FMTC_OK) return st;
+    return fmtc_reconstruct_u8(basis, syms, N, C, H, W, layout, bits, d_xq_hat, hip_stream);
 }
 
 }  // extern "C"

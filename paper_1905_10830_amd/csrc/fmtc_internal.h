@@ -123,7 +123,7 @@ struct BasisDevice {
 // ---- optional per-kernel timing (fmtc_profile_* in fmtc.h) ----
 // When enabled, a launch carries a pair of events that the runtime attaches to the kernel's own dispatch, so
 // the elapsed time is the kernel's start-to-end time on the GPU (no bracket of separate marker commands).
-enum KernelId { K_PROJECT = 0, K_HISTOGRAM, K_TABLE, K_PACK, K_DECODE, K_COPY, K_COUNT };
+enum KernelId { K_PROJECT = 0, K_HISTOGRAM, K_TABLE, K_PACK, K_DECODE, K_COPY, K_QUANTIZE_U8, K_RECONSTRUCT_U8, K_COUNT };
 bool prof_next(int id, hipEvent_t* start, hipEvent_t* stop);
 
 template <class T>
@@ -146,6 +146,21 @@ struct CoderScratch {
     unsigned long long* lookback;
     uint32_t n_groups;
 };
+
+// Device side of the 8-bit basis (fmtc_int8_kernels.hip).  nct = ceil(C / 32) tiles of 32 rows, NS = ceil(C / 16)
+// contraction steps; every per-row array is padded to nct * 32 entries.
+struct Basis8Device {
+    int C;
+    const unsigned long long* fwd8;  // [nct][NS][64] Tq, operand order, rows of a tile permuted
+    const unsigned long long* inv8;  // [nct][NS][64] Tq^T, the same
+    const long long* row_off;        // sum_c Tq[k][c] (mean_fix[c] - 256 * 128)
+    const int* col_sum;              // sum_k Tq[k][c]
+    const int* mean_fix;             // rne(256 mu[c] / s_x)
+};
+hipError_t launch_quantize_u8(const Basis8Device& b, const uint8_t* d_xq, int64_t P, int64_t HW, int layout,
+                              int bits, double g, uint8_t* d_syms, hipStream_t s);
+hipError_t launch_reconstruct_u8(const Basis8Device& b, const uint8_t* d_syms, int64_t P, int64_t HW, int layout,
+                                 int bits, double h, uint8_t* d_xq_hat, hipStream_t s);
 
 // ---- kernel launchers (definitions in the *_kernels.hip files) ----
 hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,

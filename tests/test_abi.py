@@ -24,7 +24,7 @@ def lib():
 def _declared():
     text = open(os.path.join(ROOT, "include", "fmtc.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(fmtc_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(fmtc_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -130,3 +130,14 @@ def test_fit_state_and_truncation_argument_errors_are_reported_on_the_host(lib):
     lib.fmtc_fit_state_destroy(None)  # a no-op
     assert lib.fmtc_basis_truncate(None, 4, ctypes.byref(out)) == fmtc.EINVAL
     assert lib.fmtc_basis_truncate(None, 4, None) == fmtc.EINVAL
+
+
+def test_u8_argument_errors_are_reported_on_the_host(lib):
+    out = ctypes.c_void_p()
+    assert lib.fmtc_basis8_create(None, 0.5, ctypes.byref(out)) == fmtc.EINVAL
+    assert lib.fmtc_basis8_create(None, 0.5, None) == fmtc.EINVAL
+    assert lib.fmtc_quantize_u8(None, None, 1, 16, 4, 4, fmtc.NHWC, 6, None, None) == fmtc.EINVAL
+    assert lib.fmtc_reconstruct_u8(None, None, 1, 16, 4, 4, fmtc.NHWC, 6, None, None) == fmtc.EINVAL
+    assert lib.fmtc_encode_u8(None, None, 1, 16, 4, 4, fmtc.NHWC, 6, 4096, None, 0, None, None, 0, None) == fmtc.EINVAL
+    assert lib.fmtc_decode_u8(None, None, 0, None, 1, 16, 4, 4, fmtc.NHWC, 6, None, None, 0, None) == fmtc.EINVAL
+    lib.fmtc_basis8_destroy(None)  # a no-op
