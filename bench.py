@@ -131,7 +131,7 @@ def main():
     # decode of buffer set i on stream i % 2, so the kernels of neighbouring steps overlap.  Reported beside
     # `value`, which stays the one-stream figure. ----
     dt_two = None
-    if R >= 2:
+    if R >= 2 and os.environ.get("FMTC_EXCLUSIVE_DEVICE", "0")[:1] != "1":  # (that setting promises one stream)
         side = [torch.cuda.Stream(), torch.cuda.Stream()]
         hs = [ctypes.c_void_p(st.cuda_stream) for st in side]
         ea2 = [[a[:-1] + (h,) for a in ea] for h in hs]
@@ -234,6 +234,33 @@ def main():
     static["encode_decode_GBps"] = round(in_bytes / (dt_sstep / args.steps) / 1e9, 3)
     static["us_per_step"] = round(1e6 * dt_sstep / args.steps, 2)
 
+    # ---- the 8-bit path: unsigned 8-bit activations, 8-bit basis, integer matrix cores (reported beside `value`) ----
+    sx = float(x0.max().item()) / 255.0
+    xq0 = torch.clamp(torch.round(x0 / sx), 0, 255).to(torch.uint8)
+    b8 = fmtc.Basis8(basis, sx)
+    usets = [dict(xq=xq0.clone(), out=torch.empty_like(xq0), ws=torch.empty(V, dtype=torch.uint8, device="cuda"))
+             for _ in sets]
+    ua = [(b8._h, u["xq"].data_ptr(), N, C, H, W, layout, bits, 4096, s["stream"].data_ptr(), cap,
+           s["nbytes"].data_ptr(), s["ws"].data_ptr(), ws_bytes, stream_h) for s, u in zip(sets, usets)]
+    uda = [(b8._h, s["stream"].data_ptr(), cap, u["out"].data_ptr(), N, C, H, W, layout, bits, s["err"].data_ptr(),
+            u["ws"].data_ptr(), V, stream_h) for s, u in zip(sets, usets)]
+    run(lambda i: lib.fmtc_encode_u8(*ua[i % R]) | lib.fmtc_decode_u8(*uda[i % R]), args.warmup)
+    dt_u8 = run(lambda i: lib.fmtc_encode_u8(*ua[i % R]) | lib.fmtc_decode_u8(*uda[i % R]), args.steps)
+    fmtc.profile_enable(args.steps)
+    run(lambda i: lib.fmtc_encode_u8(*ua[i % R]) | lib.fmtc_decode_u8(*uda[i % R]), args.steps)
+    uprof = fmtc.profile_read()
+    fmtc.profile_enable(0)
+    for s in sets:
+        assert int(s["err"].item()) == 0, "decoder flagged its own stream"
+    uinfo = fmtc.stream_info(sets[0]["stream"][:64].cpu().numpy())
+    u8 = {"us_per_step": round(1e6 * dt_u8 / args.steps, 2),
+          "encode_decode_Gvalues_per_s": round(V / (dt_u8 / args.steps) / 1e9, 3),
+          "bits_per_value": round(uinfo["payload_bits"] / V, 4),
+          "mse": float((((usets[0]["out"].float() - usets[0]["xq"].float()) * sx) ** 2).mean().item()),
+          "kernels": {k: round(1e3 * v[0], 3) for k, v in uprof.items()},
+          "note": "1 byte per value in and out; projection and reconstruction on the integer matrix cores, exact; "
+                  "histogram, table, packing and variable length decoding are the fp32 path's kernels"}
+
     # ---- yardstick for the memory counters: one plain copy of known size (not timed) ----
     ysrc = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     ydst = torch.empty_like(ysrc)
@@ -285,6 +312,7 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
         "static_table_codec": static,
+        "u8_codec": u8,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -478,9 +478,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             }
         }
     };
+    // Which groups a workgroup packs.  A group's position in the payload comes from the groups before it, so
+    // whoever waits for one must know that its owner is running.  With no more groups than workgroups each
+    // workgroup takes the group of its own index: the workgroups before it were dispatched before it.  With more,
+    // a fixed round-robin share would only be safe if the whole grid were resident at once, which another
+    // stream's kernels on the same device can prevent (the waits would then run into their limit and the stream
+    // would be marked invalid).  There every group is claimed from a counter, in ascending order, by a workgroup
+    // that is running and about to pack it: the lowest unfinished group then always has an owner at work on it.
+    // The first claim is made at the start and read after the table is there; the others as soon as the group at
+    // hand has published its size.  Updates of one address take their turns (about 15 ns each here), which is what
+    // this order of work costs over a fixed share when a thousand workgroups finish a group at about the same time.
+    // A caller that knows its calls have the device to themselves can ask for the fixed share (p.exclusive).
+    const bool ticketed = p.n_groups > gridDim.x && !p.exclusive;
+    constexpr int kClaimThread = 64 * (kPackWaves - 1);
+    if (ticketed && tid == kClaimThread) S.claim = atomicAdd(&p.ctrl->ticket, 1u);
     uint32_t w[16];
     uint32_t group = blockIdx.x;  // the grid never has more workgroups than groups
-    load_chunk(group * kPackWaves + (uint32_t)wave, w);  // in flight while the table is made
+    if (!ticketed) load_chunk(group * kPackWaves + (uint32_t)wave, w);  // in flight while the table is made
 
     TableLds& L = *reinterpret_cast<TableLds*>(&S.stage[0][0]);  // shares LDS with the chunk images, not in use yet
     static_assert(sizeof(TableLds) <= sizeof(S.stage), "table scratch must fit the chunk images");
@@ -508,17 +522,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         __syncthreads();
         if (MODE == kPackStatic && blockIdx.x == 0) p.stream[kHeaderBytes + tid] = (uint8_t)(S.tab[tid] >> 56);
     }
+    if (ticketed) {  // (the claim was stored before the barriers above)
+        group = S.claim;
+        if (group >= p.n_groups) return;  // every group already has an owner
+        load_chunk(group * kPackWaves + (uint32_t)wave, w);
+    }
     // nobody reads the table scratch any more: the images start out clear
     pack_clear_image(S, wave, lane);
 
-    for (; group < p.n_groups; group += gridDim.x) {
+    for (;;) {
         const uint32_t ch = group * kPackWaves + (uint32_t)wave;
         // the next group's symbols are on their way during the wait for the position and the stores
         uint32_t wn[16];
+        uint32_t next_group = p.n_groups;
         pack_group<MODE>(S, p, group, w, chunk_len(ch), [&]() {
-            const uint32_t next_group = group + gridDim.x;
+            if (ticketed) {  // this group's size is published: claiming the next one cannot block anybody
+                if (tid == kClaimThread) S.claim = atomicAdd(&p.ctrl->ticket, 1u);
+                __syncthreads();
+                next_group = S.claim;
+            } else {
+                next_group = group + gridDim.x;  // fixed share (beyond the last group where each has one)
+            }
             if (next_group < p.n_groups) load_chunk(next_group * kPackWaves + (uint32_t)wave, wn);
         });
+        if (next_group >= p.n_groups) break;  // (always so where every workgroup has one group)
+        group = next_group;
 #pragma unroll
         for (int q = 0; q < 16; q++) w[q] = wn[q];
     }
@@ -540,6 +568,16 @@ static int pack_resident_groups() {
     return cached;
 }
 
+// FMTC_EXCLUSIVE_DEVICE=1 in the environment (read once): the caller's encoder calls never overlap with other
+// kernels on the device, so a tensor with more chunk groups than workgroups may be shared out in fixed turns.
+static bool exclusive_device() {
+    static const bool on = [] {
+        const char* e = getenv("FMTC_EXCLUSIVE_DEVICE");
+        return e && e[0] == '1';
+    }();
+    return on;
+}
+
 // Table (a kernel of its own only where every pack workgroup building it would cost more than the launch)
 // and packing.
 PackParams pack_params(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
@@ -553,6 +591,7 @@ PackParams pack_params(const uint8_t* d_syms, const Geometry& g, int bits, float
     p.chunk_syms = g.chunk_syms;
     p.subs_per_chunk = g.subs_per_chunk;
     p.n_groups = cs.n_groups;
+    p.exclusive = exclusive_device() ? 1u : 0u;
     p.bits = bits;
     p.hist_parts = cs.hist_parts;
     p.n_parts = n_parts;

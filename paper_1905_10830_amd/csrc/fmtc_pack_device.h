@@ -44,6 +44,7 @@ struct PackParams {
     int n_parts;
     const uint64_t* enc_table;   // otherwise: the table (k_huffman_table's, or a static one)
     uint32_t static_max_len;     // kPackStatic: longest code of the table
+    uint32_t exclusive;          // the call has the device to itself: groups may be shared out in fixed turns
     CoderCtrl* ctrl;
     unsigned long long* lookback;
     Header hdr;
@@ -185,6 +186,7 @@ struct PackShared {
     uint16_t runs[kPackWaves][64];                                // bit counts of a chunk's runs on their way out
     uint32_t wave_words[kPackWaves], wave_slack[kPackWaves];
     uint32_t excl, excl_slack, max_len;
+    uint32_t claim;                                               // the group claimed from the counter
     unsigned long long payload_bits;
 };
 

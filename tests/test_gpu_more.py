@@ -202,3 +202,34 @@ def test_rate_distortion_sweep_against_the_oracle(fmtc, oracle):
             assert r["rate"] < prev_rate and r["mse"] > prev_mse  # fewer bits: lower rate, higher distortion
         prev_rate, prev_mse = r["rate"], r["mse"]
     assert rows[0]["mse"] < 1.3 * rows[0]["delta"] ** 2 / 12
+
+
+def test_encoders_on_two_streams_share_the_device(fmtc):
+    """Two encoder calls of a tensor with more chunk groups than the pack kernel has workgroups, in flight on
+    two HIP streams at once: neither kernel has the device to itself, so not all of its workgroups are resident
+    together.  Every call must still give the one-stream result (groups are claimed from a counter there, so a
+    wait never depends on a workgroup that has not started)."""
+    torch.manual_seed(5)
+    C, bits = 128, 6
+    calib = torch.randn(8, 28, 28, C, device="cuda").relu()
+    x = (torch.randn(256, 28, 28, C, device="cuda") * torch.linspace(2.0, 0.05, C, device="cuda")).relu()
+    basis = fmtc.fit_basis(calib)
+    P = 256 * 28 * 28
+    assert (P * C // 4096 + 3) // 4 > 1024          # more groups than workgroups
+    ref, ref_n = fmtc.encode(basis, x, bits)
+    torch.cuda.synchronize()
+    n = int(ref_n.item())
+    assert fmtc.stream_info(ref[:64].cpu().numpy())["stream_bytes"] == n
+    side = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for rep in range(3):
+        for st in side:
+            with torch.cuda.stream(st):
+                outs.append(fmtc.encode(basis, x, bits))
+    torch.cuda.synchronize()
+    for stream, nbytes in outs:
+        assert int(nbytes.item()) == n
+        assert torch.equal(stream[:n], ref[:n])
+    xhat, err = fmtc.decode(basis, outs[-1][0], x.shape, bits)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
