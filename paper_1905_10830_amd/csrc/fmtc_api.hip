@@ -955,7 +955,8 @@ fmtc_status fmtc_quantize_u8(const fmtc_basis8* basis, const uint8_t* d_xq, int6
     const int64_t HW = (int64_t)H * W;
     const double delta = (double)fmtc_delta(basis->range_A, bits);
     const double g = ((double)basis->scale_T * (double)basis->act_scale) / (256.0 * delta);
-    hipError_t e = launch_quantize_u8(basis->view, d_xq, N * HW, HW, layout, bits, g, d_syms, (hipStream_t)hip_stream);
+    hipError_t e = launch_quantize_u8(basis->view, d_xq, N * HW, HW, layout, bits, g, d_syms, nullptr, nullptr,
+                                      (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "8-bit projection kernel");
     return FMTC_OK;
 }
@@ -985,11 +986,16 @@ fmtc_status fmtc_encode_u8(const fmtc_basis8* basis, const uint8_t* d_xq, int64_
     if (st != FMTC_OK) return st;
     if (ws_bytes < pl.ws.total) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, pl.ws.total);
     if (cap < bound_from(pl, bits)) return fail(FMTC_EBUFSIZE, "stream capacity too small: %zu < %zu", cap, bound_from(pl, bits));
-    uint8_t* syms = static_cast<uint8_t*>(d_workspace) + pl.ws.off_syms;
-    st = fmtc_quantize_u8(basis, d_xq, N, C, H, W, layout, bits, syms, hip_stream);
-    if (st != FMTC_OK) return st;
-    return fmtc_code_symbols(syms, P, C, bits, chunk_syms, fmtc_delta(basis->range_A, bits), d_stream_out, cap,
-                             d_out_bytes, d_workspace, ws_bytes, hip_stream);
+    uint8_t* w = static_cast<uint8_t*>(d_workspace);
+    uint8_t* syms = w + pl.ws.off_syms;
+    const CoderScratch cs = coder_scratch(w, pl);
+    const float delta = fmtc_delta(basis->range_A, bits);
+    const double g = ((double)basis->scale_T * (double)basis->act_scale) / (256.0 * (double)delta);
+    hipStream_t s = (hipStream_t)hip_stream;
+    int n_parts = 0;
+    hipError_t e = launch_quantize_u8(basis->view, d_xq, P, (int64_t)H * W, layout, bits, g, syms, &cs, &n_parts, s);
+    if (e != hipSuccess) return hip_fail(e, "8-bit projection kernel");
+    return run_coder(syms, pl, cs, n_parts, bits, delta, w, static_cast<uint8_t*>(d_stream_out), cap, d_out_bytes, s);
 }
 
 fmtc_status fmtc_decode_u8(const fmtc_basis8* basis, const void* d_stream_in, size_t bytes, uint8_t* d_xq_hat,

@@ -19,14 +19,6 @@ namespace fmtc {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-// The first kernel of an encoder call clears what the coder kernels after it count in.
-__device__ __forceinline__ void zero_coder_scratch(CoderCtrl* ctrl, unsigned long long* lookback, uint32_t n_groups) {
-    const size_t nthreads = (size_t)gridDim.x * gridDim.y * blockDim.x;
-    const size_t gtid = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
-    for (size_t i = gtid; i < n_groups; i += nthreads) lookback[i] = 0ull;
-    if (gtid < sizeof(CoderCtrl) / 4) reinterpret_cast<uint32_t*>(ctrl)[gtid] = 0u;
-}
-
 // ---------------------------------------------------------------------------
 // Wide tensors (more than 160 channels after padding to 32).  The contraction is the same f16
 // split as in the narrow-tensor kernel below (three v_mfma_f32_32x32x16_f16 per 16 channels,

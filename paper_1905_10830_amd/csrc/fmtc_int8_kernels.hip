@@ -54,8 +54,15 @@ struct Int8Params {
     int64_t P, HW, n_tiles;
     int C, NS, nct, bits;
     double factor;                  // g (forward) or h (inverse)
+    // forward, whole encoder only (else null): one partial histogram per workgroup [gridDim.x][2^bits], and the
+    // coder's scratch that the first kernel of a call clears
+    uint32_t* hist_parts;
+    CoderCtrl* ctrl;
+    unsigned long long* lookback;
+    uint32_t n_groups;
 };
 
+constexpr int kCopies = 16;  // histogram copies per wavefront
 constexpr unsigned long long kFlip = 0x8080808080808080ull;  // unsigned byte -> (value - 128) as a signed byte
 
 // NSR > 0: the pixel tile's operand (NS <= NSR steps) stays in registers over the coefficient tiles;
@@ -67,6 +74,18 @@ __global__ __launch_bounds__(256) void k_int8_tiles(Int8Params p) {
     const int C = p.C, NS = p.NS;
     const int hk = 1 << (p.bits - 1);
     const bool wide = (C % 8) == 0;
+    // Histogram (forward, whole encoder), in dynamic LDS: kCopies interleaved copies per wavefront (bin s of copy q
+    // at word s * kCopies + q, lane l counts in copy l % kCopies), because most symbols of a tile are the same few
+    // values and one copy would serialise the lanes on a few words.
+    extern __shared__ uint32_t s_hist[];  // [4][K * kCopies], only if hist
+    const bool hist = !INVERSE && p.hist_parts != nullptr;
+    const int K = 1 << p.bits;
+    uint32_t* wh = s_hist + (size_t)wave * K * kCopies + (lane & (kCopies - 1));
+    if (hist) {
+        zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
+        for (int i = threadIdx.x; i < 4 * K * kCopies; i += 256) s_hist[i] = 0u;
+        __syncthreads();
+    }
     for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < p.n_tiles; tile += (int64_t)gridDim.x * 4) {
         const int64_t px = tile * 32 + l32;
         auto operand = [&](int s) -> long {
@@ -105,6 +124,7 @@ __global__ __launch_bounds__(256) void k_int8_tiles(Int8Params p) {
                     t = t < (double)-hk ? (double)-hk : t;
                     t = t > (double)(hk - 1) ? (double)(hk - 1) : t;
                     byte = (int)t + hk;
+                    if (hist && px < p.P && r < C) atomicAdd(&wh[byte * kCopies], 1u);
                 } else {
                     const int m = acc[v] + (128 - hk) * p.col_sum[r];
                     double t = rint(fma((double)m, p.factor, (double)p.mean_fix[r]) * 0.00390625);
@@ -135,29 +155,53 @@ __global__ __launch_bounds__(256) void k_int8_tiles(Int8Params p) {
             }
         }
     }
+    if (hist) {
+        __syncthreads();
+        if ((int)threadIdx.x < K) {
+            uint32_t sum = 0;
+            for (int q = 0; q < 4; q++)
+                for (int c = 0; c < kCopies; c++) sum += s_hist[((size_t)q * K + threadIdx.x) * kCopies + c];
+            p.hist_parts[(size_t)blockIdx.x * K + threadIdx.x] = sum;
+        }
+    }
 }
 
 template <bool INVERSE>
-static hipError_t launch_int8(int kernel_id, const Int8Params& p, int layout, hipStream_t s) {
+static hipError_t launch_int8(int kernel_id, const Int8Params& p, int layout, int* n_parts, hipStream_t s) {
     if (!p.in || !p.out || !p.op8 || (!INVERSE && !p.row_off) || (INVERSE && (!p.col_sum || !p.mean_fix)))
         return hipErrorInvalidValue;
     if (p.P < 1 || p.C < 1 || p.C > 1024 || p.NS != (p.C + 15) / 16 || p.nct != (p.C + 31) / 32 || p.HW < 1 ||
         p.n_tiles != (p.P + 31) / 32 || p.bits < 2 || p.bits > 8)
         return hipErrorInvalidValue;
+    if (p.hist_parts && (INVERSE || !p.ctrl || !p.lookback)) return hipErrorInvalidValue;
     int64_t gx = (p.n_tiles + 3) / 4;
-    if (gx > 2048) gx = 2048;
+    const int64_t cap = p.hist_parts ? kMaxHistParts : 2048;  // one histogram row per workgroup
+    if (gx > cap) gx = cap;
+    if (n_parts) *n_parts = (int)gx;
     const dim3 grid((unsigned)gx), block(256);
+    const size_t lds = p.hist_parts ? sizeof(uint32_t) * 4 * kCopies * ((size_t)1 << p.bits) : 0;
     const bool planar = layout == FMTC_NCHW;  // of the activations: read by the forward kernel, written by the inverse
+#define FMTC_INT8(LAY, NSR)                                                                                     \
+    do {                                                                                                        \
+        if (lds > 32 * 1024) {                                                                                  \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_int8_tiles<LAY, NSR, INVERSE>), \
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
+            if (ea != hipSuccess) return ea;                                                                    \
+        }                                                                                                       \
+        return launch(kernel_id, k_int8_tiles<LAY, NSR, INVERSE>, grid, block, lds, s, p);                      \
+    } while (0)
     if (p.NS <= 8) {
-        if (planar) return launch(kernel_id, k_int8_tiles<FMTC_NCHW, 8, INVERSE>, grid, block, 0, s, p);
-        return launch(kernel_id, k_int8_tiles<FMTC_NHWC, 8, INVERSE>, grid, block, 0, s, p);
+        if (planar) FMTC_INT8(FMTC_NCHW, 8);
+        FMTC_INT8(FMTC_NHWC, 8);
     }
-    if (planar) return launch(kernel_id, k_int8_tiles<FMTC_NCHW, 0, INVERSE>, grid, block, 0, s, p);
-    return launch(kernel_id, k_int8_tiles<FMTC_NHWC, 0, INVERSE>, grid, block, 0, s, p);
+    if (planar) FMTC_INT8(FMTC_NCHW, 0);
+    FMTC_INT8(FMTC_NHWC, 0);
+#undef FMTC_INT8
 }
 
 hipError_t launch_quantize_u8(const Basis8Device& b, const uint8_t* d_xq, int64_t P, int64_t HW, int layout,
-                              int bits, double g, uint8_t* d_syms, hipStream_t s) {
+                              int bits, double g, uint8_t* d_syms, const CoderScratch* cs, int* n_parts,
+                              hipStream_t s) {
     Int8Params p{};
     p.in = d_xq;
     p.out = d_syms;
@@ -173,7 +217,14 @@ hipError_t launch_quantize_u8(const Basis8Device& b, const uint8_t* d_xq, int64_
     p.nct = (b.C + 31) / 32;
     p.bits = bits;
     p.factor = g;
-    return launch_int8<false>(K_QUANTIZE_U8, p, layout, s);
+    if (cs) {
+        p.hist_parts = cs->hist_parts;
+        p.ctrl = cs->ctrl;
+        p.lookback = cs->lookback;
+        p.n_groups = cs->n_groups;
+        if (!p.hist_parts || !n_parts) return hipErrorInvalidValue;
+    }
+    return launch_int8<false>(K_QUANTIZE_U8, p, layout, n_parts, s);
 }
 
 hipError_t launch_reconstruct_u8(const Basis8Device& b, const uint8_t* d_syms, int64_t P, int64_t HW, int layout,
@@ -193,7 +244,7 @@ hipError_t launch_reconstruct_u8(const Basis8Device& b, const uint8_t* d_syms, i
     p.nct = (b.C + 31) / 32;
     p.bits = bits;
     p.factor = h;
-    return launch_int8<true>(K_RECONSTRUCT_U8, p, layout, s);
+    return launch_int8<true>(K_RECONSTRUCT_U8, p, layout, nullptr, s);
 }
 
 }  // namespace fmtc

@@ -157,10 +157,21 @@ struct Basis8Device {
     const int* col_sum;              // sum_k Tq[k][c]
     const int* mean_fix;             // rne(256 mu[c] / s_x)
 };
+// cs == nullptr: symbols only; else the kernel also clears the coder's scratch and writes one partial histogram per
+// workgroup (*n_parts of them), as the fp32 projection kernels do.
 hipError_t launch_quantize_u8(const Basis8Device& b, const uint8_t* d_xq, int64_t P, int64_t HW, int layout,
-                              int bits, double g, uint8_t* d_syms, hipStream_t s);
+                              int bits, double g, uint8_t* d_syms, const CoderScratch* cs, int* n_parts,
+                              hipStream_t s);
 hipError_t launch_reconstruct_u8(const Basis8Device& b, const uint8_t* d_syms, int64_t P, int64_t HW, int layout,
                                  int bits, double h, uint8_t* d_xq_hat, hipStream_t s);
+
+// The first kernel of an encoder call clears what the coder kernels after it count in.
+__device__ __forceinline__ void zero_coder_scratch(CoderCtrl* ctrl, unsigned long long* lookback, uint32_t n_groups) {
+    const size_t nthreads = (size_t)gridDim.x * gridDim.y * blockDim.x;
+    const size_t gtid = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+    for (size_t i = gtid; i < n_groups; i += nthreads) lookback[i] = 0ull;
+    if (gtid < sizeof(CoderCtrl) / 4) reinterpret_cast<uint32_t*>(ctrl)[gtid] = 0u;
+}
 
 // ---- kernel launchers (definitions in the *_kernels.hip files) ----
 hipError_t launch_project_quantize(const BasisDevice& b, const float* d_x, int64_t N, int64_t HW, int layout,
