@@ -350,17 +350,20 @@ fmtc_status upload_basis8(fmtc_basis8* b) {
     std::vector<unsigned long long> fwd, inv;
     pack_operand8(b->Tq, C, false, &fwd);
     pack_operand8(b->Tq, C, true, &inv);
-    std::vector<long long> row_off(rows, 0);
+    std::vector<long long> off64(rows, 0);
+    std::vector<double> row_off(rows, 0.0);
     std::vector<int> col_sum(rows, 0), mean_fix(rows, 0);
     for (int k = 0; k < C; k++)
         for (int c = 0; c < C; c++) {
             const long long t = b->Tq[(size_t)k * C + c];
-            row_off[k] += t * ((long long)b->mean_fix[c] - 256ll * 128ll);
+            off64[k] += t * ((long long)b->mean_fix[c] - 256ll * 128ll);
             col_sum[c] += (int)t;
         }
+    // |off| <= 127 * 1024 * 2^30 < 2^48: exact as a double
+    for (int k = 0; k < C; k++) row_off[k] = (double)off64[k];
     for (int c = 0; c < C; c++) mean_fix[c] = b->mean_fix[c];
     const size_t n_op = (size_t)nct * NS * 64 * sizeof(unsigned long long);
-    const size_t o_inv = n_op, o_off = 2 * n_op, o_col = o_off + sizeof(long long) * rows,
+    const size_t o_inv = n_op, o_off = 2 * n_op, o_col = o_off + sizeof(double) * rows,
                  o_mean = o_col + sizeof(int) * rows, total = o_mean + sizeof(int) * rows;
     hipError_t e;
     if ((e = hipGetDevice(&b->device)) != hipSuccess) return hip_fail(e, "hipGetDevice");
@@ -368,14 +371,14 @@ fmtc_status upload_basis8(fmtc_basis8* b) {
     uint8_t* d = static_cast<uint8_t*>(b->d_block);
     if ((e = hipMemcpy(d, fwd.data(), n_op, hipMemcpyHostToDevice)) != hipSuccess ||
         (e = hipMemcpy(d + o_inv, inv.data(), n_op, hipMemcpyHostToDevice)) != hipSuccess ||
-        (e = hipMemcpy(d + o_off, row_off.data(), sizeof(long long) * rows, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(d + o_off, row_off.data(), sizeof(double) * rows, hipMemcpyHostToDevice)) != hipSuccess ||
         (e = hipMemcpy(d + o_col, col_sum.data(), sizeof(int) * rows, hipMemcpyHostToDevice)) != hipSuccess ||
         (e = hipMemcpy(d + o_mean, mean_fix.data(), sizeof(int) * rows, hipMemcpyHostToDevice)) != hipSuccess)
         return hip_fail(e, "hipMemcpy basis");
     b->view.C = C;
     b->view.fwd8 = reinterpret_cast<const unsigned long long*>(d);
     b->view.inv8 = reinterpret_cast<const unsigned long long*>(d + o_inv);
-    b->view.row_off = reinterpret_cast<const long long*>(d + o_off);
+    b->view.row_off = reinterpret_cast<const double*>(d + o_off);
     b->view.col_sum = reinterpret_cast<const int*>(d + o_col);
     b->view.mean_fix = reinterpret_cast<const int*>(d + o_mean);
     return FMTC_OK;
@@ -1006,6 +1009,18 @@ fmtc_status fmtc_decode_u8(const fmtc_basis8* basis, const void* d_stream_in, si
     if (st != FMTC_OK) return st;
     const int64_t P = N * (int64_t)H * W;
     if (ws_bytes < (size_t)P * (size_t)C) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, (size_t)P * (size_t)C);
+    if (!aligned(d_stream_in, 16) || !aligned(d_err_flag, 4)) return fail(FMTC_EINVAL, "misaligned pointer");
+    {   // up to 128 channels: one kernel, the symbols never leave the chip
+        Geometry g;
+        if (!make_geometry(P, C, 4096, &g)) return fail(FMTC_EINVAL, "bad geometry");
+        const double delta = (double)fmtc_delta(basis->range_A, bits);
+        const double h = ((double)basis->scale_T * delta * 256.0) / (double)basis->act_scale;
+        bool applies = false;
+        hipError_t e = launch_decode_u8(basis->view, static_cast<const uint8_t*>(d_stream_in), bytes, g, bits,
+                                        (int64_t)H * W, layout, h, d_xq_hat, d_err_flag, &applies, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return hip_fail(e, "8-bit decode kernel");
+        if (applies) return FMTC_OK;
+    }
     uint8_t* syms = static_cast<uint8_t*>(d_workspace);
     st = fmtc_decode_symbols(d_stream_in, bytes, P, C, bits, syms, d_err_flag, hip_stream);
     if (st != FMTC_OK) return st;

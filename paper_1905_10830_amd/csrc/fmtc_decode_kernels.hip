@@ -394,6 +394,14 @@ struct DecodeParams {
     size_t g_off_chunk_off, g_off_sub_bits, g_off_payload;
     uint32_t g_n_chunks, g_spc;
     const void* prebuilt;  // PrebuiltTables of a code table fixed beforehand, or NULL: build them from the stream
+    // 8-bit reconstruction in the chunk decoder (k_decode_chunks<..., U8 = true>): the transposed 8-bit basis in
+    // the operand order of the integer matrix instruction [ncs][ceil(C / 16)][64], its column sums and the mean
+    // with 8 fraction bits (both padded to ncs * 32), h = 256 s_T Delta / s_x, and the output bytes
+    const unsigned long long* op8;
+    const int* col_sum;
+    const int* mean_fix;
+    double factor8;
+    uint8_t* out8;
 };
 
 // Header checks.  Returns false unless the header matches the arguments and the
@@ -714,11 +722,15 @@ __global__ __launch_bounds__(512) void k_decode_tiles(DecodeParams p) {
 // 16j + 8*half + e of its pixel (the contraction index may be walked in any order as long as
 // both operands agree on it).  Delta and mu are applied in the epilogue.
 // ---------------------------------------------------------------------------
+typedef int intx16 __attribute__((ext_vector_type(16)));
 constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes per run, slack for padded reads
 
 // WAVES wavefronts per workgroup (4 or 8): one per SIMD where the chunks do not outnumber the SIMDs, two where
 // they do (the second hides the latencies of the first; the workgroup still holds one copy of the basis).
-template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES>
+// U8: the tile's symbols go through the 8-bit basis on the integer matrix cores instead (v_mfma_i32_32x32x16_i8;
+// exact sums, one fused fp64 multiply-add and one rounding per value, 8-bit activations out); the basis operand
+// comes from global memory through the cache, nothing of it is staged in LDS.
+template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES, bool U8 = false>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k_decode_chunks(DecodeParams p) {
     constexpr int THREADS = WAVES * 64;
     __shared__ __align__(16) DecTables T;
@@ -740,7 +752,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     // the basis goes from global memory straight into LDS (no registers in between), 16 bytes per lane and
     // instruction: lane l of a wavefront lands at the wavefront's LDS base + 16 l
     constexpr int kBasisPieces = NCT * NJ * 2 * 64;  // 16-byte pieces of the basis, a multiple of 64
-    {
+    if constexpr (!U8) {
         const uint4* src = reinterpret_cast<const uint4*>(p.Bp16);
 #pragma unroll
         for (int i = 0; i < (kBasisPieces + THREADS - 1) / THREADS; i++)
@@ -791,7 +803,9 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             pre_run = ((uint32_t)lane < sv.spc) ? sv.sub_bits[(size_t)ch_first * sv.spc + lane] : 0u;
         }
     }
-    if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
+    if constexpr (!U8) {
+        if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
+    }
     if (!(p.prebuilt ? load_decode_tables<THREADS>(T, my_len, static_cast<const PrebuiltTables*>(p.prebuilt))
                      : build_decode_tables<THREADS>(T, my_len, p.bits))) {
         if (tid == 0 && blockIdx.x == 0) atomicOr(p.err, FMTC_ERR_TABLE);
@@ -854,6 +868,71 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             int pxl = pt * 32 + l32;
             if (pxl > TP - 1) pxl = TP - 1;  // rows past the chunk repeat its last pixel; never stored
             const uint32_t rowbase = (uint32_t)pxl * (uint32_t)C + 8u * (uint32_t)half;
+            if constexpr (U8) {
+                // Operands: lane (l32, half) holds the 8 symbols 16j + 8*half .. + 7 of its pixel as (s - 128),
+                // and of the basis the same 8 coefficients of channel row perm(l32) of tile ct (rows permuted so
+                // that a lane ends up with channels ct*32 + 16*half .. + 15 of its pixel).  Symbols past C meet
+                // zero basis bytes.
+                const int NS = (C + 15) / 16;  // <= NJ
+                const int hk = 1 << (p.bits - 1);
+                long b[NJ];
+#pragma unroll
+                for (int j = 0; j < NJ; j++) {
+                    const uint32_t n = rowbase + 16u * (uint32_t)j;
+                    uint32_t w0 = 0, w1 = 0;
+                    if (j < NS) {
+                        if constexpr (ALIGNED4) {
+                            w0 = *reinterpret_cast<const uint32_t*>(tile + sym_addr(n));
+                            w1 = *reinterpret_cast<const uint32_t*>(tile + sym_addr(n + 4));
+                        } else {
+                            w0 = (uint32_t)tile[sym_addr(n)] | ((uint32_t)tile[sym_addr(n + 1)] << 8) |
+                                 ((uint32_t)tile[sym_addr(n + 2)] << 16) | ((uint32_t)tile[sym_addr(n + 3)] << 24);
+                            w1 = (uint32_t)tile[sym_addr(n + 4)] | ((uint32_t)tile[sym_addr(n + 5)] << 8) |
+                                 ((uint32_t)tile[sym_addr(n + 6)] << 16) | ((uint32_t)tile[sym_addr(n + 7)] << 24);
+                        }
+                    }
+                    b[j] = (long)((((unsigned long long)w1 << 32) | w0) ^ 0x8080808080808080ull);
+                }
+                const int my_px = pt * 32 + l32;
+                const int64_t px = px_chunk0 + my_px;
+#pragma unroll
+                for (int ct = 0; ct < NCT; ct++) {
+                    intx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int j = 0; j < NJ; j++)
+                        if (j < NS)
+                            acc = __builtin_amdgcn_mfma_i32_32x32x16_i8((long)p.op8[((size_t)ct * NS + j) * 64 + lane], b[j], acc, 0, 0, 0);
+                    const int r0 = ct * 32 + 16 * half;
+                    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                    for (int v = 0; v < 16; v++) {
+                        const int r = r0 + v;  // < NCT * 32: the per-channel arrays are padded to that
+                        const int m = acc[v] + (128 - hk) * p.col_sum[r];
+                        const double t = fmin(fmax(rint(fma((double)m, p.factor8, (double)p.mean_fix[r]) * 0.00390625), 0.0), 255.0);
+                        w[v >> 2] |= (uint32_t)(int)t << (8 * (v & 3));
+                    }
+                    if (my_px < TP && r0 < C) {
+                        if constexpr (LAYOUT == FMTC_NHWC) {
+                            uint8_t* q = p.out8 + (size_t)px * (size_t)C + (size_t)r0;
+                            if ((C % 16) == 0) {
+                                *reinterpret_cast<uint4*>(q) = make_uint4(w[0], w[1], w[2], w[3]);
+                            } else {
+#pragma unroll
+                                for (int v = 0; v < 16; v++)
+                                    if (r0 + v < C) q[v] = (uint8_t)(w[v >> 2] >> (8 * (v & 3)));
+                            }
+                        } else {
+                            const int64_t n = px / p.HW, hw = px - n * p.HW;
+#pragma unroll
+                            for (int v = 0; v < 16; v++)
+                                if (r0 + v < C)
+                                    p.out8[((size_t)n * (size_t)C + (size_t)(r0 + v)) * (size_t)p.HW + (size_t)hw] =
+                                        (uint8_t)(w[v >> 2] >> (8 * (v & 3)));
+                        }
+                    }
+                }
+                continue;
+            }
             floatx16 acc[NCT], acl[NCT];
 #pragma unroll
             for (int ct = 0; ct < NCT; ct++)
@@ -1054,6 +1133,65 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         else    { if (wide) FMTC_DEC(2, FMTC_NCHW, false); else FMTC_DEC(4, FMTC_NCHW, false); }
     }
 #undef FMTC_DEC
+    return el;
+}
+
+// Whole decoder of the 8-bit path in one kernel: the chunk decoder with the integer reconstruction in place of the
+// f16 one.  *applies = false (and nothing launched) for tensors of more than 128 channels, which the caller then
+// decodes to symbols and reconstructs with the tile kernel.
+hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
+                            int64_t HW, int layout, double h, uint8_t* d_xq_hat, uint32_t* d_err, bool* applies,
+                            hipStream_t s) {
+    const int C = g.C;
+    const int ncs = (C + 31) / 32;
+    *applies = ncs <= 4;
+    if (!*applies) return hipSuccess;
+    if (!d_stream || !d_xq_hat || !d_err || !b.inv8 || !b.col_sum || !b.mean_fix || b.C != C) return hipErrorInvalidValue;
+    DecodeParams p{};
+    p.stream = d_stream;
+    p.bytes = bytes;
+    p.P = g.P;
+    p.HW = HW;
+    p.C = C;
+    p.bits = bits;
+    p.ncs = ncs;
+    p.Bp16 = nullptr;
+    p.mu = nullptr;
+    p.xhat = nullptr;
+    p.syms_out = nullptr;
+    p.err = d_err;
+    p.prebuilt = nullptr;
+    p.G = 1;
+    p.g_off_chunk_off = g.off_chunk_off;
+    p.g_off_sub_bits = g.off_sub_bits;
+    p.g_off_payload = g.off_payload;
+    p.g_n_chunks = g.n_chunks;
+    p.g_spc = g.subs_per_chunk;
+    p.op8 = b.inv8;
+    p.col_sum = b.col_sum;
+    p.mean_fix = b.mean_fix;
+    p.factor8 = h;
+    p.out8 = d_xq_hat;
+    const bool al = (C % 4) == 0;
+    const bool eight = g.n_chunks > 1024 && ncs != 3;
+    const int waves = eight ? 8 : 4;
+    unsigned gx = (g.n_chunks + waves - 1) / waves;
+    const unsigned cap = 256u * (unsigned)(8 / waves);
+    if (gx > cap) gx = cap;
+    hipError_t el = hipSuccess;
+#define FMTC_DECU(NCT, LAY, AL, WV) \
+    el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, true>, dim3(gx), dim3(WV * 64), 0, s, p)
+#define FMTC_DECU_N(LAY, AL)                                                                                     \
+    do {                                                                                                         \
+        if (ncs == 1) { if (eight) FMTC_DECU(1, LAY, AL, 8); else FMTC_DECU(1, LAY, AL, 4); }                    \
+        else if (ncs == 2) { if (eight) FMTC_DECU(2, LAY, AL, 8); else FMTC_DECU(2, LAY, AL, 4); }               \
+        else if (ncs == 3) FMTC_DECU(3, LAY, AL, 4);                                                             \
+        else { if (eight) FMTC_DECU(4, LAY, AL, 8); else FMTC_DECU(4, LAY, AL, 4); }                             \
+    } while (0)
+    if (layout == FMTC_NHWC) { if (al) FMTC_DECU_N(FMTC_NHWC, true); else FMTC_DECU_N(FMTC_NHWC, false); }
+    else                     { if (al) FMTC_DECU_N(FMTC_NCHW, true); else FMTC_DECU_N(FMTC_NCHW, false); }
+#undef FMTC_DECU_N
+#undef FMTC_DECU
     return el;
 }
 

@@ -48,7 +48,7 @@ struct Int8Params {
     const uint8_t* in;              // forward: activations in `layout`; inverse: symbols [P][C]
     uint8_t* out;                   // forward: symbols [P][C]; inverse: activations in `layout`
     const unsigned long long* op8;  // [nct][NS][64] basis (forward) or its transpose (inverse), operand order
-    const long long* row_off;       // forward [nct * 32]: sum_c Tq[k][c] (mf[c] - 256 * 128)
+    const double* row_off;          // forward [nct * 32]: sum_c Tq[k][c] (mf[c] - 256 * 128), an integer below 2^53
     const int* col_sum;             // inverse [nct * 32]: sum_k Tq[k][c]
     const int* mean_fix;            // inverse [nct * 32]
     int64_t P, HW, n_tiles;
@@ -113,26 +113,30 @@ __global__ __launch_bounds__(256) void k_int8_tiles(Int8Params p) {
             }
             // this lane: pixel px, results r0 .. r0 + 15 (coefficients, or channels for the inverse)
             const int r0 = kt * 32 + 16 * half;
+            // (all integers below 2^53, so the fp64 operations before the one rounding product are exact)
             uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int v = 0; v < 16; v++) {
                 const int r = r0 + v;  // < nct * 32: the per-row arrays are padded to that
-                int byte;
+                double t;
                 if (!INVERSE) {
-                    const long long n = 256ll * (long long)acc[v] - p.row_off[r];
-                    double t = rint((double)n * p.factor);
-                    t = t < (double)-hk ? (double)-hk : t;
-                    t = t > (double)(hk - 1) ? (double)(hk - 1) : t;
-                    byte = (int)t + hk;
-                    if (hist && px < p.P && r < C) atomicAdd(&wh[byte * kCopies], 1u);
+                    const double n = fma((double)acc[v], 256.0, -p.row_off[r]);
+                    t = fmin(fmax(rint(n * p.factor), (double)-hk), (double)(hk - 1)) + (double)hk;
                 } else {
                     const int m = acc[v] + (128 - hk) * p.col_sum[r];
-                    double t = rint(fma((double)m, p.factor, (double)p.mean_fix[r]) * 0.00390625);
-                    t = t < 0.0 ? 0.0 : t;
-                    t = t > 255.0 ? 255.0 : t;
-                    byte = (int)t;
+                    t = fmin(fmax(rint(fma((double)m, p.factor, (double)p.mean_fix[r]) * 0.00390625), 0.0), 255.0);
                 }
-                w[v >> 2] |= (uint32_t)byte << (8 * (v & 3));
+                w[v >> 2] |= (uint32_t)(int)t << (8 * (v & 3));
+            }
+            if (hist && px < p.P) {
+                if (r0 + 16 <= C) {
+#pragma unroll
+                    for (int v = 0; v < 16; v++) atomicAdd(&wh[((w[v >> 2] >> (8 * (v & 3))) & 0xffu) * kCopies], 1u);
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; v++)
+                        if (r0 + v < C) atomicAdd(&wh[((w[v >> 2] >> (8 * (v & 3))) & 0xffu) * kCopies], 1u);
+                }
             }
             if (px < p.P && r0 < C) {
                 if (INVERSE && LAYOUT == FMTC_NCHW) {

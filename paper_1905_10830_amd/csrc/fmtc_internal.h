@@ -153,7 +153,7 @@ struct Basis8Device {
     int C;
     const unsigned long long* fwd8;  // [nct][NS][64] Tq, operand order, rows of a tile permuted
     const unsigned long long* inv8;  // [nct][NS][64] Tq^T, the same
-    const long long* row_off;        // sum_c Tq[k][c] (mean_fix[c] - 256 * 128)
+    const double* row_off;           // sum_c Tq[k][c] (mean_fix[c] - 256 * 128): an integer, exact in fp64
     const int* col_sum;              // sum_k Tq[k][c]
     const int* mean_fix;             // rne(256 mu[c] / s_x)
 };
@@ -162,6 +162,9 @@ struct Basis8Device {
 hipError_t launch_quantize_u8(const Basis8Device& b, const uint8_t* d_xq, int64_t P, int64_t HW, int layout,
                               int bits, double g, uint8_t* d_syms, const CoderScratch* cs, int* n_parts,
                               hipStream_t s);
+hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size_t bytes, const Geometry& g, int bits,
+                            int64_t HW, int layout, double h, uint8_t* d_xq_hat, uint32_t* d_err, bool* applies,
+                            hipStream_t s);
 hipError_t launch_reconstruct_u8(const Basis8Device& b, const uint8_t* d_syms, int64_t P, int64_t HW, int layout,
                                  int bits, double h, uint8_t* d_xq_hat, hipStream_t s);
 
