@@ -258,8 +258,9 @@ def main():
           "bits_per_value": round(uinfo["payload_bits"] / V, 4),
           "mse": float((((usets[0]["out"].float() - usets[0]["xq"].float()) * sx) ** 2).mean().item()),
           "kernels": {k: round(1e3 * v[0], 3) for k, v in uprof.items()},
-          "note": "1 byte per value in and out; projection and reconstruction on the integer matrix cores, exact; "
-                  "histogram, table, packing and variable length decoding are the fp32 path's kernels"}
+          "note": "1 byte per value in and out; projection (with histogram) and reconstruction (inside the chunk "
+                  "decoder up to 128 channels) on the integer matrix cores, exact; table and packing by the fp32 "
+                  "path's pack kernel"}
 
     # ---- yardstick for the memory counters: one plain copy of known size (not timed) ----
     ysrc = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")

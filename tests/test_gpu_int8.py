@@ -130,3 +130,32 @@ def test_u8_codec_quality_and_errors(fmtc, oracle):
     out2, err2 = fmtc.decode_u8(b8, bad, xq.shape, 6)
     torch.cuda.synchronize()
     assert int(err2.item()) != 0
+
+
+@pytest.mark.parametrize("name,bits", [("resnet18_stage2_c128_28", 6), ("cfg0_c64_56", 8)])
+def test_u8_path_at_full_size(fmtc, oracle, name, bits):
+    """The benchmark's tensors as 8-bit activations, in the launch configuration the benchmark times: symbols,
+    stream and decoded activations equal the oracle's everywhere."""
+    calib, data = synth.workload(name, seed=0)
+    C = data.shape[-1]
+    sx = np.float32(float(data.max()) / 255.0)
+    xq = np.clip(np.rint(data / sx), 0, 255).astype(np.uint8)
+    basis = fmtc.fit_basis(dev(calib))
+    T, mu, eig, A = basis.export()
+    d = oracle.delta(A, bits)
+    Tq, sT, mf = oracle.basis8(T, mu, sx)
+    b8 = fmtc.Basis8(basis, sx)
+    want = oracle.quantize_u8(xq, Tq, sT, mf, sx, d, bits)
+    x_d = dev(xq)
+    sym = fmtc.quantize_u8(b8, x_d, bits)
+    stream, nbytes = fmtc.encode_u8(b8, x_d, bits)
+    out, err = fmtc.decode_u8(b8, stream, xq.shape, bits)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    assert np.array_equal(sym.cpu().numpy(), want)
+    h = oracle.histogram(want, bits)
+    ln = oracle.huffman_lengths(h[: 1 << bits])
+    ref_stream = oracle.pack(want, C, bits, d, ln, oracle.canonical_codes(ln))
+    nb = int(nbytes.item())
+    assert nb == len(ref_stream) and np.array_equal(stream[:nb].cpu().numpy(), ref_stream)
+    assert np.array_equal(out.cpu().numpy(), oracle.reconstruct_u8(want, xq.shape, Tq, sT, mf, sx, d, bits))
