@@ -362,9 +362,12 @@ fmtc_status upload_basis8(fmtc_basis8* b) {
     // |off| <= 127 * 1024 * 2^30 < 2^48: exact as a double
     for (int k = 0; k < C; k++) row_off[k] = (double)off64[k];
     for (int c = 0; c < C; c++) mean_fix[c] = b->mean_fix[c];
+    std::vector<double> mean_d(rows, 0.0);
+    for (int c = 0; c < C; c++) mean_d[c] = (double)b->mean_fix[c] / 256.0;
     const size_t n_op = (size_t)nct * NS * 64 * sizeof(unsigned long long);
     const size_t o_inv = n_op, o_off = 2 * n_op, o_col = o_off + sizeof(double) * rows,
-                 o_mean = o_col + sizeof(int) * rows, total = o_mean + sizeof(int) * rows;
+                 o_mean = o_col + sizeof(int) * rows, o_meand = (o_mean + sizeof(int) * rows + 7) / 8 * 8,
+                 total = o_meand + sizeof(double) * rows;
     hipError_t e;
     if ((e = hipGetDevice(&b->device)) != hipSuccess) return hip_fail(e, "hipGetDevice");
     if ((e = hipMalloc(&b->d_block, total)) != hipSuccess) return fail(FMTC_ENOMEM, "hipMalloc basis: %s", hipGetErrorString(e));
@@ -373,7 +376,8 @@ fmtc_status upload_basis8(fmtc_basis8* b) {
         (e = hipMemcpy(d + o_inv, inv.data(), n_op, hipMemcpyHostToDevice)) != hipSuccess ||
         (e = hipMemcpy(d + o_off, row_off.data(), sizeof(double) * rows, hipMemcpyHostToDevice)) != hipSuccess ||
         (e = hipMemcpy(d + o_col, col_sum.data(), sizeof(int) * rows, hipMemcpyHostToDevice)) != hipSuccess ||
-        (e = hipMemcpy(d + o_mean, mean_fix.data(), sizeof(int) * rows, hipMemcpyHostToDevice)) != hipSuccess)
+        (e = hipMemcpy(d + o_mean, mean_fix.data(), sizeof(int) * rows, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(d + o_meand, mean_d.data(), sizeof(double) * rows, hipMemcpyHostToDevice)) != hipSuccess)
         return hip_fail(e, "hipMemcpy basis");
     b->view.C = C;
     b->view.fwd8 = reinterpret_cast<const unsigned long long*>(d);
@@ -381,6 +385,7 @@ fmtc_status upload_basis8(fmtc_basis8* b) {
     b->view.row_off = reinterpret_cast<const double*>(d + o_off);
     b->view.col_sum = reinterpret_cast<const int*>(d + o_col);
     b->view.mean_fix = reinterpret_cast<const int*>(d + o_mean);
+    b->view.mean_d = reinterpret_cast<const double*>(d + o_meand);
     return FMTC_OK;
 }
 
@@ -970,8 +975,8 @@ fmtc_status fmtc_reconstruct_u8(const fmtc_basis8* basis, const uint8_t* d_syms,
     if (st != FMTC_OK) return st;
     const int64_t HW = (int64_t)H * W;
     const double delta = (double)fmtc_delta(basis->range_A, bits);
-    const double h = ((double)basis->scale_T * delta * 256.0) / (double)basis->act_scale;
-    hipError_t e = launch_reconstruct_u8(basis->view, d_syms, N * HW, HW, layout, bits, h, d_xq_hat, (hipStream_t)hip_stream);
+    const double h = ((double)basis->scale_T * delta * 256.0) / (double)basis->act_scale;  // the kernel gets h / 256 (exact)
+    hipError_t e = launch_reconstruct_u8(basis->view, d_syms, N * HW, HW, layout, bits, h / 256.0, d_xq_hat, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail(e, "8-bit reconstruction kernel");
     return FMTC_OK;
 }
@@ -1017,7 +1022,7 @@ fmtc_status fmtc_decode_u8(const fmtc_basis8* basis, const void* d_stream_in, si
         const double h = ((double)basis->scale_T * delta * 256.0) / (double)basis->act_scale;
         bool applies = false;
         hipError_t e = launch_decode_u8(basis->view, static_cast<const uint8_t*>(d_stream_in), bytes, g, bits,
-                                        (int64_t)H * W, layout, h, d_xq_hat, d_err_flag, &applies, (hipStream_t)hip_stream);
+                                        (int64_t)H * W, layout, h / 256.0, d_xq_hat, d_err_flag, &applies, (hipStream_t)hip_stream);
         if (e != hipSuccess) return hip_fail(e, "8-bit decode kernel");
         if (applies) return FMTC_OK;
     }

@@ -396,10 +396,10 @@ struct DecodeParams {
     const void* prebuilt;  // PrebuiltTables of a code table fixed beforehand, or NULL: build them from the stream
     // 8-bit reconstruction in the chunk decoder (k_decode_chunks<..., U8 = true>): the transposed 8-bit basis in
     // the operand order of the integer matrix instruction [ncs][ceil(C / 16)][64], its column sums and the mean
-    // with 8 fraction bits (both padded to ncs * 32), h = 256 s_T Delta / s_x, and the output bytes
+    // in activation units (both padded to ncs * 32), h / 256 = s_T Delta / s_x, and the output bytes
     const unsigned long long* op8;
     const int* col_sum;
-    const int* mean_fix;
+    const double* mean_d;
     double factor8;
     uint8_t* out8;
 };
@@ -728,8 +728,8 @@ constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes 
 // WAVES wavefronts per workgroup (4 or 8): one per SIMD where the chunks do not outnumber the SIMDs, two where
 // they do (the second hides the latencies of the first; the workgroup still holds one copy of the basis).
 // U8: the tile's symbols go through the 8-bit basis on the integer matrix cores instead (v_mfma_i32_32x32x16_i8;
-// exact sums, one fused fp64 multiply-add and one rounding per value, 8-bit activations out); the basis operand
-// comes from global memory through the cache, nothing of it is staged in LDS.
+// exact sums, one fused fp64 multiply-add and one rounding per value, 8-bit activations out); the 8-bit basis
+// takes the f16 basis' place in LDS.
 template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES, bool U8 = false>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k_decode_chunks(DecodeParams p) {
     constexpr int THREADS = WAVES * 64;
@@ -752,6 +752,12 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     // the basis goes from global memory straight into LDS (no registers in between), 16 bytes per lane and
     // instruction: lane l of a wavefront lands at the wavefront's LDS base + 16 l
     constexpr int kBasisPieces = NCT * NJ * 2 * 64;  // 16-byte pieces of the basis, a multiple of 64
+    if constexpr (U8) {
+        // the 8-bit basis operand, [NCT][NS][64] entries of 8 bytes, goes into the same dynamic LDS
+        const int n16 = NCT * ((C + 15) / 16) * 32;  // 16-byte pieces
+        const uint4* src = reinterpret_cast<const uint4*>(p.op8);
+        for (int i = tid; i < n16; i += THREADS) basis16[i] = src[i];
+    }
     if constexpr (!U8) {
         const uint4* src = reinterpret_cast<const uint4*>(p.Bp16);
 #pragma unroll
@@ -874,6 +880,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                 // that a lane ends up with channels ct*32 + 16*half .. + 15 of its pixel).  Symbols past C meet
                 // zero basis bytes.
                 const int NS = (C + 15) / 16;  // <= NJ
+                const unsigned long long* op8_lds = reinterpret_cast<const unsigned long long*>(basis16);
                 const int hk = 1 << (p.bits - 1);
                 long b[NJ];
 #pragma unroll
@@ -901,14 +908,14 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 #pragma unroll
                     for (int j = 0; j < NJ; j++)
                         if (j < NS)
-                            acc = __builtin_amdgcn_mfma_i32_32x32x16_i8((long)p.op8[((size_t)ct * NS + j) * 64 + lane], b[j], acc, 0, 0, 0);
+                            acc = __builtin_amdgcn_mfma_i32_32x32x16_i8((long)op8_lds[(ct * NS + j) * 64 + lane], b[j], acc, 0, 0, 0);
                     const int r0 = ct * 32 + 16 * half;
                     uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
                     for (int v = 0; v < 16; v++) {
                         const int r = r0 + v;  // < NCT * 32: the per-channel arrays are padded to that
                         const int m = acc[v] + (128 - hk) * p.col_sum[r];
-                        const double t = fmin(fmax(rint(fma((double)m, p.factor8, (double)p.mean_fix[r]) * 0.00390625), 0.0), 255.0);
+                        const double t = fmin(fmax(rint(fma((double)m, p.factor8, p.mean_d[r])), 0.0), 255.0);
                         w[v >> 2] |= (uint32_t)(int)t << (8 * (v & 3));
                     }
                     if (my_px < TP && r0 < C) {
@@ -1146,7 +1153,7 @@ hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size
     const int ncs = (C + 31) / 32;
     *applies = ncs <= 4;
     if (!*applies) return hipSuccess;
-    if (!d_stream || !d_xq_hat || !d_err || !b.inv8 || !b.col_sum || !b.mean_fix || b.C != C) return hipErrorInvalidValue;
+    if (!d_stream || !d_xq_hat || !d_err || !b.inv8 || !b.col_sum || !b.mean_d || b.C != C) return hipErrorInvalidValue;
     DecodeParams p{};
     p.stream = d_stream;
     p.bytes = bytes;
@@ -1169,10 +1176,11 @@ hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size
     p.g_spc = g.subs_per_chunk;
     p.op8 = b.inv8;
     p.col_sum = b.col_sum;
-    p.mean_fix = b.mean_fix;
+    p.mean_d = b.mean_d;
     p.factor8 = h;
     p.out8 = d_xq_hat;
     const bool al = (C % 4) == 0;
+    const size_t lds = (size_t)ncs * ((C + 15) / 16) * 64 * 8;  // the basis operand
     const bool eight = g.n_chunks > 1024 && ncs != 3;
     const int waves = eight ? 8 : 4;
     unsigned gx = (g.n_chunks + waves - 1) / waves;
@@ -1180,7 +1188,12 @@ hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size
     if (gx > cap) gx = cap;
     hipError_t el = hipSuccess;
 #define FMTC_DECU(NCT, LAY, AL, WV) \
-    el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, true>, dim3(gx), dim3(WV * 64), 0, s, p)
+    do {                                                                                                         \
+        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, true>), \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);              \
+        if (ea != hipSuccess) return ea;                                                                         \
+        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, true>, dim3(gx), dim3(WV * 64), lds, s, p);      \
+    } while (0)
 #define FMTC_DECU_N(LAY, AL)                                                                                     \
     do {                                                                                                         \
         if (ncs == 1) { if (eight) FMTC_DECU(1, LAY, AL, 8); else FMTC_DECU(1, LAY, AL, 4); }                    \

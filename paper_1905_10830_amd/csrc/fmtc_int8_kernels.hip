@@ -4,7 +4,7 @@
 // results are defined bit for bit:
 //   forward  n = 256 sum_c Tq[k][c] xq[c] - sum_c Tq[k][c] mf[c],  level = rne(n * g),  g = s_T s_x / (256 Delta)
 //   inverse  m = sum_k Tq[k][c] (s[k] - 2^(b-1)),  v = fma(m, h, mf[c]),  xq^ = clamp(rne(v / 256), 0, 255),
-//            h = 256 s_T Delta / s_x
+//            h = 256 s_T Delta / s_x   (computed as rne(fma(m, h / 256, mf[c] / 256)): scaling by 2^-8 is exact)
 // The matrix instruction multiplies signed bytes; unsigned activations and symbols enter as (value - 128) (one XOR)
 // and the difference is folded into per-row integer offsets prepared with the basis.
 //
@@ -50,10 +50,10 @@ struct Int8Params {
     const unsigned long long* op8;  // [nct][NS][64] basis (forward) or its transpose (inverse), operand order
     const double* row_off;          // forward [nct * 32]: sum_c Tq[k][c] (mf[c] - 256 * 128), an integer below 2^53
     const int* col_sum;             // inverse [nct * 32]: sum_k Tq[k][c]
-    const int* mean_fix;            // inverse [nct * 32]
+    const double* mean_d;           // inverse [nct * 32]: the mean in activation units (mean_fix / 256, exact)
     int64_t P, HW, n_tiles;
     int C, NS, nct, bits;
-    double factor;                  // g (forward) or h (inverse)
+    double factor;                  // g (forward) or h / 256 (inverse)
     // forward, whole encoder only (else null): one partial histogram per workgroup [gridDim.x][2^bits], and the
     // coder's scratch that the first kernel of a call clears
     uint32_t* hist_parts;
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void k_int8_tiles(Int8Params p) {
                     t = fmin(fmax(rint(n * p.factor), (double)-hk), (double)(hk - 1)) + (double)hk;
                 } else {
                     const int m = acc[v] + (128 - hk) * p.col_sum[r];
-                    t = fmin(fmax(rint(fma((double)m, p.factor, (double)p.mean_fix[r]) * 0.00390625), 0.0), 255.0);
+                    t = fmin(fmax(rint(fma((double)m, p.factor, p.mean_d[r])), 0.0), 255.0);
                 }
                 w[v >> 2] |= (uint32_t)(int)t << (8 * (v & 3));
             }
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void k_int8_tiles(Int8Params p) {
 
 template <bool INVERSE>
 static hipError_t launch_int8(int kernel_id, const Int8Params& p, int layout, int* n_parts, hipStream_t s) {
-    if (!p.in || !p.out || !p.op8 || (!INVERSE && !p.row_off) || (INVERSE && (!p.col_sum || !p.mean_fix)))
+    if (!p.in || !p.out || !p.op8 || (!INVERSE && !p.row_off) || (INVERSE && (!p.col_sum || !p.mean_d)))
         return hipErrorInvalidValue;
     if (p.P < 1 || p.C < 1 || p.C > 1024 || p.NS != (p.C + 15) / 16 || p.nct != (p.C + 31) / 32 || p.HW < 1 ||
         p.n_tiles != (p.P + 31) / 32 || p.bits < 2 || p.bits > 8)
@@ -212,7 +212,7 @@ hipError_t launch_quantize_u8(const Basis8Device& b, const uint8_t* d_xq, int64_
     p.op8 = b.fwd8;
     p.row_off = b.row_off;
     p.col_sum = nullptr;
-    p.mean_fix = nullptr;
+    p.mean_d = nullptr;
     p.P = P;
     p.HW = HW;
     p.n_tiles = (P + 31) / 32;
@@ -239,7 +239,7 @@ hipError_t launch_reconstruct_u8(const Basis8Device& b, const uint8_t* d_syms, i
     p.op8 = b.inv8;
     p.row_off = nullptr;
     p.col_sum = b.col_sum;
-    p.mean_fix = b.mean_fix;
+    p.mean_d = b.mean_d;
     p.P = P;
     p.HW = HW;
     p.n_tiles = (P + 31) / 32;

@@ -156,6 +156,7 @@ struct Basis8Device {
     const double* row_off;           // sum_c Tq[k][c] (mean_fix[c] - 256 * 128): an integer, exact in fp64
     const int* col_sum;              // sum_k Tq[k][c]
     const int* mean_fix;             // rne(256 mu[c] / s_x)
+    const double* mean_d;            // mean_fix / 256 (exact): the mean in activation units
 };
 // cs == nullptr: symbols only; else the kernel also clears the coder's scratch and writes one partial histogram per
 // workgroup (*n_parts of them), as the fp32 projection kernels do.
