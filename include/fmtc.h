@@ -271,8 +271,10 @@ fmtc_status fmtc_reconstruct_u8(const fmtc_basis8 *basis, const uint8_t *d_syms,
                                 fmtc_layout layout, int bits, uint8_t *d_xq_hat, void *hip_stream);
 /* Whole encoder / decoder on 8-bit activations: fmtc_quantize_u8 followed by
  * the coder of fmtc_code_symbols (same stream, bound and workspace size as
- * fmtc_encode), and fmtc_decode_symbols followed by fmtc_reconstruct_u8 (the
- * decoder's workspace holds the symbols: at least P*C bytes, 16-byte aligned).
+ * fmtc_encode), and the decoder: up to 128 channels one kernel (variable length
+ * decoding and the integer reconstruction; d_workspace may be NULL), beyond that
+ * fmtc_decode_symbols followed by fmtc_reconstruct_u8 with the symbols in
+ * d_workspace (at least P*C bytes, 16-byte aligned).
  * Errors and *d_err_flag as for fmtc_encode / fmtc_decode. */
 fmtc_status fmtc_encode_u8(const fmtc_basis8 *basis, const uint8_t *d_xq, int64_t N, int C, int H, int W,
                            fmtc_layout layout, int bits, int chunk_syms, void *d_stream_out, size_t cap,

@@ -266,13 +266,14 @@ def decode_u8(basis8, stream_in, shape, bits, layout=NHWC, out=None, err_flag=No
     if err_flag is None:
         err_flag = torch.zeros(1, dtype=torch.int32, device=stream_in.device)
     n, c, h, w = _dims(out, layout)
-    if workspace is None:
+    if workspace is None and c > 128:  # narrower tensors are decoded and reconstructed by one kernel
         workspace = torch.empty(n * h * w * c, dtype=torch.uint8, device=stream_in.device)
     _check(load_library().fmtc_decode_u8(basis8._h, _dev(stream_in, torch.uint8),
                                          stream_in.numel() if nbytes is None else int(nbytes),
                                          _dev(out, torch.uint8), n, c, h, w, layout, bits,
-                                         ctypes.c_void_p(err_flag.data_ptr()), _dev(workspace, torch.uint8),
-                                         workspace.numel(), _stream()))
+                                         ctypes.c_void_p(err_flag.data_ptr()),
+                                         None if workspace is None else _dev(workspace, torch.uint8),
+                                         0 if workspace is None else workspace.numel(), _stream()))
     return out, err_flag
 
 

@@ -1009,12 +1009,15 @@ fmtc_status fmtc_encode_u8(const fmtc_basis8* basis, const uint8_t* d_xq, int64_
 fmtc_status fmtc_decode_u8(const fmtc_basis8* basis, const void* d_stream_in, size_t bytes, uint8_t* d_xq_hat,
                            int64_t N, int C, int H, int W, fmtc_layout layout, int bits, uint32_t* d_err_flag,
                            void* d_workspace, size_t ws_bytes, void* hip_stream) {
-    if (!d_workspace || !d_stream_in || !d_err_flag) return fail(FMTC_EINVAL, "NULL argument");
-    fmtc_status st = check_u8_call(basis, d_workspace, d_xq_hat, N, C, H, W, layout, bits);
+    if (!d_stream_in || !d_err_flag) return fail(FMTC_EINVAL, "NULL argument");
+    fmtc_status st = check_u8_call(basis, d_stream_in, d_xq_hat, N, C, H, W, layout, bits);
     if (st != FMTC_OK) return st;
     const int64_t P = N * (int64_t)H * W;
-    if (ws_bytes < (size_t)P * (size_t)C) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, (size_t)P * (size_t)C);
-    if (!aligned(d_stream_in, 16) || !aligned(d_err_flag, 4)) return fail(FMTC_EINVAL, "misaligned pointer");
+    if (!aligned(d_err_flag, 4)) return fail(FMTC_EINVAL, "misaligned pointer");
+    if (C > 128) {  // wider tensors go through the symbols in the workspace
+        if (!d_workspace || !aligned(d_workspace, 16)) return fail(FMTC_EINVAL, "workspace is NULL or misaligned");
+        if (ws_bytes < (size_t)P * (size_t)C) return fail(FMTC_EBUFSIZE, "workspace too small: %zu < %zu", ws_bytes, (size_t)P * (size_t)C);
+    }
     {   // up to 128 channels: one kernel, the symbols never leave the chip
         Geometry g;
         if (!make_geometry(P, C, 4096, &g)) return fail(FMTC_EINVAL, "bad geometry");

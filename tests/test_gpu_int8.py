@@ -121,8 +121,12 @@ def test_u8_codec_quality_and_errors(fmtc, oracle):
     with pytest.raises(fmtc.FmtcError) as e:
         fmtc.quantize_u8(b8, x_d, 9)
     assert e.value.status == fmtc.EINVAL
+    # up to 128 channels the decoder needs no workspace; wider tensors refuse one that cannot hold the symbols
+    xw, sxw, Tw, muw, Aw = make_case(oracle, 144, 6, 7, 2, 18, "relu6", 43)
+    b8w = fmtc.Basis8(fmtc.basis_import(Tw, muw, Aw), sxw)
+    sw, nw = fmtc.encode_u8(b8w, dev(xw), 5)
     with pytest.raises(fmtc.FmtcError) as e:
-        fmtc.decode_u8(b8, stream, xq.shape, 6, workspace=torch.empty(1024, dtype=torch.uint8, device="cuda"))
+        fmtc.decode_u8(b8w, sw, xw.shape, 5, workspace=torch.empty(1024, dtype=torch.uint8, device="cuda"))
     assert e.value.status == fmtc.EBUFSIZE
     # a damaged stream is flagged and nothing faults
     bad = stream.clone()
