@@ -44,6 +44,7 @@ def main():
     ap.add_argument("--layout", default="nhwc", choices=["nhwc", "nchw"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--hot", action="store_true", help="one buffer set only (cache-hot figure)")
+    ap.add_argument("--keep", type=int, default=0, help="truncate the basis to this many components (0: all)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a one-GPU codec; run it with --gpus 1 "
@@ -71,6 +72,8 @@ def main():
 
     # ---- offline: fit the basis on the calibration batch (GPU moments + host eigensolver) ----
     basis = fmtc.fit_basis(torch.from_numpy(synth.to_layout(calib, layout)).cuda(), layout)
+    if args.keep:
+        basis = basis.truncate(args.keep)
 
     # ---- buffer sets ----
     cap = fmtc.encode_bound(P, C, bits)
@@ -300,7 +303,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "shape_NCHW": [N, C, H, W], "layout": args.layout, "bits": bits,
-                   "chunk_syms": 4096, "buffer_sets": R, "cache": "hot" if args.hot else "cold (rotating > 256 MB)"},
+                   "chunk_syms": 4096, "keep": args.keep or C, "buffer_sets": R, "cache": "hot" if args.hot else "cold (rotating > 256 MB)"},
         "arithmetic": "fp32 in/out; projections as split-f16 matrix products with fp32 accumulation, fp64 where a "
                       "rounding decision is close",
         "cache_hot_value": round(in_bytes / (dt_hot / args.steps) / 1e9, 3),

@@ -18,6 +18,7 @@ struct fmtc_basis {
     float *d_mu = nullptr, *d_T = nullptr;
     uint16_t *d_fwd16 = nullptr, *d_inv16 = nullptr;
     float row_norm = 1.f;  // largest Euclidean norm of a row of T (1 for an orthonormal basis)
+    int active_rows = 0;   // rows up to the last one that is not all zero
     int device = 0;
 };
 
@@ -109,6 +110,10 @@ fmtc_status upload_basis(fmtc_basis* b) {
         if (n2 > worst) worst = n2;
     }
     b->row_norm = (float)std::sqrt(worst);
+    b->active_rows = 1;
+    for (int k = 0; k < C; k++)
+        for (int c = 0; c < C; c++)
+            if (b->T[(size_t)k * C + c] != 0.f) { b->active_rows = k + 1; break; }
     for (int c = 0; c < C; c++) mu[c] = b->mu[c];
     hipError_t e;
     const size_t mat = sizeof(float) * (size_t)Cpad * Cpad;
@@ -131,6 +136,7 @@ BasisDevice device_view(const fmtc_basis* b) {
     v.inv16 = b->d_inv16;
     v.fwd16 = b->d_fwd16;
     v.row_norm = b->row_norm;
+    v.active_rows = b->active_rows;
     v.mu = b->d_mu;
     v.T = b->d_T;
     return v;

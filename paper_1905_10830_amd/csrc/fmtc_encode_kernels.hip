@@ -1567,6 +1567,22 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             ((s_red[4 * K + tid] + s_red[5 * K + tid]) + (s_red[6 * K + tid] + s_red[7 * K + tid]));
 }
 
+// Columns [c0, C) of the symbols [P][C] set to one value (c0 and C multiples of 16), and one row of partial
+// counts that says so: what the tiled projection leaves out when the basis' last rows are all zero (a truncated
+// basis: those coefficients are 0, their symbol the zero level).
+__global__ __launch_bounds__(256) void k_fill_symbol_columns(uint8_t* __restrict__ syms, int64_t P, int C, int c0,
+                                                             uint32_t value, int bits, uint32_t* __restrict__ hist_row) {
+    const uint32_t v4 = value * 0x01010101u;
+    const int64_t per_px = (C - c0) / 16;
+    const int64_t n = P * per_px;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const int64_t px = i / per_px, j = i - px * per_px;
+        *reinterpret_cast<uint4*>(syms + (size_t)px * (size_t)C + (size_t)c0 + 16 * (size_t)j) = make_uint4(v4, v4, v4, v4);
+    }
+    if (blockIdx.x == 0 && (int)threadIdx.x < (1 << bits))
+        hist_row[threadIdx.x] = threadIdx.x == value ? (uint32_t)(P * (int64_t)(C - c0)) : 0u;
+}
+
 static hipError_t launch_gemm(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
                               int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
     const int ncs = b.Cpad / 32, NJ = b.Cpad / 16;
@@ -1596,10 +1612,24 @@ static hipError_t launch_gemm(const BasisDevice& b, const float* d_x, int64_t P,
     // every pointer the kernel follows is set (a field left out here would be a wild pointer on the device)
     if (!p.x || !p.basis16 || !p.mu || !p.Trow || !p.syms || !p.hist_parts || !p.ctrl || !p.lookback)
         return hipErrorInvalidValue;
-    const int gy = (ncs + 3) / 4;
+    // groups of four coefficient tiles; those whose rows of the basis are all zero (truncation) are not computed:
+    // k_fill_symbol_columns writes their symbols and counts
+    const int gy_all = (ncs + 3) / 4;
+    int gy = ((b.active_rows + 31) / 32 + 3) / 4;
+    gy = gy < 1 ? 1 : (gy > gy_all ? gy_all : gy);
     int64_t gx = p.n_ptg;
-    if (gx * gy > kMaxHistParts) gx = kMaxHistParts / gy;
-    *n_parts = (int)(gx * gy);
+    if (gx * gy_all > kMaxHistParts) gx = kMaxHistParts / gy_all;
+    *n_parts = (int)(gx * gy) + (gy < gy_all ? 1 : 0);
+    if (gy < gy_all) {
+        const int c0 = gy * 128;  // < C, and C - c0 is a multiple of 16 like C
+        const int64_t pieces = P * ((b.C - c0) / 16);
+        int64_t blocks = (pieces + 255) / 256;
+        blocks = blocks > 2048 ? 2048 : blocks;
+        hipLaunchKernelGGL(k_fill_symbol_columns, dim3((unsigned)blocks), dim3(256), 0, s, d_syms, P, b.C, c0,
+                           (uint32_t)(1 << (bits - 1)), bits, cs.hist_parts + (size_t)(gx * gy) * ((size_t)1 << bits));
+        hipError_t ef = hipGetLastError();
+        if (ef != hipSuccess) return ef;
+    }
     // 8 wavefronts per tile while every tile has a compute unit of its own, 4 (two workgroups per compute unit) beyond
     const bool eight = p.n_ptg * gy <= 256;
     const int waves = eight ? 8 : 4;

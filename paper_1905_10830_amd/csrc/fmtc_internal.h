@@ -116,6 +116,7 @@ struct BasisDevice {
     const uint16_t* fwd16;
     const uint16_t* inv16;
     float row_norm;        // largest Euclidean norm of a row of T
+    int active_rows;       // rows of T up to the last one that is not all zero (a truncated basis has fewer than C)
     const float* mu;       // [Cpad], zero padded
     const float* T;        // [C][C] row major, unpacked
 };

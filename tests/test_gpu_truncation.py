@@ -28,6 +28,8 @@ CASES = [
     (128, 14, 14, 3, 32, "relu", 4, 127),
     (256, 14, 14, 5, 64, "relu", 4, 40),     # tiled matrix-product kernels, three coefficient tiles of zeros
     (512, 7, 7, 9, 128, "relu", 5, 130),
+    (960, 7, 7, 2, 120, "relu6", 5, 200),    # 8 groups of coefficient tiles, 6 of them skipped and filled
+    (512, 7, 7, 3, 128, "relu", 4, 16),      # all but the first group skipped
     (200, 6, 7, 3, 25, "relu", 5, 17),       # channel count that is no multiple of 16
     (50, 10, 10, 2, 10, "relu", 5, 1),
     (3, 17, 5, 1, 2, "none", 2, 2),
