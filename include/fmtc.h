@@ -117,7 +117,8 @@ void fmtc_fit_state_destroy(fmtc_fit_state *state);
  * the kept components plus the mean.  The container keeps C symbols per pixel,
  * so a dropped coefficient still costs its (short) code word.  Of the kernels,
  * the projection of tensors wider than 160 channels skips the dropped rows in
- * groups of 128.  `basis` stays valid; release both. */
+ * groups of 128 and their decoder in steps of 16.  `basis` stays valid; release
+ * both. */
 fmtc_status fmtc_basis_truncate(const fmtc_basis *basis, int keep, fmtc_basis **out);
 
 /* Builds a handle from host arrays (h_T: C*C row major, h_mu: C).  The way to

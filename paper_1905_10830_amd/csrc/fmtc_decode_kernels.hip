@@ -394,6 +394,7 @@ struct DecodeParams {
     size_t g_off_chunk_off, g_off_sub_bits, g_off_payload;
     uint32_t g_n_chunks, g_spc;
     const void* prebuilt;  // PrebuiltTables of a code table fixed beforehand, or NULL: build them from the stream
+    int active_steps;      // contraction steps of 16 coefficients up to the basis' last row that is not all zero
     // 8-bit reconstruction in the chunk decoder (k_decode_chunks<..., U8 = true>): the transposed 8-bit basis in
     // the operand order of the integer matrix instruction [ncs][ceil(C / 16)][64], its column sums and the mean
     // in activation units (both padded to ncs * 32), h / 256 = s_T Delta / s_x, and the output bytes
@@ -496,6 +497,8 @@ __global__ __launch_bounds__(512) void k_decode_tiles(DecodeParams p) {
     const _Float16 level_off = (_Float16)(float)(1024 + (1 << (p.bits - 1)));
     const halfx2 level_off2 = {level_off, level_off};
     const int NJ = p.ncs * 2;  // steps of 16 coefficients
+    // ... of which the first NJA meet basis rows that are not all zero (fewer than NJ for a truncated basis)
+    const int NJA = p.active_steps < 1 ? 1 : (p.active_steps > NJ ? NJ : p.active_steps);
 
     // x_hat = Delta (sum q T_hi + 2^-11 sum q T_lo) + mu for one 32 x 32 tile (channel tile ct, pixel tile pt of a
     // workgroup tile of TP pixels starting at pixel px_tile0).  Accumulator r of lane l is element
@@ -633,7 +636,7 @@ __global__ __launch_bounds__(512) void k_decode_tiles(DecodeParams p) {
                 // steps past the end repeat the last one: the number of loads in flight is the same in every step
                 auto issue = [&](int ks) {
                     const int slot = ks % 3;
-                    ks = ks < NJ ? ks : NJ - 1;
+                    ks = ks < NJA ? ks : NJA - 1;
 #pragma unroll
                     for (int q = 0; q < BPW; q++) {
                         const int blk = wave * BPW + q;  // (channel tile blk / 2, part blk % 2)
@@ -645,7 +648,7 @@ __global__ __launch_bounds__(512) void k_decode_tiles(DecodeParams p) {
                 };
                 issue(0);
                 issue(1);
-                for (int ks = 0; ks < NJ; ks++) {
+                for (int ks = 0; ks < NJA; ks++) {
                     wait_loads<BPW>();  // this wavefront's blocks of step ks have landed
                     __syncthreads();    // everybody's have, and everybody is done with the slot of step ks - 1
                     issue(ks + 2);
@@ -1040,6 +1043,7 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     p.bits = bits;
     p.ncs = ncs;
     p.Bp16 = b ? b->inv16 : nullptr;
+    p.active_steps = b ? (b->active_rows + 15) / 16 : 0;
     p.mu = b ? b->mu : nullptr;
     p.xhat = d_xhat;
     p.syms_out = d_syms;
