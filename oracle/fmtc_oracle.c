@@ -18,9 +18,19 @@
  * Delta are rounded to fp32 once; every later step consumes those fp32 values.
  * No blocking, fusion or reordering: each function is one step of the method.
  *
+ * Beyond that: the table fixed at calibration time (counts + 1), the
+ * truncated projection and reconstruction (section 4 "Ablation study"), the
+ * dynamic range measured on a given tensor (calibration over several
+ * tensors), and the integer arithmetic of the 8-bit basis with 8-bit
+ * activations (section 3.1 "Linear transform", section 5), which is exact
+ * integers plus one correctly rounded fp64 operation per value.
+ *
  * Pinned by tests/test_oracle_*.py (closed forms, hand-worked codes, Kraft
  * equality, brute-force optimality, entropy bounds, numpy.linalg.eigh
- * cross-check).  Parity unpinned: none of the functions below; the absolute
+ * cross-check; truncation: the dropped eigenvalues' sum and a two-channel hand
+ * case; 8-bit path: hand cases with ties and clamps, a brute force in exact
+ * rationals, the floating-point functions above on the dequantized inputs).
+ * Parity unpinned: none of the functions below; the absolute
  * bits/value of the paper's tables (real networks) cannot be reproduced here.
  */
 #include <math.h>
