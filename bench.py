@@ -48,7 +48,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a one-GPU codec; run it with --gpus 1 "
-                 "(no multi-GPU path exists, see DESIGN.md for how it would shard)")
+                 "(no multi-GPU path exists: the codec shards over pixels, each GPU coding its own share)")
 
     import numpy as np
     import torch
