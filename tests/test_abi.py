@@ -141,3 +141,13 @@ def test_u8_argument_errors_are_reported_on_the_host(lib):
     assert lib.fmtc_encode_u8(None, None, 1, 16, 4, 4, fmtc.NHWC, 6, 4096, None, 0, None, None, 0, None) == fmtc.EINVAL
     assert lib.fmtc_decode_u8(None, None, 0, None, 1, 16, 4, 4, fmtc.NHWC, 6, None, None, 0, None) == fmtc.EINVAL
     lib.fmtc_basis8_destroy(None)  # a no-op
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is a one-GPU measurement: any other count ends with a message, before anything touches a GPU."""
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one-GPU" in r.stderr and "--gpus 1" in r.stderr
