@@ -826,6 +826,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     const uint32_t payload_words = sv.payload_words;
     const uint64_t V = (uint64_t)p.P * (uint64_t)C;
     const float delta = sv.delta;
+    // contraction steps that meet a non-zero row of the basis (all of them unless the basis is truncated)
+    const int NJA = p.active_steps < 1 ? 1 : (p.active_steps > NJ ? NJ : p.active_steps);
     // 0x6400 | s is the f16 number 1024 + s: the level s - 2^(b-1) is that minus (1024 + 2^(b-1)), exactly
     const _Float16 level_off = (_Float16)(float)(1024 + (1 << (p.bits - 1)));
     const halfx2 level_off2 = {level_off, level_off};
@@ -950,6 +952,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                 for (int r = 0; r < 16; r++) { acc[ct][r] = 0.f; acl[ct][r] = 0.f; }
 #pragma unroll
             for (int j = 0; j < NJ; j++) {
+                if (j >= NJA) continue;  // wavefront-uniform: steps past the basis' last non-zero row (truncation)
                 // the eight symbols 16j + 8*half .. + 7 of this lane's pixel (coefficients past C meet zero basis
                 // entries; whatever finite level the tile's bytes give there does not count)
                 const uint32_t n = rowbase + 16u * (uint32_t)j;
@@ -1178,6 +1181,7 @@ hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size
     p.g_off_payload = g.off_payload;
     p.g_n_chunks = g.n_chunks;
     p.g_spc = g.subs_per_chunk;
+    p.active_steps = ncs * 2;  // (not used by the 8-bit variant)
     p.op8 = b.inv8;
     p.col_sum = b.col_sum;
     p.mean_d = b.mean_d;
