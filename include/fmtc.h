@@ -115,10 +115,10 @@ void fmtc_fit_state_destroy(fmtc_fit_state *state);
  * <= C.  With it every entry point works unchanged: a dropped coefficient is 0,
  * its symbol the zero level 2^(bits-1), and the reconstruction is the sum over
  * the kept components plus the mean.  The container keeps C symbols per pixel,
- * so a dropped coefficient still costs its (short) code word.  Of the kernels,
- * the projection of tensors wider than 160 channels skips the dropped rows in
- * groups of 128 and their decoder in steps of 16.  `basis` stays valid; release
- * both. */
+ * so a dropped coefficient still costs its (short) code word.  The kernels
+ * skip the dropped rows in the units they work in (projection: tiles of 32 or
+ * groups of 128 coefficients; decoders: steps of 16).  `basis` stays valid;
+ * release both. */
 fmtc_status fmtc_basis_truncate(const fmtc_basis *basis, int keep, fmtc_basis **out);
 
 /* Builds a handle from host arrays (h_T: C*C row major, h_mu: C).  The way to

@@ -446,6 +446,7 @@ struct RowParams {
     const float* Trow;        // [C][C] row major, for the exact decisions
     int64_t P, HW;
     int C, bits;
+    int active_tiles;         // 32-coefficient tiles up to the basis' last row that is not all zero
     float inv_delta, delta;
     float kappa;              // distance to a rounding boundary (in steps) below which a value of a pixel with
                               // |x - mu|_2 = 1 is decided exactly
@@ -664,6 +665,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         auto project_tile = [&](int kt, floatx16& am, floatx16& ac) {
 #pragma unroll
             for (int r = 0; r < 16; r++) { am[r] = 0.f; ac[r] = 0.f; }
+            if (kt >= p.active_tiles) return;  // all rows of the tile are zero (truncated basis): so are its coefficients
 #pragma unroll
             for (int j = 0; j < NJ; j++) {
                 const uint4 th4 = basis16[((kt * NJ + j) * 2) * 64 + lane];
@@ -878,6 +880,7 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     p.HW = HW;
     p.C = b.C;
     p.bits = bits;
+    p.active_tiles = (b.active_rows + 31) / 32;
     p.inv_delta = (float)(1.0 / (double)delta);
     p.delta = delta;
     // The fast pass is off by at most about 2^-22 sum |T[k][c]| |x[c] - mu[c]| (three representation errors of
@@ -989,6 +992,7 @@ hipError_t launch_encode_static_fused(const BasisDevice& b, const float* d_x, in
     p.HW = HW;
     p.C = b.C;
     p.bits = bits;
+    p.active_tiles = (b.active_rows + 31) / 32;
     p.inv_delta = (float)(1.0 / (double)delta);
     p.delta = delta;
     p.kappa = 1.9073486e-6f /* 2^-19 */ * b.row_norm * p.inv_delta;  // see launch_rows
