@@ -77,15 +77,26 @@ __global__ __launch_bounds__(256) void k_int8_tiles(Int8Params p) {
     // Histogram (forward, whole encoder), in dynamic LDS: kCopies interleaved copies per wavefront (bin s of copy q
     // at word s * kCopies + q, lane l counts in copy l % kCopies), because most symbols of a tile are the same few
     // values and one copy would serialise the lanes on a few words.
-    extern __shared__ uint32_t s_hist[];  // [4][K * kCopies], only if hist
+    // The basis operand of narrow tensors (NSR > 0: at most 8 steps, 16 KB) is copied into LDS first; wide ones read
+    // it from global memory through the cache.
+    extern __shared__ __align__(16) uint32_t s_dyn[];  // basis operand [nct][NS][64] x 8 bytes if NSR > 0, then
+                                                       // the histogram [4][K * kCopies] if hist
+    const int basis_words = NSR > 0 ? p.nct * NS * 128 : 0;
+    uint32_t* s_hist = s_dyn + basis_words;
     const bool hist = !INVERSE && p.hist_parts != nullptr;
     const int K = 1 << p.bits;
     uint32_t* wh = s_hist + (size_t)wave * K * kCopies + (lane & (kCopies - 1));
+    if (NSR > 0) {
+        const uint4* src = reinterpret_cast<const uint4*>(p.op8);
+        uint4* dst = reinterpret_cast<uint4*>(s_dyn);
+        for (int i = threadIdx.x; i < basis_words / 4; i += 256) dst[i] = src[i];
+    }
     if (hist) {
         zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
         for (int i = threadIdx.x; i < 4 * K * kCopies; i += 256) s_hist[i] = 0u;
-        __syncthreads();
     }
+    if (NSR > 0 || hist) __syncthreads();
+    const unsigned long long* op8 = NSR > 0 ? reinterpret_cast<const unsigned long long*>(s_dyn) : p.op8;
     for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < p.n_tiles; tile += (int64_t)gridDim.x * 4) {
         const int64_t px = tile * 32 + l32;
         auto operand = [&](int s) -> long {
@@ -102,7 +113,7 @@ __global__ __launch_bounds__(256) void k_int8_tiles(Int8Params p) {
         }
         for (int kt = 0; kt < p.nct; kt++) {
             v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-            const unsigned long long* a8 = p.op8 + ((size_t)kt * NS) * 64 + lane;
+            const unsigned long long* a8 = op8 + ((size_t)kt * NS) * 64 + lane;
             if (NSR > 0) {
 #pragma unroll
                 for (int s = 0; s < NSR; s++)
@@ -183,7 +194,8 @@ static hipError_t launch_int8(int kernel_id, const Int8Params& p, int layout, in
     if (gx > cap) gx = cap;
     if (n_parts) *n_parts = (int)gx;
     const dim3 grid((unsigned)gx), block(256);
-    const size_t lds = p.hist_parts ? sizeof(uint32_t) * 4 * kCopies * ((size_t)1 << p.bits) : 0;
+    const size_t lds = (p.NS <= 8 ? (size_t)p.nct * p.NS * 512 : 0) +  // the basis operand of the NSR = 8 kernels
+                       (p.hist_parts ? sizeof(uint32_t) * 4 * kCopies * ((size_t)1 << p.bits) : 0);
     const bool planar = layout == FMTC_NCHW;  // of the activations: read by the forward kernel, written by the inverse
 #define FMTC_INT8(LAY, NSR)                                                                                     \
     do {                                                                                                        \
