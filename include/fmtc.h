@@ -148,11 +148,7 @@ size_t fmtc_encode_bound(int64_t P, int C, int bits, int chunk_syms);
 size_t fmtc_workspace_size(int64_t P, int C, int bits, int chunk_syms);
 /* ---- hot path ---- */
 /* Calls on different HIP streams may overlap with each other and with any other
- * work on the device.  A process whose encoder calls never do can set
- * FMTC_EXCLUSIVE_DEVICE=1 in the environment (read once): tensors of more than
- * 16.8 M values are then packed with a fixed share of the chunks per workgroup,
- * 15-25 us faster, which is only safe while the pack kernel has the device to
- * itself (otherwise its waits can run out and the stream comes out invalid). */
+ * work on the device (each with its own workspace and outputs). */
 /* Whole encoder (section 3: transform, quantizer, VLC).  Reads d_x once, writes
  * the container to d_stream_out (16-byte aligned, capacity cap >=
  * fmtc_encode_bound) and, if d_out_bytes != NULL, the stream size in bytes.

@@ -228,6 +228,7 @@ CoderScratch coder_scratch(uint8_t* ws, const EncodePlan& pl) {
     cs.ctrl = reinterpret_cast<CoderCtrl*>(ws + pl.ws.off_ctrl);
     cs.lookback = reinterpret_cast<unsigned long long*>(ws + pl.ws.off_lookback);
     cs.n_groups = pack_groups(pl.g.n_chunks);
+    cs.chunk_bits = reinterpret_cast<uint32_t*>(ws + pl.ws.off_chunk_bits);
     return cs;
 }
 

@@ -10,8 +10,6 @@
 //   k_pack           one wavefront per chunk, one lane per run of 64 symbols: run sizes,
 //                    the chunk's place in the payload (a running sum over the chunk
 //                    groups handed from workgroup to workgroup), then the code bits.
-#include <cstdlib>
-
 #include "fmtc_device.h"
 #include "fmtc_internal.h"
 #include "fmtc_pack_device.h"
@@ -442,59 +440,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
     const bool aligned4 = (p.chunk_syms & 3u) == 0;  // every chunk starts on a 4-byte boundary of the symbols
 
-    // the symbols of a chunk: register q of lane l holds symbols 256q + 4l .. + 3 (zero past the chunk's end)
-    auto chunk_len = [&](uint32_t ch) -> uint32_t {
-        if (ch >= p.n_chunks) return 0u;
-        const uint64_t c0 = (uint64_t)ch * p.chunk_syms;
-        return (uint32_t)((p.V - c0 < p.chunk_syms) ? (p.V - c0) : p.chunk_syms);
-    };
-    auto load_chunk = [&](uint32_t ch, uint32_t (&w)[16]) {
-        const uint32_t clen = chunk_len(ch);
-        const uint8_t* src = p.syms + (uint64_t)ch * p.chunk_syms;
-        if (aligned4) {
-#pragma unroll
-            for (int q = 0; q < 16; q++) {
-                const uint32_t o = 256u * q + 4u * (uint32_t)lane;
-                w[q] = (o + 4u <= clen) ? *reinterpret_cast<const uint32_t*>(src + o) : 0u;
-            }
-            if (clen & 3u) {  // the last, partial word of the tensor
-                const uint32_t t = clen & ~3u;
-                uint32_t v = 0;
-                if ((uint32_t)lane == ((t >> 2) & 63u))
-                    for (uint32_t i = 0; i < (clen & 3u); i++) v |= (uint32_t)src[t + i] << (8 * i);
-#pragma unroll
-                for (int q = 0; q < 16; q++)
-                    if ((uint32_t)q == (t >> 8)) w[q] |= v;
-            }
-        } else {
-#pragma unroll
-            for (int q = 0; q < 16; q++) {
-                const uint32_t o = 256u * q + 4u * (uint32_t)lane;
-                w[q] = 0u;
-#pragma unroll
-                for (int i = 0; i < 4; i++)
-                    if (o + i < clen) w[q] |= (uint32_t)src[o + i] << (8 * i);
-                __builtin_amdgcn_sched_barrier(0);  // one register's loads at a time: this path is rare
-            }
-        }
-    };
     // Which groups a workgroup packs.  A group's position in the payload comes from the groups before it, so
-    // whoever waits for one must know that its owner is running.  With no more groups than workgroups each
-    // workgroup takes the group of its own index: the workgroups before it were dispatched before it.  With more,
-    // a fixed round-robin share would only be safe if the whole grid were resident at once, which another
-    // stream's kernels on the same device can prevent (the waits would then run into their limit and the stream
-    // would be marked invalid).  There every group is claimed from a counter, in ascending order, by a workgroup
-    // that is running and about to pack it: the lowest unfinished group then always has an owner at work on it.
-    // The first claim is made at the start and read after the table is there; the others as soon as the group at
-    // hand has published its size.  Updates of one address take their turns (about 15 ns each here), which is what
-    // this order of work costs over a fixed share when a thousand workgroups finish a group at about the same time.
-    // A caller that knows its calls have the device to themselves can ask for the fixed share (p.exclusive).
-    const bool ticketed = p.n_groups > gridDim.x && !p.exclusive;
-    constexpr int kClaimThread = 64 * (kPackWaves - 1);
-    if (ticketed && tid == kClaimThread) S.claim = atomicAdd(&p.ctrl->ticket, 1u);
+    // whoever waits for one must know that its owner gets to run.  This kernel is only launched with no more
+    // groups than the device holds workgroups of it, and workgroup g takes group g: within a part of the chip
+    // workgroups start in index order, so the lowest unfinished group is either running or next in line for a
+    // place that only other kernels' workgroups (which finish) or this kernel's finished ones can hold.  Larger
+    // tensors take the kernels below (k_chunk_bits, k_chunk_scan, k_pack_at), which never wait for each other.
     uint32_t w[16];
-    uint32_t group = blockIdx.x;  // the grid never has more workgroups than groups
-    if (!ticketed) load_chunk(group * kPackWaves + (uint32_t)wave, w);  // in flight while the table is made
+    const uint32_t group = blockIdx.x;  // the grid never has more workgroups than groups
+    load_chunk_symbols(p, group * kPackWaves + (uint32_t)wave, lane, aligned4, w);  // in flight while the table is made
 
     TableLds& L = *reinterpret_cast<TableLds*>(&S.stage[0][0]);  // shares LDS with the chunk images, not in use yet
     static_assert(sizeof(TableLds) <= sizeof(S.stage), "table scratch must fit the chunk images");
@@ -522,31 +476,196 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         __syncthreads();
         if (MODE == kPackStatic && blockIdx.x == 0) p.stream[kHeaderBytes + tid] = (uint8_t)(S.tab[tid] >> 56);
     }
-    if (ticketed) {  // (the claim was stored before the barriers above)
-        group = S.claim;
-        if (group >= p.n_groups) return;  // every group already has an owner
-        load_chunk(group * kPackWaves + (uint32_t)wave, w);
-    }
     // nobody reads the table scratch any more: the images start out clear
     pack_clear_image(S, wave, lane);
+    pack_group<MODE>(S, p, group, w, chunk_len_of(p, group * kPackWaves + (uint32_t)wave), []() {});
+}
 
-    for (;;) {
-        const uint32_t ch = group * kPackWaves + (uint32_t)wave;
-        // the next group's symbols are on their way during the wait for the position and the stores
+// ---------------------------------------------------------------------------
+// Large tensors (more chunk groups than the device holds pack workgroups): three kernels that
+// never wait for one another inside a launch, so nothing depends on which workgroups are
+// resident.  k_chunk_bits sums the code lengths of every chunk; k_chunk_scan (one workgroup)
+// turns them into the container's chunk offsets and writes the header; k_pack_at packs every
+// chunk at its known place.  The symbols are read twice (they were just written and mostly come
+// from the memory-side cache); the table is read from memory (k_huffman_table or a fixed one).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_chunk_bits(PackParams p) {
+    __shared__ uint8_t s_len[256];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool aligned4 = (p.chunk_syms & 3u) == 0;
+    uint32_t ch = blockIdx.x * kPackWaves + (uint32_t)wave;
+    uint32_t w[16];
+    if (ch < p.n_chunks) load_chunk_symbols(p, ch, lane, aligned4, w);  // in flight while the lengths arrive
+    s_len[tid] = (uint8_t)(p.enc_table[tid] >> 56);
+    __syncthreads();
+    while (ch < p.n_chunks) {  // wavefront-uniform
+        const uint32_t clen = chunk_len_of(p, ch);
+        const uint32_t next = ch + gridDim.x * kPackWaves;
         uint32_t wn[16];
-        uint32_t next_group = p.n_groups;
-        pack_group<MODE>(S, p, group, w, chunk_len(ch), [&]() {
-            if (ticketed) {  // this group's size is published: claiming the next one cannot block anybody
-                if (tid == kClaimThread) S.claim = atomicAdd(&p.ctrl->ticket, 1u);
-                __syncthreads();
-                next_group = S.claim;
+        if (next < p.n_chunks) load_chunk_symbols(p, next, lane, aligned4, wn);
+        uint32_t bits = 0;
+        if (clen == 4096u) {
+#pragma unroll
+            for (int q = 0; q < 16; q++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) bits += s_len[(w[q] >> (8 * i)) & 255u];
+        } else {
+#pragma unroll
+            for (int q = 0; q < 16; q++)
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    if (256u * q + 4u * (uint32_t)lane + i < clen) bits += s_len[(w[q] >> (8 * i)) & 255u];
+        }
+        bits = wave_sum(bits);
+        if (lane == 0) p.chunk_bits[ch] = bits;
+        ch = next;
+#pragma unroll
+        for (int q = 0; q < 16; q++) w[q] = wn[q];
+    }
+}
+
+// One workgroup: chunk_off[i] = words of the chunks before chunk i (a chunk starts on a word), the header, the
+// stream size and the zero bytes of the alignment gaps.  The stream is marked invalid if it would outgrow the buffer.
+// Rounds of kScanTile chunks: coalesced loads (all of a thread's in flight together) into LDS, every thread scans
+// kScanPer neighbouring entries there, a scan over the threads' sums, coalesced stores.
+constexpr int kScanThreads = 1024, kScanPer = 8, kScanTile = kScanThreads * kScanPer;
+__global__ __launch_bounds__(kScanThreads) void k_chunk_scan(PackParams p) {
+    __shared__ uint32_t s_w[kScanTile + kScanTile / 32];  // one pad word per 32: a thread's entries start in different banks
+    __shared__ unsigned long long s_wave[kScanThreads / 64];
+    __shared__ unsigned long long s_bits[kScanThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t n = p.n_chunks;
+    uint32_t* chunk_off = reinterpret_cast<uint32_t*>(p.stream + kHeaderBytes + kLenTableBytes);
+    auto slot = [](uint32_t i) { return i + (i >> 5); };
+    unsigned long long carry = 0, bits = 0;
+    for (uint32_t base = 0; base < n; base += kScanTile) {
+        uint32_t v[kScanPer];
+#pragma unroll
+        for (int k = 0; k < kScanPer; k++) {
+            const uint32_t i = base + (uint32_t)tid + (uint32_t)kScanThreads * k;
+            v[k] = i < n ? p.chunk_bits[i] : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < kScanPer; k++) {
+            bits += v[k];
+            s_w[slot((uint32_t)tid + (uint32_t)kScanThreads * k)] = (v[k] + 31u) >> 5;
+        }
+        __syncthreads();
+        uint32_t mine[kScanPer], sum = 0;
+#pragma unroll
+        for (int k = 0; k < kScanPer; k++) {
+            mine[k] = s_w[slot((uint32_t)tid * kScanPer + k)];
+            sum += mine[k];
+        }
+        const unsigned long long incl = wave_inclusive_scan64(sum, lane);
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        unsigned long long before = carry + incl - sum, total = 0;
+        for (int q = 0; q < kScanThreads / 64; q++) {
+            if (q < wave) before += s_wave[q];
+            total += s_wave[q];
+        }
+#pragma unroll
+        for (int k = 0; k < kScanPer; k++) {
+            s_w[slot((uint32_t)tid * kScanPer + k)] = (uint32_t)before;
+            before += mine[k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kScanPer; k++) {
+            const uint32_t i = base + (uint32_t)tid + (uint32_t)kScanThreads * k;
+            if (i < n) chunk_off[i] = s_w[slot((uint32_t)tid + (uint32_t)kScanThreads * k)];
+        }
+        carry += total;
+        __syncthreads();  // s_w and s_wave are rewritten by the next round
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) bits += __shfl_xor(bits, o, 64);
+    if (lane == 0) s_bits[wave] = bits;
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned long long total_words = carry;
+        unsigned long long total_bits = 0;
+        for (int q = 0; q < kScanThreads / 64; q++) total_bits += s_bits[q];
+        chunk_off[n] = (uint32_t)total_words;
+        Header hdr = p.hdr;
+        hdr.payload_words = total_words;
+        hdr.payload_bits = total_bits;
+        if (total_words > p.cap_words || total_words > 0xffffffffull) hdr.magic = 0u;  // does not fit: not valid
+        *reinterpret_cast<Header*>(p.stream) = hdr;
+        if (p.out_bytes) *p.out_bytes = (uint64_t)p.off_payload + 4 * total_words;
+        // alignment gaps between the sections are part of the stream: keep them zero
+        for (size_t o = kHeaderBytes + kLenTableBytes + 4 * ((size_t)n + 1); o < p.off_sub_bits; o++) p.stream[o] = 0;
+        for (size_t o = p.off_sub_bits + 2 * (size_t)n * p.subs_per_chunk; o < p.off_payload; o++) p.stream[o] = 0;
+    }
+}
+
+// Packs every chunk at the place k_chunk_scan gave it.  One wavefront per chunk and turn, no barriers after the
+// table is in LDS, the next chunk's symbols in flight while this one is packed.  STATIC: the table is a fixed one
+// (its longest code comes with the parameters, and the block that holds chunk 0 writes the container's length
+// table); otherwise k_huffman_table has left both.
+template <bool STATIC>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_pack_at(PackParams p) {
+    __shared__ PackShared S;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool aligned4 = (p.chunk_syms & 3u) == 0;
+    uint32_t ch = blockIdx.x * kPackWaves + (uint32_t)wave;
+    uint32_t w[16];
+    if (ch < p.n_chunks) load_chunk_symbols(p, ch, lane, aligned4, w);
+    S.tab[tid] = p.enc_table[tid];
+    if (STATIC && blockIdx.x == 0) p.stream[kHeaderBytes + tid] = (uint8_t)(p.enc_table[tid] >> 56);
+    pack_clear_image(S, wave, lane);
+    __syncthreads();
+    const uint32_t max_len = STATIC ? p.static_max_len : p.ctrl->max_len;
+    uint32_t* img = S.stage[wave];
+    uint16_t* sub_bits = reinterpret_cast<uint16_t*>(p.stream + p.off_sub_bits);
+    const uint32_t* chunk_off = reinterpret_cast<const uint32_t*>(p.stream + kHeaderBytes + kLenTableBytes);
+    uint32_t* payload = reinterpret_cast<uint32_t*>(p.stream + p.off_payload);
+    const uint32_t n_runs = p.subs_per_chunk;
+    auto sync_wave = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    while (ch < p.n_chunks) {  // wavefront-uniform
+        const uint32_t clen = chunk_len_of(p, ch);
+        const uint32_t next = ch + gridDim.x * kPackWaves;
+        uint32_t wn[16];
+        if (next < p.n_chunks) load_chunk_symbols(p, next, lane, aligned4, wn);
+        const uint32_t word0 = chunk_off[ch], word1 = chunk_off[ch + 1];
+        auto build_window = [&](uint32_t win, uint32_t win_words, uint16_t* run_bits) -> uint32_t {
+            uint32_t total;
+            if (win == 0) {
+                if (max_len <= 32) total = pack_chunk<false, true>(w, clen, S.tab, img, win, win_words, lane, run_bits, n_runs);
+                else total = pack_chunk<true, true>(w, clen, S.tab, img, win, win_words, lane, run_bits, n_runs);
             } else {
-                next_group = group + gridDim.x;  // fixed share (beyond the last group where each has one)
+                if (max_len <= 32) total = pack_chunk<false, false>(w, clen, S.tab, img, win, win_words, lane, run_bits, n_runs);
+                else total = pack_chunk<true, false>(w, clen, S.tab, img, win, win_words, lane, run_bits, n_runs);
             }
-            if (next_group < p.n_groups) load_chunk(next_group * kPackWaves + (uint32_t)wave, wn);
-        });
-        if (next_group >= p.n_groups) break;  // (always so where every workgroup has one group)
-        group = next_group;
+            sync_wave();  // the ORs of all lanes precede the reads that follow
+            return total;
+        };
+        uint16_t* runs_out = sub_bits + (size_t)ch * n_runs;
+        const bool staged = n_runs <= 64u;
+        const uint32_t total_bits = build_window(0, kStageWords, staged ? S.runs[wave] : runs_out);
+        if (staged && (uint32_t)lane < n_runs) runs_out[lane] = S.runs[wave][lane];
+        const uint32_t n_words = (total_bits + 31) >> 5;
+        // what the size pass counted must be what this pass produces (the same symbols and table); should the
+        // symbols have changed in between, or the payload not fit, nothing is written past the chunk's place and
+        // the stream is left invalid
+        const bool fits = word1 - word0 == n_words && (uint64_t)word0 + n_words <= p.cap_words;
+        if (!fits && lane == 0) *reinterpret_cast<uint32_t*>(p.stream) = 0u;  // the header's magic
+        for (uint32_t win = 0; win < n_words; win += kStageWords) {
+            const uint32_t win_words = (n_words - win < (uint32_t)kStageWords) ? n_words - win : (uint32_t)kStageWords;
+            if (win) build_window(win, win_words, nullptr);
+            for (uint32_t i = lane; i < win_words; i += 64) {
+                if (fits) payload[(size_t)word0 + win + i] = img[i];
+                img[i] = 0u;
+            }
+            sync_wave();  // the image is read and clear before the next window or chunk writes it
+        }
+        ch = next;
 #pragma unroll
         for (int q = 0; q < 16; q++) w[q] = wn[q];
     }
@@ -568,16 +687,6 @@ static int pack_resident_groups() {
     return cached;
 }
 
-// FMTC_EXCLUSIVE_DEVICE=1 in the environment (read once): the caller's encoder calls never overlap with other
-// kernels on the device, so a tensor with more chunk groups than workgroups may be shared out in fixed turns.
-static bool exclusive_device() {
-    static const bool on = [] {
-        const char* e = getenv("FMTC_EXCLUSIVE_DEVICE");
-        return e && e[0] == '1';
-    }();
-    return on;
-}
-
 // Table (a kernel of its own only where every pack workgroup building it would cost more than the launch)
 // and packing.
 PackParams pack_params(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
@@ -591,7 +700,7 @@ PackParams pack_params(const uint8_t* d_syms, const Geometry& g, int bits, float
     p.chunk_syms = g.chunk_syms;
     p.subs_per_chunk = g.subs_per_chunk;
     p.n_groups = cs.n_groups;
-    p.exclusive = exclusive_device() ? 1u : 0u;
+    p.chunk_bits = cs.chunk_bits;
     p.bits = bits;
     p.hist_parts = cs.hist_parts;
     p.n_parts = n_parts;
@@ -617,21 +726,38 @@ PackParams pack_params(const uint8_t* d_syms, const Geometry& g, int bits, float
     return p;
 }
 
+// Sizes, offsets and packing of a tensor with more chunk groups than the device holds pack workgroups.
+template <bool STATIC>
+static hipError_t launch_pack_large(const PackParams& p, hipStream_t s) {
+    if (!p.chunk_bits) return hipErrorInvalidValue;
+    const uint32_t n_groups = pack_groups(p.n_chunks);
+    const uint32_t cap = (uint32_t)pack_resident_groups<kPackTable>();
+    const uint32_t grid = n_groups < 2 * cap ? n_groups : 2 * cap;
+    hipError_t e = launch(K_CHUNK_BITS, k_chunk_bits, dim3(grid), dim3(256), 0, s, p);
+    if (e != hipSuccess) return e;
+    e = launch(K_CHUNK_SCAN, k_chunk_scan, dim3(1), dim3(kScanThreads), 0, s, p);
+    if (e != hipSuccess) return e;
+    return launch(K_PACK, k_pack_at<STATIC>, dim3(n_groups < cap ? n_groups : cap), dim3(256), 0, s, p);
+}
+
 hipError_t launch_coder(const uint8_t* d_syms, const Geometry& g, int bits, float delta, const CoderScratch& cs,
                         int n_parts, uint64_t* d_enc_table, uint8_t* d_stream, uint64_t cap_words,
                         uint64_t* d_out_bytes, hipStream_t s) {
     PackParams p = pack_params(d_syms, g, bits, delta, cs, n_parts, d_enc_table, d_stream, cap_words, d_out_bytes);
+    const uint32_t resident = (uint32_t)pack_resident_groups<kPackTable>();
+    const bool large = cs.n_groups > resident;
     // every pack workgroup sums the partial histograms itself while that is at most 64 KB to read
-    const bool build_in_pack = ((size_t)n_parts << bits) * 4 <= 64 * 1024;
+    const bool build_in_pack = !large && ((size_t)n_parts << bits) * 4 <= 64 * 1024;
     if (!build_in_pack) {
         hipError_t e = launch(K_TABLE, k_huffman_table, dim3(1), dim3(1024), 0, s, (const uint32_t*)cs.hist_parts,
                               n_parts, bits, (uint32_t*)nullptr, d_enc_table, d_stream + kHeaderBytes, cs.ctrl, 0u);
         if (e != hipSuccess) return e;
-        const uint32_t cap = (uint32_t)pack_resident_groups<kPackTable>();
-        return launch(K_PACK, k_pack<kPackTable>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
+        if (large) return launch_pack_large<false>(p, s);
+        return launch(K_PACK, k_pack<kPackTable>, dim3(cs.n_groups), dim3(256), 0, s, p);
     }
     const uint32_t cap = (uint32_t)pack_resident_groups<kPackBuild>();
-    return launch(K_PACK, k_pack<kPackBuild>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
+    if (cs.n_groups > cap) return hipErrorInvalidValue;  // (not reachable: the two variants hold the same number)
+    return launch(K_PACK, k_pack<kPackBuild>, dim3(cs.n_groups), dim3(256), 0, s, p);
 }
 
 // Packing with a table fixed beforehand (one code for every symbol of the alphabet): no histogram, no table build.
@@ -642,7 +768,8 @@ hipError_t launch_coder_static(const uint8_t* d_syms, const Geometry& g, int bit
     PackParams p = pack_params(d_syms, g, bits, delta, cs, 0, d_enc_table, d_stream, cap_words, d_out_bytes);
     p.static_max_len = max_len;
     const uint32_t cap = (uint32_t)pack_resident_groups<kPackStatic>();
-    return launch(K_PACK, k_pack<kPackStatic>, dim3(cs.n_groups < cap ? cs.n_groups : cap), dim3(256), 0, s, p);
+    if (cs.n_groups > cap) return launch_pack_large<true>(p, s);
+    return launch(K_PACK, k_pack<kPackStatic>, dim3(cs.n_groups), dim3(256), 0, s, p);
 }
 
 }  // namespace fmtc

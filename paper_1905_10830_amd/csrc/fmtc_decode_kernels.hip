@@ -325,7 +325,9 @@ __device__ __forceinline__ bool decode_run_bytes(const uint32_t* pw, uint32_t nw
                 const uint32_t v = __brev(w);  // first stream bit on top
                 const uint32_t top = T.max_len < 33u ? T.max_len : 33u;
                 uint32_t len = kLutBits + 1;
-                for (uint32_t l = kLutBits + 1; l < top; l++) len += (v >= T.limit32[l]) ? 1u : 0u;
+                // (fixed trip count: the reads of all limits are in flight together instead of one after the other)
+#pragma unroll
+                for (uint32_t l = kLutBits + 1; l < 33u; l++) len += (l < top && v >= T.limit32[l]) ? 1u : 0u;
                 uint32_t sym = 0;
                 uint32_t bp = (uint32_t)(pp - 3 - pw) * 32u + sh;
                 if (len <= 32) {
@@ -834,26 +836,42 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     uint8_t* tile = symtile[wave];
     uint32_t* pw = pay[wave];
 
-    for (uint32_t ch = ch_first; ch < n_chunks; ch += gridDim.x * WAVES) {
+    // Side information and payload of a chunk are requested one chunk ahead: offsets and run sizes of the next chunk
+    // at the top of a turn (they arrive during this chunk's variable length decoding), its payload words right after
+    // that decoding (they arrive during the inverse transform) -- a chunk would otherwise start with two dependent
+    // memory round trips.  cur_*: what is at hand for the chunk of this turn; pay_*: the words held in registers and
+    // the offsets they were fetched for.
+    uint32_t cur_w0 = pre_w0, cur_w1 = pre_w1, cur_run = pre_run;
+    bool pay_ok = guess_valid && pay_pre;
+    uint32_t pay_w0 = guess_w0, pay_w1 = guess_w1;
+    const uint32_t ch_step = gridDim.x * WAVES;
+    for (uint32_t ch = ch_first; ch < n_chunks; ch += ch_step) {
         // ---- variable length decoding of the chunk into the wavefront's tile ----
         const uint64_t c0 = (uint64_t)ch * chunk_syms;
         const uint32_t clen = (uint32_t)((V - c0 < chunk_syms) ? (V - c0) : chunk_syms);
-        const bool first = ch == ch_first;
-        uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(first ? pre_w0 : sv.chunk_off[ch]));
-        uint32_t w1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(first ? pre_w1 : sv.chunk_off[ch + 1]));
+        uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cur_w0);
+        uint32_t w1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cur_w1);
         if (w0 > w1 || w1 > payload_words) {
             if (lane == 0) atomicOr(p.err, FMTC_ERR_OFFSETS);
             w0 = 0; w1 = 0;
         }
-        const uint32_t run_bits = first ? pre_run : (((uint32_t)lane < spc) ? sv.sub_bits[(size_t)ch * spc + lane] : 0u);
+        const uint32_t run_bits = cur_run;
+        const uint32_t nch = ch + ch_step;
+        const bool have_next = nch < n_chunks && nch > ch;  // wavefront-uniform
+        if (have_next) {
+            cur_w0 = sv.chunk_off[nch];
+            cur_w1 = sv.chunk_off[nch + 1];
+            cur_run = ((uint32_t)lane < spc) ? sv.sub_bits[(size_t)nch * spc + lane] : 0u;
+        }
         const uint32_t start = wave_exclusive_scan(run_bits, lane);
         const uint32_t r0 = (uint32_t)lane * kSubSyms;
         const uint32_t cnt = (r0 < clen) ? ((clen - r0 < (uint32_t)kSubSyms) ? clen - r0 : (uint32_t)kSubSyms) : 0u;
         const uint32_t nwords = w1 - w0;
         bool ok_run = true;
-        if (nwords <= (uint32_t)kPayWords) {
-            if (first && guess_valid && pay_pre && w0 == guess_w0 && w1 == guess_w1) {
-                // the words requested at the start of the kernel (zero past the chunk's end)
+        const bool staged = nwords <= (uint32_t)kPayWords;
+        if (staged) {
+            if (pay_ok && w0 == pay_w0 && w1 == pay_w1) {
+                // the words requested ahead (zero past the chunk's end)
 #pragma unroll
                 for (int k = 0; k < kPrePay; k++)
                     if ((uint32_t)lane + 64u * k < nwords + 2) pw[lane + 64 * k] = pre_pay[k];
@@ -866,6 +884,21 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             if (cnt) ok_run = decode_run_bytes(pw, nwords, start, cnt, T, tile + 68u * (uint32_t)lane);
         } else if (cnt) {
             ok_run = decode_run<false>(nullptr, sv.payload + w0, nwords, start, cnt, T, ByteOut(tile, r0));
+        }
+        // the next chunk's payload words: in flight during this chunk's inverse transform
+        pay_ok = false;
+        if (have_next) {
+            pay_w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cur_w0);
+            pay_w1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cur_w1);
+            pay_ok = pay_w0 <= pay_w1 && pay_w1 <= payload_words && pay_w1 - pay_w0 <= (uint32_t)kPayWords;
+            if (pay_ok) {
+                const uint32_t* pay_src = sv.payload + pay_w0;
+#pragma unroll
+                for (int k = 0; k < kPrePay; k++) {
+                    const uint32_t i = (uint32_t)lane + 64u * k;
+                    pre_pay[k] = (i < pay_w1 - pay_w0) ? pay_src[i] : 0u;
+                }
+            }
         }
         if (!ok_run) atomicOr(p.err, FMTC_ERR_CODE);
         // the symbols of all lanes are in place before any lane reads them: one wavefront, LDS in order

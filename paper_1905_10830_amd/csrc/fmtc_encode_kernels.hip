@@ -465,21 +465,31 @@ struct RowParams {
 // C = 32 NCT in {32, 64, 128} and chunks of 4096 symbols, i.e. 4 / NCT whole pixel tiles; the grid must not exceed
 // what the device holds at once (a chunk's position in the payload comes from the workgroups before it), and the
 // look-back words and the control block must be clear when the kernel starts.
-template <int NCT, int LAYOUT, bool VEC, bool FUSED = false>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_project_quantize_rows(RowParams p) {
+// WAVES wavefronts per workgroup (4, or 8 sharing one copy of a large basis); the register budget is set so that
+// rows_waves_per_simd() wavefronts fit a SIMD: a wavefront spends most of a tile's time waiting for its pixels,
+// and the second (third, fourth) one's arithmetic fills that time.
+constexpr int rows_waves_per_simd(int nct, bool fused, int waves) {
+    return fused ? 1 : (waves == 8 ? 2 : (nct == 1 ? 4 : (nct <= 3 ? 2 : 1)));
+}
+template <int NCT, int LAYOUT, bool VEC, bool FUSED = false, int WAVES = 4>
+__global__ __launch_bounds__(WAVES * 64)
+__attribute__((amdgpu_waves_per_eu(rows_waves_per_simd(NCT, FUSED, WAVES), rows_waves_per_simd(NCT, FUSED, WAVES))))
+void k_project_quantize_rows(RowParams p) {
+    constexpr int THREADS = WAVES * 64;
+    static_assert(WAVES == 4 || (WAVES == 8 && !FUSED && (NCT * NCT * 256) % THREADS == 0), "workgroup shape");
     constexpr int NJ = NCT * 2;  // steps of 16 channels
     extern __shared__ __align__(16) uint4 basis16[];  // [NCT][NJ][2][64], then the histograms
     __shared__ __align__(16) float s_mu[NCT * 32];
-    __shared__ uint32_t s_fix_list[4][kFixList];
-    __shared__ uint32_t s_fix_tile[4][kFixList];
-    __shared__ uint32_t s_fix_count[4];
-    __shared__ uint32_t s_red[4 * 256];  // per (wavefront, bin) sums of the histogram copies
+    __shared__ uint32_t s_fix_list[WAVES][kFixList];
+    __shared__ uint32_t s_fix_tile[WAVES][kFixList];
+    __shared__ uint32_t s_fix_count[WAVES];
+    __shared__ uint32_t s_red[WAVES * 256];  // per (wavefront, bin) sums of the histogram copies
     // Histogram: kHistLanes interleaved copies per wavefront (bin s of copy q at word s * kHistLanes + q), lane l
     // counts in copy l % kHistLanes.  Most symbols of a tile are the same few values: with one copy the LDS
     // would serialise up to 64 additions to one word per instruction, and the reads of the basis queue up
     // behind them.
     const int K = 1 << p.bits;
-    uint32_t* whist = reinterpret_cast<uint32_t*>(basis16 + NCT * NJ * 2 * 64);  // [4][K * kHistLanes]
+    uint32_t* whist = reinterpret_cast<uint32_t*>(basis16 + NCT * NJ * 2 * 64);  // [WAVES][K * kHistLanes]
     // FUSED: in place of the histograms, the four wavefronts' chunks of symbols (4096 bytes each, stream order)
     // and the packer's tables and images
     constexpr int TPC = FUSED ? 4 / NCT : 1;  // pixel tiles per chunk
@@ -526,7 +536,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     };
     // the first tile's pixels come from HBM: their loads go out before anything else
-    int64_t tile = ((int64_t)blockIdx.x * 4 + wave) * TPC;
+    int64_t tile = ((int64_t)blockIdx.x * WAVES + wave) * TPC;
     if (tile < p.n_tiles) load_pixels(tile);
     if constexpr (!FUSED) zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
 
@@ -534,12 +544,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     {
         const uint4* src = reinterpret_cast<const uint4*>(p.basis16);
 #pragma unroll
-        for (int i = 0; i < NCT * NCT; i++)
-            __builtin_amdgcn_global_load_lds(src + tid + 256 * i, &basis16[256 * i + 64 * wave], 16, 0, 0);
+        for (int i = 0; i < NCT * NCT * 256 / THREADS; i++)
+            __builtin_amdgcn_global_load_lds(src + tid + THREADS * i, &basis16[THREADS * i + 64 * wave], 16, 0, 0);
     }
     if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
     if constexpr (!FUSED) {
-        for (int i = tid; i < 4 * K * kHistLanes; i += 256) whist[i] = 0u;
+        for (int i = tid; i < WAVES * K * kHistLanes; i += THREADS) whist[i] = 0u;
     } else {
         S.tab[tid] = p.pk.enc_table[tid];
         if (tid == 0) {
@@ -847,14 +857,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
         return;
     } else {
-        for (; tile < p.n_tiles; tile += (int64_t)gridDim.x * 4) process_tile(tile, tile + (int64_t)gridDim.x * 4);
+        for (; tile < p.n_tiles; tile += (int64_t)gridDim.x * WAVES) process_tile(tile, tile + (int64_t)gridDim.x * WAVES);
     }
     if (*fix_count) resolve_list();
     __syncthreads();
     // One row of partial counts per workgroup: nothing to clear beforehand, no global atomics.  Every thread sums
     // the 16 copies of some (wavefront, bin) rows with 16-byte reads (a row is contiguous; reading one copy of
-    // many bins instead would put all lanes on two banks), then the first K threads add the four wavefronts.
-    for (int row = tid; row < 4 * K; row += 256) {
+    // many bins instead would put all lanes on two banks), then the first K threads add the wavefronts.
+    for (int row = tid; row < WAVES * K; row += THREADS) {
         const uint4* r4 = reinterpret_cast<const uint4*>(whist + (size_t)row * kHistLanes);
         uint32_t total = 0;
 #pragma unroll
@@ -865,8 +875,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         s_red[row] = total;
     }
     __syncthreads();
-    if (tid < K)
-        p.hist_parts[(size_t)blockIdx.x * K + tid] = (s_red[tid] + s_red[K + tid]) + (s_red[2 * K + tid] + s_red[3 * K + tid]);
+    if (tid < K) {
+        uint32_t total = 0;
+#pragma unroll
+        for (int q = 0; q < WAVES; q++) total += s_red[q * K + tid];
+        p.hist_parts[(size_t)blockIdx.x * K + tid] = total;
+    }
 }
 
 static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
@@ -899,27 +913,40 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     if (!p.x || !p.basis16 || !p.mu || !p.Trow || !p.syms || !p.hist_parts || !p.ctrl || !p.lookback)
         return hipErrorInvalidValue;  // (a field left out would be a wild pointer on the device)
     const int nct = b.Cpad / 32;
-    const size_t lds = sizeof(float) * (size_t)b.Cpad * b.Cpad + sizeof(uint32_t) * 4 * kHistLanes * ((size_t)1 << bits);
-    int64_t gx = (p.n_tiles + 3) / 4;
-    const int64_t cap = (lds + 2 * 1024 <= 80 * 1024) ? 512 : 256;  // one or two workgroups per compute unit
+    // eight wavefronts on one copy of the basis where two four-wavefront workgroups (each with its own copy) do not
+    // fit a compute unit's LDS and there are tiles enough for them
+    // (measured at 128 channels, 25.7 M values: 67 us against 62 us with four wavefronts, one per SIMD -- the second
+    // wavefront's registers do not fit without spills -- so the eight-wavefront form stays off)
+    const bool eight = false;
+    const int waves = eight ? 8 : 4;
+    const size_t lds = sizeof(float) * (size_t)b.Cpad * b.Cpad + sizeof(uint32_t) * waves * kHistLanes * ((size_t)1 << bits);
+    // workgroups a compute unit holds at once: by registers (rows_waves_per_simd) and by LDS
+    const size_t lds_static = (size_t)waves * (2 * kFixList + 1 + 256) * 4 + (size_t)nct * 128 + 512;
+    int per_cu = eight ? 1 : rows_waves_per_simd(nct, false, 4);
+    const int by_lds = (int)((160 * 1024) / (lds + lds_static));
+    if (per_cu > by_lds) per_cu = by_lds < 1 ? 1 : by_lds;
+    int64_t gx = (p.n_tiles + waves - 1) / waves;
+    const int64_t cap = 256 * (int64_t)per_cu;
     if (gx > cap) gx = cap;
     *n_parts = (int)gx;
     const bool vec = (b.C % 4) == 0;
     hipError_t el = hipSuccess;
-#define FMTC_ROWS(NCT, LAY, VEC)                                                                                 \
+#define FMTC_ROWS_W(NCT, LAY, VEC, WV)                                                                           \
     do {                                                                                                         \
         if (lds > 32 * 1024) {                                                                                   \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project_quantize_rows<NCT, LAY, VEC>), \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project_quantize_rows<NCT, LAY, VEC, false, WV>), \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
             if (ea != hipSuccess) return ea;                                                                     \
         }                                                                                                        \
-        el = launch(K_PROJECT, k_project_quantize_rows<NCT, LAY, VEC>, dim3((unsigned)gx), dim3(256), lds, s, p); \
+        el = launch(K_PROJECT, k_project_quantize_rows<NCT, LAY, VEC, false, WV>, dim3((unsigned)gx), dim3(WV * 64), lds, s, p); \
     } while (0)
+#define FMTC_ROWS(NCT, LAY, VEC) FMTC_ROWS_W(NCT, LAY, VEC, 4)
 #define FMTC_ROWS_N(LAY, VEC)                                                                                    \
     do {                                                                                                         \
         if (nct == 1) FMTC_ROWS(1, LAY, VEC);                                                                    \
         else if (nct == 2) FMTC_ROWS(2, LAY, VEC);                                                               \
         else if (nct == 3) FMTC_ROWS(3, LAY, VEC);                                                               \
+        else if (eight) FMTC_ROWS_W(4, LAY, VEC, 8);                                                             \
         else FMTC_ROWS(4, LAY, VEC);                                                                             \
     } while (0)
     if (nct == 5) {  // channels-last only (see launch_project_quantize)
@@ -928,6 +955,7 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     else                            { if (vec) FMTC_ROWS_N(FMTC_NCHW, true); else FMTC_ROWS_N(FMTC_NCHW, false); }
 #undef FMTC_ROWS_N
 #undef FMTC_ROWS
+#undef FMTC_ROWS_W
     return el;
 }
 

@@ -66,7 +66,7 @@ inline bool make_geometry(int64_t P, int C, int chunk_syms, Geometry* g) {
 
 // Control words of one encoder call (in the workspace).  Zeroed by the first kernel of the call.
 struct alignas(64) CoderCtrl {
-    uint32_t ticket;                  // next chunk group handed out by the pack kernel
+    uint32_t reserved0;
     uint32_t max_len;                 // longest code length (table kernel)
     unsigned long long payload_bits;  // sum of count * length (table kernel)
     uint32_t error;                   // set if a bounded wait of the pack kernel ran out
@@ -83,6 +83,7 @@ struct Workspace {
     size_t off_hist;         // u32 [256] final histogram
     size_t off_enc_table;    // u64 [256]: bit-reversed code | length << 56
     size_t off_lookback;     // u64 [n_groups]: running payload word count per chunk group (flag << 32 | words)
+    size_t off_chunk_bits;   // u32 [n_chunks]: code bits per chunk (tensors packed at precomputed offsets)
     size_t off_syms;         // u8 [V]
     size_t total;
 };
@@ -102,6 +103,8 @@ inline Workspace make_workspace(uint64_t V, uint32_t n_chunks) {
     o += sizeof(uint64_t) * 256;
     w.off_lookback = o;
     o = align_up(o + sizeof(uint64_t) * (size_t)pack_groups(n_chunks), 256);
+    w.off_chunk_bits = o;
+    o = align_up(o + sizeof(uint32_t) * (size_t)n_chunks, 256);
     w.off_syms = o;
     o = align_up(o + (size_t)V, 256);
     w.total = o;
@@ -124,7 +127,7 @@ struct BasisDevice {
 // ---- optional per-kernel timing (fmtc_profile_* in fmtc.h) ----
 // When enabled, a launch carries a pair of events that the runtime attaches to the kernel's own dispatch, so
 // the elapsed time is the kernel's start-to-end time on the GPU (no bracket of separate marker commands).
-enum KernelId { K_PROJECT = 0, K_HISTOGRAM, K_TABLE, K_PACK, K_DECODE, K_COPY, K_QUANTIZE_U8, K_RECONSTRUCT_U8, K_COUNT };
+enum KernelId { K_PROJECT = 0, K_HISTOGRAM, K_TABLE, K_PACK, K_DECODE, K_COPY, K_QUANTIZE_U8, K_RECONSTRUCT_U8, K_CHUNK_BITS, K_CHUNK_SCAN, K_COUNT };
 bool prof_next(int id, hipEvent_t* start, hipEvent_t* stop);
 
 template <class T>
@@ -146,6 +149,7 @@ struct CoderScratch {
     CoderCtrl* ctrl;
     unsigned long long* lookback;
     uint32_t n_groups;
+    uint32_t* chunk_bits;  // [n_chunks]
 };
 
 // Device side of the 8-bit basis (fmtc_int8_kernels.hip).  nct = ceil(C / 32) tiles of 32 rows, NS = ceil(C / 16)

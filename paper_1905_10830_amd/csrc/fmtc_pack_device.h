@@ -44,7 +44,7 @@ struct PackParams {
     int n_parts;
     const uint64_t* enc_table;   // otherwise: the table (k_huffman_table's, or a static one)
     uint32_t static_max_len;     // kPackStatic: longest code of the table
-    uint32_t exclusive;          // the call has the device to itself: groups may be shared out in fixed turns
+    uint32_t* chunk_bits;        // large tensors: code bits of every chunk (k_chunk_bits -> k_chunk_scan)
     CoderCtrl* ctrl;
     unsigned long long* lookback;
     Header hdr;
@@ -179,6 +179,47 @@ __device__ __forceinline__ uint32_t pack_chunk(const uint32_t (&w)[16], uint32_t
     return base;
 }
 
+// Symbols of chunk `ch` (0 past the last chunk).
+__device__ __forceinline__ uint32_t chunk_len_of(const PackParams& p, uint32_t ch) {
+    if (ch >= p.n_chunks) return 0u;
+    const uint64_t c0 = (uint64_t)ch * p.chunk_syms;
+    return (uint32_t)((p.V - c0 < p.chunk_syms) ? (p.V - c0) : p.chunk_syms);
+}
+
+// The symbols of a chunk: register q of lane l holds symbols 256q + 4l .. + 3 (zero past the chunk's end).
+// aligned4: every chunk starts on a 4-byte boundary of the symbols (chunk_syms % 4 == 0).
+__device__ __forceinline__ void load_chunk_symbols(const PackParams& p, uint32_t ch, int lane, bool aligned4,
+                                                   uint32_t (&w)[16]) {
+    const uint32_t clen = chunk_len_of(p, ch);
+    const uint8_t* src = p.syms + (uint64_t)ch * p.chunk_syms;
+    if (aligned4) {
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            const uint32_t o = 256u * q + 4u * (uint32_t)lane;
+            w[q] = (o + 4u <= clen) ? *reinterpret_cast<const uint32_t*>(src + o) : 0u;
+        }
+        if (clen & 3u) {  // the last, partial word of the tensor
+            const uint32_t t = clen & ~3u;
+            uint32_t v = 0;
+            if ((uint32_t)lane == ((t >> 2) & 63u))
+                for (uint32_t i = 0; i < (clen & 3u); i++) v |= (uint32_t)src[t + i] << (8 * i);
+#pragma unroll
+            for (int q = 0; q < 16; q++)
+                if ((uint32_t)q == (t >> 8)) w[q] |= v;
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 16; q++) {
+            const uint32_t o = 256u * q + 4u * (uint32_t)lane;
+            w[q] = 0u;
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                if (o + i < clen) w[q] |= (uint32_t)src[o + i] << (8 * i);
+            __builtin_amdgcn_sched_barrier(0);  // one register's loads at a time: this path is rare
+        }
+    }
+}
+
 // What a workgroup that packs keeps in LDS.
 struct PackShared {
     unsigned long long tab[256];                                  // bit-reversed code | length << 56
@@ -186,7 +227,6 @@ struct PackShared {
     uint16_t runs[kPackWaves][64];                                // bit counts of a chunk's runs on their way out
     uint32_t wave_words[kPackWaves], wave_slack[kPackWaves];
     uint32_t excl, excl_slack, max_len;
-    uint32_t claim;                                               // the group claimed from the counter
     unsigned long long payload_bits;
 };
 

@@ -19,7 +19,8 @@ struct Profiler {
 Profiler g_prof;
 const char* const kNames[K_COUNT] = {"k_project_quantize", "k_histogram", "k_huffman_table",
                                      "k_pack",             "k_decode",    "k_copy",
-                                     "k_quantize_u8",      "k_reconstruct_u8"};
+                                     "k_quantize_u8",      "k_reconstruct_u8", "k_chunk_bits",
+                                     "k_chunk_scan"};
 
 void release() {
     for (int k = 0; k < K_COUNT; k++) {
