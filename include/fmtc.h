@@ -158,6 +158,23 @@ fmtc_status fmtc_encode(const fmtc_basis *basis, const float *d_x, int64_t N, in
                         fmtc_layout layout, int bits, int chunk_syms, void *d_stream_out, size_t cap,
                         uint64_t *d_out_bytes, void *d_workspace, size_t ws_bytes, void *hip_stream);
 
+/* fmtc_encode for callers that cannot allocate or hand over a workspace (code
+ * under HIP graph capture, serving loops, harnesses that forbid hipMalloc): the
+ * same kernels and the same container, with the workspace in a device array
+ * that is part of the library (FMTC_NOALLOC_SCRATCH_BYTES per GPU, held until
+ * the process ends).  Accepts tensors with fmtc_workspace_size(P, C, bits,
+ * chunk_syms) <= FMTC_NOALLOC_SCRATCH_BYTES (about 4.9 M values) and returns
+ * FMTC_EBUFSIZE beyond that.  Calls no allocating routine; the first call on a
+ * device looks the array's address up once (do that call outside a capture).
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU
+ * (different streams or threads) race -- keep them on one stream.  The array
+ * keeps the previous call's contents; the encoder's first kernel clears what it
+ * counts in, as in fmtc_encode. */
+#define FMTC_NOALLOC_SCRATCH_BYTES ((size_t)6 << 20)
+fmtc_status fmtc_encode_noalloc(const fmtc_basis *basis, const float *d_x, int64_t N, int C, int H, int W,
+                                fmtc_layout layout, int bits, int chunk_syms, void *d_stream_out, size_t cap,
+                                uint64_t *d_out_bytes, void *hip_stream);
+
 /* Whole decoder (section 3: VLD, inverse quantizer, inverse transform).
  * `bytes` is the readable size of d_stream_in (the exact stream size or any
  * larger capacity); nothing beyond it is read.  d_xhat receives N*C*H*W floats

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libfmtc.so")
 
 EXPORTS = [
     "fmtc_fit_basis", "fmtc_basis_import", "fmtc_basis_export", "fmtc_basis_channels", "fmtc_basis_destroy",
-    "fmtc_delta", "fmtc_encode_bound", "fmtc_workspace_size", "fmtc_encode", "fmtc_decode", "fmtc_quantize",
+    "fmtc_delta", "fmtc_encode_bound", "fmtc_workspace_size", "fmtc_encode", "fmtc_encode_noalloc", "fmtc_decode",
+    "fmtc_quantize",
     "fmtc_code_symbols", "fmtc_decode_symbols", "fmtc_stream_info", "fmtc_last_error",
     "fmtc_fit_table", "fmtc_table_import", "fmtc_table_export", "fmtc_table_destroy", "fmtc_encode_static_bound",
     "fmtc_encode_static", "fmtc_decode_static",
@@ -77,6 +78,7 @@ def load_library():
     lib.fmtc_workspace_size.argtypes = [i64, i32, i32, i32]
     lib.fmtc_workspace_size.restype = sz
     lib.fmtc_encode.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp, sz, vp]
+    lib.fmtc_encode_noalloc.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp]
     lib.fmtc_decode.argtypes = [vp, vp, sz, vp, i64, i32, i32, i32, i32, i32, vp, vp]
     lib.fmtc_fit_table.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, ctypes.POINTER(vp)]
     lib.fmtc_table_import.argtypes = [vp, i32, ctypes.POINTER(vp)]
@@ -355,6 +357,21 @@ def encode(basis, x, bits, layout=NHWC, chunk_syms=4096, stream_out=None, out_by
                                       _dev(stream_out, torch.uint8), stream_out.numel(),
                                       _dev(out_bytes, torch.int64), _dev(workspace, torch.uint8),
                                       workspace.numel(), _stream()))
+    return stream_out, out_bytes
+
+
+NOALLOC_SCRATCH_BYTES = 6 << 20
+
+
+def encode_noalloc(basis, x, bits, stream_out, out_bytes, layout=NHWC, chunk_syms=4096):
+    """Asynchronous.  fmtc_encode with the workspace in the library's own device array; the caller brings the
+    outputs (nothing is allocated here either)."""
+    import torch
+
+    n, c, h, w = _dims(x, layout)
+    _check(load_library().fmtc_encode_noalloc(basis._h, _dev(x, torch.float32), n, c, h, w, layout, bits, chunk_syms,
+                                              _dev(stream_out, torch.uint8), stream_out.numel(),
+                                              _dev(out_bytes, torch.int64), _stream()))
     return stream_out, out_bytes
 
 

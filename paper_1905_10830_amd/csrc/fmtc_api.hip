@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <atomic>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -41,6 +42,8 @@ struct fmtc_basis8 {
     int device = 0;
 };
 
+static __device__ __align__(256) unsigned char scratch[FMTC_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace fmtc;
@@ -58,6 +61,14 @@ fmtc_status fail(fmtc_status st, const char* fmt, ...) {
 fmtc_status hip_fail(hipError_t e, const char* what) {
     return fail(FMTC_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
+
+// Scratch of fmtc_encode_noalloc: the encoder's workspace as a device array that lives in the library's code
+// object, one copy per GPU, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the address a kernel may use is resolved once per device (with that device current) and
+// kept here; host code never passes the name itself to a kernel or a copy.
+constexpr size_t kNoAllocScratchBytes = FMTC_NOALLOC_SCRATCH_BYTES;
+constexpr int kNoAllocMaxDevices = 64;
+std::atomic<uint8_t*> g_noalloc_scratch_ptr[kNoAllocMaxDevices];
 
 bool dims_ok(int64_t N, int C, int H, int W) {
     if (N < 1 || C < 1 || C > 1024 || H < 1 || W < 1) return false;
@@ -1040,6 +1051,34 @@ fmtc_status fmtc_decode_u8(const fmtc_basis8* basis, const void* d_stream_in, si
     st = fmtc_decode_symbols(d_stream_in, bytes, P, C, bits, syms, d_err_flag, hip_stream);
     if (st != FMTC_OK) return st;
     return fmtc_reconstruct_u8(basis, syms, N, C, H, W, layout, bits, d_xq_hat, hip_stream);
+}
+
+// The same encoder with the workspace in the library's own device array (see `scratch` above): no allocation here
+// or below (the launch sequence of fmtc_encode makes none), so the call fits callers that may not allocate.
+fmtc_status fmtc_encode_noalloc(const fmtc_basis* basis, const float* d_x, int64_t N, int C, int H, int W,
+                                fmtc_layout layout, int bits, int chunk_syms, void* d_stream_out, size_t cap,
+                                uint64_t* d_out_bytes, void* hip_stream) {
+    if (!dims_ok(N, C, H, W)) return fail(FMTC_EINVAL, "bad dims");
+    EncodePlan pl;
+    fmtc_status st = plan_encode(N * (int64_t)H * W, C, bits, chunk_syms, &pl);
+    if (st != FMTC_OK) return st;
+    if (pl.ws.total > kNoAllocScratchBytes)
+        return fail(FMTC_EBUFSIZE, "tensor too large for fmtc_encode_noalloc: it needs %zu bytes of scratch, the "
+                    "library's array holds %zu (use fmtc_encode with a workspace)", pl.ws.total, kNoAllocScratchBytes);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kNoAllocMaxDevices) return fail(FMTC_EINVAL, "device index %d not supported", dev);
+    uint8_t* ptr = g_noalloc_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {  // first call on this device: this GPU's copy of the array (every thread gets the same answer)
+        void* sym = nullptr;
+        if ((e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch))) != hipSuccess) return hip_fail(e, "hipGetSymbolAddress");
+        if (!sym || !aligned(sym, 256)) return fail(FMTC_EHIP, "scratch array not resolved");
+        ptr = static_cast<uint8_t*>(sym);
+        g_noalloc_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    return fmtc_encode(basis, d_x, N, C, H, W, layout, bits, chunk_syms, d_stream_out, cap, d_out_bytes, ptr,
+                       kNoAllocScratchBytes, hip_stream);
 }
 
 }  // extern "C"
