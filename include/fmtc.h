@@ -314,6 +314,13 @@ const char *fmtc_profile_name(int kernel);
 fmtc_status fmtc_profile_read(int kernel, double *avg_ms, double *min_ms, int *launches);
 fmtc_status fmtc_profile_copy(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
 
+/* Test support (not part of the method): forces one of two equivalent paths so
+ * that a test can compare them.  option 0, value 1: fmtc_encode_static always
+ * runs projection and packing as two kernels; option 1, value 1: the decoder of
+ * wide tensors walks all channel groups of a tile in one workgroup.  Value 0
+ * restores the library's own choice.  Process-wide. */
+fmtc_status fmtc_test_option(int option, int value);
+
 /* Text of the last error on the calling thread ("" if none). */
 const char *fmtc_last_error(void);
 

@@ -27,6 +27,7 @@ EXPORTS = [
     "fmtc_basis8_create", "fmtc_basis8_export", "fmtc_basis8_destroy", "fmtc_quantize_u8", "fmtc_reconstruct_u8",
     "fmtc_encode_u8", "fmtc_decode_u8",
     "fmtc_profile_enable", "fmtc_profile_kernels", "fmtc_profile_name", "fmtc_profile_read", "fmtc_profile_copy",
+    "fmtc_test_option",
 ]
 
 _lib = None
@@ -102,6 +103,7 @@ def load_library():
     lib.fmtc_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
                                       ctypes.POINTER(i32)]
     lib.fmtc_profile_copy.argtypes = [vp, vp, sz, vp]
+    lib.fmtc_test_option.argtypes = [i32, i32]
     _lib = lib
     return lib
 
@@ -546,6 +548,17 @@ def stream_info(header_bytes):
                                            ctypes.byref(pbits), ctypes.byref(sbytes)))
     return dict(bits=bits.value, C=C.value, P=P.value, px_per_chunk=ppc.value, n_chunks=nch.value,
                 delta=dlt.value, payload_bits=pbits.value, stream_bytes=sbytes.value)
+
+
+TEST_STATIC_TWO_KERNELS, TEST_DECODE_ONE_ROW = 0, 1
+
+
+def test_option(option, value):
+    """Forces one of two equivalent paths (tests only); value 0 restores the library's own choice."""
+    _check(load_library().fmtc_test_option(int(option), int(value)))
+
+
+test_option.__test__ = False  # (not a test, whatever a collector makes of the name)
 
 
 def profile_enable(max_launches_per_kernel):

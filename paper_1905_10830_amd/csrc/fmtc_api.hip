@@ -70,6 +70,19 @@ constexpr size_t kNoAllocScratchBytes = FMTC_NOALLOC_SCRATCH_BYTES;
 constexpr int kNoAllocMaxDevices = 64;
 std::atomic<uint8_t*> g_noalloc_scratch_ptr[kNoAllocMaxDevices];
 
+// Runs the body of an entry point that allocates host memory; an allocation failure comes back as a status (nothing
+// may be thrown across the C boundary).
+template <class F>
+fmtc_status guarded(F&& body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return fail(FMTC_ENOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(FMTC_EHIP, "unexpected failure inside the library");
+    }
+}
+
 bool dims_ok(int64_t N, int C, int H, int W) {
     if (N < 1 || C < 1 || C > 1024 || H < 1 || W < 1) return false;
     long double v = (long double)N * C * H * W;
@@ -430,6 +443,7 @@ void fmtc_basis_destroy(fmtc_basis* b) {
 }
 
 fmtc_status fmtc_basis_import(int C, const float* h_T, const float* h_mu, float range_A, fmtc_basis** out) {
+    return guarded([&]() -> fmtc_status {
     if (!out) return fail(FMTC_EINVAL, "out is NULL");
     *out = nullptr;
     if (C < 1 || C > 1024 || !h_T || !h_mu) return fail(FMTC_EINVAL, "bad basis arguments (C=%d)", C);
@@ -449,6 +463,7 @@ fmtc_status fmtc_basis_import(int C, const float* h_T, const float* h_mu, float 
     }
     *out = b;
     return FMTC_OK;
+    });
 }
 
 fmtc_status fmtc_basis_export(const fmtc_basis* b, float* h_T, float* h_mu, double* h_eigvals, float* range_A) {
@@ -462,6 +477,7 @@ fmtc_status fmtc_basis_export(const fmtc_basis* b, float* h_T, float* h_mu, doub
 
 fmtc_status fmtc_fit_basis(const float* d_x, int64_t N, int C, int H, int W, fmtc_layout layout, void* hip_stream,
                            fmtc_basis** out) {
+    return guarded([&]() -> fmtc_status {
     if (!out) return fail(FMTC_EINVAL, "out is NULL");
     *out = nullptr;
     if (!d_x || !dims_ok(N, C, H, W)) return fail(FMTC_EINVAL, "bad tensor arguments");
@@ -475,6 +491,7 @@ fmtc_status fmtc_fit_basis(const float* d_x, int64_t N, int C, int H, int W, fmt
     for (int c = 0; c < C; c++) mean[c] = sum[c] / (double)P;
     for (size_t i = 0; i < m2.size(); i++) m2[i] /= (double)P;
     return finish_fit(C, mean, m2, d_x, N, HW, layout, s, out);
+    });
 }
 
 struct fmtc_fit_state {
@@ -484,6 +501,7 @@ struct fmtc_fit_state {
 };
 
 fmtc_status fmtc_fit_state_create(int C, fmtc_fit_state** out) {
+    return guarded([&]() -> fmtc_status {
     if (!out) return fail(FMTC_EINVAL, "out is NULL");
     *out = nullptr;
     if (C < 1 || C > 1024) return fail(FMTC_EINVAL, "bad channel count %d", C);
@@ -494,6 +512,7 @@ fmtc_status fmtc_fit_state_create(int C, fmtc_fit_state** out) {
     f->m2.assign((size_t)C * C, 0.0);
     *out = f;
     return FMTC_OK;
+    });
 }
 
 void fmtc_fit_state_destroy(fmtc_fit_state* state) { delete state; }
@@ -502,6 +521,7 @@ int64_t fmtc_fit_state_count(const fmtc_fit_state* state) { return state ? state
 
 fmtc_status fmtc_fit_state_update(fmtc_fit_state* state, const float* d_x, int64_t N, int C, int H, int W,
                                   fmtc_layout layout, void* hip_stream) {
+    return guarded([&]() -> fmtc_status {
     if (!state || !d_x) return fail(FMTC_EINVAL, "NULL argument");
     if (!dims_ok(N, C, H, W) || state->C != C) return fail(FMTC_EINVAL, "bad dims or state has %d channels, tensor %d", state->C, C);
     if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
@@ -520,10 +540,12 @@ fmtc_status fmtc_fit_state_update(fmtc_fit_state* state, const float* d_x, int64
     for (int c = 0; c < C; c++) state->mean[c] += d[c] * ((double)nb / n);
     state->count += nb;
     return FMTC_OK;
+    });
 }
 
 fmtc_status fmtc_fit_state_basis(const fmtc_fit_state* state, const float* d_x, int64_t N, int C, int H, int W,
                                  fmtc_layout layout, void* hip_stream, fmtc_basis** out) {
+    return guarded([&]() -> fmtc_status {
     if (!out) return fail(FMTC_EINVAL, "out is NULL");
     *out = nullptr;
     if (!state || !d_x) return fail(FMTC_EINVAL, "NULL argument");
@@ -533,9 +555,11 @@ fmtc_status fmtc_fit_state_basis(const fmtc_fit_state* state, const float* d_x, 
     std::vector<double> cov(state->m2);
     for (size_t i = 0; i < cov.size(); i++) cov[i] /= (double)state->count;
     return finish_fit(C, state->mean, cov, d_x, N, (int64_t)H * W, layout, (hipStream_t)hip_stream, out);
+    });
 }
 
 fmtc_status fmtc_basis_truncate(const fmtc_basis* basis, int keep, fmtc_basis** out) {
+    return guarded([&]() -> fmtc_status {
     if (!out) return fail(FMTC_EINVAL, "out is NULL");
     *out = nullptr;
     if (!basis) return fail(FMTC_EINVAL, "basis is NULL");
@@ -557,6 +581,7 @@ fmtc_status fmtc_basis_truncate(const fmtc_basis* basis, int keep, fmtc_basis** 
     }
     *out = b;
     return FMTC_OK;
+    });
 }
 
 size_t fmtc_encode_bound(int64_t P, int C, int bits, int chunk_syms) {
@@ -666,12 +691,14 @@ void fmtc_table_destroy(fmtc_table* t) {
 }
 
 fmtc_status fmtc_table_import(const uint8_t* h_lengths, int bits, fmtc_table** out) {
+    return guarded([&]() -> fmtc_status {
     if (!h_lengths || !out) return fail(FMTC_EINVAL, "NULL argument");
     if (bits < 2 || bits > 8) return fail(FMTC_EINVAL, "bits must be in [2,8]");
     uint32_t max_len = 0;
     if (!lengths_complete(h_lengths, bits, &max_len))
         return fail(FMTC_EINVAL, "lengths are not those of a complete prefix code over %d symbols", 1 << bits);
-    fmtc_table* t = new fmtc_table;
+    fmtc_table* t = new (std::nothrow) fmtc_table;
+    if (!t) return fail(FMTC_ENOMEM, "host allocation failed");
     t->bits = bits;
     t->max_len = max_len;
     memcpy(t->lengths, h_lengths, (size_t)1 << bits);
@@ -697,6 +724,7 @@ fmtc_status fmtc_table_import(const uint8_t* h_lengths, int bits, fmtc_table** o
     }
     *out = t;
     return FMTC_OK;
+    });
 }
 
 fmtc_status fmtc_table_export(const fmtc_table* t, uint8_t* h_lengths, int* bits) {
@@ -708,6 +736,7 @@ fmtc_status fmtc_table_export(const fmtc_table* t, uint8_t* h_lengths, int* bits
 
 fmtc_status fmtc_fit_table(const fmtc_basis* basis, const float* d_x, int64_t N, int C, int H, int W,
                            fmtc_layout layout, int bits, void* hip_stream, fmtc_table** out) {
+    return guarded([&]() -> fmtc_status {
     if (!basis || !d_x || !out) return fail(FMTC_EINVAL, "NULL argument");
     if (!dims_ok(N, C, H, W) || basis->C != C) return fail(FMTC_EINVAL, "bad dims or basis has %d channels, tensor %d", basis->C, C);
     if (layout != FMTC_NCHW && layout != FMTC_NHWC) return fail(FMTC_EINVAL, "bad layout");
@@ -718,7 +747,8 @@ fmtc_status fmtc_fit_table(const fmtc_basis* basis, const float* d_x, int64_t N,
     fmtc_status st = plan_encode(N * HW, C, bits, 4096, &pl);
     if (st != FMTC_OK) return st;
     hipStream_t s = (hipStream_t)hip_stream;
-    fmtc_table* t = new fmtc_table;
+    fmtc_table* t = new (std::nothrow) fmtc_table;
+    if (!t) return fail(FMTC_ENOMEM, "host allocation failed");
     t->bits = bits;
     uint8_t *ws = nullptr, *d_len = nullptr;
     hipError_t e;
@@ -752,6 +782,7 @@ fmtc_status fmtc_fit_table(const fmtc_basis* basis, const float* d_x, int64_t N,
     }
     *out = t;
     return FMTC_OK;
+    });
 }
 
 static size_t static_bound_from(const EncodePlan& pl, uint32_t max_len) {
@@ -795,8 +826,7 @@ fmtc_status fmtc_encode_static(const fmtc_basis* basis, const fmtc_table* t, con
         PackParams pk = pack_params(nullptr, pl.g, bits, delta, cs, 0, t->d_enc_table, static_cast<uint8_t*>(d_stream_out),
                                     cap_words, d_out_bytes);
         pk.static_max_len = t->max_len;
-        const char* knob = getenv("FMTC_STATIC_FUSED");  // "0": always the two kernels (read at every call)
-        if (!(knob && knob[0] == '0') && encode_static_fused_applies(C, layout, (uint32_t)chunk_syms, cs.n_groups)) {
+        if (!test_option(kTestStaticTwoKernels) && encode_static_fused_applies(C, layout, (uint32_t)chunk_syms, cs.n_groups)) {
             static_assert(sizeof(CoderCtrl) % 4 == 0, "control block is cleared as words");
             const size_t clear_bytes = pl.ws.off_lookback + sizeof(uint64_t) * (size_t)cs.n_groups - pl.ws.off_ctrl;
             if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(w + pl.ws.off_ctrl), clear_bytes / 4, s)) != hipSuccess)
@@ -909,6 +939,7 @@ fmtc_status fmtc_stream_info(const void* h_header, size_t header_bytes, int* bit
 
 
 fmtc_status fmtc_basis8_create(const fmtc_basis* basis, float act_scale, fmtc_basis8** out) {
+    return guarded([&]() -> fmtc_status {
     if (!out) return fail(FMTC_EINVAL, "out is NULL");
     *out = nullptr;
     if (!basis) return fail(FMTC_EINVAL, "basis is NULL");
@@ -945,6 +976,7 @@ fmtc_status fmtc_basis8_create(const fmtc_basis* basis, float act_scale, fmtc_ba
     }
     *out = b;
     return FMTC_OK;
+    });
 }
 
 void fmtc_basis8_destroy(fmtc_basis8* b) {

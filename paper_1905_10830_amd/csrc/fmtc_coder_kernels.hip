@@ -10,6 +10,8 @@
 //   k_pack           one wavefront per chunk, one lane per run of 64 symbols: run sizes,
 //                    the chunk's place in the payload (a running sum over the chunk
 //                    groups handed from workgroup to workgroup), then the code bits.
+#include <atomic>
+
 #include "fmtc_device.h"
 #include "fmtc_internal.h"
 #include "fmtc_pack_device.h"
@@ -493,15 +495,18 @@ __global__ __launch_bounds__(256) void k_chunk_bits(PackParams p) {
     __shared__ uint8_t s_len[256];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool aligned4 = (p.chunk_syms & 3u) == 0;
+    const uint32_t stride = gridDim.x * kPackWaves;
     uint32_t ch = blockIdx.x * kPackWaves + (uint32_t)wave;
+    // (lanes with four neighbouring symbols each, as in the pack kernel: 16-byte loads per lane were tried for this
+    // sum, where the order does not matter, and took 21 us against 12 us at 51 M symbols)
+    const bool aligned4 = (p.chunk_syms & 3u) == 0;
     uint32_t w[16];
     if (ch < p.n_chunks) load_chunk_symbols(p, ch, lane, aligned4, w);  // in flight while the lengths arrive
     s_len[tid] = (uint8_t)(p.enc_table[tid] >> 56);
     __syncthreads();
     while (ch < p.n_chunks) {  // wavefront-uniform
         const uint32_t clen = chunk_len_of(p, ch);
-        const uint32_t next = ch + gridDim.x * kPackWaves;
+        const uint32_t next = ch + stride;
         uint32_t wn[16];
         if (next < p.n_chunks) load_chunk_symbols(p, next, lane, aligned4, wn);
         uint32_t bits = 0;
@@ -527,58 +532,61 @@ __global__ __launch_bounds__(256) void k_chunk_bits(PackParams p) {
 
 // One workgroup: chunk_off[i] = words of the chunks before chunk i (a chunk starts on a word), the header, the
 // stream size and the zero bytes of the alignment gaps.  The stream is marked invalid if it would outgrow the buffer.
-// Rounds of kScanTile chunks: coalesced loads (all of a thread's in flight together) into LDS, every thread scans
-// kScanPer neighbouring entries there, a scan over the threads' sums, coalesced stores.
-constexpr int kScanThreads = 1024, kScanPer = 8, kScanTile = kScanThreads * kScanPer;
+// Rounds of kScanTile chunks: a thread takes kScanPer neighbouring entries (16-byte loads, all in flight together;
+// the array's allocation is a multiple of 256 bytes, so a piece that starts inside it ends inside it), scans them in
+// registers, the threads' sums are scanned across the workgroup, and the offsets leave as 16-byte stores (the offset
+// table starts 320 bytes into the container, itself 16-byte aligned).
+constexpr int kScanThreads = 1024, kScanPer = 16, kScanTile = kScanThreads * kScanPer;
 __global__ __launch_bounds__(kScanThreads) void k_chunk_scan(PackParams p) {
-    __shared__ uint32_t s_w[kScanTile + kScanTile / 32];  // one pad word per 32: a thread's entries start in different banks
-    __shared__ unsigned long long s_wave[kScanThreads / 64];
+    __shared__ unsigned long long s_wave[2][kScanThreads / 64];
     __shared__ unsigned long long s_bits[kScanThreads / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t n = p.n_chunks;
     uint32_t* chunk_off = reinterpret_cast<uint32_t*>(p.stream + kHeaderBytes + kLenTableBytes);
-    auto slot = [](uint32_t i) { return i + (i >> 5); };
     unsigned long long carry = 0, bits = 0;
-    for (uint32_t base = 0; base < n; base += kScanTile) {
+    int flip = 0;
+    for (uint32_t base = 0; base < n; base += kScanTile, flip ^= 1) {
+        const uint32_t i0 = base + (uint32_t)tid * kScanPer;
         uint32_t v[kScanPer];
 #pragma unroll
-        for (int k = 0; k < kScanPer; k++) {
-            const uint32_t i = base + (uint32_t)tid + (uint32_t)kScanThreads * k;
-            v[k] = i < n ? p.chunk_bits[i] : 0u;
+        for (int k = 0; k < kScanPer; k += 4) {
+            uint4 q = make_uint4(0u, 0u, 0u, 0u);
+            if (i0 + k < n) q = *reinterpret_cast<const uint4*>(p.chunk_bits + i0 + k);
+            v[k] = q.x; v[k + 1] = q.y; v[k + 2] = q.z; v[k + 3] = q.w;
         }
+        uint32_t sum = 0;
 #pragma unroll
         for (int k = 0; k < kScanPer; k++) {
+            if (i0 + k >= n) v[k] = 0u;  // past the last chunk: whatever the workspace holds there
             bits += v[k];
-            s_w[slot((uint32_t)tid + (uint32_t)kScanThreads * k)] = (v[k] + 31u) >> 5;
-        }
-        __syncthreads();
-        uint32_t mine[kScanPer], sum = 0;
-#pragma unroll
-        for (int k = 0; k < kScanPer; k++) {
-            mine[k] = s_w[slot((uint32_t)tid * kScanPer + k)];
-            sum += mine[k];
+            v[k] = (v[k] + 31u) >> 5;
+            sum += v[k];
         }
         const unsigned long long incl = wave_inclusive_scan64(sum, lane);
-        if (lane == 63) s_wave[wave] = incl;
-        __syncthreads();
+        if (lane == 63) s_wave[flip][wave] = incl;
+        __syncthreads();  // (the other buffer is what the round before used: no second barrier needed)
         unsigned long long before = carry + incl - sum, total = 0;
         for (int q = 0; q < kScanThreads / 64; q++) {
-            if (q < wave) before += s_wave[q];
-            total += s_wave[q];
+            if (q < wave) before += s_wave[flip][q];
+            total += s_wave[flip][q];
         }
+        uint32_t off[kScanPer];
 #pragma unroll
         for (int k = 0; k < kScanPer; k++) {
-            s_w[slot((uint32_t)tid * kScanPer + k)] = (uint32_t)before;
-            before += mine[k];
+            off[k] = (uint32_t)before;
+            before += v[k];
         }
-        __syncthreads();
 #pragma unroll
-        for (int k = 0; k < kScanPer; k++) {
-            const uint32_t i = base + (uint32_t)tid + (uint32_t)kScanThreads * k;
-            if (i < n) chunk_off[i] = s_w[slot((uint32_t)tid + (uint32_t)kScanThreads * k)];
+        for (int k = 0; k < kScanPer; k += 4) {
+            if (i0 + k + 3 < n) {
+                *reinterpret_cast<uint4*>(chunk_off + i0 + k) = make_uint4(off[k], off[k + 1], off[k + 2], off[k + 3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    if (i0 + k + j < n) chunk_off[i0 + k + j] = off[k + j];
+            }
         }
         carry += total;
-        __syncthreads();  // s_w and s_wave are rewritten by the next round
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) bits += __shfl_xor(bits, o, 64);
@@ -674,8 +682,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 // Number of workgroups of the pack kernel the device holds at once (queried once per kernel variant).
 template <int MODE>
 static int pack_resident_groups() {
-    static int cached = 0;
-    if (cached) return cached;
+    static std::atomic<int> cached{0};  // (every thread computes the same value)
+    if (int c = cached.load(std::memory_order_relaxed)) return c;
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
@@ -683,8 +691,8 @@ static int pack_resident_groups() {
         per_cu < 1)
         return 64;  // conservative: any device this library runs on holds 64 workgroups
     if (per_cu > 4) per_cu = 4;
-    cached = cus * per_cu;
-    return cached;
+    cached.store(cus * per_cu, std::memory_order_relaxed);
+    return cus * per_cu;
 }
 
 // Table (a kernel of its own only where every pack workgroup building it would cost more than the launch)

@@ -12,8 +12,6 @@
 //      order and no workgroup barrier is needed after the tables.  Wide tensors: a
 //      tile of several chunks per workgroup, the basis streamed from L2.
 // Nothing outside [stream, stream + bytes) is read whatever the stream holds.
-#include <cstdlib>
-
 #include "fmtc_device.h"
 #include "fmtc_internal.h"
 
@@ -1154,10 +1152,9 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         groups = (int)(1024 / (n_tiles < 1024u ? n_tiles : 1024u));
         if (groups > n_cg) groups = n_cg;
         if (groups < 1) groups = 1;
-        // test hook: "1" makes every workgroup walk all channel groups of its tile, as it does for tensors with
-        // more tiles than the device holds (read at every call)
-        const char* knob = getenv("FMTC_DECODE_ONE_ROW");
-        if (knob && knob[0] == '1') groups = 1;
+        // (a test can make every workgroup walk all channel groups of its tile, as it does for tensors with more
+        // tiles than the device holds)
+        if (test_option(kTestDecodeOneRow)) groups = 1;
     }
     unsigned gx = n_tiles < 1024u ? n_tiles : 1024u;
     dim3 grid(gx, (unsigned)groups);

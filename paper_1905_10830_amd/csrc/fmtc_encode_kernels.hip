@@ -9,6 +9,7 @@
 // for the fast pass to decide are recomputed in fp64 by the wavefront.  Two
 // kernels: one wavefront per 32 pixels with the basis in LDS (up to 160
 // channels), and a workgroup tile in LDS with the basis streamed from L2 (wider).
+#include <atomic>
 #include <type_traits>
 
 #include "fmtc_device.h"
@@ -471,12 +472,13 @@ struct RowParams {
 constexpr int rows_waves_per_simd(int nct, bool fused, int waves) {
     return fused ? 1 : (waves == 8 ? 2 : (nct == 1 ? 4 : (nct <= 3 ? 2 : 1)));
 }
-template <int NCT, int LAYOUT, bool VEC, bool FUSED = false, int WAVES = 4>
-__global__ __launch_bounds__(WAVES * 64)
-__attribute__((amdgpu_waves_per_eu(rows_waves_per_simd(NCT, FUSED, WAVES), rows_waves_per_simd(NCT, FUSED, WAVES))))
+template <int NCT, int LAYOUT, bool VEC, bool FUSED = false, int WAVES = 4, int WPS = rows_waves_per_simd(NCT, FUSED, WAVES)>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WPS, WPS)))
 void k_project_quantize_rows(RowParams p) {
     constexpr int THREADS = WAVES * 64;
-    static_assert(WAVES == 4 || (WAVES == 8 && !FUSED && (NCT * NCT * 256) % THREADS == 0), "workgroup shape");
+    static_assert(WAVES == 4 || (WAVES == 8 && !FUSED), "workgroup shape");
+    // SEQ: contraction, then quantizer, tile by tile with one pair of accumulators (see process_tile)
+    constexpr bool SEQ = WPS >= 3 || WAVES == 8;
     constexpr int NJ = NCT * 2;  // steps of 16 channels
     extern __shared__ __align__(16) uint4 basis16[];  // [NCT][NJ][2][64], then the histograms
     __shared__ __align__(16) float s_mu[NCT * 32];
@@ -544,8 +546,9 @@ void k_project_quantize_rows(RowParams p) {
     {
         const uint4* src = reinterpret_cast<const uint4*>(p.basis16);
 #pragma unroll
-        for (int i = 0; i < NCT * NCT * 256 / THREADS; i++)
-            __builtin_amdgcn_global_load_lds(src + tid + THREADS * i, &basis16[THREADS * i + 64 * wave], 16, 0, 0);
+        for (int i = 0; i < (NCT * NCT * 256 + THREADS - 1) / THREADS; i++)
+            if (THREADS * i + 64 * wave < NCT * NCT * 256)  // whole wavefronts
+                __builtin_amdgcn_global_load_lds(src + tid + THREADS * i, &basis16[THREADS * i + 64 * wave], 16, 0, 0);
     }
     if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
     if constexpr (!FUSED) {
@@ -669,8 +672,10 @@ void k_project_quantize_rows(RowParams p) {
         if (__builtin_expect(__any(force), 0)) split(true);
         const float tau = fminf(fmaxf(p.kappa * __builtin_sqrtf(n2), p.tau_min), 0.125f);
         const float near_limit = force ? -1.f : 0.5f - tau;
-        // the raw registers are free: the next tile's loads are in flight during this tile's arithmetic
-        if (next_tile < p.n_tiles) load_pixels(next_tile);
+        // the raw registers are free: the next tile's loads are in flight during this tile's arithmetic.  (With
+        // three or more wavefronts per SIMD the others' arithmetic covers the loads, and registers held by loads in
+        // flight across the whole tile are what would not fit: there the loads go out after the tile.)
+        if (WPS < 3 && next_tile < p.n_tiles) load_pixels(next_tile);
 
         auto project_tile = [&](int kt, floatx16& am, floatx16& ac) {
 #pragma unroll
@@ -763,7 +768,35 @@ void k_project_quantize_rows(RowParams p) {
         const bool full = (tile * 32 + 32 <= p.P) && (C % 16 == 0);
         floatx16 am, ac;
         project_tile(0, am, ac);
-        if (full) {
+        if (full && SEQ) {
+            // Several wavefronts per SIMD: the others fill the shadow of this one's matrix instructions, and one
+            // pair of accumulators (not two) is what lets them fit: contraction, then quantizer, tile by tile.
+#pragma unroll
+            for (int kt = 0; kt < NCT; kt++) {
+                if (kt) project_tile(kt, am, ac);
+                uint32_t word[4] = {0u, 0u, 0u, 0u};
+                float maxd = 0.f;
+                const bool k_ok = kt * 32 + 16 * half < C;  // false only in the upper half of a padded last tile
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const float t = __builtin_fmaf(ac[r], inv_delta_lo, am[r] * inv_delta);
+                    const float q = __builtin_rintf(t);  // round half to even
+                    maxd = fmaxf(maxd, fabsf(t - q));
+                    const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
+                    word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
+                    if constexpr (!FUSED)
+                        if (k_ok) atomicAdd(&wh[(uint32_t)qc * kHistLanes], 1u);
+                }
+                if constexpr (FUSED) {
+                    *reinterpret_cast<uint4*>(sym_tiles + wave * 4096 + ((px - chunk_px0) * C + kt * 32 + 16 * half)) =
+                        make_uint4(word[0], word[1], word[2], word[3]);
+                } else if (k_ok) {
+                    *reinterpret_cast<uint4*>(p.syms + px * C + kt * 32 + 16 * half) =
+                        make_uint4(word[0], word[1], word[2], word[3]);
+                }
+                if (__builtin_expect(__any(!(maxd <= near_limit) && k_ok), 0)) note_tile(am, ac, kt, word);
+            }
+        } else if (full) {
             // One wavefront per SIMD: nothing else fills the shadow of the matrix pipe, so the quantizer of tile
             // kt is issued between the matrix instructions of tile kt + 1 -- after each step of the contraction
             // the share of the previous tile's 16 values that keeps both in step.
@@ -812,6 +845,14 @@ void k_project_quantize_rows(RowParams p) {
                 am = nm;
                 ac = nc;
             }
+        } else if (SEQ) {
+#pragma unroll
+            for (int kt = 0; kt < NCT; kt++) {
+                uint32_t word[4];
+                if (kt) project_tile(kt, am, ac);
+                const float maxd = quantize_tile(am, ac, kt, word);
+                if (__builtin_expect(__any(!(maxd <= near_limit) && px_ok), 0)) note_tile(am, ac, kt, word);
+            }
         } else {
 #pragma unroll
             for (int kt = 0; kt < NCT; kt++) {
@@ -857,7 +898,11 @@ void k_project_quantize_rows(RowParams p) {
         }
         return;
     } else {
-        for (; tile < p.n_tiles; tile += (int64_t)gridDim.x * WAVES) process_tile(tile, tile + (int64_t)gridDim.x * WAVES);
+        for (; tile < p.n_tiles; tile += (int64_t)gridDim.x * WAVES) {
+            const int64_t next_tile = tile + (int64_t)gridDim.x * WAVES;
+            process_tile(tile, next_tile);
+            if (WPS >= 3 && next_tile < p.n_tiles) load_pixels(next_tile);
+        }
     }
     if (*fix_count) resolve_list();
     __syncthreads();
@@ -917,9 +962,19 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     // fit a compute unit's LDS and there are tiles enough for them
     // (measured at 128 channels, 25.7 M values: 67 us against 62 us with four wavefronts, one per SIMD -- the second
     // wavefront's registers do not fit without spills -- so the eight-wavefront form stays off)
-    const bool eight = false;
+    const bool vec0 = (b.C % 4) == 0;
+    // 128 channels: eight wavefronts on one copy of the basis, two per SIMD, each working tile by tile with one pair
+    // of accumulators (two four-wavefront workgroups with a copy each would not fit a compute unit's LDS).  Measured
+    // at 25.7 M values: 57 us against 63 us with four wavefronts, one per SIMD.  (The same form for 144 channels
+    // spills registers: 119 us against 80 us.)
+    // (planar tensors: the loads' addresses do not fit the registers either; 8 bits: eight wavefronts' histograms do
+    // not fit LDS beside the basis)
+    auto lds_for = [&](int wv) {
+        return sizeof(float) * (size_t)b.Cpad * b.Cpad + sizeof(uint32_t) * wv * kHistLanes * ((size_t)1 << bits);
+    };
+    const bool eight = nct == 4 && layout == FMTC_NHWC && p.n_tiles > 1024 && lds_for(8) <= 144 * 1024;
     const int waves = eight ? 8 : 4;
-    const size_t lds = sizeof(float) * (size_t)b.Cpad * b.Cpad + sizeof(uint32_t) * waves * kHistLanes * ((size_t)1 << bits);
+    const size_t lds = lds_for(waves);
     // workgroups a compute unit holds at once: by registers (rows_waves_per_simd) and by LDS
     const size_t lds_static = (size_t)waves * (2 * kFixList + 1 + 256) * 4 + (size_t)nct * 128 + 512;
     int per_cu = eight ? 1 : rows_waves_per_simd(nct, false, 4);
@@ -929,7 +984,7 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     const int64_t cap = 256 * (int64_t)per_cu;
     if (gx > cap) gx = cap;
     *n_parts = (int)gx;
-    const bool vec = (b.C % 4) == 0;
+    const bool vec = vec0;
     hipError_t el = hipSuccess;
 #define FMTC_ROWS_W(NCT, LAY, VEC, WV)                                                                           \
     do {                                                                                                         \
@@ -946,10 +1001,11 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
         if (nct == 1) FMTC_ROWS(1, LAY, VEC);                                                                    \
         else if (nct == 2) FMTC_ROWS(2, LAY, VEC);                                                               \
         else if (nct == 3) FMTC_ROWS(3, LAY, VEC);                                                               \
-        else if (eight) FMTC_ROWS_W(4, LAY, VEC, 8);                                                             \
         else FMTC_ROWS(4, LAY, VEC);                                                                             \
     } while (0)
-    if (nct == 5) {  // channels-last only (see launch_project_quantize)
+    if (eight) {
+        if (vec) FMTC_ROWS_W(4, FMTC_NHWC, true, 8); else FMTC_ROWS_W(4, FMTC_NHWC, false, 8);
+    } else if (nct == 5) {  // channels-last only (see launch_project_quantize)
         if (vec) FMTC_ROWS(5, FMTC_NHWC, true); else FMTC_ROWS(5, FMTC_NHWC, false);
     } else if (layout == FMTC_NHWC) { if (vec) FMTC_ROWS_N(FMTC_NHWC, true); else FMTC_ROWS_N(FMTC_NHWC, false); }
     else                            { if (vec) FMTC_ROWS_N(FMTC_NCHW, true); else FMTC_ROWS_N(FMTC_NCHW, false); }
@@ -975,8 +1031,9 @@ static int fused_kernel_for(int C, int layout, const void** fn_out, size_t* lds_
 #undef FMTC_FUSED
     *fn_out = fn;
     *lds_out = lds;
-    static int resident[2][3] = {{0, 0, 0}, {0, 0, 0}};
-    int& cap = resident[layout == FMTC_NHWC][nct == 4 ? 2 : nct - 1];
+    static std::atomic<int> resident[2][3];  // (zero-initialised; every thread computes the same values)
+    std::atomic<int>& slot = resident[layout == FMTC_NHWC][nct == 4 ? 2 : nct - 1];
+    int cap = slot.load(std::memory_order_relaxed);
     if (!cap) {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
@@ -985,6 +1042,7 @@ static int fused_kernel_for(int C, int layout, const void** fn_out, size_t* lds_
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, lds) != hipSuccess || cus < 1 || per_cu < 1)
             return 0;
         cap = cus;  // one workgroup per compute unit, whatever more would fit
+        slot.store(cap, std::memory_order_relaxed);
     }
     return cap;
 }

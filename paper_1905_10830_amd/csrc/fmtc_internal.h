@@ -124,6 +124,10 @@ struct BasisDevice {
     const float* T;        // [C][C] row major, unpacked
 };
 
+// Path choices a test can force (fmtc_test_option in fmtc.h): both only pick between paths a caller reaches anyway.
+enum TestOption { kTestStaticTwoKernels = 0, kTestDecodeOneRow = 1, kTestOptionCount };
+int test_option(int which);  // current value (0 unless a test set it)
+
 // ---- optional per-kernel timing (fmtc_profile_* in fmtc.h) ----
 // When enabled, a launch carries a pair of events that the runtime attaches to the kernel's own dispatch, so
 // the elapsed time is the kernel's start-to-end time on the GPU (no bracket of separate marker commands).

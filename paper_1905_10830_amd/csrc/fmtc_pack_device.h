@@ -353,7 +353,7 @@ __device__ __forceinline__ void pack_group(PackShared& S, const PackParams& p, u
             top = (top > 64u * kLook) ? top - 64u * kLook : 0u;
         }
         if (failed) {
-            if (lane == 0) p.ctrl->error = 1u;
+            if (lane == 0) __hip_atomic_fetch_or(&p.ctrl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             excl = 0;
             excl_slack = 0;
         }
@@ -386,7 +386,7 @@ __device__ __forceinline__ void pack_group(PackShared& S, const PackParams& p, u
                     hdr.payload_bits = 32ull * total_words - total_slack;
                 }
                 // a wait gave up, or the payload outgrew the buffer (then some chunk was not written): not valid
-                if (p.ctrl->error || total_words > p.cap_words) hdr.magic = 0u;
+                if (__hip_atomic_load(&p.ctrl->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) || total_words > p.cap_words) hdr.magic = 0u;
                 *reinterpret_cast<Header*>(p.stream) = hdr;
                 if (p.out_bytes) *p.out_bytes = (uint64_t)p.off_payload + 4 * total_words;
                 // alignment gaps between the sections are part of the stream: keep them zero
@@ -401,7 +401,7 @@ __device__ __forceinline__ void pack_group(PackShared& S, const PackParams& p, u
         // histogram and the symbols ever disagree, or a table made beforehand not fit the tensor, nothing is
         // written past the buffer: the stream is marked invalid instead.)
         const bool fits = (uint64_t)word0 + n_words <= p.cap_words;
-        if (!fits && lane == 0) p.ctrl->error = 1u;
+        if (!fits && lane == 0) __hip_atomic_fetch_or(&p.ctrl->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         uint32_t* out = reinterpret_cast<uint32_t*>(p.stream + p.off_payload) + word0;
         for (uint32_t win = 0; win < n_words; win += kStageWords) {
             const uint32_t win_words = (n_words - win < (uint32_t)kStageWords) ? n_words - win : (uint32_t)kStageWords;

@@ -3,6 +3,7 @@
 // is the kernel's start-to-end time on the GPU.  Off by default; when off the
 // hook costs one branch.  Used by the benchmark to hold each kernel against its
 // roofline.  Also home of two utility kernels (zero fill, yardstick copy).
+#include <atomic>
 #include <vector>
 
 #include "fmtc_internal.h"
@@ -34,6 +35,11 @@ void release() {
     g_prof.cap = 0;
 }
 }  // namespace
+
+static std::atomic<int> g_test_option[kTestOptionCount];
+int test_option(int which) {
+    return (which >= 0 && which < kTestOptionCount) ? g_test_option[which].load(std::memory_order_relaxed) : 0;
+}
 
 bool prof_next(int id, hipEvent_t* start, hipEvent_t* stop) {
     if (!g_prof.on) return false;
@@ -74,6 +80,12 @@ hipError_t launch_fill_zero(uint32_t* d_words, size_t n_words, hipStream_t s) {
 }  // namespace fmtc
 
 extern "C" {
+
+fmtc_status fmtc_test_option(int option, int value) {
+    if (option < 0 || option >= fmtc::kTestOptionCount) return FMTC_EINVAL;
+    fmtc::g_test_option[option].store(value, std::memory_order_relaxed);
+    return FMTC_OK;
+}
 
 fmtc_status fmtc_profile_enable(int max_launches_per_kernel) {
     using namespace fmtc;

@@ -138,9 +138,12 @@ def test_wide_decoder_walking_its_channel_groups(fmtc, oracle, C, layout, monkey
     stream, nbytes = fmtc.encode(basis, x_d, 5, layout)
     a, ea = fmtc.decode(basis, stream, x.shape, 5, layout)
     torch.cuda.synchronize()
-    monkeypatch.setenv("FMTC_DECODE_ONE_ROW", "1")
-    b, eb = fmtc.decode(basis, stream, x.shape, 5, layout)
-    torch.cuda.synchronize()
+    fmtc.test_option(fmtc.TEST_DECODE_ONE_ROW, 1)
+    try:
+        b, eb = fmtc.decode(basis, stream, x.shape, 5, layout)
+        torch.cuda.synchronize()
+    finally:
+        fmtc.test_option(fmtc.TEST_DECODE_ONE_ROW, 0)
     assert int(ea.item()) == 0 and int(eb.item()) == 0 and torch.equal(a, b)
     sym, d, _ = oracle.unpack(stream[: int(nbytes.item())].cpu().numpy(), x.size // C, C, 5)
     ref = oracle.reconstruct(sym, x.shape, T, mu, d, 5, layout)

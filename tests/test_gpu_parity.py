@@ -44,10 +44,10 @@ def make_case(oracle, C, H, W, n_calib, n_data, rank, act, seed, layout):
         calib = data
     xs = synth.to_layout(data, layout)
     cal = synth.to_layout(calib, layout)
-    if C <= 160:
+    if C <= 256:
         T, mu, eig, A = oracle.fit(cal, layout)
     else:
-        # the oracle's Jacobi solver is too slow here; any orthonormal basis serves codec parity, so take
+        # the oracle's Jacobi solver takes a quarter of a minute at 512 channels and minutes beyond; any orthonormal basis serves codec parity, so take
         # the library eigensolver's (test side only) and the oracle's projection for the range
         mean, cov = oracle.covariance(cal, layout)
         w, v = np.linalg.eigh(cov)
@@ -307,20 +307,31 @@ def test_argument_errors(fmtc, oracle):
     assert e.value.status == fmtc.EBUFSIZE
 
 
+# (C, H, W, images, rank): the benchmark's channel counts 128 and 256 beside a small case; more pixels than channels
+FIT_CASES = [(48, 12, 12, 4, 12), (128, 14, 14, 3, 32), (256, 14, 14, 3, 64)]
+
+
 @pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
-def test_fit_basis_matches_oracle(fmtc, oracle, layout):
-    s = synth.FeatureMapStream(C=48, H=12, W=12, rank=12, act="relu", seed=77)
-    x = synth.to_layout(s.images(4), layout)
+@pytest.mark.parametrize("case", FIT_CASES, ids=[f"C{c[0]}" for c in FIT_CASES])
+def test_fit_basis_matches_oracle(fmtc, oracle, case, layout):
+    C, H, W, n, rank = case
+    s = synth.FeatureMapStream(C=C, H=H, W=W, rank=rank, act="relu", seed=77)
+    x = synth.to_layout(s.images(n), layout)
     T, mu, eig, A = oracle.fit(x, layout)
     basis = fmtc.fit_basis(dev(x), layout)
     Tg, mug, eigg, Ag = basis.export()
     assert np.abs(mug - mu).max() <= 1e-7
-    assert np.allclose(eigg, eig, rtol=1e-9, atol=1e-12)
-    assert np.abs(Tg.astype(np.float64) @ Tg.T.astype(np.float64) - np.eye(48)).max() < 1e-6
+    assert np.allclose(eigg, eig, rtol=1e-9, atol=1e-12 * C)
+    assert np.abs(Tg.astype(np.float64) @ Tg.T.astype(np.float64) - np.eye(C)).max() < 1e-6
+    # the fitted rows diagonalise the oracle's covariance: off-diagonal entries vanish against the largest eigenvalue
+    _, cov = oracle.covariance(x, layout)
+    D = Tg.astype(np.float64) @ cov @ Tg.T.astype(np.float64)
+    assert np.abs(D - np.diag(np.diag(D))).max() <= 1e-5 * eig[0]
+    assert np.allclose(np.diag(D), eig, rtol=1e-5, atol=1e-6 * eig[0])
     # eigenvectors are unique (up to the fixed sign rule) where eigenvalues are separated
     gaps = np.minimum(np.abs(np.diff(eig, prepend=np.inf)), np.abs(np.diff(eig, append=-np.inf)))
-    sep = gaps > 1e-6 * eig[0]
-    assert sep.sum() >= 12
+    sep = gaps > 1e-4 * eig[0]
+    assert sep.sum() >= rank // 2
     assert np.abs(Tg[sep] - T[sep]).max() < 1e-5
     assert Ag == pytest.approx(float(A), rel=1e-6)
     # the fitted handle drives the codec: full round trip within the quantizer's error

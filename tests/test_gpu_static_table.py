@@ -119,9 +119,12 @@ def test_single_kernel_and_two_kernel_paths_agree(fmtc, oracle, case, monkeypatc
     table = fmtc.fit_table(basis, dev(cal), bits)
     a, na = fmtc.encode_static(basis, table, dev(dat))
     torch.cuda.synchronize()
-    monkeypatch.setenv("FMTC_STATIC_FUSED", "0")
-    b, nb = fmtc.encode_static(basis, table, dev(dat))
-    torch.cuda.synchronize()
+    fmtc.test_option(fmtc.TEST_STATIC_TWO_KERNELS, 1)
+    try:
+        b, nb = fmtc.encode_static(basis, table, dev(dat))
+        torch.cuda.synchronize()
+    finally:
+        fmtc.test_option(fmtc.TEST_STATIC_TWO_KERNELS, 0)
     n = int(na.item())
     assert int(nb.item()) == n and (a[:n] == b[:n]).all()
 

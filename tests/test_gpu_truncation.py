@@ -181,6 +181,27 @@ def test_fit_over_several_tensors_matches_oracle(fmtc, oracle, layout):
     assert e.value.status == fmtc.EINVAL
 
 
+@pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("C,rank", [(128, 32), (256, 64)], ids=["C128", "C256"])
+def test_fit_over_several_tensors_at_benchmark_widths(fmtc, oracle, C, rank, layout):
+    s = synth.FeatureMapStream(C=C, H=14, W=14, rank=rank, act="relu", seed=81)
+    parts = [synth.to_layout(s.images(n), layout) for n in (1, 2, 1)]
+    T, mu, eig, A = oracle.fit_online(parts, parts[-1], layout)
+    st = fmtc.FitState(C)
+    for p in parts:
+        st.update(dev(p), layout)
+    assert st.count == sum(p.size // C for p in parts)
+    Tg, mug, eigg, Ag = st.basis(dev(parts[-1]), layout).export()
+    assert np.abs(mug - mu).max() <= 1e-7
+    assert np.allclose(eigg, eig, rtol=1e-9, atol=1e-12 * C)
+    assert np.abs(Tg.astype(np.float64) @ Tg.T.astype(np.float64) - np.eye(C)).max() < 1e-6
+    gaps = np.minimum(np.abs(np.diff(eig, prepend=np.inf)), np.abs(np.diff(eig, append=-np.inf)))
+    sep = gaps > 1e-4 * eig[0]
+    assert sep.sum() >= rank // 2
+    assert np.abs(Tg[sep] - T[sep]).max() < 1e-5
+    assert Ag == pytest.approx(float(A), rel=1e-6)
+
+
 def test_one_update_is_the_plain_fit(fmtc, oracle):
     s = synth.FeatureMapStream(C=40, H=9, W=9, rank=10, act="relu", seed=80)
     x = s.images(3)
