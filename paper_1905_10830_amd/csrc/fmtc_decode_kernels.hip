@@ -26,6 +26,8 @@ typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t sym_addr(uint32_t n) { return n + 4u * (n >> 6); }
 
 
+constexpr int kLut2Bits = 10;  // second table: codes longer than kLutBits bits
+
 // Decode tables, in LDS, built by every workgroup from the code length table of the stream.
 struct DecTables {
     uint32_t cnt_len[64];     // number of codes of each length
@@ -39,11 +41,20 @@ struct DecTables {
     // n = number of whole codes found in those bits (0: the first code is longer than kLutBits), bits = their
     // total length
     uint32_t lut[1 << kLutBits];
-    // scratch of the construction
-    uint16_t first[1 << kLutBits];  // first code in a kLutBits-bit value (first stream bit on top): sym | len << 8
+    // Codes longer than kLutBits bits.  Canonical codes grow with their length, so left-aligned in 32 bits all of
+    // them lie at or above long_base (the first value the short codes do not cover), in a range whose size is about
+    // their share of the probability mass.  lut2 is indexed by (value - long_base) >> long_shift: sym | len << 8
+    // where those bits decide the code (its length is at most 32 - long_shift and at most 31), 0 where they do not
+    // (the decoders then search the per-length limits).  It shares its place with scratch of the construction:
+    // `first` = first code in a kLutBits-bit value (first stream bit on top), sym | len << 8.
+    union {
+        uint16_t lut2[1 << kLut2Bits];
+        uint16_t first[1 << kLutBits];
+    };
     uint32_t wave_len_count[4][64];
     uint32_t lut_limit[kLutBits + 1];  // limit[] in a kLutBits-bit frame
     uint32_t n_used, bad_len, ok, max_len;
+    uint32_t long_base, long_shift, pad0, pad1;
 };
 
 // All THREADS threads of the workgroup call this (THREADS a multiple of 256); my_len is the code length of symbol
@@ -160,6 +171,53 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
             T.lut[idx] = e;
         }
     }
+    __syncthreads();  // `first` is not read any more: the second table takes its place
+    {
+        // Step 3: the table of the longer codes (see DecTables).  Nothing to do where no code is longer than kLutBits.
+        const uint32_t lim = T.lut_limit[kLutBits];  // kLutBits-bit values below it start with a short code
+        const uint32_t max_len = T.max_len;
+        const bool have_long = max_len > (uint32_t)kLutBits && lim < (1u << kLutBits);
+        const uint32_t base = have_long ? lim << (32 - kLutBits) : 0xffffffffu;
+        const uint64_t span = (1ull << 32) - base;  // values at or above base
+        uint32_t shift = 0;
+        while (shift < 32u - kLut2Bits && (span >> shift) > (1ull << kLut2Bits)) shift++;
+        if (tid == 0) {
+            T.long_base = base;
+            T.long_shift = shift;
+            T.pad0 = 0u;
+            T.pad1 = 0u;
+        }
+        // (worth its construction only where long codes are frequent: their share of the code space, about their
+        // share of the symbols, is span / 2^32; below 2^-11 a chunk meets a handful of them)
+        if (have_long && span >= (1ull << 21)) {
+            const uint32_t top = max_len < 33u ? max_len : 33u;
+            uint32_t lim32[33 - (kLutBits + 1)];  // the limits, read once
+#pragma unroll
+            for (uint32_t l = kLutBits + 1; l < 33u; l++) lim32[l - (kLutBits + 1)] = T.limit32[l];
+#pragma unroll
+            for (int it = 0; it < ((1 << kLut2Bits) + THREADS - 1) / THREADS; it++) {
+                const uint32_t idx = (uint32_t)tid + (uint32_t)(it * THREADS);
+                if (idx >= (1u << kLut2Bits)) break;
+                const uint64_t v64 = (uint64_t)base + ((uint64_t)idx << shift);
+                const uint32_t v = (uint32_t)v64;
+                uint32_t len = kLutBits + 1;
+#pragma unroll
+                for (uint32_t l = kLutBits + 1; l < 33u; l++) {
+                    len += (l < top && v >= lim32[l - (kLutBits + 1)]) ? 1u : 0u;
+                }
+                uint32_t entry = 0;
+                if (v64 <= 0xffffffffull && len <= 32u - shift && len <= 31u) {
+                    const uint32_t off = (v >> (32 - len)) - (uint32_t)T.first_code[len];
+                    if (off < T.cnt_len[len]) entry = (uint32_t)T.sorted_sym[(T.first_rank[len] + off) & 255u] | (len << 8);
+                }
+                T.lut2[idx] = (uint16_t)entry;
+            }
+        } else {
+            // no entry of the first table sends a valid stream here; a corrupt one finds "undecided" and is caught
+            // by the search
+            for (uint32_t idx = (uint32_t)tid; idx < (1u << kLut2Bits); idx += THREADS) T.lut2[idx] = 0;
+        }
+    }
     __syncthreads();
     return true;
 }
@@ -236,8 +294,16 @@ __device__ __forceinline__ bool decode_run(const uint32_t* pw, const uint32_t* _
         const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, sh);
         uint32_t e = T.lut[w & ((1u << kLutBits) - 1)];
         uint32_t n = e >> 29, sym0 = e & 255u, len0 = (e >> 24) & 31u;
+        if (n == 0) {  // a code longer than the table: the second table decides most of them
+            const uint32_t e2 = T.lut2[((__brev(w) - T.long_base) >> T.long_shift) & ((1u << kLut2Bits) - 1)];
+            if (e2) {
+                sym0 = e2 & 255u;
+                len0 = e2 >> 8;
+                n = 1;
+            }
+        }
         if (__builtin_expect(n == 0, 0)) {
-            // A code longer than the table.  Canonical codes, left-aligned, grow with their length, so the
+            // Canonical codes, left-aligned, grow with their length, so the
             // length is kLutBits + 1 + the number of longer-length limits the next 32 bits reach.
             const uint32_t v = __brev(w);  // first stream bit on top
             uint32_t len = kLutBits + 1;
@@ -315,6 +381,14 @@ __device__ __forceinline__ bool decode_run_bytes(const uint32_t* pw, uint32_t nw
         const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, sh);
         uint32_t e = T.lut[w & ((1u << kLutBits) - 1)];
         uint32_t after = *pp;  // does not wait for the entry: both reads are in flight
+        if (__builtin_expect(__any((e >> 29) == 0), 0)) {
+            if ((e >> 29) == 0) {
+                // a code longer than the table: the second table decides most of them (one symbol, its length at
+                // most 31, so the step below moves the cursor as for any other entry)
+                const uint32_t e2 = T.lut2[((__brev(w) - T.long_base) >> T.long_shift) & ((1u << kLut2Bits) - 1)];
+                if (e2) e = (e2 & 255u) | ((e2 >> 8) << 24) | (1u << 29);
+            }
+        }
         if (__builtin_expect(__any((e >> 29) == 0), 0)) {
             if ((e >> 29) == 0) {
                 // A code longer than the table.  Canonical codes, left-aligned, grow with their length, so the
