@@ -267,24 +267,29 @@ fmtc_status run_coder(const uint8_t* d_syms, const EncodePlan& pl, const CoderSc
 }
 
 
-// Sums [C] and cross-product sums about this tensor's own mean [C*C] (both triangles accumulated separately on the
-// device, made exactly symmetric here), in fp64.  Synchronises the stream.
+// Sums [C] and cross-product sums about this tensor's own mean [C*C] (fp64 matrix cores; 64 x 64 blocks off the
+// diagonal are computed once and mirrored, the blocks on it in full: made exactly symmetric here), in fp64.
+// Synchronises the stream.
 fmtc_status device_moments(const float* d_x, int64_t N, int C, int64_t HW, int layout, hipStream_t s,
                            std::vector<double>* sum, std::vector<double>* m2) {
     hipError_t e;
-    double* d_stat = nullptr;
+    double *d_stat = nullptr, *d_part = nullptr;
     const size_t n_stat = (size_t)C + (size_t)C * C;
-    if ((e = hipMalloc((void**)&d_stat, sizeof(double) * n_stat)) != hipSuccess)
+    if ((e = hipMalloc((void**)&d_stat, sizeof(double) * n_stat)) != hipSuccess ||
+        (e = hipMalloc((void**)&d_part, fit_moments_scratch_bytes(N * HW, C))) != hipSuccess) {
+        if (d_stat) (void)hipFree(d_stat);
         return fail(FMTC_ENOMEM, "hipMalloc fit scratch: %s", hipGetErrorString(e));
+    }
     std::vector<double> stat(n_stat);
     fmtc_status st = FMTC_OK;
     do {
-        if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(d_stat), 2 * n_stat, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
-        if ((e = launch_fit_moments(d_x, N, C, HW, layout, d_stat, d_stat + C, s)) != hipSuccess) { st = hip_fail(e, "fit moments"); break; }
+        if ((e = launch_fill_zero(reinterpret_cast<uint32_t*>(d_stat), 2 * (size_t)C, s)) != hipSuccess) { st = hip_fail(e, "clear"); break; }
+        if ((e = launch_fit_moments(d_x, N, C, HW, layout, d_stat, d_stat + C, d_part, s)) != hipSuccess) { st = hip_fail(e, "fit moments"); break; }
         if ((e = hipMemcpyAsync(stat.data(), d_stat, sizeof(double) * n_stat, hipMemcpyDeviceToHost, s)) != hipSuccess) { st = hip_fail(e, "copy moments"); break; }
         if ((e = hipStreamSynchronize(s)) != hipSuccess) { st = hip_fail(e, "fit sync"); break; }
     } while (0);
     (void)hipFree(d_stat);
+    (void)hipFree(d_part);
     if (st != FMTC_OK) return st;
     sum->assign(stat.begin(), stat.begin() + C);
     m2->assign(stat.begin() + C, stat.end());

@@ -218,8 +218,10 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
 hipError_t launch_build_decode_tables(const uint8_t* d_len_table, int bits, void* d_prebuilt, uint32_t* d_ok, hipStream_t s);
 size_t prebuilt_decode_tables_bytes();
 
+// d_sum [C] must be zero on entry; d_cov [C*C] is overwritten; d_scratch: fit_moments_scratch_bytes(N * HW, C) bytes
 hipError_t launch_fit_moments(const float* d_x, int64_t N, int C, int64_t HW, int layout, double* d_sum,
-                              double* d_cov, hipStream_t s);
+                              double* d_cov, double* d_scratch, hipStream_t s);
+size_t fit_moments_scratch_bytes(int64_t P, int C);
 hipError_t launch_fit_range(const float* d_x, int64_t N, int C, int64_t HW, int layout, const float* d_t0,
                             const float* d_mu, double* d_amax, hipStream_t s);
 hipError_t launch_fill_zero(uint32_t* d_words, size_t n_words, hipStream_t s);
