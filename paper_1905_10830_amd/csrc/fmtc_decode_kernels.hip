@@ -1050,16 +1050,11 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                 }
                 continue;
             }
-            floatx16 acc[NCT], acl[NCT];
-#pragma unroll
-            for (int ct = 0; ct < NCT; ct++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) { acc[ct][r] = 0.f; acl[ct][r] = 0.f; }
+            // the levels of this lane's pixel as f16 operands, all contraction steps (coefficients past C meet zero
+            // basis entries; whatever finite level the tile's bytes give there does not count)
+            halfx8 q[NJ];
 #pragma unroll
             for (int j = 0; j < NJ; j++) {
-                if (j >= NJA) continue;  // wavefront-uniform: steps past the basis' last non-zero row (truncation)
-                // the eight symbols 16j + 8*half .. + 7 of this lane's pixel (coefficients past C meet zero basis
-                // entries; whatever finite level the tile's bytes give there does not count)
                 const uint32_t n = rowbase + 16u * (uint32_t)j;
                 uint32_t w0, w1;
                 if constexpr (ALIGNED4) {
@@ -1075,28 +1070,32 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                 const halfx2 q23 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w0, 0x07030602u)) - level_off2;
                 const halfx2 q45 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w1, 0x05010400u)) - level_off2;
                 const halfx2 q67 = __builtin_bit_cast(halfx2, __builtin_amdgcn_perm(0x64646464u, w1, 0x07030602u)) - level_off2;
-                const halfx8 q = {q01[0], q01[1], q23[0], q23[1], q45[0], q45[1], q67[0], q67[1]};
+                q[j] = halfx8{q01[0], q01[1], q23[0], q23[1], q45[0], q45[1], q67[0], q67[1]};
+            }
+            // One channel tile at a time: one pair of accumulators, the contraction, the epilogue, the stores (all
+            // tiles at once would hold 2 NCT accumulators: the registers of a third wavefront per SIMD).
 #pragma unroll
-                for (int ct = 0; ct < NCT; ct++) {
+            for (int ct = 0; ct < NCT; ct++) {
+                floatx16 acc, acl;
+#pragma unroll
+                for (int r = 0; r < 16; r++) { acc[r] = 0.f; acl[r] = 0.f; }
+#pragma unroll
+                for (int j = 0; j < NJ; j++) {
+                    if (j >= NJA) continue;  // wavefront-uniform: steps past the basis' last non-zero row (truncation)
                     const halfx8 bh = __builtin_bit_cast(halfx8, basis16[((ct * NJ + j) * 2) * 64 + lane]);
                     const halfx8 bl = __builtin_bit_cast(halfx8, basis16[((ct * NJ + j) * 2 + 1) * 64 + lane]);
                     if constexpr (LAYOUT == FMTC_NHWC) {
-                        acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q, bh, acc[ct], 0, 0, 0);
-                        acl[ct] = __builtin_amdgcn_mfma_f32_32x32x16_f16(q, bl, acl[ct], 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[j], bh, acc, 0, 0, 0);
+                        acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[j], bl, acl, 0, 0, 0);
                     } else {
-                        acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, q, acc[ct], 0, 0, 0);
-                        acl[ct] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q, acl[ct], 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, q[j], acc, 0, 0, 0);
+                        acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q[j], acl, 0, 0, 0);
                     }
                 }
-            }
 #pragma unroll
-            for (int ct = 0; ct < NCT; ct++)
-#pragma unroll
-                for (int r = 0; r < 16; r++) acc[ct][r] = __builtin_fmaf(acl[ct][r], 1.f / 2048.f, acc[ct][r]);
-            // accumulator r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of the 32x32 tile
-            if constexpr (LAYOUT == FMTC_NHWC) {
-#pragma unroll
-                for (int ct = 0; ct < NCT; ct++) {
+                for (int r = 0; r < 16; r++) acc[r] = __builtin_fmaf(acl[r], 1.f / 2048.f, acc[r]);
+                // accumulator r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of the 32x32 tile
+                if constexpr (LAYOUT == FMTC_NHWC) {
                     const int c = ct * 32 + l32;
                     if (c < C) {
                         const float m_c = s_mu[c];
@@ -1104,28 +1103,25 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                         if (pt * 32 + 32 <= TP) {
 #pragma unroll
                             for (int r = 0; r < 16; r++)
-                                dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = __builtin_fmaf(acc[ct][r], delta, m_c);
+                                dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = __builtin_fmaf(acc[r], delta, m_c);
                         } else {
 #pragma unroll
                             for (int r = 0; r < 16; r++)
                                 if (pt * 32 + 8 * (r >> 2) + 4 * half + (r & 3) < TP)
-                                    dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = __builtin_fmaf(acc[ct][r], delta, m_c);
+                                    dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = __builtin_fmaf(acc[r], delta, m_c);
                         }
                     }
-                }
-            } else {
-                const int my_px = pt * 32 + l32;
-                if (my_px < TP) {
-                    const int64_t px = px_chunk0 + my_px;
-                    const int64_t n = px / p.HW, hw = px - n * p.HW;
-#pragma unroll
-                    for (int ct = 0; ct < NCT; ct++) {
+                } else {
+                    const int my_px = pt * 32 + l32;
+                    if (my_px < TP) {
+                        const int64_t px = px_chunk0 + my_px;
+                        const int64_t n = px / p.HW, hw = px - n * p.HW;
                         const int cb = ct * 32 + 4 * half;
                         float* dst = p.xhat + (n * (int64_t)C + cb) * p.HW + hw;
 #pragma unroll
                         for (int r = 0; r < 16; r++) {
                             const int co = 8 * (r >> 2) + (r & 3);
-                            if (cb + co < C) dst[(int64_t)co * p.HW] = __builtin_fmaf(acc[ct][r], delta, s_mu[cb + co]);
+                            if (cb + co < C) dst[(int64_t)co * p.HW] = __builtin_fmaf(acc[r], delta, s_mu[cb + co]);
                         }
                     }
                 }
