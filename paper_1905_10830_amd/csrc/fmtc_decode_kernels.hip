@@ -28,6 +28,13 @@ __device__ __forceinline__ uint32_t sym_addr(uint32_t n) { return n + 4u * (n >>
 
 constexpr int kLut2Bits = 10;  // second table: codes longer than kLutBits bits
 
+// Where the lookup table keeps the entry of the stream bits `v` (kLutBits of them, first bit lowest).  The LDS bank of
+// a word is its index modulo 64; short codes are frequent, so many lanes of a wavefront look at bit patterns that
+// agree in their first bits and differ in the later ones -- with the plain index these would be different words of
+// one bank, read one after the other.  Folding the upper bits into the lower six spreads them over the banks
+// (patterns that agree in all bits are one word, which the LDS reads once for all lanes).
+__device__ __forceinline__ uint32_t lut_slot(uint32_t v) { return v ^ (v >> 6); }
+
 // Decode tables, in LDS, built by every workgroup from the code length table of the stream.
 struct DecTables {
     uint32_t cnt_len[64];     // number of codes of each length
@@ -168,7 +175,7 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
             if (ok0) e = (f0 & 255u) | (len0 << 24) | (1u << 29);
             if (ok1) e = (f0 & 255u) | ((f1 & 255u) << 8) | ((len0 + len1) << 24) | (2u << 29);
             if (ok2) e = (f0 & 255u) | ((f1 & 255u) << 8) | ((f2 & 255u) << 16) | ((len0 + len1 + len2) << 24) | (3u << 29);
-            T.lut[idx] = e;
+            T.lut[lut_slot((uint32_t)idx)] = e;
         }
     }
     __syncthreads();  // `first` is not read any more: the second table takes its place
@@ -292,7 +299,7 @@ __device__ __forceinline__ bool decode_run(const uint32_t* pw, const uint32_t* _
     uint32_t i = 0;
     while (i < cnt) {
         const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, sh);
-        uint32_t e = T.lut[w & ((1u << kLutBits) - 1)];
+        uint32_t e = T.lut[lut_slot(w & ((1u << kLutBits) - 1))];
         uint32_t n = e >> 29, sym0 = e & 255u, len0 = (e >> 24) & 31u;
         if (n == 0) {  // a code longer than the table: the second table decides most of them
             const uint32_t e2 = T.lut2[((__brev(w) - T.long_base) >> T.long_shift) & ((1u << kLut2Bits) - 1)];
@@ -360,92 +367,106 @@ __device__ __forceinline__ bool decode_run(const uint32_t* pw, const uint32_t* _
     return ok;
 }
 
-// The same for a chunk staged in LDS whose run goes to 64 consecutive bytes `out`, which up to 3 more bytes
-// may follow (pad bytes of the tile): every step stores the three symbol bytes of its table entry at the
-// current position, and the next step overwrites what was not a symbol.  One table read and a handful of
-// dependent operations per up to three symbols.  Codes longer than the table are rare: the wavefront branches
-// (as a whole) only when one of its lanes meets one.
-// `pw` holds the chunk's nwords words, two zero words, and at least kPayOverrun words of any content behind
-// them: a run of a corrupt stream may read that far (64 steps of at most 48 bits), never further.
+// The same for a chunk staged in LDS whose run goes to 64 consecutive bytes `out`, which 4 pad bytes of the tile
+// follow.  One turn of the loop reads the 64 stream bits around the cursor once (two words, at least 33 of them
+// ahead of the cursor) and looks three table entries up in them, one after the other (up to 11 bits each, so the
+// third still finds its 11 bits): up to nine symbols for one read of the stream and three of the table.  An
+// entry's three symbol bytes go to the current position with byte stores (one unaligned 32-bit store instead
+// stalls the LDS: its counters showed 70 % of its busy time in such stalls); the next entry overwrites what was not a
+// symbol, and stores past the end of the run go to the pad bytes.  An entry of no symbols (a code longer than the table) leaves the cursor where it is, so the
+// entries after it in the same turn are the same one: the wavefront looks at the last entry only, and branches (as
+// a whole) when one of its lanes has met such a code inside its run.
+// `pw` holds the chunk's nwords words and at least kPayOverrun words of any content behind them: a run of a corrupt
+// stream may read that far (every symbol moves the cursor by at most 48 bits, and a run ends after 64 symbols and
+// at most two more table entries), never further.
 constexpr int kPayOverrun = 104;
 __device__ __forceinline__ bool decode_run_bytes(const uint32_t* pw, uint32_t nwords, uint32_t start, uint32_t cnt,
                                                  const DecTables& T, uint8_t* out) {
-    const uint32_t w0 = (start >> 5) < nwords ? (start >> 5) : nwords;
-    const uint32_t* pp = pw + w0;  // word after the three at hand
-    uint32_t sh = start & 31;
-    uint32_t lo = pp[0], hi = pp[1], nxt = pp[2];
-    pp += 3;
+    constexpr uint32_t kMask = (1u << kLutBits) - 1u;
+    uint32_t bit = start < 32u * nwords ? start : 32u * nwords;  // (side information of a corrupt stream)
     bool ok = true;
     uint32_t i = 0;
     while (i < cnt) {
-        const uint32_t w = __builtin_amdgcn_alignbit(hi, lo, sh);
-        uint32_t e = T.lut[w & ((1u << kLutBits) - 1)];
-        uint32_t after = *pp;  // does not wait for the entry: both reads are in flight
-        if (__builtin_expect(__any((e >> 29) == 0), 0)) {
-            if ((e >> 29) == 0) {
-                // a code longer than the table: the second table decides most of them (one symbol, its length at
-                // most 31, so the step below moves the cursor as for any other entry)
-                const uint32_t e2 = T.lut2[((__brev(w) - T.long_base) >> T.long_shift) & ((1u << kLut2Bits) - 1)];
-                if (e2) e = (e2 & 255u) | ((e2 >> 8) << 24) | (1u << 29);
-            }
-        }
-        if (__builtin_expect(__any((e >> 29) == 0), 0)) {
-            if ((e >> 29) == 0) {
-                // A code longer than the table.  Canonical codes, left-aligned, grow with their length, so the
-                // length is kLutBits + 1 + the number of longer-length limits the next 32 bits reach (limits of
-                // the lengths below the longest one are below 2^32; the longest needs no test).
-                const uint32_t v = __brev(w);  // first stream bit on top
-                const uint32_t top = T.max_len < 33u ? T.max_len : 33u;
-                uint32_t len = kLutBits + 1;
-                // (fixed trip count: the reads of all limits are in flight together instead of one after the other)
-#pragma unroll
-                for (uint32_t l = kLutBits + 1; l < 33u; l++) len += (l < top && v >= T.limit32[l]) ? 1u : 0u;
-                uint32_t sym = 0;
-                uint32_t bp = (uint32_t)(pp - 3 - pw) * 32u + sh;
-                if (len <= 32) {
-                    const uint32_t off = (v >> (32 - len)) - (uint32_t)T.first_code[len];
-                    if (off >= T.cnt_len[len]) ok = false;
-                    sym = T.sorted_sym[(T.first_rank[len] + off) & 255u];
-                    bp += len;
-                } else {
-                    // longer than 32 bits (needs a histogram as skewed as the Fibonacci numbers): bit by bit
-                    uint64_t code = 0;
-                    bool found = false;
-                    for (uint32_t l = 1; l <= (uint32_t)kMaxLen; l++) {
-                        code = (code << 1) | ((pw[bp >> 5] >> (bp & 31)) & 1u);
-                        bp++;
-                        const uint64_t f = T.first_code[l];
-                        const uint32_t c = T.cnt_len[l];
-                        if (c && code >= f && code - f < c) {
-                            sym = T.sorted_sym[T.first_rank[l] + (uint32_t)(code - f)];
-                            found = true;
-                            break;
-                        }
-                    }
-                    if (!found) ok = false;
-                }
-                // the cursor moves here; what follows sees an entry of one symbol and no bits
-                pp = pw + (bp >> 5);
-                sh = bp & 31;
-                lo = pp[0];
-                hi = pp[1];
-                nxt = pp[2];
-                after = pp[3];
-                pp += 3;
-                e = sym | (1u << 29);
-            }
-        }
+        const uint32_t* pp = pw + (bit >> 5);
+        const uint32_t lo = pp[0], hi = pp[1];
+        const unsigned long long win = ((unsigned long long)hi << 32) | lo;
+        uint32_t sh = bit & 31u;
+        // first entry: i < 64, the store stays inside the run's 64 + 4 bytes
+        uint32_t e = T.lut[lut_slot(__builtin_amdgcn_alignbit(hi, lo, sh) & kMask)];
         out[i] = (uint8_t)e;
         out[i + 1] = (uint8_t)(e >> 8);
         out[i + 2] = (uint8_t)(e >> 16);
         i += e >> 29;
-        sh += (e >> 24) & 31u;  // at most 31 + kLutBits: one word boundary at most
-        const bool cross = sh >= 32;
-        lo = cross ? hi : lo;
-        hi = cross ? nxt : hi;
-        nxt = cross ? after : nxt;
-        pp += cross ? 1 : 0;
-        sh &= 31u;
+        uint32_t l = (e >> 24) & 31u;
+        sh += l;
+        bit += l;
+#pragma unroll
+        for (int step = 1; step < 3; step++) {
+            e = T.lut[lut_slot((uint32_t)(win >> sh) & kMask)];
+            const uint32_t io = i < 64u ? i : 64u;
+            out[io] = (uint8_t)e;
+            out[io + 1] = (uint8_t)(e >> 8);
+            out[io + 2] = (uint8_t)(e >> 16);
+            i += e >> 29;
+            l = (e >> 24) & 31u;
+            sh += l;
+            bit += l;
+        }
+        if (__builtin_expect(__any((e >> 29) == 0 && i < cnt), 0)) {
+            if ((e >> 29) == 0 && i < cnt) {
+                // A code longer than the table starts at the cursor.  The next 32 bits, first stream bit on top:
+                const uint32_t* qq = pw + (bit >> 5);
+                const uint32_t v = __brev(__builtin_amdgcn_alignbit(qq[1], qq[0], bit & 31u));
+                uint32_t sym = 0, len = 0;
+                // the second table decides most of them
+                const uint32_t e2 = T.lut2[((v - T.long_base) >> T.long_shift) & ((1u << kLut2Bits) - 1)];
+                if (e2) {
+                    sym = e2 & 255u;
+                    len = e2 >> 8;
+                } else {
+                    // Canonical codes, left-aligned, grow with their length, so the length is kLutBits + 1 + the
+                    // number of longer-length limits the 32 bits reach (limits of the lengths below the longest one
+                    // are below 2^32; the longest needs no test).  One limit at a time: this is rare, and registers
+                    // it would hold for all limits at once would be the whole loop's.
+                    const uint32_t top = T.max_len < 33u ? T.max_len : 33u;
+                    len = kLutBits + 1;
+#pragma unroll 1
+                    for (uint32_t q = kLutBits + 1; q < top; q++) {
+                        if (v < T.limit32[q]) break;
+                        len++;
+                    }
+                    if (len <= 32) {
+                        const uint32_t off = (v >> (32 - len)) - (uint32_t)T.first_code[len];
+                        if (off >= T.cnt_len[len]) ok = false;
+                        sym = T.sorted_sym[(T.first_rank[len] + off) & 255u];
+                    } else {
+                        // longer than 32 bits (needs a histogram as skewed as the Fibonacci numbers): bit by bit
+                        unsigned long long code = 0;
+                        bool found = false;
+                        uint32_t bp = bit;
+#pragma unroll 1
+                        for (len = 1; len <= (uint32_t)kMaxLen; len++) {
+                            code = (code << 1) | ((pw[bp >> 5] >> (bp & 31)) & 1u);
+                            bp++;
+                            const unsigned long long f = T.first_code[len];
+                            const uint32_t c = T.cnt_len[len];
+                            if (c && code >= f && code - f < c) {
+                                sym = T.sorted_sym[T.first_rank[len] + (uint32_t)(code - f)];
+                                found = true;
+                                break;
+                            }
+                        }
+                        if (!found) {
+                            ok = false;
+                            len = kMaxLen;
+                        }
+                    }
+                }
+                out[i] = (uint8_t)sym;
+                i++;
+                bit += len;
+            }
+        }
     }
     return ok;
 }
@@ -468,6 +489,9 @@ struct DecodeParams {
     size_t g_off_chunk_off, g_off_sub_bits, g_off_payload;
     uint32_t g_n_chunks, g_spc;
     const void* prebuilt;  // PrebuiltTables of a code table fixed beforehand, or NULL: build them from the stream
+    // chunk decoder: bytes of the basis operand at the start of its dynamic LDS, and the words of payload the LDS
+    // copy of a chunk holds (larger chunks are read in place); a multiple of 64
+    uint32_t lds_basis_bytes, pay_words;
     int active_steps;      // contraction steps of 16 coefficients up to the basis' last row that is not all zero
     // 8-bit reconstruction in the chunk decoder (k_decode_chunks<..., U8 = true>): the transposed 8-bit basis in
     // the operand order of the integer matrix instruction [ncs][ceil(C / 16)][64], its column sums and the mean
@@ -807,21 +831,23 @@ constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes 
 // U8: the tile's symbols go through the 8-bit basis on the integer matrix cores instead (v_mfma_i32_32x32x16_i8;
 // exact sums, one fused fp64 multiply-add and one rounding per value, 8-bit activations out); the 8-bit basis
 // takes the f16 basis' place in LDS.
-template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES, bool U8 = false>
+// FIXC: the tensor has exactly 32 NCT channels (the launcher checks it), so every row stride is a constant.
+template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES, bool U8 = false, bool FIXC = false>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k_decode_chunks(DecodeParams p) {
     constexpr int THREADS = WAVES * 64;
     __shared__ __align__(16) DecTables T;
-    __shared__ uint32_t pay[WAVES][kPayWords + 2 + kPayOverrun];  // per wavefront: the chunk's payload words, 2 zero
-                                                                  // words, room for a corrupt stream's overrun
     __shared__ __align__(16) uint8_t symtile[WAVES][kChunkTileBytes];
     __shared__ float s_mu[NCT * 32];
-    extern __shared__ __align__(16) uint4 basis16[];  // [NCT][NJ][2][64]
+    // the basis operand [NCT][NJ][2][64], then per wavefront the chunk's payload words and room for a corrupt
+    // stream's overrun
+    extern __shared__ __align__(16) uint4 basis16[];
     constexpr int NJ = NCT * 2;  // steps of 16 coefficients
+    const uint32_t pay_cap = p.pay_words;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
     const int half = lane >> 5, l32 = lane & 31;
-    const int C = p.C;
+    const int C = FIXC ? NCT * 32 : p.C;
 
     // loads that do not depend on the header go out first: the code length table and the basis
     int my_len = 0;
@@ -846,11 +872,25 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     // the nominal chunk size puts them: three dependent memory round trips (header, offsets, payload) become
     // two that overlap with the table build.  The guess is checked against the header below; a stream made with
     // another chunk size loads them again.  Nothing outside [stream, stream + bytes) is touched either way.
-    const uint32_t ch_first = blockIdx.x * WAVES + (uint32_t)wave;
-    constexpr int kPrePay = (kPayWords + 2 + 63) / 64;
+    // (chunk c goes to workgroup c mod gridDim.x: a last, partly filled round of chunks is spread over all compute
+    // units, one wavefront each, instead of filling a few of them)
+    const uint32_t ch_first = (uint32_t)wave * gridDim.x + blockIdx.x;
+    // this wavefront's LDS copy of a chunk's payload: pay_cap words and the overrun room
+    uint32_t* pw = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(basis16) + p.lds_basis_bytes) +
+                   (size_t)wave * (pay_cap + (uint32_t)kPayOverrun);
+    // Words [w0, w0 + n) of the payload go from global memory straight into that copy, 4 bytes per lane and
+    // instruction, no registers in between; lanes past the chunk's end load nothing (what lies behind the chunk in
+    // LDS is whatever was there: the decoder never takes a symbol of its run from it).  Asynchronous: wait_loads<0>()
+    // before the copy is read.
+    auto request_payload = [&](const uint32_t* payload, uint32_t w0, uint32_t n) {
+        const uint32_t* src = payload + w0;
+        for (uint32_t k = 0; 64u * k < n; k++) {  // wavefront-uniform trip count
+            const uint32_t i = (uint32_t)lane + 64u * k;
+            if (i < n) load_to_lds<4>(src + i, pw + 64u * k);
+        }
+    };
     const bool guess = p.g_off_payload <= p.bytes && ch_first < p.g_n_chunks;
     uint32_t pre_w0 = 0, pre_w1 = 0, pre_run = 0;
-    uint32_t pre_pay[kPrePay];
     bool pay_pre = false;
     if (guess) {
         const uint32_t* co = reinterpret_cast<const uint32_t*>(p.stream + p.g_off_chunk_off);
@@ -861,15 +901,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         const size_t cap_words = (p.bytes - p.g_off_payload) / 4;
         const uint32_t gw0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)pre_w0);
         const uint32_t gw1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)pre_w1);
-        pay_pre = gw0 <= gw1 && (size_t)gw1 <= cap_words && gw1 - gw0 <= (uint32_t)kPayWords;
-        if (pay_pre) {
-            const uint32_t* pay_src = reinterpret_cast<const uint32_t*>(p.stream + p.g_off_payload) + gw0;
-#pragma unroll
-            for (int k = 0; k < kPrePay; k++) {
-                const uint32_t i = (uint32_t)lane + 64u * k;
-                pre_pay[k] = (i < gw1 - gw0) ? pay_src[i] : 0u;
-            }
-        }
+        pay_pre = gw0 <= gw1 && (size_t)gw1 <= cap_words && gw1 - gw0 <= pay_cap;
+        if (pay_pre) request_payload(reinterpret_cast<const uint32_t*>(p.stream + p.g_off_payload), gw0, gw1 - gw0);
     }
     StreamView sv;
     if (!open_stream(p, &sv)) {
@@ -906,13 +939,12 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     const _Float16 level_off = (_Float16)(float)(1024 + (1 << (p.bits - 1)));
     const halfx2 level_off2 = {level_off, level_off};
     uint8_t* tile = symtile[wave];
-    uint32_t* pw = pay[wave];
 
-    // Side information and payload of a chunk are requested one chunk ahead: offsets and run sizes of the next chunk
-    // at the top of a turn (they arrive during this chunk's variable length decoding), its payload words right after
-    // that decoding (they arrive during the inverse transform) -- a chunk would otherwise start with two dependent
-    // memory round trips.  cur_*: what is at hand for the chunk of this turn; pay_*: the words held in registers and
-    // the offsets they were fetched for.
+    // Side information and payload of a chunk are requested one chunk ahead: its payload words right after the
+    // variable length decoding of the chunk before it (the LDS copy is free then; they arrive during the inverse
+    // transform), offsets and run sizes of the chunk after it once those words have landed (they arrive during the
+    // variable length decoding) -- a chunk would otherwise start with two dependent memory round trips.  cur_*:
+    // what is at hand for the chunk of this turn; pay_*: the offsets the words in the LDS copy were requested for.
     uint32_t cur_w0 = pre_w0, cur_w1 = pre_w1, cur_run = pre_run;
     bool pay_ok = guess_valid && pay_pre;
     uint32_t pay_w0 = guess_w0, pay_w1 = guess_w1;
@@ -928,6 +960,15 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             w0 = 0; w1 = 0;
         }
         const uint32_t run_bits = cur_run;
+        const uint32_t nwords = w1 - w0;
+        const bool staged = nwords <= pay_cap;
+        // (whatever was requested for the LDS copy has landed before it is read or requested again; this also waits
+        // for the stores of the chunk before)
+        wait_loads<0>();
+        if (staged && !(pay_ok && w0 == pay_w0 && w1 == pay_w1)) {
+            request_payload(sv.payload, w0, nwords);
+            wait_loads<0>();
+        }
         const uint32_t nch = ch + ch_step;
         const bool have_next = nch < n_chunks && nch > ch;  // wavefront-uniform
         if (have_next) {
@@ -938,18 +979,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         const uint32_t start = wave_exclusive_scan(run_bits, lane);
         const uint32_t r0 = (uint32_t)lane * kSubSyms;
         const uint32_t cnt = (r0 < clen) ? ((clen - r0 < (uint32_t)kSubSyms) ? clen - r0 : (uint32_t)kSubSyms) : 0u;
-        const uint32_t nwords = w1 - w0;
         bool ok_run = true;
-        const bool staged = nwords <= (uint32_t)kPayWords;
         if (staged) {
-            if (pay_ok && w0 == pay_w0 && w1 == pay_w1) {
-                // the words requested ahead (zero past the chunk's end)
-#pragma unroll
-                for (int k = 0; k < kPrePay; k++)
-                    if ((uint32_t)lane + 64u * k < nwords + 2) pw[lane + 64 * k] = pre_pay[k];
-            } else {
-                for (uint32_t i = lane; i < nwords + 2; i += 64) pw[i] = (i < nwords) ? sv.payload[w0 + i] : 0u;
-            }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
             // run `lane` goes to bytes [68 * lane, 68 * lane + 64) of the tile (sym_addr), 4 pad bytes behind it
@@ -957,20 +988,16 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         } else if (cnt) {
             ok_run = decode_run<false>(nullptr, sv.payload + w0, nwords, start, cnt, T, ByteOut(tile, r0));
         }
-        // the next chunk's payload words: in flight during this chunk's inverse transform
+        // the next chunk's payload words: in flight during this chunk's inverse transform (every lane is done with
+        // the LDS copy: the reads of a wavefront complete in order, and each lane has used its last one)
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
         pay_ok = false;
         if (have_next) {
             pay_w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cur_w0);
             pay_w1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cur_w1);
-            pay_ok = pay_w0 <= pay_w1 && pay_w1 <= payload_words && pay_w1 - pay_w0 <= (uint32_t)kPayWords;
-            if (pay_ok) {
-                const uint32_t* pay_src = sv.payload + pay_w0;
-#pragma unroll
-                for (int k = 0; k < kPrePay; k++) {
-                    const uint32_t i = (uint32_t)lane + 64u * k;
-                    pre_pay[k] = (i < pay_w1 - pay_w0) ? pay_src[i] : 0u;
-                }
-            }
+            pay_ok = pay_w0 <= pay_w1 && pay_w1 <= payload_words && pay_w1 - pay_w0 <= pay_cap;
+            if (pay_ok) request_payload(sv.payload, pay_w0, pay_w1 - pay_w0);
         }
         if (!ok_run) atomicOr(p.err, FMTC_ERR_CODE);
         // the symbols of all lanes are in place before any lane reads them: one wavefront, LDS in order
@@ -1100,7 +1127,13 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                     if (c < C) {
                         const float m_c = s_mu[c];
                         float* dst = p.xhat + (px_chunk0 + pt * 32 + 4 * half) * C + c;
-                        if (pt * 32 + 32 <= TP) {
+                        if (pt * 32 + 32 <= TP && C == NCT * 32) {
+                            // (the usual case, with the row stride a constant: the stores' offsets are immediates
+                            // instead of sixteen 64-bit values in registers)
+#pragma unroll
+                            for (int r = 0; r < 16; r++)
+                                dst[(size_t)(8 * (r >> 2) + (r & 3)) * (NCT * 32)] = __builtin_fmaf(acc[r], delta, m_c);
+                        } else if (pt * 32 + 32 <= TP) {
 #pragma unroll
                             for (int r = 0; r < 16; r++)
                                 dst[(size_t)(8 * (r >> 2) + (r & 3)) * C] = __builtin_fmaf(acc[r], delta, m_c);
@@ -1165,37 +1198,51 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     // (five channel tiles: channels-last only, the planar stores take more registers than are left)
     if (!d_syms && (ncs <= 4 || (ncs == 5 && layout == FMTC_NHWC))) {
         // ---- one wavefront per chunk ----
-        const size_t lds = sizeof(float) * (size_t)ncs * 32 * ncs * 32;
-        // two wavefronts per SIMD once the chunks outnumber the SIMDs of the device
-        // (three channel tiles need more registers, five more LDS, than two wavefronts per SIMD leave)
-        const bool eight = g.n_chunks > 1024 && ncs != 3 && ncs != 5;
-        const int waves = eight ? 8 : 4;
-        const size_t lds_static = sizeof(DecTables) + (size_t)waves * ((kPayWords + 2 + kPayOverrun) * 4 + kChunkTileBytes) + 1024;
-        const unsigned per_cu = (unsigned)((160 * 1024) / (lds + lds_static));
+        const size_t lds_basis = sizeof(float) * (size_t)ncs * 32 * ncs * 32;
+        // The LDS copy of a chunk's payload holds what a chunk takes at the fixed-length rate of `bits` per symbol
+        // (which the code of the whole tensor never exceeds on average) and a little more; a chunk beyond that is
+        // read in place.
+        p.lds_basis_bytes = (uint32_t)lds_basis;
+        p.pay_words = 128u * (uint32_t)bits + 64u;
+        auto lds_dyn = [&](int wv) { return lds_basis + (size_t)wv * (p.pay_words + kPayOverrun) * 4; };
+        auto lds_all = [&](int wv) { return lds_dyn(wv) + sizeof(DecTables) + (size_t)wv * kChunkTileBytes + (size_t)ncs * 128 + 64; };
+        // One, two or four wavefronts per SIMD as the chunks outnumber the SIMDs of the device: the variable length
+        // decoding is a chain of dependent LDS reads, and the other wavefronts' work fills its waits.  (Three channel
+        // tiles need more registers, five more LDS, than two wavefronts per SIMD leave; four per SIMD fit up to two
+        // channel tiles.)
+        int waves = 4;
+        if (g.n_chunks > 1024 && ncs != 3 && ncs != 5) waves = 8;
+        if (g.n_chunks > 3072 && ncs <= 2 && C == ncs * 32 && layout == FMTC_NHWC && lds_all(16) <= 160 * 1024) waves = 16;
+        const size_t lds = lds_dyn(waves);
+        const unsigned per_cu = (unsigned)((160 * 1024) / lds_all(waves));
         unsigned gx = (g.n_chunks + waves - 1) / waves;
-        const unsigned cap = 256u * (per_cu < 1 ? 1u : (per_cu > (unsigned)(8 / waves) ? (unsigned)(8 / waves) : per_cu));
+        const unsigned most = waves >= 8 ? 1u : 2u;
+        const unsigned cap = 256u * (per_cu < 1 ? 1u : (per_cu > most ? most : per_cu));
         if (gx > cap) gx = cap;
-#define FMTC_DECC(NCT, LAY, AL, WV)                                                                              \
+#define FMTC_DECC_F(NCT, LAY, AL, WV, FX)                                                                        \
     do {                                                                                                         \
         if (lds > 16 * 1024) {                                                                                   \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV>), \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, false, FX>), \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
             if (ea != hipSuccess) return ea;                                                                     \
         }                                                                                                        \
-        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV>, dim3(gx), dim3(WV * 64), lds, s, p);            \
+        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, false, FX>, dim3(gx), dim3(WV * 64), lds, s, p); \
     } while (0)
+#define FMTC_DECC(NCT, LAY, AL, WV) FMTC_DECC_F(NCT, LAY, AL, WV, false)
 #define FMTC_DECC_N(LAY, AL)                                                                                     \
     do {                                                                                                         \
-        if (ncs == 1) { if (eight) FMTC_DECC(1, LAY, AL, 8); else FMTC_DECC(1, LAY, AL, 4); }                    \
-        else if (ncs == 2) { if (eight) FMTC_DECC(2, LAY, AL, 8); else FMTC_DECC(2, LAY, AL, 4); }               \
+        if (ncs == 1) { if (waves == 8) FMTC_DECC(1, LAY, AL, 8); else FMTC_DECC(1, LAY, AL, 4); }               \
+        else if (ncs == 2) { if (waves == 8) FMTC_DECC(2, LAY, AL, 8); else FMTC_DECC(2, LAY, AL, 4); }          \
         else if (ncs == 3) FMTC_DECC(3, LAY, AL, 4);                                                             \
-        else { if (eight) FMTC_DECC(4, LAY, AL, 8); else FMTC_DECC(4, LAY, AL, 4); }                             \
+        else { if (waves == 8) FMTC_DECC(4, LAY, AL, 8); else FMTC_DECC(4, LAY, AL, 4); }                        \
     } while (0)
-        if (ncs == 5) { if (al) FMTC_DECC(5, FMTC_NHWC, true, 4); else FMTC_DECC(5, FMTC_NHWC, false, 4); }
+        if (waves == 16) { if (ncs == 1) FMTC_DECC_F(1, FMTC_NHWC, true, 16, true); else FMTC_DECC_F(2, FMTC_NHWC, true, 16, true); }
+        else if (ncs == 5) { if (al) FMTC_DECC(5, FMTC_NHWC, true, 4); else FMTC_DECC(5, FMTC_NHWC, false, 4); }
         else if (layout == FMTC_NHWC) { if (al) FMTC_DECC_N(FMTC_NHWC, true); else FMTC_DECC_N(FMTC_NHWC, false); }
         else                          { if (al) FMTC_DECC_N(FMTC_NCHW, true); else FMTC_DECC_N(FMTC_NCHW, false); }
 #undef FMTC_DECC_N
 #undef FMTC_DECC
+#undef FMTC_DECC_F
         return el;
     }
 
@@ -1288,9 +1335,12 @@ hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size
     p.factor8 = h;
     p.out8 = d_xq_hat;
     const bool al = (C % 4) == 0;
-    const size_t lds = (size_t)ncs * ((C + 15) / 16) * 64 * 8;  // the basis operand
+    const size_t lds_basis = (size_t)ncs * ((C + 15) / 16) * 64 * 8;  // the basis operand
     const bool eight = g.n_chunks > 1024 && ncs != 3;
     const int waves = eight ? 8 : 4;
+    p.lds_basis_bytes = (uint32_t)lds_basis;
+    p.pay_words = 128u * (uint32_t)bits + 64u;
+    const size_t lds = lds_basis + (size_t)waves * (p.pay_words + kPayOverrun) * 4;
     unsigned gx = (g.n_chunks + waves - 1) / waves;
     const unsigned cap = 256u * (unsigned)(8 / waves);
     if (gx > cap) gx = cap;
