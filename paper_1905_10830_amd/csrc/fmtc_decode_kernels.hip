@@ -34,6 +34,9 @@ constexpr int kLut2Bits = 10;  // second table: codes longer than kLutBits bits
 // one bank, read one after the other.  Folding the upper bits into the lower six spreads them over the banks
 // (patterns that agree in all bits are one word, which the LDS reads once for all lanes).
 __device__ __forceinline__ uint32_t lut_slot(uint32_t v) { return v ^ (v >> 6); }
+// The same for the 16-bit scratch table of the construction (two entries per word: bits 1..6 choose the bank), which
+// is read at values shifted left by a code length: their lower bits are zero, and the upper ones must choose the bank.
+__device__ __forceinline__ uint32_t first_slot(uint32_t v) { return v ^ (v >> 5); }
 
 // Decode tables, in LDS, built by every workgroup from the code length table of the stream.
 struct DecTables {
@@ -114,12 +117,15 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
     // symbols of equal length are numbered in symbol order
     uint32_t before = 0;
     if (tid < 256) {
-        const uint32_t max_len = T.max_len;
-        for (uint32_t q = 1; q <= max_len; q++) {
-            const unsigned long long m = __ballot(my_len == (int)q);
-            if (my_len == (int)q) before = (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-            if (lane == 0 && m) T.wave_len_count[tid >> 6][q] = (uint32_t)__popcll(m);
+        // the lanes of this wavefront with the same length as this one: six ballots, one per bit of the length
+        unsigned long long same = ~0ull;
+#pragma unroll
+        for (int bit = 0; bit < 6; bit++) {
+            const unsigned long long m = __ballot((my_len >> bit) & 1);
+            same &= ((my_len >> bit) & 1) ? m : ~m;
         }
+        before = (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+        if (my_len && before == 0) T.wave_len_count[tid >> 6][my_len] = (uint32_t)__popcll(same);  // the first of them
     }
     __syncthreads();
     if (tid < 256) {
@@ -148,7 +154,7 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
                 const uint32_t off = (v >> (kLutBits - len)) - (uint32_t)T.first_code[len];
                 entry = (uint32_t)T.sorted_sym[(T.first_rank[len] + off) & 255u] | (len << 8);
             }
-            T.first[v] = (uint16_t)entry;
+            T.first[first_slot(v)] = (uint16_t)entry;
         }
     }
     __syncthreads();
@@ -158,15 +164,18 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
         constexpr uint32_t kMask = (1u << kLutBits) - 1u;
 #pragma unroll
         for (int it = 0; it < (1 << kLutBits) / THREADS; it++) {
-            const int idx = tid + it * THREADS;
-            const uint32_t v0 = __brev((uint32_t)idx) >> (32 - kLutBits);
-            const uint32_t f0 = T.first[v0];
+            // (neighbouring threads take neighbouring values v0: the reads of `first` below are neighbours, and the
+            // entries, whose indices differ in their upper bits, go to different banks through lut_slot; taking
+            // neighbouring indices instead puts every read of a wavefront on one bank)
+            const uint32_t v0 = (uint32_t)(tid + it * THREADS);
+            const int idx = (int)(__brev(v0) >> (32 - kLutBits));
+            const uint32_t f0 = T.first[first_slot(v0)];
             const uint32_t len0 = f0 >> 8;
             const uint32_t v1 = (v0 << len0) & kMask;
-            const uint32_t f1 = T.first[v1];
+            const uint32_t f1 = T.first[first_slot(v1)];
             const uint32_t len1 = f1 >> 8;
             const uint32_t v2 = (v1 << len1) & kMask;
-            const uint32_t f2 = T.first[v2];
+            const uint32_t f2 = T.first[first_slot(v2)];
             const uint32_t len2 = f2 >> 8;
             const bool ok0 = len0 != 0;
             const bool ok1 = ok0 && len1 != 0 && len0 + len1 <= (uint32_t)kLutBits;
@@ -838,6 +847,9 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     __shared__ __align__(16) DecTables T;
     __shared__ __align__(16) uint8_t symtile[WAVES][kChunkTileBytes];
     __shared__ float s_mu[NCT * 32];
+    // 8-bit variant: column sums and means of the channels (read for every value of the epilogue)
+    __shared__ int s_col_sum[U8 ? NCT * 32 : 1];
+    __shared__ double s_mean_d[U8 ? NCT * 32 : 1];
     // the basis operand [NCT][NJ][2][64], then per wavefront the chunk's payload words and room for a corrupt
     // stream's overrun
     extern __shared__ __align__(16) uint4 basis16[];
@@ -921,6 +933,11 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     }
     if constexpr (!U8) {
         if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
+    } else {
+        if (tid < NCT * 32) {  // (both arrays are padded to NCT * 32 entries)
+            s_col_sum[tid] = p.col_sum[tid];
+            s_mean_d[tid] = p.mean_d[tid];
+        }
     }
     if (!(p.prebuilt ? load_decode_tables<THREADS>(T, my_len, static_cast<const PrebuiltTables*>(p.prebuilt))
                      : build_decode_tables<THREADS>(T, my_len, p.bits))) {
@@ -1051,8 +1068,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 #pragma unroll
                     for (int v = 0; v < 16; v++) {
                         const int r = r0 + v;  // < NCT * 32: the per-channel arrays are padded to that
-                        const int m = acc[v] + (128 - hk) * p.col_sum[r];
-                        const double t = fmin(fmax(rint(fma((double)m, p.factor8, p.mean_d[r])), 0.0), 255.0);
+                        const int m = acc[v] + (128 - hk) * s_col_sum[r];
+                        const double t = fmin(fmax(rint(fma((double)m, p.factor8, s_mean_d[r])), 0.0), 255.0);
                         w[v >> 2] |= (uint32_t)(int)t << (8 * (v & 3));
                     }
                     if (my_px < TP && r0 < C) {
@@ -1337,21 +1354,26 @@ hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size
     const bool al = (C % 4) == 0;
     const size_t lds_basis = (size_t)ncs * ((C + 15) / 16) * 64 * 8;  // the basis operand
     const bool eight = g.n_chunks > 1024 && ncs != 3;
-    const int waves = eight ? 8 : 4;
     p.lds_basis_bytes = (uint32_t)lds_basis;
     p.pay_words = 128u * (uint32_t)bits + 64u;
-    const size_t lds = lds_basis + (size_t)waves * (p.pay_words + kPayOverrun) * 4;
+    auto lds_dyn = [&](int wv) { return lds_basis + (size_t)wv * (p.pay_words + kPayOverrun) * 4; };
+    // four wavefronts per SIMD under the conditions of the fp32 decoder (see launch_decode)
+    const bool sixteen = g.n_chunks > 3072 && ncs <= 2 && C == ncs * 32 && layout == FMTC_NHWC &&
+                         lds_dyn(16) + sizeof(DecTables) + 16 * (size_t)kChunkTileBytes + 64 <= 160 * 1024;
+    const int waves = sixteen ? 16 : (eight ? 8 : 4);
+    const size_t lds = lds_dyn(waves);
     unsigned gx = (g.n_chunks + waves - 1) / waves;
-    const unsigned cap = 256u * (unsigned)(8 / waves);
+    const unsigned cap = 256u * (waves >= 8 ? 1u : 2u);
     if (gx > cap) gx = cap;
     hipError_t el = hipSuccess;
-#define FMTC_DECU(NCT, LAY, AL, WV) \
+#define FMTC_DECU_F(NCT, LAY, AL, WV, FX) \
     do {                                                                                                         \
-        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, true>), \
+        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, true, FX>), \
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);              \
         if (ea != hipSuccess) return ea;                                                                         \
-        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, true>, dim3(gx), dim3(WV * 64), lds, s, p);      \
+        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, true, FX>, dim3(gx), dim3(WV * 64), lds, s, p);  \
     } while (0)
+#define FMTC_DECU(NCT, LAY, AL, WV) FMTC_DECU_F(NCT, LAY, AL, WV, false)
 #define FMTC_DECU_N(LAY, AL)                                                                                     \
     do {                                                                                                         \
         if (ncs == 1) { if (eight) FMTC_DECU(1, LAY, AL, 8); else FMTC_DECU(1, LAY, AL, 4); }                    \
@@ -1359,10 +1381,12 @@ hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size
         else if (ncs == 3) FMTC_DECU(3, LAY, AL, 4);                                                             \
         else { if (eight) FMTC_DECU(4, LAY, AL, 8); else FMTC_DECU(4, LAY, AL, 4); }                             \
     } while (0)
-    if (layout == FMTC_NHWC) { if (al) FMTC_DECU_N(FMTC_NHWC, true); else FMTC_DECU_N(FMTC_NHWC, false); }
+    if (sixteen) { if (ncs == 1) FMTC_DECU_F(1, FMTC_NHWC, true, 16, true); else FMTC_DECU_F(2, FMTC_NHWC, true, 16, true); }
+    else if (layout == FMTC_NHWC) { if (al) FMTC_DECU_N(FMTC_NHWC, true); else FMTC_DECU_N(FMTC_NHWC, false); }
     else                     { if (al) FMTC_DECU_N(FMTC_NCHW, true); else FMTC_DECU_N(FMTC_NCHW, false); }
 #undef FMTC_DECU_N
 #undef FMTC_DECU
+#undef FMTC_DECU_F
     return el;
 }
 
