@@ -508,6 +508,18 @@ void k_project_quantize_rows(RowParams p) {
         const int64_t px = tile * 32 + l32;
         const bool px_ok = px < p.P;
         if constexpr (LAYOUT == FMTC_NHWC && VEC) {
+            if (C == NCT * 32 && tile * 32 + 32 <= p.P) {  // wavefront-uniform: nothing to mask, nothing to fill
+                const float4* row = reinterpret_cast<const float4*>(p.x + px * (NCT * 32)) + 2 * half;
+#pragma unroll
+                for (int j = 0; j < NJ; j++)
+#pragma unroll
+                    for (int q = 0; q < 2; q++) {
+                        const float4 v = row[4 * j + q];
+                        xr[8 * j + 4 * q] = v.x; xr[8 * j + 4 * q + 1] = v.y;
+                        xr[8 * j + 4 * q + 2] = v.z; xr[8 * j + 4 * q + 3] = v.w;
+                    }
+                return;
+            }
             const float4* row = reinterpret_cast<const float4*>(p.x + (px_ok ? px : 0) * C) + 2 * half;
 #pragma unroll
             for (int j = 0; j < NJ; j++)
@@ -567,8 +579,24 @@ void k_project_quantize_rows(RowParams p) {
     const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1), zero_f = (float)zero_sym;
     const float inv_delta = p.inv_delta;
     const float inv_delta_lo = p.inv_delta * (1.f / 2048.f);
+    // Rounding, offset and conversion in one addition: for |t| < 2^22, t + (1.5 * 2^23 + 2^(b-1)) rounds (half to
+    // even, the unit in the last place there being 1) to the number whose bit pattern is kMagicBits + 2^(b-1) +
+    // rne(t); clamped between the patterns of symbol 0 and symbol 2^b - 1 its lowest byte is the symbol, and
+    // subtracting the constant again gives rne(t) for the distance to the rounding boundary.  Larger |t| clamp the
+    // same way (their distance is then meaningless and large: such a value is decided exactly, like any flagged one).
+    constexpr uint32_t kMagicBits = 0x4B400000u;  // 1.5 * 2^23
+    const float magic = 12582912.f + (float)zero_sym;
+    const float magic_lo = 12582912.f, magic_hi = 12582912.f + (float)(2 * zero_sym - 1);
     uint32_t* wh0 = whist + wave * K * kHistLanes;          // this wavefront's histogram, copy 0
     uint32_t* wh = wh0 + (lane & (kHistLanes - 1));         // bin s of this lane's copy: wh[s * kHistLanes]
+    // count of the symbol in the clamped pattern `ub` (kMagicBits + symbol): the LDS address is one shift-and-add
+    // from the pattern itself (the constant is folded into the base; the arithmetic wraps)
+    static_assert(kHistLanes * sizeof(uint32_t) == 64, "shift of the histogram address");
+    typedef __attribute__((address_space(3))) uint32_t lds_u32;
+    const uint32_t wh_magic = (uint32_t)(uintptr_t)(lds_u32*)wh - (kMagicBits << 6);
+    auto hist_add = [&](uint32_t ub) {
+        __hip_atomic_fetch_add((lds_u32*)(uintptr_t)((ub << 6) + wh_magic), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
     uint32_t* fix_list = s_fix_list[wave];
     uint32_t* fix_tile = s_fix_tile[wave];
     uint32_t* fix_count = &s_fix_count[wave];
@@ -660,7 +688,8 @@ void k_project_quantize_rows(RowParams p) {
                         if (clamp) v = __builtin_amdgcn_fmed3f(v, -60000.f, 60000.f);
                         const _Float16 vh = (_Float16)v;
                         xh[j][4 * q + i] = vh;
-                        xl[j][4 * q + i] = (_Float16)((v - (float)vh) * 2048.f);
+                        // 2^11 (v - vh), exact (one multiply-add that takes the f16 operand as it is)
+                        xl[j][4 * q + i] = (_Float16)__builtin_fmaf((float)vh, -2048.f, v * 2048.f);
                     }
                 }
         };
@@ -678,16 +707,20 @@ void k_project_quantize_rows(RowParams p) {
         if (WPS < 3 && next_tile < p.n_tiles) load_pixels(next_tile);
 
         auto project_tile = [&](int kt, floatx16& am, floatx16& ac) {
+            if (kt >= p.active_tiles) {  // all rows of the tile are zero (truncated basis): so are its coefficients
 #pragma unroll
-            for (int r = 0; r < 16; r++) { am[r] = 0.f; ac[r] = 0.f; }
-            if (kt >= p.active_tiles) return;  // all rows of the tile are zero (truncated basis): so are its coefficients
+                for (int r = 0; r < 16; r++) { am[r] = 0.f; ac[r] = 0.f; }
+                return;
+            }
+            // (the first step starts from the instruction's constant zero: no registers to clear)
+            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < NJ; j++) {
                 const uint4 th4 = basis16[((kt * NJ + j) * 2) * 64 + lane];
                 const uint4 tl4 = basis16[((kt * NJ + j) * 2 + 1) * 64 + lane];
                 const halfx8 th = __builtin_bit_cast(halfx8, th4), tl = __builtin_bit_cast(halfx8, tl4);
-                am = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xh[j], am, 0, 0, 0);
-                ac = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xl[j], ac, 0, 0, 0);
+                am = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xh[j], j ? am : zero, 0, 0, 0);
+                ac = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xl[j], j ? ac : zero, 0, 0, 0);
                 ac = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, xh[j], ac, 0, 0, 0);
             }
         };
@@ -777,16 +810,20 @@ void k_project_quantize_rows(RowParams p) {
                 uint32_t word[4] = {0u, 0u, 0u, 0u};
                 float maxd = 0.f;
                 const bool k_ok = kt * 32 + 16 * half < C;  // false only in the upper half of a padded last tile
+                uint32_t ub[16];
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const float t = __builtin_fmaf(ac[r], inv_delta_lo, am[r] * inv_delta);
-                    const float q = __builtin_rintf(t);  // round half to even
-                    maxd = fmaxf(maxd, fabsf(t - q));
-                    const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
-                    word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
+                    const float u = t + magic;  // round half to even
+                    maxd = fmaxf(maxd, fabsf(t - (u - magic)));
+                    ub[r] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_fmed3f(u, magic_lo, magic_hi));  // clamped
                     if constexpr (!FUSED)
-                        if (k_ok) atomicAdd(&wh[(uint32_t)qc * kHistLanes], 1u);
+                        if (k_ok) hist_add(ub[r]);
                 }
+#pragma unroll
+                for (int g = 0; g < 4; g++)
+                    word[g] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(ub[4 * g + 3], ub[4 * g + 2], 0x0c0c0400u),
+                                                    __builtin_amdgcn_perm(ub[4 * g + 1], ub[4 * g], 0x0c0c0400u), 0x05040100u);
                 if constexpr (FUSED) {
                     *reinterpret_cast<uint4*>(sym_tiles + wave * 4096 + ((px - chunk_px0) * C + kt * 32 + 16 * half)) =
                         make_uint4(word[0], word[1], word[2], word[3]);
@@ -806,16 +843,19 @@ void k_project_quantize_rows(RowParams p) {
 #pragma unroll
                 for (int r = 0; r < 16; r++) { nm[r] = 0.f; nc[r] = 0.f; }
                 uint32_t word[4] = {0u, 0u, 0u, 0u};
+                uint32_t ub[16];
                 float maxd = 0.f;
                 const bool k_ok = kt * 32 + 16 * half < C;  // false only in the upper half of a padded last tile
                 auto quantize_value = [&](int r) {
                     const float t = __builtin_fmaf(ac[r], inv_delta_lo, am[r] * inv_delta);
-                    const float q = __builtin_rintf(t);  // round half to even
-                    maxd = fmaxf(maxd, fabsf(t - q));
-                    const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
-                    word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
+                    const float u = t + magic;  // round half to even
+                    maxd = fmaxf(maxd, fabsf(t - (u - magic)));
+                    ub[r] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_fmed3f(u, magic_lo, magic_hi));  // clamped
                     if constexpr (!FUSED)
-                        if (k_ok) atomicAdd(&wh[(uint32_t)qc * kHistLanes], 1u);
+                        if (k_ok) hist_add(ub[r]);
+                    if ((r & 3) == 3)
+                        word[r >> 2] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(ub[r], ub[r - 1], 0x0c0c0400u),
+                                                             __builtin_amdgcn_perm(ub[r - 2], ub[r - 3], 0x0c0c0400u), 0x05040100u);
                 };
                 if (kt + 1 < NCT) {
 #pragma unroll
