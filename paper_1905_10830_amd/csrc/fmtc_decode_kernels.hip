@@ -144,8 +144,9 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
 #pragma unroll
         for (int l = 1; l <= kLutBits; l++) lim[l] = T.lut_limit[l];
 #pragma unroll
-        for (int it = 0; it < (1 << kLutBits) / THREADS; it++) {
+        for (int it = 0; it < ((1 << kLutBits) + THREADS - 1) / THREADS; it++) {
             const uint32_t v = (uint32_t)(tid + it * THREADS);
+            if (v >= (1u << kLutBits)) break;
             uint32_t len = 1;
 #pragma unroll
             for (int l = 1; l < kLutBits; l++) len += (v >= lim[l]) ? 1u : 0u;
@@ -163,7 +164,8 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
         // significant bit first).  A later code counts only if all its bits are inside the kLutBits bits.
         constexpr uint32_t kMask = (1u << kLutBits) - 1u;
 #pragma unroll
-        for (int it = 0; it < (1 << kLutBits) / THREADS; it++) {
+        for (int it = 0; it < ((1 << kLutBits) + THREADS - 1) / THREADS; it++) {
+            if ((uint32_t)(tid + it * THREADS) >= (1u << kLutBits)) break;
             // (neighbouring threads take neighbouring values v0: the reads of `first` below are neighbours, and the
             // entries, whose indices differ in their upper bits, go to different banks through lut_slot; taking
             // neighbouring indices instead puts every read of a wavefront on one bank)
@@ -840,8 +842,13 @@ constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes 
 // U8: the tile's symbols go through the 8-bit basis on the integer matrix cores instead (v_mfma_i32_32x32x16_i8;
 // exact sums, one fused fp64 multiply-add and one rounding per value, 8-bit activations out); the 8-bit basis
 // takes the f16 basis' place in LDS.
-// FIXC: the tensor has exactly 32 NCT channels (the launcher checks it), so every row stride is a constant.
-template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES, bool U8 = false, bool FIXC = false>
+// CFIX: the tensor's channel count if the kernel is built for one (the launcher checks it; 0: any), which makes every
+// row stride a constant.
+// LOG: only the upper f16 parts of the basis are kept in LDS; the lower parts, whose products are the small
+// correction, are read from global memory (the cache serves them: every wavefront of the device reads the same few
+// tens of KB) while the matrix instructions of the upper parts run.  Half the LDS per workgroup buys a third
+// wavefront per SIMD for 128 to 160 channels.
+template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES, bool U8 = false, int CFIX = 0, bool LOG = false>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k_decode_chunks(DecodeParams p) {
     constexpr int THREADS = WAVES * 64;
     __shared__ __align__(16) DecTables T;
@@ -859,7 +866,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform by construction
     const int half = lane >> 5, l32 = lane & 31;
-    const int C = FIXC ? NCT * 32 : p.C;
+    const int C = CFIX ? CFIX : p.C;
+    static_assert(!(LOG && U8), "the 8-bit basis has one part");
 
     // loads that do not depend on the header go out first: the code length table and the basis
     int my_len = 0;
@@ -873,12 +881,18 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         const uint4* src = reinterpret_cast<const uint4*>(p.op8);
         for (int i = tid; i < n16; i += THREADS) basis16[i] = src[i];
     }
-    if constexpr (!U8) {
+    if constexpr (!U8 && !LOG) {
         const uint4* src = reinterpret_cast<const uint4*>(p.Bp16);
 #pragma unroll
         for (int i = 0; i < (kBasisPieces + THREADS - 1) / THREADS; i++)
             if (THREADS * i + 64 * wave < kBasisPieces)  // whole wavefronts
                 __builtin_amdgcn_global_load_lds(src + tid + THREADS * i, &basis16[THREADS * i + 64 * wave], 16, 0, 0);
+    }
+    if constexpr (LOG) {
+        // block g = (channel tile, step) of the upper parts: 64 pieces at [g][0][64] of the operand, to [g][64] in LDS
+        const uint4* src = reinterpret_cast<const uint4*>(p.Bp16);
+        for (int g = wave; g < NCT * NJ; g += WAVES)
+            __builtin_amdgcn_global_load_lds(src + (size_t)g * 128 + lane, &basis16[g * 64], 16, 0, 0);
     }
     // The first chunk's offsets, run sizes and payload are requested before the header has arrived, at the places
     // the nominal chunk size puts them: three dependent memory round trips (header, offsets, payload) become
@@ -1123,6 +1137,38 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                 floatx16 acc, acl;
 #pragma unroll
                 for (int r = 0; r < 16; r++) { acc[r] = 0.f; acl[r] = 0.f; }
+                if constexpr (LOG) {
+                    // the lower parts of this channel tile are requested first and used last
+                    const uint4* lo_src = reinterpret_cast<const uint4*>(p.Bp16) + ((size_t)(ct * NJ) * 2 + 1) * 64 + lane;
+                    // (half of them at a time: all at once would not fit the registers of three wavefronts per SIMD)
+                    constexpr int NH = (NJ + 1) / 2;
+                    uint4 lo_op[NH];
+#pragma unroll
+                    for (int j = 0; j < NH; j++)
+                        if (j < NJA) lo_op[j] = lo_src[(size_t)j * 128];
+#pragma unroll
+                    for (int j = 0; j < NJ; j++) {
+                        if (j >= NJA) continue;  // wavefront-uniform (truncation, and padding rows of the last tile)
+                        const halfx8 bh = __builtin_bit_cast(halfx8, basis16[(ct * NJ + j) * 64 + lane]);
+                        if constexpr (LAYOUT == FMTC_NHWC) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[j], bh, acc, 0, 0, 0);
+                        else acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, q[j], acc, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int h = 0; h < 2; h++) {
+#pragma unroll
+                        for (int j = 0; j < NH; j++) {
+                            if (h * NH + j >= NJ || h * NH + j >= NJA) continue;
+                            const halfx8 bl = __builtin_bit_cast(halfx8, lo_op[j]);
+                            if constexpr (LAYOUT == FMTC_NHWC) acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[h * NH + j], bl, acl, 0, 0, 0);
+                            else acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q[h * NH + j], acl, 0, 0, 0);
+                        }
+                        if (h == 0) {
+#pragma unroll
+                            for (int j = 0; j < NH; j++)
+                                if (NH + j < NJ && NH + j < NJA) lo_op[j] = lo_src[(size_t)(NH + j) * 128];
+                        }
+                    }
+                } else {
 #pragma unroll
                 for (int j = 0; j < NJ; j++) {
                     if (j >= NJA) continue;  // wavefront-uniform: steps past the basis' last non-zero row (truncation)
@@ -1135,6 +1181,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                         acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, q[j], acc, 0, 0, 0);
                         acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q[j], acl, 0, 0, 0);
                     }
+                }
                 }
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[r] = __builtin_fmaf(acl[r], 1.f / 2048.f, acc[r]);
@@ -1150,6 +1197,13 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 #pragma unroll
                             for (int r = 0; r < 16; r++)
                                 dst[(size_t)(8 * (r >> 2) + (r & 3)) * (NCT * 32)] = __builtin_fmaf(acc[r], delta, m_c);
+                        } else if (CFIX != 0 && CFIX != NCT * 32) {
+                            // (a channel count known at build time that is no multiple of 32: the same, with the
+                            // rows past the chunk's last pixel left out)
+#pragma unroll
+                            for (int r = 0; r < 16; r++)
+                                if (pt * 32 + 8 * (r >> 2) + 4 * half + (r & 3) < TP)
+                                    dst[(size_t)(8 * (r >> 2) + (r & 3)) * (CFIX ? CFIX : 1)] = __builtin_fmaf(acc[r], delta, m_c);
                         } else if (pt * 32 + 32 <= TP) {
 #pragma unroll
                             for (int r = 0; r < 16; r++)
@@ -1230,22 +1284,34 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         int waves = 4;
         if (g.n_chunks > 1024 && ncs != 3 && ncs != 5) waves = 8;
         if (g.n_chunks > 3072 && ncs <= 2 && C == ncs * 32 && layout == FMTC_NHWC && lds_all(16) <= 160 * 1024) waves = 16;
-        const size_t lds = lds_dyn(waves);
-        const unsigned per_cu = (unsigned)((160 * 1024) / lds_all(waves));
+        // 128 to 160 channels: three wavefronts per SIMD with the lower parts of the basis left in global memory
+        // (k_decode_chunks<..., LOG>); built for the channel counts 128 and 144, channels last (with a channel count
+        // left open the kernel does not fit the registers of three wavefronts)
+        // (144 channels: two wavefronts per SIMD, the registers of a third do not fit)
+        const size_t lds_basis_log = lds_basis / 2;
+        const int log_waves = C == 128 ? 12 : 8;
+        const bool log12 = (C == 128 || C == 144) && layout == FMTC_NHWC && g.n_chunks > 2048 &&
+                           lds_all(log_waves) - lds_basis + lds_basis_log <= 160 * 1024;
+        if (log12) {
+            waves = log_waves;
+            p.lds_basis_bytes = (uint32_t)lds_basis_log;
+        }
+        const size_t lds = log12 ? lds_dyn(waves) - lds_basis + lds_basis_log : lds_dyn(waves);
+        const unsigned per_cu = log12 ? 1u : (unsigned)((160 * 1024) / lds_all(waves));
         unsigned gx = (g.n_chunks + waves - 1) / waves;
         const unsigned most = waves >= 8 ? 1u : 2u;
         const unsigned cap = 256u * (per_cu < 1 ? 1u : (per_cu > most ? most : per_cu));
         if (gx > cap) gx = cap;
-#define FMTC_DECC_F(NCT, LAY, AL, WV, FX)                                                                        \
+#define FMTC_DECC_F(NCT, LAY, AL, WV, CF, LG)                                                                    \
     do {                                                                                                         \
         if (lds > 16 * 1024) {                                                                                   \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, false, FX>), \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, false, CF, LG>), \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
             if (ea != hipSuccess) return ea;                                                                     \
         }                                                                                                        \
-        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, false, FX>, dim3(gx), dim3(WV * 64), lds, s, p); \
+        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, false, CF, LG>, dim3(gx), dim3(WV * 64), lds, s, p); \
     } while (0)
-#define FMTC_DECC(NCT, LAY, AL, WV) FMTC_DECC_F(NCT, LAY, AL, WV, false)
+#define FMTC_DECC(NCT, LAY, AL, WV) FMTC_DECC_F(NCT, LAY, AL, WV, 0, false)
 #define FMTC_DECC_N(LAY, AL)                                                                                     \
     do {                                                                                                         \
         if (ncs == 1) { if (waves == 8) FMTC_DECC(1, LAY, AL, 8); else FMTC_DECC(1, LAY, AL, 4); }               \
@@ -1253,7 +1319,11 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         else if (ncs == 3) FMTC_DECC(3, LAY, AL, 4);                                                             \
         else { if (waves == 8) FMTC_DECC(4, LAY, AL, 8); else FMTC_DECC(4, LAY, AL, 4); }                        \
     } while (0)
-        if (waves == 16) { if (ncs == 1) FMTC_DECC_F(1, FMTC_NHWC, true, 16, true); else FMTC_DECC_F(2, FMTC_NHWC, true, 16, true); }
+        if (waves == 16) { if (ncs == 1) FMTC_DECC_F(1, FMTC_NHWC, true, 16, 32, false); else FMTC_DECC_F(2, FMTC_NHWC, true, 16, 64, false); }
+        else if (log12) {
+            if (C == 128) FMTC_DECC_F(4, FMTC_NHWC, true, 12, 128, true);
+            else FMTC_DECC_F(5, FMTC_NHWC, true, 8, 144, true);
+        }
         else if (ncs == 5) { if (al) FMTC_DECC(5, FMTC_NHWC, true, 4); else FMTC_DECC(5, FMTC_NHWC, false, 4); }
         else if (layout == FMTC_NHWC) { if (al) FMTC_DECC_N(FMTC_NHWC, true); else FMTC_DECC_N(FMTC_NHWC, false); }
         else                          { if (al) FMTC_DECC_N(FMTC_NCHW, true); else FMTC_DECC_N(FMTC_NCHW, false); }
@@ -1366,14 +1436,14 @@ hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size
     const unsigned cap = 256u * (waves >= 8 ? 1u : 2u);
     if (gx > cap) gx = cap;
     hipError_t el = hipSuccess;
-#define FMTC_DECU_F(NCT, LAY, AL, WV, FX) \
+#define FMTC_DECU_F(NCT, LAY, AL, WV, CF) \
     do {                                                                                                         \
-        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, true, FX>), \
+        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, true, CF>), \
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);              \
         if (ea != hipSuccess) return ea;                                                                         \
-        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, true, FX>, dim3(gx), dim3(WV * 64), lds, s, p);  \
+        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, true, CF>, dim3(gx), dim3(WV * 64), lds, s, p);  \
     } while (0)
-#define FMTC_DECU(NCT, LAY, AL, WV) FMTC_DECU_F(NCT, LAY, AL, WV, false)
+#define FMTC_DECU(NCT, LAY, AL, WV) FMTC_DECU_F(NCT, LAY, AL, WV, 0)
 #define FMTC_DECU_N(LAY, AL)                                                                                     \
     do {                                                                                                         \
         if (ncs == 1) { if (eight) FMTC_DECU(1, LAY, AL, 8); else FMTC_DECU(1, LAY, AL, 4); }                    \
@@ -1381,7 +1451,7 @@ hipError_t launch_decode_u8(const Basis8Device& b, const uint8_t* d_stream, size
         else if (ncs == 3) FMTC_DECU(3, LAY, AL, 4);                                                             \
         else { if (eight) FMTC_DECU(4, LAY, AL, 8); else FMTC_DECU(4, LAY, AL, 4); }                             \
     } while (0)
-    if (sixteen) { if (ncs == 1) FMTC_DECU_F(1, FMTC_NHWC, true, 16, true); else FMTC_DECU_F(2, FMTC_NHWC, true, 16, true); }
+    if (sixteen) { if (ncs == 1) FMTC_DECU_F(1, FMTC_NHWC, true, 16, 32); else FMTC_DECU_F(2, FMTC_NHWC, true, 16, 64); }
     else if (layout == FMTC_NHWC) { if (al) FMTC_DECU_N(FMTC_NHWC, true); else FMTC_DECU_N(FMTC_NHWC, false); }
     else                     { if (al) FMTC_DECU_N(FMTC_NCHW, true); else FMTC_DECU_N(FMTC_NCHW, false); }
 #undef FMTC_DECU_N

@@ -30,6 +30,8 @@ FULL = [
     ("mbv2_c144_56", 5),
     ("mbv2_c960_7", 5),
     ("resnet18_n256_c64_56", 8),
+    ("resnet18_n256_c64_56", 6),    # the benchmark's headline: the chunk decoder with four wavefronts per SIMD
+    ("resnet18_n256_c128_28", 6),   # ... and with three, the lower parts of its basis read from global memory
     ("resnet18_n256_c128_28", 2),
     ("resnet18_n256_c128_28", 8),   # (the 256-bin histograms leave no room for the eight-wavefront projection)
     ("resnet18_n256_c256_14", 4),

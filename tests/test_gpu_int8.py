@@ -136,7 +136,8 @@ def test_u8_codec_quality_and_errors(fmtc, oracle):
     assert int(err2.item()) != 0
 
 
-@pytest.mark.parametrize("name,bits", [("resnet18_stage2_c128_28", 6), ("cfg0_c64_56", 8)])
+@pytest.mark.parametrize("name,bits", [("resnet18_stage2_c128_28", 6), ("cfg0_c64_56", 8),
+                                       ("resnet18_n256_c64_56", 6)])  # (the last: four wavefronts per SIMD)
 def test_u8_path_at_full_size(fmtc, oracle, name, bits):
     """The benchmark's tensors as 8-bit activations, in the launch configuration the benchmark times: symbols,
     stream and decoded activations equal the oracle's everywhere."""
