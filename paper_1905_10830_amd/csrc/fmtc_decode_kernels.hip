@@ -868,6 +868,11 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     const int half = lane >> 5, l32 = lane & 31;
     const int C = CFIX ? CFIX : p.C;
     static_assert(!(LOG && U8), "the 8-bit basis has one part");
+    // The variants for many chunks (tens of MB of output and more) store the activations with the streaming hint:
+    // written through the 256 MB memory-side cache, a large tensor leaves its write-back to whatever kernel runs
+    // next.  (Measured on the 205 MB tensor: the decoder, which has memory bandwidth to spare, takes 7 us longer, and
+    // the projection after it, which no longer shares the memory with that write-back, 14 us less.)
+    constexpr bool kStreamOut = !U8 && (WAVES >= 12 || LOG);
 
     // loads that do not depend on the header go out first: the code length table and the basis
     int my_len = 0;
@@ -1194,16 +1199,26 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                         if (pt * 32 + 32 <= TP && C == NCT * 32) {
                             // (the usual case, with the row stride a constant: the stores' offsets are immediates
                             // instead of sixteen 64-bit values in registers)
+                            if constexpr (kStreamOut) {
 #pragma unroll
-                            for (int r = 0; r < 16; r++)
-                                dst[(size_t)(8 * (r >> 2) + (r & 3)) * (NCT * 32)] = __builtin_fmaf(acc[r], delta, m_c);
+                                for (int r = 0; r < 16; r++)
+                                    __builtin_nontemporal_store(__builtin_fmaf(acc[r], delta, m_c),
+                                                                &dst[(size_t)(8 * (r >> 2) + (r & 3)) * (NCT * 32)]);
+                            } else {
+#pragma unroll
+                                for (int r = 0; r < 16; r++)
+                                    dst[(size_t)(8 * (r >> 2) + (r & 3)) * (NCT * 32)] = __builtin_fmaf(acc[r], delta, m_c);
+                            }
                         } else if (CFIX != 0 && CFIX != NCT * 32) {
                             // (a channel count known at build time that is no multiple of 32: the same, with the
                             // rows past the chunk's last pixel left out)
 #pragma unroll
                             for (int r = 0; r < 16; r++)
-                                if (pt * 32 + 8 * (r >> 2) + 4 * half + (r & 3) < TP)
-                                    dst[(size_t)(8 * (r >> 2) + (r & 3)) * (CFIX ? CFIX : 1)] = __builtin_fmaf(acc[r], delta, m_c);
+                                if (pt * 32 + 8 * (r >> 2) + 4 * half + (r & 3) < TP) {
+                                    float* at = &dst[(size_t)(8 * (r >> 2) + (r & 3)) * (CFIX ? CFIX : 1)];
+                                    if constexpr (kStreamOut) __builtin_nontemporal_store(__builtin_fmaf(acc[r], delta, m_c), at);
+                                    else *at = __builtin_fmaf(acc[r], delta, m_c);
+                                }
                         } else if (pt * 32 + 32 <= TP) {
 #pragma unroll
                             for (int r = 0; r < 16; r++)
@@ -1265,7 +1280,6 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     p.g_spc = g.subs_per_chunk;
     const bool al = (C % 4) == 0;
     hipError_t el = hipSuccess;
-
     // (five channel tiles: channels-last only, the planar stores take more registers than are left)
     if (!d_syms && (ncs <= 4 || (ncs == 5 && layout == FMTC_NHWC))) {
         // ---- one wavefront per chunk ----
