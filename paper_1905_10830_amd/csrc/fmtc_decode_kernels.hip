@@ -197,8 +197,15 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
         const bool have_long = max_len > (uint32_t)kLutBits && lim < (1u << kLutBits);
         const uint32_t base = have_long ? lim << (32 - kLutBits) : 0xffffffffu;
         const uint64_t span = (1ull << 32) - base;  // values at or above base
+        // the smallest shift that brings the span down to the table's 2^kLut2Bits entries (at most 32 - kLut2Bits),
+        // in closed form: a loop over the candidates was 1.6 us of every workgroup's start
         uint32_t shift = 0;
-        while (shift < 32u - kLut2Bits && (span >> shift) > (1ull << kLut2Bits)) shift++;
+        if (span > (1ull << kLut2Bits)) {
+            const uint32_t m = 63u - (uint32_t)__clzll((long long)span);  // 2^m <= span < 2^(m+1), m > kLut2Bits - 1
+            shift = m - kLut2Bits;
+            if ((span >> shift) > (1ull << kLut2Bits)) shift++;
+            if (shift > 32u - kLut2Bits) shift = 32u - kLut2Bits;
+        }
         if (tid == 0) {
             T.long_base = base;
             T.long_shift = shift;

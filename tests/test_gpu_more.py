@@ -236,3 +236,32 @@ def test_encoders_on_two_streams_share_the_device(fmtc):
     xhat, err = fmtc.decode(basis, outs[-1][0], x.shape, bits)
     torch.cuda.synchronize()
     assert int(err.item()) == 0
+
+
+def test_small_tensor_encoders_on_two_streams(fmtc):
+    """The same for a tensor that takes the one-kernel packer (at most 1024 chunk groups, workgroup g packs group g
+    and waits for the groups before it through the look-back words): calls in flight on two HIP streams give the
+    one-stream bytes.  What the packer relies on there: the workgroups of a launch start in index order, so the
+    group a workgroup waits for belongs to a workgroup that was dispatched before it; if that ever failed to hold,
+    a wait would run into its limit and the stream would come out marked invalid, which this test would see."""
+    torch.manual_seed(6)
+    C, bits = 128, 6
+    calib = torch.randn(8, 28, 28, C, device="cuda").relu()
+    x = (torch.randn(64, 28, 28, C, device="cuda") * torch.linspace(2.0, 0.05, C, device="cuda")).relu()
+    basis = fmtc.fit_basis(calib)
+    P = 64 * 28 * 28
+    assert (P * C // 4096 + 3) // 4 <= 1024
+    ref, ref_n = fmtc.encode(basis, x, bits)
+    torch.cuda.synchronize()
+    n = int(ref_n.item())
+    assert fmtc.stream_info(ref[:64].cpu().numpy())["stream_bytes"] == n
+    side = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for rep in range(4):
+        for st in side:
+            with torch.cuda.stream(st):
+                outs.append(fmtc.encode(basis, x, bits))
+    torch.cuda.synchronize()
+    for stream, nbytes in outs:
+        assert int(nbytes.item()) == n
+        assert torch.equal(stream[:n], ref[:n])
