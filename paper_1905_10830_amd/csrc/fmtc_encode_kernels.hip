@@ -968,6 +968,285 @@ void k_project_quantize_rows(RowParams p) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// 128 to 160 channels, channels last, a multiple of 16 of them: the same projection with the loops the other way
+// round.  k_project_quantize_rows holds a whole pixel tile twice (the fp32 values of the next tile on their way in, the
+// two f16 parts of this one) and one or two pairs of accumulators: 350 to 450 registers at four and five coefficient
+// tiles, one wavefront per SIMD -- where a vector instruction issues every 8 clocks instead of every 4 and nothing
+// covers a wait.  Here the channel steps are the outer loop: a step's eight channels per lane are converted when
+// their turn comes and go into the accumulators of ALL coefficient tiles at once (32 NCT accumulator registers), and
+// the pixels stream in through two small buffers of two steps each, across tile boundaries, so that between one and
+// two buffers (4 to 8 KB per wavefront) are in flight at any time.  130 registers less at four tiles: two wavefronts
+// per SIMD (eight on one copy of the basis) without spills.  A pixel too large for f16 needs no clamp here: what its
+// infinities make of the matrix product stays in its own column of outputs, all of which are decided exactly, and
+// the clamp of the quantizer keeps the histogram index in range whatever the value.
+// ---------------------------------------------------------------------------
+// NJA: the tensor's channel count / 16 (the launcher checks it), 2 NCT - 1 or 2 NCT.
+template <int NCT, int WAVES, int NJA>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4)))
+void k_project_quantize_stream(RowParams p) {
+    constexpr int THREADS = WAVES * 64;
+    constexpr int NJ = NCT * 2;        // steps of 16 channels in the basis operand (of which the first NJA hold channels)
+    static_assert(NJA == NJ || NJA == NJ - 1, "channel count");
+    constexpr int NP = (NJ + 1) / 2;   // pairs of steps: the unit of the pixel buffers
+    extern __shared__ __align__(16) uint4 basis16[];  // [NCT][NJ][2][64], then the histograms
+    __shared__ __align__(16) float s_mu[NCT * 32];
+    __shared__ uint32_t s_fix_list[WAVES][kFixList];
+    __shared__ uint32_t s_fix_tile[WAVES][kFixList];
+    __shared__ uint32_t s_fix_count[WAVES];
+    __shared__ uint32_t s_red[WAVES * 256];
+    const int K = 1 << p.bits;
+    uint32_t* whist = reinterpret_cast<uint32_t*>(basis16 + NCT * NJ * 2 * 64);  // [WAVES][K * kHistLanes]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l32 = lane & 31;
+    constexpr int C = 16 * NJA;
+    typedef float f4_t __attribute__((ext_vector_type(4)));
+
+    // this lane's channels [16 j + 8 half, + 8) of its pixel, steps 2 pr and 2 pr + 1, of pixel tile `tile`
+    auto load_pair = [&](int64_t tile, int pr, f4_t (&buf)[2][2]) __attribute__((always_inline)) {
+        int64_t px = tile * 32 + l32;
+        px = px < p.P ? px : p.P - 1;  // rows past the tensor repeat its last pixel; never stored or counted
+        const f4_t* row = reinterpret_cast<const f4_t*>(p.x + px * C) + 2 * half;
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const int j = 2 * pr + u;
+            if (j < NJ && j < NJA) {  // wavefront-uniform
+                buf[u][0] = row[4 * j];
+                buf[u][1] = row[4 * j + 1];
+            }
+        }
+    };
+    const int64_t stride = (int64_t)gridDim.x * WAVES;
+    int64_t tile = (int64_t)blockIdx.x * WAVES + wave;
+    f4_t bufA[2][2], bufB[2][2];
+    if (tile < p.n_tiles) {
+        load_pair(tile, 0, bufA);
+        if (NP > 1) load_pair(tile, 1, bufB);
+    }
+    zero_coder_scratch(p.ctrl, p.lookback, p.n_groups);
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(p.basis16);
+#pragma unroll
+        for (int i = 0; i < (NCT * NCT * 256 + THREADS - 1) / THREADS; i++)
+            if (THREADS * i + 64 * wave < NCT * NCT * 256)  // whole wavefronts
+                __builtin_amdgcn_global_load_lds(src + tid + THREADS * i, &basis16[THREADS * i + 64 * wave], 16, 0, 0);
+    }
+    if (tid < NCT * 32) s_mu[tid] = p.mu[tid];
+    for (int i = tid; i < WAVES * K * kHistLanes; i += THREADS) whist[i] = 0u;
+
+    const int zero_sym = 1 << (p.bits - 1);
+    const float lo = (float)(-zero_sym), hi = (float)(zero_sym - 1);
+    const float inv_delta = p.inv_delta;
+    const float inv_delta_lo = p.inv_delta * (1.f / 2048.f);
+    constexpr uint32_t kMagicBits = 0x4B400000u;  // 1.5 * 2^23: see k_project_quantize_rows
+    const float magic = 12582912.f + (float)zero_sym;
+    const float magic_lo = 12582912.f, magic_hi = 12582912.f + (float)(2 * zero_sym - 1);
+    uint32_t* wh0 = whist + wave * K * kHistLanes;
+    uint32_t* wh = wh0 + (lane & (kHistLanes - 1));
+    static_assert(kHistLanes * sizeof(uint32_t) == 64, "shift of the histogram address");
+    typedef __attribute__((address_space(3))) uint32_t lds_u32;
+    const uint32_t wh_magic = (uint32_t)(uintptr_t)(lds_u32*)wh - (kMagicBits << 6);
+    auto hist_add = [&](uint32_t ub) {
+        __hip_atomic_fetch_add((lds_u32*)(uintptr_t)((ub << 6) + wh_magic), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    uint32_t* fix_list = s_fix_list[wave];
+    uint32_t* fix_tile = s_fix_tile[wave];
+    uint32_t* fix_count = &s_fix_count[wave];
+    if (lane == 0) *fix_count = 0u;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's part of the basis has landed in LDS
+    __syncthreads();
+
+    // exact decision of the listed values (as in k_project_quantize_rows)
+    auto resolve_list = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        const uint32_t n = (uint32_t)__builtin_amdgcn_readfirstlane((int)*fix_count);
+        for (uint32_t base = 0; base < n; base += 4) {
+            const uint32_t idx = base + (uint32_t)(lane >> 4);
+            const bool active = idx < n;
+            const uint32_t e = active ? fix_list[idx] : 0u;
+            const int k = (int)(e & 255u), pl = (int)((e >> 8) & 31u);
+            const uint32_t old = e >> 13;
+            const int64_t qpx = (int64_t)fix_tile[idx < (uint32_t)kFixList ? idx : 0] * 32 + pl;
+            double part = 0.0;
+            if (active)
+#pragma unroll 5
+                for (int c = lane & 15; c < C; c += 16)
+                    part += (double)p.Trow[(size_t)k * C + c] * ((double)p.x[qpx * C + c] - (double)s_mu[c]);
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);  // stays inside the 16-lane group
+            double qd = rint(part / (double)p.delta);
+            qd = fmin(fmax(qd, (double)lo), (double)hi);
+            const uint32_t sfix = (uint32_t)((int)qd + zero_sym);
+            if (active && (lane & 15) == 0 && sfix != old) {
+                atomicSub(&wh0[old * kHistLanes], 1u);
+                atomicAdd(&wh0[sfix * kHistLanes], 1u);
+                p.syms[qpx * C + k] = (uint8_t)sfix;
+            }
+        }
+        wave_sync_lds();
+        if (lane == 0) *fix_count = 0u;
+        wave_sync_lds();
+    };
+
+    // One pixel tile.  SWAP (a compile-time flag): the roles of the two buffers are exchanged (see the loop below).
+    auto tile_body = [&](auto swap_c, const int64_t tile) __attribute__((always_inline)) {
+        constexpr bool SWAP = decltype(swap_c)::value;
+        const int64_t next_tile = tile + stride;
+        const int64_t px = tile * 32 + l32;
+        const bool px_ok = px < p.P;
+        floatx16 am[NCT], ac[NCT];
+        float n2 = 0.f;
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        // one step: this lane's eight channels converted, then into every coefficient tile's accumulators
+        auto step = [&](int j, const f4_t (&raw)[2]) __attribute__((always_inline)) {
+            halfx8 xh, xl;
+#pragma unroll
+            for (int q = 0; q < 2; q++) {
+                const float4 m = *reinterpret_cast<const float4*>(&s_mu[16 * j + 8 * half + 4 * q]);
+                const float mv[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const float v = raw[q][i] - mv[i];
+                    n2 = __builtin_fmaf(v, v, n2);
+                    const _Float16 vh = (_Float16)v;
+                    xh[4 * q + i] = vh;
+                    xl[4 * q + i] = (_Float16)__builtin_fmaf((float)vh, -2048.f, v * 2048.f);  // 2^11 (v - vh), exact
+                }
+            }
+#pragma unroll
+            for (int kt = 0; kt < NCT; kt++) {
+                // (a truncated basis' zero rows are multiplied like any others: their coefficients come out zero)
+                const halfx8 th = __builtin_bit_cast(halfx8, basis16[((kt * NJ + j) * 2) * 64 + lane]);
+                const halfx8 tl = __builtin_bit_cast(halfx8, basis16[((kt * NJ + j) * 2 + 1) * 64 + lane]);
+                am[kt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xh, j ? am[kt] : zero, 0, 0, 0);
+                ac[kt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(th, xl, j ? ac[kt] : zero, 0, 0, 0);
+                ac[kt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(tl, xh, ac[kt], 0, 0, 0);
+            }
+            // (steps stay apart in the schedule: merged, their operands would not fit the registers of two wavefronts
+            // per SIMD)
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // Pair pr of this tile sits in buffer A or B as (pr odd) != SWAP says; a buffer is requested again as soon as
+        // its steps are converted: for the pair two further on, which past this tile's end is pair 0 or 1 of the next
+        // tile (whose SWAP is this one's for an even number of pairs and the opposite for an odd one, so that pair
+        // finds its data where it looks for it).
+#pragma unroll
+        for (int pr = 0; pr < NP; pr++) {
+            const bool in_b = ((pr & 1) != 0) != SWAP;
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int j = 2 * pr + u;
+                if (j < NJ && j < NJA) {  // wavefront-uniform
+                    if (in_b) step(j, bufB[u]); else step(j, bufA[u]);
+                }
+            }
+            const int npr = pr + 2;
+            if (npr < NP) {
+                if (in_b) load_pair(tile, npr, bufB); else load_pair(tile, npr, bufA);
+            } else if (next_tile < p.n_tiles && npr - NP < NP) {
+                if (in_b) load_pair(next_tile, npr - NP, bufB); else load_pair(next_tile, npr - NP, bufA);
+            }
+        }
+        n2 += __shfl_xor(n2, 32, 64);  // the other half of the pixel
+        const bool force = !(n2 < 1.0e9f);  // too large for f16 (or not finite): every coefficient decided exactly
+        const float tau = fminf(fmaxf(p.kappa * __builtin_sqrtf(n2), p.tau_min), 0.125f);
+        const float near_limit = force ? -1.f : 0.5f - tau;
+
+#pragma unroll
+        for (int kt = 0; kt < NCT; kt++) {
+            const bool k_ok = kt * 32 + 16 * half < C && px_ok;  // (C a multiple of 16: a lane's 16 coefficients all in or all out)
+            uint32_t word[4], ub[16];
+            float maxd = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const float t = __builtin_fmaf(ac[kt][r], inv_delta_lo, am[kt][r] * inv_delta);
+                const float u = t + magic;  // round half to even
+                maxd = fmaxf(maxd, fabsf(t - (u - magic)));
+                ub[r] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_fmed3f(u, magic_lo, magic_hi));  // clamped
+                if (k_ok) hist_add(ub[r]);
+            }
+#pragma unroll
+            for (int g = 0; g < 4; g++)
+                word[g] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(ub[4 * g + 3], ub[4 * g + 2], 0x0c0c0400u),
+                                                __builtin_amdgcn_perm(ub[4 * g + 1], ub[4 * g], 0x0c0c0400u), 0x05040100u);
+            if (k_ok)
+                *reinterpret_cast<uint4*>(p.syms + px * C + kt * 32 + 16 * half) = make_uint4(word[0], word[1], word[2], word[3]);
+            if (__builtin_expect(__any(!(maxd <= near_limit) && k_ok), 0)) {
+                // the values too close to a rounding boundary go to the wavefront's list (resolved when it is full
+                // and after the last tile)
+                uint32_t near_mask = 0;
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const float t = __builtin_fmaf(ac[kt][r], inv_delta_lo, am[kt][r] * inv_delta);
+                    if (!(fabsf(t - __builtin_rintf(t)) <= near_limit) && k_ok) near_mask |= 1u << r;
+                }
+                const int k0 = kt * 32 + 16 * half;
+                const uint32_t incoming = wave_sum((uint32_t)__popc(near_mask));
+                if (*fix_count + incoming > (uint32_t)kFixList) resolve_list();
+                if (incoming > (uint32_t)kFixList) {
+#pragma unroll 1
+                    for (int r = 0; r < 16; r++) {
+                        if ((near_mask >> r) & 1u) {
+                            const uint32_t slot = atomicAdd(fix_count, 1u);
+                            fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 8) |
+                                             (((word[r >> 2] >> (8 * (r & 3))) & 255u) << 13);
+                            fix_tile[slot] = (uint32_t)tile;
+                        }
+                        wave_sync_lds();
+                        resolve_list();
+                    }
+                } else {
+                    while (near_mask) {
+                        const int r = __ffs((int)near_mask) - 1;
+                        near_mask &= near_mask - 1;
+                        uint32_t sy = 0;
+#pragma unroll
+                        for (int g = 0; g < 4; g++)
+                            if (g == (r >> 2)) sy = (word[g] >> (8 * (r & 3))) & 255u;
+                        const uint32_t slot = atomicAdd(fix_count, 1u);
+                        fix_list[slot] = (uint32_t)(k0 + r) | ((uint32_t)l32 << 8) | (sy << 13);
+                        fix_tile[slot] = (uint32_t)tile;
+                    }
+                    wave_sync_lds();
+                }
+            }
+        }
+    };
+    if constexpr ((NP & 1) != 0) {
+        for (;;) {
+            if (tile >= p.n_tiles) break;
+            tile_body(std::false_type{}, tile);
+            tile += stride;
+            if (tile >= p.n_tiles) break;
+            tile_body(std::true_type{}, tile);
+            tile += stride;
+        }
+    } else {
+        for (; tile < p.n_tiles; tile += stride) tile_body(std::false_type{}, tile);
+    }
+    if (*fix_count) resolve_list();
+    __syncthreads();
+    for (int row = tid; row < WAVES * K; row += THREADS) {
+        const uint4* r4 = reinterpret_cast<const uint4*>(whist + (size_t)row * kHistLanes);
+        uint32_t total = 0;
+#pragma unroll
+        for (int q = 0; q < kHistLanes / 4; q++) {
+            const uint4 v = r4[q];
+            total += (v.x + v.y) + (v.z + v.w);
+        }
+        s_red[row] = total;
+    }
+    __syncthreads();
+    if (tid < K) {
+        uint32_t total = 0;
+#pragma unroll
+        for (int q = 0; q < WAVES; q++) total += s_red[q * K + tid];
+        p.hist_parts[(size_t)blockIdx.x * K + tid] = total;
+    }
+}
+
 static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P, int64_t HW, int layout, float delta,
                               int bits, uint8_t* d_syms, const CoderScratch& cs, int* n_parts, hipStream_t s) {
     RowParams p{};
@@ -1026,6 +1305,35 @@ static hipError_t launch_rows(const BasisDevice& b, const float* d_x, int64_t P,
     *n_parts = (int)gx;
     const bool vec = vec0;
     hipError_t el = hipSuccess;
+    // Four and five coefficient tiles, channels last, a multiple of 16 channels: the streaming form, four wavefronts.
+    // (Measured: 144 channels, 28.9 M values, 79 -> 62 us; 128 channels, 3.2 M values, 15.9 -> 13.6 us.  With more
+    // tiles than SIMDs at four coefficient tiles the eight-wavefront form of k_project_quantize_rows below stays: 50 us
+    // at 25.7 M values against 53 us for this kernel with four wavefronts and 48 to 58 us with eight, whose registers
+    // fit or spill with the compiler's schedule.)
+    if ((nct == 5 || (nct == 4 && !eight)) && layout == FMTC_NHWC && (b.C % 16) == 0) {
+        const int swaves = 4;
+        const bool whole = b.C == nct * 32;  // else 16 channels less
+        const size_t slds = lds_for(swaves);
+        int64_t sgx = (p.n_tiles + swaves - 1) / swaves;
+        if (sgx > 256) sgx = 256;  // one workgroup per compute unit (the basis takes 64 to 100 KB of its LDS)
+        *n_parts = (int)sgx;
+#define FMTC_STREAM_J(NCT, WV, NJA)                                                                              \
+    do {                                                                                                         \
+        hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project_quantize_stream<NCT, WV, NJA>), \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)slds);             \
+        if (ea != hipSuccess) return ea;                                                                         \
+        el = launch(K_PROJECT, k_project_quantize_stream<NCT, WV, NJA>, dim3((unsigned)sgx), dim3(WV * 64), slds, s, p); \
+    } while (0)
+#define FMTC_STREAM(NCT, WV)                                                                                     \
+    do {                                                                                                         \
+        if (whole) FMTC_STREAM_J(NCT, WV, 2 * NCT); else FMTC_STREAM_J(NCT, WV, 2 * NCT - 1);                    \
+    } while (0)
+        if (nct == 5) FMTC_STREAM(5, 4);
+        else FMTC_STREAM(4, 4);
+#undef FMTC_STREAM_J
+#undef FMTC_STREAM
+        return el;
+    }
 #define FMTC_ROWS_W(NCT, LAY, VEC, WV)                                                                           \
     do {                                                                                                         \
         if (lds > 32 * 1024) {                                                                                   \
