@@ -515,12 +515,29 @@ __global__ __launch_bounds__(256) void k_chunk_bits(PackParams p) {
             for (int q = 0; q < 16; q++)
 #pragma unroll
                 for (int i = 0; i < 4; i++) bits += s_len[(w[q] >> (8 * i)) & 255u];
+        } else if (clen >= 3840u) {
+            // (whole chunks of channel counts that do not divide 4096 -- 4032 symbols at 144 channels, 3840 at 960:
+            // fifteen whole registers in one straight run, the tests for the last one only)
+#pragma unroll
+            for (int q = 0; q < 15; q++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) bits += s_len[(w[q] >> (8 * i)) & 255u];
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                if (3840u + 4u * (uint32_t)lane + i < clen) bits += s_len[(w[15] >> (8 * i)) & 255u];
         } else {
+            // registers that lie inside the chunk whole need no per-symbol test
 #pragma unroll
-            for (int q = 0; q < 16; q++)
+            for (int q = 0; q < 16; q++) {
+                if (256u * (q + 1) <= clen) {  // wavefront-uniform
 #pragma unroll
-                for (int i = 0; i < 4; i++)
-                    if (256u * q + 4u * (uint32_t)lane + i < clen) bits += s_len[(w[q] >> (8 * i)) & 255u];
+                    for (int i = 0; i < 4; i++) bits += s_len[(w[q] >> (8 * i)) & 255u];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; i++)
+                        if (256u * q + 4u * (uint32_t)lane + i < clen) bits += s_len[(w[q] >> (8 * i)) & 255u];
+                }
+            }
         }
         bits = wave_sum(bits);
         if (lane == 0) p.chunk_bits[ch] = bits;

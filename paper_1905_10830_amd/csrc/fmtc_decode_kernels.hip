@@ -1144,12 +1144,42 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             }
             // One channel tile at a time: one pair of accumulators, the contraction, the epilogue, the stores (all
             // tiles at once would hold 2 NCT accumulators: the registers of a third wavefront per SIMD).
+            // LOG with registers to spare (at most two wavefronts per SIMD): the lower parts of a whole channel tile
+            // are requested as soon as the tile before has issued its last matrix instruction on them, and arrive
+            // during that tile's epilogue and stores and this tile's upper-part instructions.
+            constexpr bool kLoAhead = LOG && WAVES <= 8;
+            uint4 lo_ahead[kLoAhead ? NJ : 1];
+            auto request_lo = [&](int ct, uint4 (&dst)[kLoAhead ? NJ : 1]) __attribute__((always_inline)) {
+                if constexpr (kLoAhead) {
+                    const uint4* lo_src = reinterpret_cast<const uint4*>(p.Bp16) + ((size_t)(ct * NJ) * 2 + 1) * 64 + lane;
+#pragma unroll
+                    for (int j = 0; j < NJ; j++)
+                        if (j < NJA) dst[j] = lo_src[(size_t)j * 128];
+                }
+            };
+            if constexpr (kLoAhead) request_lo(0, lo_ahead);
 #pragma unroll
             for (int ct = 0; ct < NCT; ct++) {
                 floatx16 acc, acl;
 #pragma unroll
                 for (int r = 0; r < 16; r++) { acc[r] = 0.f; acl[r] = 0.f; }
-                if constexpr (LOG) {
+                if constexpr (kLoAhead) {
+#pragma unroll
+                    for (int j = 0; j < NJ; j++) {
+                        if (j >= NJA) continue;  // wavefront-uniform (truncation, and padding rows of the last tile)
+                        const halfx8 bh = __builtin_bit_cast(halfx8, basis16[(ct * NJ + j) * 64 + lane]);
+                        if constexpr (LAYOUT == FMTC_NHWC) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[j], bh, acc, 0, 0, 0);
+                        else acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, q[j], acc, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int j = 0; j < NJ; j++) {
+                        if (j >= NJA) continue;
+                        const halfx8 bl = __builtin_bit_cast(halfx8, lo_ahead[j]);
+                        if constexpr (LAYOUT == FMTC_NHWC) acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[j], bl, acl, 0, 0, 0);
+                        else acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q[j], acl, 0, 0, 0);
+                    }
+                    if (ct + 1 < NCT) request_lo(ct + 1, lo_ahead);
+                } else if constexpr (LOG) {
                     // the lower parts of this channel tile are requested first and used last
                     const uint4* lo_src = reinterpret_cast<const uint4*>(p.Bp16) + ((size_t)(ct * NJ) * 2 + 1) * 64 + lane;
                     // (half of them at a time: all at once would not fit the registers of three wavefronts per SIMD)
