@@ -220,23 +220,45 @@ struct TableOut {
 // Canonical codes from code lengths (len[j] of symbol 64 j + lane, 0 = unused; max_len the longest, the same in
 // every lane): codes of one length are numbered in symbol order, shorter codes first.  One wavefront; entry[] (256
 // words, LDS or global) is written whole.
+// scratch64: 64 words of LDS the wavefront may use (or NULL).
 template <int NVS>
 __device__ __forceinline__ void canonical_entries(const uint32_t (&len)[NVS], int lane, uint32_t max_len,
-                                                  unsigned long long* entry_out) {
+                                                  unsigned long long* entry_out, uint32_t* scratch64 = nullptr) {
     uint32_t before[NVS];
 #pragma unroll
     for (int j = 0; j < NVS; j++) before[j] = 0;
     // lane q ends up with the number of codes of length q
     uint32_t my_count = 0;
-    for (uint32_t q = 1; q <= max_len; q++) {
-        uint32_t total = 0;
+    if (NVS == 1 && scratch64) {
+        // One symbol per lane: the lanes of equal length found with six ballots (one per bit of the length) instead
+        // of a loop over the lengths; the first lane of every length hands the group's size to the lane whose
+        // index is that length.
+        unsigned long long same = ~0ull;
 #pragma unroll
-        for (int j = 0; j < NVS; j++) {
-            const unsigned long long m = __ballot(len[j] == q);
-            if (len[j] == q) before[j] = total + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-            total += (uint32_t)__popcll(m);
+        for (int bit = 0; bit < 6; bit++) {
+            const unsigned long long m = __ballot((len[0] >> bit) & 1u);
+            same &= ((len[0] >> bit) & 1u) ? m : ~m;
         }
-        if ((uint32_t)lane == q) my_count = total;
+        before[0] = (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+        const uint32_t group = (uint32_t)__popcll(same);
+        // (lengths are at most kMaxLen < 64: the lane that holds a length's count exists)
+        scratch64[lane] = 0u;
+        wave_sync();
+        if (len[0] && before[0] == 0) scratch64[len[0]] = group;
+        wave_sync();
+        const uint32_t cnt_here = scratch64[lane];
+        my_count = cnt_here;
+    } else {
+        for (uint32_t q = 1; q <= max_len; q++) {
+            uint32_t total = 0;
+#pragma unroll
+            for (int j = 0; j < NVS; j++) {
+                const unsigned long long m = __ballot(len[j] == q);
+                if (len[j] == q) before[j] = total + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                total += (uint32_t)__popcll(m);
+            }
+            if ((uint32_t)lane == q) my_count = total;
+        }
     }
     // first canonical code of every length: code(l) = sum_{j<l} count(j) << (l-j), i.e. the running sum of
     // count(j) * 2^(48-j) shifted down to l bits
@@ -340,7 +362,7 @@ __device__ __forceinline__ void table_from_hist(TableLds& L, int lane, int K, Ta
         pbits += __shfl_xor(pbits, o, 64);
     }
     max_len = (uint32_t)__builtin_amdgcn_readfirstlane((int)max_len);
-    canonical_entries<NVS>(len, lane, max_len, out.entry);
+    canonical_entries<NVS>(len, lane, max_len, out.entry, L.rank);  // (the ranks are in registers by now)
     out.max_len = max_len;
     out.payload_bits = pbits;
     wave_sync();
