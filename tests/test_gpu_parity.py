@@ -79,6 +79,8 @@ CASES = [
     (512, 7, 7, 2, 9, 128, "relu", 4),
     (144, 13, 11, 2, 3, 18, "relu6", 5),   # C not a multiple of 32, chunk of 28 pixels
     (960, 7, 7, 1, 2, 120, "relu6", 5),
+    (112, 9, 9, 1, 3, 14, "relu", 5),      # four coefficient tiles, the last 16-channel step is padding; ragged tile
+    (160, 7, 9, 1, 3, 20, "relu6", 6),     # five whole coefficient tiles
     (192, 5, 9, 1, 4, 24, "relu", 4),      # wide, 6 coefficient tiles: the second group of four is half empty
     (208, 6, 7, 1, 3, 26, "relu", 5),      # wide, C % 32 == 16: the last 16-channel step is padding
     (200, 6, 7, 1, 3, 25, "relu", 5),      # wide, C % 16 != 0
