@@ -575,9 +575,11 @@ __global__ __launch_bounds__(512) void k_decode_tiles(DecodeParams p) {
     constexpr int PTW = MT, CTW = 8, PPW = MT / 2;  // PPW: pixel tiles per wavefront
     // the chunks' payload words (one buffer per wavefront) while decoding, the basis blocks of three contraction
     // steps afterwards: the two uses are a workgroup barrier apart
-    constexpr size_t kPayBytes = sizeof(uint32_t) * 8 * (kPayWords + 2), kRingBytes = sizeof(uint4) * 3 * CTW * 2 * 64;
+    // (a payload buffer: the chunk's words, two zero words, and the room a corrupt stream's cursor may run into)
+    constexpr int kPayStride = kPayWords + 2 + kPayOverrun;
+    constexpr size_t kPayBytes = sizeof(uint32_t) * 8 * kPayStride, kRingBytes = sizeof(uint4) * 3 * CTW * 2 * 64;
     __shared__ __align__(16) uint8_t s_shared[kPayBytes > kRingBytes ? kPayBytes : kRingBytes];
-    uint32_t(*pay)[kPayWords + 2] = reinterpret_cast<uint32_t(*)[kPayWords + 2]>(s_shared);
+    uint32_t(*pay)[kPayStride] = reinterpret_cast<uint32_t(*)[kPayStride]>(s_shared);
     uint4(*s_ring)[CTW * 2][64] = reinterpret_cast<uint4(*)[CTW * 2][64]>(s_shared);
     extern __shared__ __align__(16) uint8_t symtile[];
 
@@ -691,7 +693,14 @@ __global__ __launch_bounds__(512) void k_decode_tiles(DecodeParams p) {
                 for (uint32_t i = lane; i < nwords + 2; i += 64) pw[i] = (i < nwords) ? payload[w0 + i] : 0u;
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 __builtin_amdgcn_wave_barrier();
-                if (cnt) ok_run = decode_run<true>(pw, nullptr, nwords, start, cnt, T, ByteOut(symtile, nbase));
+                if (cnt) {
+                    // Chunk sizes that are a multiple of 64 (every run starts a 68-byte slot of the tile, and only the
+                    // tensor's last run can be short) take the decoder of the narrow kernel: three table entries per
+                    // read of the stream.  It stores up to three bytes past a run's last symbol: with other chunk sizes
+                    // those would be the first symbols of the next chunk, which another wavefront writes.
+                    if ((chunk_syms & 63u) == 0) ok_run = decode_run_bytes(pw, nwords, start, cnt, T, symtile + sym_addr(nbase));
+                    else ok_run = decode_run<true>(pw, nullptr, nwords, start, cnt, T, ByteOut(symtile, nbase));
+                }
                 // the next chunk of this wavefront overwrites pay[]: all lanes are done reading here
                 __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
                 __builtin_amdgcn_wave_barrier();
