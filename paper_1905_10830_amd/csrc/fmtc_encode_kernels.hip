@@ -431,6 +431,15 @@ static hipError_t launch_wide(const BasisDevice& b, const float* d_x, int64_t P,
 // quantizer of tile kt is scheduled between the matrix instructions of tile kt+1.
 // Histogram: interleaved LDS copies per wavefront.
 // ---------------------------------------------------------------------------
+// Bit pattern of u clamped between the patterns of lo and hi (positive floats: their order is the order of their
+// patterns as signed integers).  Compared as integers so that every input ends in range: a negative u (sign bit set)
+// below lo, a NaN at one end or the other -- the result indexes the histogram.
+__device__ __forceinline__ uint32_t clamp_pattern(float u, float lo, float hi) {
+    const int ui = __builtin_bit_cast(int, u), li = __builtin_bit_cast(int, lo), hi_i = __builtin_bit_cast(int, hi);
+    const int c = ui < li ? li : (ui > hi_i ? hi_i : ui);
+    return (uint32_t)c;
+}
+
 constexpr int kHistLanes = 16;  // histogram copies per wavefront in the narrow-tensor kernel
 constexpr int kFixList = 64;    // values per wavefront waiting for their exact decision
 
@@ -816,7 +825,7 @@ void k_project_quantize_rows(RowParams p) {
                     const float t = __builtin_fmaf(ac[r], inv_delta_lo, am[r] * inv_delta);
                     const float u = t + magic;  // round half to even
                     maxd = fmaxf(maxd, fabsf(t - (u - magic)));
-                    ub[r] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_fmed3f(u, magic_lo, magic_hi));  // clamped
+                    ub[r] = clamp_pattern(u, magic_lo, magic_hi);
                     if constexpr (!FUSED)
                         if (k_ok) hist_add(ub[r]);
                 }
@@ -850,7 +859,7 @@ void k_project_quantize_rows(RowParams p) {
                     const float t = __builtin_fmaf(ac[r], inv_delta_lo, am[r] * inv_delta);
                     const float u = t + magic;  // round half to even
                     maxd = fmaxf(maxd, fabsf(t - (u - magic)));
-                    ub[r] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_fmed3f(u, magic_lo, magic_hi));  // clamped
+                    ub[r] = clamp_pattern(u, magic_lo, magic_hi);
                     if constexpr (!FUSED)
                         if (k_ok) hist_add(ub[r]);
                     if ((r & 3) == 3)
@@ -1164,7 +1173,7 @@ void k_project_quantize_stream(RowParams p) {
                 const float t = __builtin_fmaf(ac[kt][r], inv_delta_lo, am[kt][r] * inv_delta);
                 const float u = t + magic;  // round half to even
                 maxd = fmaxf(maxd, fabsf(t - (u - magic)));
-                ub[r] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_fmed3f(u, magic_lo, magic_hi));  // clamped
+                ub[r] = clamp_pattern(u, magic_lo, magic_hi);
                 if (k_ok) hist_add(ub[r]);
             }
 #pragma unroll

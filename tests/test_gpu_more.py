@@ -265,3 +265,32 @@ def test_small_tensor_encoders_on_two_streams(fmtc):
     for stream, nbytes in outs:
         assert int(nbytes.item()) == n
         assert torch.equal(stream[:n], ref[:n])
+
+
+@pytest.mark.parametrize("layout", [synth.NHWC, synth.NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("C,rank", [(64, 16), (128, 32), (144, 18), (160, 20), (256, 64)], ids=["C64", "C128", "C144", "C160", "C256"])
+def test_pixels_too_large_for_f16(fmtc, oracle, C, rank, layout):
+    """Activations far outside the range the split-f16 products cover (a component beyond the largest f16 number
+    turns into infinity on the way into the matrix cores): such a pixel's coefficients are all decided in fp64, so
+    the symbols still equal the oracle's, the pixels around it are untouched, and the histogram, the container and
+    the decoded tensor stay consistent.  One pixel just below the limit of the exact treatment as well."""
+    s = synth.FeatureMapStream(C, 9, 11, rank, "relu", seed=900 + C)
+    calib, x = s.images(1), s.images(3)
+    if C <= 160:
+        T, mu, _, A = oracle.fit(calib)
+    else:
+        mean, cov = oracle.covariance(calib)
+        w, v = np.linalg.eigh(cov)
+        T = np.ascontiguousarray(v[:, ::-1].T).astype(np.float32)
+        mu = mean.astype(np.float32)
+        A = np.float32(np.abs(oracle.project(calib, T, mu)[:, 0]).max())
+    x = x.copy()
+    flat = x.reshape(-1, C)
+    flat[5, 3] = 1.0e5          # beyond f16
+    flat[5, C - 1] = -2.5e5
+    flat[40, 0] = 3.0e7         # far beyond: its products overflow fp32 accumulation of the others' scale
+    flat[77, C // 2] = 7.0e4
+    flat[130, 1] = 2.0e4        # large, still inside f16: the ordinary path with a wide exact-decision band
+    flat[131] = 900.0           # |x - mu|_2 close to the limit of the exact treatment (about 3e4) at 1e3 per channel
+    xs = synth.to_layout(x, layout)
+    roundtrip(fmtc, oracle, xs, T, mu, A, 6, layout)
