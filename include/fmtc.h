@@ -182,7 +182,10 @@ fmtc_status fmtc_encode_noalloc(const fmtc_basis *basis, const float *d_x, int64
  * before the call) is OR-ed with FMTC_ERR_* bits if the stream fails validation;
  * in that case d_xhat is unspecified but no access leaves the given buffers.
  * The decoder needs no workspace: every workgroup builds the decode tables from
- * the stream's code length table in LDS. */
+ * the stream's code length table in LDS.  Channels-last tensors of up to 144
+ * channels and some tens of MB or more are written with streaming stores
+ * (they pass the device's memory-side cache instead of displacing its
+ * contents; a consumer that reads the tensor at once reads it from memory). */
 fmtc_status fmtc_decode(const fmtc_basis *basis, const void *d_stream_in, size_t bytes, float *d_xhat, int64_t N,
                         int C, int H, int W, fmtc_layout layout, int bits, uint32_t *d_err_flag, void *hip_stream);
 
