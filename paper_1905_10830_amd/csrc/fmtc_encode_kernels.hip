@@ -1643,10 +1643,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int e = 0; e < 8; e++) {
                 float d = ok ? v[e] - m[e] : 0.f;
                 n2 = __builtin_fmaf(d, d, n2);
-                d = __builtin_amdgcn_fmed3f(d, -60000.f, 60000.f);  // such a pixel is decided exactly (see n2)
+                // (no clamp of values beyond f16: what their infinities make of the products stays in the pixel's own
+                // column of outputs, and such a pixel is decided exactly in all coefficients, see n2)
                 const _Float16 h = (_Float16)d;
                 vh[e] = h;
-                vl[e] = (_Float16)((d - (float)h) * 2048.f);
+                vl[e] = (_Float16)__builtin_fmaf((float)h, -2048.f, d * 2048.f);  // 2^11 (d - h), exact, one mixed multiply-add
             }
             stageB[s & 1][wave][0][lane] = __builtin_bit_cast(uint4, vh);
             stageB[s & 1][wave][1][lane] = __builtin_bit_cast(uint4, vl);
@@ -1716,7 +1717,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     if (!(fabsf(t - q) <= near_limit)) near_mask |= 1u << r;
                     const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
                     word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
-                    if (ok) atomicAdd(&wh[(uint32_t)qc << HS], 1u);
+                    if (ok) atomicAdd(&wh[((uint32_t)qc < (uint32_t)K ? (uint32_t)qc : (uint32_t)(K - 1)) << HS], 1u);  // (in range whatever qc is)
                 }
                 if (ok)
                     *reinterpret_cast<uint4*>(p.syms + px * C + k0) = make_uint4(word[0], word[1], word[2], word[3]);
@@ -1903,10 +1904,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int e = 0; e < 4; e++) {
                 float d = ok ? v[e] - m[e] : 0.f;
                 n2 = __builtin_fmaf(d, d, n2);
-                d = __builtin_amdgcn_fmed3f(d, -60000.f, 60000.f);  // such a pixel is decided exactly (see n2)
+                // (no clamp of values beyond f16: what their infinities make of the products stays in the pixel's own
+                // column of outputs, and such a pixel is decided exactly in all coefficients, see n2)
                 const _Float16 h = (_Float16)d;
                 vh[e] = h;
-                vl[e] = (_Float16)((d - (float)h) * 2048.f);
+                vl[e] = (_Float16)__builtin_fmaf((float)h, -2048.f, d * 2048.f);  // 2^11 (d - h), exact, one mixed multiply-add
             }
             uint2* dst = reinterpret_cast<uint2*>(&stageB[s & 1][xpt][0][l32 + 32 * (xq >> 1)]) + (xq & 1);
             dst[0] = __builtin_bit_cast(uint2, vh);
@@ -1973,7 +1975,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     if (!(fabsf(t - q) <= near_limit)) near_mask |= 1u << r;
                     const float qc = __builtin_amdgcn_fmed3f(q, lo, hi) + zero_f;  // clamped level, as a symbol
                     word[r >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(qc, r & 3, word[r >> 2]);
-                    if (ok) atomicAdd(&wh[(uint32_t)qc << HS], 1u);
+                    if (ok) atomicAdd(&wh[((uint32_t)qc < (uint32_t)K ? (uint32_t)qc : (uint32_t)(K - 1)) << HS], 1u);  // (in range whatever qc is)
                 }
                 if (ok)
                     *reinterpret_cast<uint4*>(p.syms + px * C + k0) = make_uint4(word[0], word[1], word[2], word[3]);
