@@ -864,7 +864,7 @@ constexpr int kChunkTileBytes = 4096 + 4096 / 16 + 64;  // symbols, 4 pad bytes 
 // correction, are read from global memory (the cache serves them: every wavefront of the device reads the same few
 // tens of KB) while the matrix instructions of the upper parts run.  Half the LDS per workgroup buys a third
 // wavefront per SIMD for 128 to 160 channels.
-template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES, bool U8 = false, int CFIX = 0, bool LOG = false>
+template <int NCT, int LAYOUT, bool ALIGNED4, int WAVES, bool U8 = false, int CFIX = 0, bool LOG = false, int NLO = 0>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void k_decode_chunks(DecodeParams p) {
     constexpr int THREADS = WAVES * 64;
     __shared__ __align__(16) DecTables T;
@@ -914,6 +914,9 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         const uint4* src = reinterpret_cast<const uint4*>(p.Bp16);
         for (int g = wave; g < NCT * NJ; g += WAVES)
             __builtin_amdgcn_global_load_lds(src + (size_t)g * 128 + lane, &basis16[g * 64], 16, 0, 0);
+        // ... and the lower parts of the first NLO channel tiles behind them
+        for (int g = wave; g < NLO * NJ; g += WAVES)
+            __builtin_amdgcn_global_load_lds(src + (size_t)g * 128 + 64 + lane, &basis16[(NCT * NJ + g) * 64], 16, 0, 0);
     }
     // The first chunk's offsets, run sizes and payload are requested before the header has arrived, at the places
     // the nominal chunk size puts them: three dependent memory round trips (header, offsets, payload) become
@@ -1153,26 +1156,36 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             }
             // One channel tile at a time: one pair of accumulators, the contraction, the epilogue, the stores (all
             // tiles at once would hold 2 NCT accumulators: the registers of a third wavefront per SIMD).
-            // LOG with registers to spare (at most two wavefronts per SIMD): the lower parts of a whole channel tile
-            // are requested as soon as the tile before has issued its last matrix instruction on them, and arrive
-            // during that tile's epilogue and stores and this tile's upper-part instructions.
-            constexpr bool kLoAhead = LOG && WAVES <= 8;
-            uint4 lo_ahead[kLoAhead ? NJ : 1];
-            auto request_lo = [&](int ct, uint4 (&dst)[kLoAhead ? NJ : 1]) __attribute__((always_inline)) {
-                if constexpr (kLoAhead) {
+            // LOG: the lower parts of the first NLO channel tiles sit in LDS behind the upper parts (as many as fit
+            // beside the wavefronts' buffers), those of the others come from global memory.  The tiles with everything in
+            // LDS go first, and the others' lower parts are requested before them: a round trip to the cache takes 1 to
+            // 1.5 us under this kernel's load, a channel tile's arithmetic a third of that.  At most two wavefronts per
+            // SIMD have the registers to request all of them at the top; three request one tile's, and the next tile's
+            // when that one's matrix instructions have issued.
+            constexpr int NG = LOG ? NCT - NLO : 0;
+            constexpr bool kLoAll = LOG && WAVES <= 8 && NG <= 2;
+            uint4 lo_g[kLoAll ? (NG > 0 ? NG : 1) : 1][LOG ? NJ : 1];
+            auto request_lo = [&](int ct, uint4 (&dst)[LOG ? NJ : 1]) __attribute__((always_inline)) {
+                if constexpr (LOG) {
                     const uint4* lo_src = reinterpret_cast<const uint4*>(p.Bp16) + ((size_t)(ct * NJ) * 2 + 1) * 64 + lane;
 #pragma unroll
                     for (int j = 0; j < NJ; j++)
                         if (j < NJA) dst[j] = lo_src[(size_t)j * 128];
                 }
             };
-            if constexpr (kLoAhead) request_lo(0, lo_ahead);
+            if constexpr (LOG && NG > 0) {
+                request_lo(NLO, lo_g[0]);
+                if constexpr (kLoAll) {
+#pragma unroll
+                    for (int g = 1; g < NG; g++) request_lo(NLO + g, lo_g[g]);
+                }
+            }
 #pragma unroll
             for (int ct = 0; ct < NCT; ct++) {
                 floatx16 acc, acl;
 #pragma unroll
                 for (int r = 0; r < 16; r++) { acc[r] = 0.f; acl[r] = 0.f; }
-                if constexpr (kLoAhead) {
+                if constexpr (LOG) {
 #pragma unroll
                     for (int j = 0; j < NJ; j++) {
                         if (j >= NJA) continue;  // wavefront-uniform (truncation, and padding rows of the last tile)
@@ -1183,41 +1196,14 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 #pragma unroll
                     for (int j = 0; j < NJ; j++) {
                         if (j >= NJA) continue;
-                        const halfx8 bl = __builtin_bit_cast(halfx8, lo_ahead[j]);
+                        halfx8 bl;
+                        if (ct < NLO) bl = __builtin_bit_cast(halfx8, basis16[((NCT + ct) * NJ + j) * 64 + lane]);
+                        else bl = __builtin_bit_cast(halfx8, lo_g[kLoAll ? ct - NLO : 0][j]);
                         if constexpr (LAYOUT == FMTC_NHWC) acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[j], bl, acl, 0, 0, 0);
                         else acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q[j], acl, 0, 0, 0);
                     }
-                    if (ct + 1 < NCT) request_lo(ct + 1, lo_ahead);
-                } else if constexpr (LOG) {
-                    // the lower parts of this channel tile are requested first and used last
-                    const uint4* lo_src = reinterpret_cast<const uint4*>(p.Bp16) + ((size_t)(ct * NJ) * 2 + 1) * 64 + lane;
-                    // (half of them at a time: all at once would not fit the registers of three wavefronts per SIMD)
-                    constexpr int NH = (NJ + 1) / 2;
-                    uint4 lo_op[NH];
-#pragma unroll
-                    for (int j = 0; j < NH; j++)
-                        if (j < NJA) lo_op[j] = lo_src[(size_t)j * 128];
-#pragma unroll
-                    for (int j = 0; j < NJ; j++) {
-                        if (j >= NJA) continue;  // wavefront-uniform (truncation, and padding rows of the last tile)
-                        const halfx8 bh = __builtin_bit_cast(halfx8, basis16[(ct * NJ + j) * 64 + lane]);
-                        if constexpr (LAYOUT == FMTC_NHWC) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[j], bh, acc, 0, 0, 0);
-                        else acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, q[j], acc, 0, 0, 0);
-                    }
-#pragma unroll
-                    for (int h = 0; h < 2; h++) {
-#pragma unroll
-                        for (int j = 0; j < NH; j++) {
-                            if (h * NH + j >= NJ || h * NH + j >= NJA) continue;
-                            const halfx8 bl = __builtin_bit_cast(halfx8, lo_op[j]);
-                            if constexpr (LAYOUT == FMTC_NHWC) acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(q[h * NH + j], bl, acl, 0, 0, 0);
-                            else acl = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, q[h * NH + j], acl, 0, 0, 0);
-                        }
-                        if (h == 0) {
-#pragma unroll
-                            for (int j = 0; j < NH; j++)
-                                if (NH + j < NJ && NH + j < NJA) lo_op[j] = lo_src[(size_t)(NH + j) * 128];
-                        }
+                    if constexpr (!kLoAll) {
+                        if (ct >= NLO && ct + 1 < NCT) request_lo(ct + 1, lo_g[0]);
                     }
                 } else {
 #pragma unroll
@@ -1258,9 +1244,12 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                         } else if (CFIX != 0 && CFIX != NCT * 32) {
                             // (a channel count known at build time that is no multiple of 32: the same, with the
                             // rows past the chunk's last pixel left out)
+                            // (a whole chunk of such a tensor ends inside the last eight rows of the tile: the rows before
+                            // them need no test -- wavefront-uniform -- and the stores go out in one run)
+                            const bool first24 = pt * 32 + 24 <= TP;
 #pragma unroll
                             for (int r = 0; r < 16; r++)
-                                if (pt * 32 + 8 * (r >> 2) + 4 * half + (r & 3) < TP) {
+                                if ((r < 12 && first24) || pt * 32 + 8 * (r >> 2) + 4 * half + (r & 3) < TP) {
                                     float* at = &dst[(size_t)(8 * (r >> 2) + (r & 3)) * (CFIX ? CFIX : 1)];
                                     if constexpr (kStreamOut) __builtin_nontemporal_store(__builtin_fmaf(acc[r], delta, m_c), at);
                                     else *at = __builtin_fmaf(acc[r], delta, m_c);
@@ -1348,8 +1337,15 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         // (k_decode_chunks<..., LOG>); built for the channel counts 128 and 144, channels last (with a channel count
         // left open the kernel does not fit the registers of three wavefronts)
         // (144 channels: two wavefronts per SIMD, the registers of a third do not fit)
-        const size_t lds_basis_log = lds_basis / 2;
+        // (the lower parts of the first `nlo` channel tiles go to LDS all the same if the bit depth's payload buffers
+        // leave the room: 2 of 4 tiles at 128 channels, 3 of 5 at 144)
         const int log_waves = C == 128 ? 12 : 8;
+        const int nlo_want = C == 128 ? 2 : 3;
+        const size_t lo_tile = lds_basis / 2 / (size_t)ncs;  // bytes of one channel tile's lower parts
+        auto lds_basis_for = [&](int nlo) { return lds_basis / 2 + (size_t)nlo * lo_tile; };
+        const bool fits_lo = lds_all(log_waves) - lds_basis + lds_basis_for(nlo_want) <= 160 * 1024;
+        const int nlo = fits_lo ? nlo_want : 0;
+        const size_t lds_basis_log = lds_basis_for(nlo);
         const bool log12 = (C == 128 || C == 144) && layout == FMTC_NHWC && g.n_chunks > 2048 &&
                            lds_all(log_waves) - lds_basis + lds_basis_log <= 160 * 1024;
         if (log12) {
@@ -1362,15 +1358,16 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
         const unsigned most = waves >= 8 ? 1u : 2u;
         const unsigned cap = 256u * (per_cu < 1 ? 1u : (per_cu > most ? most : per_cu));
         if (gx > cap) gx = cap;
-#define FMTC_DECC_F(NCT, LAY, AL, WV, CF, LG)                                                                    \
+#define FMTC_DECC_L(NCT, LAY, AL, WV, CF, LG, NL)                                                                \
     do {                                                                                                         \
         if (lds > 16 * 1024) {                                                                                   \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, false, CF, LG>), \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_chunks<NCT, LAY, AL, WV, false, CF, LG, NL>), \
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
             if (ea != hipSuccess) return ea;                                                                     \
         }                                                                                                        \
-        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, false, CF, LG>, dim3(gx), dim3(WV * 64), lds, s, p); \
+        el = launch(K_DECODE, k_decode_chunks<NCT, LAY, AL, WV, false, CF, LG, NL>, dim3(gx), dim3(WV * 64), lds, s, p); \
     } while (0)
+#define FMTC_DECC_F(NCT, LAY, AL, WV, CF, LG) FMTC_DECC_L(NCT, LAY, AL, WV, CF, LG, 0)
 #define FMTC_DECC(NCT, LAY, AL, WV) FMTC_DECC_F(NCT, LAY, AL, WV, 0, false)
 #define FMTC_DECC_N(LAY, AL)                                                                                     \
     do {                                                                                                         \
@@ -1381,8 +1378,8 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
     } while (0)
         if (waves == 16) { if (ncs == 1) FMTC_DECC_F(1, FMTC_NHWC, true, 16, 32, false); else FMTC_DECC_F(2, FMTC_NHWC, true, 16, 64, false); }
         else if (log12) {
-            if (C == 128) FMTC_DECC_F(4, FMTC_NHWC, true, 12, 128, true);
-            else FMTC_DECC_F(5, FMTC_NHWC, true, 8, 144, true);
+            if (C == 128) { if (nlo) FMTC_DECC_L(4, FMTC_NHWC, true, 12, 128, true, 2); else FMTC_DECC_L(4, FMTC_NHWC, true, 12, 128, true, 0); }
+            else { if (nlo) FMTC_DECC_L(5, FMTC_NHWC, true, 8, 144, true, 3); else FMTC_DECC_L(5, FMTC_NHWC, true, 8, 144, true, 0); }
         }
         else if (ncs == 5) { if (al) FMTC_DECC(5, FMTC_NHWC, true, 4); else FMTC_DECC(5, FMTC_NHWC, false, 4); }
         else if (layout == FMTC_NHWC) { if (al) FMTC_DECC_N(FMTC_NHWC, true); else FMTC_DECC_N(FMTC_NHWC, false); }
@@ -1390,6 +1387,7 @@ hipError_t launch_decode(const BasisDevice* b, const uint8_t* d_stream, size_t b
 #undef FMTC_DECC_N
 #undef FMTC_DECC
 #undef FMTC_DECC_F
+#undef FMTC_DECC_L
         return el;
     }
 
