@@ -294,3 +294,62 @@ def test_pixels_too_large_for_f16(fmtc, oracle, C, rank, layout):
     flat[131] = 900.0           # |x - mu|_2 close to the limit of the exact treatment (about 3e4) at 1e3 per channel
     xs = synth.to_layout(x, layout)
     roundtrip(fmtc, oracle, xs, T, mu, A, 6, layout)
+
+
+@pytest.mark.parametrize("C,hw,N", [(64, 56, 64), (128, 28, 128), (144, 56, 24)], ids=["C64", "C128", "C144"])
+def test_damaged_streams_through_the_many_wavefront_decoders(fmtc, C, hw, N):
+    """Tensors of more than 3000 chunks take the chunk decoder's variants with three and four wavefronts per SIMD
+    (payload straight into LDS, three table entries per stream read, part of the basis read from global memory).
+    Damage to the payload, the run sizes and the chunk offsets of such a stream must end in a flag or in garbage,
+    never in an access outside the buffers; the undamaged stream decodes without a flag before and after."""
+    torch.manual_seed(11)
+    calib = torch.randn(4, hw, hw, C, device="cuda").relu()
+    x = (torch.randn(N, hw, hw, C, device="cuda") * torch.linspace(2.0, 0.05, C, device="cuda")).relu()
+    P = N * hw * hw
+    assert (P + 4096 // C - 1) // (4096 // C) > (3072 if C <= 64 else 2048)
+    basis = fmtc.fit_basis(calib)
+    stream, nbytes = fmtc.encode(basis, x, 6)
+    ref, err = fmtc.decode(basis, stream, x.shape, 6)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    n = int(nbytes.item())
+    good = stream[:n].cpu().numpy()
+    info = fmtc.stream_info(good[:64])
+    n_chunks = info["n_chunks"]
+    off_co = 64 + 256
+    off_sub = (off_co + 4 * (n_chunks + 1) + 15) // 16 * 16
+    spc = (4096 // C * C + 63) // 64
+    off_pay = (off_sub + 2 * n_chunks * spc + 15) // 16 * 16
+    rng = np.random.default_rng(C)
+
+    def run(bad):
+        out, e = fmtc.decode(basis, dev(bad), x.shape, 6)
+        torch.cuda.synchronize()
+        return int(e.item())
+
+    # payload bytes at random places
+    bad = good.copy()
+    idx = rng.integers(off_pay, n, size=4000)
+    bad[idx] = rng.integers(0, 256, size=4000, dtype=np.uint8)
+    run(bad)
+    # run sizes: some far too large, some zero
+    bad = good.copy()
+    sub = bad[off_sub:off_sub + 2 * n_chunks * spc].view(np.uint16)
+    pick = rng.integers(0, sub.size, size=2000)
+    sub[pick[:1000]] = 0xFFFF
+    sub[pick[1000:]] = 0
+    run(bad)
+    # chunk offsets: two neighbours swapped (decreasing), one beyond the payload
+    bad = good.copy()
+    co = bad[off_co:off_co + 4 * (n_chunks + 1)].view(np.uint32)
+    co[[100, 101]] = co[[101, 100]]
+    co[n_chunks // 2] = 0xFFFFFFF0
+    assert run(bad) & fmtc.ERR_OFFSETS
+    # the payload cut short of what the header announces
+    out, e = fmtc.decode(basis, dev(good), x.shape, 6, nbytes=n - 4096)
+    torch.cuda.synchronize()
+    assert int(e.item()) & fmtc.ERR_HEADER
+    # and the good stream still decodes to the same tensor
+    again, err = fmtc.decode(basis, dev(good), x.shape, 6)
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0 and torch.equal(again, ref)
