@@ -146,7 +146,11 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
 #pragma unroll
         for (int it = 0; it < ((1 << kLutBits) + THREADS - 1) / THREADS; it++) {
             const uint32_t v = (uint32_t)(tid + it * THREADS);
-            if (v >= (1u << kLutBits)) break;
+            // (only workgroup sizes that do not divide the table need the test: without it the turns are one
+            // straight run and their dependent LDS reads overlap)
+            if constexpr (((1 << kLutBits) % THREADS) != 0) {
+                if (v >= (1u << kLutBits)) break;
+            }
             uint32_t len = 1;
 #pragma unroll
             for (int l = 1; l < kLutBits; l++) len += (v >= lim[l]) ? 1u : 0u;
@@ -165,7 +169,9 @@ __device__ __forceinline__ bool build_decode_tables(DecTables& T, int my_len, in
         constexpr uint32_t kMask = (1u << kLutBits) - 1u;
 #pragma unroll
         for (int it = 0; it < ((1 << kLutBits) + THREADS - 1) / THREADS; it++) {
-            if ((uint32_t)(tid + it * THREADS) >= (1u << kLutBits)) break;
+            if constexpr (((1 << kLutBits) % THREADS) != 0) {
+                if ((uint32_t)(tid + it * THREADS) >= (1u << kLutBits)) break;
+            }
             // (neighbouring threads take neighbouring values v0: the reads of `first` below are neighbours, and the
             // entries, whose indices differ in their upper bits, go to different banks through lut_slot; taking
             // neighbouring indices instead puts every read of a wavefront on one bank)
